@@ -1,0 +1,429 @@
+"""Pins of the CPU oracle against what the paper prints and what the mathematics fixes.
+
+Nothing here touches the GPU path.  Every expected value is the paper's (fixtures under
+tests/golden/, each with its citation), a closed form, or a hand-worked number.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from conftest import golden_lines
+
+AR, RS, AG, RD, BC = range(5)
+INSIDE, PARALLEL, MASTER = range(3)
+
+
+# --------------------------------------------------------------------------- placements (Sec. 3.1)
+def _prime_factors(v):
+    out, p = {}, 2
+    while v > 1:
+        while v % p == 0:
+            out[p] = out.get(p, 0) + 1
+            v //= p
+        p += 1
+    return out
+
+
+def _contingency(rows, cols):
+    """Number of non-negative integer tables with the given row and column sums."""
+    if len(rows) == 1:
+        return 1 if rows[0] == sum(cols) else 0
+    total = 0
+    for first in itertools.product(*[range(c + 1) for c in cols]):
+        if sum(first) == rows[0]:
+            total += _contingency(rows[1:], [c - f for c, f in zip(cols, first)])
+    return total
+
+
+def _closed_form_count(card, axes):
+    primes = set()
+    for v in list(card) + list(axes):
+        primes |= set(_prime_factors(v))
+    n = 1
+    for p in primes:
+        n *= _contingency([_prime_factors(a).get(p, 0) for a in axes], [_prime_factors(h).get(p, 0) for h in card])
+    return n
+
+
+@pytest.mark.parametrize("card,axes", [([1, 2, 2, 4], [4, 4]), ([2, 4], [2, 4]), ([4, 2, 4], [4, 8]), ([2, 4, 8], [2, 4, 8]),
+                                       ([4, 8, 8], [4, 8, 8]), ([2, 4, 8, 8], [2, 4, 8, 8]), ([6, 4], [3, 8]), ([3, 6], [2, 9]),
+                                       ([4, 16], [8, 2, 4]), ([2, 3], [7])])
+def test_placement_count_closed_form_and_constraints(oracle, card, axes):
+    pls = oracle.enumerate_placements(card, axes)
+    assert len(pls) == _closed_form_count(card, axes)
+    for x in pls:
+        assert (x >= 1).all()
+        assert [int(v) for v in x.prod(axis=0)] == list(card)      # Eq. (1): column products
+        assert [int(v) for v in x.prod(axis=1)] == list(axes)      # Eq. (2): row products
+    flat = [tuple(x.flatten()) for x in pls]
+    assert flat == sorted(set(flat))                               # distinct, lexicographic
+
+
+def test_placement_examples_of_the_overview_figure(oracle):
+    # Fig. "overview" (b), (c), (d): three placements of [4,4] on [1,2,2,4]
+    got = {tuple(x.flatten()) for x in oracle.enumerate_placements([1, 2, 2, 4], [4, 4])}
+    for m in ([[1, 2, 2, 1], [1, 1, 1, 4]], [[1, 2, 1, 2], [1, 1, 2, 2]], [[1, 1, 2, 2], [1, 2, 1, 2]]):
+        assert tuple(np.array(m).flatten()) in got
+
+
+def _parse_matrices(text):
+    return [tuple(tuple(int(v) for v in row.split(",")) for row in m.strip().split("/")) for m in text.split(";")]
+
+
+@pytest.mark.parametrize("row", golden_lines("paper_program_counts.txt"), ids=lambda r: "%s|%s|%s" % (r[0], r[1], r[2]))
+def test_paper_placement_lists_and_program_counts(oracle, row):
+    """Appendix A: complete matrix list per row, and the total number of synthesized programs
+    at size limit 5.  The printed totals (6 ... 235) are reproduced by the InsideGroup and
+    Parallel forms (3 programs for a one-level hierarchy, 47 for a two-level one)."""
+    card = [int(v) for v in row[0].split(",")]
+    axes = [int(v) for v in row[1].split(",")]
+    reduce_axes = [int(v) for v in row[2].split(",")]
+    total = int(row[3])
+    printed = _parse_matrices(row[4])
+    pls = oracle.enumerate_placements(card, axes)
+    assert {tuple(tuple(int(v) for v in r) for r in x) for x in pls} == set(printed)
+    got = 0
+    for x in pls:
+        q = oracle.Query(card, axes, x, reduce_axes, form_mask=3)
+        got += len(q.synthesize(5)["index"])
+    assert got == total
+
+
+def test_saturation_at_size_limit_five(oracle):
+    # Sec. 4.2 Result 2: a larger size limit "for most cases does not generate new programs"
+    q = oracle.Query([4, 16], [64], [[4, 16]], [0], form_mask=3)
+    assert len(q.synthesize(5)["index"]) == len(q.synthesize(6)["index"]) == 47
+
+
+# --------------------------------------------------------------------------- rules (Sec. 3.2)
+def _state(text, D=4, k=4):
+    s = np.zeros((k, D), dtype=np.uint8)
+    if text != "-":
+        for part in text.split(";"):
+            r, cols = part.split(":")
+            for c in cols.split(","):
+                s[int(r), int(c)] = 1
+    return s
+
+
+@pytest.mark.parametrize("row", golden_lines("collective_examples.txt"), ids=lambda r: r[0])
+def test_worked_examples_of_the_semantics_figure(oracle, row):
+    op = ["AllReduce", "ReduceScatter", "AllGather", "Reduce", "Broadcast"].index(row[0])
+    st = np.zeros((4, 4, 4), dtype=np.uint8)
+    st[0], st[1] = _state(row[1]), _state(row[2])
+    st[2] = _state("1:2")       # bystanders keep whatever they hold
+    ok, out = oracle.apply_collective(st, op, [0, 1])
+    assert ok
+    assert (out[0] == _state(row[3])).all()
+    assert (out[1] == _state(row[4])).all()
+    assert (out[2] == st[2]).all() and (out[3] == st[3]).all()
+
+
+def test_device_state_figure_rows(oracle):
+    # Fig. "A device state": rows 0,1,3 non-empty ("3 data chunks"), row 2 empty
+    fig = _state("0:0,1;1:1,2;3:2,3")
+    st = np.zeros((4, 4, 4), dtype=np.uint8)
+    st[0] = fig
+    st[1] = _state("2:0")                       # exactly the missing chunk
+    ok, out = oracle.apply_collective(st, AG, [0, 1])
+    assert ok and (out[0] == _state("0:0,1;1:1,2;2:0;3:2,3")).all() and (out[1] == out[0]).all()
+    st[1] = _state("3:0")                       # overlaps chunk 3 -> rows not disjoint
+    assert not oracle.apply_collective(st, AG, [0, 1])[0]
+    assert not oracle.apply_collective(st, AR, [0, 1])[0]   # different chunk sets
+
+
+def test_rule_premises(oracle):
+    init = np.zeros((4, 4, 4), dtype=np.uint8)
+    for d in range(4):
+        init[d, :, d] = 1
+    # same data twice: after AllReduce(0,1) another AllReduce(0,1) must fail (columns not disjoint)
+    ok, s1 = oracle.apply_collective(init, AR, [0, 1])
+    assert ok and not oracle.apply_collective(s1, AR, [0, 1])[0]
+    # scatter: contiguous blocks in ascending row order, rank p gets block p
+    ok, s2 = oracle.apply_collective(init, RS, [0, 1])
+    assert ok
+    assert (s2[0] == _state("0:0,1;1:0,1")).all() and (s2[1] == _state("2:0,1;3:0,1")).all()
+    # Sec. 2.3: ReduceScatter(A0,A1) then AllReduce(A0,A1) mixes different chunks -> invalid
+    assert not oracle.apply_collective(s2, AR, [0, 1])[0]
+    # scatter error when the chunk count is not divisible by the group size
+    three = np.zeros((3, 4, 3), dtype=np.uint8)
+    for d in range(3):
+        three[d, :, d] = 1
+    assert not oracle.apply_collective(three, RS, [0, 1, 2])[0]
+    assert oracle.apply_collective(three, AR, [0, 1, 2])[0]
+    # Reduce puts the sum on the first device and clears the others
+    ok, s3 = oracle.apply_collective(init, RD, [1, 3])
+    assert ok and (s3[1] == _state("0:1,3;1:1,3;2:1,3;3:1,3")).all() and not s3[3].any()
+    # Broadcast needs information increase: from the init state the root knows nothing more
+    assert not oracle.apply_collective(init, BC, [0, 1])[0]
+    ok, s4 = oracle.apply_collective(s3, BC, [1, 3])
+    assert ok and (s4[3] == s4[1]).all() and (s4[1] == s3[1]).all()
+    assert not oracle.apply_collective(s4, BC, [1, 3])[0]     # nothing left to tell
+    # AllGather of an empty member is rejected (reading: every member holds something)
+    assert not oracle.apply_collective(s3, AG, [1, 3])[0]
+    # ReduceScatter + AllGather == AllReduce
+    ok, s5 = oracle.apply_collective(s2, AG, [0, 1])
+    assert ok and (s5 == s1).all()
+
+
+# --------------------------------------------------------------------------- groups (Sec. 3.3)
+def _dev(name):
+    return "ABCD".index(name[0]) * 4 + int(name[1])
+
+
+def test_group_table_of_the_paper(oracle):
+    # system hierarchy used as the synthesis hierarchy: one axis of 16 over [1,2,2,4], reduced
+    q = oracle.Query([1, 2, 2, 4], [16], [[1, 2, 2, 4]], [0])
+    level = {"root": 0, "rack": 1, "server": 2, "CPU": 3, "GPU": 4}    # (root,1) is put in front
+    assert q.synthesis_hierarchy() == [1, 1, 2, 2, 4]
+    for slice_name, form_text, groups_text in golden_lines("group_table.txt"):
+        want = sorted(sorted(_dev(n.strip()) for n in g.split(",")) for g in groups_text.split(";"))
+        if form_text == "InsideGroup":
+            got = q.groups_raw(level[slice_name], INSIDE)
+        else:
+            form = PARALLEL if form_text.startswith("Parallel") else MASTER
+            got = q.groups_raw(level[slice_name], form, level[form_text[form_text.index("(") + 1:-1]])
+        assert sorted(got) == want, (slice_name, form_text)
+
+
+@pytest.mark.parametrize("f", [[2, 3, 2], [4, 2, 2, 2], [3, 1, 4]])
+def test_parallel_group_size_and_count_lemma(oracle, f):
+    # Appendix B, lemma "Parallel reduction": (x_i, Parallel(x_j)) has groups of size
+    # x_{j+1}...x_i and x_0...x_j * x_{i+1}...x_n of them.  Levels here are e_0=root, e_1..e_n.
+    q = oracle.Query(f, [math.prod(f)], [f], [0])
+    x = [1] + f
+    n = len(f)
+    for i in range(1, n + 1):
+        for j in range(0, i):
+            size = math.prod(x[j + 1:i + 1])
+            count = math.prod(x[:j + 1]) * math.prod(x[i + 1:])
+            groups = q.groups_raw(i, PARALLEL, j)
+            if size == 1:
+                assert groups == []          # groups of one device are not generated
+            else:
+                assert len(groups) == count and all(len(g) == size for g in groups)
+            master = q.groups_raw(i, MASTER, j)
+            if size > 1:
+                assert len(master) == math.prod(x[:j + 1]) and all(len(g) == size for g in master)
+                assert all(g in groups for g in master)
+        inside = q.groups_raw(i, INSIDE)
+        size = math.prod(x[i + 1:])
+        if size > 1:
+            assert len(inside) == math.prod(x[:i + 1]) and all(len(g) == size for g in inside)
+
+
+def test_synthesis_hierarchies_of_the_overview_table(oracle):
+    # Table "Synthesis hierarchy"
+    m = [[1, 1, 2, 2], [1, 2, 1, 2]]
+    assert oracle.hierarchy_of_matrix(m, [1], "column") == [1, 1, 1, 2, 2, 1, 2, 2]
+    assert oracle.hierarchy_of_matrix(m, [1], "row") == [1, 1, 2, 2, 1, 2, 1, 2]
+    assert oracle.hierarchy_of_matrix(m, [1], "reduction") == [1, 2, 1, 2]
+    m3 = [[1, 2, 3], [4, 5, 6], [7, 8, 9]]
+    assert oracle.hierarchy_of_matrix(m3, [0, 2], "column") == [1, 4, 7, 2, 5, 8, 3, 6, 9]
+    assert oracle.hierarchy_of_matrix(m3, [0, 2], "row") == [1, 2, 3, 4, 5, 6, 7, 8, 9]
+    assert oracle.hierarchy_of_matrix(m3, [0, 2], "reduction") == [1, 2, 3, 7, 8, 9]
+    assert oracle.hierarchy_of_matrix(m3, [0, 2], "collapsed") == [7, 16, 27]
+
+
+# --------------------------------------------------------------------------- running example (Sec. 2)
+@pytest.fixture()
+def running(oracle):
+    # Fig. "overview" (d): matrix [[1,1,2,2],[1,2,1,2]] on [1,2,2,4], reduce along parameter sharding (axis 1)
+    q = oracle.Query([1, 2, 2, 4], [4, 4], [[1, 1, 2, 2], [1, 2, 1, 2]], [1])
+    pats = {}
+    for pid in range(q.n_patterns):
+        g = q.groups(pid)
+        if [0, 1] in g and [2, 3] in g:
+            pats["local"] = pid                  # {A0,A1},{A2,A3},... (Sec. 2.4)
+        elif [0, 8] in g and [1, 9] in g:
+            pats["remote"] = pid                 # A0 with C0 (Sec. 2.3), every device
+        elif [0, 8] in g:
+            pats["roots"] = pid                  # root devices only
+        elif [0, 1, 8, 9] in g:
+            pats["all"] = pid
+    return q, pats
+
+
+def test_running_example_named_programs(running):
+    q, p = running
+    assert set(p) == {"local", "remote", "roots", "all"} and q.n_patterns == 4
+    assert q.synthesis_hierarchy() == [1, 1, 2, 1, 2]
+    # reduction groups: devices with the same data batch, e.g. A0,A1,C0,C1
+    ran, st, goal = q.run_state([p["all"] * 5 + AR])
+    assert goal and sorted(np.nonzero(st[0, 0])[0]) == [0, 1, 8, 9]
+    valid = [
+        [p["all"] * 5 + AR],                                               # Fig. reduction (a)
+        [p["local"] * 5 + AR, p["remote"] * 5 + AR],                       # (b) AllReduce-AllReduce
+        [p["local"] * 5 + RD, p["roots"] * 5 + AR, p["local"] * 5 + BC],   # (c) Reduce-AllReduce-Broadcast
+        [p["local"] * 5 + RS, p["remote"] * 5 + AR, p["local"] * 5 + AG],  # RS-AR-AG (Sec. 4.2)
+    ]
+    for prog in valid:
+        assert q.eval_program(prog)[0], prog
+    # Fig. "Semantically invalid reduction"
+    assert q.run_state([p["local"] * 5 + RS, p["local"] * 5 + AR])[0] == 1      # second step rejected
+    assert q.run_state([p["remote"] * 5 + AR, p["remote"] * 5 + AR])[0] == 1    # A0,C0 reduced twice
+    # every valid program is found by the synthesizer, and only once
+    res = q.synthesize(5)
+    progs = [tuple(res["instr"][i][:res["len"][i]]) for i in range(len(res["index"]))]
+    assert len(set(progs)) == len(progs)
+    for prog in valid:
+        assert tuple(prog) in progs
+
+
+def test_valid_programs_obey_the_validity_lemmas(oracle):
+    # Appendix B: an instruction of a valid program only varies levels that are 1 or on the
+    # reduction axes; with hierarchy (d) that is automatic, so check it on the lowered groups:
+    # every group lies inside one reduction group.
+    card, axes = [2, 2, 4], [4, 4]
+    for x in oracle.enumerate_placements(card, axes):
+        q = oracle.Query(card, axes, x, [1])
+        _, goal, _ = q.run_state([])
+        for pid in range(q.n_patterns):
+            for g in q.groups(pid):
+                # devices of one group must end up reducing with each other
+                ran, st, ok = q.run_state([0 * 5 + AR])
+                assert ok
+                members = set(np.nonzero(st[g[0], 0])[0])
+                assert set(g) <= members
+
+
+# --------------------------------------------------------------------------- enumeration invariants
+def test_unrank_order_and_flat_equals_pruned(oracle):
+    q = oracle.Query([2, 4], [2, 4], [[1, 2], [2, 2]], [1])
+    I = q.alphabet
+    assert q.num_candidates(3) == I + I * I + I ** 3
+    progs = [q.unrank(3, i) for i in range(q.num_candidates(3))]
+    assert [len(p) for p in progs] == [1] * I + [2] * I * I + [3] * I ** 3
+    for block in (progs[:I], progs[I:I + I * I], progs[I + I * I:]):
+        assert block == sorted(block)                      # lexicographic, first instruction most significant
+    res = q.synthesize(3)
+    n, valid, steps = q.eval_indices(3, start=0, count=q.num_candidates(3))
+    assert np.nonzero(valid)[0].tolist() == res["index"].tolist()
+    for i, idx in enumerate(res["index"]):
+        assert q.unrank(3, int(idx)) == res["instr"][i][:res["len"][i]].tolist()
+
+
+def test_single_allreduce_over_the_reduce_axes_is_always_valid(oracle):
+    for card, axes in (([2, 4], [2, 4]), ([4, 2, 4], [4, 8]), ([2, 3, 2], [6, 2])):
+        for x in oracle.enumerate_placements(card, axes):
+            for red in ([0], [1], [0, 1]):
+                q = oracle.Query(card, axes, x, red)
+                assert q.pattern(0)["slice"] == 0 and q.pattern(0)["form"] == INSIDE
+                assert q.eval_program([AR])[0]
+                # RS;AG and Reduce;Broadcast on the same pattern leave the same state
+                _, s_ar, _ = q.run_state([AR])
+                for pair in ([RS, AG], [RD, BC]):
+                    ran, s2, goal = q.run_state(pair)
+                    assert ran == 2 and goal and (s2 == s_ar).all()
+
+
+def test_validity_depends_only_on_the_number_of_levels(oracle):
+    sets = []
+    for f in ([2, 2], [2, 4], [3, 2], [4, 3]):
+        q = oracle.Query(f, [math.prod(f)], [f], [0])
+        sets.append([tuple(r) for r in q.synthesize(4)["instr"].tolist()])
+    assert all(s == sets[0] for s in sets) and len(sets[0]) == 1 + 4 + 30 + 51
+
+
+def test_all_axes_reduced_is_placement_independent(oracle):
+    card, axes = [2, 2, 4], [4, 4]
+    msg = [2.0 ** 20, 2.0 ** 26]
+    ref = None
+    for x in oracle.enumerate_placements(card, axes):
+        q = oracle.Query(card, axes, x, [0, 1], bw=[25e9, 100e9, 300e9], alpha=[20e-6, 10e-6, 5e-6])
+        r = q.synthesize(4, msg)
+        key = (r["index"].tolist(), r["cost"].tolist())
+        ref = ref or key
+        assert key == ref
+
+
+def test_chunk_count_multiple_of_group_size_gives_same_programs(oracle):
+    x = [[1, 2], [2, 2]]
+    base = oracle.Query([2, 4], [2, 4], x, [1]).synthesize(4)["index"].tolist()       # k = D = 8
+    for k in (4, 12, 16):
+        assert oracle.Query([2, 4], [2, 4], x, [1], n_chunks=k).synthesize(4)["index"].tolist() == base
+    fewer = oracle.Query([2, 4], [2, 4], x, [1], n_chunks=1).synthesize(4)
+    assert len(fewer["index"]) < len(base)
+    assert all(RS not in [c % 5 for c in row[:n]] for row, n in zip(fewer["instr"], fewer["len"]))
+
+
+# --------------------------------------------------------------------------- cost (ring alpha-beta reading)
+N26 = float(1 << 26)
+
+
+def test_single_level_allreduce_is_the_textbook_ring(oracle):
+    for g, bw, a in ((8, 300e9, 5e-6), (3, 10e9, 1e-6)):
+        q = oracle.Query([g], [g], [[g]], [0], bw=[bw], alpha=[a])
+        ok, cost, _ = q.eval_program([AR], [N26])
+        assert ok and cost[0] == pytest.approx(2 * (g - 1) * a + 2 * (g - 1) / g * N26 / bw, rel=1e-14)
+
+
+def test_hand_worked_two_level_costs(oracle):
+    # [2 nodes x 4 GPUs], NIC 25 GB/s / 20 us, in-node 300 GB/s / 5 us, one axis of 8, 64 MiB, k = 8
+    q = oracle.Query([2, 4], [8], [[2, 4]], [0], bw=[25e9, 300e9], alpha=[20e-6, 5e-6])
+    pats = {}
+    for pid in range(q.n_patterns):
+        g = q.groups(pid)
+        pats["all" if len(g[0]) == 8 else "node" if g[0] == [0, 1, 2, 3] else "pairs" if len(g) == 4 else "roots"] = pid
+    assert sorted(pats.values()) == [0, 1, 2, 3]
+    n = N26
+    # one AllReduce over 8: 14 steps across nodes; each node uplink carries 2*7/8*n
+    want_a = 14 * 20e-6 + (2 * 7 / 8 * n) / 25e9
+    # RS in node (3 steps, 3/4 n per GPU port); AR over pairs on n/4 bytes: 4 groups share each NIC
+    # -> n bytes through it; AG in node moves 3/4 n again
+    local = 3 * 5e-6 + (3 / 4 * n) / 300e9
+    want_b = local + (2 * 20e-6 + (4 * (2 * 1 / 2 * n / 4)) / 25e9) + local
+    # Reduce to the node root (n bytes into its port), AR between the two roots (n through each NIC),
+    # Broadcast back
+    red = 3 * 5e-6 + n / 300e9
+    want_c = red + (2 * 20e-6 + (2 * 1 / 2 * n) / 25e9) + red
+    for prog, want in (([pats["all"] * 5 + AR], want_a),
+                       ([pats["node"] * 5 + RS, pats["pairs"] * 5 + AR, pats["node"] * 5 + AG], want_b),
+                       ([pats["node"] * 5 + RD, pats["roots"] * 5 + AR, pats["node"] * 5 + BC], want_c)):
+        ok, cost, _ = q.eval_program(prog, [n])
+        assert ok and cost[0] == pytest.approx(want, rel=1e-13), prog
+    assert want_b < want_c < want_a      # Sec. 4.2 Result 5: topology-aware programs win across nodes
+
+
+def test_cost_identities_and_independence(oracle):
+    card, axes, x = [2, 2, 4], [4, 4], [[1, 2, 2], [2, 1, 2]]
+    bw, al = [25e9, 100e9, 300e9], [20e-6, 10e-6, 5e-6]
+    q = oracle.Query(card, axes, x, [0], bw=bw, alpha=al)
+    q0 = oracle.Query(card, axes, x, [0], bw=bw, alpha=[0, 0, 0])
+    q2 = oracle.Query(card, axes, x, [0], bw=[1e9, 7e9, 3e9], alpha=[1e-3, 0, 2e-6])
+    msg = [2.0 ** 20, 2.0 ** 21, 2.0 ** 30]
+    r, r0, r2 = q.synthesize(4, msg), q0.synthesize(4, msg), q2.synthesize(4, msg)
+    assert r["index"].tolist() == r0["index"].tolist() == r2["index"].tolist()     # validity ignores the links
+    assert np.allclose(r0["cost"][:, 1], 2 * r0["cost"][:, 0], rtol=1e-14)         # linear in bytes when alpha = 0
+    assert np.allclose(r0["cost"][:, 2], 1024 * r0["cost"][:, 0], rtol=1e-14)
+    assert (r["cost"] > r0["cost"]).all()
+    # RS;AG on a pattern costs what AR on it costs (the ring identities add up)
+    for pid in range(q.n_patterns):
+        ok1, c1, _ = q.eval_program([pid * 5 + AR], msg)
+        st = q.run_state([pid * 5 + RS, pid * 5 + AG])
+        if st[0] == 2:
+            # cost of the two steps: evaluate through a program that continues to the goal if needed
+            ran, s_ar, _ = q.run_state([pid * 5 + AR])
+            assert (st[1] == s_ar).all()
+
+
+def test_rs_ag_costs_the_same_as_ar_when_both_complete(oracle):
+    q = oracle.Query([2, 4], [8], [[2, 4]], [0], bw=[25e9, 300e9], alpha=[20e-6, 5e-6])
+    msg = [N26, 3.0e6]
+    ok1, c1, _ = q.eval_program([AR], msg)
+    ok2, c2, _ = q.eval_program([RS, AG], msg)
+    assert ok1 and ok2 and np.allclose(c1, c2, rtol=1e-14)
+
+
+# --------------------------------------------------------------------------- top-k
+def test_topk_against_lexsort(oracle):
+    rng = np.random.default_rng(7)
+    for n, k in ((1, 1), (10, 3), (1000, 10), (1000, 2000), (50, 50)):
+        cost = np.round(rng.random(n), 2)            # many ties
+        index = rng.permutation(n).astype(np.uint64)
+        want = np.lexsort((index, cost))[:k]
+        assert oracle.topk(cost, index, k).tolist() == want.tolist()
+    with pytest.raises(ValueError):
+        oracle.topk([1.0, float("nan")], [0, 1], 1)
