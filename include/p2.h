@@ -1,0 +1,174 @@
+/*
+ * p2.h -- C ABI of the MI355X batch evaluator for reduction programs.
+ *
+ * The library evaluates, on one GPU, candidate reduction programs of the P^2
+ * synthesizer (arXiv 2110.10548): a candidate is a sequence of collectives
+ * (AllReduce, ReduceScatter, AllGather, Reduce, Broadcast) in the
+ * InsideGroup / Parallel / Master forms (Sec. 3.3), applied to levels of the
+ * reduction-axis synthesis hierarchy of a parallelism placement (Sec. 3.4).
+ * Every candidate is derived from an integer index, checked against the
+ * device-state semantics of Sec. 3.2 from the init state to the goal state
+ * of Sec. 3.5, costed with a hierarchical ring alpha-beta model in fp64
+ * (Sec. 5 gives the simulator's inputs) and ranked.
+ *
+ * Conventions
+ *  - Every function returns an int32 status: P2_OK or a negative error.  The
+ *    library never throws and never aborts; p2_last_error() returns the text
+ *    of the calling thread's last error.
+ *  - Unless a parameter says "device", every pointer is a HOST pointer.  All
+ *    buffers are caller-owned; the library keeps no caller pointer after a
+ *    call returns.  Device scratch is owned by the library, cached per host
+ *    thread and reused between calls; calls from different host threads do
+ *    not share it.
+ *  - Two-call sizing: a call with cap = 0 (and NULL outputs) only writes the
+ *    required count.  If cap is too small the call returns P2_ENOSPC, the
+ *    required count is still written and the output contents are unspecified.
+ *  - Arrays over hardware levels are outermost level first.
+ */
+#ifndef P2_H
+#define P2_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define P2_OK 0
+#define P2_EINVAL (-1)        /* bad pointer, factor does not divide, empty/duplicate reduce axes,
+                                 prod(axes) != prod(card), placement violating Eq. (1)-(2),
+                                 max_len < 1, candidate count overflowing 64 bits, NaN cost       */
+#define P2_ENOSPC (-2)        /* caller buffer too small                                          */
+#define P2_EUNSUPPORTED (-3)  /* more than 512 devices, 8 levels, 8 axes, max_len > 7, top-k > 1024,
+                                 or a state too large for the selected engine                     */
+#define P2_EDEVICE (-4)       /* a HIP call failed; see p2_last_error()                            */
+
+#define P2_MAX_LEVELS 8
+#define P2_MAX_AXES 8
+#define P2_MAX_DEVICES 512
+#define P2_MAX_LEN 7
+
+/* A hierarchical system (Sec. 2): level j has card[j] children per parent; two devices that
+ * first differ at level j talk through the uplinks of their level-j units, each of bandwidth
+ * bw_bytes_per_s[j] and latency alpha_s[j].  bw and alpha may be NULL where no cost is asked. */
+typedef struct {
+    int32_t n_levels;
+    const int32_t* card;            /* [n_levels], >= 1                       */
+    const double* bw_bytes_per_s;   /* [n_levels], > 0                        */
+    const double* alpha_s;          /* [n_levels], >= 0                       */
+} p2_hierarchy;
+
+/* Sec. 3.1: all parallelism matrices x[n_axes][n_levels] of positive integers whose column
+ * products are card[j] (Eq. 1) and row products are axes[i] (Eq. 2), written row-major into
+ * out[cap][n_axes][n_levels] in lexicographic order of the flattening.  *out_count = number of
+ * matrices.  Host-only; no device work. */
+int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes,
+                                int32_t* out, int64_t cap, int64_t* out_count);
+
+/* Evaluation engines.  Both give identical results; they differ in the state they keep. */
+#define P2_ENGINE_AUTO 0      /* compact engine, literal engine for the candidates it cannot hold */
+#define P2_ENGINE_LITERAL 1   /* R x k masks of R bits per candidate in LDS, one wavefront each   */
+#define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask               */
+
+typedef struct {
+    int32_t n_chunks;    /* k of Sec. 3.2; 0 => number of devices (the paper's choice)           */
+    uint32_t form_mask;  /* bit 0 InsideGroup, bit 1 Parallel, bit 2 Master; 0 => all            */
+    uint32_t op_mask;    /* bits 0..4 = AllReduce, ReduceScatter, AllGather, Reduce, Broadcast;
+                            0 => all                                                             */
+    int32_t algo;        /* 0 = ring (the only cost model)                                       */
+    int32_t topk;        /* 0 => return every valid program; else see p2_synthesize              */
+    int32_t engine;      /* P2_ENGINE_*                                                          */
+    void* hip_stream;    /* hipStream_t to run on; NULL => the default stream                    */
+} p2_options;
+
+/* One program.  instr[t] = pattern_id * 5 + op, op in the order AllReduce, ReduceScatter,
+ * AllGather, Reduce, Broadcast; pattern ids are those of p2_describe_pattern.  index is the
+ * candidate's rank: programs ordered by length, then lexicographically with instr[0] most
+ * significant, the digit of an instruction being pattern_id * (enabled ops) + (rank of op
+ * among the enabled ops). */
+typedef struct {
+    uint64_t index;
+    uint8_t len;
+    uint8_t instr[7];
+} p2_program;
+
+/* Counters of one query (all optional outputs). */
+typedef struct {
+    uint64_t candidates;       /* programs of length <= max_len over the alphabet, all evaluated  */
+    uint64_t steps_executed;   /* instructions applied (a candidate stops at its first bad step)  */
+    uint64_t literal_reruns;   /* candidates the compact engine handed to the literal engine      */
+    int64_t valid;             /* valid programs found                                            */
+    int32_t group_size;        /* R: devices in one reduction group                               */
+    int32_t n_patterns;        /* canonical (slice, form) patterns                                */
+    int32_t alphabet;          /* instructions = patterns x enabled ops                           */
+    int32_t engine;            /* engine that evaluated the bulk of the candidates                */
+} p2_stats;
+
+/* Sec. 3.5 on one placement: evaluate every program of length <= max_len.  A program is valid
+ * iff each instruction satisfies its rule (Sec. 3.2) on every device group of its pattern,
+ * changes the state, and the final state is the goal.  Valid programs are written in ascending
+ * candidate index with cost[i][m] = simulated seconds for msg_bytes[m] (bytes held per device).
+ *
+ * With opt->topk = K > 0 the output is instead n_msg consecutive blocks of kk = min(K, valid)
+ * programs: block m holds the kk cheapest programs for msg_bytes[m] in ascending (cost, index);
+ * out_cost keeps all n_msg costs of each listed program; *out_count = n_msg * kk.
+ *
+ * placement [n_axes][n_levels] row-major; reduce_axes: distinct axis numbers.  n_msg may be 0
+ * (then out_cost is unused and topk must be 0).  stats may be NULL. */
+int32_t p2_synthesize(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
+                      const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len,
+                      const double* msg_bytes, int32_t n_msg, const p2_options* opt,
+                      p2_program* out_prog, double* out_cost /* [cap][n_msg] */, int64_t cap,
+                      int64_t* out_count, uint64_t* out_candidates_evaluated, p2_stats* stats);
+
+/* One query of a batch (same meaning as the arguments of p2_synthesize). */
+typedef struct {
+    const p2_hierarchy* h;
+    const int32_t* axes;
+    int32_t n_axes;
+    const int32_t* placement;
+    const int32_t* reduce_axes;
+    int32_t n_reduce;
+    int32_t max_len;
+    const p2_options* opt;     /* NULL => defaults; hip_stream of the first query is used for all */
+} p2_query;
+
+/* Many placements / reduce sets at once (the synthesizer's outer loop, Sec. 4: every matrix of
+ * every requested reduction).  All queries share msg_bytes.  Results of query i occupy
+ * out_prog[out_offset[i] .. out_offset[i+1]) and the matching rows of out_cost;
+ * out_offset has n_queries + 1 entries; stats (optional) has n_queries entries.
+ * All device work of the batch is enqueued before the single wait at the end. */
+int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
+                            p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset,
+                            p2_stats* stats);
+
+/* The device groups of canonical pattern `pattern_id` on the full system (Sec. 3.3 and the
+ * table of hierarchical communication patterns): slice level and form level are indices into
+ * the synthesis hierarchy e_0 = root, e_1..e_n (form_level = -1 for InsideGroup); form is
+ * 0 InsideGroup, 1 Parallel, 2 Master.  group_of_device[d] = group id (groups numbered by their
+ * smallest device) or -1; rank_in_group[d] = position in ascending device order (rank 0 is the
+ * root of Reduce and Broadcast).  *out_n_patterns (optional) = number of canonical patterns.
+ * Host-only. */
+int32_t p2_describe_pattern(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
+                            const int32_t* reduce_axes, int32_t n_reduce, const p2_options* opt,
+                            int32_t pattern_id, int32_t* slice_level, int32_t* form, int32_t* form_level,
+                            int32_t* group_of_device /* [D] */, int32_t* rank_in_group /* [D] */,
+                            int32_t* out_n_patterns);
+
+/* Positions of the min(k, n) smallest (cost, index) pairs in ascending cost, ties by ascending
+ * index (the simulator's shortlist, Sec. 5).  NaN in cost => P2_EINVAL.  Host arrays; the data
+ * is copied to the GPU and selected there. */
+int32_t p2_topk(const double* cost, const uint64_t* index, int64_t n, int32_t k, int64_t* out_pos);
+
+/* Same on DEVICE arrays: cost, index (n entries each; cost read with stride cost_stride doubles)
+ * and out_pos (min(k, n) entries) are device pointers; stream is a hipStream_t or NULL.
+ * Returns after the result is in out_pos. */
+int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
+                       int64_t* out_pos, void* stream);
+
+const char* p2_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* P2_H */

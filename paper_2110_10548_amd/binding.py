@@ -1,0 +1,230 @@
+"""Thin ctypes binding of libp2.so: same names as include/p2.h, argument marshalling only.
+
+Every step of the evaluation runs inside the library's kernels.  Importing this module
+fails loudly if the library has not been built (python paper_2110_10548_amd/build.py,
+or __graft_entry__.build()).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libp2.so")
+
+P2_OK, P2_EINVAL, P2_ENOSPC, P2_EUNSUPPORTED, P2_EDEVICE = 0, -1, -2, -3, -4
+ENGINE_AUTO, ENGINE_LITERAL, ENGINE_COMPACT = 0, 1, 2
+OPS = ("AllReduce", "ReduceScatter", "AllGather", "Reduce", "Broadcast")
+FORMS = ("InsideGroup", "Parallel", "Master")
+
+
+class P2Error(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("p2 error %d: %s" % (code, text))
+        self.code = code
+
+
+class p2_hierarchy(C.Structure):
+    _fields_ = [("n_levels", C.c_int32), ("card", C.POINTER(C.c_int32)),
+                ("bw_bytes_per_s", C.POINTER(C.c_double)), ("alpha_s", C.POINTER(C.c_double))]
+
+
+class p2_options(C.Structure):
+    _fields_ = [("n_chunks", C.c_int32), ("form_mask", C.c_uint32), ("op_mask", C.c_uint32), ("algo", C.c_int32),
+                ("topk", C.c_int32), ("engine", C.c_int32), ("hip_stream", C.c_void_p)]
+
+
+class p2_program(C.Structure):
+    _fields_ = [("index", C.c_uint64), ("len", C.c_uint8), ("instr", C.c_uint8 * 7)]
+
+
+class p2_stats(C.Structure):
+    _fields_ = [("candidates", C.c_uint64), ("steps_executed", C.c_uint64), ("literal_reruns", C.c_uint64),
+                ("valid", C.c_int64), ("group_size", C.c_int32), ("n_patterns", C.c_int32), ("alphabet", C.c_int32),
+                ("engine", C.c_int32)]
+
+
+class p2_query(C.Structure):
+    _fields_ = [("h", C.POINTER(p2_hierarchy)), ("axes", C.POINTER(C.c_int32)), ("n_axes", C.c_int32),
+                ("placement", C.POINTER(C.c_int32)), ("reduce_axes", C.POINTER(C.c_int32)), ("n_reduce", C.c_int32),
+                ("max_len", C.c_int32), ("opt", C.POINTER(p2_options))]
+
+
+PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.uint8, (7,))])
+assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
+
+EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
+           "p2_topk_device", "p2_last_error")
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libp2.so is not built: run `python paper_2110_10548_amd/build.py` "
+                              "(there is no CPU fallback for the evaluator)")
+        L = C.CDLL(LIB_PATH)
+        i32p, f64p, u64p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_uint64), C.POINTER(C.c_int64)
+        L.p2_last_error.restype = C.c_char_p
+        L.p2_enumerate_placements.restype = C.c_int32
+        L.p2_enumerate_placements.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, C.c_int64, i64p]
+        L.p2_synthesize.restype = C.c_int32
+        L.p2_synthesize.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, i32p, C.c_int32, C.c_int32, f64p,
+                                    C.c_int32, C.POINTER(p2_options), C.c_void_p, f64p, C.c_int64, i64p, u64p,
+                                    C.POINTER(p2_stats)]
+        L.p2_synthesize_batch.restype = C.c_int32
+        L.p2_synthesize_batch.argtypes = [C.POINTER(p2_query), C.c_int32, f64p, C.c_int32, C.c_void_p, f64p, C.c_int64,
+                                          i64p, C.POINTER(p2_stats)]
+        L.p2_describe_pattern.restype = C.c_int32
+        L.p2_describe_pattern.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, i32p, C.c_int32,
+                                          C.POINTER(p2_options), C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p]
+        L.p2_topk.restype = C.c_int32
+        L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
+        L.p2_topk_device.restype = C.c_int32
+        L.p2_topk_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc, allow=()):
+    if rc != P2_OK and rc not in allow:
+        raise P2Error(rc, lib().p2_last_error().decode())
+    return rc
+
+
+def _i32(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.int32))
+
+
+def _f64(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+class _Hier:
+    """Keeps the arrays of a p2_hierarchy alive."""
+
+    def __init__(self, card, bw=None, alpha=None):
+        self.card = _i32(card)
+        self.bw = _f64(bw) if bw is not None else None
+        self.alpha = _f64(alpha) if alpha is not None else None
+        self.c = p2_hierarchy(len(self.card), _p(self.card, C.c_int32),
+                              _p(self.bw, C.c_double) if self.bw is not None else None,
+                              _p(self.alpha, C.c_double) if self.alpha is not None else None)
+
+
+def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None):
+    return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, stream)
+
+
+def p2_enumerate_placements(card, axes):
+    """All parallelism matrices [count][n_axes][n_levels] (Sec. 3.1), lexicographic."""
+    h, axes = _Hier(card), _i32(axes)
+    n = C.c_int64()
+    _check(lib().p2_enumerate_placements(C.byref(h.c), _p(axes, C.c_int32), len(axes), None, 0, C.byref(n)))
+    out = np.zeros((max(n.value, 1), len(axes), len(h.card)), dtype=np.int32)
+    _check(lib().p2_enumerate_placements(C.byref(h.c), _p(axes, C.c_int32), len(axes), _p(out, C.c_int32), n.value, C.byref(n)))
+    return out[:n.value]
+
+
+def p2_describe_pattern(card, axes, placement, reduce_axes, pattern_id, form_mask=7, op_mask=31):
+    h, axes, placement, red = _Hier(card), _i32(axes), _i32(placement), _i32(reduce_axes)
+    opt = _options(form_mask=form_mask, op_mask=op_mask)
+    D = int(np.prod(h.card))
+    s, f, fl, npat = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+    g = np.zeros(D, dtype=np.int32)
+    r = np.zeros(D, dtype=np.int32)
+    _check(lib().p2_describe_pattern(C.byref(h.c), _p(axes, C.c_int32), len(axes), _p(placement, C.c_int32),
+                                     _p(red, C.c_int32), len(red), C.byref(opt), pattern_id, C.byref(s), C.byref(f),
+                                     C.byref(fl), _p(g, C.c_int32), _p(r, C.c_int32), C.byref(npat)))
+    return {"slice": s.value, "form": f.value, "form_level": fl.value, "group_of": g, "rank": r, "n_patterns": npat.value}
+
+
+def p2_num_patterns(card, axes, placement, reduce_axes, form_mask=7):
+    h, axes, placement, red = _Hier(card), _i32(axes), _i32(placement), _i32(reduce_axes)
+    opt = _options(form_mask=form_mask)
+    npat = C.c_int32()
+    _check(lib().p2_describe_pattern(C.byref(h.c), _p(axes, C.c_int32), len(axes), _p(placement, C.c_int32),
+                                     _p(red, C.c_int32), len(red), C.byref(opt), -1, None, None, None, None, None,
+                                     C.byref(npat)), allow=(P2_EINVAL,))
+    return npat.value
+
+
+def _stats_dict(s):
+    return {k: getattr(s, k) for k, _ in p2_stats._fields_}
+
+
+def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
+    """queries: list of dicts with card, bw, alpha, axes, placement, reduce_axes, max_len and optional
+    n_chunks, form_mask, op_mask, topk, engine.  Returns a list of results, one per query:
+    {"programs": structured array, "cost": [n][n_msg], "stats": dict}."""
+    nq = len(queries)
+    keep = []
+    arr = (p2_query * nq)()
+    for i, q in enumerate(queries):
+        h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
+        axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
+        opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), 0, q.get("topk", 0),
+                       q.get("engine", ENGINE_AUTO), stream)
+        keep.append((h, axes, pl, red, opt))
+        arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32), len(red),
+                          int(q["max_len"]), C.pointer(opt))
+    msg = _f64(list(msg_bytes))
+    n_msg = len(msg)
+    offs = np.zeros(nq + 1, dtype=np.int64)
+    stats = (p2_stats * nq)()
+    if cap is None:
+        rc = lib().p2_synthesize_batch(arr, nq, _p(msg, C.c_double), n_msg, None, None, 0, _p(offs, C.c_int64), stats)
+        _check(rc, allow=(P2_ENOSPC,))
+        cap = int(offs[nq])
+    progs = np.zeros(max(cap, 1), dtype=PROGRAM_DTYPE)
+    cost = np.zeros((max(cap, 1), max(n_msg, 1)), dtype=np.float64)
+    _check(lib().p2_synthesize_batch(arr, nq, _p(msg, C.c_double), n_msg, progs.ctypes.data_as(C.c_void_p),
+                                     _p(cost, C.c_double), cap, _p(offs, C.c_int64), stats))
+    out = []
+    for i in range(nq):
+        a, b = int(offs[i]), int(offs[i + 1])
+        out.append({"programs": progs[a:b].copy(), "cost": cost[a:b, :n_msg].copy(), "stats": _stats_dict(stats[i])})
+    return out
+
+
+def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=None, alpha=None, n_chunks=0,
+                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None):
+    """Valid programs of one placement with their simulated costs (through the single-query entry point)."""
+    h, axes_a, pl, red = _Hier(card, bw, alpha), _i32(axes), _i32(placement), _i32(reduce_axes)
+    opt = _options(n_chunks, form_mask, op_mask, 0, topk, engine, stream)
+    msg = _f64(list(msg_bytes))
+    n_msg = len(msg)
+    count, cands, st = C.c_int64(), C.c_uint64(), p2_stats()
+
+    def call(progs_p, cost_p, cap_):
+        return lib().p2_synthesize(C.byref(h.c), _p(axes_a, C.c_int32), len(axes_a), _p(pl, C.c_int32), _p(red, C.c_int32),
+                                   len(red), max_len, _p(msg, C.c_double), n_msg, C.byref(opt), progs_p, cost_p, cap_,
+                                   C.byref(count), C.byref(cands), C.byref(st))
+    if cap is None:
+        _check(call(None, None, 0), allow=(P2_ENOSPC,))
+        cap = count.value
+    progs = np.zeros(max(cap, 1), dtype=PROGRAM_DTYPE)
+    cost = np.zeros((max(cap, 1), max(n_msg, 1)), dtype=np.float64)
+    _check(call(progs.ctypes.data_as(C.c_void_p), _p(cost, C.c_double), cap))
+    n = count.value
+    return {"programs": progs[:n].copy(), "cost": cost[:n, :n_msg].copy(), "candidates": cands.value,
+            "stats": _stats_dict(st)}
+
+
+def p2_topk(cost, index, k):
+    cost = _f64(cost)
+    index = np.ascontiguousarray(np.asarray(index, dtype=np.uint64))
+    out = np.zeros(max(min(k, len(cost)), 1), dtype=np.int64)
+    _check(lib().p2_topk(_p(cost, C.c_double), _p(index, C.c_uint64), len(cost), k, _p(out, C.c_int64)))
+    return out[:min(k, len(cost))].copy()
+
+
+def p2_topk_device(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, stream=None):
+    """Device pointers (e.g. torch tensor .data_ptr()); out_pos: int64[min(k, n)] on the device."""
+    _check(lib().p2_topk_device(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, stream))

@@ -1,0 +1,435 @@
+// The C ABI of include/p2.h: argument checks, planning, table upload, kernel launches and
+// copy-back.  All arithmetic of the method runs in the kernels; this file only moves data.
+#include <algorithm>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "p2_device.h"
+#include "p2_plan.h"
+
+namespace p2 {
+hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
+                               p2_program* out_prog, double* out_cost, hipStream_t stream);
+hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
+                               p2_program* out_prog, double* out_cost, hipStream_t stream);
+}
+
+namespace {
+
+thread_local std::string g_err;
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    hipError_t ensure(size_t bytes) {
+        if (bytes <= cap) return hipSuccess;
+        if (p) (void)hipFree(p);
+        p = nullptr; cap = 0;
+        size_t want = std::max(bytes, (size_t)4096);
+        want = (want + 4095) & ~(size_t)4095;
+        hipError_t e = hipMalloc(&p, want);
+        if (e == hipSuccess) cap = want;
+        return e;
+    }
+};
+struct HostBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    hipError_t ensure(size_t bytes) {
+        if (bytes <= cap) return hipSuccess;
+        if (p) (void)hipHostFree(p);
+        p = nullptr; cap = 0;
+        size_t want = std::max(bytes, (size_t)4096);
+        hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
+        if (e == hipSuccess) cap = want;
+        return e;
+    }
+};
+
+// Device scratch owned by the library, one set per host thread, reused between calls.
+struct Ctx {
+    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in;
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos;
+};
+thread_local Ctx g_ctx;
+
+int32_t fail(int32_t code, const std::string& msg) {
+    g_err = msg;
+    return code;
+}
+int32_t hip_fail(hipError_t e, const char* what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return P2_EDEVICE;
+}
+#define P2_HIP(call)                                      \
+    do {                                                  \
+        hipError_t e_ = (call);                           \
+        if (e_ != hipSuccess) return hip_fail(e_, #call); \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct QueryRun {
+    p2::Plan plan;
+    int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk
+    int topk = 0;
+    size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
+    uint32_t valid_cap = 0, rerun_cap = 0;
+    size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
+    uint32_t n_valid = 0, n_rerun = 0;
+    unsigned long long steps = 0;
+    size_t out_first = 0;                 // first row of this query in the sorted/prog/cost buffers
+};
+
+int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
+                  p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset, p2_stats* stats) {
+    using namespace p2;
+    if (!queries || n_queries < 1 || !out_offset) return fail(P2_EINVAL, "null or empty query list");
+    if (n_msg < 0 || (n_msg > 0 && !msg_bytes)) return fail(P2_EINVAL, "bad message size list");
+    if (n_msg > kMaxMsg) return fail(P2_EUNSUPPORTED, "more than 64 message sizes");
+    if (cap < 0 || (cap > 0 && (!out_prog || (n_msg > 0 && !out_cost)))) return fail(P2_EINVAL, "bad output buffers");
+    for (int m = 0; m < n_msg; ++m)
+        if (!(msg_bytes[m] >= 0.0)) return fail(P2_EINVAL, "message size must be >= 0");
+    hipStream_t stream = (queries[0].opt) ? (hipStream_t)queries[0].opt->hip_stream : nullptr;
+    Ctx& C = g_ctx;
+
+    // ---- plan every query on the host
+    std::vector<QueryRun> runs(n_queries);
+    std::string err;
+    for (int i = 0; i < n_queries; ++i) {
+        const p2_query& Q = queries[i];
+        int32_t st = make_plan(Q.h, Q.axes, Q.n_axes, Q.placement, Q.reduce_axes, Q.n_reduce, Q.max_len, Q.opt,
+                               n_msg > 0, runs[i].plan, err);
+        if (st != P2_OK) return fail(st, "query " + std::to_string(i) + ": " + err);
+        runs[i].topk = Q.opt ? Q.opt->topk : 0;
+        if (runs[i].topk < 0) return fail(P2_EINVAL, "topk < 0");
+        if (runs[i].topk > kMaxTopK) return fail(P2_EUNSUPPORTED, "topk > 1024");
+        if (runs[i].topk > 0 && n_msg == 0) return fail(P2_EINVAL, "topk needs at least one message size");
+        const int want = Q.opt ? Q.opt->engine : P2_ENGINE_AUTO;
+        const Plan& pl = runs[i].plan;
+        const bool lit_ok = literal_lds_bytes(pl.R, pl.k) != 0;
+        const bool cmp_ok = compact_lds_bytes(pl.R, pl.k) != 0;
+        if (want == P2_ENGINE_LITERAL) {
+            if (!lit_ok) return fail(P2_EUNSUPPORTED, "state too large for the literal engine");
+            runs[i].engine = P2_ENGINE_LITERAL;
+        } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO) {
+            if (cmp_ok) runs[i].engine = P2_ENGINE_COMPACT;
+            else if (lit_ok && want == P2_ENGINE_AUTO) runs[i].engine = P2_ENGINE_LITERAL;
+            else return fail(P2_EUNSUPPORTED, "state too large for the available engines");
+        } else return fail(P2_EINVAL, "unknown engine");
+        if ((size_t)pl.patterns.size() > (size_t)kMaxPatterns) return fail(P2_EUNSUPPORTED, "more than 64 patterns");
+    }
+
+    // ---- lay out the table blob: queries, message sizes, bandwidth rows
+    size_t off = 0;
+    for (auto& r : runs) { r.off_query = off; off += align_up(sizeof(DevQuery), 256); }
+    const size_t off_msg = off;
+    off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
+    for (auto& r : runs) {
+        size_t n_rows = 0, n_ent = 0;
+        for (const Pattern& p : r.plan.patterns) { n_rows += p.row_level.size(); n_ent += p.entries.size(); }
+        r.off_rowptr = off; off += align_up(sizeof(int32_t) * (n_rows + 1), 16);
+        r.off_rowlevel = off; off += align_up(sizeof(int32_t) * std::max<size_t>(n_rows, 1), 16);
+        r.off_entries = off; off += align_up(sizeof(uint32_t) * std::max<size_t>(n_ent, 1), 256);
+    }
+    const size_t blob_bytes = off;
+    P2_HIP(C.blob.ensure(blob_bytes));
+    P2_HIP(C.h_blob.ensure(blob_bytes));
+    P2_HIP(C.counters.ensure(sizeof(DevCounters) * (size_t)n_queries));
+    P2_HIP(C.h_counters.ensure(sizeof(DevCounters) * (size_t)n_queries));
+
+    // valid / rerun list capacities (grown and retried if a query overflows them)
+    auto layout_lists = [&]() {
+        size_t v = 0, rr = 0;
+        for (auto& r : runs) { r.off_valid = v; v += r.valid_cap; r.off_rerun = rr; rr += r.rerun_cap; }
+        return std::make_pair(v, rr);
+    };
+    for (auto& r : runs) {
+        const unsigned long long N = r.plan.n_candidates;
+        r.valid_cap = (uint32_t)std::min<unsigned long long>(N, 1u << 15);
+        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT) ? (uint32_t)std::min<unsigned long long>(N, 1u << 12) : 0u;
+    }
+
+    char* hb = static_cast<char*>(C.h_blob.p);
+    char* db = static_cast<char*>(C.blob.p);
+    std::vector<char> done(n_queries, 0);
+    for (int attempt = 0; attempt < 4; ++attempt) {
+        auto tot = layout_lists();
+        P2_HIP(C.valid.ensure(sizeof(unsigned long long) * std::max<size_t>(tot.first, 1)));
+        P2_HIP(C.rerun.ensure(sizeof(unsigned long long) * std::max<size_t>(tot.second, 1)));
+        std::memset(hb, 0, blob_bytes);
+        for (int m = 0; m < n_msg; ++m) reinterpret_cast<double*>(hb + off_msg)[m] = msg_bytes[m];
+        for (int i = 0; i < n_queries; ++i) {
+            QueryRun& r = runs[i];
+            const Plan& pl = r.plan;
+            DevQuery* dq = reinterpret_cast<DevQuery*>(hb + r.off_query);
+            dq->R = pl.R; dq->k = pl.k;
+            dq->MW = (pl.R + 31) / 32; dq->KW = (pl.k + 31) / 32;
+            dq->n_patterns = (int)pl.patterns.size(); dq->n_ops = pl.n_ops; dq->alphabet = pl.alphabet;
+            dq->max_len = pl.max_len; dq->n_levels = pl.n; dq->n_msg = n_msg;
+            dq->n_candidates = pl.n_candidates;
+            for (int l = 0; l <= P2_MAX_LEN + 1; ++l) dq->base[l] = pl.base[l];
+            for (int o = 0; o < pl.n_ops; ++o) dq->ops[o] = (uint8_t)pl.ops[o];
+            for (int j = 0; j < pl.n; ++j) { dq->alpha[j] = pl.alpha[j]; dq->inv_bw[j] = 1.0 / pl.bw[j]; }
+            int32_t* rp = reinterpret_cast<int32_t*>(hb + r.off_rowptr);
+            int32_t* rl = reinterpret_cast<int32_t*>(hb + r.off_rowlevel);
+            uint32_t* en = reinterpret_cast<uint32_t*>(hb + r.off_entries);
+            int row = 0, ent = 0;
+            rp[0] = 0;
+            for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
+                const Pattern& p = pl.patterns[pi];
+                DevPattern& dp = dq->pat[pi];
+                dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.lo;
+                dp.row_begin = row;
+                for (size_t t = 0; t < p.row_level.size(); ++t) {
+                    for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
+                    rl[row] = p.row_level[t];
+                    rp[++row] = ent;
+                }
+                dp.row_end = row;
+            }
+            dq->row_ptr = reinterpret_cast<const int32_t*>(db + r.off_rowptr);
+            dq->row_level = reinterpret_cast<const int32_t*>(db + r.off_rowlevel);
+            dq->entries = reinterpret_cast<const uint32_t*>(db + r.off_entries);
+            dq->msg_bytes = reinterpret_cast<const double*>(db + off_msg);
+            dq->valid_idx = static_cast<unsigned long long*>(C.valid.p) + r.off_valid;
+            dq->rerun_idx = static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun;
+            dq->valid_cap = r.valid_cap; dq->rerun_cap = r.rerun_cap;
+            dq->counters = static_cast<DevCounters*>(C.counters.p) + i;
+        }
+        P2_HIP(hipMemcpyAsync(db, hb, blob_bytes, hipMemcpyHostToDevice, stream));
+        P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters) * (size_t)n_queries, stream));
+        // ---- evaluate every candidate of every query
+        for (int i = 0; i < n_queries; ++i) {
+            QueryRun& r = runs[i];
+            const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
+            if (r.engine == P2_ENGINE_COMPACT) {
+                P2_HIP(launch_eval_compact(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, stream));
+                // candidates whose state the compact engine cannot hold are re-run literally
+                if (literal_lds_bytes(r.plan.R, r.plan.k) != 0 && r.rerun_cap > 0)
+                    P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.rerun_cap,
+                                               static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun,
+                                               &(static_cast<DevCounters*>(C.counters.p) + i)->n_rerun, stream));
+            } else {
+                P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, nullptr, nullptr, stream));
+            }
+        }
+        P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
+                              hipMemcpyDeviceToHost, stream));
+        P2_HIP(hipStreamSynchronize(stream));
+        bool again = false;
+        const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
+        for (int i = 0; i < n_queries; ++i) {
+            QueryRun& r = runs[i];
+            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.steps = hc[i].steps;
+            if (r.n_rerun > 0 && literal_lds_bytes(r.plan.R, r.plan.k) == 0)
+                return fail(P2_EUNSUPPORTED, "a candidate needs the literal engine but its state does not fit");
+            if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
+                again = true;
+                r.valid_cap = std::max(r.valid_cap, r.n_valid);
+                r.rerun_cap = std::max(r.rerun_cap, r.n_rerun);
+            }
+        }
+        if (!again) break;
+        if (attempt == 3) return fail(P2_EDEVICE, "result lists kept overflowing");
+    }
+
+    // ---- order, cost, select
+    size_t total_valid = 0;
+    for (auto& r : runs) { r.out_first = total_valid; total_valid += r.n_valid; }
+    const size_t nm = (size_t)std::max(n_msg, 1);
+    P2_HIP(C.sorted.ensure(sizeof(unsigned long long) * std::max<size_t>(total_valid, 1)));
+    P2_HIP(C.progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
+    P2_HIP(C.costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
+    size_t topk_rows = 0, topk_scratch = 0;
+    for (auto& r : runs)
+        if (r.topk > 0 && r.n_valid > 0) {
+            topk_rows += (size_t)n_msg * std::min<size_t>(r.topk, r.n_valid);
+            topk_scratch = std::max(topk_scratch, topk_scratch_bytes(r.n_valid, r.topk));
+        }
+    P2_HIP(C.topk_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
+    P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
+    size_t pos_off = 0;
+    for (int i = 0; i < n_queries; ++i) {
+        QueryRun& r = runs[i];
+        if (r.n_valid == 0) continue;
+        const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
+        unsigned long long* sorted = static_cast<unsigned long long*>(C.sorted.p) + r.out_first;
+        p2_program* progs = static_cast<p2_program*>(C.progs.p) + r.out_first;
+        double* costs = static_cast<double*>(C.costs.p) + r.out_first * nm;
+        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p) + r.off_valid, sorted, r.n_valid, stream));
+        if (r.engine == P2_ENGINE_COMPACT && r.n_rerun == 0)
+            P2_HIP(launch_cost_compact(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs, stream));
+        else
+            P2_HIP(launch_cost_literal(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs, stream));
+        if (r.topk > 0) {
+            const size_t kk = std::min<size_t>(r.topk, r.n_valid);
+            for (int m = 0; m < n_msg; ++m) {
+                P2_HIP(launch_topk(costs + m, n_msg, sorted, r.n_valid, r.topk,
+                                   static_cast<long long*>(C.topk_pos.p) + pos_off, C.topk_scratch.p,
+                                   &static_cast<DevCounters*>(C.counters.p)[i].nan_seen, stream));
+                pos_off += kk;
+            }
+        }
+    }
+    P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
+    P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
+    P2_HIP(C.h_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
+    if (total_valid > 0) {
+        P2_HIP(hipMemcpyAsync(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid, hipMemcpyDeviceToHost, stream));
+        if (n_msg > 0)
+            P2_HIP(hipMemcpyAsync(C.h_costs.p, C.costs.p, sizeof(double) * total_valid * nm, hipMemcpyDeviceToHost, stream));
+    }
+    if (topk_rows > 0)
+        P2_HIP(hipMemcpyAsync(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, hipMemcpyDeviceToHost, stream));
+    P2_HIP(hipStreamSynchronize(stream));
+
+    // ---- hand the results over
+    const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);
+    const double* hcst = static_cast<const double*>(C.h_costs.p);
+    const long long* hpos = static_cast<const long long*>(C.h_pos.p);
+    int64_t need = 0;
+    for (auto& r : runs) need += r.topk > 0 ? (int64_t)n_msg * (int64_t)std::min<size_t>(r.topk, r.n_valid) : (int64_t)r.n_valid;
+    int64_t w = 0;
+    pos_off = 0;
+    const bool store = cap >= need && cap > 0;
+    for (int i = 0; i < n_queries; ++i) {
+        QueryRun& r = runs[i];
+        out_offset[i] = w;
+        if (r.topk > 0) {
+            const size_t kk = std::min<size_t>(r.topk, r.n_valid);
+            for (int m = 0; m < n_msg; ++m)
+                for (size_t t = 0; t < kk; ++t, ++w) {
+                    const long long pos = hpos[pos_off++];
+                    if (!store) continue;
+                    if (pos < 0 || pos >= (long long)r.n_valid) return fail(P2_EDEVICE, "top-k returned a bad position");
+                    out_prog[w] = hp[r.out_first + pos];
+                    for (int c = 0; c < n_msg; ++c) out_cost[w * n_msg + c] = hcst[(r.out_first + pos) * nm + c];
+                }
+        } else {
+            if (store) {
+                std::memcpy(out_prog + w, hp + r.out_first, sizeof(p2_program) * r.n_valid);
+                if (n_msg > 0) std::memcpy(out_cost + w * n_msg, hcst + r.out_first * nm, sizeof(double) * r.n_valid * nm);
+            }
+            w += r.n_valid;
+        }
+        if (stats) {
+            p2_stats& s = stats[i];
+            s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun;
+            s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
+            s.alphabet = r.plan.alphabet; s.engine = r.engine;
+        }
+    }
+    out_offset[n_queries] = w;
+    if (!store && need > 0) return fail(P2_ENOSPC, "output buffer too small: " + std::to_string(need) + " rows needed");
+    return P2_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* p2_last_error(void) { return g_err.c_str(); }
+
+int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, int32_t* out, int64_t cap,
+                                int64_t* out_count) {
+    std::string err;
+    int32_t st = p2::enumerate_placements(h, axes, n_axes, out, cap, out_count, err);
+    if (st != P2_OK) g_err = err;
+    return st;
+}
+
+int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
+                            p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset, p2_stats* stats) {
+    try {
+        return run_batch(queries, n_queries, msg_bytes, n_msg, out_prog, out_cost, cap, out_offset, stats);
+    } catch (const std::exception& e) {
+        return fail(P2_EDEVICE, std::string("host failure: ") + e.what());
+    }
+}
+
+int32_t p2_synthesize(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
+                      const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len, const double* msg_bytes, int32_t n_msg,
+                      const p2_options* opt, p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_count,
+                      uint64_t* out_candidates_evaluated, p2_stats* stats) {
+    if (!out_count) return fail(P2_EINVAL, "out_count is null");
+    p2_query q{h, axes, n_axes, placement, reduce_axes, n_reduce, max_len, opt};
+    int64_t offs[2] = {0, 0};
+    p2_stats st;
+    std::memset(&st, 0, sizeof st);
+    int32_t rc = p2_synthesize_batch(&q, 1, msg_bytes, n_msg, out_prog, out_cost, cap, offs, &st);
+    if (rc == P2_OK || rc == P2_ENOSPC) {
+        *out_count = offs[1];
+        if (out_candidates_evaluated) *out_candidates_evaluated = st.candidates;
+        if (stats) *stats = st;
+    }
+    return rc;
+}
+
+int32_t p2_describe_pattern(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
+                            const int32_t* reduce_axes, int32_t n_reduce, const p2_options* opt, int32_t pattern_id,
+                            int32_t* slice_level, int32_t* form, int32_t* form_level, int32_t* group_of_device,
+                            int32_t* rank_in_group, int32_t* out_n_patterns) {
+    try {
+        p2::Plan pl;
+        std::string err;
+        int32_t st = p2::make_plan(h, axes, n_axes, placement, reduce_axes, n_reduce, 1, opt, false, pl, err);
+        if (st != P2_OK) return fail(st, err);
+        if (out_n_patterns) *out_n_patterns = (int32_t)pl.patterns.size();
+        if (pattern_id < 0 || pattern_id >= (int32_t)pl.patterns.size()) return fail(P2_EINVAL, "pattern id out of range");
+        const p2::Pattern& p = pl.patterns[pattern_id];
+        if (slice_level) *slice_level = p.slice;
+        if (form) *form = p.form;
+        if (form_level) *form_level = p.form_level;
+        if (group_of_device && rank_in_group) p2::describe_pattern(pl, pattern_id, group_of_device, rank_in_group);
+        return P2_OK;
+    } catch (const std::exception& e) {
+        return fail(P2_EDEVICE, std::string("host failure: ") + e.what());
+    }
+}
+
+int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
+                       int64_t* out_pos, void* stream_) {
+    using namespace p2;
+    if (n < 0 || k < 0 || cost_stride < 1) return fail(P2_EINVAL, "bad n, k or stride");
+    if (k > kMaxTopK) return fail(P2_EUNSUPPORTED, "topk > 1024");
+    if (n == 0 || k == 0) return P2_OK;
+    if (!cost || !index || !out_pos) return fail(P2_EINVAL, "null argument");
+    hipStream_t stream = (hipStream_t)stream_;
+    Ctx& C = g_ctx;
+    P2_HIP(C.topk_scratch.ensure(topk_scratch_bytes(n, k)));
+    P2_HIP(C.counters.ensure(sizeof(DevCounters)));
+    P2_HIP(C.h_counters.ensure(sizeof(DevCounters)));
+    P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters), stream));
+    DevCounters* dc = static_cast<DevCounters*>(C.counters.p);
+    P2_HIP(launch_topk(cost, cost_stride, reinterpret_cast<const unsigned long long*>(index), n, k,
+                       reinterpret_cast<long long*>(out_pos), C.topk_scratch.p, &dc->nan_seen, stream));
+    P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters), hipMemcpyDeviceToHost, stream));
+    P2_HIP(hipStreamSynchronize(stream));
+    if (static_cast<const DevCounters*>(C.h_counters.p)->nan_seen) return fail(P2_EINVAL, "NaN cost");
+    return P2_OK;
+}
+
+int32_t p2_topk(const double* cost, const uint64_t* index, int64_t n, int32_t k, int64_t* out_pos) {
+    using namespace p2;
+    if (n < 0 || k < 0) return fail(P2_EINVAL, "bad n or k");
+    if (k > kMaxTopK) return fail(P2_EUNSUPPORTED, "topk > 1024");
+    if (n == 0 || k == 0) return P2_OK;
+    if (!cost || !index || !out_pos) return fail(P2_EINVAL, "null argument");
+    Ctx& C = g_ctx;
+    const size_t kk = (size_t)std::min<int64_t>(k, n);
+    P2_HIP(C.topk_in.ensure((size_t)n * 16));
+    P2_HIP(C.topk_pos.ensure(kk * sizeof(long long)));
+    double* dcost = static_cast<double*>(C.topk_in.p);
+    uint64_t* didx = reinterpret_cast<uint64_t*>(dcost + n);
+    P2_HIP(hipMemcpy(dcost, cost, (size_t)n * 8, hipMemcpyHostToDevice));
+    P2_HIP(hipMemcpy(didx, index, (size_t)n * 8, hipMemcpyHostToDevice));
+    int32_t rc = p2_topk_device(dcost, 1, didx, n, k, static_cast<int64_t*>(C.topk_pos.p), nullptr);
+    if (rc != P2_OK) return rc;
+    P2_HIP(hipMemcpy(out_pos, C.topk_pos.p, kk * sizeof(long long), hipMemcpyDeviceToHost));
+    return P2_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Structures shared by the host API and the kernels, and the launch entry points.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "../../include/p2.h"
+
+namespace p2 {
+
+constexpr int kMaxPatterns = 64;
+constexpr int kMaxMsg = 64;        // message sizes per call (one wavefront lane each)
+constexpr int kMaxTopK = 1024;
+
+enum : int { OP_AR = 0, OP_RS = 1, OP_AG = 2, OP_RD = 3, OP_BC = 4 };
+
+// One canonical pattern inside a reduction group of R devices numbered by local id: group G is
+// {base(G) + t*s : t < g}; with master only bases whose (id % s) == 0 exist.
+struct DevPattern {
+    int32_t g, s, master, n_groups;
+    int32_t span_level;            // outermost hardware level at which members differ
+    int32_t row_begin, row_end;    // bandwidth rows of this pattern (indices into row_ptr/row_level)
+};
+
+// Counters a query's kernels add to.
+struct DevCounters {
+    uint32_t n_valid;              // entries appended to valid_idx (may exceed valid_cap)
+    uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
+    unsigned long long steps;      // instructions applied
+    uint32_t nan_seen;
+    uint32_t pad;
+};
+
+struct DevQuery {
+    int32_t R, k;                  // devices of one reduction group, chunks
+    int32_t MW, KW;                // 32-bit words per contribution mask / per chunk set
+    int32_t n_patterns, n_ops, alphabet, max_len;
+    int32_t n_levels, n_msg;
+    unsigned long long n_candidates;
+    unsigned long long base[P2_MAX_LEN + 2];   // base[l]: index of the first program of length l
+    uint8_t ops[8];
+    DevPattern pat[kMaxPatterns];
+    double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
+    // bandwidth rows (device pointers into the uploaded table blob)
+    const int32_t* row_ptr;
+    const int32_t* row_level;
+    const uint32_t* entries;       // (local group << 16) | number of system groups touching the unit
+    const double* msg_bytes;       // [n_msg]
+    // outputs of the evaluation kernels
+    unsigned long long* valid_idx;
+    unsigned long long* rerun_idx;
+    uint32_t valid_cap, rerun_cap;
+    DevCounters* counters;
+};
+
+// LDS bytes one wavefront of the literal engine needs for a query (0 = does not fit).
+size_t literal_lds_bytes(int R, int k);
+// LDS bytes one wavefront (64 candidates) of the compact engine needs.
+size_t compact_lds_bytes(int R, int k);
+
+// Evaluate candidates [start, start + count) of query *q (device pointer), or, if list != nullptr,
+// the `count` candidate indices stored at list (device pointer; count may also be read from
+// *list_count when list_count != nullptr).  Valid ones are appended to q->valid_idx.
+hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
+                               const unsigned long long* list, const uint32_t* list_count, hipStream_t stream);
+hipError_t launch_eval_compact(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
+                               hipStream_t stream);
+// sorted[i] = i-th smallest of in[0..n)  (distinct keys)
+hipError_t launch_rank_sort(const unsigned long long* in, unsigned long long* sorted, uint32_t n, hipStream_t stream);
+// For each of the n sorted valid candidates: its program record and its cost for every message size.
+hipError_t launch_cost(const DevQuery* q, int R, int k, int engine, const unsigned long long* sorted, uint32_t n,
+                       p2_program* out_prog, double* out_cost, hipStream_t stream);
+// Top-k of (cost[i * stride], index[i]) over i < n: positions into out_pos[min(k, n)].
+// scratch: device buffer of topk_scratch_bytes(n, k) bytes.  nan_flag: device uint32 set to 1 on NaN.
+size_t topk_scratch_bytes(long long n, int k);
+hipError_t launch_topk(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
+                       long long* out_pos, void* scratch, uint32_t* nan_flag, hipStream_t stream);
+
+}  // namespace p2

@@ -1,0 +1,387 @@
+// Literal engine: the device-state semantics of Sec. 3.2 on the literal state of one reduction
+// group -- R devices x k chunk rows, each row a mask of R contribution bits -- kept in LDS by
+// one wavefront per candidate.  A step works on (group, row) items: an item reads the row of
+// every member of its group, checks the rule's premises, and writes the members' new rows.
+// The same code, with kCost set, recomputes a valid program and adds up its ring alpha-beta
+// step times (hierarchical cost model, see p2.h).
+#include "p2_device.h"
+
+namespace p2 {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr size_t kLdsLimit = 160 * 1024 - 512;
+
+struct LitLayout {
+    int s_words, t_words, ngmax, kw;
+    __host__ __device__ LitLayout(int R, int k, int MW) {
+        ngmax = R / 2 > 0 ? R / 2 : 1;
+        kw = (k + 31) / 32;
+        s_words = R * k * MW;
+        t_words = ngmax * k * MW;
+    }
+    __host__ __device__ int total_words() const { return s_words + t_words + ngmax * (2 + kw) + 512 + 4; }
+};
+
+struct LitLds {
+    uint32_t* S;       // [R][k][MW]   state
+    uint32_t* T;       // [ng][k][MW]  combined rows of each group
+    uint32_t* gcount;  // [ng]         non-empty rows of the group's result / root
+    uint32_t* gflag;   // [ng]         Broadcast: some member differs from the root
+    uint32_t* gbits;   // [ng][kw]     which rows of the group's result are non-empty
+    uint32_t* devne;   // [R] (<=512)  AllGather: device holds something
+    uint32_t* flags;   // [4]          0: premise failed, 1: state changed
+};
+
+__device__ inline LitLds carve(uint32_t* lds, int R, int k, int MW) {
+    LitLayout lay(R, k, MW);
+    LitLds L;
+    L.S = lds;
+    L.T = L.S + lay.s_words;
+    L.gcount = L.T + lay.t_words;
+    L.gflag = L.gcount + lay.ngmax;
+    L.gbits = L.gflag + lay.ngmax;
+    L.devne = L.gbits + lay.ngmax * lay.kw;
+    L.flags = L.devne + 512;
+    return L;
+}
+
+__device__ inline int unrank(const DevQuery& q, unsigned long long idx, uint16_t* digit) {
+    int len = 1;
+    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
+    unsigned long long rem = idx - q.base[len];
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    for (int t = len - 1; t >= 0; --t) {
+        unsigned long long nx = rem / I;
+        digit[t] = (uint16_t)(rem - nx * I);
+        rem = nx;
+    }
+    return len;
+}
+
+__device__ inline double wave_max(double v) {
+    for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// One instruction on the literal state.  All 64 lanes call it with identical arguments.
+// Returns false if a premise fails or nothing changes.  With kCost, *cost_lane (lane m = message
+// size m) gets the step time added.
+template <int MW, bool kCost>
+__device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, int lane, double* cost_lane) {
+    const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    const int kw = (k + 31) / 32;
+    for (int i = lane; i < ng; i += kWave) { L.gcount[i] = 0; L.gflag[i] = 0; }
+    for (int i = lane; i < ng * kw; i += kWave) L.gbits[i] = 0;
+    if (op == OP_AG)
+        for (int i = lane; i < q.R; i += kWave) L.devne[i] = 0;
+    if (lane == 0) { L.flags[0] = 0; L.flags[1] = 0; }
+    __syncthreads();
+
+    const int items = ng * k;
+    bool bad = false;
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / k, r = it - G * k;
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t acc[MW];
+#pragma unroll
+        for (int w = 0; w < MW; ++w) acc[w] = 0;
+        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+            // premises: same non-empty rows on every member; columns of a row pairwise disjoint
+            bool ne0 = false;
+            for (int p = 0; p < g; ++p) {
+                const uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    uint32_t v = x[w];
+                    any |= v;
+                    bad |= (acc[w] & v) != 0;
+                    acc[w] |= v;
+                }
+                if (p == 0) ne0 = any != 0;
+                else bad |= (any != 0) != ne0;
+            }
+            if (ne0) {
+                atomicAdd(&L.gcount[G], 1u);
+                atomicOr(&L.gbits[G * kw + (r >> 5)], 1u << (r & 31));
+            }
+        } else if (op == OP_AG) {
+            // premises: every member holds something; a row is held by at most one member
+            int holders = 0;
+            for (int p = 0; p < g; ++p) {
+                const int dev = base + p * s;
+                const uint32_t* x = L.S + (dev * k + r) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) { uint32_t v = x[w]; any |= v; acc[w] |= v; }
+                if (any) { ++holders; L.devne[dev] = 1; }
+            }
+            bad |= holders > 1;
+            if (holders) atomicAdd(&L.gcount[G], 1u);
+        } else {
+            // Broadcast: the root's row contains every member's row; some member differs somewhere
+            const uint32_t* root = L.S + (base * k + r) * MW;
+            uint32_t any = 0;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) { acc[w] = root[w]; any |= acc[w]; }
+            bool differs = false;
+            for (int p = 1; p < g; ++p) {
+                const uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    uint32_t v = x[w];
+                    bad |= (v & ~acc[w]) != 0;
+                    differs |= v != acc[w];
+                }
+            }
+            if (differs) L.gflag[G] = 1;
+            if (any) atomicAdd(&L.gcount[G], 1u);
+        }
+        uint32_t* t = L.T + (G * k + r) * MW;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) t[w] = acc[w];
+    }
+    if (bad) L.flags[0] = 1;
+    __syncthreads();
+
+    // per-group premises
+    for (int G = lane; G < ng; G += kWave) {
+        const uint32_t cnt = L.gcount[G];
+        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+            if (op == OP_RS && cnt % (uint32_t)g != 0) L.flags[0] = 1;   // scatter: chunks must divide evenly
+            if (cnt) L.flags[1] = 1;                                    // a group of empty devices is a no-op
+        } else if (op == OP_AG) {
+            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            for (int p = 0; p < g; ++p)
+                if (!L.devne[base + p * s]) L.flags[0] = 1;
+            L.flags[1] = 1;
+        } else {
+            if (!L.gflag[G]) L.flags[0] = 1;                            // no information increase
+            L.flags[1] = 1;
+        }
+    }
+    __syncthreads();
+    if (L.flags[0] || !L.flags[1]) return false;
+
+    if (kCost) {
+        // bandwidth term: the most loaded uplink; gcount holds the rows that set a group's bytes
+        double best = 0.0;
+        for (int row = P.row_begin + lane; row < P.row_end; row += kWave) {
+            long long dot = 0;
+            for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
+                const uint32_t ent = q.entries[e];
+                dot += (long long)(ent & 0xffffu) * (long long)L.gcount[ent >> 16];
+            }
+            best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+        }
+        best = wave_max(best);
+        const double gm1 = (double)(g - 1);
+        const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
+        const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)g : (op == OP_RS || op == OP_AG) ? gm1 / (double)g : 1.0;
+        if (lane < q.n_msg) *cost_lane += ring_steps * q.alpha[P.span_level] + q.msg_bytes[lane] * (mult / (double)k) * best;
+    }
+
+    // write the members' new rows
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / k, r = it - G * k;
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t t[MW];
+        uint32_t any = 0;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) { t[w] = L.T[(G * k + r) * MW + w]; any |= t[w]; }
+        int owner = -2;                                   // -2: everyone, else the only member keeping the row
+        if (op == OP_RD) owner = 0;
+        else if (op == OP_RS) {
+            owner = -1;
+            if (any) {
+                // position of row r among the group's non-empty rows, ascending
+                int before = 0;
+                for (int w = 0; w < (r >> 5); ++w) before += __popc(L.gbits[G * kw + w]);
+                before += __popc(L.gbits[G * kw + (r >> 5)] & ((1u << (r & 31)) - 1u));
+                owner = before / (int)(L.gcount[G] / (uint32_t)g);
+            }
+        }
+        for (int p = (op == OP_BC ? 1 : 0); p < g; ++p) {
+            uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
+            const bool keep = owner == -2 || owner == p;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) x[w] = keep ? t[w] : 0u;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+template <int MW>
+__device__ inline void lit_init(const DevQuery& q, const LitLds& L, int lane) {
+    // Sec. 3.5: device i holds column i in every row
+    const int cells = q.R * q.k;
+    for (int c = lane; c < cells; c += kWave) {
+        const int d = c / q.k;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) L.S[c * MW + w] = (w == (d >> 5)) ? (1u << (d & 31)) : 0u;
+    }
+    __syncthreads();
+}
+
+template <int MW>
+__device__ inline bool lit_is_goal(const DevQuery& q, const LitLds& L, int lane) {
+    // every device holds, in every row, the columns of its whole reduction group
+    const int cells = q.R * q.k;
+    bool ok = true;
+    for (int c = lane; c < cells; c += kWave) {
+#pragma unroll
+        for (int w = 0; w < MW; ++w) {
+            const int bits = q.R - 32 * w;
+            const uint32_t full = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+            ok &= L.S[c * MW + w] == full;
+        }
+    }
+    return __all(ok);
+}
+
+// One wavefront per candidate; a block takes `per_block` consecutive candidates.
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restrict__ qp, unsigned long long start,
+                                                        unsigned long long count, uint32_t per_block,
+                                                        const unsigned long long* __restrict__ list,
+                                                        const uint32_t* __restrict__ list_count) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    const LitLds L = carve(lds, q.R, q.k, MW);
+    if (list_count) {
+        unsigned long long n = *list_count;
+        if (n < count) count = n;
+    }
+    unsigned long long first = (unsigned long long)blockIdx.x * per_block;
+    unsigned long long steps = 0;
+    for (uint32_t i = 0; i < per_block && first + i < count; ++i) {
+        const unsigned long long idx = list ? list[first + i] : start + first + i;
+        uint16_t digit[P2_MAX_LEN + 1];
+        const int len = unrank(q, idx, digit);
+        lit_init<MW>(q, L, lane);
+        bool ok = true;
+        for (int t = 0; t < len && ok; ++t) {
+            const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+            ++steps;
+            ok = lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr);
+        }
+        if (ok && lit_is_goal<MW>(q, L, lane) && lane == 0) {
+            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+            if (pos < q.valid_cap) q.valid_idx[pos] = idx;
+        }
+        __syncthreads();
+    }
+    if (lane == 0 && steps) atomicAdd(&q.counters->steps, steps);
+}
+
+// Cost of valid programs: block i re-runs sorted[i] with the cost terms switched on and writes
+// the program record and cost[i][0..n_msg).
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_cost_literal(const DevQuery* __restrict__ qp,
+                                                        const unsigned long long* __restrict__ sorted, uint32_t n,
+                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    const LitLds L = carve(lds, q.R, q.k, MW);
+    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        const unsigned long long idx = sorted[i];
+        uint16_t digit[P2_MAX_LEN + 1];
+        const int len = unrank(q, idx, digit);
+        lit_init<MW>(q, L, lane);
+        double cost = 0.0;
+        bool ok = true;
+        for (int t = 0; t < len && ok; ++t) {
+            const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+            ok = lit_step<MW, true>(q, q.pat[pid], op, L, lane, &cost);
+        }
+        if (lane == 0) {
+            p2_program pr;
+            pr.index = idx;
+            pr.len = (uint8_t)len;
+            for (int t = 0; t < 7; ++t) {
+                int code = 0;
+                if (t < len) { const int pid = digit[t] / q.n_ops; code = pid * 5 + q.ops[digit[t] - pid * q.n_ops]; }
+                pr.instr[t] = (uint8_t)code;
+            }
+            out_prog[i] = pr;
+        }
+        if (lane < q.n_msg) out_cost[(size_t)i * q.n_msg + lane] = ok ? cost : __longlong_as_double(0x7ff8000000000000ll);
+        __syncthreads();
+    }
+}
+
+template <typename F>
+hipError_t allow_big_lds(F func, size_t bytes) {
+    if (bytes <= 48 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(func), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+inline int mask_words(int R) { return R <= 32 ? 1 : R <= 64 ? 2 : R <= 128 ? 4 : R <= 256 ? 8 : 16; }
+
+}  // namespace
+
+size_t literal_lds_bytes(int R, int k) {
+    LitLayout lay(R, k, mask_words(R));
+    size_t bytes = (size_t)lay.total_words() * 4;
+    return bytes <= kLdsLimit ? bytes : 0;
+}
+
+hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
+                               const unsigned long long* list, const uint32_t* list_count, hipStream_t stream) {
+    if (count == 0) return hipSuccess;
+    const size_t lds = literal_lds_bytes(R, k);
+    if (lds == 0) return hipErrorInvalidValue;
+    const int MW = mask_words(R);
+    // enough blocks to fill 256 CUs several times over, at most 64 candidates per block
+    uint32_t per_block = 64;
+    while (per_block > 1 && (count + per_block - 1) / per_block < 8192) per_block >>= 1;
+    const unsigned long long blocks = (count + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_eval_literal<MWV>, lds);                                                               \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_eval_literal<MWV>, dim3((unsigned)blocks), dim3(kWave), lds, stream, q, start,    \
+                           count, per_block, list, list_count);
+    switch (MW) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
+                               p2_program* out_prog, double* out_cost, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const size_t lds = literal_lds_bytes(R, k);
+    if (lds == 0) return hipErrorInvalidValue;
+    const int MW = mask_words(R);
+    const unsigned blocks = n < 65536u ? n : 65536u;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_cost_literal<MWV>, lds);                                                               \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_cost_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, sorted, n, out_prog, out_cost);
+    switch (MW) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+}  // namespace p2

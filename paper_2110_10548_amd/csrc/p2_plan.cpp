@@ -1,0 +1,339 @@
+// Host-side planning (see p2_plan.h).  Sections cited are those of arXiv 2110.10548.
+#include "p2_plan.h"
+
+#include <algorithm>
+#include <map>
+
+namespace p2 {
+
+// ---------------------------------------------------------------------------------------------
+// Sec. 3.1.  A row of the matrix is a factorisation of its axis over the levels with each factor
+// dividing the level's cardinality; rows are generated in lexicographic order and combined row by
+// row under the column constraint, which yields the lexicographic order of the flattening.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+void row_factorisations(const int32_t* card, int n, int j, int64_t left, std::vector<int32_t>& cur,
+                        std::vector<std::vector<int32_t>>& out) {
+    if (j == n) {
+        if (left == 1) out.push_back(cur);
+        return;
+    }
+    for (int32_t v = 1; v <= card[j]; ++v) {
+        if (card[j] % v != 0 || left % v != 0) continue;
+        cur[j] = v;
+        row_factorisations(card, n, j + 1, left / v, cur, out);
+    }
+}
+
+struct PlaceCtx {
+    int n, m;
+    std::vector<std::vector<std::vector<int32_t>>> rows;   // per axis, its factorisations
+    std::vector<int64_t> col_left;
+    std::vector<const std::vector<int32_t>*> chosen;
+    int32_t* out;
+    int64_t cap, count;
+};
+
+void place_rows(PlaceCtx& c, int i) {
+    if (i == c.m) {
+        for (int j = 0; j < c.n; ++j)
+            if (c.col_left[j] != 1) return;
+        if (c.count < c.cap)
+            for (int a = 0; a < c.m; ++a)
+                for (int j = 0; j < c.n; ++j) c.out[(c.count * c.m + a) * c.n + j] = (*c.chosen[a])[j];
+        ++c.count;
+        return;
+    }
+    for (const auto& row : c.rows[i]) {
+        bool ok = true;
+        for (int j = 0; j < c.n && ok; ++j) ok = (c.col_left[j] % row[j] == 0);
+        if (!ok) continue;
+        for (int j = 0; j < c.n; ++j) c.col_left[j] /= row[j];
+        c.chosen[i] = &row;
+        place_rows(c, i + 1);
+        for (int j = 0; j < c.n; ++j) c.col_left[j] *= row[j];
+    }
+}
+
+int32_t check_hierarchy(const p2_hierarchy* h, bool need_links, int64_t& devices, std::string& err) {
+    if (!h || !h->card) { err = "null hierarchy"; return P2_EINVAL; }
+    if (h->n_levels < 1) { err = "n_levels < 1"; return P2_EINVAL; }
+    if (h->n_levels > P2_MAX_LEVELS) { err = "more than 8 hardware levels"; return P2_EUNSUPPORTED; }
+    devices = 1;
+    for (int j = 0; j < h->n_levels; ++j) {
+        if (h->card[j] < 1) { err = "level cardinality < 1"; return P2_EINVAL; }
+        devices *= h->card[j];
+        if (devices > (int64_t)1 << 40) { err = "too many devices"; return P2_EUNSUPPORTED; }
+    }
+    if (need_links) {
+        if (!h->bw_bytes_per_s || !h->alpha_s) { err = "bandwidth/latency arrays are required for costs"; return P2_EINVAL; }
+        for (int j = 0; j < h->n_levels; ++j) {
+            if (!(h->bw_bytes_per_s[j] > 0.0)) { err = "bandwidth must be > 0"; return P2_EINVAL; }
+            if (!(h->alpha_s[j] >= 0.0)) { err = "latency must be >= 0"; return P2_EINVAL; }
+        }
+    }
+    return P2_OK;
+}
+
+}  // namespace
+
+int32_t enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, int32_t* out, int64_t cap,
+                             int64_t* out_count, std::string& err) {
+    int64_t devices = 0;
+    int32_t st = check_hierarchy(h, false, devices, err);
+    if (st != P2_OK) return st;
+    if (!axes || !out_count) { err = "null argument"; return P2_EINVAL; }
+    if (n_axes < 1) { err = "n_axes < 1"; return P2_EINVAL; }
+    if (n_axes > P2_MAX_AXES) { err = "more than 8 axes"; return P2_EUNSUPPORTED; }
+    if (cap < 0 || (cap > 0 && !out)) { err = "bad output buffer"; return P2_EINVAL; }
+    int64_t prod = 1;
+    for (int i = 0; i < n_axes; ++i) {
+        if (axes[i] < 1) { err = "axis size < 1"; return P2_EINVAL; }
+        prod *= axes[i];
+        if (prod > (int64_t)1 << 40) break;
+    }
+    if (prod != devices) { err = "product of axes differs from the number of devices"; return P2_EINVAL; }
+    PlaceCtx c;
+    c.n = h->n_levels; c.m = n_axes; c.out = out; c.cap = cap; c.count = 0;
+    c.rows.resize(n_axes);
+    c.chosen.resize(n_axes);
+    std::vector<int32_t> cur(c.n);
+    for (int i = 0; i < n_axes; ++i) row_factorisations(h->card, c.n, 0, axes[i], cur, c.rows[i]);
+    c.col_left.assign(h->card, h->card + c.n);
+    place_rows(c, 0);
+    *out_count = c.count;
+    if (c.count > cap && cap > 0) { err = "placement buffer too small"; return P2_ENOSPC; }
+    return P2_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Bandwidth rows of one pattern.  A group whose members first differ at hardware level `lo`
+// crosses the uplink of every level-j unit (j >= lo) that holds one of its members; the load of
+// a unit is the sum of the bytes of those groups (they all belong to this pattern).  Groups of
+// different copies with the same local group id carry the same bytes, so a unit is described by
+// how many groups of each local id touch it.  Units with equal descriptions are merged, and a
+// unit is dropped when another unit of the same level is at least as loaded whatever the bytes.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+inline bool takes_part(const Pattern& p, int local) { return !p.master || (local % p.s) == 0; }
+inline int local_group(const Pattern& p, int local) {
+    int hi = local / (p.g * p.s), lo = local % p.s;
+    return p.master ? hi : hi * p.s + lo;
+}
+
+void build_cost_rows(const Plan& pl, Pattern& p) {
+    p.row_ptr.assign(1, 0);
+    p.row_level.clear();
+    p.entries.clear();
+    const int n_rep = pl.D / pl.R;
+    std::vector<int32_t> stamp((size_t)n_rep * p.n_groups, -1);
+    std::vector<int32_t> cnt(p.n_groups, 0);
+    std::vector<int32_t> touched;
+    int stamp_id = 0;
+    int below = pl.D;
+    for (int j = 0; j < pl.n; ++j) {
+        below /= pl.h[j];
+        if (j < p.lo) continue;
+        std::map<std::vector<uint32_t>, int> seen;
+        std::vector<std::vector<uint32_t>> rows;
+        for (int u = 0; u < pl.D / below; ++u) {
+            ++stamp_id;
+            touched.clear();
+            for (int d = u * below; d < (u + 1) * below; ++d) {
+                int loc = pl.local_of[d];
+                if (!takes_part(p, loc)) continue;
+                int lg = local_group(p, loc);
+                size_t key = (size_t)pl.replica_of[d] * p.n_groups + lg;
+                if (stamp[key] == stamp_id) continue;
+                stamp[key] = stamp_id;
+                if (cnt[lg]++ == 0) touched.push_back(lg);
+            }
+            if (touched.empty()) continue;
+            std::sort(touched.begin(), touched.end());
+            std::vector<uint32_t> row;
+            row.reserve(touched.size());
+            for (int lg : touched) { row.push_back(((uint32_t)lg << 16) | (uint32_t)cnt[lg]); cnt[lg] = 0; }
+            if (seen.emplace(row, 1).second) rows.push_back(std::move(row));
+        }
+        // drop rows dominated by another row of the same level
+        std::vector<char> dead(rows.size(), 0);
+        for (size_t a = 0; a < rows.size(); ++a) {
+            for (size_t b = 0; b < rows.size() && !dead[a]; ++b) {
+                if (a == b || dead[b] || rows[b].size() < rows[a].size()) continue;
+                size_t ib = 0;
+                bool dom = true;
+                for (size_t ia = 0; ia < rows[a].size() && dom; ++ia) {
+                    uint32_t lg = rows[a][ia] >> 16, c = rows[a][ia] & 0xffffu;
+                    while (ib < rows[b].size() && (rows[b][ib] >> 16) < lg) ++ib;
+                    dom = ib < rows[b].size() && (rows[b][ib] >> 16) == lg && (rows[b][ib] & 0xffffu) >= c;
+                }
+                if (dom) dead[a] = 1;
+            }
+        }
+        for (size_t a = 0; a < rows.size(); ++a) {
+            if (dead[a]) continue;
+            p.entries.insert(p.entries.end(), rows[a].begin(), rows[a].end());
+            p.row_ptr.push_back((int32_t)p.entries.size());
+            p.row_level.push_back(j);
+        }
+    }
+}
+
+}  // namespace
+
+int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
+                  const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len, const p2_options* opt, bool with_cost,
+                  Plan& pl, std::string& err) {
+    int64_t devices = 0;
+    int32_t st = check_hierarchy(h, with_cost, devices, err);
+    if (st != P2_OK) return st;
+    if (!axes || !placement || !reduce_axes) { err = "null argument"; return P2_EINVAL; }
+    if (n_axes < 1) { err = "n_axes < 1"; return P2_EINVAL; }
+    if (n_axes > P2_MAX_AXES) { err = "more than 8 axes"; return P2_EUNSUPPORTED; }
+    if (devices > P2_MAX_DEVICES) { err = "more than 512 devices"; return P2_EUNSUPPORTED; }
+    if (n_reduce < 1) { err = "empty set of reduce axes"; return P2_EINVAL; }
+    if (max_len < 1) { err = "max_len < 1"; return P2_EINVAL; }
+    if (max_len > P2_MAX_LEN) { err = "max_len > 7"; return P2_EUNSUPPORTED; }
+    if (opt && opt->algo != 0) { err = "only the ring cost model (algo 0) exists"; return P2_EUNSUPPORTED; }
+
+    pl = Plan();
+    pl.n = h->n_levels; pl.m = n_axes; pl.D = (int)devices; pl.max_len = max_len;
+    for (int j = 0; j < pl.n; ++j) {
+        pl.h[j] = h->card[j];
+        pl.bw[j] = h->bw_bytes_per_s ? h->bw_bytes_per_s[j] : 1.0;
+        pl.alpha[j] = h->alpha_s ? h->alpha_s[j] : 0.0;
+    }
+    int64_t prod_axes = 1;
+    for (int i = 0; i < n_axes; ++i) {
+        if (axes[i] < 1) { err = "axis size < 1"; return P2_EINVAL; }
+        prod_axes *= axes[i];
+        if (prod_axes > devices) break;
+    }
+    if (prod_axes != devices) { err = "product of axes differs from the number of devices"; return P2_EINVAL; }
+    for (int i = 0; i < n_axes; ++i) {
+        int64_t pr = 1;
+        for (int j = 0; j < pl.n; ++j) {
+            int v = placement[i * pl.n + j];
+            if (v < 1) { err = "placement factor < 1"; return P2_EINVAL; }
+            pl.x[i][j] = v;
+            pr *= v;
+        }
+        if (pr != axes[i]) { err = "placement row product differs from the axis size (Eq. 2)"; return P2_EINVAL; }
+    }
+    for (int j = 0; j < pl.n; ++j) {
+        int64_t pr = 1;
+        for (int i = 0; i < n_axes; ++i) pr *= pl.x[i][j];
+        if (pr != pl.h[j]) { err = "placement column product differs from the level cardinality (Eq. 1)"; return P2_EINVAL; }
+    }
+    for (int r = 0; r < n_reduce; ++r) {
+        int a = reduce_axes[r];
+        if (a < 0 || a >= n_axes) { err = "reduce axis out of range"; return P2_EINVAL; }
+        if (pl.is_reduce[a]) { err = "duplicate reduce axis"; return P2_EINVAL; }
+        pl.is_reduce[a] = true;
+    }
+    pl.form_mask = (opt && opt->form_mask) ? (opt->form_mask & 7u) : 7u;
+    pl.op_mask = (opt && opt->op_mask) ? (opt->op_mask & 31u) : 31u;
+    if (pl.form_mask == 0 || pl.op_mask == 0) { err = "empty form or op mask"; return P2_EINVAL; }
+    for (int o = 0; o < 5; ++o)
+        if (pl.op_mask & (1u << o)) pl.ops[pl.n_ops++] = o;
+    int k = (opt && opt->n_chunks != 0) ? opt->n_chunks : pl.D;
+    if (k < 1) { err = "n_chunks < 0"; return P2_EINVAL; }
+    if (k > 512) { err = "more than 512 chunks"; return P2_EUNSUPPORTED; }
+    pl.k = k;
+
+    // Sec. 3.4, hierarchy (d): per hardware level the product of the reduce axes' factors.
+    pl.R = 1;
+    for (int j = 0; j < pl.n; ++j) {
+        pl.f[j] = 1;
+        for (int i = 0; i < n_axes; ++i)
+            if (pl.is_reduce[i]) pl.f[j] *= pl.x[i][j];
+        pl.R *= pl.f[j];
+    }
+    // Devices: id = mixed radix of hardware coordinates; inside a level the coordinate is a mixed
+    // radix of the axis digits, axis 0 most significant.  Split every coordinate into its
+    // reduce-axis part (-> local id) and the rest (-> replica).
+    pl.local_of.resize(pl.D);
+    pl.replica_of.resize(pl.D);
+    for (int d = 0; d < pl.D; ++d) {
+        int coord[P2_MAX_LEVELS], rest = d;
+        for (int j = pl.n - 1; j >= 0; --j) { coord[j] = rest % pl.h[j]; rest /= pl.h[j]; }
+        int local = 0, rep = 0;
+        for (int j = 0; j < pl.n; ++j) {
+            int c = coord[j], gdig = 0, rdig = 0, gmul = 1, rmul = 1;
+            for (int i = n_axes - 1; i >= 0; --i) {          // least significant axis first
+                int a = c % pl.x[i][j];
+                c /= pl.x[i][j];
+                if (pl.is_reduce[i]) { gdig += a * gmul; gmul *= pl.x[i][j]; }
+                else { rdig += a * rmul; rmul *= pl.x[i][j]; }
+            }
+            local = local * pl.f[j] + gdig;
+            rep = rep * (pl.h[j] / pl.f[j]) + rdig;
+        }
+        pl.local_of[d] = local;
+        pl.replica_of[d] = rep;
+    }
+
+    // Sec. 3.3 patterns in the order: for every slice e_i (e_0 = root): InsideGroup,
+    // Parallel(e_0..e_{i-1}), Master(e_0..e_{i-1}).  Level e_l (l >= 1) is hardware level l-1.
+    // A pattern is identified by the levels with factor > 1 that vary inside a group plus whether
+    // the Master restriction removes anything; equal identities give equal group sets, and the
+    // first occurrence keeps the id.
+    std::vector<int> suffix(pl.n + 1, 1);                       // suffix[j] = prod f[j..n-1]
+    for (int j = pl.n - 1; j >= 0; --j) suffix[j] = suffix[j + 1] * pl.f[j];
+    auto add = [&](int slice, int form, int form_level, int a, int b) {   // hardware levels a..b vary
+        int lo = -1, hi = -1;
+        for (int j = a; j <= b; ++j)
+            if (pl.f[j] > 1) { if (lo < 0) lo = j; hi = j; }
+        if (lo < 0) return;                                     // only groups of one device
+        Pattern p;
+        p.slice = slice; p.form = form; p.form_level = form_level; p.lo = lo; p.hi = hi;
+        p.s = suffix[hi + 1];
+        p.g = suffix[lo] / p.s;
+        p.master = (form == 2 && p.s > 1) ? 1 : 0;
+        p.n_groups = p.master ? pl.R / (p.g * p.s) : pl.R / p.g;
+        for (const Pattern& q : pl.patterns)
+            if (q.lo == p.lo && q.hi == p.hi && q.master == p.master) return;
+        pl.patterns.push_back(p);
+    };
+    for (int i = 0; i <= pl.n; ++i) {
+        if (pl.form_mask & 1u) add(i, 0, -1, i, pl.n - 1);
+        if (pl.form_mask & 2u)
+            for (int j = 0; j < i; ++j) add(i, 1, j, j, i - 1);
+        if (pl.form_mask & 4u)
+            for (int j = 0; j < i; ++j) add(i, 2, j, j, i - 1);
+    }
+    pl.alphabet = (int)pl.patterns.size() * pl.n_ops;
+
+    // Candidate numbering: by length, then lexicographic.
+    uint64_t pw = 1, total = 0;
+    pl.base[1] = 0;
+    for (int l = 1; l <= max_len; ++l) {
+        if (pl.alphabet != 0 && pw > UINT64_MAX / (uint64_t)pl.alphabet) { err = "candidate count overflows 64 bits"; return P2_EINVAL; }
+        pw *= (uint64_t)pl.alphabet;
+        if (total > UINT64_MAX - pw) { err = "candidate count overflows 64 bits"; return P2_EINVAL; }
+        total += pw;
+        pl.base[l + 1] = total;
+    }
+    pl.n_candidates = total;
+    if (with_cost)
+        for (Pattern& p : pl.patterns) build_cost_rows(pl, p);
+    return P2_OK;
+}
+
+void describe_pattern(const Plan& pl, int pattern_id, int32_t* group_of_device, int32_t* rank_in_group) {
+    const Pattern& p = pl.patterns[pattern_id];
+    std::map<std::pair<int, int>, int> ids;
+    for (int d = 0; d < pl.D; ++d) {
+        int loc = pl.local_of[d];
+        if (!takes_part(p, loc)) { group_of_device[d] = -1; rank_in_group[d] = -1; continue; }
+        auto key = std::make_pair(pl.replica_of[d], local_group(p, loc));
+        auto it = ids.find(key);
+        if (it == ids.end()) it = ids.emplace(key, (int)ids.size()).first;
+        group_of_device[d] = it->second;
+        rank_in_group[d] = (loc / p.s) % p.g;
+    }
+}
+
+}  // namespace p2

@@ -1,0 +1,181 @@
+// Ordering kernels: rank-sort of the (few) valid candidate indices, and top-k selection of
+// (cost, index) pairs by wavefront-level filtered insertion (the simulator's shortlist, Sec. 5).
+#include "p2_device.h"
+
+namespace p2 {
+
+namespace {
+
+constexpr int kWave = 64;
+
+// sorted[rank(in[i])] = in[i], rank = number of smaller keys.  Keys are distinct candidate
+// indices and n is tiny next to the candidate space, so the quadratic count is the cheap way
+// to a deterministic ascending order after an unordered atomic append.
+__global__ __launch_bounds__(256) void k_rank_sort(const unsigned long long* __restrict__ in,
+                                                   unsigned long long* __restrict__ sorted, uint32_t n) {
+    __shared__ unsigned long long tile[256];
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const unsigned long long key = i < n ? in[i] : 0ull;
+    uint32_t rank = 0;
+    for (uint32_t t0 = 0; t0 < n; t0 += 256u) {
+        const uint32_t j = t0 + threadIdx.x;
+        tile[threadIdx.x] = j < n ? in[j] : ~0ull;
+        __syncthreads();
+        const uint32_t lim = n - t0 < 256u ? n - t0 : 256u;
+        for (uint32_t u = 0; u < lim; ++u) rank += tile[u] < key;
+        __syncthreads();
+    }
+    if (i < n) sorted[rank] = key;
+}
+
+struct Item {
+    double c;
+    unsigned long long idx;
+    long long pos;
+};
+
+__device__ inline bool item_less(const Item& a, const Item& b) {
+    if (a.c < b.c) return true;
+    if (a.c > b.c) return false;
+    if (a.idx != b.idx) return a.idx < b.idx;
+    return a.pos < b.pos;
+}
+
+struct TopList {
+    double* c;
+    unsigned long long* idx;
+    long long* pos;
+};
+
+// Insert `it` (same value in all lanes) into the wavefront's sorted list of at most K entries.
+__device__ inline void list_insert(const TopList& L, int& cnt, int K, const Item& it, int lane) {
+    int below = 0;
+    for (int j = lane; j < cnt; j += kWave) {
+        Item e{L.c[j], L.idx[j], L.pos[j]};
+        below += item_less(e, it) ? 1 : 0;
+    }
+    for (int off = 32; off > 0; off >>= 1) below += __shfl_xor(below, off, kWave);
+    const int p = below;
+    if (p >= K) return;
+    const int newcnt = cnt < K ? cnt + 1 : K;
+    // shift entries p .. newcnt-2 one place up, highest chunk first
+    for (int hi = newcnt - 1; hi > p; hi -= kWave) {
+        const int j = hi - lane;                // destination
+        Item e{0.0, 0ull, 0ll};
+        const bool act = j > p;
+        if (act) e = Item{L.c[j - 1], L.idx[j - 1], L.pos[j - 1]};
+        __syncthreads();
+        if (act) { L.c[j] = e.c; L.idx[j] = e.idx; L.pos[j] = e.pos; }
+        __syncthreads();
+    }
+    if (lane == 0) { L.c[p] = it.c; L.idx[p] = it.idx; L.pos[p] = it.pos; }
+    __syncthreads();
+    cnt = newcnt;
+}
+
+// Feed one item per lane (valid = lane has one) through the list.
+__device__ inline void list_offer(const TopList& L, int& cnt, int K, Item mine, bool valid, int lane) {
+    for (;;) {
+        bool want = valid;
+        if (want && cnt == K) {
+            Item last{L.c[K - 1], L.idx[K - 1], L.pos[K - 1]};
+            want = item_less(mine, last);
+        }
+        const unsigned long long m = __ballot(want);
+        if (m == 0ull) break;
+        const int src = __ffsll((long long)m) - 1;
+        Item it;
+        it.c = __shfl(mine.c, src, kWave);
+        it.idx = __shfl(mine.idx, src, kWave);
+        it.pos = __shfl(mine.pos, src, kWave);
+        list_insert(L, cnt, K, it, lane);
+        if (lane == src) valid = false;
+    }
+}
+
+// Stage 1: block b keeps the K best of its strided share of the input; stage 2 (one block) merges
+// the block lists.  part_* hold gridDim.x lists of K entries (pos = -1 marks an unused slot).
+__global__ __launch_bounds__(kWave) void k_topk_partial(const double* __restrict__ cost, long long stride,
+                                                        const unsigned long long* __restrict__ index, long long n, int K,
+                                                        double* __restrict__ part_c, unsigned long long* __restrict__ part_i,
+                                                        long long* __restrict__ part_p, uint32_t* __restrict__ nan_flag) {
+    extern __shared__ unsigned char raw[];
+    TopList L;
+    L.c = reinterpret_cast<double*>(raw);
+    L.idx = reinterpret_cast<unsigned long long*>(L.c + K);
+    L.pos = reinterpret_cast<long long*>(L.idx + K);
+    const int lane = threadIdx.x;
+    int cnt = 0;
+    bool nan = false;
+    for (long long t0 = (long long)blockIdx.x * kWave; t0 < n; t0 += (long long)gridDim.x * kWave) {
+        const long long i = t0 + lane;
+        Item mine{0.0, 0ull, i};
+        const bool valid = i < n;
+        if (valid) { mine.c = cost[i * stride]; mine.idx = index[i]; nan |= mine.c != mine.c; }
+        list_offer(L, cnt, K, mine, valid && !(mine.c != mine.c), lane);
+    }
+    if (nan) atomicOr(nan_flag, 1u);
+    __syncthreads();
+    for (int j = lane; j < K; j += kWave) {
+        const size_t o = (size_t)blockIdx.x * K + j;
+        part_c[o] = j < cnt ? L.c[j] : 0.0;
+        part_i[o] = j < cnt ? L.idx[j] : 0ull;
+        part_p[o] = j < cnt ? L.pos[j] : -1ll;
+    }
+}
+
+__global__ __launch_bounds__(kWave) void k_topk_merge(const double* __restrict__ part_c,
+                                                      const unsigned long long* __restrict__ part_i,
+                                                      const long long* __restrict__ part_p, long long total, int K,
+                                                      long long* __restrict__ out_pos, long long n_out) {
+    extern __shared__ unsigned char raw[];
+    TopList L;
+    L.c = reinterpret_cast<double*>(raw);
+    L.idx = reinterpret_cast<unsigned long long*>(L.c + K);
+    L.pos = reinterpret_cast<long long*>(L.idx + K);
+    const int lane = threadIdx.x;
+    int cnt = 0;
+    for (long long t0 = 0; t0 < total; t0 += kWave) {
+        const long long i = t0 + lane;
+        Item mine{0.0, 0ull, -1ll};
+        if (i < total) mine = Item{part_c[i], part_i[i], part_p[i]};
+        list_offer(L, cnt, K, mine, i < total && mine.pos >= 0, lane);
+    }
+    __syncthreads();
+    for (int j = lane; j < n_out; j += kWave) out_pos[j] = j < cnt ? L.pos[j] : -1ll;
+}
+
+inline unsigned topk_blocks(long long n) {
+    long long b = (n + 64 * 16 - 1) / (64 * 16);      // at least 16 tiles per block
+    if (b < 1) b = 1;
+    if (b > 2048) b = 2048;
+    return (unsigned)b;
+}
+
+}  // namespace
+
+hipError_t launch_rank_sort(const unsigned long long* in, unsigned long long* sorted, uint32_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_rank_sort, dim3((n + 255u) / 256u), dim3(256), 0, stream, in, sorted, n);
+    return hipGetLastError();
+}
+
+size_t topk_scratch_bytes(long long n, int k) { return (size_t)topk_blocks(n) * (size_t)k * 24; }
+
+hipError_t launch_topk(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
+                       long long* out_pos, void* scratch, uint32_t* nan_flag, hipStream_t stream) {
+    if (n <= 0 || k <= 0) return hipSuccess;
+    const unsigned blocks = topk_blocks(n);
+    double* pc = reinterpret_cast<double*>(scratch);
+    unsigned long long* pi = reinterpret_cast<unsigned long long*>(pc + (size_t)blocks * k);
+    long long* pp = reinterpret_cast<long long*>(pi + (size_t)blocks * k);
+    const size_t lds = (size_t)k * 24;
+    hipLaunchKernelGGL(k_topk_partial, dim3(blocks), dim3(kWave), lds, stream, cost, stride, index, n, k, pc, pi, pp, nan_flag);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long n_out = k < n ? k : n;
+    hipLaunchKernelGGL(k_topk_merge, dim3(1), dim3(kWave), lds, stream, pc, pi, pp, (long long)blocks * k, k, out_pos, n_out);
+    return hipGetLastError();
+}
+
+}  // namespace p2

@@ -1,0 +1,181 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: valid program lists bit-exact (index, length, instruction codes); costs within 1e-9 relative.
+"""
+import numpy as np
+import pytest
+
+from paper_2110_10548_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-9
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2110_10548_amd import binding
+    binding.lib()
+    return binding
+
+
+def oracle_result(oracle, q, msg, form_mask=7, op_mask=31):
+    oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q.get("bw"), alpha=q.get("alpha"),
+                      n_chunks=q.get("n_chunks", 0), form_mask=form_mask, op_mask=op_mask)
+    return oq, oq.synthesize(q["max_len"], msg)
+
+
+def assert_same(res, ora, n_msg):
+    progs = res["programs"]
+    assert progs["index"].tolist() == ora["index"].tolist()
+    assert progs["len"].tolist() == ora["len"].tolist()
+    assert (progs["instr"] == ora["instr"][:, :7]).all()
+    if n_msg:
+        assert res["cost"].shape == ora["cost"].shape
+        assert np.allclose(res["cost"], ora["cost"], rtol=RTOL, atol=0.0)
+
+
+def queries_of(cfg_id, B):
+    cfg = workloads.config(cfg_id)
+    pls = B.p2_enumerate_placements(cfg["card"], cfg["axes"])
+    return cfg, workloads.expand(cfg, pls)
+
+
+@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+def test_config1_every_query(B, oracle, engine):
+    cfg, queries = queries_of(1, B)
+    assert len(queries) == 2
+    for q in queries:
+        q["engine"] = engine
+    results = B.p2_synthesize_batch(queries, cfg["msg_bytes"])
+    for q, res in zip(queries, results):
+        oq, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+        assert res["stats"]["candidates"] == oq.num_candidates(q["max_len"])
+        assert_same(res, ora, len(cfg["msg_bytes"]))
+        # steps executed == what flat, unpruned evaluation of every index executes
+        _, _, steps = oq.eval_indices(q["max_len"], start=0, count=oq.num_candidates(q["max_len"]))
+        assert res["stats"]["steps_executed"] == steps
+
+
+@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+def test_config2_every_query(B, oracle, engine):
+    cfg, queries = queries_of(2, B)
+    assert len(queries) == 10
+    for q in queries:
+        q["engine"] = engine
+    results = B.p2_synthesize_batch(queries, cfg["msg_bytes"])
+    cache = {}
+    for q, res in zip(queries, results):
+        key = (tuple(map(tuple, q["placement"])), tuple(q["reduce_axes"]))
+        oq, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+        cache[key] = ora
+        assert_same(res, ora, len(cfg["msg_bytes"]))
+    # reducing over all axes: the same programs and costs whatever the placement
+    full = [r for q, r in zip(queries, results) if q["reduce_axes"] == [0, 1]]
+    for r in full[1:]:
+        assert r["programs"]["index"].tolist() == full[0]["programs"]["index"].tolist()
+        assert np.allclose(r["cost"], full[0]["cost"], rtol=1e-12)
+
+
+def test_single_query_entry_point_and_sizing(B, oracle):
+    cfg, queries = queries_of(1, B)
+    q = queries[0]
+    res = B.p2_synthesize(q["card"], q["axes"], q["placement"], q["reduce_axes"], q["max_len"], cfg["msg_bytes"],
+                          bw=q["bw"], alpha=q["alpha"])
+    _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+    assert_same(res, ora, 1)
+    assert res["candidates"] == res["stats"]["candidates"]
+    with pytest.raises(B.P2Error) as e:
+        B.p2_synthesize(q["card"], q["axes"], q["placement"], q["reduce_axes"], q["max_len"], cfg["msg_bytes"],
+                        bw=q["bw"], alpha=q["alpha"], cap=1)
+    assert e.value.code == B.P2_ENOSPC
+
+
+@pytest.mark.parametrize("card,axes,red,max_len,k", [
+    ([3, 2, 2], [6, 2], [0], 4, 0),          # radix 3: groups are not bit-fields
+    ([2, 3, 2], [2, 6], [1], 4, 0),
+    ([2, 2, 3], [4, 3], [0, 1], 3, 0),
+    ([2, 4], [8], [0], 4, 3),                # chunk counts that break ReduceScatter
+    ([2, 4], [8], [0], 4, 1),
+    ([2, 2, 2], [8], [0], 4, 16),
+    ([5], [5], [0], 4, 0),
+    ([2, 4, 8], [2, 4, 8], [1], 4, 0),
+])
+@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+def test_ragged_shapes_every_placement(B, oracle, card, axes, red, max_len, k, engine):
+    bw = [11e9 * (j + 1) for j in range(len(card))]
+    alpha = [7e-6 / (j + 1) for j in range(len(card))]
+    msg = [1.0e6, 3.0e8]
+    queries = [dict(card=card, axes=axes, placement=pl, reduce_axes=red, max_len=max_len, bw=bw, alpha=alpha,
+                    n_chunks=k, engine=engine) for pl in B.p2_enumerate_placements(card, axes).tolist()]
+    for q, res in zip(queries, B.p2_synthesize_batch(queries, msg)):
+        _, ora = oracle_result(oracle, q, msg)
+        assert_same(res, ora, 2)
+
+
+@pytest.mark.parametrize("form_mask,op_mask", [(3, 31), (5, 31), (7, 0b01101), (7, 0b11001), (4, 31)])
+def test_grammar_masks(B, oracle, form_mask, op_mask):
+    q = dict(card=[2, 2, 2], axes=[8], placement=[[2, 2, 2]], reduce_axes=[0], max_len=4, bw=[1e9, 2e9, 3e9],
+             alpha=[1e-6, 2e-6, 3e-6], form_mask=form_mask, op_mask=op_mask)
+    res = B.p2_synthesize_batch([q], [1e7])[0]
+    _, ora = oracle_result(oracle, q, [1e7], form_mask=form_mask, op_mask=op_mask)
+    assert_same(res, ora, 1)
+
+
+def test_paper_counts_on_the_gpu(B):
+    # Appendix A: 47 programs for a two-level hierarchy, 3 for a one-level one (InsideGroup + Parallel)
+    r = B.p2_synthesize([4, 16], [64], [[4, 16]], [0], 5, form_mask=3)
+    assert len(r["programs"]) == 47
+    r = B.p2_synthesize([4, 16], [4, 16], [[4, 1], [1, 16]], [0], 5, form_mask=3)
+    assert len(r["programs"]) == 3
+
+
+def test_topk_in_synthesize(B, oracle):
+    cfg, queries = queries_of(2, B)
+    q = dict(queries[1], topk=10)       # first placement, reduce over both axes
+    msg = cfg["msg_bytes"]
+    res = B.p2_synthesize_batch([q], msg)[0]
+    _, ora = oracle_result(oracle, q, msg)
+    n = len(ora["index"])
+    kk = min(10, n)
+    assert len(res["programs"]) == kk * len(msg)
+    for m in range(len(msg)):
+        want = oracle.topk(ora["cost"][:, m], ora["index"], 10)
+        got = res["programs"]["index"][m * kk:(m + 1) * kk]
+        assert got.tolist() == ora["index"][want].tolist()
+        assert np.allclose(res["cost"][m * kk:(m + 1) * kk], ora["cost"][want], rtol=RTOL)
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (7, 10), (64, 64), (1000, 10), (100003, 10), (100003, 1024), (5000, 1000)])
+def test_topk_kernel(B, oracle, n, k):
+    rng = np.random.default_rng(n * 31 + k)
+    cost = np.round(rng.random(n), 3) if n > 100 else rng.random(n)      # ties in the big cases
+    index = rng.permutation(n).astype(np.uint64)
+    assert B.p2_topk(cost, index, k).tolist() == oracle.topk(cost, index, k).tolist()
+
+
+def test_topk_device_pointers_and_nan(B, oracle):
+    import torch
+    n, k = 50000, 10
+    rng = np.random.default_rng(5)
+    cost = rng.random((n, 3))
+    index = rng.permutation(n).astype(np.int64)
+    dc = torch.from_numpy(cost).cuda()
+    di = torch.from_numpy(index).cuda()
+    out = torch.empty(k, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    for m in range(3):
+        B.p2_topk_device(dc.data_ptr() + 8 * m, 3, di.data_ptr(), n, k, out.data_ptr())
+        assert out.cpu().numpy().tolist() == oracle.topk(cost[:, m], index.astype(np.uint64), k).tolist()
+    bad = cost[:, 0].copy()
+    bad[123] = np.nan
+    with pytest.raises(B.P2Error) as e:
+        B.p2_topk(bad, index.astype(np.uint64), k)
+    assert e.value.code == B.P2_EINVAL
+
+
+def test_empty_and_degenerate(B):
+    # a reduce axis of size 1: nothing to reduce, no instruction exists, no candidate
+    r = B.p2_synthesize([2, 2], [1, 4], [[1, 1], [2, 2]], [0], 3)
+    assert r["candidates"] == 0 and len(r["programs"]) == 0
+    assert B.p2_topk(np.zeros(0), np.zeros(0, dtype=np.uint64), 5).tolist() == []
