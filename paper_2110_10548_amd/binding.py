@@ -65,6 +65,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError("libp2.so is not built: run `python paper_2110_10548_amd/build.py` "
                               "(there is no CPU fallback for the evaluator)")
+        # torch ships its own HIP runtime under the same soname as the system one; loading torch
+        # first makes the library and torch share one runtime, so torch's device pointers and
+        # streams are valid inside the library.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         i32p, f64p, u64p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_uint64), C.POINTER(C.c_int64)
         L.p2_last_error.restype = C.c_char_p

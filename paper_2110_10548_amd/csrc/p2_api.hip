@@ -110,7 +110,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         const int want = Q.opt ? Q.opt->engine : P2_ENGINE_AUTO;
         const Plan& pl = runs[i].plan;
         const bool lit_ok = literal_lds_bytes(pl.R, pl.k) != 0;
-        const bool cmp_ok = compact_lds_bytes(pl.R, pl.k) != 0;
+        const bool cmp_ok = compact_lanes(pl.R, pl.k) != 0;
         if (want == P2_ENGINE_LITERAL) {
             if (!lit_ok) return fail(P2_EUNSUPPORTED, "state too large for the literal engine");
             runs[i].engine = P2_ENGINE_LITERAL;
@@ -124,7 +124,47 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
 
     // ---- lay out the table blob: queries, message sizes, bandwidth rows
     size_t off = 0;
-    for (auto& r : runs) { r.off_query = off; off += align_up(sizeof(DevQuery), 256); }
+    for (auto& r : runs) { r.off_query = off; off += sizeof(DevQuery); }      // one contiguous DevQuery array
+    off = align_up(off, 256);
+    // compact-engine queries are launched together, one launch per (chunk words, mask words) class
+    struct Launch { int kw, mw, max_R, max_k; std::vector<DevSegment> segs; unsigned blocks; size_t off_segs; };
+    std::vector<Launch> launches;
+    auto word_class = [](int bits) { int w = (bits + 31) / 32; return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16; };
+    for (int i = 0; i < n_queries; ++i) {
+        if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].plan.n_candidates == 0) continue;
+        const Plan& pl = runs[i].plan;
+        const int kw = word_class(pl.k), mw = word_class(pl.R);
+        Launch* L = nullptr;
+        for (auto& c : launches) if (c.kw == kw && c.mw == mw) L = &c;
+        if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0}); L = &launches.back(); }
+        L->max_R = std::max(L->max_R, pl.R);
+        L->max_k = std::max(L->max_k, pl.k);
+    }
+    for (auto& L : launches) {
+        const int lanes = compact_lanes(L.max_R, L.max_k);
+        if (lanes == 0) return fail(P2_EUNSUPPORTED, "state too large for the compact engine");
+        unsigned long long blocks = 0;
+        for (int i = 0; i < n_queries; ++i) {
+            const Plan& pl = runs[i].plan;
+            if (runs[i].engine != P2_ENGINE_COMPACT || pl.n_candidates == 0) continue;
+            if (word_class(pl.k) != L.kw || word_class(pl.R) != L.mw) continue;
+            for (int len = 1; len <= pl.max_len; ++len) {
+                const unsigned long long count = pl.base[len + 1] - pl.base[len];
+                const unsigned long long chunks = (count + lanes - 1) / lanes;
+                unsigned long long iters = (chunks + 16383) / 16384;
+                iters = std::min<unsigned long long>(std::max<unsigned long long>(iters, 1), 64);
+                DevSegment sg;
+                sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len; sg.iters = (int)iters;
+                sg.first_index = pl.base[len]; sg.count = count;
+                L.segs.push_back(sg);
+                blocks += (chunks + iters - 1) / iters;
+                if (blocks > 0x7fffffffull) return fail(P2_EUNSUPPORTED, "too many candidates for one launch");
+            }
+        }
+        L.blocks = (unsigned)blocks;
+        L.off_segs = off;
+        off += align_up(sizeof(DevSegment) * L.segs.size(), 256);
+    }
     const size_t off_msg = off;
     off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
     for (auto& r : runs) {
@@ -149,7 +189,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& r : runs) {
         const unsigned long long N = r.plan.n_candidates;
         r.valid_cap = (uint32_t)std::min<unsigned long long>(N, 1u << 15);
-        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT) ? (uint32_t)std::min<unsigned long long>(N, 1u << 12) : 0u;
+        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
     }
 
     char* hb = static_cast<char*>(C.h_blob.p);
@@ -172,6 +212,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             dq->n_candidates = pl.n_candidates;
             for (int l = 0; l <= P2_MAX_LEN + 1; ++l) dq->base[l] = pl.base[l];
             for (int o = 0; o < pl.n_ops; ++o) dq->ops[o] = (uint8_t)pl.ops[o];
+            dq->magic_alphabet = pl.alphabet <= 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (unsigned)pl.alphabet + 1ull);
+            for (int d = 0; d < pl.alphabet; ++d)
+                dq->instr_of_digit[d] = (uint16_t)(((d / pl.n_ops) << 3) | pl.ops[d % pl.n_ops]);
             for (int j = 0; j < pl.n; ++j) { dq->alpha[j] = pl.alpha[j]; dq->inv_bw[j] = 1.0 / pl.bw[j]; }
             int32_t* rp = reinterpret_cast<int32_t*>(hb + r.off_rowptr);
             int32_t* rl = reinterpret_cast<int32_t*>(hb + r.off_rowlevel);
@@ -199,33 +242,44 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             dq->valid_cap = r.valid_cap; dq->rerun_cap = r.rerun_cap;
             dq->counters = static_cast<DevCounters*>(C.counters.p) + i;
         }
+        for (auto& L : launches)
+            std::memcpy(hb + L.off_segs, L.segs.data(), sizeof(DevSegment) * L.segs.size());
         P2_HIP(hipMemcpyAsync(db, hb, blob_bytes, hipMemcpyHostToDevice, stream));
         P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters) * (size_t)n_queries, stream));
         // ---- evaluate every candidate of every query
+        for (auto& L : launches)
+            P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
+                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
-            if (r.engine == P2_ENGINE_COMPACT) {
-                P2_HIP(launch_eval_compact(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, stream));
-                // candidates whose state the compact engine cannot hold are re-run literally
-                if (literal_lds_bytes(r.plan.R, r.plan.k) != 0 && r.rerun_cap > 0)
-                    P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.rerun_cap,
-                                               static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun,
-                                               &(static_cast<DevCounters*>(C.counters.p) + i)->n_rerun, stream));
-            } else {
+            if (r.engine == P2_ENGINE_LITERAL)
                 P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, nullptr, nullptr, stream));
-            }
         }
         P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
                               hipMemcpyDeviceToHost, stream));
         P2_HIP(hipStreamSynchronize(stream));
         bool again = false;
         const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
+        // candidates whose state the compact engine could not hold go through the literal engine
+        bool reran = false;
+        for (int i = 0; i < n_queries; ++i) {
+            QueryRun& r = runs[i];
+            if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap) continue;
+            if (literal_lds_bytes(r.plan.R, r.plan.k) == 0)
+                return fail(P2_EUNSUPPORTED, "a candidate needs the literal engine but its state does not fit");
+            P2_HIP(launch_eval_literal(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k, 0ull,
+                                       hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, stream));
+            reran = true;
+        }
+        if (reran) {
+            P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
+                                  hipMemcpyDeviceToHost, stream));
+            P2_HIP(hipStreamSynchronize(stream));
+        }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.steps = hc[i].steps;
-            if (r.n_rerun > 0 && literal_lds_bytes(r.plan.R, r.plan.k) == 0)
-                return fail(P2_EUNSUPPORTED, "a candidate needs the literal engine but its state does not fit");
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);

@@ -5,6 +5,7 @@
 #include <cstdint>
 
 #include "../../include/p2.h"
+#include "p2_device_pack.h"
 
 namespace p2 {
 
@@ -20,6 +21,17 @@ struct DevPattern {
     int32_t g, s, master, n_groups;
     int32_t span_level;            // outermost hardware level at which members differ
     int32_t row_begin, row_end;    // bandwidth rows of this pattern (indices into row_ptr/row_level)
+};
+
+// A run of equally long candidates of one query: blocks [first_block, next segment's first_block)
+// take `iters` x 64 consecutive candidates each, starting at candidate index first_index.
+struct DevSegment {
+    uint32_t first_block;
+    int32_t query;
+    int32_t len;
+    int32_t iters;
+    unsigned long long first_index;
+    unsigned long long count;
 };
 
 // Counters a query's kernels add to.
@@ -39,12 +51,14 @@ struct DevQuery {
     unsigned long long n_candidates;
     unsigned long long base[P2_MAX_LEN + 2];   // base[l]: index of the first program of length l
     uint8_t ops[8];
+    uint32_t magic_alphabet;       // ceil(2^32 / alphabet): v / alphabet == umulhi(v, magic) for v < 2^23
+    uint16_t instr_of_digit[kMaxPatterns * 5];   // digit -> (pattern id << 3) | op
     DevPattern pat[kMaxPatterns];
     double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
     // bandwidth rows (device pointers into the uploaded table blob)
     const int32_t* row_ptr;
     const int32_t* row_level;
-    const uint32_t* entries;       // (local group << 16) | number of system groups touching the unit
+    const uint32_t* entries;       // entry_pack(local group, its first device, groups touching the unit)
     const double* msg_bytes;       // [n_msg]
     // outputs of the evaluation kernels
     unsigned long long* valid_idx;
@@ -55,16 +69,17 @@ struct DevQuery {
 
 // LDS bytes one wavefront of the literal engine needs for a query (0 = does not fit).
 size_t literal_lds_bytes(int R, int k);
-// LDS bytes one wavefront (64 candidates) of the compact engine needs.
-size_t compact_lds_bytes(int R, int k);
 
 // Evaluate candidates [start, start + count) of query *q (device pointer), or, if list != nullptr,
 // the `count` candidate indices stored at list (device pointer; count may also be read from
 // *list_count when list_count != nullptr).  Valid ones are appended to q->valid_idx.
 hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
                                const unsigned long long* list, const uint32_t* list_count, hipStream_t stream);
-hipError_t launch_eval_compact(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
-                               hipStream_t stream);
+// Compact engine: one launch over the segments of many queries (all with R <= max_R, k <= max_k).
+hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
+                               int max_R, int max_k, hipStream_t stream);
+// Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
+int compact_lanes(int R, int k);
 // sorted[i] = i-th smallest of in[0..n)  (distinct keys)
 hipError_t launch_rank_sort(const unsigned long long* in, unsigned long long* sorted, uint32_t n, hipStream_t stream);
 // For each of the n sorted valid candidates: its program record and its cost for every message size.

@@ -172,7 +172,7 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
             long long dot = 0;
             for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
                 const uint32_t ent = q.entries[e];
-                dot += (long long)(ent & 0xffffu) * (long long)L.gcount[ent >> 16];
+                dot += (long long)entry_cnt(ent) * (long long)L.gcount[entry_group(ent)];
             }
             best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
         }

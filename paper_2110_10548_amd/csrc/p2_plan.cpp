@@ -1,5 +1,6 @@
 // Host-side planning (see p2_plan.h).  Sections cited are those of arXiv 2110.10548.
 #include "p2_plan.h"
+#include "p2_device_pack.h"
 
 #include <algorithm>
 #include <map>
@@ -122,6 +123,9 @@ inline int local_group(const Pattern& p, int local) {
     int hi = local / (p.g * p.s), lo = local % p.s;
     return p.master ? hi : hi * p.s + lo;
 }
+inline int group_base(const Pattern& p, int group) {       // local id of the group's first device
+    return p.master ? group * p.g * p.s : (group / p.s) * p.g * p.s + group % p.s;
+}
 
 void build_cost_rows(const Plan& pl, Pattern& p) {
     p.row_ptr.assign(1, 0);
@@ -154,7 +158,7 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
             std::sort(touched.begin(), touched.end());
             std::vector<uint32_t> row;
             row.reserve(touched.size());
-            for (int lg : touched) { row.push_back(((uint32_t)lg << 16) | (uint32_t)cnt[lg]); cnt[lg] = 0; }
+            for (int lg : touched) { row.push_back(entry_pack((uint32_t)lg, (uint32_t)group_base(p, lg), (uint32_t)cnt[lg])); cnt[lg] = 0; }
             if (seen.emplace(row, 1).second) rows.push_back(std::move(row));
         }
         // drop rows dominated by another row of the same level
@@ -165,9 +169,9 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
                 size_t ib = 0;
                 bool dom = true;
                 for (size_t ia = 0; ia < rows[a].size() && dom; ++ia) {
-                    uint32_t lg = rows[a][ia] >> 16, c = rows[a][ia] & 0xffffu;
-                    while (ib < rows[b].size() && (rows[b][ib] >> 16) < lg) ++ib;
-                    dom = ib < rows[b].size() && (rows[b][ib] >> 16) == lg && (rows[b][ib] & 0xffffu) >= c;
+                    uint32_t lg = entry_group(rows[a][ia]), c = entry_cnt(rows[a][ia]);
+                    while (ib < rows[b].size() && entry_group(rows[b][ib]) < lg) ++ib;
+                    dom = ib < rows[b].size() && entry_group(rows[b][ib]) == lg && entry_cnt(rows[b][ib]) >= c;
                 }
                 if (dom) dead[a] = 1;
             }

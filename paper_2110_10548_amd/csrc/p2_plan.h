@@ -29,7 +29,7 @@ struct Pattern {
     // maximum load, (local group, number of system groups touching the unit) pairs
     std::vector<int32_t> row_ptr;      // [n_rows + 1]
     std::vector<int32_t> row_level;    // [n_rows] hardware level of the unit
-    std::vector<uint32_t> entries;     // (local group << 16) | count
+    std::vector<uint32_t> entries;     // entry_pack(local group, its first device, count)
 };
 
 struct Plan {
