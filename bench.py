@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark: one step = one pass of the whole hot path (plan, unrank, semantic evaluation,
+goal test, cost, compaction, ordering, top-k) over every query of the workload.
+
+Prints ONE JSON line.  `value` is candidate programs evaluated per second: every candidate
+index of every query is unranked and simulated from the init state on the GPU (no candidate
+is skipped because it shares a prefix with a dead one).  The roofline object prices the
+evaluation kernel's algorithmic lane-operations against the chip's 32-bit integer VALU rate;
+the cpu_baseline object times the plain CPU oracle on a bounded sample of the same candidates.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: 32-bit integer lane-operations per second
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+
+
+def algorithmic_lane_ops(stats, n_chunks):
+    """Lane-operations the evaluation must do in the compact state form: every device taking part in
+    an applied instruction has ceil(k/32) chunk-set words and ceil(R/32) mask words, and each word is
+    read, tested against the rule's premise, folded into the group's result and written: 4 each."""
+    words = -(-n_chunks // 32) + -(-stats["group_size"] // 32)
+    return 4.0 * words * stats["member_visits"]
+
+
+def cpu_baseline(queries, budget_s=15.0):
+    """The oracle as it stands: flat, unpruned evaluation of a bounded sample of each query's
+    candidate indices (the first S and S seeded-random ones; all of them where the space is smaller),
+    OpenMP over all host cores this process may use."""
+    import numpy as np
+    from oracle import p2_oracle
+    from paper_2110_10548_amd.workloads import SplitMix64
+    cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1024")))
+    S = 250_000
+    total, t_all, t_one, n_one = 0, 0.0, 0.0, 0
+    t_begin = time.time()
+    for qi, q in enumerate(queries):
+        oq = p2_oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
+                             n_chunks=q.get("n_chunks", 0))
+        N = oq.num_candidates(q["max_len"])
+        if N <= 2 * S:
+            idx = np.arange(N, dtype=np.uint64)
+        else:
+            rng = SplitMix64(1000 + qi)
+            idx = np.concatenate([np.arange(S, dtype=np.uint64),
+                                  np.array([rng.below(N) for _ in range(S)], dtype=np.uint64)])
+        t0 = time.time()
+        oq.eval_indices(q["max_len"], indices=idx, n_threads=cores)
+        t_all += time.time() - t0
+        total += len(idx)
+        sub = idx[::16]
+        t0 = time.time()
+        oq.eval_indices(q["max_len"], indices=sub, n_threads=1)
+        t_one += time.time() - t0
+        n_one += len(sub)
+        if time.time() - t_begin > 2 * budget_s:
+            break
+    return {"value": total / t_all, "unit": "candidates/s", "cores": cores, "kind": "oracle",
+            "value_1core": n_one / t_one,
+            "sample": "per query the first %d and %d SplitMix64-random candidate indices (the whole space where "
+                      "smaller), flat unpruned evaluation from the init state; %d candidates in %.1f s" % (S, S, total, t_all)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..4")
+    ap.add_argument("--engine", type=int, default=0, help="0 auto, 1 literal, 2 compact")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: candidate evaluation is embarrassingly parallel and this build "
+              "runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2110_10548_amd import binding as B, workloads
+    if not torch.cuda.is_available():
+        print("no GPU visible: the evaluator has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    cfg = workloads.config(args.config)
+    queries = workloads.expand(cfg, B.p2_enumerate_placements(cfg["card"], cfg["axes"]))
+    for q in queries:
+        q["engine"] = args.engine
+    msg = cfg["msg_bytes"]
+    B.p2_set_profiling(True)
+
+    batch = B.Batch(queries, msg)                 # argument marshalling only; every step replans on the host
+    for _ in range(max(args.warmup, 1)):
+        batch.run_raw()
+    torch.cuda.synchronize()
+    eval_ms, post_ms, launches = 0.0, 0.0, 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        batch.run_raw()                           # one p2_synthesize_batch call; returns after its stream sync
+        prof = B.p2_get_profile()
+        eval_ms += prof["eval_ms"]
+        post_ms += prof["post_ms"]
+        launches += prof["eval_launches"]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    results = batch.results()
+
+    candidates = sum(r["stats"]["candidates"] for r in results)
+    steps_exec = sum(r["stats"]["steps_executed"] for r in results)
+    valid = sum(r["stats"]["valid"] for r in results)
+    reruns = sum(r["stats"]["literal_reruns"] for r in results)
+    ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()))
+              for q, r in zip(queries, results))
+    ms_per_step = dt / args.steps * 1e3
+    eval_ms_per_launch = eval_ms / max(launches, 1)
+    launches_per_step = launches / args.steps
+    achieved = (ops / launches_per_step) / (eval_ms_per_launch * 1e-3)     # lane-ops/s of the evaluation kernel
+
+    out = {
+        "metric": "candidate programs evaluated/sec (validity+cost)",
+        "value": candidates / (dt / args.steps),
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "%s: hierarchy %s, axes %s, all %d placements x reduce sets %s, max_len %d, %d message sizes"
+                               % (cfg["name"], cfg["card"], cfg["axes"], len(queries) // max(len(cfg["reduce_sets"]) * len(cfg["n_chunks"]), 1),
+                                  cfg["reduce_sets"], cfg["max_len"], len(msg)),
+                   "queries": len(queries), "candidates_per_step": candidates, "valid_per_step": valid,
+                   "steps_executed_per_step": steps_exec, "literal_reruns_per_step": reruns,
+                   "engine": {0: "auto", 1: "literal", 2: "compact"}[args.engine]},
+        "device_ms_per_step": {"evaluate": eval_ms / args.steps, "order_cost_topk": post_ms / args.steps},
+        "evaluate_only_candidates_per_s": candidates / (eval_ms / args.steps * 1e-3),
+        "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),
+        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+                     "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
+                     "kernel": "k_eval_compact" if args.engine != 1 else "k_eval_literal",
+                     "launch_ms": eval_ms_per_launch, "algorithmic_lane_ops_per_launch": ops / launches_per_step},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(queries)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -97,6 +97,7 @@ typedef struct {
     uint64_t candidates;       /* programs of length <= max_len over the alphabet, all evaluated  */
     uint64_t steps_executed;   /* instructions applied (a candidate stops at its first bad step)  */
     uint64_t literal_reruns;   /* candidates the compact engine handed to the literal engine      */
+    uint64_t member_visits;    /* sum over applied instructions of the devices taking part in them */
     int64_t valid;             /* valid programs found                                            */
     int32_t group_size;        /* R: devices in one reduction group                               */
     int32_t n_patterns;        /* canonical (slice, form) patterns                                */
@@ -165,6 +166,19 @@ int32_t p2_topk(const double* cost, const uint64_t* index, int64_t n, int32_t k,
  * Returns after the result is in out_pos. */
 int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
                        int64_t* out_pos, void* stream);
+
+/* Timing of the calling thread's last p2_synthesize / p2_synthesize_batch call, taken with HIP
+ * events on the call's stream.  Off by default; p2_set_profiling(1) turns the events on. */
+typedef struct {
+    float eval_ms;             /* all evaluation-kernel launches of the call                       */
+    float post_ms;             /* ordering, cost and top-k kernels                                 */
+    int32_t eval_launches;     /* evaluation kernels launched                                      */
+    int32_t post_launches;
+    float host_plan_ms;        /* host: planning of all queries (patterns, bandwidth rows)         */
+    float host_total_ms;       /* host: whole call, wall clock                                     */
+} p2_profile;
+int32_t p2_set_profiling(int32_t on);
+int32_t p2_get_profile(p2_profile* out);
 
 const char* p2_last_error(void);
 

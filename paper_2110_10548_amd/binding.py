@@ -40,8 +40,13 @@ class p2_program(C.Structure):
 
 class p2_stats(C.Structure):
     _fields_ = [("candidates", C.c_uint64), ("steps_executed", C.c_uint64), ("literal_reruns", C.c_uint64),
-                ("valid", C.c_int64), ("group_size", C.c_int32), ("n_patterns", C.c_int32), ("alphabet", C.c_int32),
+                ("member_visits", C.c_uint64), ("valid", C.c_int64), ("group_size", C.c_int32), ("n_patterns", C.c_int32), ("alphabet", C.c_int32),
                 ("engine", C.c_int32)]
+
+
+class p2_profile(C.Structure):
+    _fields_ = [("eval_ms", C.c_float), ("post_ms", C.c_float), ("eval_launches", C.c_int32), ("post_launches", C.c_int32),
+                ("host_plan_ms", C.c_float), ("host_total_ms", C.c_float)]
 
 
 class p2_query(C.Structure):
@@ -54,7 +59,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_last_error")
+           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile")
 
 _lib = None
 
@@ -88,6 +93,10 @@ def lib():
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
         L.p2_topk_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.p2_set_profiling.restype = C.c_int32
+        L.p2_set_profiling.argtypes = [C.c_int32]
+        L.p2_get_profile.restype = C.c_int32
+        L.p2_get_profile.argtypes = [C.POINTER(p2_profile)]
         _lib = L
     return _lib
 
@@ -163,38 +172,71 @@ def _stats_dict(s):
     return {k: getattr(s, k) for k, _ in p2_stats._fields_}
 
 
+class Batch:
+    """A marshalled list of queries: the ctypes structures are built once, `run` calls
+    p2_synthesize_batch into output buffers that are reused (grown on P2_ENOSPC)."""
+
+    def __init__(self, queries, msg_bytes=(), stream=None):
+        self.nq = len(queries)
+        self._keep = []
+        self._arr = (p2_query * self.nq)()
+        for i, q in enumerate(queries):
+            h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
+            axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
+            opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), 0, q.get("topk", 0),
+                           q.get("engine", ENGINE_AUTO), stream)
+            self._keep.append((h, axes, pl, red, opt))
+            self._arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32),
+                                    len(red), int(q["max_len"]), C.pointer(opt))
+        self._msg = _f64(list(msg_bytes))
+        self.n_msg = len(self._msg)
+        self._offs = np.zeros(self.nq + 1, dtype=np.int64)
+        self._stats = (p2_stats * self.nq)()
+        self._alloc(0)
+
+    def _alloc(self, cap):
+        self.cap = cap
+        self._progs = np.zeros(max(cap, 1), dtype=PROGRAM_DTYPE)
+        self._cost = np.zeros((max(cap, 1), max(self.n_msg, 1)), dtype=np.float64)
+
+    def run_raw(self):
+        """One p2_synthesize_batch call (two if the output buffers had to grow)."""
+        while True:
+            rc = lib().p2_synthesize_batch(self._arr, self.nq, _p(self._msg, C.c_double), self.n_msg,
+                                           self._progs.ctypes.data_as(C.c_void_p) if self.cap else None,
+                                           _p(self._cost, C.c_double) if self.cap else None, self.cap,
+                                           _p(self._offs, C.c_int64), self._stats)
+            if rc == P2_ENOSPC or (rc == P2_OK and self.cap == 0 and self._offs[self.nq] > 0):
+                self._alloc(int(self._offs[self.nq]))
+                continue
+            _check(rc)
+            return
+
+    def results(self):
+        out = []
+        for i in range(self.nq):
+            a, b = int(self._offs[i]), int(self._offs[i + 1])
+            out.append({"programs": self._progs[a:b].copy(), "cost": self._cost[a:b, :self.n_msg].copy(),
+                        "stats": _stats_dict(self._stats[i])})
+        return out
+
+    def run(self):
+        self.run_raw()
+        return self.results()
+
+
 def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
     """queries: list of dicts with card, bw, alpha, axes, placement, reduce_axes, max_len and optional
     n_chunks, form_mask, op_mask, topk, engine.  Returns a list of results, one per query:
     {"programs": structured array, "cost": [n][n_msg], "stats": dict}."""
-    nq = len(queries)
-    keep = []
-    arr = (p2_query * nq)()
-    for i, q in enumerate(queries):
-        h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
-        axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
-        opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), 0, q.get("topk", 0),
-                       q.get("engine", ENGINE_AUTO), stream)
-        keep.append((h, axes, pl, red, opt))
-        arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32), len(red),
-                          int(q["max_len"]), C.pointer(opt))
-    msg = _f64(list(msg_bytes))
-    n_msg = len(msg)
-    offs = np.zeros(nq + 1, dtype=np.int64)
-    stats = (p2_stats * nq)()
-    if cap is None:
-        rc = lib().p2_synthesize_batch(arr, nq, _p(msg, C.c_double), n_msg, None, None, 0, _p(offs, C.c_int64), stats)
-        _check(rc, allow=(P2_ENOSPC,))
-        cap = int(offs[nq])
-    progs = np.zeros(max(cap, 1), dtype=PROGRAM_DTYPE)
-    cost = np.zeros((max(cap, 1), max(n_msg, 1)), dtype=np.float64)
-    _check(lib().p2_synthesize_batch(arr, nq, _p(msg, C.c_double), n_msg, progs.ctypes.data_as(C.c_void_p),
-                                     _p(cost, C.c_double), cap, _p(offs, C.c_int64), stats))
-    out = []
-    for i in range(nq):
-        a, b = int(offs[i]), int(offs[i + 1])
-        out.append({"programs": progs[a:b].copy(), "cost": cost[a:b, :n_msg].copy(), "stats": _stats_dict(stats[i])})
-    return out
+    b = Batch(queries, msg_bytes, stream)
+    if cap is not None:
+        b._alloc(cap)
+        _check(lib().p2_synthesize_batch(b._arr, b.nq, _p(b._msg, C.c_double), b.n_msg,
+                                         b._progs.ctypes.data_as(C.c_void_p), _p(b._cost, C.c_double), cap,
+                                         _p(b._offs, C.c_int64), b._stats))
+        return b.results()
+    return b.run()
 
 
 def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=None, alpha=None, n_chunks=0,
@@ -219,6 +261,16 @@ def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=
     n = count.value
     return {"programs": progs[:n].copy(), "cost": cost[:n, :n_msg].copy(), "candidates": cands.value,
             "stats": _stats_dict(st)}
+
+
+def p2_set_profiling(on):
+    _check(lib().p2_set_profiling(1 if on else 0))
+
+
+def p2_get_profile():
+    p = p2_profile()
+    _check(lib().p2_get_profile(C.byref(p)))
+    return {k: getattr(p, k) for k, _ in p2_profile._fields_}
 
 
 def p2_topk(cost, index, k):

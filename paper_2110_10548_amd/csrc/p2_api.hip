@@ -1,6 +1,7 @@
 // The C ABI of include/p2.h: argument checks, planning, table upload, kernel launches and
 // copy-back.  All arithmetic of the method runs in the kernels; this file only moves data.
 #include <algorithm>
+#include <chrono>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -10,7 +11,8 @@
 
 namespace p2 {
 hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
-                               p2_program* out_prog, double* out_cost, hipStream_t stream);
+                               p2_program* out_prog, double* out_cost, int only_missing, void* gscratch,
+                               hipStream_t stream);
 hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
                                p2_program* out_prog, double* out_cost, hipStream_t stream);
 }
@@ -49,10 +51,17 @@ struct HostBuf {
 
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
-    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in;
+    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, lit_scratch;
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos;
 };
 thread_local Ctx g_ctx;
+
+struct Prof {
+    bool on = false;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    p2_profile last = {0.f, 0.f, 0, 0, 0.f, 0.f};
+};
+thread_local Prof g_prof;
 
 int32_t fail(int32_t code, const std::string& msg) {
     g_err = msg;
@@ -79,7 +88,7 @@ struct QueryRun {
     uint32_t valid_cap = 0, rerun_cap = 0;
     size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
     uint32_t n_valid = 0, n_rerun = 0;
-    unsigned long long steps = 0;
+    unsigned long long steps = 0, members = 0;
     size_t out_first = 0;                 // first row of this query in the sorted/prog/cost buffers
 };
 
@@ -96,6 +105,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     Ctx& C = g_ctx;
 
     // ---- plan every query on the host
+    const auto t_begin = std::chrono::steady_clock::now();
     std::vector<QueryRun> runs(n_queries);
     std::string err;
     for (int i = 0; i < n_queries; ++i) {
@@ -109,7 +119,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (runs[i].topk > 0 && n_msg == 0) return fail(P2_EINVAL, "topk needs at least one message size");
         const int want = Q.opt ? Q.opt->engine : P2_ENGINE_AUTO;
         const Plan& pl = runs[i].plan;
-        const bool lit_ok = literal_lds_bytes(pl.R, pl.k) != 0;
+        const bool lit_ok = true;        // the literal engine falls back to a global state buffer
         const bool cmp_ok = compact_lanes(pl.R, pl.k) != 0;
         if (want == P2_ENGINE_LITERAL) {
             if (!lit_ok) return fail(P2_EUNSUPPORTED, "state too large for the literal engine");
@@ -122,6 +132,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if ((size_t)pl.patterns.size() > (size_t)kMaxPatterns) return fail(P2_EUNSUPPORTED, "more than 64 patterns");
     }
 
+    g_prof.last.host_plan_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     // ---- lay out the table blob: queries, message sizes, bandwidth rows
     size_t off = 0;
     for (auto& r : runs) { r.off_query = off; off += sizeof(DevQuery); }      // one contiguous DevQuery array
@@ -192,6 +203,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         r.rerun_cap = (r.engine == P2_ENGINE_COMPACT) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
     }
 
+    // global state buffer for literal evaluations whose state does not fit in LDS
+    auto lit_scratch = [&](const Plan& pl, void** out) -> hipError_t {
+        *out = nullptr;
+        if (literal_lds_bytes(pl.R, pl.k) != 0) return hipSuccess;
+        unsigned nb = 0;
+        hipError_t e = C.lit_scratch.ensure(literal_scratch_bytes(pl.R, pl.k, &nb));
+        *out = C.lit_scratch.p;
+        return e;
+    };
     char* hb = static_cast<char*>(C.h_blob.p);
     char* db = static_cast<char*>(C.blob.p);
     std::vector<char> done(n_queries, 0);
@@ -247,15 +267,22 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(hipMemcpyAsync(db, hb, blob_bytes, hipMemcpyHostToDevice, stream));
         P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters) * (size_t)n_queries, stream));
         // ---- evaluate every candidate of every query
-        for (auto& L : launches)
+        int eval_launches = 0;
+        if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[0], stream));
+        for (auto& L : launches) { ++eval_launches;
             P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
-                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
+                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream)); }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
-            if (r.engine == P2_ENGINE_LITERAL)
-                P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, nullptr, nullptr, stream));
+            if (r.engine == P2_ENGINE_LITERAL && r.plan.n_candidates > 0) {
+                ++eval_launches;
+                void* gs = nullptr;
+                P2_HIP(lit_scratch(r.plan, &gs));
+                P2_HIP(launch_eval_literal(dq, r.plan.R, r.plan.k, 0ull, r.plan.n_candidates, nullptr, nullptr, gs, stream));
+            }
         }
+        if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[1], stream)); g_prof.last.eval_launches = eval_launches; }
         P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
                               hipMemcpyDeviceToHost, stream));
         P2_HIP(hipStreamSynchronize(stream));
@@ -266,10 +293,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap) continue;
-            if (literal_lds_bytes(r.plan.R, r.plan.k) == 0)
-                return fail(P2_EUNSUPPORTED, "a candidate needs the literal engine but its state does not fit");
+            void* gs = nullptr;
+            P2_HIP(lit_scratch(r.plan, &gs));
             P2_HIP(launch_eval_literal(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k, 0ull,
-                                       hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, stream));
+                                       hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, gs, stream));
             reran = true;
         }
         if (reran) {
@@ -279,7 +306,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
-            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.steps = hc[i].steps;
+            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.steps = hc[i].steps; r.members = hc[i].members;
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);
@@ -306,18 +333,25 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.topk_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
     P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
     size_t pos_off = 0;
+    int post_launches = 0;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
+        post_launches += 2 + (r.topk > 0 ? 2 * n_msg : 0);
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
         unsigned long long* sorted = static_cast<unsigned long long*>(C.sorted.p) + r.out_first;
         p2_program* progs = static_cast<p2_program*>(C.progs.p) + r.out_first;
         double* costs = static_cast<double*>(C.costs.p) + r.out_first * nm;
         P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p) + r.off_valid, sorted, r.n_valid, stream));
-        if (r.engine == P2_ENGINE_COMPACT && r.n_rerun == 0)
+        // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
+        if (r.engine == P2_ENGINE_COMPACT)
             P2_HIP(launch_cost_compact(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs, stream));
-        else
-            P2_HIP(launch_cost_literal(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs, stream));
+        if (r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0)) {
+            void* gs = nullptr;
+            P2_HIP(lit_scratch(r.plan, &gs));
+            P2_HIP(launch_cost_literal(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs,
+                                       r.engine == P2_ENGINE_COMPACT ? 1 : 0, gs, stream));
+        }
         if (r.topk > 0) {
             const size_t kk = std::min<size_t>(r.topk, r.n_valid);
             for (int m = 0; m < n_msg; ++m) {
@@ -328,6 +362,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
         }
     }
+    if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[2], stream)); g_prof.last.post_launches = post_launches; }
     P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
     P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
     P2_HIP(C.h_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
@@ -340,6 +375,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(hipMemcpyAsync(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, hipMemcpyDeviceToHost, stream));
     P2_HIP(hipStreamSynchronize(stream));
 
+    if (g_prof.on) {
+        P2_HIP(hipEventElapsedTime(&g_prof.last.eval_ms, g_prof.ev[0], g_prof.ev[1]));
+        P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[1], g_prof.ev[2]));
+    }
     // ---- hand the results over
     const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);
     const double* hcst = static_cast<const double*>(C.h_costs.p);
@@ -371,12 +410,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         if (stats) {
             p2_stats& s = stats[i];
-            s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun;
+            s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
             s.alphabet = r.plan.alphabet; s.engine = r.engine;
         }
     }
     out_offset[n_queries] = w;
+    g_prof.last.host_total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     if (!store && need > 0) return fail(P2_ENOSPC, "output buffer too small: " + std::to_string(need) + " rows needed");
     return P2_OK;
 }
@@ -386,6 +426,18 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
 extern "C" {
 
 const char* p2_last_error(void) { return g_err.c_str(); }
+
+int32_t p2_set_profiling(int32_t on) {
+    if (on && !g_prof.ev[0])
+        for (auto& e : g_prof.ev) P2_HIP(hipEventCreate(&e));
+    g_prof.on = on != 0;
+    return P2_OK;
+}
+int32_t p2_get_profile(p2_profile* out) {
+    if (!out) return fail(P2_EINVAL, "null argument");
+    *out = g_prof.last;
+    return P2_OK;
+}
 
 int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, int32_t* out, int64_t cap,
                                 int64_t* out_count) {

@@ -8,14 +8,18 @@
 // An AllGather of members with different masks leaves that form; the lane then reports the
 // candidate for re-evaluation by the literal engine, so results stay exact.
 //
-// A lane keeps the R (chunk set, mask) pairs of its candidate in LDS, word-interleaved across
-// lanes (word w of lane l at w * LS + l: every lane its own bank).  No lane ever reads another
-// lane's state, so the kernel needs no barrier.  A step is two flat loops over the participating
-// devices of the instruction's pattern in group-major order: pass A folds the members of a
-// group and checks the rule's premises, leaving the group's result in its first member's slot;
-// pass B writes every member's new pair from that slot.  The rule-specific parts are selects,
-// not branches, because the 64 lanes of a wavefront hold consecutive candidates whose last
-// instructions all differ.
+// A lane keeps the R (chunk set, mask) pairs of its candidate in LDS: the pair of device d of
+// lane l sits at word (d * LS + l) * WS, WS = words per pair (padded to an odd count unless it is
+// 2 or 4, which are read with one 64/128-bit access), so the 64 lanes of one access fall into
+// distinct banks.  No lane ever reads another lane's state, so the kernel needs no barrier.
+//
+// The 64 lanes of a wavefront hold consecutive candidates, which share every instruction but the
+// last.  A step whose instruction is the same in all live lanes takes the uniform path: scalar
+// loops over groups and members, one specialised body per rule.  Otherwise (the last instruction,
+// or a wavefront that straddles two prefixes) the mixed path runs two flat loops over the
+// participating devices in group-major order -- pass A folds a group and leaves its result in
+// the first member's slot, pass B writes every member's new pair from that slot -- with the
+// rule-specific parts as selects, so lanes with different rules and group shapes stay together.
 #include "p2_device.h"
 
 namespace p2 {
@@ -107,27 +111,99 @@ struct Slot {
     Words<MW> m;   // contribution mask of every non-empty row
 };
 template <int KW, int MW>
-__device__ inline Slot<KW, MW> load_slot(const uint32_t* my, int LS, int dev) {
-    const uint32_t* p = my + dev * (KW + MW) * LS;
+struct Lay {
+    static constexpr int WPD = KW + MW;
+    static constexpr int WS = (WPD == 2 || WPD == 4) ? WPD : (WPD | 1);   // words between lanes
+};
+// `my` points at this lane's pair of device 0; device d is at my + d * dstride (dstride = LS * WS).
+template <int KW, int MW>
+__device__ inline Slot<KW, MW> load_slot(const uint32_t* my, int dstride, int dev) {
+    const uint32_t* p = my + dev * dstride;
     Slot<KW, MW> s;
+    if constexpr (KW == 1 && MW == 1) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        s.r.w[0] = v.x; s.m.w[0] = v.y;
+    } else if constexpr (KW + MW == 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t t[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int i = 0; i < KW; ++i) s.r.w[i] = p[i * LS];
+        for (int i = 0; i < KW; ++i) s.r.w[i] = t[i];
 #pragma unroll
-    for (int i = 0; i < MW; ++i) s.m.w[i] = p[(KW + i) * LS];
+        for (int i = 0; i < MW; ++i) s.m.w[i] = t[KW + i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < KW; ++i) s.r.w[i] = p[i];
+#pragma unroll
+        for (int i = 0; i < MW; ++i) s.m.w[i] = p[KW + i];
+    }
     return s;
 }
 template <int KW, int MW>
-__device__ inline void store_slot(uint32_t* my, int LS, int dev, const Words<KW>& r, const Words<MW>& m) {
-    uint32_t* p = my + dev * (KW + MW) * LS;
+__device__ inline void store_slot(uint32_t* my, int dstride, int dev, const Words<KW>& r, const Words<MW>& m) {
+    uint32_t* p = my + dev * dstride;
+    if constexpr (KW == 1 && MW == 1) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(r.w[0], m.w[0]);
+    } else if constexpr (KW + MW == 4) {
+        uint32_t t[4];
 #pragma unroll
-    for (int i = 0; i < KW; ++i) p[i * LS] = r.w[i];
+        for (int i = 0; i < KW; ++i) t[i] = r.w[i];
 #pragma unroll
-    for (int i = 0; i < MW; ++i) p[(KW + i) * LS] = m.w[i];
+        for (int i = 0; i < MW; ++i) t[KW + i] = m.w[i];
+        *reinterpret_cast<uint4*>(p) = make_uint4(t[0], t[1], t[2], t[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < KW; ++i) p[i] = r.w[i];
+#pragma unroll
+        for (int i = 0; i < MW; ++i) p[KW + i] = m.w[i];
+    }
+}
+template <int KW, int MW>
+__device__ inline void store_mask(uint32_t* my, int dstride, int dev, const Words<MW>& m) {
+    uint32_t* p = my + dev * dstride + KW;
+#pragma unroll
+    for (int i = 0; i < MW; ++i) p[i] = m.w[i];
+}
+template <int KW, int MW>
+__device__ inline void store_rows(uint32_t* my, int dstride, int dev, const Words<KW>& r) {
+    uint32_t* p = my + dev * dstride;
+#pragma unroll
+    for (int i = 0; i < KW; ++i) p[i] = r.w[i];
+}
+template <int N>
+__device__ inline uint32_t fold_xor(const Words<N>& a, const Words<N>& b) {
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o |= a.w[i] ^ b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline uint32_t fold_and(const Words<N>& a, const Words<N>& b) {
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o |= a.w[i] & b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline uint32_t fold_andn(const Words<N>& a, const Words<N>& b) {   // bits of a outside b
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o |= a.w[i] & ~b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline uint32_t fold_or(const Words<N>& a) {
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o |= a.w[i];
+    return o;
 }
 
 struct PatLds {
-    int g, s, master, n_part;     // n_part = participating devices = groups * g
+    int g, s, master, n_groups;   // participating devices = n_groups * g
 };
+__device__ inline int div_small(int v, int d) {      // v / d for 0 <= v <= 512, 1 <= d <= 512, exact
+    return (int)__fdividef((float)v + 0.5f, (float)d);
+}
 
 struct GroupWalk {                // group-major walk over the participating devices of a pattern
     int p, lo, hib, dev;
@@ -149,31 +225,114 @@ struct GroupWalk {                // group-major walk over the participating dev
 
 enum : int { STEP_INVALID = 0, STEP_OK = 1, STEP_GIVE_UP = 2 };
 
-// One instruction for this lane's candidate.  cost_* only with kCost.
+// One instruction, the same (pattern, rule) in every live lane: g, s, master, n_groups are scalars.
+template <int KW, int MW>
+__device__ inline int step_uniform(uint32_t* my, int dstride, int g, int s, int master, int n_groups, int op) {
+    const int gs = g * s;
+    uint32_t badx = 0;          // any bit set: a premise failed
+    bool changed = false, give_up = false;
+    int lo = 0, hib = 0;
+    for (int G = 0; G < n_groups; ++G) {
+        const int base = hib + lo;
+        const Slot<KW, MW> first = load_slot<KW, MW>(my, dstride, base);
+        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+            // premises: same chunks on every member, no contribution reduced twice
+            Words<MW> accm = first.m;
+            for (int p = 1; p < g; ++p) {
+                const Slot<KW, MW> cur = load_slot<KW, MW>(my, dstride, base + p * s);
+                badx |= fold_xor(cur.r, first.r) | fold_and(cur.m, accm);
+#pragma unroll
+                for (int i = 0; i < MW; ++i) accm.w[i] |= cur.m.w[i];
+            }
+            changed |= fold_or(first.r) != 0;               // a group of empty devices is a no-op
+            if (op == OP_AR) {
+                for (int p = 0; p < g; ++p) store_mask<KW, MW>(my, dstride, base + p * s, accm);
+            } else if (op == OP_RD) {
+                store_mask<KW, MW>(my, dstride, base, accm);
+                Words<KW> zr; Words<MW> zm;
+#pragma unroll
+                for (int i = 0; i < KW; ++i) zr.w[i] = 0;
+#pragma unroll
+                for (int i = 0; i < MW; ++i) zm.w[i] = 0;
+                for (int p = 1; p < g; ++p) store_slot<KW, MW>(my, dstride, base + p * s, zr, zm);
+            } else {
+                // scatter: the chunks must divide evenly; rank p keeps the p-th block in ascending order
+                const int rows = popcount(first.r);
+                const int per = div_small(rows, g);
+                badx |= (uint32_t)(per * g != rows);
+                Words<KW> prev;
+#pragma unroll
+                for (int i = 0; i < KW; ++i) prev.w[i] = 0;
+                for (int p = 0; p < g; ++p) {
+                    const Words<KW> upto = lowest_n(first.r, (p + 1) * per);
+                    Words<KW> nr;
+#pragma unroll
+                    for (int i = 0; i < KW; ++i) { nr.w[i] = upto.w[i] & ~prev.w[i]; prev.w[i] = upto.w[i]; }
+                    store_slot<KW, MW>(my, dstride, base + p * s, nr, accm);
+                }
+            }
+        } else if (op == OP_AG) {
+            // premises: nobody empty, every chunk held once; members with different masks leave this form
+            Words<KW> accr = first.r;
+            uint32_t smx = 0;
+            bool anyzero = fold_or(first.r) == 0;
+            for (int p = 1; p < g; ++p) {
+                const Slot<KW, MW> cur = load_slot<KW, MW>(my, dstride, base + p * s);
+                badx |= fold_and(cur.r, accr);
+                smx |= fold_xor(cur.m, first.m);
+                anyzero |= fold_or(cur.r) == 0;
+#pragma unroll
+                for (int i = 0; i < KW; ++i) accr.w[i] |= cur.r.w[i];
+            }
+            badx |= (uint32_t)anyzero;
+            give_up |= smx != 0;
+            changed = true;
+            for (int p = 0; p < g; ++p) store_rows<KW, MW>(my, dstride, base + p * s, accr);
+        } else {
+            // Broadcast: the root holds what every member holds, and more than at least one of them
+            uint32_t subx = 0, difx = 0;
+            for (int p = 1; p < g; ++p) {
+                const Slot<KW, MW> cur = load_slot<KW, MW>(my, dstride, base + p * s);
+                subx |= fold_andn(cur.r, first.r) | fold_andn(cur.m, first.m);
+                difx |= fold_xor(cur.r, first.r) | fold_xor(cur.m, first.m);
+            }
+            badx |= subx | (uint32_t)(difx == 0);
+            changed = true;
+            for (int p = 1; p < g; ++p) store_slot<KW, MW>(my, dstride, base + p * s, first.r, first.m);
+        }
+        if (master) hib += gs;
+        else if (++lo == s) { lo = 0; hib += gs; }
+    }
+    if (badx != 0 || !changed) return STEP_INVALID;
+    return give_up ? STEP_GIVE_UP : STEP_OK;
+}
+
+// One instruction, lanes may differ in pattern and rule.  cost_* only with kCost.
 template <int KW, int MW, bool kCost>
-__device__ inline int compact_step(uint32_t* my, int LS, const PatLds P, int op, const DevQuery& q, const DevPattern* dp,
-                                   double* sum_alpha, double* sum_beta) {
+__device__ inline int step_mixed(uint32_t* my, int dstride, const PatLds P, int op, const DevQuery& q, const DevPattern* dp,
+                                 double* sum_alpha, double* sum_beta) {
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
-    bool bad = false, changed = false, give_up = false;
+    uint32_t badx = 0;
+    bool changed = false, give_up = false;
     GroupWalk wk;
     wk.start();
     Slot<KW, MW> first, acc;
-    bool eq = true, disj_m = true, disj_r = true, all_ne = true, same_m = true, sub = true, strict = false;
+    uint32_t eqx = 0, dmx = 0, drx = 0, smx = 0, subx = 0;
+    bool anyzero = false;
     // ---- pass A: fold each group, check the premises, leave the result in the first member's slot
-    for (int j = 0; j < P.n_part; ++j) {
-        const Slot<KW, MW> cur = load_slot<KW, MW>(my, LS, wk.dev);
+    for (int j = 0, n_part = P.n_groups * P.g; j < n_part; ++j) {
+        const Slot<KW, MW> cur = load_slot<KW, MW>(my, dstride, wk.dev);
         if (wk.p == 0) {
             first = cur; acc = cur;
-            eq = true; disj_m = true; disj_r = true; same_m = true; sub = true; strict = false;
-            all_ne = !is_zero(cur.r);
+            eqx = 0; dmx = 0; drx = 0; smx = 0; subx = 0;
+            anyzero = fold_or(cur.r) == 0;
         } else {
-            eq &= !differs(cur.r, first.r);               // same chunks on every member
-            disj_m &= !intersects(cur.m, acc.m);          // no contribution reduced twice
-            disj_r &= !intersects(cur.r, acc.r);          // AllGather: chunks held once
-            all_ne &= !is_zero(cur.r);                    // AllGather: nobody empty
-            same_m &= !differs(cur.m, first.m);
-            sub &= !not_subset(cur.r, first.r) && !not_subset(cur.m, first.m);   // Broadcast: root knows more
-            strict |= differs(cur.r, first.r) || differs(cur.m, first.m);
+            eqx |= fold_xor(cur.r, first.r);              // same chunks on every member
+            dmx |= fold_and(cur.m, acc.m);                // no contribution reduced twice
+            drx |= fold_and(cur.r, acc.r);                // AllGather: chunks held once
+            smx |= fold_xor(cur.m, first.m);
+            subx |= fold_andn(cur.r, first.r) | fold_andn(cur.m, first.m);   // Broadcast: root knows more
+            anyzero |= fold_or(cur.r) == 0;               // AllGather: nobody empty
 #pragma unroll
             for (int i = 0; i < KW; ++i) acc.r.w[i] |= cur.r.w[i];
 #pragma unroll
@@ -182,27 +341,26 @@ __device__ inline int compact_step(uint32_t* my, int LS, const PatLds P, int op,
         if (wk.next(P)) {
             const int root = wk.root();
             if (red) {
-                bad |= !eq || !disj_m;
-                const bool ne = !is_zero(first.r);
-                changed |= ne;                            // a group of empty devices is a no-op
+                badx |= eqx | dmx;
+                changed |= fold_or(first.r) != 0;         // a group of empty devices is a no-op
                 if (op == OP_RS) {
                     const int rows = popcount(first.r);
-                    bad |= (rows / P.g) * P.g != rows;    // scatter needs the chunks to divide evenly
+                    badx |= (uint32_t)(div_small(rows, P.g) * P.g != rows);   // chunks must divide evenly
                 }
-                store_slot<KW, MW>(my, LS, root, first.r, acc.m);
+                store_mask<KW, MW>(my, dstride, root, acc.m);
             } else if (op == OP_AG) {
-                bad |= !all_ne || !disj_r;
-                give_up |= !same_m;                       // rows with different column sets: not this form
+                badx |= drx | (uint32_t)anyzero;
+                give_up |= smx != 0;                      // rows with different column sets: not this form
                 changed = true;
-                store_slot<KW, MW>(my, LS, root, acc.r, first.m);
+                store_rows<KW, MW>(my, dstride, root, acc.r);
             } else {
-                bad |= !sub || !strict;                   // information increase
+                badx |= subx | (uint32_t)((eqx | smx) == 0);   // information increase
                 changed = true;
             }
             wk.next_group(P);
         }
     }
-    if (bad || !changed) return STEP_INVALID;
+    if (badx != 0 || !changed) return STEP_INVALID;
     if (give_up) return STEP_GIVE_UP;
 
     if (kCost) {
@@ -213,8 +371,8 @@ __device__ inline int compact_step(uint32_t* my, int LS, const PatLds P, int op,
             long long dot = 0;
             for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
                 const uint32_t ent = q.entries[e];
-                const Slot<KW, MW> s = load_slot<KW, MW>(my, LS, (int)entry_base(ent));
-                dot += (long long)entry_cnt(ent) * (long long)popcount(s.r);
+                const Slot<KW, MW> sl = load_slot<KW, MW>(my, dstride, (int)entry_base(ent));
+                dot += (long long)entry_cnt(ent) * (long long)popcount(sl.r);
             }
             best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
         }
@@ -230,11 +388,11 @@ __device__ inline int compact_step(uint32_t* my, int LS, const PatLds P, int op,
     Slot<KW, MW> grp;
     Words<KW> prev;
     int per = 0;
-    for (int j = 0; j < P.n_part; ++j) {
+    for (int j = 0, n_part = P.n_groups * P.g; j < n_part; ++j) {
         if (wk.p == 0) {
-            grp = load_slot<KW, MW>(my, LS, wk.dev);
+            grp = load_slot<KW, MW>(my, dstride, wk.dev);
             if (op == OP_RS) {
-                per = popcount(grp.r) / P.g;
+                per = div_small(popcount(grp.r), P.g);
 #pragma unroll
                 for (int i = 0; i < KW; ++i) prev.w[i] = 0;
             }
@@ -252,38 +410,40 @@ __device__ inline int compact_step(uint32_t* my, int LS, const PatLds P, int op,
 #pragma unroll
             for (int i = 0; i < MW; ++i) nm.w[i] = 0;
         }
-        store_slot<KW, MW>(my, LS, wk.dev, nr, nm);
+        store_slot<KW, MW>(my, dstride, wk.dev, nr, nm);
         if (wk.next(P)) wk.next_group(P);
     }
     return STEP_OK;
 }
 
 template <int KW, int MW>
-__device__ inline void compact_init(uint32_t* my, int LS, int R, int k) {
+__device__ inline void compact_init(uint32_t* my, int dstride, int R, int k) {
+    // Sec. 3.5: device i holds column i in every row
     const Words<KW> all_rows = full_mask<KW>(k);
     for (int d = 0; d < R; ++d) {
         Words<MW> m;
 #pragma unroll
         for (int i = 0; i < MW; ++i) m.w[i] = (i == (d >> 5)) ? (1u << (d & 31)) : 0u;
-        store_slot<KW, MW>(my, LS, d, all_rows, m);
+        store_slot<KW, MW>(my, dstride, d, all_rows, m);
     }
 }
 template <int KW, int MW>
-__device__ inline bool compact_is_goal(const uint32_t* my, int LS, int R, int k) {
+__device__ inline bool compact_is_goal(const uint32_t* my, int dstride, int R, int k) {
+    // every device holds every row, each with the columns of the whole reduction group
     const Words<KW> all_rows = full_mask<KW>(k);
     const Words<MW> all_cols = full_mask<MW>(R);
-    bool ok = true;
+    uint32_t dif = 0;
     for (int d = 0; d < R; ++d) {
-        const Slot<KW, MW> s = load_slot<KW, MW>(my, LS, d);
-        ok &= !differs(s.r, all_rows) && !differs(s.m, all_cols);
+        const Slot<KW, MW> sl = load_slot<KW, MW>(my, dstride, d);
+        dif |= fold_xor(sl.r, all_rows) | fold_xor(sl.m, all_cols);
     }
-    return ok;
+    return dif == 0;
 }
 
 __device__ inline void load_patterns(const DevQuery& q, PatLds* spat, uint16_t* sdig) {
     for (int i = threadIdx.x; i < q.n_patterns; i += kWave) {
         PatLds p;
-        p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_part = q.pat[i].n_groups * q.pat[i].g;
+        p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
     }
     for (int i = threadIdx.x; i < q.alphabet; i += kWave) sdig[i] = q.instr_of_digit[i];
@@ -307,7 +467,9 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
     const DevQuery& q = queries[seg.query];
     load_patterns(q, spat, sdig);
     const int lane = threadIdx.x;
-    uint32_t* my = lds + lane;
+    constexpr int WS = Lay<KW, MW>::WS;
+    uint32_t* my = lds + lane * WS;
+    const int dstride = LS * WS;
     const int len = seg.len;
     const uint32_t I = (uint32_t)q.alphabet;
     const unsigned long long off0 = (unsigned long long)(blockIdx.x - seg.first_block) * (unsigned long long)(seg.iters * LS);
@@ -321,7 +483,7 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
             else d0[t] = 0;
         }
     }
-    unsigned long long steps = 0;
+    unsigned long long steps = 0, members = 0;
     for (int it = 0; it < seg.iters; ++it) {
         const uint32_t add = (uint32_t)(it * LS + lane);
         const unsigned long long off = off0 + add;
@@ -338,20 +500,32 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
                 prog = (prog << 9) | sdig[v - carry * I];
             }
         }
-        if (alive) compact_init<KW, MW>(my, LS, q.R, q.k);
+        if (alive) compact_init<KW, MW>(my, dstride, q.R, q.k);
         bool give_up = false;
-        uint32_t ran = 0;
+        uint32_t ran = 0, visited = 0;
         for (int t = 0; t < len; ++t) {
             if (!__any(alive)) break;
             if (alive) {
                 const uint32_t ins = (uint32_t)(prog >> (9 * t)) & 511u;
                 ++ran;
-                const int rc = compact_step<KW, MW, false>(my, LS, spat[ins >> 3], (int)(ins & 7u), q, nullptr, nullptr, nullptr);
+                visited += (uint32_t)(spat[ins >> 3].n_groups * spat[ins >> 3].g);
+                // the live lanes of a wavefront usually hold the same instruction here
+                const uint32_t ins0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)ins);
+                int rc;
+                if (__all(ins == ins0)) {
+                    const PatLds P0 = spat[ins0 >> 3];
+                    rc = step_uniform<KW, MW>(my, dstride, __builtin_amdgcn_readfirstlane(P0.g), __builtin_amdgcn_readfirstlane(P0.s),
+                                              __builtin_amdgcn_readfirstlane(P0.master),
+                                              __builtin_amdgcn_readfirstlane(P0.n_groups),
+                                              (int)(ins0 & 7u));
+                } else {
+                    rc = step_mixed<KW, MW, false>(my, dstride, spat[ins >> 3], (int)(ins & 7u), q, nullptr, nullptr, nullptr);
+                }
                 alive = rc == STEP_OK;
                 give_up = rc == STEP_GIVE_UP;
             }
         }
-        if (alive && compact_is_goal<KW, MW>(my, LS, q.R, q.k)) {
+        if (alive && compact_is_goal<KW, MW>(my, dstride, q.R, q.k)) {
             const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
             if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + off;
         }
@@ -361,10 +535,11 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
             if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + off;
         } else {
             steps += ran;
+            members += visited;
         }
     }
-    for (int o = 32; o > 0; o >>= 1) steps += __shfl_xor(steps, o, kWave);
-    if (lane == 0 && steps) atomicAdd(&q.counters->steps, steps);
+    for (int o = 32; o > 0; o >>= 1) { steps += __shfl_xor(steps, o, kWave); members += __shfl_xor(members, o, kWave); }
+    if (lane == 0 && steps) { atomicAdd(&q.counters->steps, steps); atomicAdd(&q.counters->members, members); }
 }
 
 // Cost of the valid programs of one query: lane i re-runs sorted[i] with the cost terms on.
@@ -379,7 +554,9 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
     const DevQuery& q = *qp;
     load_patterns(q, spat, sdig);
     const int lane = threadIdx.x;
-    uint32_t* my = lds + lane;
+    constexpr int WS = Lay<KW, MW>::WS;
+    uint32_t* my = lds + lane * WS;
+    const int dstride = LS * WS;
     const uint32_t i = blockIdx.x * (uint32_t)LS + (uint32_t)lane;
     if (lane >= LS || i >= n) return;
     const unsigned long long idx = sorted[i];
@@ -395,7 +572,7 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
             rem = nx;
         }
     }
-    compact_init<KW, MW>(my, LS, q.R, q.k);
+    compact_init<KW, MW>(my, dstride, q.R, q.k);
     double sum_alpha = 0.0, sum_beta = 0.0;
     bool ok = true;
     p2_program pr;
@@ -405,7 +582,7 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
     for (int t = 0; t < len; ++t) {
         const uint32_t ins = (uint32_t)(prog >> (9 * t)) & 511u;
         pr.instr[t] = (uint8_t)((ins >> 3) * 5u + (ins & 7u));
-        if (ok) ok = compact_step<KW, MW, true>(my, LS, spat[ins >> 3], (int)(ins & 7u), q, &q.pat[ins >> 3],
+        if (ok) ok = step_mixed<KW, MW, true>(my, dstride, spat[ins >> 3], (int)(ins & 7u), q, &q.pat[ins >> 3],
                                                 &sum_alpha, &sum_beta) == STEP_OK;
     }
     out_prog[i] = pr;
@@ -416,6 +593,10 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
 inline int round_words(int bits) {
     const int w = (bits + 31) / 32;
     return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16;
+}
+inline int lane_words(int kw, int mw) {          // Lay<kw, mw>::WS
+    const int wpd = kw + mw;
+    return (wpd == 2 || wpd == 4) ? wpd : (wpd | 1);
 }
 
 template <typename F>
@@ -462,7 +643,7 @@ hipError_t cost_mw(int MW, const DevQuery* q, const unsigned long long* sorted, 
 }  // namespace
 
 int compact_lanes(int R, int k) {
-    const size_t per_lane = (size_t)R * (size_t)(round_words(k) + round_words(R)) * 4;
+    const size_t per_lane = (size_t)R * (size_t)lane_words(round_words(k), round_words(R)) * 4;
     int lanes = 64;
     while (lanes >= 1 && per_lane * (size_t)lanes > kLdsBudget) lanes >>= 1;
     return lanes;       // 0 if even one candidate does not fit
@@ -474,7 +655,7 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
     const int LS = compact_lanes(max_R, max_k);
     if (LS == 0) return hipErrorInvalidValue;
     const int KW = round_words(max_k), MW = round_words(max_R);
-    const size_t lds = (size_t)max_R * (size_t)(KW + MW) * 4 * (size_t)LS;
+    const size_t lds = (size_t)max_R * (size_t)lane_words(KW, MW) * 4 * (size_t)LS;
     switch (KW) {
     case 1: return eval_mw<1>(MW, queries, segs, n_segs, total_blocks, LS, lds, stream);
     case 2: return eval_mw<2>(MW, queries, segs, n_segs, total_blocks, LS, lds, stream);
@@ -490,7 +671,7 @@ hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned l
     const int LS = compact_lanes(R, k);
     if (LS == 0) return hipErrorInvalidValue;
     const int KW = round_words(k), MW = round_words(R);
-    const size_t lds = (size_t)R * (size_t)(KW + MW) * 4 * (size_t)LS;
+    const size_t lds = (size_t)R * (size_t)lane_words(KW, MW) * 4 * (size_t)LS;
     const unsigned blocks = (n + (unsigned)LS - 1) / (unsigned)LS;
     switch (KW) {
     case 1: return cost_mw<1>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);

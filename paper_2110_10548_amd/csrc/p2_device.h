@@ -39,6 +39,7 @@ struct DevCounters {
     uint32_t n_valid;              // entries appended to valid_idx (may exceed valid_cap)
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
     unsigned long long steps;      // instructions applied
+    unsigned long long members;    // devices taking part in those instructions, summed
     uint32_t nan_seen;
     uint32_t pad;
 };
@@ -67,14 +68,17 @@ struct DevQuery {
     DevCounters* counters;
 };
 
-// LDS bytes one wavefront of the literal engine needs for a query (0 = does not fit).
+// LDS bytes one wavefront of the literal engine needs for a query (0 = does not fit; the state
+// then lives in a global buffer of literal_scratch_bytes, split over *blocks blocks).
 size_t literal_lds_bytes(int R, int k);
+size_t literal_scratch_bytes(int R, int k, unsigned* blocks);
 
 // Evaluate candidates [start, start + count) of query *q (device pointer), or, if list != nullptr,
 // the `count` candidate indices stored at list (device pointer; count may also be read from
 // *list_count when list_count != nullptr).  Valid ones are appended to q->valid_idx.
 hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
-                               const unsigned long long* list, const uint32_t* list_count, hipStream_t stream);
+                               const unsigned long long* list, const uint32_t* list_count, void* gscratch,
+                               hipStream_t stream);
 // Compact engine: one launch over the segments of many queries (all with R <= max_R, k <= max_k).
 hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
                                int max_R, int max_k, hipStream_t stream);

@@ -247,17 +247,19 @@ template <int MW>
 __global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restrict__ qp, unsigned long long start,
                                                         unsigned long long count, uint32_t per_block,
                                                         const unsigned long long* __restrict__ list,
-                                                        const uint32_t* __restrict__ list_count) {
+                                                        const uint32_t* __restrict__ list_count,
+                                                        uint32_t* __restrict__ gscratch, unsigned long long gwords) {
     extern __shared__ uint32_t lds[];
     const DevQuery& q = *qp;
     const int lane = threadIdx.x;
-    const LitLds L = carve(lds, q.R, q.k, MW);
+    // the state lives in LDS, or, when it does not fit, in this block's slice of a global buffer
+    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
     if (list_count) {
         unsigned long long n = *list_count;
         if (n < count) count = n;
     }
     unsigned long long first = (unsigned long long)blockIdx.x * per_block;
-    unsigned long long steps = 0;
+    unsigned long long steps = 0, members = 0;
     for (uint32_t i = 0; i < per_block && first + i < count; ++i) {
         const unsigned long long idx = list ? list[first + i] : start + first + i;
         uint16_t digit[P2_MAX_LEN + 1];
@@ -267,6 +269,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restri
         for (int t = 0; t < len && ok; ++t) {
             const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
             ++steps;
+            members += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
             ok = lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr);
         }
         if (ok && lit_is_goal<MW>(q, L, lane) && lane == 0) {
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restri
         }
         __syncthreads();
     }
-    if (lane == 0 && steps) atomicAdd(&q.counters->steps, steps);
+    if (lane == 0 && steps) { atomicAdd(&q.counters->steps, steps); atomicAdd(&q.counters->members, members); }
 }
 
 // Cost of valid programs: block i re-runs sorted[i] with the cost terms switched on and writes
@@ -283,12 +286,19 @@ __global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restri
 template <int MW>
 __global__ __launch_bounds__(kWave) void k_cost_literal(const DevQuery* __restrict__ qp,
                                                         const unsigned long long* __restrict__ sorted, uint32_t n,
-                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
+                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost,
+                                                        int only_missing, uint32_t* __restrict__ gscratch,
+                                                        unsigned long long gwords) {
     extern __shared__ uint32_t lds[];
     const DevQuery& q = *qp;
     const int lane = threadIdx.x;
-    const LitLds L = carve(lds, q.R, q.k, MW);
+    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
     for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        // only_missing: another engine has filled every row but those it marked with NaN
+        if (only_missing) {
+            const double have = out_cost[(size_t)i * q.n_msg];
+            if (have == have) continue;
+        }
         const unsigned long long idx = sorted[i];
         uint16_t digit[P2_MAX_LEN + 1];
         const int len = unrank(q, idx, digit);
@@ -330,24 +340,47 @@ size_t literal_lds_bytes(int R, int k) {
     size_t bytes = (size_t)lay.total_words() * 4;
     return bytes <= kLdsLimit ? bytes : 0;
 }
+size_t literal_scratch_bytes(int R, int k, unsigned* blocks) {
+    // states that do not fit in LDS: a fixed number of blocks, each with its own global slice
+    LitLayout lay(R, k, mask_words(R));
+    const size_t per = ((size_t)lay.total_words() * 4 + 255) / 256 * 256;
+    unsigned b = 256;
+    while (b > 1 && per * b > ((size_t)4 << 30)) b >>= 1;
+    *blocks = b;
+    return per * b;
+}
 
 hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
-                               const unsigned long long* list, const uint32_t* list_count, hipStream_t stream) {
+                               const unsigned long long* list, const uint32_t* list_count, void* gscratch,
+                               hipStream_t stream) {
     if (count == 0) return hipSuccess;
-    const size_t lds = literal_lds_bytes(R, k);
-    if (lds == 0) return hipErrorInvalidValue;
+    size_t lds = literal_lds_bytes(R, k);
     const int MW = mask_words(R);
-    // enough blocks to fill 256 CUs several times over, at most 64 candidates per block
     uint32_t per_block = 64;
-    while (per_block > 1 && (count + per_block - 1) / per_block < 8192) per_block >>= 1;
-    const unsigned long long blocks = (count + per_block - 1) / per_block;
+    unsigned long long blocks;
+    unsigned long long gwords = 0;
+    if (lds == 0) {
+        if (!gscratch) return hipErrorInvalidValue;
+        unsigned nb = 0;
+        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
+        blocks = nb < count ? nb : count;
+        const unsigned long long pb = (count + blocks - 1) / blocks;
+        if (pb > 0xffffffffull) return hipErrorInvalidValue;
+        per_block = (uint32_t)pb;
+        blocks = (count + per_block - 1) / per_block;
+    } else {
+        gscratch = nullptr;
+        // enough blocks to fill 256 CUs several times over, at most 64 candidates per block
+        while (per_block > 1 && (count + per_block - 1) / per_block < 8192) per_block >>= 1;
+        blocks = (count + per_block - 1) / per_block;
+    }
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal<MWV>, lds);                                                               \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_eval_literal<MWV>, dim3((unsigned)blocks), dim3(kWave), lds, stream, q, start,    \
-                           count, per_block, list, list_count);
+                           count, per_block, list, list_count, static_cast<uint32_t*>(gscratch), gwords);
     switch (MW) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
@@ -361,17 +394,25 @@ hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long lo
 }
 
 hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
-                               p2_program* out_prog, double* out_cost, hipStream_t stream) {
+                               p2_program* out_prog, double* out_cost, int only_missing, void* gscratch,
+                               hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const size_t lds = literal_lds_bytes(R, k);
-    if (lds == 0) return hipErrorInvalidValue;
+    size_t lds = literal_lds_bytes(R, k);
     const int MW = mask_words(R);
-    const unsigned blocks = n < 65536u ? n : 65536u;
+    unsigned blocks = n < 65536u ? n : 65536u;
+    unsigned long long gwords = 0;
+    if (lds == 0) {
+        if (!gscratch) return hipErrorInvalidValue;
+        unsigned nb = 0;
+        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
+        blocks = nb < n ? nb : n;
+    } else gscratch = nullptr;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_cost_literal<MWV>, lds);                                                               \
     if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_cost_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, sorted, n, out_prog, out_cost);
+        hipLaunchKernelGGL(k_cost_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, sorted, n, out_prog, \
+                           out_cost, only_missing, static_cast<uint32_t*>(gscratch), gwords);
     switch (MW) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;

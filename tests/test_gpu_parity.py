@@ -191,3 +191,100 @@ def test_empty_and_degenerate(B):
     r = B.p2_synthesize([2, 2], [1, 4], [[1, 1], [2, 2]], [0], 3)
     assert r["candidates"] == 0 and len(r["programs"]) == 0
     assert B.p2_topk(np.zeros(0), np.zeros(0, dtype=np.uint64), 5).tolist() == []
+
+
+# --------------------------------------------------------------------------- full-size configurations 3 and 4
+def _levels(q):
+    f = [1] * len(q["card"])
+    for a in q["reduce_axes"]:
+        f = [x * y for x, y in zip(f, q["placement"][a])]
+    return sum(1 for v in f if v > 1)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 3])
+def test_config3_every_query(B, oracle, levels):
+    """64 devices, 64-bit masks, every placement x every non-empty reduce-axis subset, length <= 5
+    (up to 1.9e8 candidates per query), all queries with `levels` non-unit hierarchy levels at once."""
+    cfg, queries = queries_of(3, B)
+    assert len(queries) == 84
+    mine = [q for q in queries if _levels(q) == levels]
+    assert len(mine) == {1: 20, 2: 32, 3: 32}[levels]
+    results = B.p2_synthesize_batch(mine, cfg["msg_bytes"])
+    want_valid = {1: 3, 2: 110, 3: 2549}[levels]
+    cache = {}
+    for q, res in zip(mine, results):
+        assert res["stats"]["valid"] == want_valid
+        # the oracle works on the full 64-device system; queries whose lowered groups coincide
+        # (same reduce-axis factors per level, same placement of the other axes) are not recomputed
+        key = (tuple(map(tuple, q["placement"])), tuple(q["reduce_axes"]))
+        if levels == 3 and len(cache) >= 6 and key not in cache:
+            continue                       # 6 three-level queries checked element by element (~1 s each)
+        if key not in cache:
+            cache[key] = oracle_result(oracle, q, cfg["msg_bytes"])[1]
+        assert_same(res, cache[key], 1)
+    assert len(cache) >= 6
+
+
+def test_config3_literal_engine_small_queries(B, oracle):
+    cfg, queries = queries_of(3, B)
+    mine = [dict(q, engine=1) for q in queries if _levels(q) == 1][:6] + \
+           [dict(q, engine=1, max_len=4) for q in queries if _levels(q) == 2][:3]
+    for q, res in zip(mine, B.p2_synthesize_batch(mine, cfg["msg_bytes"])):
+        assert res["stats"]["engine"] == 1
+        assert_same(res, oracle_result(oracle, q, cfg["msg_bytes"])[1], 1)
+
+
+def test_config4_chunk_granularities_and_topk(B, oracle):
+    """256 devices, reduction groups of 64, chunk counts 1 / 8 / 64 / 256, top-10."""
+    cfg, queries = queries_of(4, B)
+    assert len(queries) == 140
+    by_pl = {}
+    for q in queries:
+        by_pl.setdefault(q["placement_index"], []).append(q)
+    two_level = [p for p, qs in by_pl.items() if _levels(qs[0]) == 2]
+    three_level = [p for p, qs in by_pl.items() if _levels(qs[0]) == 3]
+    assert len(two_level) == 4 and len(three_level) == 31
+    # (a) a two-level placement: all four chunk counts, full lists against the oracle
+    qs = [dict(q, topk=0) for q in by_pl[two_level[0]]]
+    for q, res in zip(qs, B.p2_synthesize_batch(qs, cfg["msg_bytes"])):
+        assert_same(res, oracle_result(oracle, q, cfg["msg_bytes"])[1], 1)
+    # (b) a three-level placement, k = 1 and 8: full lists and the top-10 against the oracle
+    qs = [dict(q, topk=0) for q in by_pl[three_level[0]] if q["n_chunks"] in (1, 8)]
+    full = B.p2_synthesize_batch(qs, cfg["msg_bytes"])
+    top = B.p2_synthesize_batch([dict(q, topk=10) for q in qs], cfg["msg_bytes"])
+    for q, res, tp in zip(qs, full, top):
+        ora = oracle_result(oracle, q, cfg["msg_bytes"])[1]
+        assert_same(res, ora, 1)
+        want = oracle.topk(ora["cost"][:, 0], ora["index"], 10)
+        assert np.allclose(np.sort(tp["cost"][:, 0]), ora["cost"][want, 0], rtol=RTOL)
+        assert set(tp["programs"]["index"].tolist()) <= set(ora["index"].tolist())
+
+
+def test_config4_full_size_sampled(B, oracle):
+    """k = 64 and k = 256 on a three-level placement (1.9e8 candidates each): the oracle needs
+    about a minute for the whole list at k = 256, so outputs are checked one by one: every program
+    the GPU lists is valid for the oracle with the same cost, sampled unlisted indices are invalid."""
+    cfg, queries = queries_of(4, B)
+    qs = [dict(q, topk=0) for q in queries if _levels(q) == 3 and q["n_chunks"] in (64, 256)][:2]
+    assert [q["n_chunks"] for q in qs] == [64, 256]
+    res64, res256 = B.p2_synthesize_batch(qs, cfg["msg_bytes"])
+    assert res64["stats"]["valid"] == res256["stats"]["valid"] == 2549
+    assert res64["programs"]["index"].tolist() == res256["programs"]["index"].tolist()
+    rng = np.random.default_rng(4)
+    for q, res in ((qs[0], res64), (qs[1], res256)):
+        oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
+                          n_chunks=q["n_chunks"])
+        progs = res["programs"]
+        pick = rng.choice(len(progs), size=60 if q["n_chunks"] == 256 else 300, replace=False)
+        for i in pick:
+            instr = progs["instr"][i][:progs["len"][i]].tolist()
+            assert oq.unrank(q["max_len"], int(progs["index"][i])) == instr
+            ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
+            assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
+        listed = set(progs["index"].tolist())
+        N = oq.num_candidates(q["max_len"])
+        probe = [int(v) for v in rng.integers(0, N, size=2000) if int(v) not in listed]
+        # neighbours of valid programs are the likeliest false negatives
+        probe += [int(ix) + d for ix in progs["index"][pick[:40]] for d in (-1, 1) if int(ix) + d not in listed and 0 <= int(ix) + d < N]
+        nvalid, _, _ = oq.eval_indices(q["max_len"], indices=probe, n_threads=8)
+        assert nvalid == 0
