@@ -138,7 +138,7 @@ def main():
         "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
                      "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
-                     "kernel": "k_eval_compact" if args.engine != 1 else "k_eval_literal",
+                     "kernel": "k_eval_literal" if args.engine == 1 else "k_eval_compact",
                      "launch_ms": eval_ms_per_launch, "algorithmic_lane_ops_per_launch": ops / launches_per_step},
     }
     if not args.no_cpu:

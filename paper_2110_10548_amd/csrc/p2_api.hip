@@ -13,8 +13,6 @@ namespace p2 {
 hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
                                p2_program* out_prog, double* out_cost, int only_missing, void* gscratch,
                                hipStream_t stream);
-hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
-                               p2_program* out_prog, double* out_cost, hipStream_t stream);
 }
 
 namespace {
@@ -51,8 +49,8 @@ struct HostBuf {
 
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
-    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, lit_scratch;
-    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos;
+    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, lit_scratch, post;
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post;
 };
 thread_local Ctx g_ctx;
 
@@ -82,7 +80,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct QueryRun {
     p2::Plan plan;
-    int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk
+    int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk (LITERAL or COMPACT)
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
     uint32_t valid_cap = 0, rerun_cap = 0;
@@ -162,7 +160,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
                 const unsigned long long chunks = (count + lanes - 1) / lanes;
-                unsigned long long iters = (chunks + 16383) / 16384;
+                unsigned long long iters = (chunks + 4095) / 4096;
                 iters = std::min<unsigned long long>(std::max<unsigned long long>(iters, 1), 64);
                 DevSegment sg;
                 sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len; sg.iters = (int)iters;
@@ -212,6 +210,35 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         *out = C.lit_scratch.p;
         return e;
     };
+    // Segment tables for the kernels that serve many queries per launch.  Tables of one phase are
+    // packed into C.post and uploaded with one copy; `PostLaunch` remembers where each one starts.
+    struct PostLaunch { int cls = 0; int max_R = 0, max_k = 0; std::vector<DevPostSeg> segs; unsigned blocks = 0; size_t off = 0; };
+    auto add_seg = [](std::vector<PostLaunch>& v, int cls, const Plan& pl, int query, uint32_t count, uint32_t per_block,
+                      size_t in_off, size_t out_off) {
+        PostLaunch* L = nullptr;
+        for (auto& c : v) if (c.cls == cls) L = &c;
+        if (!L) { v.emplace_back(); L = &v.back(); L->cls = cls; }
+        L->max_R = std::max(L->max_R, pl.R); L->max_k = std::max(L->max_k, pl.k);
+        DevPostSeg sg;
+        sg.first_block = L->blocks; sg.query = query; sg.count = count; sg.per_block = per_block;
+        sg.in_off = in_off; sg.out_off = out_off;
+        L->segs.push_back(sg);
+        L->blocks += (count + per_block - 1) / per_block;
+    };
+    auto upload_segs = [&](std::vector<std::vector<PostLaunch>*> groups) -> hipError_t {
+        size_t bytes = 0;
+        for (auto* g : groups) for (auto& L : *g) { L.off = bytes; bytes += align_up(sizeof(DevPostSeg) * L.segs.size(), 256); }
+        if (bytes == 0) return hipSuccess;
+        hipError_t e = C.post.ensure(bytes);
+        if (e != hipSuccess) return e;
+        e = C.h_post.ensure(bytes);
+        if (e != hipSuccess) return e;
+        for (auto* g : groups) for (auto& L : *g)
+            std::memcpy(static_cast<char*>(C.h_post.p) + L.off, L.segs.data(), sizeof(DevPostSeg) * L.segs.size());
+        return hipMemcpyAsync(C.post.p, C.h_post.p, bytes, hipMemcpyHostToDevice, stream);
+    };
+    auto segs_of = [&](const PostLaunch& L) { return reinterpret_cast<const DevPostSeg*>(static_cast<char*>(C.post.p) + L.off); };
+    auto mask_class = [](int R) { return R <= 32 ? 1 : R <= 64 ? 2 : R <= 128 ? 4 : R <= 256 ? 8 : 16; };
     char* hb = static_cast<char*>(C.h_blob.p);
     char* db = static_cast<char*>(C.blob.p);
     std::vector<char> done(n_queries, 0);
@@ -269,9 +296,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         // ---- evaluate every candidate of every query
         int eval_launches = 0;
         if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[0], stream));
-        for (auto& L : launches) { ++eval_launches;
+        for (auto& L : launches) {
+            ++eval_launches;
             P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
-                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream)); }
+                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
+        }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
@@ -288,16 +317,28 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(hipStreamSynchronize(stream));
         bool again = false;
         const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
-        // candidates whose state the compact engine could not hold go through the literal engine
+        // candidates whose state the compact engine could not hold go through the literal engine:
+        // one launch per mask-width class for the states that fit in LDS, one per query otherwise
         bool reran = false;
+        std::vector<PostLaunch> rerun_launches;
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap) continue;
-            void* gs = nullptr;
-            P2_HIP(lit_scratch(r.plan, &gs));
-            P2_HIP(launch_eval_literal(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k, 0ull,
-                                       hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, gs, stream));
             reran = true;
+            if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
+                add_seg(rerun_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
+            } else {
+                void* gs = nullptr;
+                P2_HIP(lit_scratch(r.plan, &gs));
+                P2_HIP(launch_eval_literal(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k, 0ull,
+                                           hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, gs, stream));
+            }
+        }
+        if (!rerun_launches.empty()) {
+            P2_HIP(upload_segs({&rerun_launches}));
+            for (auto& L : rerun_launches)
+                P2_HIP(launch_eval_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
+                                                L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
         }
         if (reran) {
             P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
@@ -306,7 +347,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
-            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.steps = hc[i].steps; r.members = hc[i].members;
+            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun;
+            r.steps = 0; r.members = 0;
+            for (int t = 0; t < kCounterStripes; ++t) { r.steps += hc[i].steps[t]; r.members += hc[i].members[t]; }
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);
@@ -334,27 +377,64 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
     size_t pos_off = 0;
     int post_launches = 0;
+    // ordering and costing: one launch per kernel and state-size class
+    std::vector<PostLaunch> sort_launches, ccost_launches, lcost_launches;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
-        post_launches += 2 + (r.topk > 0 ? 2 * n_msg : 0);
+        add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.off_valid, r.out_first);
+        if (r.engine == P2_ENGINE_COMPACT) {
+            const int cls = word_class(r.plan.k) * 100 + word_class(r.plan.R);
+            add_seg(ccost_launches, cls, r.plan, i, r.n_valid, 1, 0, r.out_first);     // per_block set below
+        }
+        const bool lit_cost = r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0);
+        if (lit_cost && literal_lds_bytes(r.plan.R, r.plan.k) != 0)
+            add_seg(lcost_launches, mask_class(r.plan.R) * 2 + (r.engine == P2_ENGINE_COMPACT ? 1 : 0), r.plan, i, r.n_valid, 1, 0,
+                    r.out_first);
+    }
+    for (auto& L : ccost_launches) {      // a block of the compact cost kernel takes as many entries as it has lanes
+        const uint32_t lanes = (uint32_t)compact_lanes(L.max_R, L.max_k);
+        L.blocks = 0;
+        for (auto& sg : L.segs) { sg.per_block = lanes; sg.first_block = L.blocks; L.blocks += (sg.count + lanes - 1) / lanes; }
+    }
+    P2_HIP(upload_segs({&sort_launches, &ccost_launches, &lcost_launches}));
+    unsigned long long* sorted_base = static_cast<unsigned long long*>(C.sorted.p);
+    p2_program* progs_base = static_cast<p2_program*>(C.progs.p);
+    double* costs_base = static_cast<double*>(C.costs.p);
+    for (auto& L : sort_launches) {
+        ++post_launches;
+        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p), sorted_base, segs_of(L), (int)L.segs.size(), L.blocks, stream));
+    }
+    // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
+    for (auto& L : ccost_launches) {
+        ++post_launches;
+        P2_HIP(launch_cost_compact_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
+                                        L.max_k, sorted_base, progs_base, costs_base, stream));
+    }
+    for (auto& L : lcost_launches) {
+        ++post_launches;
+        P2_HIP(launch_cost_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
+                                        L.max_k, sorted_base, progs_base, costs_base, L.cls & 1, stream));
+    }
+    for (int i = 0; i < n_queries; ++i) {
+        QueryRun& r = runs[i];
+        if (r.n_valid == 0) continue;
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
-        unsigned long long* sorted = static_cast<unsigned long long*>(C.sorted.p) + r.out_first;
-        p2_program* progs = static_cast<p2_program*>(C.progs.p) + r.out_first;
-        double* costs = static_cast<double*>(C.costs.p) + r.out_first * nm;
-        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p) + r.off_valid, sorted, r.n_valid, stream));
-        // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
-        if (r.engine == P2_ENGINE_COMPACT)
-            P2_HIP(launch_cost_compact(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs, stream));
-        if (r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0)) {
+        unsigned long long* sorted = sorted_base + r.out_first;
+        p2_program* progs = progs_base + r.out_first;
+        double* costs = costs_base + r.out_first * nm;
+        const bool lit_cost = r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0);
+        if (lit_cost && literal_lds_bytes(r.plan.R, r.plan.k) == 0) {      // literal state too large for LDS
             void* gs = nullptr;
             P2_HIP(lit_scratch(r.plan, &gs));
+            ++post_launches;
             P2_HIP(launch_cost_literal(dq, r.plan.R, r.plan.k, sorted, r.n_valid, progs, costs,
                                        r.engine == P2_ENGINE_COMPACT ? 1 : 0, gs, stream));
         }
         if (r.topk > 0) {
             const size_t kk = std::min<size_t>(r.topk, r.n_valid);
             for (int m = 0; m < n_msg; ++m) {
+                post_launches += 2;
                 P2_HIP(launch_topk(costs + m, n_msg, sorted, r.n_valid, r.topk,
                                    static_cast<long long*>(C.topk_pos.p) + pos_off, C.topk_scratch.p,
                                    &static_cast<DevCounters*>(C.counters.p)[i].nan_seen, stream));

@@ -24,9 +24,6 @@
 
 namespace p2 {
 
-hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
-                               p2_program* out_prog, double* out_cost, hipStream_t stream);
-
 namespace {
 
 constexpr int kWave = 64;
@@ -307,6 +304,118 @@ __device__ inline int step_uniform(uint32_t* my, int dstride, int g, int s, int 
     return give_up ? STEP_GIVE_UP : STEP_OK;
 }
 
+// The same for groups of GT = 2, 4, 8 or 16 devices: 16 members (16 / GT whole groups) are loaded
+// back to back before any of them is used, so a step waits for LDS once per 16 devices instead of
+// once per device.
+template <int KW, int MW, int GT>
+__device__ inline int step_batched(uint32_t* my, int dstride, int s, int master, int n_groups, int op) {
+    constexpr int WPD = KW + MW;
+    constexpr int NB_MAX = WPD <= 4 ? 16 : WPD <= 8 ? 8 : WPD <= 16 ? 4 : 2;   // keep a batch within ~64 registers
+    if constexpr (GT > NB_MAX) {
+        return step_uniform<KW, MW>(my, dstride, GT, s, master, n_groups, op);
+    } else {
+    constexpr int NB = NB_MAX, GPB = NB / GT;
+    const int gs = GT * s;
+    uint32_t badx = 0;
+    bool changed = false, give_up = false;
+    int lo = 0, hib = 0;
+    for (int G0 = 0; G0 < n_groups; G0 += GPB) {
+        int base[GPB];
+#pragma unroll
+        for (int i = 0; i < GPB; ++i) {
+            base[i] = hib + lo;
+            if (master) hib += gs;
+            else if (++lo == s) { lo = 0; hib += gs; }
+        }
+        Slot<KW, MW> L[NB];
+#pragma unroll
+        for (int i = 0; i < GPB; ++i) {
+            if (G0 + i < n_groups) {
+#pragma unroll
+                for (int p = 0; p < GT; ++p) L[i * GT + p] = load_slot<KW, MW>(my, dstride, base[i] + p * s);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < GPB; ++i) {
+            if (G0 + i >= n_groups) continue;
+            const Slot<KW, MW> first = L[i * GT];
+            const int b0 = base[i];
+            if (op == OP_AR || op == OP_RS || op == OP_RD) {
+                Words<MW> accm = first.m;
+#pragma unroll
+                for (int p = 1; p < GT; ++p) {
+                    const Slot<KW, MW>& cur = L[i * GT + p];
+                    badx |= fold_xor(cur.r, first.r) | fold_and(cur.m, accm);
+#pragma unroll
+                    for (int w = 0; w < MW; ++w) accm.w[w] |= cur.m.w[w];
+                }
+                changed |= fold_or(first.r) != 0;
+                if (op == OP_AR) {
+#pragma unroll
+                    for (int p = 0; p < GT; ++p) store_mask<KW, MW>(my, dstride, b0 + p * s, accm);
+                } else if (op == OP_RD) {
+                    store_mask<KW, MW>(my, dstride, b0, accm);
+                    Words<KW> zr; Words<MW> zm;
+#pragma unroll
+                    for (int w = 0; w < KW; ++w) zr.w[w] = 0;
+#pragma unroll
+                    for (int w = 0; w < MW; ++w) zm.w[w] = 0;
+#pragma unroll
+                    for (int p = 1; p < GT; ++p) store_slot<KW, MW>(my, dstride, b0 + p * s, zr, zm);
+                } else {
+                    const int rows = popcount(first.r);
+                    const int per = rows / GT;
+                    badx |= (uint32_t)(per * GT != rows);
+                    Words<KW> prev;
+#pragma unroll
+                    for (int w = 0; w < KW; ++w) prev.w[w] = 0;
+#pragma unroll
+                    for (int p = 0; p < GT; ++p) {
+                        const Words<KW> upto = lowest_n(first.r, (p + 1) * per);
+                        Words<KW> nr;
+#pragma unroll
+                        for (int w = 0; w < KW; ++w) { nr.w[w] = upto.w[w] & ~prev.w[w]; prev.w[w] = upto.w[w]; }
+                        store_slot<KW, MW>(my, dstride, b0 + p * s, nr, accm);
+                    }
+                }
+            } else if (op == OP_AG) {
+                Words<KW> accr = first.r;
+                uint32_t smx = 0;
+                bool anyzero = fold_or(first.r) == 0;
+#pragma unroll
+                for (int p = 1; p < GT; ++p) {
+                    const Slot<KW, MW>& cur = L[i * GT + p];
+                    badx |= fold_and(cur.r, accr);
+                    smx |= fold_xor(cur.m, first.m);
+                    anyzero |= fold_or(cur.r) == 0;
+#pragma unroll
+                    for (int w = 0; w < KW; ++w) accr.w[w] |= cur.r.w[w];
+                }
+                badx |= (uint32_t)anyzero;
+                give_up |= smx != 0;
+                changed = true;
+#pragma unroll
+                for (int p = 0; p < GT; ++p) store_rows<KW, MW>(my, dstride, b0 + p * s, accr);
+            } else {
+                uint32_t subx = 0, difx = 0;
+#pragma unroll
+                for (int p = 1; p < GT; ++p) {
+                    const Slot<KW, MW>& cur = L[i * GT + p];
+                    subx |= fold_andn(cur.r, first.r) | fold_andn(cur.m, first.m);
+                    difx |= fold_xor(cur.r, first.r) | fold_xor(cur.m, first.m);
+                }
+                badx |= subx | (uint32_t)(difx == 0);
+                changed = true;
+#pragma unroll
+                for (int p = 1; p < GT; ++p) store_slot<KW, MW>(my, dstride, b0 + p * s, first.r, first.m);
+            }
+        }
+    }
+    if (badx != 0 || !changed) return STEP_INVALID;
+    return give_up ? STEP_GIVE_UP : STEP_OK;
+    }
+}
+
 // One instruction, lanes may differ in pattern and rule.  cost_* only with kCost.
 template <int KW, int MW, bool kCost>
 __device__ inline int step_mixed(uint32_t* my, int dstride, const PatLds P, int op, const DevQuery& q, const DevPattern* dp,
@@ -514,10 +623,16 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
                 int rc;
                 if (__all(ins == ins0)) {
                     const PatLds P0 = spat[ins0 >> 3];
-                    rc = step_uniform<KW, MW>(my, dstride, __builtin_amdgcn_readfirstlane(P0.g), __builtin_amdgcn_readfirstlane(P0.s),
-                                              __builtin_amdgcn_readfirstlane(P0.master),
-                                              __builtin_amdgcn_readfirstlane(P0.n_groups),
-                                              (int)(ins0 & 7u));
+                    const int g0 = __builtin_amdgcn_readfirstlane(P0.g), s0 = __builtin_amdgcn_readfirstlane(P0.s);
+                    const int ma0 = __builtin_amdgcn_readfirstlane(P0.master), ng0 = __builtin_amdgcn_readfirstlane(P0.n_groups);
+                    const int op0 = (int)(ins0 & 7u);
+                    switch (g0) {
+                    case 2: rc = step_batched<KW, MW, 2>(my, dstride, s0, ma0, ng0, op0); break;
+                    case 4: rc = step_batched<KW, MW, 4>(my, dstride, s0, ma0, ng0, op0); break;
+                    case 8: rc = step_batched<KW, MW, 8>(my, dstride, s0, ma0, ng0, op0); break;
+                    case 16: rc = step_batched<KW, MW, 16>(my, dstride, s0, ma0, ng0, op0); break;
+                    default: rc = step_uniform<KW, MW>(my, dstride, g0, s0, ma0, ng0, op0); break;
+                    }
                 } else {
                     rc = step_mixed<KW, MW, false>(my, dstride, spat[ins >> 3], (int)(ins & 7u), q, nullptr, nullptr, nullptr);
                 }
@@ -539,26 +654,32 @@ __global__ __launch_bounds__(kWave) void k_eval_compact(const DevQuery* __restri
         }
     }
     for (int o = 32; o > 0; o >>= 1) { steps += __shfl_xor(steps, o, kWave); members += __shfl_xor(members, o, kWave); }
-    if (lane == 0 && steps) { atomicAdd(&q.counters->steps, steps); atomicAdd(&q.counters->members, members); }
+    if (lane == 0 && steps) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
 }
 
-// Cost of the valid programs of one query: lane i re-runs sorted[i] with the cost terms on.
+// Cost of valid programs: lane i of a segment's block re-runs sorted[out_off + i] with the cost terms on.
 template <int KW, int MW>
-__global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restrict__ qp,
-                                                        const unsigned long long* __restrict__ sorted, uint32_t n,
+__global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restrict__ queries,
+                                                        const DevPostSeg* __restrict__ segs, int n_segs,
+                                                        const unsigned long long* __restrict__ sorted,
                                                         p2_program* __restrict__ out_prog, double* __restrict__ out_cost,
                                                         int LS) {
     extern __shared__ uint32_t lds[];
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint16_t sdig[kMaxPatterns * 5];
-    const DevQuery& q = *qp;
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
     load_patterns(q, spat, sdig);
     const int lane = threadIdx.x;
     constexpr int WS = Lay<KW, MW>::WS;
     uint32_t* my = lds + lane * WS;
     const int dstride = LS * WS;
-    const uint32_t i = blockIdx.x * (uint32_t)LS + (uint32_t)lane;
-    if (lane >= LS || i >= n) return;
+    const uint32_t li = (blockIdx.x - seg.first_block) * (uint32_t)LS + (uint32_t)lane;
+    if (lane >= LS || li >= seg.count) return;
+    const size_t i = seg.out_off + li;
     const unsigned long long idx = sorted[i];
     int len = 1;
     while (len < q.max_len && idx >= q.base[len + 1]) ++len;
@@ -587,7 +708,7 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
     }
     out_prog[i] = pr;
     for (int m = 0; m < q.n_msg; ++m)
-        out_cost[(size_t)i * q.n_msg + m] = ok ? sum_alpha + q.msg_bytes[m] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
+        out_cost[i * q.n_msg + m] = ok ? sum_alpha + q.msg_bytes[m] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
 }
 
 inline int round_words(int bits) {
@@ -623,12 +744,12 @@ hipError_t eval_mw(int MW, const DevQuery* queries, const DevSegment* segs, int 
     return e != hipSuccess ? e : hipGetLastError();
 }
 template <int KW>
-hipError_t cost_mw(int MW, const DevQuery* q, const unsigned long long* sorted, uint32_t n, p2_program* out_prog,
-                   double* out_cost, unsigned blocks, int LS, size_t lds, hipStream_t stream) {
+hipError_t cost_mw(int MW, const DevQuery* queries, const DevPostSeg* segs, int n_segs, const unsigned long long* sorted,
+                   p2_program* out_prog, double* out_cost, unsigned blocks, int LS, size_t lds, hipStream_t stream) {
     hipError_t e = hipSuccess;
 #define P2_GO(MWV)                                                                                                        \
     e = allow_lds(k_cost_compact<KW, MWV>, lds);                                                                          \
-    if (e == hipSuccess) hipLaunchKernelGGL((k_cost_compact<KW, MWV>), dim3(blocks), dim3(kWave), lds, stream, q, sorted, n, out_prog, out_cost, LS);
+    if (e == hipSuccess) hipLaunchKernelGGL((k_cost_compact<KW, MWV>), dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, sorted, out_prog, out_cost, LS);
     switch (MW) {
     case 1: P2_GO(1) break;
     case 2: P2_GO(2) break;
@@ -665,20 +786,20 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
     }
 }
 
-hipError_t launch_cost_compact(const DevQuery* q, int R, int k, const unsigned long long* sorted, uint32_t n,
-                               p2_program* out_prog, double* out_cost, hipStream_t stream) {
-    if (n == 0) return hipSuccess;
-    const int LS = compact_lanes(R, k);
+hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    double* costs, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const int LS = compact_lanes(max_R, max_k);       // the segments' per_block
     if (LS == 0) return hipErrorInvalidValue;
-    const int KW = round_words(k), MW = round_words(R);
-    const size_t lds = (size_t)R * (size_t)lane_words(KW, MW) * 4 * (size_t)LS;
-    const unsigned blocks = (n + (unsigned)LS - 1) / (unsigned)LS;
+    const int KW = round_words(max_k), MW = round_words(max_R);
+    const size_t lds = (size_t)max_R * (size_t)lane_words(KW, MW) * 4 * (size_t)LS;
     switch (KW) {
-    case 1: return cost_mw<1>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);
-    case 2: return cost_mw<2>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);
-    case 4: return cost_mw<4>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);
-    case 8: return cost_mw<8>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);
-    default: return cost_mw<16>(MW, q, sorted, n, out_prog, out_cost, blocks, LS, lds, stream);
+    case 1: return cost_mw<1>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
+    case 2: return cost_mw<2>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
+    case 4: return cost_mw<4>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
+    case 8: return cost_mw<8>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
+    default: return cost_mw<16>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
     }
 }
 

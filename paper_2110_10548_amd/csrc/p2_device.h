@@ -34,14 +34,36 @@ struct DevSegment {
     unsigned long long count;
 };
 
+// Work of the kernels that run after the evaluation (ordering, costing, literal re-runs), which
+// serve all queries of a batch in one launch: blocks [first_block, next first_block) handle
+// `count` list entries of one query, `per_block` each, read at in_off and written at out_off
+// (element offsets into the batch-wide buffers).
+struct DevPostSeg {
+    uint32_t first_block;
+    int32_t query;
+    uint32_t count;
+    uint32_t per_block;
+    unsigned long long in_off;
+    unsigned long long out_off;
+};
+__device__ inline DevPostSeg find_post_seg(const DevPostSeg* __restrict__ segs, int n_segs, uint32_t block) {
+    int a = 0, b = n_segs - 1;
+    while (a < b) {
+        const int mid = (a + b + 1) >> 1;
+        if (segs[mid].first_block <= block) a = mid; else b = mid - 1;
+    }
+    return segs[a];
+}
+
 // Counters a query's kernels add to.
+constexpr int kCounterStripes = 64;   // blocks add to stripe (blockIdx % 64): same-address atomics serialise
 struct DevCounters {
     uint32_t n_valid;              // entries appended to valid_idx (may exceed valid_cap)
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
-    unsigned long long steps;      // instructions applied
-    unsigned long long members;    // devices taking part in those instructions, summed
     uint32_t nan_seen;
     uint32_t pad;
+    unsigned long long steps[kCounterStripes];     // instructions applied
+    unsigned long long members[kCounterStripes];   // devices taking part in those instructions, summed
 };
 
 struct DevQuery {
@@ -84,8 +106,20 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
                                int max_R, int max_k, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
-// sorted[i] = i-th smallest of in[0..n)  (distinct keys)
-hipError_t launch_rank_sort(const unsigned long long* in, unsigned long long* sorted, uint32_t n, hipStream_t stream);
+// Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).
+// per_block must be 256.
+hipError_t launch_rank_sort(const unsigned long long* valid, unsigned long long* sorted, const DevPostSeg* segs,
+                            int n_segs, unsigned blocks, hipStream_t stream);
+// Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
+hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
+// Program records and costs of the sorted valid candidates at out_off + i of each segment.
+hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    double* costs, hipStream_t stream);
+hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    double* costs, int only_missing, hipStream_t stream);
 // For each of the n sorted valid candidates: its program record and its cost for every message size.
 hipError_t launch_cost(const DevQuery* q, int R, int k, int engine, const unsigned long long* sorted, uint32_t n,
                        p2_program* out_prog, double* out_cost, hipStream_t stream);

@@ -278,7 +278,10 @@ __global__ __launch_bounds__(kWave) void k_eval_literal(const DevQuery* __restri
         }
         __syncthreads();
     }
-    if (lane == 0 && steps) { atomicAdd(&q.counters->steps, steps); atomicAdd(&q.counters->members, members); }
+    if (lane == 0 && steps) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
 }
 
 // Cost of valid programs: block i re-runs sorted[i] with the cost terms switched on and writes
@@ -323,6 +326,79 @@ __global__ __launch_bounds__(kWave) void k_cost_literal(const DevQuery* __restri
         if (lane < q.n_msg) out_cost[(size_t)i * q.n_msg + lane] = ok ? cost : __longlong_as_double(0x7ff8000000000000ll);
         __syncthreads();
     }
+}
+
+// The two kernels above for lists spread over many queries: block b serves one entry of its segment.
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_eval_literal_list(const DevQuery* __restrict__ queries,
+                                                             const DevPostSeg* __restrict__ segs, int n_segs,
+                                                             const unsigned long long* __restrict__ list) {
+    extern __shared__ uint32_t lds[];
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const LitLds L = carve(lds, q.R, q.k, MW);
+    const unsigned long long idx = list[seg.in_off + (blockIdx.x - seg.first_block)];
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx, digit);
+    lit_init<MW>(q, L, lane);
+    unsigned long long steps = 0, members = 0;
+    bool ok = true;
+    for (int t = 0; t < len && ok; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ++steps;
+        members += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        ok = lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr);
+    }
+    if (ok && lit_is_goal<MW>(q, L, lane) && lane == 0) {
+        const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+        if (pos < q.valid_cap) q.valid_idx[pos] = idx;
+    }
+    if (lane == 0) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
+}
+
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_cost_literal_list(const DevQuery* __restrict__ queries,
+                                                             const DevPostSeg* __restrict__ segs, int n_segs,
+                                                             const unsigned long long* __restrict__ sorted,
+                                                             p2_program* __restrict__ out_prog, double* __restrict__ out_cost,
+                                                             int only_missing) {
+    extern __shared__ uint32_t lds[];
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
+    // only_missing: another engine has filled every row but those it marked with NaN
+    if (only_missing) {
+        const double have = out_cost[i * q.n_msg];
+        if (have == have) return;
+    }
+    const LitLds L = carve(lds, q.R, q.k, MW);
+    const unsigned long long idx = sorted[i];
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx, digit);
+    lit_init<MW>(q, L, lane);
+    double cost = 0.0;
+    bool ok = true;
+    for (int t = 0; t < len && ok; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ok = lit_step<MW, true>(q, q.pat[pid], op, L, lane, &cost);
+    }
+    if (lane == 0) {
+        p2_program pr;
+        pr.index = idx;
+        pr.len = (uint8_t)len;
+        for (int t = 0; t < 7; ++t) {
+            int code = 0;
+            if (t < len) { const int pid = digit[t] / q.n_ops; code = pid * 5 + q.ops[digit[t] - pid * q.n_ops]; }
+            pr.instr[t] = (uint8_t)code;
+        }
+        out_prog[i] = pr;
+    }
+    if (lane < q.n_msg) out_cost[i * q.n_msg + lane] = ok ? cost : __longlong_as_double(0x7ff8000000000000ll);
 }
 
 template <typename F>
@@ -414,6 +490,52 @@ hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned l
         hipLaunchKernelGGL(k_cost_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, sorted, n, out_prog, \
                            out_cost, only_missing, static_cast<uint32_t*>(gscratch), gwords);
     switch (MW) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* list, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const size_t lds = literal_lds_bytes(max_R, max_k);
+    if (lds == 0) return hipErrorInvalidValue;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_eval_literal_list<MWV>, lds);                                                          \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_eval_literal_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, list);
+    switch (mask_words(max_R)) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    double* costs, int only_missing, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const size_t lds = literal_lds_bytes(max_R, max_k);
+    if (lds == 0) return hipErrorInvalidValue;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_cost_literal_list<MWV>, lds);                                                          \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_cost_literal_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, \
+                           sorted, progs, costs, only_missing);
+    switch (mask_words(max_R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
     case 4: P2_LAUNCH(4) break;

@@ -8,13 +8,17 @@ namespace {
 
 constexpr int kWave = 64;
 
-// sorted[rank(in[i])] = in[i], rank = number of smaller keys.  Keys are distinct candidate
-// indices and n is tiny next to the candidate space, so the quadratic count is the cheap way
-// to a deterministic ascending order after an unordered atomic append.
-__global__ __launch_bounds__(256) void k_rank_sort(const unsigned long long* __restrict__ in,
-                                                   unsigned long long* __restrict__ sorted, uint32_t n) {
+// sorted[rank(in[i])] = in[i], rank = number of smaller keys, per segment.  Keys are distinct
+// candidate indices and a query has few valid ones next to its candidate space, so the quadratic
+// count is the cheap way to a deterministic ascending order after an unordered atomic append.
+__global__ __launch_bounds__(256) void k_rank_sort(const unsigned long long* __restrict__ valid,
+                                                   unsigned long long* __restrict__ sorted,
+                                                   const DevPostSeg* __restrict__ segs, int n_segs) {
     __shared__ unsigned long long tile[256];
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const unsigned long long* in = valid + seg.in_off;
+    const uint32_t n = seg.count;
+    const uint32_t i = (blockIdx.x - seg.first_block) * 256u + threadIdx.x;
     const unsigned long long key = i < n ? in[i] : 0ull;
     uint32_t rank = 0;
     for (uint32_t t0 = 0; t0 < n; t0 += 256u) {
@@ -25,7 +29,7 @@ __global__ __launch_bounds__(256) void k_rank_sort(const unsigned long long* __r
         for (uint32_t u = 0; u < lim; ++u) rank += tile[u] < key;
         __syncthreads();
     }
-    if (i < n) sorted[rank] = key;
+    if (i < n) sorted[seg.out_off + rank] = key;
 }
 
 struct Item {
@@ -154,9 +158,10 @@ inline unsigned topk_blocks(long long n) {
 
 }  // namespace
 
-hipError_t launch_rank_sort(const unsigned long long* in, unsigned long long* sorted, uint32_t n, hipStream_t stream) {
-    if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_rank_sort, dim3((n + 255u) / 256u), dim3(256), 0, stream, in, sorted, n);
+hipError_t launch_rank_sort(const unsigned long long* valid, unsigned long long* sorted, const DevPostSeg* segs,
+                            int n_segs, unsigned blocks, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_rank_sort, dim3(blocks), dim3(256), 0, stream, valid, sorted, segs, n_segs);
     return hipGetLastError();
 }
 
