@@ -9,6 +9,7 @@ evaluation kernel's algorithmic lane-operations against the chip's 32-bit intege
 the cpu_baseline object times the plain CPU oracle on a bounded sample of the same candidates.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,6 +28,20 @@ def algorithmic_lane_ops(stats, n_chunks):
     read, tested against the rule's premise, folded into the group's result and written: 4 each."""
     words = -(-n_chunks // 32) + -(-stats["group_size"] // 32)
     return 4.0 * words * stats["member_visits"]
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or
+    None when there is none or the kernel source has changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "%s_cfg2_traffic.json" % kernel)
+    src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc", "p2_compact.hip" if kernel == "k_eval_compact" else "p2_literal.hip")
+    try:
+        rec = json.load(open(path))
+        if rec["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
+            return None
+        return rec["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(queries, budget_s=15.0):
@@ -75,6 +90,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..4")
     ap.add_argument("--engine", type=int, default=0, help="0 auto, 1 literal, 2 compact")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: candidate evaluation is embarrassingly parallel and this build "
@@ -93,6 +110,12 @@ def main():
     msg = cfg["msg_bytes"]
     B.p2_set_profiling(True)
 
+    if args.copy_mib > 0:
+        src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                            # reads and writes copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     batch = B.Batch(queries, msg)                 # argument marshalling only; every step replans on the host
     for _ in range(max(args.warmup, 1)):
         batch.run_raw()
@@ -115,6 +138,7 @@ def main():
     reruns = sum(r["stats"]["literal_reruns"] for r in results)
     ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()))
               for q, r in zip(queries, results))
+    kernel = "k_eval_literal" if args.engine == 1 else "k_eval_compact"
     ms_per_step = dt / args.steps * 1e3
     eval_ms_per_launch = eval_ms / max(launches, 1)
     launches_per_step = launches / args.steps
@@ -137,8 +161,9 @@ def main():
         "evaluate_only_candidates_per_s": candidates / (eval_ms / args.steps * 1e-3),
         "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-                     "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
-                     "kernel": "k_eval_literal" if args.engine == 1 else "k_eval_compact",
+                     "frac": achieved / ALU_PEAK_LANE_OPS,
+                     "traffic": measured_traffic(kernel) if args.config == 2 else None,
+                     "kernel": kernel,
                      "launch_ms": eval_ms_per_launch, "algorithmic_lane_ops_per_launch": ops / launches_per_step},
     }
     if not args.no_cpu:
