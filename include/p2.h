@@ -66,9 +66,12 @@ int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int3
                                 int32_t* out, int64_t cap, int64_t* out_count);
 
 /* Evaluation engines.  Both give identical results; they differ in the state they keep. */
-#define P2_ENGINE_AUTO 0      /* compact engine, literal engine for the candidates it cannot hold */
+#define P2_ENGINE_AUTO 0      /* compact engine, literal engine for the candidates it cannot hold;
+                                 every candidate index is evaluated on its own                    */
 #define P2_ENGINE_LITERAL 1   /* R x k masks of R bits per candidate in LDS, one wavefront each   */
 #define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask               */
+#define P2_ENGINE_FRONTIER 3  /* enumeration by program size with pruning (Sec. 3.5): only valid
+                                 prefixes are extended; AUTO picks it above 2^30 candidates       */
 
 typedef struct {
     int32_t n_chunks;    /* k of Sec. 3.2; 0 => number of devices (the paper's choice)           */

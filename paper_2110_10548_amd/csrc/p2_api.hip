@@ -2,6 +2,7 @@
 // copy-back.  All arithmetic of the method runs in the kernels; this file only moves data.
 #include <algorithm>
 #include <chrono>
+#include <cstddef>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -33,6 +34,24 @@ struct DevBuf {
         return e;
     }
 };
+// grow a device buffer to `bytes`, keeping its first `keep` bytes
+hipError_t grow_keep(DevBuf& b, size_t bytes, size_t keep, hipStream_t stream) {
+    if (bytes <= b.cap) return hipSuccess;
+    size_t want = std::max(bytes, b.cap * 2);
+    want = (want + 4095) & ~(size_t)4095;
+    void* np = nullptr;
+    hipError_t e = hipMalloc(&np, want);
+    if (e != hipSuccess) return e;
+    if (b.p && keep) {
+        e = hipMemcpyAsync(np, b.p, keep, hipMemcpyDeviceToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) { (void)hipFree(np); return e; }
+    }
+    if (b.p) (void)hipFree(b.p);
+    b.p = np; b.cap = want;
+    return hipSuccess;
+}
+
 struct HostBuf {
     void* p = nullptr;
     size_t cap = 0;
@@ -50,7 +69,8 @@ struct HostBuf {
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, lit_scratch, post;
-    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post;
+    DevBuf f_entries[2], f_states[2], f_literal[2], f_surv, f_surv_literal, f_ctr, f_valid;   // frontier engine
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr;
 };
 thread_local Ctx g_ctx;
 
@@ -81,6 +101,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct QueryRun {
     p2::Plan plan;
     int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk (LITERAL or COMPACT)
+    bool frontier = false;                // enumeration by size with pruning instead of index by index
+    size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
     uint32_t valid_cap = 0, rerun_cap = 0;
@@ -122,6 +144,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (want == P2_ENGINE_LITERAL) {
             if (!lit_ok) return fail(P2_EUNSUPPORTED, "state too large for the literal engine");
             runs[i].engine = P2_ENGINE_LITERAL;
+        } else if (want == P2_ENGINE_FRONTIER || (want == P2_ENGINE_AUTO && pl.n_candidates > (1ull << 30))) {
+            runs[i].engine = P2_ENGINE_COMPACT;      // its programs are costed like the compact engine's
+            runs[i].frontier = true;
         } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO) {
             if (cmp_ok) runs[i].engine = P2_ENGINE_COMPACT;
             else if (lit_ok && want == P2_ENGINE_AUTO) runs[i].engine = P2_ENGINE_LITERAL;
@@ -140,7 +165,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     std::vector<Launch> launches;
     auto word_class = [](int bits) { int w = (bits + 31) / 32; return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16; };
     for (int i = 0; i < n_queries; ++i) {
-        if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].plan.n_candidates == 0) continue;
+        if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].plan.n_candidates == 0) continue;
         const Plan& pl = runs[i].plan;
         const int kw = word_class(pl.k), mw = word_class(pl.R);
         Launch* L = nullptr;
@@ -155,7 +180,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         unsigned long long blocks = 0;
         for (int i = 0; i < n_queries; ++i) {
             const Plan& pl = runs[i].plan;
-            if (runs[i].engine != P2_ENGINE_COMPACT || pl.n_candidates == 0) continue;
+            if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || pl.n_candidates == 0) continue;
             if (word_class(pl.k) != L.kw || word_class(pl.R) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
@@ -197,8 +222,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     };
     for (auto& r : runs) {
         const unsigned long long N = r.plan.n_candidates;
-        r.valid_cap = (uint32_t)std::min<unsigned long long>(N, 1u << 15);
-        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
+        r.valid_cap = r.frontier ? 0u : (uint32_t)std::min<unsigned long long>(N, 1u << 15);
+        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT && !r.frontier) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
     }
 
     // global state buffer for literal evaluations whose state does not fit in LDS
@@ -360,6 +385,93 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (attempt == 3) return fail(P2_EDEVICE, "result lists kept overflowing");
     }
 
+    // ---- frontier queries: enumeration by program size, one query at a time, one wait per level
+    size_t fvalid_used = 0;
+    for (int i = 0; i < n_queries; ++i) {
+        QueryRun& r = runs[i];
+        if (!r.frontier) continue;
+        const Plan& pl = r.plan;
+        r.off_fvalid = fvalid_used;
+        r.n_valid = 0; r.n_rerun = 0; r.steps = 0; r.members = 0;
+        if (pl.n_candidates == 0) continue;
+        const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
+        const size_t sw = frontier_state_words(pl.R, pl.k);
+        P2_HIP(C.f_ctr.ensure(sizeof(FrontCounters)));
+        P2_HIP(C.h_fctr.ensure(sizeof(FrontCounters)));
+        FrontCounters* dctr = static_cast<FrontCounters*>(C.f_ctr.p);
+        const FrontCounters* hctr = static_cast<const FrontCounters*>(C.h_fctr.p);
+        P2_HIP(hipMemsetAsync(dctr, 0, sizeof(FrontCounters), stream));
+        int cur = 0;
+        P2_HIP(C.f_entries[cur].ensure(sizeof(FrontEntry)));
+        P2_HIP(C.f_states[cur].ensure(sw * 4));
+        P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(C.f_entries[cur].p),
+                                 static_cast<uint32_t*>(C.f_states[cur].p), stream));
+        uint32_t n_c = 1, n_l = 0;
+        void* gs = nullptr;
+        for (int len = 0; len < pl.max_len && (n_c > 0 || n_l > 0); ++len) {
+            const int keep = len + 1 < pl.max_len ? 1 : 0;
+            size_t cap_c = std::max<size_t>(1024, (size_t)n_c * pl.alphabet / 8);
+            size_t cap_l = std::max<size_t>(1024, (size_t)n_l * pl.alphabet / 2);
+            for (;;) {     // classify; repeat with larger survivor lists if they overflow
+                P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
+                P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
+                P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, valid_written), stream));
+                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
+                                             static_cast<const uint32_t*>(C.f_states[cur].p), n_c,
+                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, dctr, stream));
+                if (n_l > 0) {
+                    gs = nullptr;
+                    if (front_literal_lds_bytes(pl.R, pl.k) == 0) {
+                        unsigned nb = 0;
+                        P2_HIP(C.lit_scratch.ensure(literal_scratch_bytes(pl.R, pl.k, &nb)));
+                        gs = C.lit_scratch.p;
+                    }
+                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
+                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, stream));
+                }
+                P2_HIP(hipMemcpyAsync(C.h_fctr.p, dctr, sizeof(FrontCounters), hipMemcpyDeviceToHost, stream));
+                P2_HIP(hipStreamSynchronize(stream));
+                if (hctr->n_surv <= cap_c && hctr->n_surv_literal <= cap_l) break;
+                // the repeated classification counts its steps again: take them back
+                cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, hctr->n_surv_literal);
+                FrontCounters fix = *hctr;
+                fix.steps = r.steps; fix.members = r.members;
+                P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
+                P2_HIP(hipStreamSynchronize(stream));
+            }
+            const uint32_t n_surv = hctr->n_surv, n_surv_l = hctr->n_surv_literal;
+            const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_plit = hctr->n_prefix_literal;
+            r.steps = hctr->steps; r.members = hctr->members;
+            r.n_rerun += n_plit;
+            P2_HIP(grow_keep(C.f_valid, (fvalid_used + r.n_valid + n_goal + 1) * sizeof(unsigned long long),
+                             (fvalid_used + r.n_valid) * sizeof(unsigned long long), stream));
+            const int nxt = cur ^ 1;
+            if (keep) {
+                P2_HIP(C.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
+                P2_HIP(C.f_states[nxt].ensure(std::max<size_t>(n_prefix, 1) * sw * 4));
+                P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
+            }
+            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used;
+            P2_HIP(launch_front_materialize(dq, (uint32_t)i, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
+                                            static_cast<const uint32_t*>(C.f_states[cur].p),
+                                            static_cast<const FrontSurvivor*>(C.f_surv.p), n_surv, len, keep,
+                                            static_cast<FrontEntry*>(C.f_entries[nxt].p), static_cast<uint32_t*>(C.f_states[nxt].p),
+                                            static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, dctr, stream));
+            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
+                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l, len, keep,
+                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, dctr, stream));
+            r.n_valid += n_goal;
+            n_c = keep ? n_prefix : 0;
+            n_l = keep ? n_plit : 0;
+            cur = nxt;
+        }
+        // steps of the last materialisation
+        P2_HIP(hipMemcpyAsync(C.h_fctr.p, dctr, sizeof(FrontCounters), hipMemcpyDeviceToHost, stream));
+        P2_HIP(hipStreamSynchronize(stream));
+        r.steps = hctr->steps; r.members = hctr->members;
+        fvalid_used += r.n_valid;
+    }
+
     // ---- order, cost, select
     size_t total_valid = 0;
     for (auto& r : runs) { r.out_first = total_valid; total_valid += r.n_valid; }
@@ -382,7 +494,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
-        add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.off_valid, r.out_first);
+        add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid, r.out_first);
         if (r.engine == P2_ENGINE_COMPACT) {
             const int cls = word_class(r.plan.k) * 100 + word_class(r.plan.R);
             add_seg(ccost_launches, cls, r.plan, i, r.n_valid, 1, 0, r.out_first);     // per_block set below
@@ -403,7 +515,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     double* costs_base = static_cast<double*>(C.costs.p);
     for (auto& L : sort_launches) {
         ++post_launches;
-        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p), sorted_base, segs_of(L), (int)L.segs.size(), L.blocks, stream));
+        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p), static_cast<unsigned long long*>(C.f_valid.p), sorted_base,
+                                segs_of(L), (int)L.segs.size(), L.blocks, stream));
     }
     // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
     for (auto& L : ccost_launches) {
@@ -492,7 +605,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             p2_stats& s = stats[i];
             s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
-            s.alphabet = r.plan.alphabet; s.engine = r.engine;
+            s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.engine;
         }
     }
     out_offset[n_queries] = w;

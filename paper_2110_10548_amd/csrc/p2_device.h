@@ -94,6 +94,8 @@ struct DevQuery {
 // then lives in a global buffer of literal_scratch_bytes, split over *blocks blocks).
 size_t literal_lds_bytes(int R, int k);
 size_t literal_scratch_bytes(int R, int k, unsigned* blocks);
+// Same for the literal frontier kernel, which keeps row-class tables beside the state.
+size_t front_literal_lds_bytes(int R, int k);
 
 // Evaluate candidates [start, start + count) of query *q (device pointer), or, if list != nullptr,
 // the `count` candidate indices stored at list (device pointer; count may also be read from
@@ -108,8 +110,9 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).
 // per_block must be 256.
-hipError_t launch_rank_sort(const unsigned long long* valid, unsigned long long* sorted, const DevPostSeg* segs,
-                            int n_segs, unsigned blocks, hipStream_t stream);
+// A segment whose in_off has bit 63 set reads from valid2 (the frontier engine's lists) instead.
+hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long long* valid2, unsigned long long* sorted,
+                            const DevPostSeg* segs, int n_segs, unsigned blocks, hipStream_t stream);
 // Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
@@ -123,6 +126,47 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
 // For each of the n sorted valid candidates: its program record and its cost for every message size.
 hipError_t launch_cost(const DevQuery* q, int R, int k, int engine, const unsigned long long* sorted, uint32_t n,
                        p2_program* out_prog, double* out_cost, hipStream_t stream);
+// ---- frontier evaluation (p2_frontier.hip, p2_literal.hip) -------------------------------------
+// A prefix of the frontier: instruction digit t at bits [9t, 9t + 9) of `digits`.
+struct FrontEntry {
+    uint32_t query;
+    uint32_t len;
+    unsigned long long digits;
+};
+// A valid extension of a prefix: code 1 = prefix with a compact state, 2 = goal, 3 = prefix whose
+// state only the literal engine can hold.
+struct FrontSurvivor {
+    uint32_t entry;
+    uint16_t digit;
+    uint16_t code;
+};
+struct FrontCounters {
+    // reset before every level
+    uint32_t n_surv, n_surv_literal;        // survivors appended by the compact / literal classify kernels
+    uint32_t n_goal, n_prefix, n_prefix_literal;
+    uint32_t next_compact, next_literal;    // entries written to the next frontiers
+    uint32_t pad;
+    // running totals of the query
+    uint32_t valid_written, pad2;
+    unsigned long long steps, members;
+};
+size_t frontier_state_words(int R, int k);
+hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
+                             hipStream_t stream);
+hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
+                                 uint32_t n, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr, hipStream_t stream);
+hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
+                                         int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
+                                         void* gscratch, hipStream_t stream);
+hipError_t launch_front_materialize(const DevQuery* q, uint32_t query, int R, int k, const FrontEntry* entries,
+                                    const uint32_t* states, const FrontSurvivor* surv, uint32_t n_surv, int parent_len,
+                                    int keep_prefixes, FrontEntry* next_entries, uint32_t* next_states,
+                                    FrontEntry* next_literal, unsigned long long* valid_out, FrontCounters* ctr,
+                                    hipStream_t stream);
+hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry* entries, const FrontSurvivor* surv,
+                             uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
+                             unsigned long long* valid_out, FrontCounters* ctr, hipStream_t stream);
+
 // Top-k of (cost[i * stride], index[i]) over i < n: positions into out_pos[min(k, n)].
 // scratch: device buffer of topk_scratch_bytes(n, k) bytes.  nan_flag: device uint32 set to 1 on NaN.
 size_t topk_scratch_bytes(long long n, int k);

@@ -401,6 +401,217 @@ __global__ __launch_bounds__(kWave) void k_cost_literal_list(const DevQuery* __r
     if (lane < q.n_msg) out_cost[i * q.n_msg + lane] = ok ? cost : __longlong_as_double(0x7ff8000000000000ll);
 }
 
+// ---- frontier level for prefixes only the literal engine can hold ---------------------------------
+// A block rebuilds the literal state of one prefix, then classifies every instruction against it
+// without writing the state.  All rules act row by row, and rows that are equal on every device
+// behave alike, so the classification looks at one representative row per class of equal rows
+// (with the class size where the rule counts rows).
+struct FrontLit {
+    uint32_t* h1;       // [k]   two hashes of a row over all devices
+    uint32_t* h2;       // [k]
+    uint32_t* rep;      // [k]   smallest equal row
+    uint32_t* reps;     // [k]   the representatives, ascending
+    uint32_t* multr;    // [k]   rows in the class of a representative
+    uint32_t* devany;   // [512] device holds something
+    uint32_t* devfull;  // [512] device is at the goal
+};
+__host__ __device__ inline int front_lit_words(int k) { return 5 * k + 1024; }
+__device__ inline FrontLit carve_front(uint32_t* p, int k) {
+    FrontLit X;
+    X.h1 = p; X.h2 = X.h1 + k; X.rep = X.h2 + k; X.reps = X.rep + k; X.multr = X.reps + k;
+    X.devany = X.multr + k; X.devfull = X.devany + 512;
+    return X;
+}
+
+// One instruction against the state, read-only: 0 = invalid step, 2 = valid and the result is the
+// goal, 3 = valid prefix.  C = number of row classes.  All 64 lanes call it with the same arguments.
+template <int MW>
+__device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, const FrontLit& X, int C,
+                            const uint32_t* full, int lane) {
+    const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
+    for (int i = lane; i < ng; i += kWave) { L.gcount[i] = 0; L.gflag[i] = 0; }
+    if (lane == 0) { L.flags[0] = 0; L.flags[1] = 0; L.flags[2] = 0; }
+    __syncthreads();
+    const int items = ng * C;
+    bool bad = false, notfull = false;
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / C, c = it - G * C;
+        const int r = (int)X.reps[c];
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t acc[MW];
+#pragma unroll
+        for (int w = 0; w < MW; ++w) acc[w] = 0;
+        if (red) {
+            bool ne0 = false;
+            for (int p = 0; p < g; ++p) {
+                const uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    uint32_t v = x[w];
+                    any |= v;
+                    bad |= (acc[w] & v) != 0;
+                    acc[w] |= v;
+                }
+                if (p == 0) ne0 = any != 0;
+                else bad |= (any != 0) != ne0;
+            }
+            if (ne0) atomicAdd(&L.gcount[G], X.multr[r]);
+        } else if (op == OP_AG) {
+            int holders = 0;
+            for (int p = 0; p < g; ++p) {
+                const int dev = base + p * s;
+                const uint32_t* x = L.S + (dev * k + r) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) { uint32_t v = x[w]; any |= v; acc[w] |= v; }
+                holders += any != 0;
+                if (c == 0) bad |= X.devany[dev] == 0;
+            }
+            bad |= holders > 1;
+        } else {
+            const uint32_t* root = L.S + (base * k + r) * MW;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) acc[w] = root[w];
+            bool differs = false;
+            for (int p = 1; p < g; ++p) {
+                const uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    uint32_t v = x[w];
+                    bad |= (v & ~acc[w]) != 0;
+                    differs |= v != acc[w];
+                }
+            }
+            if (differs) L.gflag[G] = 1;
+        }
+        // AllReduce, AllGather and Broadcast leave acc on every member
+#pragma unroll
+        for (int w = 0; w < MW; ++w) notfull |= acc[w] != full[w];
+    }
+    if (bad) L.flags[0] = 1;
+    if (notfull) L.flags[2] = 1;
+    // devices the pattern does not touch must already be at the goal
+    if (P.master)
+        for (int d = lane; d < q.R; d += kWave) {
+            const bool part = d % s == 0 && d / gs < ng;
+            if (!part && !X.devfull[d]) L.flags[2] = 1;
+        }
+    __syncthreads();
+    for (int G = lane; G < ng; G += kWave) {
+        const uint32_t cnt = L.gcount[G];
+        if (red) {
+            if (op == OP_RS && cnt % (uint32_t)g != 0) L.flags[0] = 1;
+            if (cnt) L.flags[1] = 1;
+        } else if (op == OP_BC) {
+            if (!L.gflag[G]) L.flags[0] = 1;
+        }
+    }
+    __syncthreads();
+    const bool invalid = L.flags[0] != 0 || (red && L.flags[1] == 0);
+    const bool goal = (op == OP_AR || op == OP_AG || op == OP_BC) && L.flags[2] == 0;
+    __syncthreads();
+    return invalid ? 0 : goal ? 2 : 3;
+}
+
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery* __restrict__ qp,
+                                                                  const FrontEntry* __restrict__ entries, uint32_t n_entries,
+                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
+                                                                  uint32_t surv_cap, FrontCounters* __restrict__ ctr,
+                                                                  uint32_t* __restrict__ gscratch, unsigned long long gwords) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
+    const FrontLit X = carve_front(L.flags + 4, q.k);
+    const int R = q.R, k = q.k, I = q.alphabet;
+    uint32_t full[MW];
+#pragma unroll
+    for (int w = 0; w < MW; ++w) {
+        const int bits = R - 32 * w;
+        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+    }
+    unsigned long long steps = 0, members = 0;
+    for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
+        const unsigned long long digits = entries[e].digits;
+        lit_init<MW>(q, L, lane);
+        for (int t = 0; t < parent_len; ++t) {
+            const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
+            lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
+        }
+        // classes of equal rows: hash every row over all devices, point each row at the first row
+        // with its hash, and keep the pointer only if the two rows really are equal
+        for (int r = lane; r < k; r += kWave) {
+            uint32_t a = 0x811c9dc5u, b = 0x9e3779b9u;
+            for (int d = 0; d < R; ++d) {
+                const uint32_t* x = L.S + (d * k + r) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    const uint32_t v = x[w];
+                    a = (a ^ v) * 0x01000193u;
+                    b = (b + v) * 0x85ebca6bu + (b >> 13);
+                }
+            }
+            X.h1[r] = a; X.h2[r] = b;
+            X.multr[r] = 0;
+        }
+        __syncthreads();
+        for (int r = lane; r < k; r += kWave) {
+            const uint32_t a = X.h1[r], b = X.h2[r];
+            int r0 = 0;
+            while (r0 < r && (X.h1[r0] != a || X.h2[r0] != b)) ++r0;
+            if (r0 != r) {
+                bool same = true;
+                for (int d = 0; d < R; ++d) {
+                    const uint32_t* x = L.S + (d * k + r) * MW;
+                    const uint32_t* y = L.S + (d * k + r0) * MW;
+#pragma unroll
+                    for (int w = 0; w < MW; ++w) same &= x[w] == y[w];
+                }
+                if (!same) r0 = r;
+            }
+            X.rep[r] = (uint32_t)r0;
+        }
+        __syncthreads();
+        int C = 0;
+        for (int r0 = 0; r0 < k; r0 += kWave) {
+            const int r = r0 + lane;
+            const bool is = r < k && X.rep[r] == (uint32_t)r;
+            const unsigned long long bal = __ballot(is);
+            if (is) X.reps[C + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)r;
+            C += __popcll(bal);
+            if (r < k) atomicAdd(&X.multr[X.rep[r]], 1u);
+        }
+        __syncthreads();
+        for (int d = lane; d < R; d += kWave) {
+            bool any = false, all = true;
+            for (int c = 0; c < C; ++c) {
+                const uint32_t* x = L.S + (d * k + (int)X.reps[c]) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) { any |= x[w] != 0; all &= x[w] == full[w]; }
+            }
+            X.devany[d] = any; X.devfull[d] = all;
+        }
+        __syncthreads();
+        for (int a = 0; a < I; ++a) {
+            const uint32_t ins = q.instr_of_digit[a];
+            const DevPattern& P = q.pat[ins >> 3];
+            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
+            ++steps;
+            members += (unsigned long long)(P.n_groups * P.g);
+            if (code != 0 && lane == 0) {
+                const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
+                if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
+                atomicAdd(code == 2 ? &ctr->n_goal : &ctr->n_prefix_literal, 1u);
+            }
+        }
+        __syncthreads();
+    }
+    if (lane == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
+}
+
 template <typename F>
 hipError_t allow_big_lds(F func, size_t bytes) {
     if (bytes <= 48 * 1024) return hipSuccess;
@@ -419,11 +630,16 @@ size_t literal_lds_bytes(int R, int k) {
 size_t literal_scratch_bytes(int R, int k, unsigned* blocks) {
     // states that do not fit in LDS: a fixed number of blocks, each with its own global slice
     LitLayout lay(R, k, mask_words(R));
-    const size_t per = ((size_t)lay.total_words() * 4 + 255) / 256 * 256;
-    unsigned b = 256;
-    while (b > 1 && per * b > ((size_t)4 << 30)) b >>= 1;
+    const size_t per = ((size_t)(lay.total_words() + front_lit_words(k)) * 4 + 255) / 256 * 256;
+    unsigned b = 512;
+    while (b > 1 && per * b > ((size_t)8 << 30)) b >>= 1;
     *blocks = b;
     return per * b;
+}
+size_t front_literal_lds_bytes(int R, int k) {
+    LitLayout lay(R, k, mask_words(R));
+    size_t bytes = (size_t)(lay.total_words() + front_lit_words(k)) * 4;
+    return bytes <= kLdsLimit ? bytes : 0;
 }
 
 hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long long start, unsigned long long count,
@@ -536,6 +752,37 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
         hipLaunchKernelGGL(k_cost_literal_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, \
                            sorted, progs, costs, only_missing);
     switch (mask_words(max_R)) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
+                                         int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
+                                         void* gscratch, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    size_t lds = front_literal_lds_bytes(R, k);
+    unsigned blocks = n < 16384u ? n : 16384u;
+    unsigned long long gwords = 0;
+    if (lds == 0) {
+        if (!gscratch) return hipErrorInvalidValue;
+        unsigned nb = 0;
+        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
+        blocks = nb < n ? nb : n;
+    } else gscratch = nullptr;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_front_classify_literal<MWV>, lds);                                                     \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, entries, n, \
+                           parent_len, surv, surv_cap, ctr, static_cast<uint32_t*>(gscratch), gwords);
+    switch (mask_words(R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
     case 4: P2_LAUNCH(4) break;

@@ -12,11 +12,12 @@ constexpr int kWave = 64;
 // candidate indices and a query has few valid ones next to its candidate space, so the quadratic
 // count is the cheap way to a deterministic ascending order after an unordered atomic append.
 __global__ __launch_bounds__(256) void k_rank_sort(const unsigned long long* __restrict__ valid,
+                                                   const unsigned long long* __restrict__ valid2,
                                                    unsigned long long* __restrict__ sorted,
                                                    const DevPostSeg* __restrict__ segs, int n_segs) {
     __shared__ unsigned long long tile[256];
     const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
-    const unsigned long long* in = valid + seg.in_off;
+    const unsigned long long* in = (seg.in_off >> 63) ? valid2 + (seg.in_off & ~(1ull << 63)) : valid + seg.in_off;
     const uint32_t n = seg.count;
     const uint32_t i = (blockIdx.x - seg.first_block) * 256u + threadIdx.x;
     const unsigned long long key = i < n ? in[i] : 0ull;
@@ -158,10 +159,10 @@ inline unsigned topk_blocks(long long n) {
 
 }  // namespace
 
-hipError_t launch_rank_sort(const unsigned long long* valid, unsigned long long* sorted, const DevPostSeg* segs,
-                            int n_segs, unsigned blocks, hipStream_t stream) {
+hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long long* valid2, unsigned long long* sorted,
+                            const DevPostSeg* segs, int n_segs, unsigned blocks, hipStream_t stream) {
     if (n_segs == 0 || blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_rank_sort, dim3(blocks), dim3(256), 0, stream, valid, sorted, segs, n_segs);
+    hipLaunchKernelGGL(k_rank_sort, dim3(blocks), dim3(256), 0, stream, valid, valid2, sorted, segs, n_segs);
     return hipGetLastError();
 }
 

@@ -41,7 +41,7 @@ def queries_of(cfg_id, B):
     return cfg, workloads.expand(cfg, pls)
 
 
-@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+@pytest.mark.parametrize("engine", [1, 0, 3], ids=["literal", "auto", "frontier"])
 def test_config1_every_query(B, oracle, engine):
     cfg, queries = queries_of(1, B)
     assert len(queries) == 2
@@ -54,10 +54,13 @@ def test_config1_every_query(B, oracle, engine):
         assert_same(res, ora, len(cfg["msg_bytes"]))
         # steps executed == what flat, unpruned evaluation of every index executes
         _, _, steps = oq.eval_indices(q["max_len"], start=0, count=oq.num_candidates(q["max_len"]))
-        assert res["stats"]["steps_executed"] == steps
+        if engine == 3:      # pruned enumeration: only valid prefixes are extended
+            assert res["stats"]["engine"] == 3 and 0 < res["stats"]["steps_executed"] < steps
+        else:
+            assert res["stats"]["steps_executed"] == steps
 
 
-@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+@pytest.mark.parametrize("engine", [1, 0, 3], ids=["literal", "auto", "frontier"])
 def test_config2_every_query(B, oracle, engine):
     cfg, queries = queries_of(2, B)
     assert len(queries) == 10
@@ -101,7 +104,7 @@ def test_single_query_entry_point_and_sizing(B, oracle):
     ([5], [5], [0], 4, 0),
     ([2, 4, 8], [2, 4, 8], [1], 4, 0),
 ])
-@pytest.mark.parametrize("engine", [1, 0], ids=["literal", "auto"])
+@pytest.mark.parametrize("engine", [1, 0, 3], ids=["literal", "auto", "frontier"])
 def test_ragged_shapes_every_placement(B, oracle, card, axes, red, max_len, k, engine):
     bw = [11e9 * (j + 1) for j in range(len(card))]
     alpha = [7e-6 / (j + 1) for j in range(len(card))]
@@ -288,3 +291,69 @@ def test_config4_full_size_sampled(B, oracle):
         probe += [int(ix) + d for ix in progs["index"][pick[:40]] for d in (-1, 1) if int(ix) + d not in listed and 0 <= int(ix) + d < N]
         nvalid, _, _ = oq.eval_indices(q["max_len"], indices=probe, n_threads=8)
         assert nvalid == 0
+
+
+# --------------------------------------------------------------------------- frontier engine (enumeration by size, Sec. 3.5)
+def test_frontier_four_levels_size_limit_six(B, oracle):
+    """Four hierarchy levels, size limit 6: 2.65e11 candidates, far beyond index-by-index evaluation.
+    On 16 devices the oracle's own pruned enumeration gives the whole list (83 920 programs)."""
+    q = dict(card=[2, 2, 2, 2], axes=[16], placement=[[2, 2, 2, 2]], reduce_axes=[0], max_len=6,
+             bw=[10e9, 40e9, 100e9, 300e9], alpha=[20e-6, 10e-6, 5e-6, 2e-6], engine=3)
+    msg = [float(1 << 26)]
+    res = B.p2_synthesize_batch([q], msg)[0]
+    assert res["stats"]["candidates"] == sum(80 ** l for l in range(1, 7))
+    oq, ora = oracle_result(oracle, q, msg)
+    assert len(ora["index"]) == 83920
+    assert_same(res, ora, 1)
+    # pruning: far fewer steps than candidates
+    assert res["stats"]["steps_executed"] < 1e8
+
+
+def test_frontier_matches_flat_engine_on_config3_sample(B):
+    cfg, queries = queries_of(3, B)
+    mine = [q for q in queries if _levels(q) == 3][:4] + [q for q in queries if _levels(q) == 2][:4]
+    flat = B.p2_synthesize_batch([dict(q, engine=0) for q in mine], cfg["msg_bytes"])
+    front = B.p2_synthesize_batch([dict(q, engine=3) for q in mine], cfg["msg_bytes"])
+    for a, b in zip(flat, front):
+        assert a["programs"]["index"].tolist() == b["programs"]["index"].tolist()
+        assert (a["programs"]["instr"] == b["programs"]["instr"]).all()
+        assert np.allclose(a["cost"], b["cost"], rtol=1e-12)
+        assert b["stats"]["engine"] == 3 and b["stats"]["steps_executed"] < a["stats"]["steps_executed"]
+
+
+def test_config5_sampled(B, oracle):
+    """512 devices, size limit 6, random (placement, reduce-axis subset) queries: the frontier engine
+    produces the full lists; the oracle (literal 512 x 512 x 512-bit states, ~0.1 s per instruction)
+    checks sampled outputs one by one: listed programs are valid with the same cost, sampled
+    unlisted indices next to them are invalid.  The first 40 of the 512 queries are run here (they
+    span one to four levels and reduction groups of 2 to 512 devices)."""
+    cfg, queries = queries_of(5, B)
+    assert len(queries) == 512
+    mine = [dict(q, topk=0) for q in queries[:40]]
+    results = B.p2_synthesize_batch(mine, cfg["msg_bytes"])
+    want = {1: 3, 2: 110, 3: None, 4: 83920}
+    rng = np.random.default_rng(5)
+    checked = 0
+    for q, res in zip(mine, results):
+        L = _levels(q)
+        if L == 0:
+            assert res["stats"]["candidates"] == 0
+            continue
+        if want[L] is not None:
+            assert res["stats"]["valid"] == want[L]
+        progs = res["programs"]
+        assert (np.diff(progs["index"].astype(np.int64)) > 0).all()
+        if checked >= 6 or len(progs) == 0:
+            continue
+        checked += 1
+        oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"])
+        for i in rng.choice(len(progs), size=min(3, len(progs)), replace=False):
+            instr = progs["instr"][i][:progs["len"][i]].tolist()
+            assert oq.unrank(q["max_len"], int(progs["index"][i])) == instr
+            ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
+            assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
+            listed = set(progs["index"].tolist())
+            near = [int(progs["index"][i]) + d for d in (-1, 1) if int(progs["index"][i]) + d not in listed]
+            nvalid, _, _ = oq.eval_indices(q["max_len"], indices=near, n_threads=2)
+            assert nvalid == 0
+    assert checked >= 4
