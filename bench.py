@@ -34,7 +34,8 @@ def measured_traffic(kernel):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or
     None when there is none or the kernel source has changed since the counters were taken."""
     path = os.path.join(ROOT, "profiles", "%s_cfg2_traffic.json" % kernel)
-    src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc", "p2_compact.hip" if kernel == "k_eval_compact" else "p2_literal.hip")
+    src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc",
+                       {"k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
     try:
         rec = json.load(open(path))
         if rec["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
@@ -88,7 +89,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..4")
-    ap.add_argument("--engine", type=int, default=0, help="0 auto, 1 literal, 2 compact")
+    ap.add_argument("--engine", type=int, default=0, help="0 auto, 1 literal, 2 compact (state in LDS), 4 small-group")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
@@ -138,7 +139,8 @@ def main():
     reruns = sum(r["stats"]["literal_reruns"] for r in results)
     ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()))
               for q, r in zip(queries, results))
-    kernel = "k_eval_literal" if args.engine == 1 else "k_eval_compact"
+    engines = {r["stats"]["engine"] for r in results}
+    kernel = "k_eval_literal" if engines == {1} else "k_eval_regs" if 4 in engines else "k_eval_compact"
     ms_per_step = dt / args.steps * 1e3
     eval_ms_per_launch = eval_ms / max(launches, 1)
     launches_per_step = launches / args.steps
@@ -156,7 +158,7 @@ def main():
                                   cfg["reduce_sets"], cfg["max_len"], len(msg)),
                    "queries": len(queries), "candidates_per_step": candidates, "valid_per_step": valid,
                    "steps_executed_per_step": steps_exec, "literal_reruns_per_step": reruns,
-                   "engine": {0: "auto", 1: "literal", 2: "compact"}[args.engine]},
+                   "engine": {0: "auto", 1: "literal", 2: "compact", 4: "small-group"}[args.engine]},
         "device_ms_per_step": {"evaluate": eval_ms / args.steps, "order_cost_topk": post_ms / args.steps},
         "evaluate_only_candidates_per_s": candidates / (eval_ms / args.steps * 1e-3),
         "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),

@@ -65,13 +65,18 @@ typedef struct {
 int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes,
                                 int32_t* out, int64_t cap, int64_t* out_count);
 
-/* Evaluation engines.  Both give identical results; they differ in the state they keep. */
-#define P2_ENGINE_AUTO 0      /* compact engine, literal engine for the candidates it cannot hold;
-                                 every candidate index is evaluated on its own                    */
+/* Evaluation engines.  All give identical results; they differ in the state they keep. */
+#define P2_ENGINE_AUTO 0      /* small-group engine where it applies, else the compact engine; the
+                                 literal engine for the candidates they cannot hold; every
+                                 candidate index is evaluated on its own                          */
 #define P2_ENGINE_LITERAL 1   /* R x k masks of R bits per candidate in LDS, one wavefront each   */
 #define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask               */
 #define P2_ENGINE_FRONTIER 3  /* enumeration by program size with pruning (Sec. 3.5): only valid
                                  prefixes are extended; AUTO picks it above 2^30 candidates       */
+#define P2_ENGINE_SMALL 4     /* compact form for reduction groups of at most 32 devices, at most
+                                 32 chunks and patterns whose group size and stride are powers of
+                                 two: every step is computed in registers; P2_EUNSUPPORTED where
+                                 it does not apply                                                */
 
 typedef struct {
     int32_t n_chunks;    /* k of Sec. 3.2; 0 => number of devices (the paper's choice)           */

@@ -102,6 +102,7 @@ struct QueryRun {
     p2::Plan plan;
     int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk (LITERAL or COMPACT)
     bool frontier = false;                // enumeration by size with pruning instead of index by index
+    bool regs = false;                    // compact state in registers (small reduction groups)
     size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
@@ -147,7 +148,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         } else if (want == P2_ENGINE_FRONTIER || (want == P2_ENGINE_AUTO && pl.n_candidates > (1ull << 30))) {
             runs[i].engine = P2_ENGINE_COMPACT;      // its programs are costed like the compact engine's
             runs[i].frontier = true;
-        } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO) {
+        } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO || want == P2_ENGINE_SMALL) {
+            if (want != P2_ENGINE_COMPACT && pl.R <= 32 && pl.k <= 32) {
+                runs[i].regs = true;
+                for (const Pattern& p : pl.patterns) runs[i].regs = runs[i].regs && reg_shape_of(p.g, p.s, p.master) >= 0;
+            }
+            if (want == P2_ENGINE_SMALL && !runs[i].regs)
+                return fail(P2_EUNSUPPORTED, "the small-group engine needs R <= 32, k <= 32 and power-of-two patterns");
             if (cmp_ok) runs[i].engine = P2_ENGINE_COMPACT;
             else if (lit_ok && want == P2_ENGINE_AUTO) runs[i].engine = P2_ENGINE_LITERAL;
             else return fail(P2_EUNSUPPORTED, "state too large for the available engines");
@@ -167,7 +174,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].plan.n_candidates == 0) continue;
         const Plan& pl = runs[i].plan;
-        const int kw = word_class(pl.k), mw = word_class(pl.R);
+        const int kw = runs[i].regs ? 0 : word_class(pl.k), mw = runs[i].regs ? 0 : word_class(pl.R);
         Launch* L = nullptr;
         for (auto& c : launches) if (c.kw == kw && c.mw == mw) L = &c;
         if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0}); L = &launches.back(); }
@@ -175,13 +182,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         L->max_k = std::max(L->max_k, pl.k);
     }
     for (auto& L : launches) {
-        const int lanes = compact_lanes(L.max_R, L.max_k);
+        const int lanes = L.kw == 0 ? 64 : compact_lanes(L.max_R, L.max_k);
         if (lanes == 0) return fail(P2_EUNSUPPORTED, "state too large for the compact engine");
         unsigned long long blocks = 0;
         for (int i = 0; i < n_queries; ++i) {
             const Plan& pl = runs[i].plan;
             if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || pl.n_candidates == 0) continue;
-            if (word_class(pl.k) != L.kw || word_class(pl.R) != L.mw) continue;
+            if ((runs[i].regs ? 0 : word_class(pl.k)) != L.kw || (runs[i].regs ? 0 : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
                 const unsigned long long chunks = (count + lanes - 1) / lanes;
@@ -297,6 +304,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 const Pattern& p = pl.patterns[pi];
                 DevPattern& dp = dq->pat[pi];
                 dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.lo;
+                dp.reg_shape = reg_shape_of(p.g, p.s, p.master);
                 dp.row_begin = row;
                 for (size_t t = 0; t < p.row_level.size(); ++t) {
                     for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
@@ -323,8 +331,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[0], stream));
         for (auto& L : launches) {
             ++eval_launches;
-            P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
-                                       (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
+            if (L.kw == 0)
+                P2_HIP(launch_eval_regs(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
+                                        (int)L.segs.size(), L.blocks, stream));
+            else
+                P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
+                                           (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
@@ -605,7 +617,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             p2_stats& s = stats[i];
             s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
-            s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.engine;
+            s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.regs ? P2_ENGINE_SMALL : r.engine;
         }
     }
     out_offset[n_queries] = w;

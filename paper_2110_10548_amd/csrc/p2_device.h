@@ -21,6 +21,7 @@ struct DevPattern {
     int32_t g, s, master, n_groups;
     int32_t span_level;            // outermost hardware level at which members differ
     int32_t row_begin, row_end;    // bandwidth rows of this pattern (indices into row_ptr/row_level)
+    int32_t reg_shape;             // shape number of the register engine (p2_regs.hip), -1 if it has none
 };
 
 // A run of equally long candidates of one query: blocks [first_block, next segment's first_block)
@@ -106,6 +107,11 @@ hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long lo
 // Compact engine: one launch over the segments of many queries (all with R <= max_R, k <= max_k).
 hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
                                int max_R, int max_k, hipStream_t stream);
+// Register engine (R <= 32, k <= 32, patterns with power-of-two shapes): shape number of a pattern
+// or -1, and the launch over the segments of many queries (64 candidates per wavefront).
+int reg_shape_of(int g, int s, int master);
+hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
+                            hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).
