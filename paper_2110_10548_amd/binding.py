@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("P2_LIB_PATH", os.path.join(HERE, "libp2.so"))
 
 P2_OK, P2_EINVAL, P2_ENOSPC, P2_EUNSUPPORTED, P2_EDEVICE = 0, -1, -2, -3, -4
-ENGINE_AUTO, ENGINE_LITERAL, ENGINE_COMPACT, ENGINE_FRONTIER, ENGINE_SMALL = 0, 1, 2, 3, 4
+ENGINE_AUTO, ENGINE_LITERAL, ENGINE_COMPACT, ENGINE_FRONTIER, ENGINE_SMALL, ENGINE_SHARED = 0, 1, 2, 3, 4, 5
 OPS = ("AllReduce", "ReduceScatter", "AllGather", "Reduce", "Broadcast")
 FORMS = ("InsideGroup", "Parallel", "Master")
 

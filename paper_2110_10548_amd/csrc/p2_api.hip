@@ -102,7 +102,8 @@ struct QueryRun {
     p2::Plan plan;
     int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk (LITERAL or COMPACT)
     bool frontier = false;                // enumeration by size with pruning instead of index by index
-    bool regs = false;                    // compact state in registers (small reduction groups)
+    bool regs = false;                    // small-group engine (steps computed in registers)
+    bool shared = false;                  // ... with the common instructions of a wavefront applied once
     size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
@@ -148,13 +149,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         } else if (want == P2_ENGINE_FRONTIER || (want == P2_ENGINE_AUTO && pl.n_candidates > (1ull << 30))) {
             runs[i].engine = P2_ENGINE_COMPACT;      // its programs are costed like the compact engine's
             runs[i].frontier = true;
-        } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO || want == P2_ENGINE_SMALL) {
+        } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO || want == P2_ENGINE_SMALL || want == P2_ENGINE_SHARED) {
             if (want != P2_ENGINE_COMPACT && pl.R <= 32 && pl.k <= 32) {
                 runs[i].regs = true;
                 for (const Pattern& p : pl.patterns) runs[i].regs = runs[i].regs && reg_shape_of(p.g, p.s, p.master) >= 0;
             }
-            if (want == P2_ENGINE_SMALL && !runs[i].regs)
-                return fail(P2_EUNSUPPORTED, "the small-group engine needs R <= 32, k <= 32 and power-of-two patterns");
+            if ((want == P2_ENGINE_SMALL || want == P2_ENGINE_SHARED) && !runs[i].regs)
+                return fail(P2_EUNSUPPORTED, "the small-group engines need R <= 32, k <= 32 and power-of-two patterns");
+            runs[i].shared = runs[i].regs && want != P2_ENGINE_SMALL;
             if (cmp_ok) runs[i].engine = P2_ENGINE_COMPACT;
             else if (lit_ok && want == P2_ENGINE_AUTO) runs[i].engine = P2_ENGINE_LITERAL;
             else return fail(P2_EUNSUPPORTED, "state too large for the available engines");
@@ -174,7 +176,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].plan.n_candidates == 0) continue;
         const Plan& pl = runs[i].plan;
-        const int kw = runs[i].regs ? 0 : word_class(pl.k), mw = runs[i].regs ? 0 : word_class(pl.R);
+        const int kw = runs[i].regs ? 0 : word_class(pl.k), mw = runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R);
         Launch* L = nullptr;
         for (auto& c : launches) if (c.kw == kw && c.mw == mw) L = &c;
         if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0}); L = &launches.back(); }
@@ -188,7 +190,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (int i = 0; i < n_queries; ++i) {
             const Plan& pl = runs[i].plan;
             if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || pl.n_candidates == 0) continue;
-            if ((runs[i].regs ? 0 : word_class(pl.k)) != L.kw || (runs[i].regs ? 0 : word_class(pl.R)) != L.mw) continue;
+            if ((runs[i].regs ? 0 : word_class(pl.k)) != L.kw ||
+                (runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
                 const unsigned long long chunks = (count + lanes - 1) / lanes;
@@ -333,7 +336,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             ++eval_launches;
             if (L.kw == 0)
                 P2_HIP(launch_eval_regs(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
-                                        (int)L.segs.size(), L.blocks, stream));
+                                        (int)L.segs.size(), L.blocks, L.mw, stream));
             else
                 P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
                                            (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
@@ -617,7 +620,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             p2_stats& s = stats[i];
             s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
-            s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.regs ? P2_ENGINE_SMALL : r.engine;
+            s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.shared ? P2_ENGINE_SHARED : r.regs ? P2_ENGINE_SMALL : r.engine;
         }
     }
     out_offset[n_queries] = w;

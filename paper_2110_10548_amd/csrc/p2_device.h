@@ -111,7 +111,7 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
 // or -1, and the launch over the segments of many queries (64 candidates per wavefront).
 int reg_shape_of(int g, int s, int master);
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
-                            hipStream_t stream);
+                            int shared_prefix, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).

@@ -227,9 +227,11 @@ __device__ __forceinline__ bool first_step(uint2* my, int op, int lg, int ls, ui
     return true;
 }
 
-// The last instruction of a candidate, a different one in every lane: decides from the state in LDS,
+// The last instruction of a candidate, a different one in every lane: decides from the state in LDS
+// (pair of device d at my[d * STRIDE]),
 // without writing it, whether the step is valid and its result the goal.  All arguments are per lane.
 // Members are visited in group-major order, eight loads at a time.
+template <int STRIDE>
 __device__ __forceinline__ int judge_last(const uint2* my, uint32_t shape, int op, int R, uint32_t all_rows, uint32_t all_cols) {
     const int lg = (int)(shape & 15u), ls = (int)((shape >> 4) & 15u);
     const bool master = ((shape >> 8) & 1u) != 0u;
@@ -249,7 +251,7 @@ __device__ __forceinline__ int judge_last(const uint2* my, uint32_t shape, int o
             if (j < n_part) {
                 const int G = j >> lg, p = j & gm1;
                 const int base = master ? (G << (lg + ls)) : (((G >> ls) << (lg + ls)) + (G & sm1));
-                L[b] = my[(base + (p << ls)) * kWaveR];
+                L[b] = my[(base + (p << ls)) * STRIDE];
             }
         }
 #pragma unroll
@@ -300,7 +302,7 @@ __device__ __forceinline__ int judge_last(const uint2* my, uint32_t shape, int o
         uint32_t dif = 0;
         for (int d = 0; d < R; ++d) {
             if ((d & sm1) == 0) continue;
-            const uint2 v = my[d * kWaveR];
+            const uint2 v = my[d * STRIDE];
             dif |= (v.x ^ all_rows) | (v.y ^ all_cols);
         }
         if (dif != 0u) return RSTEP_OK;
@@ -378,7 +380,7 @@ __global__ __launch_bounds__(kWaveR) void k_eval_regs(const DevQuery* __restrict
 #pragma unroll
                         for (int d = 0; d < kRegDevices; ++d) my[d * kWaveR] = make_uint2(all_rows, 1u << d);
                     }
-                    rc = judge_last(my, sshape[ins >> 3], (int)(ins & 7u), R, all_rows, all_cols);
+                    rc = judge_last<kWaveR>(my, sshape[ins >> 3], (int)(ins & 7u), R, all_rows, all_cols);
                     done = true;
                 }
                 while (__any(!done)) {
@@ -439,6 +441,225 @@ __global__ __launch_bounds__(kWaveR) void k_eval_regs(const DevQuery* __restrict
     }
 }
 
+// ---- shared-prefix evaluation ---------------------------------------------------------------------
+// The 64 consecutive candidates of a wavefront differ in their last instruction and fall into a
+// few groups with the same first len-1 instructions.  The state after such a common prefix is the
+// same for the whole group, so it is computed once, by the wavefront as a whole: lane d (and lane
+// d + 32) plays device d, a stage along bit J exchanges pairs with lane d ^ 2^J.  The group's
+// candidates then judge their own last instruction against that state (32 pairs in LDS).  A
+// candidate is still resolved by its own lane; what the lanes of a group would compute
+// identically is computed once.
+
+// One instruction on the wavefront-held state (rv, mv: pair of device lane & 31).  All lanes are
+// active and all arguments but rv, mv are wave-uniform.  Returns RSTEP_INVALID, RSTEP_OK or RSTEP_GIVE_UP.
+__device__ __forceinline__ int wave_step(uint32_t& rv, uint32_t& mv, int dev, int op, int lg, int ls, uint32_t part) {
+    const int gm1 = (1 << lg) - 1;
+    const uint32_t gmask = (uint32_t)gm1 << ls;
+    const bool in = ((part >> dev) & 1u) != 0u;
+    bool bad = false;
+    if (op == OP_AR || op == OP_RS || op == OP_RD) {
+        // same chunks on every member, no contribution reduced twice: union of the masks along each bit
+        for (int J = ls; J < ls + lg; ++J) {
+            const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
+            const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
+            bad |= in && (((rv ^ pr) | (mv & pm)) != 0u);
+            if (in) mv |= pm;
+        }
+        if (__any(bad)) return RSTEP_INVALID;
+        if (!__any(in && rv != 0u)) return RSTEP_INVALID;      // only groups of empty devices: nothing changes
+        if (op == OP_RS) {
+            // the member of rank p keeps the p-th block of the chunks in ascending order
+            const int c = __popc(rv);
+            const int per = c >> lg, p = (dev >> ls) & gm1;
+            bad = in && (c & gm1) != 0;
+            const uint32_t lowbit = rv & (0u - rv);
+            uint32_t nv;
+            if (((rv + lowbit) & rv) == 0u) nv = (((lowbit << per) - lowbit) << (p * per)) & rv;
+            else nv = lowest_bits(rv, (p + 1) * per) ^ lowest_bits(rv, p * per);
+            if (in) rv = nv;
+            if (__any(bad)) return RSTEP_INVALID;
+        } else if (op == OP_RD) {
+            if (in && ((uint32_t)dev & gmask) != 0u) { rv = 0u; mv = 0u; }
+        }
+        return RSTEP_OK;
+    }
+    if (op == OP_AG) {
+        // nobody empty, every chunk held once: union of the chunk sets along each bit
+        if (__any(in && rv == 0u)) return RSTEP_INVALID;
+        bool differs = false;
+        for (int J = ls; J < ls + lg; ++J) {
+            const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
+            const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
+            bad |= in && (rv & pr) != 0u;
+            differs |= in && (mv ^ pm) != 0u;
+            if (in) rv |= pr;
+        }
+        if (__any(bad)) return RSTEP_INVALID;
+        return __any(differs) ? RSTEP_GIVE_UP : RSTEP_OK;      // rows with different column sets leave this form
+    }
+    // Broadcast as a binomial tree from the member with all group bits clear: a member is compared
+    // with the root's pair right before it takes it
+    bool neq = false;
+    for (int J = ls; J < ls + lg; ++J) {
+        const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
+        const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
+        const bool takes = in && ((dev >> J) & 1) != 0 && ((uint32_t)dev & gmask & (~0u << (J + 1))) == 0u;
+        if (takes) {
+            bad |= ((rv & ~pr) | (mv & ~pm)) != 0u;
+            neq |= ((rv ^ pr) | (mv ^ pm)) != 0u;
+            rv = pr;
+            mv = pm;
+        }
+    }
+    if (__any(bad)) return RSTEP_INVALID;
+    // in every group some member must have differed from the root: fold the flags onto the roots' bits
+    uint32_t flags = (uint32_t)__ballot(neq);
+    const uint32_t roots = (uint32_t)__ballot(in && ((uint32_t)dev & gmask) == 0u);
+    for (int J = ls; J < ls + lg; ++J) flags |= flags >> (1u << J);
+    return (~flags & roots) != 0u ? RSTEP_INVALID : RSTEP_OK;
+}
+
+__global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restrict__ queries,
+                                                        const DevSegment* __restrict__ segs, int n_segs) {
+    __shared__ uint2 sh[kRegDevices];                // the group's state: pair of device d
+    __shared__ uint16_t sdig[kMaxPatterns * 5];      // digit -> (pattern id << 3) | op
+    __shared__ uint32_t sshape[kMaxPatterns];        // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
+    __shared__ uint32_t spart[kMaxPatterns];         // pattern id -> bit d set iff device d takes part
+    int a = 0, b = n_segs - 1;                       // last segment whose first_block <= blockIdx.x
+    while (a < b) {
+        const int mid = (a + b + 1) >> 1;
+        if (segs[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
+    }
+    const DevSegment seg = segs[a];
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const int dev = lane & (kRegDevices - 1);
+    for (int i = lane; i < q.n_patterns; i += kWaveR) {
+        const uint32_t shape = (uint32_t)q.pat[i].reg_shape;
+        sshape[i] = shape | ((uint32_t)(q.pat[i].n_groups * q.pat[i].g) << 16);
+        // devices taking part: below R and, in a Master form, those whose bits below the stride are clear
+        uint32_t part = q.R >= 32 ? 0xffffffffu : ((1u << q.R) - 1u);
+        if ((shape >> 8) & 1u) {
+            uint32_t every = 1u;                          // bit d set iff d % 2^ls == 0
+            for (int j = (int)((shape >> 4) & 15u); j < 5; ++j) every |= every << (1u << j);
+            part &= every;
+        }
+        spart[i] = part;
+    }
+    for (int i = lane; i < q.alphabet; i += kWaveR) sdig[i] = q.instr_of_digit[i];
+    __syncthreads();
+    const int len = seg.len;
+    const int R = q.R;
+    const uint32_t I = (uint32_t)q.alphabet;
+    const uint32_t magic = q.magic_alphabet;
+    const uint32_t all_rows = q.k >= 32 ? 0xffffffffu : ((1u << q.k) - 1u);
+    const uint32_t all_cols = R >= 32 ? 0xffffffffu : ((1u << R) - 1u);
+    const unsigned long long prefix_bits = (1ull << (9 * (len - 1))) - 1ull;      // the first len-1 instructions of prog
+    const unsigned long long off0 = (unsigned long long)(blockIdx.x - seg.first_block) * (unsigned long long)(seg.iters * kWaveR);
+    uint32_t d0[P2_MAX_LEN];
+    {
+        unsigned long long rem = off0;
+#pragma unroll
+        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
+            if (t < len) { const unsigned long long nx = rem / I; d0[t] = (uint32_t)(rem - nx * I); rem = nx; }
+            else d0[t] = 0;
+        }
+    }
+    const unsigned long long stem_bits = len >= 2 ? (1ull << (9 * (len - 2))) - 1ull : 0ull;   // the first len-2 instructions
+    bool c_have = false;
+    unsigned long long c_key = 0;
+    uint32_t c_rv = 0, c_mv = 0, c_ran = 0, c_visited = 0;
+    int c_rc = RSTEP_OK;
+    unsigned long long steps = 0, members = 0;
+    for (int it = 0; it < seg.iters; ++it) {
+        const uint32_t add = (uint32_t)(it * kWaveR + lane);
+        const unsigned long long off = off0 + add;
+        const bool alive = off < seg.count;
+        unsigned long long todo = __ballot(alive);
+        if (todo == 0ull) break;
+        unsigned long long prog = 0;
+        uint32_t carry = add;
+#pragma unroll
+        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
+            if (t < len) {
+                const uint32_t v = d0[t] + carry;
+                carry = __umulhi(v, magic);
+                prog = (prog << 9) | sdig[v - carry * I];
+            }
+        }
+        bool give_up = false, goal = false;
+        uint32_t ran = 0, visited = 0;
+        while (todo != 0ull) {
+            // the group of the first candidate not yet served: same first len-1 instructions
+            const int f = __ffsll((long long)todo) - 1;
+            const uint32_t plo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)prog, f);
+            const uint32_t phi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(prog >> 32), f);
+            const unsigned long long pf = ((unsigned long long)phi << 32) | plo;
+            const bool mine = alive && ((prog ^ pf) & prefix_bits) == 0ull;
+            todo &= ~__ballot(mine);
+            // the state after the first len-2 instructions is kept from group to group (and from one
+            // 64-candidate slice to the next): it changes once in alphabet^2 candidates
+            if (!c_have || (pf & stem_bits) != c_key) {
+                c_have = true;
+                c_key = pf & stem_bits;
+                // Sec. 3.5: device i holds column i in every row
+                c_rv = all_rows; c_mv = 1u << dev;
+                c_rc = RSTEP_OK; c_ran = 0; c_visited = 0;
+                for (int t = 0; t < len - 2 && c_rc == RSTEP_OK; ++t) {
+                    const uint32_t ins0 = (uint32_t)(pf >> (9 * t)) & 511u;
+                    const uint32_t shape = sshape[ins0 >> 3];
+                    ++c_ran;
+                    c_visited += shape >> 16;
+                    c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
+                }
+            }
+            uint32_t rv = c_rv, mv = c_mv;
+            int rc = c_rc;
+            uint32_t g_ran = c_ran, g_visited = c_visited;
+            if (rc == RSTEP_OK && len >= 2) {
+                const uint32_t ins0 = (uint32_t)(pf >> (9 * (len - 2))) & 511u;
+                const uint32_t shape = sshape[ins0 >> 3];
+                ++g_ran;
+                g_visited += shape >> 16;
+                rc = wave_step(rv, mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
+            }
+            if (rc == RSTEP_OK) {
+                __syncthreads();
+                if (lane < kRegDevices) sh[lane] = make_uint2(rv, mv);
+                __syncthreads();
+            }
+            if (mine) {
+                ran = g_ran;
+                visited = g_visited;
+                give_up = rc == RSTEP_GIVE_UP;
+                if (rc == RSTEP_OK) {
+                    const uint32_t ins = (uint32_t)(prog >> (9 * (len - 1))) & 511u;
+                    ++ran;
+                    visited += sshape[ins >> 3] >> 16;
+                    goal = judge_last<1>(sh, sshape[ins >> 3], (int)(ins & 7u), R, all_rows, all_cols) == RSTEP_GOAL;
+                }
+            }
+        }
+        if (goal) {
+            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+            if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + off;
+        }
+        if (give_up) {
+            // the literal engine evaluates (and counts) this candidate from its first instruction
+            const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
+            if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + off;
+        } else if (alive) {
+            steps += ran;
+            members += visited;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) { steps += __shfl_xor(steps, o, kWaveR); members += __shfl_xor(members, o, kWaveR); }
+    if (lane == 0 && steps) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
+}
+
 inline int exact_log2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -454,9 +675,10 @@ int reg_shape_of(int g, int s, int master) {
 }
 
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
-                            hipStream_t stream) {
+                            int shared_prefix, hipStream_t stream) {
     if (n_segs == 0 || total_blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
+    if (shared_prefix) hipLaunchKernelGGL(k_eval_shared, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
+    else hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
     return hipGetLastError();
 }
 

@@ -41,7 +41,7 @@ def queries_of(cfg_id, B):
     return cfg, workloads.expand(cfg, pls)
 
 
-@pytest.mark.parametrize("engine", [1, 0, 2, 3], ids=["literal", "auto", "compact", "frontier"])
+@pytest.mark.parametrize("engine", [1, 0, 2, 4, 3], ids=["literal", "auto", "compact", "small", "frontier"])
 def test_config1_every_query(B, oracle, engine):
     cfg, queries = queries_of(1, B)
     assert len(queries) == 2
@@ -60,7 +60,7 @@ def test_config1_every_query(B, oracle, engine):
             assert res["stats"]["steps_executed"] == steps
 
 
-@pytest.mark.parametrize("engine", [1, 0, 2, 3], ids=["literal", "auto", "compact", "frontier"])
+@pytest.mark.parametrize("engine", [1, 0, 2, 4, 3], ids=["literal", "auto", "compact", "small", "frontier"])
 def test_config2_every_query(B, oracle, engine):
     cfg, queries = queries_of(2, B)
     assert len(queries) == 10
@@ -104,33 +104,42 @@ def test_single_query_entry_point_and_sizing(B, oracle):
     ([5], [5], [0], 4, 0),
     ([2, 4, 8], [2, 4, 8], [1], 4, 0),
 ])
-@pytest.mark.parametrize("engine", [1, 0, 2, 3], ids=["literal", "auto", "compact", "frontier"])
+@pytest.mark.parametrize("engine", [1, 0, 2, 4, 3], ids=["literal", "auto", "compact", "small", "frontier"])
 def test_ragged_shapes_every_placement(B, oracle, card, axes, red, max_len, k, engine):
     bw = [11e9 * (j + 1) for j in range(len(card))]
     alpha = [7e-6 / (j + 1) for j in range(len(card))]
     msg = [1.0e6, 3.0e8]
     queries = [dict(card=card, axes=axes, placement=pl, reduce_axes=red, max_len=max_len, bw=bw, alpha=alpha,
                     n_chunks=k, engine=engine) for pl in B.p2_enumerate_placements(card, axes).tolist()]
-    for q, res in zip(queries, B.p2_synthesize_batch(queries, msg)):
+    try:
+        results = B.p2_synthesize_batch(queries, msg)
+    except B.P2Error as e:
+        if engine == 4 and e.code == B.P2_EUNSUPPORTED:
+            pytest.skip("groups that are not bit-fields of the device number: outside the small-group engine")
+        raise
+    for q, res in zip(queries, results):
         _, ora = oracle_result(oracle, q, msg)
         assert_same(res, ora, 2)
 
 
 def test_small_group_engine_selection(B, oracle):
-    """AUTO evaluates reduction groups of at most 32 devices with power-of-two patterns on the small-group
-    engine (engine 4 in the stats), which can also be asked for; it refuses hierarchies it cannot hold."""
+    """AUTO evaluates reduction groups of at most 32 devices with power-of-two patterns on the shared-prefix
+    engine (engine 5 in the stats); it and the small-group engine (4) can also be asked for, and refuse
+    hierarchies they cannot hold."""
     cfg, queries = queries_of(2, B)
-    for q, res in zip(queries, B.p2_synthesize_batch([dict(q, engine=4) for q in queries], cfg["msg_bytes"])):
-        assert res["stats"]["engine"] == 4
-        _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
-        assert_same(res, ora, len(cfg["msg_bytes"]))
+    for engine in (4, 5):
+        for q, res in zip(queries, B.p2_synthesize_batch([dict(q, engine=engine) for q in queries], cfg["msg_bytes"])):
+            assert res["stats"]["engine"] == engine
+            _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+            assert_same(res, ora, len(cfg["msg_bytes"]))
     auto = B.p2_synthesize_batch(queries[:2], cfg["msg_bytes"])
-    assert [r["stats"]["engine"] for r in auto] == [4, 4]
+    assert [r["stats"]["engine"] for r in auto] == [5, 5]
     odd = dict(card=[2, 3], axes=[6], placement=[[2, 3]], reduce_axes=[0], max_len=3, bw=[1e10, 1e11], alpha=[1e-5, 1e-6])
     assert B.p2_synthesize_batch([odd], [1e6])[0]["stats"]["engine"] == 2          # groups of 3: compact engine
-    with pytest.raises(B.P2Error) as ei:
-        B.p2_synthesize_batch([dict(odd, engine=4)], [1e6])
-    assert ei.value.code == B.P2_EUNSUPPORTED
+    for engine in (4, 5):
+        with pytest.raises(B.P2Error) as ei:
+            B.p2_synthesize_batch([dict(odd, engine=engine)], [1e6])
+        assert ei.value.code == B.P2_EUNSUPPORTED
 
 
 @pytest.mark.parametrize("form_mask,op_mask", [(3, 31), (5, 31), (7, 0b01101), (7, 0b11001), (4, 31)])
