@@ -2,11 +2,15 @@
 """Benchmark: one step = one pass of the whole hot path (plan, unrank, semantic evaluation,
 goal test, cost, compaction, ordering, top-k) over every query of the workload.
 
-Prints ONE JSON line.  `value` is candidate programs evaluated per second: every candidate
-index of every query is unranked and simulated from the init state on the GPU (no candidate
-is skipped because it shares a prefix with a dead one).  The roofline object prices the
-evaluation kernel's algorithmic lane-operations against the chip's 32-bit integer VALU rate;
-the cpu_baseline object times the plain CPU oracle on a bounded sample of the same candidates.
+Prints ONE JSON line.  `value` is candidate programs resolved per second (valid or not, cost and
+rank for the valid ones) by the library's default engine.  On this workload that is the
+shared-prefix engine: the instructions that the candidates of a wavefront have in common are
+applied once, so it carries out far fewer instruction applications than there are candidates.
+The `roofline` object therefore prices the lane-operations that kernel really carried out
+against the chip's 32-bit integer VALU rate (a small fraction: the kernel is bound by
+bookkeeping and dependent lane exchanges, not by arithmetic), and `per_candidate_engine` reports
+the engine that evaluates every candidate on its own, lane by lane, with its own roofline
+fraction.  `cpu_baseline` times the plain CPU oracle on a bounded sample of the same candidates.
 """
 import argparse
 import hashlib
@@ -22,12 +26,14 @@ sys.path.insert(0, ROOT)
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
-def algorithmic_lane_ops(stats, n_chunks):
-    """Lane-operations the evaluation must do in the compact state form: every device taking part in
-    an applied instruction has ceil(k/32) chunk-set words and ceil(R/32) mask words, and each word is
-    read, tested against the rule's premise, folded into the group's result and written: 4 each."""
+def algorithmic_lane_ops(stats, n_chunks, key="member_visits"):
+    """Lane-operations of instruction applications in the compact state form: every device taking part
+    in an applied instruction has ceil(k/32) chunk-set words and ceil(R/32) mask words, and each word is
+    read, tested against the rule's premise, folded into the group's result and written: 4 each.
+    key = "member_visits": applications counted per candidate (what evaluating every candidate on its own
+    executes); key = "members_evaluated": applications the engine really carried out."""
     words = -(-n_chunks // 32) + -(-stats["group_size"] // 32)
-    return 4.0 * words * stats["member_visits"]
+    return 4.0 * words * stats[key]
 
 
 def measured_traffic(kernel):
@@ -35,7 +41,7 @@ def measured_traffic(kernel):
     None when there is none or the kernel source has changed since the counters were taken."""
     path = os.path.join(ROOT, "profiles", "%s_cfg2_traffic.json" % kernel)
     src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc",
-                       {"k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
+                       {"k_eval_shared": "p2_regs.hip", "k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
     try:
         rec = json.load(open(path))
         if rec["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
@@ -89,7 +95,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..4")
-    ap.add_argument("--engine", type=int, default=0, help="0 auto, 1 literal, 2 compact (state in LDS), 4 small-group")
+    ap.add_argument("--engine", type=int, default=0,
+                    help="0 auto, 1 literal, 2 compact (state in LDS), 3 frontier, 4 small-group, 5 shared-prefix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
@@ -106,8 +113,6 @@ def main():
         sys.exit(3)
     cfg = workloads.config(args.config)
     queries = workloads.expand(cfg, B.p2_enumerate_placements(cfg["card"], cfg["axes"]))
-    for q in queries:
-        q["engine"] = args.engine
     msg = cfg["msg_bytes"]
     B.p2_set_profiling(True)
 
@@ -117,34 +122,49 @@ def main():
         dst.copy_(src)                            # reads and writes copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    batch = B.Batch(queries, msg)                 # argument marshalling only; every step replans on the host
-    for _ in range(max(args.warmup, 1)):
-        batch.run_raw()
-    torch.cuda.synchronize()
-    eval_ms, post_ms, launches = 0.0, 0.0, 0
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        batch.run_raw()                           # one p2_synthesize_batch call; returns after its stream sync
-        prof = B.p2_get_profile()
-        eval_ms += prof["eval_ms"]
-        post_ms += prof["post_ms"]
-        launches += prof["eval_launches"]
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    results = batch.results()
+    def timed(engine, steps, warmup):
+        """K timed steps of the whole path with one engine: wall time, device times, results."""
+        qs = [dict(q, engine=engine) for q in queries]
+        batch = B.Batch(qs, msg)                  # argument marshalling only; every step replans on the host
+        for _ in range(max(warmup, 1)):
+            batch.run_raw()
+        torch.cuda.synchronize()
+        eval_ms, post_ms, launches = 0.0, 0.0, 0
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            batch.run_raw()                       # one p2_synthesize_batch call; returns after its stream sync
+            prof = B.p2_get_profile()
+            eval_ms += prof["eval_ms"]
+            post_ms += prof["post_ms"]
+            launches += prof["eval_launches"]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return {"dt": dt, "eval_ms": eval_ms, "post_ms": post_ms, "launches": launches, "results": batch.results(), "steps": steps}
 
-    candidates = sum(r["stats"]["candidates"] for r in results)
+    def summarise(run, key):
+        """Throughput and the evaluation kernel's lane-operation rate; key selects which applications count."""
+        results = run["results"]
+        candidates = sum(r["stats"]["candidates"] for r in results)
+        ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()), key)
+                  for q, r in zip(queries, results))
+        launch_ms = run["eval_ms"] / max(run["launches"], 1)
+        ops_per_launch = ops / (run["launches"] / run["steps"])
+        return candidates, ops_per_launch, launch_ms, ops_per_launch / (launch_ms * 1e-3)
+
+    KERNEL = {1: "k_eval_literal", 2: "k_eval_compact", 4: "k_eval_regs", 5: "k_eval_shared", 3: "k_front_classify"}
+    run = timed(args.engine, args.steps, args.warmup)
+    results = run["results"]
+    dt = run["dt"]
+    engines = sorted({r["stats"]["engine"] for r in results})
+    kernel = KERNEL[max(engines, key=lambda e: sum(r["stats"]["candidates"] for r in results if r["stats"]["engine"] == e))]
     steps_exec = sum(r["stats"]["steps_executed"] for r in results)
+    steps_eval = sum(r["stats"]["steps_evaluated"] for r in results)
     valid = sum(r["stats"]["valid"] for r in results)
     reruns = sum(r["stats"]["literal_reruns"] for r in results)
-    ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()))
-              for q, r in zip(queries, results))
-    engines = {r["stats"]["engine"] for r in results}
-    kernel = "k_eval_literal" if engines == {1} else "k_eval_regs" if 4 in engines else "k_eval_compact"
+    candidates, ops_launch, launch_ms, achieved = summarise(run, "members_evaluated")
+    _, flat_ops_launch, _, flat_rate = summarise(run, "member_visits")
     ms_per_step = dt / args.steps * 1e3
-    eval_ms_per_launch = eval_ms / max(launches, 1)
-    launches_per_step = launches / args.steps
-    achieved = (ops / launches_per_step) / (eval_ms_per_launch * 1e-3)     # lane-ops/s of the evaluation kernel
+    eval_ms, post_ms = run["eval_ms"], run["post_ms"]
 
     out = {
         "metric": "candidate programs evaluated/sec (validity+cost)",
@@ -157,17 +177,34 @@ def main():
                                % (cfg["name"], cfg["card"], cfg["axes"], len(queries) // max(len(cfg["reduce_sets"]) * len(cfg["n_chunks"]), 1),
                                   cfg["reduce_sets"], cfg["max_len"], len(msg)),
                    "queries": len(queries), "candidates_per_step": candidates, "valid_per_step": valid,
-                   "steps_executed_per_step": steps_exec, "literal_reruns_per_step": reruns,
-                   "engine": {0: "auto", 1: "literal", 2: "compact", 4: "small-group"}[args.engine]},
+                   "steps_executed_per_step": steps_exec, "steps_evaluated_per_step": steps_eval,
+                   "literal_reruns_per_step": reruns,
+                   "engine": {0: "auto", 1: "literal", 2: "compact", 3: "frontier", 4: "small-group", 5: "shared-prefix"}[args.engine],
+                   "engines_used": engines},
         "device_ms_per_step": {"evaluate": eval_ms / args.steps, "order_cost_topk": post_ms / args.steps},
         "evaluate_only_candidates_per_s": candidates / (eval_ms / args.steps * 1e-3),
         "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),
+        "steps_evaluated_per_s": steps_eval / (eval_ms / args.steps * 1e-3),
+        # lane-operations of the instruction applications the kernel carried out (shared ones once)
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
                      "frac": achieved / ALU_PEAK_LANE_OPS,
                      "traffic": measured_traffic(kernel) if args.config == 2 else None,
                      "kernel": kernel,
-                     "launch_ms": eval_ms_per_launch, "algorithmic_lane_ops_per_launch": ops / launches_per_step},
+                     "launch_ms": launch_ms, "algorithmic_lane_ops_per_launch": ops_launch,
+                     # the same launch priced with every candidate's applications counted on their own
+                     "per_candidate_lane_ops_per_launch": flat_ops_launch,
+                     "per_candidate_equivalent_frac": flat_rate / ALU_PEAK_LANE_OPS},
     }
+    if 5 in engines and args.engine == 0:
+        # the engine that evaluates every candidate on its own, timed the same way (fewer steps)
+        own = timed(4, max(args.steps // 2, 2), 2)
+        c2, ops2, ms2, rate2 = summarise(own, "member_visits")
+        out["per_candidate_engine"] = {
+            "engine": "small-group", "kernel": "k_eval_regs", "value": c2 / (own["dt"] / own["steps"]), "unit": "candidates/s",
+            "ms_per_step": own["dt"] / own["steps"] * 1e3, "steps": own["steps"],
+            "roofline": {"bound": "alu", "achieved": rate2 / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+                         "frac": rate2 / ALU_PEAK_LANE_OPS, "launch_ms": ms2, "algorithmic_lane_ops_per_launch": ops2,
+                         "traffic": measured_traffic("k_eval_regs") if args.config == 2 else None}}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(queries)
     print(json.dumps(out))

@@ -107,7 +107,9 @@ typedef struct {
 /* Counters of one query (all optional outputs). */
 typedef struct {
     uint64_t candidates;       /* programs of length <= max_len over the alphabet, all evaluated  */
-    uint64_t steps_executed;   /* instructions applied (a candidate stops at its first bad step)  */
+    uint64_t steps_executed;   /* instructions applied, counted per candidate (a candidate stops at
+                                  its first bad step): what evaluating every candidate on its own
+                                  executes, whichever engine ran                                  */
     uint64_t literal_reruns;   /* candidates the compact engine handed to the literal engine      */
     uint64_t member_visits;    /* sum over applied instructions of the devices taking part in them */
     int64_t valid;             /* valid programs found                                            */
@@ -115,6 +117,11 @@ typedef struct {
     int32_t n_patterns;        /* canonical (slice, form) patterns                                */
     int32_t alphabet;          /* instructions = patterns x enabled ops                           */
     int32_t engine;            /* engine that evaluated the bulk of the candidates                */
+    uint64_t steps_evaluated;  /* instruction applications the engine carried out; an application
+                                  shared by several candidates counts once (P2_ENGINE_SHARED: the
+                                  candidates handed to the literal engine not included), so it is
+                                  at most steps_executed                                          */
+    uint64_t members_evaluated;/* devices taking part in those applications, summed               */
 } p2_stats;
 
 /* Sec. 3.5 on one placement: evaluate every program of length <= max_len.  A program is valid

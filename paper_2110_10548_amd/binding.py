@@ -41,7 +41,7 @@ class p2_program(C.Structure):
 class p2_stats(C.Structure):
     _fields_ = [("candidates", C.c_uint64), ("steps_executed", C.c_uint64), ("literal_reruns", C.c_uint64),
                 ("member_visits", C.c_uint64), ("valid", C.c_int64), ("group_size", C.c_int32), ("n_patterns", C.c_int32), ("alphabet", C.c_int32),
-                ("engine", C.c_int32)]
+                ("engine", C.c_int32), ("steps_evaluated", C.c_uint64), ("members_evaluated", C.c_uint64)]
 
 
 class p2_profile(C.Structure):

@@ -111,6 +111,7 @@ struct QueryRun {
     size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
     uint32_t n_valid = 0, n_rerun = 0;
     unsigned long long steps = 0, members = 0;
+    unsigned long long evaluated = 0, evaluated_members = 0;   // instruction applications carried out where they differ from steps
     size_t out_first = 0;                 // first row of this query in the sorted/prog/cost buffers
 };
 
@@ -194,9 +195,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 (runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
-                const unsigned long long chunks = (count + lanes - 1) / lanes;
+                const bool by_group = L.kw == 0 && L.mw == 1;      // shared-prefix kernel: an item is a run of groups
+                const unsigned long long chunks = by_group ? count / (unsigned long long)pl.alphabet : (count + lanes - 1) / lanes;
                 unsigned long long iters = (chunks + 4095) / 4096;
                 iters = std::min<unsigned long long>(std::max<unsigned long long>(iters, 1), 64);
+                // that kernel strides a fixed grid over the items: small items balance its load
+                if (by_group) iters = std::min<unsigned long long>(std::max<unsigned long long>(chunks, 1), 4);
                 DevSegment sg;
                 sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len; sg.iters = (int)iters;
                 sg.first_index = pl.base[len]; sg.count = count;
@@ -390,6 +394,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun;
             r.steps = 0; r.members = 0;
             for (int t = 0; t < kCounterStripes; ++t) { r.steps += hc[i].steps[t]; r.members += hc[i].members[t]; }
+            r.evaluated = hc[i].evaluated; r.evaluated_members = hc[i].evaluated_members;
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);
@@ -619,6 +624,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (stats) {
             p2_stats& s = stats[i];
             s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
+            s.steps_evaluated = r.shared ? r.evaluated : r.steps;
+            s.members_evaluated = r.shared ? r.evaluated_members : r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
             s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.shared ? P2_ENGINE_SHARED : r.regs ? P2_ENGINE_SMALL : r.engine;
         }

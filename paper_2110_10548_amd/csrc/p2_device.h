@@ -63,6 +63,8 @@ struct DevCounters {
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
     uint32_t nan_seen;
     uint32_t pad;
+    unsigned long long evaluated;                  // instruction applications carried out, where they differ from `steps`
+    unsigned long long evaluated_members;          // devices taking part in those, summed
     unsigned long long steps[kCounterStripes];     // instructions applied
     unsigned long long members[kCounterStripes];   // devices taking part in those instructions, summed
 };

@@ -519,144 +519,205 @@ __device__ __forceinline__ int wave_step(uint32_t& rv, uint32_t& mv, int dev, in
     return (~flags & roots) != 0u ? RSTEP_INVALID : RSTEP_OK;
 }
 
+// Candidates of one length are numbered prefix * alphabet + last instruction, so the `alphabet`
+// candidates of a group (same first len-1 instructions) are consecutive; lane a holds the one whose
+// last instruction has digit a (a + 64 in a second pass for alphabets above 64).  A work item is
+// seg.iters consecutive groups; a block walks the items blockIdx.x, blockIdx.x + gridDim.x, ..., so the
+// groups under one valid stem, which are the expensive ones, are spread over many blocks.
+// The state after the first len-2 instructions (the stem) changes once in `alphabet` groups and is
+// kept; a group whose stem or prefix is invalid is settled for all its candidates at once.
 __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restrict__ queries,
-                                                        const DevSegment* __restrict__ segs, int n_segs) {
-    __shared__ uint2 sh[kRegDevices];                // the group's state: pair of device d
+                                                        const DevSegment* __restrict__ segs, int n_segs,
+                                                        uint32_t total_items) {
     __shared__ uint16_t sdig[kMaxPatterns * 5];      // digit -> (pattern id << 3) | op
     __shared__ uint32_t sshape[kMaxPatterns];        // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
     __shared__ uint32_t spart[kMaxPatterns];         // pattern id -> bit d set iff device d takes part
-    int a = 0, b = n_segs - 1;                       // last segment whose first_block <= blockIdx.x
-    while (a < b) {
-        const int mid = (a + b + 1) >> 1;
-        if (segs[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
-    }
-    const DevSegment seg = segs[a];
-    const DevQuery& q = queries[seg.query];
     const int lane = threadIdx.x;
     const int dev = lane & (kRegDevices - 1);
-    for (int i = lane; i < q.n_patterns; i += kWaveR) {
-        const uint32_t shape = (uint32_t)q.pat[i].reg_shape;
-        sshape[i] = shape | ((uint32_t)(q.pat[i].n_groups * q.pat[i].g) << 16);
-        // devices taking part: below R and, in a Master form, those whose bits below the stride are clear
-        uint32_t part = q.R >= 32 ? 0xffffffffu : ((1u << q.R) - 1u);
-        if ((shape >> 8) & 1u) {
-            uint32_t every = 1u;                          // bit d set iff d % 2^ls == 0
-            for (int j = (int)((shape >> 4) & 15u); j < 5; ++j) every |= every << (1u << j);
-            part &= every;
+    DevSegment seg;
+    seg.first_block = 0; seg.query = -1; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
+    uint32_t next_first = 0;                         // first item of the next segment
+    const DevQuery* qp = nullptr;
+    int len = 1, R = 1;
+    uint32_t I = 1, all_rows = 0, all_cols = 0;
+    uint32_t sum_part = 0;                           // participating devices summed over the alphabet
+    unsigned long long n_groups_seg = 0;             // groups of the segment
+    unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block for the current query
+    for (uint32_t item = blockIdx.x; item < total_items; item += gridDim.x) {
+        if (qp == nullptr || item >= next_first || item < seg.first_block) {
+            int a = 0, b = n_segs - 1;               // last segment whose first_block <= item
+            while (a < b) {
+                const int mid = (a + b + 1) >> 1;
+                if (segs[mid].first_block <= item) a = mid; else b = mid - 1;
+            }
+            const int old_query = seg.query;
+            seg = segs[a];
+            next_first = a + 1 < n_segs ? segs[a + 1].first_block : 0xffffffffu;
+            if (seg.query != old_query) {
+                // hand the finished query its counts, then load the new query's tables
+                if (lane == 0 && (steps | evaluated) != 0ull) {
+                    atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
+                    atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
+                    atomicAdd(&qp->counters->evaluated, evaluated);
+                    atomicAdd(&qp->counters->evaluated_members, evaluated_members);
+                }
+                steps = 0; members = 0; evaluated = 0; evaluated_members = 0;
+                qp = queries + seg.query;
+                __syncthreads();
+                for (int i = lane; i < qp->n_patterns; i += kWaveR) {
+                    const uint32_t shape = (uint32_t)qp->pat[i].reg_shape;
+                    sshape[i] = shape | ((uint32_t)(qp->pat[i].n_groups * qp->pat[i].g) << 16);
+                    // devices taking part: below R and, in a Master form, those whose bits below the stride are clear
+                    uint32_t part = qp->R >= 32 ? 0xffffffffu : ((1u << qp->R) - 1u);
+                    if ((shape >> 8) & 1u) {
+                        uint32_t every = 1u;                          // bit d set iff d % 2^ls == 0
+                        for (int j = (int)((shape >> 4) & 15u); j < 5; ++j) every |= every << (1u << j);
+                        part &= every;
+                    }
+                    spart[i] = part;
+                }
+                for (int i = lane; i < qp->alphabet; i += kWaveR) sdig[i] = qp->instr_of_digit[i];
+                __syncthreads();
+                R = qp->R;
+                I = (uint32_t)qp->alphabet;
+                all_rows = qp->k >= 32 ? 0xffffffffu : ((1u << qp->k) - 1u);
+                all_cols = R >= 32 ? 0xffffffffu : ((1u << R) - 1u);
+                sum_part = 0;
+                for (uint32_t d = 0; d < I; ++d) sum_part += sshape[sdig[d] >> 3] >> 16;
+            }
+            len = seg.len;
+            n_groups_seg = seg.count / I;
         }
-        spart[i] = part;
-    }
-    for (int i = lane; i < q.alphabet; i += kWaveR) sdig[i] = q.instr_of_digit[i];
-    __syncthreads();
-    const int len = seg.len;
-    const int R = q.R;
-    const uint32_t I = (uint32_t)q.alphabet;
-    const uint32_t magic = q.magic_alphabet;
-    const uint32_t all_rows = q.k >= 32 ? 0xffffffffu : ((1u << q.k) - 1u);
-    const uint32_t all_cols = R >= 32 ? 0xffffffffu : ((1u << R) - 1u);
-    const unsigned long long prefix_bits = (1ull << (9 * (len - 1))) - 1ull;      // the first len-1 instructions of prog
-    const unsigned long long off0 = (unsigned long long)(blockIdx.x - seg.first_block) * (unsigned long long)(seg.iters * kWaveR);
-    uint32_t d0[P2_MAX_LEN];
-    {
-        unsigned long long rem = off0;
+        const DevQuery& q = *qp;
+        // the item's first group: the stem's digits (instruction t at dg[t], t < len-2) and the digit of
+        // the prefix's last instruction
+        const unsigned long long P0 = (unsigned long long)(item - seg.first_block) * (unsigned long long)seg.iters;
+        const int n_here = (int)(n_groups_seg - P0 < (unsigned long long)seg.iters ? n_groups_seg - P0 : (unsigned long long)seg.iters);
+        uint32_t dg[P2_MAX_LEN];
+        uint32_t dlast = 0;
+        {
+            unsigned long long rem = P0;
+            if (len >= 2) {
+                const unsigned long long nx = rem < (1ull << 32) ? (unsigned long long)((uint32_t)rem / I) : rem / I;
+                dlast = (uint32_t)(rem - nx * I);
+                rem = nx;
+            }
 #pragma unroll
-        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
-            if (t < len) { const unsigned long long nx = rem / I; d0[t] = (uint32_t)(rem - nx * I); rem = nx; }
-            else d0[t] = 0;
-        }
-    }
-    const unsigned long long stem_bits = len >= 2 ? (1ull << (9 * (len - 2))) - 1ull : 0ull;   // the first len-2 instructions
-    bool c_have = false;
-    unsigned long long c_key = 0;
-    uint32_t c_rv = 0, c_mv = 0, c_ran = 0, c_visited = 0;
-    int c_rc = RSTEP_OK;
-    unsigned long long steps = 0, members = 0;
-    for (int it = 0; it < seg.iters; ++it) {
-        const uint32_t add = (uint32_t)(it * kWaveR + lane);
-        const unsigned long long off = off0 + add;
-        const bool alive = off < seg.count;
-        unsigned long long todo = __ballot(alive);
-        if (todo == 0ull) break;
-        unsigned long long prog = 0;
-        uint32_t carry = add;
-#pragma unroll
-        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
-            if (t < len) {
-                const uint32_t v = d0[t] + carry;
-                carry = __umulhi(v, magic);
-                prog = (prog << 9) | sdig[v - carry * I];
+            for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
+                if (t < len - 2) {
+                    const unsigned long long nx = rem < (1ull << 32) ? (unsigned long long)((uint32_t)rem / I) : rem / I;
+                    dg[t] = (uint32_t)(rem - nx * I);
+                    rem = nx;
+                } else dg[t] = 0;
             }
         }
-        bool give_up = false, goal = false;
-        uint32_t ran = 0, visited = 0;
-        while (todo != 0ull) {
-            // the group of the first candidate not yet served: same first len-1 instructions
-            const int f = __ffsll((long long)todo) - 1;
-            const uint32_t plo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)prog, f);
-            const uint32_t phi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(prog >> 32), f);
-            const unsigned long long pf = ((unsigned long long)phi << 32) | plo;
-            const bool mine = alive && ((prog ^ pf) & prefix_bits) == 0ull;
-            todo &= ~__ballot(mine);
-            // the state after the first len-2 instructions is kept from group to group (and from one
-            // 64-candidate slice to the next): it changes once in alphabet^2 candidates
-            if (!c_have || (pf & stem_bits) != c_key) {
+        unsigned long long first_off = P0 * I;       // offset of the group's first candidate in the segment
+        uint32_t item_steps = 0, item_members = 0;   // an item is at most 64 groups: these stay below 2^32
+        bool c_have = false;                         // stem state: after the first len-2 instructions
+        uint32_t c_rv = 0, c_mv = 0, c_ran = 0, c_visited = 0;
+        int c_rc = RSTEP_OK;
+        for (int gi = 0; gi < n_here; ++gi) {
+            if (!c_have) {
                 c_have = true;
-                c_key = pf & stem_bits;
                 // Sec. 3.5: device i holds column i in every row
                 c_rv = all_rows; c_mv = 1u << dev;
                 c_rc = RSTEP_OK; c_ran = 0; c_visited = 0;
-                for (int t = 0; t < len - 2 && c_rc == RSTEP_OK; ++t) {
-                    const uint32_t ins0 = (uint32_t)(pf >> (9 * t)) & 511u;
-                    const uint32_t shape = sshape[ins0 >> 3];
-                    ++c_ran;
-                    c_visited += shape >> 16;
-                    c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
+#pragma unroll
+                for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
+                    if (t < len - 2 && c_rc == RSTEP_OK) {
+                        const uint32_t ins0 = sdig[dg[t]];
+                        const uint32_t shape = sshape[ins0 >> 3];
+                        ++c_ran;
+                        c_visited += shape >> 16;
+                        ++evaluated; evaluated_members += shape >> 16;
+                        c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
+                    }
                 }
             }
             uint32_t rv = c_rv, mv = c_mv;
             int rc = c_rc;
             uint32_t g_ran = c_ran, g_visited = c_visited;
             if (rc == RSTEP_OK && len >= 2) {
-                const uint32_t ins0 = (uint32_t)(pf >> (9 * (len - 2))) & 511u;
+                const uint32_t ins0 = sdig[dlast];
                 const uint32_t shape = sshape[ins0 >> 3];
                 ++g_ran;
                 g_visited += shape >> 16;
+                ++evaluated; evaluated_members += shape >> 16;
                 rc = wave_step(rv, mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
             }
-            if (rc == RSTEP_OK) {
-                __syncthreads();
-                if (lane < kRegDevices) sh[lane] = make_uint2(rv, mv);
-                __syncthreads();
+            if (rc == RSTEP_GIVE_UP) {
+                // the literal engine evaluates (and counts) these candidates from their first instruction
+                for (uint32_t a0 = 0; a0 < I; a0 += kWaveR) {
+                    const uint32_t a = a0 + (uint32_t)lane;
+                    if (a < I) {
+                        const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
+                        if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + first_off + a;
+                    }
+                }
+            } else if (rc == RSTEP_INVALID) {
+                item_steps += I * g_ran;
+                item_members += I * g_visited;
+            } else {
+                // every candidate applies its last instruction
+                item_steps += I * (g_ran + 1u);
+                item_members += I * g_visited + sum_part;
+                // The last instruction matters only through the goal test.  The goal can only come from an
+                // AllReduce on devices that all hold every chunk, from an AllGather on devices whose chunks
+                // all carry every column, or from a Broadcast whose roots (device 0 is one in every pattern)
+                // are at the goal already; ReduceScatter and Reduce leave members short of chunks.
+                // Candidates that pass this test apply their last instruction to a copy of the group's
+                // state, one after the other, again with the wavefront's lanes as devices.
+                const bool rows_full = !__any(dev < R && rv != all_rows);
+                const bool cols_full = !__any(dev < R && mv != all_cols);
+                const bool root_done = (uint32_t)__builtin_amdgcn_readlane((int)(rv ^ all_rows), 0) == 0u &&
+                                       (uint32_t)__builtin_amdgcn_readlane((int)(mv ^ all_cols), 0) == 0u;
+                if (rows_full || cols_full || root_done) {
+                    for (uint32_t a0 = 0; a0 < I; a0 += kWaveR) {
+                        const uint32_t a = a0 + (uint32_t)lane;
+                        const uint32_t my_ins = a < I ? sdig[a] : 0u;
+                        const int my_op = (int)(my_ins & 7u);
+                        const bool may = a < I && ((my_op == OP_AR && rows_full) || (my_op == OP_AG && cols_full) || (my_op == OP_BC && root_done));
+                        bool goal = false;
+                        for (unsigned long long left = __ballot(may); left != 0ull; left &= left - 1ull) {
+                            const int l = __ffsll((long long)left) - 1;
+                            const uint32_t ins0 = sdig[a0 + (uint32_t)l];
+                            const uint32_t shape = sshape[ins0 >> 3];
+                            uint32_t r2 = rv, m2 = mv;
+                            ++evaluated; evaluated_members += shape >> 16;
+                            const int rc2 = wave_step(r2, m2, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
+                            // goal: every device holds every chunk with the columns of the whole group
+                            const bool reached = rc2 == RSTEP_OK && !__any(dev < R && ((r2 ^ all_rows) | (m2 ^ all_cols)) != 0u);
+                            if (lane == l) goal = reached;
+                        }
+                        if (goal) {
+                            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+                            if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + first_off + a;
+                        }
+                    }
+                }
             }
-            if (mine) {
-                ran = g_ran;
-                visited = g_visited;
-                give_up = rc == RSTEP_GIVE_UP;
-                if (rc == RSTEP_OK) {
-                    const uint32_t ins = (uint32_t)(prog >> (9 * (len - 1))) & 511u;
-                    ++ran;
-                    visited += sshape[ins >> 3] >> 16;
-                    goal = judge_last<1>(sh, sshape[ins >> 3], (int)(ins & 7u), R, all_rows, all_cols) == RSTEP_GOAL;
+            // next group: the prefix's last digit goes up; when it wraps the stem changes
+            first_off += I;
+            if (++dlast == I) {
+                dlast = 0;
+                c_have = false;
+                bool carry = true;
+#pragma unroll
+                for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
+                    if (t < len - 2 && carry) {
+                        if (++dg[t] == I) dg[t] = 0; else carry = false;
+                    }
                 }
             }
         }
-        if (goal) {
-            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
-            if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + off;
-        }
-        if (give_up) {
-            // the literal engine evaluates (and counts) this candidate from its first instruction
-            const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
-            if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + off;
-        } else if (alive) {
-            steps += ran;
-            members += visited;
-        }
+        steps += item_steps;
+        members += item_members;
     }
-    for (int o = 32; o > 0; o >>= 1) { steps += __shfl_xor(steps, o, kWaveR); members += __shfl_xor(members, o, kWaveR); }
-    if (lane == 0 && steps) {
-        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
-        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    if (lane == 0 && (steps | evaluated) != 0ull) {
+        atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
+        atomicAdd(&qp->counters->evaluated, evaluated);
+        atomicAdd(&qp->counters->evaluated_members, evaluated_members);
     }
 }
 
@@ -677,7 +738,11 @@ int reg_shape_of(int g, int s, int master) {
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
                             int shared_prefix, hipStream_t stream) {
     if (n_segs == 0 || total_blocks == 0) return hipSuccess;
-    if (shared_prefix) hipLaunchKernelGGL(k_eval_shared, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
+    if (shared_prefix) {
+        // 16 wavefronts per compute unit, or one block per item if there are fewer
+        const unsigned grid = total_blocks < 4096u ? total_blocks : 4096u;
+        hipLaunchKernelGGL(k_eval_shared, dim3(grid), dim3(kWaveR), 0, stream, queries, segs, n_segs, (uint32_t)total_blocks);
+    }
     else hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
     return hipGetLastError();
 }
