@@ -171,7 +171,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& r : runs) { r.off_query = off; off += sizeof(DevQuery); }      // one contiguous DevQuery array
     off = align_up(off, 256);
     // compact-engine queries are launched together, one launch per (chunk words, mask words) class
-    struct Launch { int kw, mw, max_R, max_k; std::vector<DevSegment> segs; unsigned blocks; size_t off_segs; };
+    struct Launch {
+        int kw, mw, max_R, max_k; std::vector<DevSegment> segs; unsigned blocks; size_t off_segs;
+        std::vector<DevShare> shares; unsigned grid = 0; size_t off_shares = 0;     // shared-prefix kernel only
+    };
     std::vector<Launch> launches;
     auto word_class = [](int bits) { int w = (bits + 31) / 32; return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16; };
     for (int i = 0; i < n_queries; ++i) {
@@ -180,7 +183,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         const int kw = runs[i].regs ? 0 : word_class(pl.k), mw = runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R);
         Launch* L = nullptr;
         for (auto& c : launches) if (c.kw == kw && c.mw == mw) L = &c;
-        if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0}); L = &launches.back(); }
+        if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0, {}, 0u, 0}); L = &launches.back(); }
         L->max_R = std::max(L->max_R, pl.R);
         L->max_k = std::max(L->max_k, pl.k);
     }
@@ -195,23 +198,50 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 (runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
-                const bool by_group = L.kw == 0 && L.mw == 1;      // shared-prefix kernel: an item is a run of groups
-                const unsigned long long chunks = by_group ? count / (unsigned long long)pl.alphabet : (count + lanes - 1) / lanes;
-                unsigned long long iters = (chunks + 4095) / 4096;
-                iters = std::min<unsigned long long>(std::max<unsigned long long>(iters, 1), 64);
-                // that kernel strides a fixed grid over the items: small items balance its load
-                if (by_group) iters = std::min<unsigned long long>(std::max<unsigned long long>(chunks, 1), 4);
                 DevSegment sg;
-                sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len; sg.iters = (int)iters;
+                sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len;
                 sg.first_index = pl.base[len]; sg.count = count;
+                if (L.kw == 0 && L.mw == 1) {
+                    // shared-prefix kernel: an item is a quarter of the groups under one stem (the first
+                    // len-2 instructions); small items balance the load of its fixed grid
+                    const unsigned long long I = (unsigned long long)pl.alphabet;
+                    const unsigned long long per_item = len >= 2 ? (I + 3) / 4 : 1;
+                    const unsigned long long items_per_stem = len >= 2 ? (I + per_item - 1) / per_item : 1;
+                    sg.iters = (int)per_item;
+                    blocks += len >= 2 ? (count / (I * I)) * items_per_stem : 1;
+                } else {
+                    const unsigned long long chunks = (count + lanes - 1) / lanes;
+                    unsigned long long iters = (chunks + 4095) / 4096;
+                    iters = std::min<unsigned long long>(std::max<unsigned long long>(iters, 1), 64);
+                    sg.iters = (int)iters;
+                    blocks += (chunks + iters - 1) / iters;
+                }
                 L.segs.push_back(sg);
-                blocks += (chunks + iters - 1) / iters;
                 if (blocks > 0x7fffffffull) return fail(P2_EUNSUPPORTED, "too many candidates for one launch");
             }
         }
         L.blocks = (unsigned)blocks;
         L.off_segs = off;
         off += align_up(sizeof(DevSegment) * L.segs.size(), 256);
+        if (L.kw == 0 && L.mw == 1) {
+            // divide a grid of about 4096 blocks (16 wavefronts per compute unit) among the queries by their items
+            const unsigned long long target = 4096;
+            for (size_t a = 0; a < L.segs.size();) {
+                size_t b = a;
+                while (b < L.segs.size() && L.segs[b].query == L.segs[a].query) ++b;
+                DevShare shq;
+                shq.first_item = L.segs[a].first_block;
+                shq.n_items = (b < L.segs.size() ? L.segs[b].first_block : L.blocks) - shq.first_item;
+                unsigned long long nb = (target * shq.n_items + L.blocks / 2) / std::max(1u, L.blocks);
+                nb = std::min<unsigned long long>(std::max<unsigned long long>(nb, 1), std::max(1u, shq.n_items));
+                shq.first_block = L.grid; shq.n_blocks = (uint32_t)nb;
+                L.grid += (unsigned)nb;
+                L.shares.push_back(shq);
+                a = b;
+            }
+            L.off_shares = off;
+            off += align_up(sizeof(DevShare) * L.shares.size(), 256);
+        }
     }
     const size_t off_msg = off;
     off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
@@ -320,6 +350,20 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 }
                 dp.row_end = row;
             }
+            dq->reg_sum_part = 0;
+            for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
+                const Pattern& p = pl.patterns[pi];
+                const int shape = reg_shape_of(p.g, p.s, p.master);
+                uint32_t part = pl.R >= 32 ? 0xffffffffu : ((1u << pl.R) - 1u);
+                if (p.master) {
+                    uint32_t every = 0;                       // bit d set iff d % s == 0
+                    for (int d = 0; d < 32; d += p.s) every |= 1u << d;
+                    part &= every;
+                }
+                dq->reg_shape[pi] = (shape < 0 ? 0u : (uint32_t)shape) | ((uint32_t)(p.n_groups * p.g) << 16);
+                dq->reg_part[pi] = part;
+                dq->reg_sum_part += (uint32_t)(p.n_groups * p.g) * (uint32_t)pl.n_ops;
+            }
             dq->row_ptr = reinterpret_cast<const int32_t*>(db + r.off_rowptr);
             dq->row_level = reinterpret_cast<const int32_t*>(db + r.off_rowlevel);
             dq->entries = reinterpret_cast<const uint32_t*>(db + r.off_entries);
@@ -330,7 +374,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             dq->counters = static_cast<DevCounters*>(C.counters.p) + i;
         }
         for (auto& L : launches)
+        {
             std::memcpy(hb + L.off_segs, L.segs.data(), sizeof(DevSegment) * L.segs.size());
+            if (!L.shares.empty()) std::memcpy(hb + L.off_shares, L.shares.data(), sizeof(DevShare) * L.shares.size());
+        }
         P2_HIP(hipMemcpyAsync(db, hb, blob_bytes, hipMemcpyHostToDevice, stream));
         P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters) * (size_t)n_queries, stream));
         // ---- evaluate every candidate of every query
@@ -338,9 +385,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[0], stream));
         for (auto& L : launches) {
             ++eval_launches;
-            if (L.kw == 0)
+            if (L.kw == 0 && L.mw == 1)
+                P2_HIP(launch_eval_shared(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
+                                          (int)L.segs.size(), reinterpret_cast<const DevShare*>(db + L.off_shares),
+                                          (int)L.shares.size(), L.grid, stream));
+            else if (L.kw == 0)
                 P2_HIP(launch_eval_regs(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
-                                        (int)L.segs.size(), L.blocks, L.mw, stream));
+                                        (int)L.segs.size(), L.blocks, stream));
             else
                 P2_HIP(launch_eval_compact(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
                                            (int)L.segs.size(), L.blocks, L.max_R, L.max_k, stream));
@@ -394,7 +445,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun;
             r.steps = 0; r.members = 0;
             for (int t = 0; t < kCounterStripes; ++t) { r.steps += hc[i].steps[t]; r.members += hc[i].members[t]; }
-            r.evaluated = hc[i].evaluated; r.evaluated_members = hc[i].evaluated_members;
+            r.evaluated = 0; r.evaluated_members = 0;
+            for (int t = 0; t < kCounterStripes; ++t) { r.evaluated += hc[i].evaluated[t]; r.evaluated_members += hc[i].evaluated_members[t]; }
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);

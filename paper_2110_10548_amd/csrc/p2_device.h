@@ -35,6 +35,13 @@ struct DevSegment {
     unsigned long long count;
 };
 
+// Shared-prefix kernel: the grid blocks [first_block, first_block + n_blocks) serve the work items
+// [first_item, first_item + n_items) of one query (item numbers are the first_block numbers of its segments).
+struct DevShare {
+    uint32_t first_block, n_blocks;
+    uint32_t first_item, n_items;
+};
+
 // Work of the kernels that run after the evaluation (ordering, costing, literal re-runs), which
 // serve all queries of a batch in one launch: blocks [first_block, next first_block) handle
 // `count` list entries of one query, `per_block` each, read at in_off and written at out_off
@@ -63,10 +70,10 @@ struct DevCounters {
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
     uint32_t nan_seen;
     uint32_t pad;
-    unsigned long long evaluated;                  // instruction applications carried out, where they differ from `steps`
-    unsigned long long evaluated_members;          // devices taking part in those, summed
     unsigned long long steps[kCounterStripes];     // instructions applied
     unsigned long long members[kCounterStripes];   // devices taking part in those instructions, summed
+    unsigned long long evaluated[kCounterStripes];           // instruction applications carried out, where they differ from `steps`
+    unsigned long long evaluated_members[kCounterStripes];   // devices taking part in those, summed
 };
 
 struct DevQuery {
@@ -80,6 +87,11 @@ struct DevQuery {
     uint32_t magic_alphabet;       // ceil(2^32 / alphabet): v / alphabet == umulhi(v, magic) for v < 2^23
     uint16_t instr_of_digit[kMaxPatterns * 5];   // digit -> (pattern id << 3) | op
     DevPattern pat[kMaxPatterns];
+    // small-group engines: per pattern, shape (log2 g | log2 s << 4 | master << 8) | participating devices << 16,
+    // the bit set of participating devices, and the participating devices summed over the alphabet
+    uint32_t reg_shape[kMaxPatterns];
+    uint32_t reg_part[kMaxPatterns];
+    uint32_t reg_sum_part;
     double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
     // bandwidth rows (device pointers into the uploaded table blob)
     const int32_t* row_ptr;
@@ -113,7 +125,10 @@ hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, 
 // or -1, and the launch over the segments of many queries (64 candidates per wavefront).
 int reg_shape_of(int g, int s, int master);
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
-                            int shared_prefix, hipStream_t stream);
+                            hipStream_t stream);
+// Shared-prefix engine: `grid` blocks, divided among the queries by the share table.
+hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
+                              int n_shares, unsigned grid, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).

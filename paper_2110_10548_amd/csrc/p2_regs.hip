@@ -38,6 +38,7 @@ namespace {
 
 constexpr int kWaveR = 64;
 constexpr int kRegDevices = 32;
+constexpr int kSegCache = 512;       // segments whose first items the shared-prefix kernel keeps in LDS
 
 enum : int { RSTEP_INVALID = 0, RSTEP_OK = 1, RSTEP_GIVE_UP = 2, RSTEP_GOAL = 3 };
 
@@ -521,19 +522,36 @@ __device__ __forceinline__ int wave_step(uint32_t& rv, uint32_t& mv, int dev, in
 
 // Candidates of one length are numbered prefix * alphabet + last instruction, so the `alphabet`
 // candidates of a group (same first len-1 instructions) are consecutive; lane a holds the one whose
-// last instruction has digit a (a + 64 in a second pass for alphabets above 64).  A work item is
-// seg.iters consecutive groups; a block walks the items blockIdx.x, blockIdx.x + gridDim.x, ..., so the
-// groups under one valid stem, which are the expensive ones, are spread over many blocks.
-// The state after the first len-2 instructions (the stem) changes once in `alphabet` groups and is
-// kept; a group whose stem or prefix is invalid is settled for all its candidates at once.
+// last instruction has digit a (a + 64 in a second pass for alphabets above 64).  The groups under
+// one stem (same first len-2 instructions) are consecutive too.  A work item is seg.iters
+// consecutive groups of one stem (a length-1 segment is a single item).  Every query has a share of
+// the grid's blocks in proportion to its items; block j of n walks the query's items j, j + n, ..., so
+// the items of a valid stem, which are the expensive ones, go to different blocks.  An item whose
+// stem is invalid is settled for all its candidates at once.
 __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restrict__ queries,
                                                         const DevSegment* __restrict__ segs, int n_segs,
-                                                        uint32_t total_items) {
+                                                        const DevShare* __restrict__ shares, int n_shares) {
     __shared__ uint16_t sdig[kMaxPatterns * 5];      // digit -> (pattern id << 3) | op
     __shared__ uint32_t sshape[kMaxPatterns];        // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
     __shared__ uint32_t spart[kMaxPatterns];         // pattern id -> bit d set iff device d takes part
+    __shared__ uint32_t sfirst[kSegCache];           // first item of every segment, where the table fits
     const int lane = threadIdx.x;
     const int dev = lane & (kRegDevices - 1);
+    const bool cached = n_segs <= kSegCache;
+    if (cached) {
+        for (int i = lane; i < n_segs; i += kWaveR) sfirst[i] = segs[i].first_block;
+        __syncthreads();
+    }
+    // the query this block works for
+    DevShare sh;
+    {
+        int a = 0, b = n_shares - 1;                 // last share whose first_block <= blockIdx.x
+        while (a < b) {
+            const int mid = (a + b + 1) >> 1;
+            if (shares[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
+        }
+        sh = shares[a];
+    }
     DevSegment seg;
     seg.first_block = 0; seg.query = -1; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
     uint32_t next_first = 0;                         // first item of the next segment
@@ -541,104 +559,87 @@ __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restri
     int len = 1, R = 1;
     uint32_t I = 1, all_rows = 0, all_cols = 0;
     uint32_t sum_part = 0;                           // participating devices summed over the alphabet
-    unsigned long long n_groups_seg = 0;             // groups of the segment
-    unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block for the current query
-    for (uint32_t item = blockIdx.x; item < total_items; item += gridDim.x) {
-        if (qp == nullptr || item >= next_first || item < seg.first_block) {
+    uint32_t items_per_stem = 1;
+    unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
+    const uint32_t end_item = sh.first_item + sh.n_items;
+    for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
+        if (qp == nullptr || item >= next_first) {
             int a = 0, b = n_segs - 1;               // last segment whose first_block <= item
             while (a < b) {
                 const int mid = (a + b + 1) >> 1;
-                if (segs[mid].first_block <= item) a = mid; else b = mid - 1;
+                if ((cached ? sfirst[mid] : segs[mid].first_block) <= item) a = mid; else b = mid - 1;
             }
             const int old_query = seg.query;
             seg = segs[a];
-            next_first = a + 1 < n_segs ? segs[a + 1].first_block : 0xffffffffu;
+            next_first = a + 1 < n_segs ? (cached ? sfirst[a + 1] : segs[a + 1].first_block) : 0xffffffffu;
             if (seg.query != old_query) {
                 // hand the finished query its counts, then load the new query's tables
                 if (lane == 0 && (steps | evaluated) != 0ull) {
                     atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
                     atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
-                    atomicAdd(&qp->counters->evaluated, evaluated);
-                    atomicAdd(&qp->counters->evaluated_members, evaluated_members);
+                    atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
+                    atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
                 }
                 steps = 0; members = 0; evaluated = 0; evaluated_members = 0;
                 qp = queries + seg.query;
                 __syncthreads();
-                for (int i = lane; i < qp->n_patterns; i += kWaveR) {
-                    const uint32_t shape = (uint32_t)qp->pat[i].reg_shape;
-                    sshape[i] = shape | ((uint32_t)(qp->pat[i].n_groups * qp->pat[i].g) << 16);
-                    // devices taking part: below R and, in a Master form, those whose bits below the stride are clear
-                    uint32_t part = qp->R >= 32 ? 0xffffffffu : ((1u << qp->R) - 1u);
-                    if ((shape >> 8) & 1u) {
-                        uint32_t every = 1u;                          // bit d set iff d % 2^ls == 0
-                        for (int j = (int)((shape >> 4) & 15u); j < 5; ++j) every |= every << (1u << j);
-                        part &= every;
-                    }
-                    spart[i] = part;
-                }
+                for (int i = lane; i < qp->n_patterns; i += kWaveR) { sshape[i] = qp->reg_shape[i]; spart[i] = qp->reg_part[i]; }
                 for (int i = lane; i < qp->alphabet; i += kWaveR) sdig[i] = qp->instr_of_digit[i];
                 __syncthreads();
                 R = qp->R;
                 I = (uint32_t)qp->alphabet;
                 all_rows = qp->k >= 32 ? 0xffffffffu : ((1u << qp->k) - 1u);
                 all_cols = R >= 32 ? 0xffffffffu : ((1u << R) - 1u);
-                sum_part = 0;
-                for (uint32_t d = 0; d < I; ++d) sum_part += sshape[sdig[d] >> 3] >> 16;
+                sum_part = qp->reg_sum_part;
             }
             len = seg.len;
-            n_groups_seg = seg.count / I;
+            items_per_stem = len >= 2 ? (I + (uint32_t)seg.iters - 1u) / (uint32_t)seg.iters : 1u;
         }
         const DevQuery& q = *qp;
-        // the item's first group: the stem's digits (instruction t at dg[t], t < len-2) and the digit of
-        // the prefix's last instruction
-        const unsigned long long P0 = (unsigned long long)(item - seg.first_block) * (unsigned long long)seg.iters;
-        const int n_here = (int)(n_groups_seg - P0 < (unsigned long long)seg.iters ? n_groups_seg - P0 : (unsigned long long)seg.iters);
+        // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
+        // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
+        const uint32_t rel = item - seg.first_block;
+        const uint32_t S = rel / items_per_stem;
+        const uint32_t dlast0 = len >= 2 ? (rel - S * items_per_stem) * (uint32_t)seg.iters : 0u;
+        const uint32_t n_here = len >= 2 ? (I - dlast0 < (uint32_t)seg.iters ? I - dlast0 : (uint32_t)seg.iters) : 1u;
         uint32_t dg[P2_MAX_LEN];
-        uint32_t dlast = 0;
         {
-            unsigned long long rem = P0;
-            if (len >= 2) {
-                const unsigned long long nx = rem < (1ull << 32) ? (unsigned long long)((uint32_t)rem / I) : rem / I;
-                dlast = (uint32_t)(rem - nx * I);
-                rem = nx;
-            }
+            uint32_t rem = S;
 #pragma unroll
             for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
-                if (t < len - 2) {
-                    const unsigned long long nx = rem < (1ull << 32) ? (unsigned long long)((uint32_t)rem / I) : rem / I;
-                    dg[t] = (uint32_t)(rem - nx * I);
-                    rem = nx;
-                } else dg[t] = 0;
+                if (t < len - 2) { const uint32_t nx = rem / I; dg[t] = rem - nx * I; rem = nx; }
+                else dg[t] = 0;
             }
         }
-        unsigned long long first_off = P0 * I;       // offset of the group's first candidate in the segment
-        uint32_t item_steps = 0, item_members = 0;   // an item is at most 64 groups: these stay below 2^32
-        bool c_have = false;                         // stem state: after the first len-2 instructions
-        uint32_t c_rv = 0, c_mv = 0, c_ran = 0, c_visited = 0;
+        // offset in the segment of the first candidate of the item's first group
+        unsigned long long first_off = len >= 2 ? ((unsigned long long)S * I + dlast0) * I : 0ull;
+        // the stem's state; Sec. 3.5: device i holds column i in every row
+        uint32_t c_rv = all_rows, c_mv = 1u << dev, c_ran = 0, c_visited = 0;
         int c_rc = RSTEP_OK;
-        for (int gi = 0; gi < n_here; ++gi) {
-            if (!c_have) {
-                c_have = true;
-                // Sec. 3.5: device i holds column i in every row
-                c_rv = all_rows; c_mv = 1u << dev;
-                c_rc = RSTEP_OK; c_ran = 0; c_visited = 0;
 #pragma unroll
-                for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
-                    if (t < len - 2 && c_rc == RSTEP_OK) {
-                        const uint32_t ins0 = sdig[dg[t]];
-                        const uint32_t shape = sshape[ins0 >> 3];
-                        ++c_ran;
-                        c_visited += shape >> 16;
-                        ++evaluated; evaluated_members += shape >> 16;
-                        c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
-                    }
-                }
+        for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
+            if (t < len - 2 && c_rc == RSTEP_OK) {
+                const uint32_t ins0 = sdig[dg[t]];
+                const uint32_t shape = sshape[ins0 >> 3];
+                ++c_ran;
+                c_visited += shape >> 16;
+                ++evaluated; evaluated_members += shape >> 16;
+                c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
             }
+        }
+        if (c_rc == RSTEP_INVALID) {
+            // every candidate of the item stops inside the stem
+            steps += (unsigned long long)(n_here * I) * c_ran;
+            members += (unsigned long long)(n_here * I) * c_visited;
+            continue;
+        }
+        uint32_t item_steps = 0, item_members = 0;   // an item is at most alphabet / 4 groups: these stay below 2^32
+        for (uint32_t gi = 0; gi < n_here; ++gi, first_off += I) {
             uint32_t rv = c_rv, mv = c_mv;
             int rc = c_rc;
             uint32_t g_ran = c_ran, g_visited = c_visited;
             if (rc == RSTEP_OK && len >= 2) {
-                const uint32_t ins0 = sdig[dlast];
+                const uint32_t ins0 = sdig[dlast0 + gi];
                 const uint32_t shape = sshape[ins0 >> 3];
                 ++g_ran;
                 g_visited += shape >> 16;
@@ -696,19 +697,6 @@ __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restri
                     }
                 }
             }
-            // next group: the prefix's last digit goes up; when it wraps the stem changes
-            first_off += I;
-            if (++dlast == I) {
-                dlast = 0;
-                c_have = false;
-                bool carry = true;
-#pragma unroll
-                for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
-                    if (t < len - 2 && carry) {
-                        if (++dg[t] == I) dg[t] = 0; else carry = false;
-                    }
-                }
-            }
         }
         steps += item_steps;
         members += item_members;
@@ -716,8 +704,8 @@ __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restri
     if (lane == 0 && (steps | evaluated) != 0ull) {
         atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
         atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
-        atomicAdd(&qp->counters->evaluated, evaluated);
-        atomicAdd(&qp->counters->evaluated_members, evaluated_members);
+        atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
+        atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
     }
 }
 
@@ -736,14 +724,16 @@ int reg_shape_of(int g, int s, int master) {
 }
 
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
-                            int shared_prefix, hipStream_t stream) {
+                            hipStream_t stream) {
     if (n_segs == 0 || total_blocks == 0) return hipSuccess;
-    if (shared_prefix) {
-        // 16 wavefronts per compute unit, or one block per item if there are fewer
-        const unsigned grid = total_blocks < 4096u ? total_blocks : 4096u;
-        hipLaunchKernelGGL(k_eval_shared, dim3(grid), dim3(kWaveR), 0, stream, queries, segs, n_segs, (uint32_t)total_blocks);
-    }
-    else hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
+    hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
+                              int n_shares, unsigned grid, hipStream_t stream) {
+    if (n_segs == 0 || n_shares == 0 || grid == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_eval_shared, dim3(grid), dim3(kWaveR), 0, stream, queries, segs, n_segs, shares, n_shares);
     return hipGetLastError();
 }
 
