@@ -562,12 +562,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     size_t pos_off = 0;
     int post_launches = 0;
     // ordering and costing: one launch per kernel and state-size class
-    std::vector<PostLaunch> sort_launches, ccost_launches, lcost_launches;
+    std::vector<PostLaunch> sort_launches, ccost_launches, scost_launches, lcost_launches;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
         add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid, r.out_first);
-        if (r.engine == P2_ENGINE_COMPACT) {
+        if (r.regs) {
+            add_seg(scost_launches, 0, r.plan, i, r.n_valid, 1, 0, r.out_first);       // one wavefront per program
+        } else if (r.engine == P2_ENGINE_COMPACT) {
             const int cls = word_class(r.plan.k) * 100 + word_class(r.plan.R);
             add_seg(ccost_launches, cls, r.plan, i, r.n_valid, 1, 0, r.out_first);     // per_block set below
         }
@@ -581,7 +583,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         L.blocks = 0;
         for (auto& sg : L.segs) { sg.per_block = lanes; sg.first_block = L.blocks; L.blocks += (sg.count + lanes - 1) / lanes; }
     }
-    P2_HIP(upload_segs({&sort_launches, &ccost_launches, &lcost_launches}));
+    P2_HIP(upload_segs({&sort_launches, &ccost_launches, &scost_launches, &lcost_launches}));
     unsigned long long* sorted_base = static_cast<unsigned long long*>(C.sorted.p);
     p2_program* progs_base = static_cast<p2_program*>(C.progs.p);
     double* costs_base = static_cast<double*>(C.costs.p);
@@ -595,6 +597,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         ++post_launches;
         P2_HIP(launch_cost_compact_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
                                         L.max_k, sorted_base, progs_base, costs_base, stream));
+    }
+    for (auto& L : scost_launches) {
+        ++post_launches;
+        P2_HIP(launch_cost_shared(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, sorted_base,
+                                  progs_base, costs_base, stream));
     }
     for (auto& L : lcost_launches) {
         ++post_launches;

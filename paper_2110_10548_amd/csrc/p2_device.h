@@ -129,6 +129,9 @@ hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int
 // Shared-prefix engine: `grid` blocks, divided among the queries by the share table.
 hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
                               int n_shares, unsigned grid, hipStream_t stream);
+// Program records and costs of the sorted valid candidates of small-group queries, one block per entry.
+hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                              const unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).

@@ -128,20 +128,24 @@ inline int group_base(const Pattern& p, int group) {       // local id of the gr
 }
 
 void build_cost_rows(const Plan& pl, Pattern& p) {
+    // scratch kept between calls: this runs for every pattern of every query of every call
+    thread_local std::vector<int32_t> stamp, cnt, touched, row_begin;
+    thread_local std::vector<uint32_t> flat;
+    thread_local std::vector<char> dead;
     p.row_ptr.assign(1, 0);
     p.row_level.clear();
     p.entries.clear();
     const int n_rep = pl.D / pl.R;
-    std::vector<int32_t> stamp((size_t)n_rep * p.n_groups, -1);
-    std::vector<int32_t> cnt(p.n_groups, 0);
-    std::vector<int32_t> touched;
+    stamp.assign((size_t)n_rep * p.n_groups, -1);
+    cnt.assign(p.n_groups, 0);
     int stamp_id = 0;
     int below = pl.D;
     for (int j = 0; j < pl.n; ++j) {
         below /= pl.h[j];
         if (j < p.lo) continue;
-        std::map<std::vector<uint32_t>, int> seen;
-        std::vector<std::vector<uint32_t>> rows;
+        // rows of this level, one after the other in `flat`; row r is flat[row_begin[r] .. row_begin[r + 1])
+        flat.clear();
+        row_begin.assign(1, 0);
         for (int u = 0; u < pl.D / below; ++u) {
             ++stamp_id;
             touched.clear();
@@ -156,29 +160,40 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
             }
             if (touched.empty()) continue;
             std::sort(touched.begin(), touched.end());
-            std::vector<uint32_t> row;
-            row.reserve(touched.size());
-            for (int lg : touched) { row.push_back(entry_pack((uint32_t)lg, (uint32_t)group_base(p, lg), (uint32_t)cnt[lg])); cnt[lg] = 0; }
-            if (seen.emplace(row, 1).second) rows.push_back(std::move(row));
+            const size_t first = flat.size();
+            for (int lg : touched) { flat.push_back(entry_pack((uint32_t)lg, (uint32_t)group_base(p, lg), (uint32_t)cnt[lg])); cnt[lg] = 0; }
+            // units with equal descriptions are one row
+            const size_t len = flat.size() - first;
+            bool dup = false;
+            for (size_t r = 0; r + 1 < row_begin.size() && !dup; ++r)
+                dup = (size_t)(row_begin[r + 1] - row_begin[r]) == len &&
+                      std::equal(flat.begin() + first, flat.end(), flat.begin() + row_begin[r]);
+            if (dup) flat.resize(first);
+            else row_begin.push_back((int32_t)flat.size());
         }
         // drop rows dominated by another row of the same level
-        std::vector<char> dead(rows.size(), 0);
-        for (size_t a = 0; a < rows.size(); ++a) {
-            for (size_t b = 0; b < rows.size() && !dead[a]; ++b) {
-                if (a == b || dead[b] || rows[b].size() < rows[a].size()) continue;
+        const size_t n_rows = row_begin.size() - 1;
+        dead.assign(n_rows, 0);
+        for (size_t a = 0; a < n_rows; ++a) {
+            const uint32_t* ra = flat.data() + row_begin[a];
+            const size_t na = (size_t)(row_begin[a + 1] - row_begin[a]);
+            for (size_t b = 0; b < n_rows && !dead[a]; ++b) {
+                const uint32_t* rb = flat.data() + row_begin[b];
+                const size_t nb = (size_t)(row_begin[b + 1] - row_begin[b]);
+                if (a == b || dead[b] || nb < na) continue;
                 size_t ib = 0;
                 bool dom = true;
-                for (size_t ia = 0; ia < rows[a].size() && dom; ++ia) {
-                    uint32_t lg = entry_group(rows[a][ia]), c = entry_cnt(rows[a][ia]);
-                    while (ib < rows[b].size() && entry_group(rows[b][ib]) < lg) ++ib;
-                    dom = ib < rows[b].size() && entry_group(rows[b][ib]) == lg && entry_cnt(rows[b][ib]) >= c;
+                for (size_t ia = 0; ia < na && dom; ++ia) {
+                    uint32_t lg = entry_group(ra[ia]), c = entry_cnt(ra[ia]);
+                    while (ib < nb && entry_group(rb[ib]) < lg) ++ib;
+                    dom = ib < nb && entry_group(rb[ib]) == lg && entry_cnt(rb[ib]) >= c;
                 }
                 if (dom) dead[a] = 1;
             }
         }
-        for (size_t a = 0; a < rows.size(); ++a) {
+        for (size_t a = 0; a < n_rows; ++a) {
             if (dead[a]) continue;
-            p.entries.insert(p.entries.end(), rows[a].begin(), rows[a].end());
+            p.entries.insert(p.entries.end(), flat.begin() + row_begin[a], flat.begin() + row_begin[a + 1]);
             p.row_ptr.push_back((int32_t)p.entries.size());
             p.row_level.push_back(j);
         }

@@ -709,6 +709,85 @@ __global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restri
     }
 }
 
+// Cost of valid programs of small-group queries: one wavefront per program re-runs it with the
+// lanes as devices and adds up the ring alpha-beta step times (hierarchical cost model, see p2.h).
+// The chunk set that sets a group's bytes is the members' common one before an AllReduce-like
+// step, the root's before a Broadcast, the gathered one after an AllGather.  A program whose state
+// leaves the compact form gets NaN costs; the literal cost kernel fills those rows.
+__global__ __launch_bounds__(kWaveR) void k_cost_shared(const DevQuery* __restrict__ queries,
+                                                        const DevPostSeg* __restrict__ segs, int n_segs,
+                                                        const unsigned long long* __restrict__ sorted,
+                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
+    __shared__ uint32_t srows[kRegDevices];          // chunks that set the bytes of the group whose first device is d
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const int dev = lane & (kRegDevices - 1);
+    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
+    const unsigned long long idx = sorted[i];
+    const int R = q.R;
+    const uint32_t all_rows = q.k >= 32 ? 0xffffffffu : ((1u << q.k) - 1u);
+    int len = 1;
+    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
+    uint32_t digit[P2_MAX_LEN];
+    {
+        unsigned long long rem = idx - q.base[len];
+        const unsigned long long I = (unsigned long long)q.alphabet;
+#pragma unroll
+        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
+            if (t < len) { const unsigned long long nx = rem / I; digit[t] = (uint32_t)(rem - nx * I); rem = nx; }
+            else digit[t] = 0;
+        }
+    }
+    // Sec. 3.5: device i holds column i in every row
+    uint32_t rv = all_rows, mv = 1u << dev;
+    double sum_alpha = 0.0, sum_beta = 0.0;
+    bool ok = true;
+    p2_program pr;
+    pr.index = idx;
+    pr.len = (uint8_t)len;
+#pragma unroll
+    for (int t = 0; t < P2_MAX_LEN; ++t) {
+        pr.instr[t] = 0;
+        if (t < len) {
+            const uint32_t ins = q.instr_of_digit[digit[t]];
+            const int pid = (int)(ins >> 3), op = (int)(ins & 7u);
+            pr.instr[t] = (uint8_t)(pid * 5 + op);
+            if (ok) {
+                const uint32_t shape = q.reg_shape[pid];
+                const uint32_t before = rv;
+                ok = wave_step(rv, mv, dev, op, (int)(shape & 15u), (int)((shape >> 4) & 15u), q.reg_part[pid]) == RSTEP_OK;
+                if (ok) {
+                    __syncthreads();
+                    if (lane < kRegDevices) srows[lane] = (uint32_t)__popc(op == OP_AG ? rv : before);
+                    __syncthreads();
+                    // bandwidth term: the most loaded uplink
+                    const DevPattern& P = q.pat[pid];
+                    double best = 0.0;
+                    for (int row = P.row_begin + lane; row < P.row_end; row += kWaveR) {
+                        long long dot = 0;
+                        for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
+                            const uint32_t ent = q.entries[e];
+                            dot += (long long)entry_cnt(ent) * (long long)srows[entry_base(ent)];
+                        }
+                        best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+                    }
+                    for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWaveR));
+                    const double gm1 = (double)(P.g - 1);
+                    const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
+                    const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)P.g : (op == OP_RS || op == OP_AG) ? gm1 / (double)P.g : 1.0;
+                    sum_alpha += ring_steps * q.alpha[P.span_level];
+                    sum_beta += (mult / (double)q.k) * best;
+                }
+            }
+        }
+    }
+    (void)R;
+    if (lane == 0) out_prog[i] = pr;
+    if (lane < q.n_msg)
+        out_cost[i * q.n_msg + lane] = ok ? sum_alpha + q.msg_bytes[lane] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
+}
+
 inline int exact_log2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -734,6 +813,13 @@ hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, i
                               int n_shares, unsigned grid, hipStream_t stream) {
     if (n_segs == 0 || n_shares == 0 || grid == 0) return hipSuccess;
     hipLaunchKernelGGL(k_eval_shared, dim3(grid), dim3(kWaveR), 0, stream, queries, segs, n_segs, shares, n_shares);
+    return hipGetLastError();
+}
+
+hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                              const unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_cost_shared, dim3(blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs, sorted, progs, costs);
     return hipGetLastError();
 }
 
