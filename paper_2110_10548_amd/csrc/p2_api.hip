@@ -102,8 +102,9 @@ struct QueryRun {
     p2::Plan plan;
     int engine = P2_ENGINE_LITERAL;       // engine evaluating the bulk (LITERAL or COMPACT)
     bool frontier = false;                // enumeration by size with pruning instead of index by index
-    bool regs = false;                    // small-group engine (steps computed in registers)
-    bool shared = false;                  // ... with the common instructions of a wavefront applied once
+    bool regs = false;                    // per-candidate small-group engine (steps computed in registers)
+    bool shared = false;                  // shared-prefix engine (the common instructions of a group applied once)
+    bool wave_cost = false;               // valid programs costed by the wavefront-per-program kernel
     size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
@@ -151,18 +152,27 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             runs[i].engine = P2_ENGINE_COMPACT;      // its programs are costed like the compact engine's
             runs[i].frontier = true;
         } else if (want == P2_ENGINE_COMPACT || want == P2_ENGINE_AUTO || want == P2_ENGINE_SMALL || want == P2_ENGINE_SHARED) {
-            if (want != P2_ENGINE_COMPACT && pl.R <= 32 && pl.k <= 32) {
-                runs[i].regs = true;
-                for (const Pattern& p : pl.patterns) runs[i].regs = runs[i].regs && reg_shape_of(p.g, p.s, p.master) >= 0;
+            // power-of-two patterns: the shared-prefix engine holds up to 64 devices, the per-candidate
+            // small-group engine up to 32 devices and 32 chunks
+            bool shared_ok = pl.R <= 64, regs_ok = pl.R <= 32 && pl.k <= 32;
+            for (const Pattern& p : pl.patterns) {
+                shared_ok = shared_ok && reg_shape_of(p.g, p.s, p.master, 6) >= 0;
+                regs_ok = regs_ok && reg_shape_of(p.g, p.s, p.master, 5) >= 0;
             }
-            if ((want == P2_ENGINE_SMALL || want == P2_ENGINE_SHARED) && !runs[i].regs)
-                return fail(P2_EUNSUPPORTED, "the small-group engines need R <= 32, k <= 32 and power-of-two patterns");
-            runs[i].shared = runs[i].regs && want != P2_ENGINE_SMALL;
+            if (want == P2_ENGINE_SMALL && !regs_ok)
+                return fail(P2_EUNSUPPORTED, "the small-group engine needs R <= 32, k <= 32 and power-of-two patterns");
+            if (want == P2_ENGINE_SHARED && !shared_ok)
+                return fail(P2_EUNSUPPORTED, "the shared-prefix engine needs R <= 64 and power-of-two patterns");
+            runs[i].regs = want == P2_ENGINE_SMALL;
+            runs[i].shared = shared_ok && (want == P2_ENGINE_SHARED || want == P2_ENGINE_AUTO);
             if (cmp_ok) runs[i].engine = P2_ENGINE_COMPACT;
             else if (lit_ok && want == P2_ENGINE_AUTO) runs[i].engine = P2_ENGINE_LITERAL;
             else return fail(P2_EUNSUPPORTED, "state too large for the available engines");
         } else return fail(P2_EINVAL, "unknown engine");
         if ((size_t)pl.patterns.size() > (size_t)kMaxPatterns) return fail(P2_EUNSUPPORTED, "more than 64 patterns");
+        // valid programs of these queries are costed one per wavefront, lanes as devices
+        runs[i].wave_cost = runs[i].engine == P2_ENGINE_COMPACT && pl.R <= 64;
+        for (const Pattern& p : pl.patterns) runs[i].wave_cost = runs[i].wave_cost && reg_shape_of(p.g, p.s, p.master, 6) >= 0;
     }
 
     g_prof.last.host_plan_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
@@ -172,6 +182,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     off = align_up(off, 256);
     // compact-engine queries are launched together, one launch per (chunk words, mask words) class
     struct Launch {
+        int kind;                                   // 0 compact engine (state in LDS), 1 per-candidate small-group, 2 shared-prefix
         int kw, mw, max_R, max_k; std::vector<DevSegment> segs; unsigned blocks; size_t off_segs;
         std::vector<DevShare> shares; unsigned grid = 0; size_t off_shares = 0;     // shared-prefix kernel only
     };
@@ -180,28 +191,29 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].plan.n_candidates == 0) continue;
         const Plan& pl = runs[i].plan;
-        const int kw = runs[i].regs ? 0 : word_class(pl.k), mw = runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R);
+        const int kind = runs[i].shared ? 2 : runs[i].regs ? 1 : 0;
+        const int kw = kind == 1 ? 1 : word_class(pl.k), mw = kind == 1 ? 1 : word_class(pl.R);
         Launch* L = nullptr;
-        for (auto& c : launches) if (c.kw == kw && c.mw == mw) L = &c;
-        if (!L) { launches.push_back(Launch{kw, mw, 0, 0, {}, 0u, 0, {}, 0u, 0}); L = &launches.back(); }
+        for (auto& c : launches) if (c.kind == kind && c.kw == kw && c.mw == mw) L = &c;
+        if (!L) { launches.push_back(Launch{kind, kw, mw, 0, 0, {}, 0u, 0, {}, 0u, 0}); L = &launches.back(); }
         L->max_R = std::max(L->max_R, pl.R);
         L->max_k = std::max(L->max_k, pl.k);
     }
     for (auto& L : launches) {
-        const int lanes = L.kw == 0 ? 64 : compact_lanes(L.max_R, L.max_k);
+        const int lanes = L.kind != 0 ? 64 : compact_lanes(L.max_R, L.max_k);
         if (lanes == 0) return fail(P2_EUNSUPPORTED, "state too large for the compact engine");
         unsigned long long blocks = 0;
         for (int i = 0; i < n_queries; ++i) {
             const Plan& pl = runs[i].plan;
             if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || pl.n_candidates == 0) continue;
-            if ((runs[i].regs ? 0 : word_class(pl.k)) != L.kw ||
-                (runs[i].regs ? (runs[i].shared ? 1 : 0) : word_class(pl.R)) != L.mw) continue;
+            const int kind = runs[i].shared ? 2 : runs[i].regs ? 1 : 0;
+            if (kind != L.kind || (kind == 1 ? 1 : word_class(pl.k)) != L.kw || (kind == 1 ? 1 : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
                 const unsigned long long count = pl.base[len + 1] - pl.base[len];
                 DevSegment sg;
                 sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len;
                 sg.first_index = pl.base[len]; sg.count = count;
-                if (L.kw == 0 && L.mw == 1) {
+                if (L.kind == 2) {
                     // shared-prefix kernel: an item is a quarter of the groups under one stem (the first
                     // len-2 instructions); small items balance the load of its fixed grid
                     const unsigned long long I = (unsigned long long)pl.alphabet;
@@ -223,7 +235,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         L.blocks = (unsigned)blocks;
         L.off_segs = off;
         off += align_up(sizeof(DevSegment) * L.segs.size(), 256);
-        if (L.kw == 0 && L.mw == 1) {
+        if (L.kind == 2) {
             // divide a grid of about 4096 blocks (16 wavefronts per compute unit) among the queries by their items
             const unsigned long long target = 4096;
             for (size_t a = 0; a < L.segs.size();) {
@@ -341,7 +353,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 const Pattern& p = pl.patterns[pi];
                 DevPattern& dp = dq->pat[pi];
                 dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.lo;
-                dp.reg_shape = reg_shape_of(p.g, p.s, p.master);
+                dp.reg_shape = reg_shape_of(p.g, p.s, p.master, 5);
                 dp.row_begin = row;
                 for (size_t t = 0; t < p.row_level.size(); ++t) {
                     for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
@@ -353,11 +365,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             dq->reg_sum_part = 0;
             for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
                 const Pattern& p = pl.patterns[pi];
-                const int shape = reg_shape_of(p.g, p.s, p.master);
-                uint32_t part = pl.R >= 32 ? 0xffffffffu : ((1u << pl.R) - 1u);
+                const int shape = reg_shape_of(p.g, p.s, p.master, 6);
+                unsigned long long part = pl.R >= 64 ? ~0ull : ((1ull << pl.R) - 1ull);
                 if (p.master) {
-                    uint32_t every = 0;                       // bit d set iff d % s == 0
-                    for (int d = 0; d < 32; d += p.s) every |= 1u << d;
+                    unsigned long long every = 0;             // bit d set iff d % s == 0
+                    for (int d = 0; d < 64; d += p.s) every |= 1ull << d;
                     part &= every;
                 }
                 dq->reg_shape[pi] = (shape < 0 ? 0u : (uint32_t)shape) | ((uint32_t)(p.n_groups * p.g) << 16);
@@ -385,11 +397,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[0], stream));
         for (auto& L : launches) {
             ++eval_launches;
-            if (L.kw == 0 && L.mw == 1)
+            if (L.kind == 2)
                 P2_HIP(launch_eval_shared(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
                                           (int)L.segs.size(), reinterpret_cast<const DevShare*>(db + L.off_shares),
-                                          (int)L.shares.size(), L.grid, stream));
-            else if (L.kw == 0)
+                                          (int)L.shares.size(), L.grid, L.max_R, L.max_k, stream));
+            else if (L.kind == 1)
                 P2_HIP(launch_eval_regs(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const DevSegment*>(db + L.off_segs),
                                         (int)L.segs.size(), L.blocks, stream));
             else
@@ -415,12 +427,23 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         // candidates whose state the compact engine could not hold go through the literal engine:
         // one launch per mask-width class for the states that fit in LDS, one per query otherwise
         bool reran = false;
-        std::vector<PostLaunch> rerun_launches;
+        std::vector<PostLaunch> rerun_launches, group_launches;
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap) continue;
             reran = true;
-            if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
+            if (r.shared) {
+                // the shared-prefix engine hands over whole groups (an entry is a group's first candidate)
+                if (front_literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
+                    add_seg(group_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
+                } else {
+                    unsigned nb = 0;
+                    P2_HIP(C.lit_scratch.ensure(literal_scratch_bytes(r.plan.R, r.plan.k, &nb)));
+                    P2_HIP(launch_eval_literal_groups(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k,
+                                                      static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, hc[i].n_rerun,
+                                                      C.lit_scratch.p, stream));
+                }
+            } else if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
                 add_seg(rerun_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
             } else {
                 void* gs = nullptr;
@@ -429,11 +452,22 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                            hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, gs, stream));
             }
         }
-        if (!rerun_launches.empty()) {
-            P2_HIP(upload_segs({&rerun_launches}));
+        for (auto& L : group_launches) {
+            // few groups: several blocks share a group, each judging part of the last instructions
+            unsigned total = 0;
+            for (auto& sg : L.segs) total += sg.count;
+            const uint32_t parts = std::min<uint32_t>(8, std::max<uint32_t>(1, 2048 / std::max(1u, total)));
+            L.blocks = 0;
+            for (auto& sg : L.segs) { sg.per_block = parts; sg.first_block = L.blocks; L.blocks += sg.count * parts; }
+        }
+        if (!rerun_launches.empty() || !group_launches.empty()) {
+            P2_HIP(upload_segs({&rerun_launches, &group_launches}));
             for (auto& L : rerun_launches)
                 P2_HIP(launch_eval_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
                                                 L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
+            for (auto& L : group_launches)
+                P2_HIP(launch_eval_literal_groups_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
+                                                       L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
         }
         if (reran) {
             P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
@@ -567,8 +601,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
         add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid, r.out_first);
-        if (r.regs) {
-            add_seg(scost_launches, 0, r.plan, i, r.n_valid, 1, 0, r.out_first);       // one wavefront per program
+        if (r.wave_cost) {
+            add_seg(scost_launches, word_class(r.plan.k) * 100 + word_class(r.plan.R), r.plan, i, r.n_valid, 1, 0,
+                    r.out_first);                                                  // one wavefront per program
         } else if (r.engine == P2_ENGINE_COMPACT) {
             const int cls = word_class(r.plan.k) * 100 + word_class(r.plan.R);
             add_seg(ccost_launches, cls, r.plan, i, r.n_valid, 1, 0, r.out_first);     // per_block set below
@@ -600,8 +635,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     }
     for (auto& L : scost_launches) {
         ++post_launches;
-        P2_HIP(launch_cost_shared(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, sorted_base,
-                                  progs_base, costs_base, stream));
+        P2_HIP(launch_cost_shared(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
+                                  L.max_k, sorted_base, progs_base, costs_base, stream));
     }
     for (auto& L : lcost_launches) {
         ++post_launches;
@@ -682,7 +717,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         if (stats) {
             p2_stats& s = stats[i];
-            s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.literal_reruns = r.n_rerun; s.member_visits = r.members;
+            s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.member_visits = r.members;
+            s.literal_reruns = r.shared ? (uint64_t)r.n_rerun * (uint64_t)r.plan.alphabet : r.n_rerun;
             s.steps_evaluated = r.shared ? r.evaluated : r.steps;
             s.members_evaluated = r.shared ? r.evaluated_members : r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();

@@ -90,7 +90,7 @@ struct DevQuery {
     // small-group engines: per pattern, shape (log2 g | log2 s << 4 | master << 8) | participating devices << 16,
     // the bit set of participating devices, and the participating devices summed over the alphabet
     uint32_t reg_shape[kMaxPatterns];
-    uint32_t reg_part[kMaxPatterns];
+    unsigned long long reg_part[kMaxPatterns];
     uint32_t reg_sum_part;
     double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
     // bandwidth rows (device pointers into the uploaded table blob)
@@ -121,17 +121,20 @@ hipError_t launch_eval_literal(const DevQuery* q, int R, int k, unsigned long lo
 // Compact engine: one launch over the segments of many queries (all with R <= max_R, k <= max_k).
 hipError_t launch_eval_compact(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
                                int max_R, int max_k, hipStream_t stream);
-// Register engine (R <= 32, k <= 32, patterns with power-of-two shapes): shape number of a pattern
-// or -1, and the launch over the segments of many queries (64 candidates per wavefront).
-int reg_shape_of(int g, int s, int master);
+// Engines for patterns with power-of-two group size and stride: shape word of a pattern
+// (log2 g | log2 s << 4 | master << 8) or -1 if its group bits do not fit in max_bits (5: the
+// per-candidate engine for R <= 32, k <= 32; 6: the shared-prefix engine for R <= 64), and the launch
+// of the per-candidate engine over the segments of many queries (64 candidates per wavefront).
+int reg_shape_of(int g, int s, int master, int max_bits);
 hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int n_segs, unsigned total_blocks,
                             hipStream_t stream);
 // Shared-prefix engine: `grid` blocks, divided among the queries by the share table.
 hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
-                              int n_shares, unsigned grid, hipStream_t stream);
-// Program records and costs of the sorted valid candidates of small-group queries, one block per entry.
-hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                              const unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream);
+                              int n_shares, unsigned grid, int max_R, int max_k, hipStream_t stream);
+// Program records and costs of the sorted valid candidates of shared-prefix-capable queries, one block per entry.
+hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks, int max_R,
+                              int max_k, const unsigned long long* sorted, p2_program* progs, double* costs,
+                              hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).
@@ -142,6 +145,13 @@ hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long
 // Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
+// Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate):
+// one block per entry of each segment, or, for one query, blocks striding over n entries with the state
+// in a global buffer when it does not fit in LDS (front_literal_lds_bytes).
+hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                           int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
+hipError_t launch_eval_literal_groups(const DevQuery* q, int R, int k, const unsigned long long* list, uint32_t n,
+                                      void* gscratch, hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.
 hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,

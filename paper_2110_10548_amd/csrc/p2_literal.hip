@@ -515,6 +515,67 @@ __device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, cons
     return invalid ? 0 : goal ? 2 : 3;
 }
 
+// Classes of equal rows of the state in L.S, and per device whether it holds anything and whether it
+// is at the goal.  Hash every row over all devices, point each row at the first row with its hash,
+// and keep the pointer only if the two rows really are equal.  Returns the number of classes.
+template <int MW>
+__device__ inline int row_classes(const DevQuery& q, const LitLds& L, const FrontLit& X, const uint32_t* full, int lane) {
+    const int R = q.R, k = q.k;
+    for (int r = lane; r < k; r += kWave) {
+        uint32_t a = 0x811c9dc5u, b = 0x9e3779b9u;
+        for (int d = 0; d < R; ++d) {
+            const uint32_t* x = L.S + (d * k + r) * MW;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) {
+                const uint32_t v = x[w];
+                a = (a ^ v) * 0x01000193u;
+                b = (b + v) * 0x85ebca6bu + (b >> 13);
+            }
+        }
+        X.h1[r] = a; X.h2[r] = b;
+        X.multr[r] = 0;
+    }
+    __syncthreads();
+    for (int r = lane; r < k; r += kWave) {
+        const uint32_t a = X.h1[r], b = X.h2[r];
+        int r0 = 0;
+        while (r0 < r && (X.h1[r0] != a || X.h2[r0] != b)) ++r0;
+        if (r0 != r) {
+            bool same = true;
+            for (int d = 0; d < R; ++d) {
+                const uint32_t* x = L.S + (d * k + r) * MW;
+                const uint32_t* y = L.S + (d * k + r0) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) same &= x[w] == y[w];
+            }
+            if (!same) r0 = r;
+        }
+        X.rep[r] = (uint32_t)r0;
+    }
+    __syncthreads();
+    int C = 0;
+    for (int r0 = 0; r0 < k; r0 += kWave) {
+        const int r = r0 + lane;
+        const bool is = r < k && X.rep[r] == (uint32_t)r;
+        const unsigned long long bal = __ballot(is);
+        if (is) X.reps[C + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)r;
+        C += __popcll(bal);
+        if (r < k) atomicAdd(&X.multr[X.rep[r]], 1u);
+    }
+    __syncthreads();
+    for (int d = lane; d < R; d += kWave) {
+        bool any = false, all = true;
+        for (int c = 0; c < C; ++c) {
+            const uint32_t* x = L.S + (d * k + (int)X.reps[c]) * MW;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) { any |= x[w] != 0; all &= x[w] == full[w]; }
+        }
+        X.devany[d] = any; X.devfull[d] = all;
+    }
+    __syncthreads();
+    return C;
+}
+
 template <int MW>
 __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery* __restrict__ qp,
                                                                   const FrontEntry* __restrict__ entries, uint32_t n_entries,
@@ -541,60 +602,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
             const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
             lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
         }
-        // classes of equal rows: hash every row over all devices, point each row at the first row
-        // with its hash, and keep the pointer only if the two rows really are equal
-        for (int r = lane; r < k; r += kWave) {
-            uint32_t a = 0x811c9dc5u, b = 0x9e3779b9u;
-            for (int d = 0; d < R; ++d) {
-                const uint32_t* x = L.S + (d * k + r) * MW;
-#pragma unroll
-                for (int w = 0; w < MW; ++w) {
-                    const uint32_t v = x[w];
-                    a = (a ^ v) * 0x01000193u;
-                    b = (b + v) * 0x85ebca6bu + (b >> 13);
-                }
-            }
-            X.h1[r] = a; X.h2[r] = b;
-            X.multr[r] = 0;
-        }
-        __syncthreads();
-        for (int r = lane; r < k; r += kWave) {
-            const uint32_t a = X.h1[r], b = X.h2[r];
-            int r0 = 0;
-            while (r0 < r && (X.h1[r0] != a || X.h2[r0] != b)) ++r0;
-            if (r0 != r) {
-                bool same = true;
-                for (int d = 0; d < R; ++d) {
-                    const uint32_t* x = L.S + (d * k + r) * MW;
-                    const uint32_t* y = L.S + (d * k + r0) * MW;
-#pragma unroll
-                    for (int w = 0; w < MW; ++w) same &= x[w] == y[w];
-                }
-                if (!same) r0 = r;
-            }
-            X.rep[r] = (uint32_t)r0;
-        }
-        __syncthreads();
-        int C = 0;
-        for (int r0 = 0; r0 < k; r0 += kWave) {
-            const int r = r0 + lane;
-            const bool is = r < k && X.rep[r] == (uint32_t)r;
-            const unsigned long long bal = __ballot(is);
-            if (is) X.reps[C + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)r;
-            C += __popcll(bal);
-            if (r < k) atomicAdd(&X.multr[X.rep[r]], 1u);
-        }
-        __syncthreads();
-        for (int d = lane; d < R; d += kWave) {
-            bool any = false, all = true;
-            for (int c = 0; c < C; ++c) {
-                const uint32_t* x = L.S + (d * k + (int)X.reps[c]) * MW;
-#pragma unroll
-                for (int w = 0; w < MW; ++w) { any |= x[w] != 0; all &= x[w] == full[w]; }
-            }
-            X.devany[d] = any; X.devfull[d] = all;
-        }
-        __syncthreads();
+        const int C = row_classes<MW>(q, L, X, full, lane);
         for (int a = 0; a < I; ++a) {
             const uint32_t ins = q.instr_of_digit[a];
             const DevPattern& P = q.pat[ins >> 3];
@@ -610,6 +618,101 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
         __syncthreads();
     }
     if (lane == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
+}
+
+// ---- groups handed over by the shared-prefix engine ------------------------------------------------
+// A list entry is the index of a group's first candidate: `alphabet` consecutive candidates with the
+// same first len-1 instructions, whose common state the compact form could not hold.  The literal
+// state of that prefix is rebuilt once, every step checked, and all last instructions are judged
+// against it (one representative per class of equal rows, as in the frontier kernel above).
+// part / parts: this block judges the last instructions a = part, part + parts, ... and part 0 does the counting.
+template <int MW>
+__device__ inline void literal_group(const DevQuery& q, unsigned long long idx0, const LitLds& L, const FrontLit& X,
+                                     const uint32_t* full, int lane, int part, int parts, unsigned long long& steps,
+                                     unsigned long long& members) {
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx0, digit);
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    lit_init<MW>(q, L, lane);
+    bool ok = true;
+    unsigned long long ran = 0, visited = 0;
+    for (int t = 0; t < len - 1 && ok; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ++ran;
+        visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        ok = lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr);
+    }
+    if (!ok) {                       // every candidate of the group stops inside the prefix
+        if (part == 0) { steps += I * ran; members += I * visited; }
+        return;
+    }
+    const int C = row_classes<MW>(q, L, X, full, lane);
+    for (int a = part; a < q.alphabet; a += parts) {
+        const uint32_t ins = q.instr_of_digit[a];
+        if (lit_classify<MW>(q, q.pat[ins >> 3], (int)(ins & 7u), L, X, C, full, lane) == 2 && lane == 0) {
+            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+            if (pos < q.valid_cap) q.valid_idx[pos] = idx0 + (unsigned long long)a;
+        }
+    }
+    if (part == 0) {
+        steps += I * (ran + 1ull);
+        members += I * visited + (unsigned long long)q.reg_sum_part;
+    }
+}
+
+// Groups of many queries (states that fit in LDS).
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_eval_literal_groups_list(const DevQuery* __restrict__ queries,
+                                                                    const DevPostSeg* __restrict__ segs, int n_segs,
+                                                                    const unsigned long long* __restrict__ list) {
+    extern __shared__ uint32_t lds[];
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const LitLds L = carve(lds, q.R, q.k, MW);
+    const FrontLit X = carve_front(L.flags + 4, q.k);
+    uint32_t full[MW];
+#pragma unroll
+    for (int w = 0; w < MW; ++w) {
+        const int bits = q.R - 32 * w;
+        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+    }
+    unsigned long long steps = 0, members = 0;
+    // seg.per_block blocks share one list entry, each judging its share of the last instructions
+    const uint32_t local = blockIdx.x - seg.first_block;
+    literal_group<MW>(q, list[seg.in_off + local / seg.per_block], L, X, full, lane, (int)(local % seg.per_block), (int)seg.per_block,
+                      steps, members);
+    if (lane == 0 && steps) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
+}
+
+// Groups of one query, blocks striding over the list; the state may live in a global buffer.
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_eval_literal_groups(const DevQuery* __restrict__ qp,
+                                                               const unsigned long long* __restrict__ list, uint32_t n,
+                                                               uint32_t* __restrict__ gscratch, unsigned long long gwords) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
+    const FrontLit X = carve_front(L.flags + 4, q.k);
+    uint32_t full[MW];
+#pragma unroll
+    for (int w = 0; w < MW; ++w) {
+        const int bits = q.R - 32 * w;
+        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+    }
+    unsigned long long steps = 0, members = 0;
+    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
+        literal_group<MW>(q, list[e], L, X, full, lane, 0, 1, steps, members);
+        __syncthreads();
+    }
+    if (lane == 0 && steps) {
+        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
+    }
 }
 
 template <typename F>
@@ -782,6 +885,58 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, entries, n, \
                            parent_len, surv, surv_cap, ctr, static_cast<uint32_t*>(gscratch), gwords);
+    switch (mask_words(R)) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                           int max_R, int max_k, const unsigned long long* list, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const size_t lds = front_literal_lds_bytes(max_R, max_k);
+    if (lds == 0) return hipErrorInvalidValue;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_eval_literal_groups_list<MWV>, lds);                                                   \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_eval_literal_groups_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, list);
+    switch (mask_words(max_R)) {
+    case 1: P2_LAUNCH(1) break;
+    case 2: P2_LAUNCH(2) break;
+    case 4: P2_LAUNCH(4) break;
+    case 8: P2_LAUNCH(8) break;
+    default: P2_LAUNCH(16) break;
+    }
+#undef P2_LAUNCH
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_literal_groups(const DevQuery* q, int R, int k, const unsigned long long* list, uint32_t n,
+                                      void* gscratch, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    size_t lds = front_literal_lds_bytes(R, k);
+    unsigned blocks = n < 16384u ? n : 16384u;
+    unsigned long long gwords = 0;
+    if (lds == 0) {
+        if (!gscratch) return hipErrorInvalidValue;
+        unsigned nb = 0;
+        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
+        blocks = nb < n ? nb : n;
+    } else gscratch = nullptr;
+    hipError_t e = hipSuccess;
+#define P2_LAUNCH(MWV)                                                                                         \
+    e = allow_big_lds(k_eval_literal_groups<MWV>, lds);                                                        \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_eval_literal_groups<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, list, n,     \
+                           static_cast<uint32_t*>(gscratch), gwords);
     switch (mask_words(R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;

@@ -1,4 +1,5 @@
-// Compact engine for small reduction groups: every step is computed in registers.
+// Per-candidate engine for small reduction groups: one candidate per lane, every step computed in
+// registers.
 //
 // Same state form as p2_compact.hip -- per device one chunk set and one contribution mask -- for
 // R <= 32 devices and k <= 32 chunks, so a pair is two 32-bit words and a candidate's state is 64
@@ -6,7 +7,7 @@
 // every access of the wavefront is conflict-free and addressed with a constant offset).  A step
 // loads all 32 pairs back to back (one LDS round trip), applies the rule in registers as straight
 // vector code without address arithmetic, and writes the pairs back only if the step is valid and
-// is not the last; the first step makes the init state up in registers instead of loading it.
+// is not the last; the first step uses the closed form of the rules on the init state.
 //
 // Registers cannot be indexed by a run-time device number.  For patterns whose group size g and
 // stride s are powers of two (every pattern of a hierarchy with power-of-two levels), the members
@@ -17,9 +18,8 @@
 //   AllReduce-like : union of the masks along each bit; the two sides of every pair must hold the
 //                    same chunks and disjoint masks (the sides' running unions are disjoint at
 //                    every stage iff all members are pairwise disjoint).
-//   ReduceScatter  : then halve the chunk set once per bit, highest first: bit clear keeps the
-//                    lower half, bit set the upper half -- rank p ends with the p-th block.
-//   Reduce         : then clear every member that has one of the bits set.
+//   ReduceScatter  : then the member of rank p keeps the p-th block of the chunks.
+//   Reduce         : then every member that has one of the bits set is cleared.
 //   AllGather      : union of the chunk sets along each bit, sides disjoint; nobody empty.
 //   Broadcast      : binomial tree from the device with all bits clear; a member is compared with
 //                    the root's pair right before it is overwritten.
@@ -28,8 +28,8 @@
 //
 // The 64 lanes of a wavefront hold consecutive candidates.  At a step the lanes that share the
 // first pending lane's instruction run it together under their execution mask; the others wait
-// for the next round.  Prefix instructions are the same in all lanes, so they take one round; the
-// last instruction takes one round per distinct instruction still alive.
+// for the next round.  Prefix instructions are the same in all lanes, so they take one round.  The
+// last instruction, different in every lane, is judged per lane without writing the state.
 #include "p2_device.h"
 
 namespace p2 {
@@ -38,7 +38,6 @@ namespace {
 
 constexpr int kWaveR = 64;
 constexpr int kRegDevices = 32;
-constexpr int kSegCache = 512;       // segments whose first items the shared-prefix kernel keeps in LDS
 
 enum : int { RSTEP_INVALID = 0, RSTEP_OK = 1, RSTEP_GIVE_UP = 2, RSTEP_GOAL = 3 };
 
@@ -442,352 +441,6 @@ __global__ __launch_bounds__(kWaveR) void k_eval_regs(const DevQuery* __restrict
     }
 }
 
-// ---- shared-prefix evaluation ---------------------------------------------------------------------
-// The 64 consecutive candidates of a wavefront differ in their last instruction and fall into a
-// few groups with the same first len-1 instructions.  The state after such a common prefix is the
-// same for the whole group, so it is computed once, by the wavefront as a whole: lane d (and lane
-// d + 32) plays device d, a stage along bit J exchanges pairs with lane d ^ 2^J.  The group's
-// candidates then judge their own last instruction against that state (32 pairs in LDS).  A
-// candidate is still resolved by its own lane; what the lanes of a group would compute
-// identically is computed once.
-
-// One instruction on the wavefront-held state (rv, mv: pair of device lane & 31).  All lanes are
-// active and all arguments but rv, mv are wave-uniform.  Returns RSTEP_INVALID, RSTEP_OK or RSTEP_GIVE_UP.
-__device__ __forceinline__ int wave_step(uint32_t& rv, uint32_t& mv, int dev, int op, int lg, int ls, uint32_t part) {
-    const int gm1 = (1 << lg) - 1;
-    const uint32_t gmask = (uint32_t)gm1 << ls;
-    const bool in = ((part >> dev) & 1u) != 0u;
-    bool bad = false;
-    if (op == OP_AR || op == OP_RS || op == OP_RD) {
-        // same chunks on every member, no contribution reduced twice: union of the masks along each bit
-        for (int J = ls; J < ls + lg; ++J) {
-            const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
-            const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
-            bad |= in && (((rv ^ pr) | (mv & pm)) != 0u);
-            if (in) mv |= pm;
-        }
-        if (__any(bad)) return RSTEP_INVALID;
-        if (!__any(in && rv != 0u)) return RSTEP_INVALID;      // only groups of empty devices: nothing changes
-        if (op == OP_RS) {
-            // the member of rank p keeps the p-th block of the chunks in ascending order
-            const int c = __popc(rv);
-            const int per = c >> lg, p = (dev >> ls) & gm1;
-            bad = in && (c & gm1) != 0;
-            const uint32_t lowbit = rv & (0u - rv);
-            uint32_t nv;
-            if (((rv + lowbit) & rv) == 0u) nv = (((lowbit << per) - lowbit) << (p * per)) & rv;
-            else nv = lowest_bits(rv, (p + 1) * per) ^ lowest_bits(rv, p * per);
-            if (in) rv = nv;
-            if (__any(bad)) return RSTEP_INVALID;
-        } else if (op == OP_RD) {
-            if (in && ((uint32_t)dev & gmask) != 0u) { rv = 0u; mv = 0u; }
-        }
-        return RSTEP_OK;
-    }
-    if (op == OP_AG) {
-        // nobody empty, every chunk held once: union of the chunk sets along each bit
-        if (__any(in && rv == 0u)) return RSTEP_INVALID;
-        bool differs = false;
-        for (int J = ls; J < ls + lg; ++J) {
-            const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
-            const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
-            bad |= in && (rv & pr) != 0u;
-            differs |= in && (mv ^ pm) != 0u;
-            if (in) rv |= pr;
-        }
-        if (__any(bad)) return RSTEP_INVALID;
-        return __any(differs) ? RSTEP_GIVE_UP : RSTEP_OK;      // rows with different column sets leave this form
-    }
-    // Broadcast as a binomial tree from the member with all group bits clear: a member is compared
-    // with the root's pair right before it takes it
-    bool neq = false;
-    for (int J = ls; J < ls + lg; ++J) {
-        const uint32_t pr = (uint32_t)__shfl_xor((int)rv, 1 << J, kWaveR);
-        const uint32_t pm = (uint32_t)__shfl_xor((int)mv, 1 << J, kWaveR);
-        const bool takes = in && ((dev >> J) & 1) != 0 && ((uint32_t)dev & gmask & (~0u << (J + 1))) == 0u;
-        if (takes) {
-            bad |= ((rv & ~pr) | (mv & ~pm)) != 0u;
-            neq |= ((rv ^ pr) | (mv ^ pm)) != 0u;
-            rv = pr;
-            mv = pm;
-        }
-    }
-    if (__any(bad)) return RSTEP_INVALID;
-    // in every group some member must have differed from the root: fold the flags onto the roots' bits
-    uint32_t flags = (uint32_t)__ballot(neq);
-    const uint32_t roots = (uint32_t)__ballot(in && ((uint32_t)dev & gmask) == 0u);
-    for (int J = ls; J < ls + lg; ++J) flags |= flags >> (1u << J);
-    return (~flags & roots) != 0u ? RSTEP_INVALID : RSTEP_OK;
-}
-
-// Candidates of one length are numbered prefix * alphabet + last instruction, so the `alphabet`
-// candidates of a group (same first len-1 instructions) are consecutive; lane a holds the one whose
-// last instruction has digit a (a + 64 in a second pass for alphabets above 64).  The groups under
-// one stem (same first len-2 instructions) are consecutive too.  A work item is seg.iters
-// consecutive groups of one stem (a length-1 segment is a single item).  Every query has a share of
-// the grid's blocks in proportion to its items; block j of n walks the query's items j, j + n, ..., so
-// the items of a valid stem, which are the expensive ones, go to different blocks.  An item whose
-// stem is invalid is settled for all its candidates at once.
-__global__ __launch_bounds__(kWaveR) void k_eval_shared(const DevQuery* __restrict__ queries,
-                                                        const DevSegment* __restrict__ segs, int n_segs,
-                                                        const DevShare* __restrict__ shares, int n_shares) {
-    __shared__ uint16_t sdig[kMaxPatterns * 5];      // digit -> (pattern id << 3) | op
-    __shared__ uint32_t sshape[kMaxPatterns];        // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
-    __shared__ uint32_t spart[kMaxPatterns];         // pattern id -> bit d set iff device d takes part
-    __shared__ uint32_t sfirst[kSegCache];           // first item of every segment, where the table fits
-    const int lane = threadIdx.x;
-    const int dev = lane & (kRegDevices - 1);
-    const bool cached = n_segs <= kSegCache;
-    if (cached) {
-        for (int i = lane; i < n_segs; i += kWaveR) sfirst[i] = segs[i].first_block;
-        __syncthreads();
-    }
-    // the query this block works for
-    DevShare sh;
-    {
-        int a = 0, b = n_shares - 1;                 // last share whose first_block <= blockIdx.x
-        while (a < b) {
-            const int mid = (a + b + 1) >> 1;
-            if (shares[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
-        }
-        sh = shares[a];
-    }
-    DevSegment seg;
-    seg.first_block = 0; seg.query = -1; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
-    uint32_t next_first = 0;                         // first item of the next segment
-    const DevQuery* qp = nullptr;
-    int len = 1, R = 1;
-    uint32_t I = 1, all_rows = 0, all_cols = 0;
-    uint32_t sum_part = 0;                           // participating devices summed over the alphabet
-    uint32_t items_per_stem = 1;
-    unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
-    const uint32_t end_item = sh.first_item + sh.n_items;
-    for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
-        if (qp == nullptr || item >= next_first) {
-            int a = 0, b = n_segs - 1;               // last segment whose first_block <= item
-            while (a < b) {
-                const int mid = (a + b + 1) >> 1;
-                if ((cached ? sfirst[mid] : segs[mid].first_block) <= item) a = mid; else b = mid - 1;
-            }
-            const int old_query = seg.query;
-            seg = segs[a];
-            next_first = a + 1 < n_segs ? (cached ? sfirst[a + 1] : segs[a + 1].first_block) : 0xffffffffu;
-            if (seg.query != old_query) {
-                // hand the finished query its counts, then load the new query's tables
-                if (lane == 0 && (steps | evaluated) != 0ull) {
-                    atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
-                    atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
-                    atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
-                    atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
-                }
-                steps = 0; members = 0; evaluated = 0; evaluated_members = 0;
-                qp = queries + seg.query;
-                __syncthreads();
-                for (int i = lane; i < qp->n_patterns; i += kWaveR) { sshape[i] = qp->reg_shape[i]; spart[i] = qp->reg_part[i]; }
-                for (int i = lane; i < qp->alphabet; i += kWaveR) sdig[i] = qp->instr_of_digit[i];
-                __syncthreads();
-                R = qp->R;
-                I = (uint32_t)qp->alphabet;
-                all_rows = qp->k >= 32 ? 0xffffffffu : ((1u << qp->k) - 1u);
-                all_cols = R >= 32 ? 0xffffffffu : ((1u << R) - 1u);
-                sum_part = qp->reg_sum_part;
-            }
-            len = seg.len;
-            items_per_stem = len >= 2 ? (I + (uint32_t)seg.iters - 1u) / (uint32_t)seg.iters : 1u;
-        }
-        const DevQuery& q = *qp;
-        // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
-        // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
-        const uint32_t rel = item - seg.first_block;
-        const uint32_t S = rel / items_per_stem;
-        const uint32_t dlast0 = len >= 2 ? (rel - S * items_per_stem) * (uint32_t)seg.iters : 0u;
-        const uint32_t n_here = len >= 2 ? (I - dlast0 < (uint32_t)seg.iters ? I - dlast0 : (uint32_t)seg.iters) : 1u;
-        uint32_t dg[P2_MAX_LEN];
-        {
-            uint32_t rem = S;
-#pragma unroll
-            for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
-                if (t < len - 2) { const uint32_t nx = rem / I; dg[t] = rem - nx * I; rem = nx; }
-                else dg[t] = 0;
-            }
-        }
-        // offset in the segment of the first candidate of the item's first group
-        unsigned long long first_off = len >= 2 ? ((unsigned long long)S * I + dlast0) * I : 0ull;
-        // the stem's state; Sec. 3.5: device i holds column i in every row
-        uint32_t c_rv = all_rows, c_mv = 1u << dev, c_ran = 0, c_visited = 0;
-        int c_rc = RSTEP_OK;
-#pragma unroll
-        for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
-            if (t < len - 2 && c_rc == RSTEP_OK) {
-                const uint32_t ins0 = sdig[dg[t]];
-                const uint32_t shape = sshape[ins0 >> 3];
-                ++c_ran;
-                c_visited += shape >> 16;
-                ++evaluated; evaluated_members += shape >> 16;
-                c_rc = wave_step(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
-            }
-        }
-        if (c_rc == RSTEP_INVALID) {
-            // every candidate of the item stops inside the stem
-            steps += (unsigned long long)(n_here * I) * c_ran;
-            members += (unsigned long long)(n_here * I) * c_visited;
-            continue;
-        }
-        uint32_t item_steps = 0, item_members = 0;   // an item is at most alphabet / 4 groups: these stay below 2^32
-        for (uint32_t gi = 0; gi < n_here; ++gi, first_off += I) {
-            uint32_t rv = c_rv, mv = c_mv;
-            int rc = c_rc;
-            uint32_t g_ran = c_ran, g_visited = c_visited;
-            if (rc == RSTEP_OK && len >= 2) {
-                const uint32_t ins0 = sdig[dlast0 + gi];
-                const uint32_t shape = sshape[ins0 >> 3];
-                ++g_ran;
-                g_visited += shape >> 16;
-                ++evaluated; evaluated_members += shape >> 16;
-                rc = wave_step(rv, mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
-            }
-            if (rc == RSTEP_GIVE_UP) {
-                // the literal engine evaluates (and counts) these candidates from their first instruction
-                for (uint32_t a0 = 0; a0 < I; a0 += kWaveR) {
-                    const uint32_t a = a0 + (uint32_t)lane;
-                    if (a < I) {
-                        const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
-                        if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + first_off + a;
-                    }
-                }
-            } else if (rc == RSTEP_INVALID) {
-                item_steps += I * g_ran;
-                item_members += I * g_visited;
-            } else {
-                // every candidate applies its last instruction
-                item_steps += I * (g_ran + 1u);
-                item_members += I * g_visited + sum_part;
-                // The last instruction matters only through the goal test.  The goal can only come from an
-                // AllReduce on devices that all hold every chunk, from an AllGather on devices whose chunks
-                // all carry every column, or from a Broadcast whose roots (device 0 is one in every pattern)
-                // are at the goal already; ReduceScatter and Reduce leave members short of chunks.
-                // Candidates that pass this test apply their last instruction to a copy of the group's
-                // state, one after the other, again with the wavefront's lanes as devices.
-                const bool rows_full = !__any(dev < R && rv != all_rows);
-                const bool cols_full = !__any(dev < R && mv != all_cols);
-                const bool root_done = (uint32_t)__builtin_amdgcn_readlane((int)(rv ^ all_rows), 0) == 0u &&
-                                       (uint32_t)__builtin_amdgcn_readlane((int)(mv ^ all_cols), 0) == 0u;
-                if (rows_full || cols_full || root_done) {
-                    for (uint32_t a0 = 0; a0 < I; a0 += kWaveR) {
-                        const uint32_t a = a0 + (uint32_t)lane;
-                        const uint32_t my_ins = a < I ? sdig[a] : 0u;
-                        const int my_op = (int)(my_ins & 7u);
-                        const bool may = a < I && ((my_op == OP_AR && rows_full) || (my_op == OP_AG && cols_full) || (my_op == OP_BC && root_done));
-                        bool goal = false;
-                        for (unsigned long long left = __ballot(may); left != 0ull; left &= left - 1ull) {
-                            const int l = __ffsll((long long)left) - 1;
-                            const uint32_t ins0 = sdig[a0 + (uint32_t)l];
-                            const uint32_t shape = sshape[ins0 >> 3];
-                            uint32_t r2 = rv, m2 = mv;
-                            ++evaluated; evaluated_members += shape >> 16;
-                            const int rc2 = wave_step(r2, m2, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3]);
-                            // goal: every device holds every chunk with the columns of the whole group
-                            const bool reached = rc2 == RSTEP_OK && !__any(dev < R && ((r2 ^ all_rows) | (m2 ^ all_cols)) != 0u);
-                            if (lane == l) goal = reached;
-                        }
-                        if (goal) {
-                            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
-                            if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + first_off + a;
-                        }
-                    }
-                }
-            }
-        }
-        steps += item_steps;
-        members += item_members;
-    }
-    if (lane == 0 && (steps | evaluated) != 0ull) {
-        atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
-        atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
-        atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
-        atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
-    }
-}
-
-// Cost of valid programs of small-group queries: one wavefront per program re-runs it with the
-// lanes as devices and adds up the ring alpha-beta step times (hierarchical cost model, see p2.h).
-// The chunk set that sets a group's bytes is the members' common one before an AllReduce-like
-// step, the root's before a Broadcast, the gathered one after an AllGather.  A program whose state
-// leaves the compact form gets NaN costs; the literal cost kernel fills those rows.
-__global__ __launch_bounds__(kWaveR) void k_cost_shared(const DevQuery* __restrict__ queries,
-                                                        const DevPostSeg* __restrict__ segs, int n_segs,
-                                                        const unsigned long long* __restrict__ sorted,
-                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
-    __shared__ uint32_t srows[kRegDevices];          // chunks that set the bytes of the group whose first device is d
-    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
-    const DevQuery& q = queries[seg.query];
-    const int lane = threadIdx.x;
-    const int dev = lane & (kRegDevices - 1);
-    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
-    const unsigned long long idx = sorted[i];
-    const int R = q.R;
-    const uint32_t all_rows = q.k >= 32 ? 0xffffffffu : ((1u << q.k) - 1u);
-    int len = 1;
-    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
-    uint32_t digit[P2_MAX_LEN];
-    {
-        unsigned long long rem = idx - q.base[len];
-        const unsigned long long I = (unsigned long long)q.alphabet;
-#pragma unroll
-        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
-            if (t < len) { const unsigned long long nx = rem / I; digit[t] = (uint32_t)(rem - nx * I); rem = nx; }
-            else digit[t] = 0;
-        }
-    }
-    // Sec. 3.5: device i holds column i in every row
-    uint32_t rv = all_rows, mv = 1u << dev;
-    double sum_alpha = 0.0, sum_beta = 0.0;
-    bool ok = true;
-    p2_program pr;
-    pr.index = idx;
-    pr.len = (uint8_t)len;
-#pragma unroll
-    for (int t = 0; t < P2_MAX_LEN; ++t) {
-        pr.instr[t] = 0;
-        if (t < len) {
-            const uint32_t ins = q.instr_of_digit[digit[t]];
-            const int pid = (int)(ins >> 3), op = (int)(ins & 7u);
-            pr.instr[t] = (uint8_t)(pid * 5 + op);
-            if (ok) {
-                const uint32_t shape = q.reg_shape[pid];
-                const uint32_t before = rv;
-                ok = wave_step(rv, mv, dev, op, (int)(shape & 15u), (int)((shape >> 4) & 15u), q.reg_part[pid]) == RSTEP_OK;
-                if (ok) {
-                    __syncthreads();
-                    if (lane < kRegDevices) srows[lane] = (uint32_t)__popc(op == OP_AG ? rv : before);
-                    __syncthreads();
-                    // bandwidth term: the most loaded uplink
-                    const DevPattern& P = q.pat[pid];
-                    double best = 0.0;
-                    for (int row = P.row_begin + lane; row < P.row_end; row += kWaveR) {
-                        long long dot = 0;
-                        for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
-                            const uint32_t ent = q.entries[e];
-                            dot += (long long)entry_cnt(ent) * (long long)srows[entry_base(ent)];
-                        }
-                        best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
-                    }
-                    for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWaveR));
-                    const double gm1 = (double)(P.g - 1);
-                    const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
-                    const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)P.g : (op == OP_RS || op == OP_AG) ? gm1 / (double)P.g : 1.0;
-                    sum_alpha += ring_steps * q.alpha[P.span_level];
-                    sum_beta += (mult / (double)q.k) * best;
-                }
-            }
-        }
-    }
-    (void)R;
-    if (lane == 0) out_prog[i] = pr;
-    if (lane < q.n_msg)
-        out_cost[i * q.n_msg + lane] = ok ? sum_alpha + q.msg_bytes[lane] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
-}
-
 inline int exact_log2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -796,9 +449,9 @@ inline int exact_log2(int v) {
 
 }  // namespace
 
-int reg_shape_of(int g, int s, int master) {
+int reg_shape_of(int g, int s, int master, int max_bits) {
     const int lg = exact_log2(g), ls = exact_log2(s);
-    if (lg < 1 || ls < 0 || lg + ls > 5) return -1;
+    if (lg < 1 || ls < 0 || lg + ls > max_bits) return -1;
     return lg | (ls << 4) | ((master ? 1 : 0) << 8);
 }
 
@@ -806,20 +459,6 @@ hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int
                             hipStream_t stream) {
     if (n_segs == 0 || total_blocks == 0) return hipSuccess;
     hipLaunchKernelGGL(k_eval_regs, dim3(total_blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs);
-    return hipGetLastError();
-}
-
-hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
-                              int n_shares, unsigned grid, hipStream_t stream) {
-    if (n_segs == 0 || n_shares == 0 || grid == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_eval_shared, dim3(grid), dim3(kWaveR), 0, stream, queries, segs, n_segs, shares, n_shares);
-    return hipGetLastError();
-}
-
-hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                              const unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream) {
-    if (n_segs == 0 || blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_cost_shared, dim3(blocks), dim3(kWaveR), 0, stream, queries, segs, n_segs, sorted, progs, costs);
     return hipGetLastError();
 }
 

@@ -1,0 +1,447 @@
+// Shared-prefix engine: reduction groups of at most 64 devices, patterns whose group size g and
+// stride s are powers of two (every pattern of a hierarchy with power-of-two levels).
+//
+// Same state form as p2_compact.hip -- per device one chunk set and one contribution mask -- but
+// held by the wavefront as a whole: lane d plays device d (with at most 32 devices, lane d + 32
+// mirrors lane d) and keeps that device's pair in registers.  The members of a group differ exactly
+// in bits [log2 s, log2 s + log2 g) of the device number, so a rule is a sequence of stages, one
+// per such bit J, each a lane exchange with lane d ^ 2^J:
+//   AllReduce-like : union of the masks along each bit; the two sides of every pair must hold the
+//                    same chunks and disjoint masks (the sides' running unions are disjoint at
+//                    every stage iff all members are pairwise disjoint).
+//   ReduceScatter  : then the member of rank p keeps the p-th block of the chunks.
+//   Reduce         : then every member that has one of the bits set is cleared.
+//   AllGather      : union of the chunk sets along each bit, sides disjoint; nobody empty.
+//   Broadcast      : binomial tree from the member with all bits clear; a member is compared with
+//                    the root's pair right before it takes it.
+//
+// Candidates of one length are numbered prefix * alphabet + last instruction, so the `alphabet`
+// candidates of a group (same first len-1 instructions) are consecutive, and so are the groups of
+// a stem (same first len-2 instructions).  The state after a prefix is the same for the whole
+// group, so it is computed once per group, the stem's part of it once per work item; a group whose
+// stem or prefix is invalid is settled for all its candidates at once.  A candidate is still
+// resolved individually: under a valid prefix it applies its own last instruction where that can
+// reach the goal.
+#include "p2_compact_dev.h"
+
+namespace p2 {
+
+namespace {
+
+constexpr int kSegCache = 512;       // segments whose first items the evaluation kernel keeps in LDS
+
+enum : int { WSTEP_INVALID = 0, WSTEP_OK = 1, WSTEP_GIVE_UP = 2 };
+
+template <int N>
+__device__ __forceinline__ Words<N> exchange(const Words<N>& a, int lane_xor) {
+    Words<N> o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o.w[i] = (uint32_t)__shfl_xor((int)a.w[i], lane_xor, kWave);
+    return o;
+}
+template <int N>
+__device__ __forceinline__ void unite(Words<N>& a, const Words<N>& b) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) a.w[i] |= b.w[i];
+}
+template <int N>
+__device__ __forceinline__ void clear(Words<N>& a) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) a.w[i] = 0u;
+}
+
+// One instruction on the wavefront-held state (rv, mv: pair of device `dev` = lane modulo 32 or 64).
+// All lanes are active and all arguments but rv, mv, dev are wave-uniform.  lg, ls: log2 of group
+// size and stride; part: bit d set iff device d takes part; devs: 32 or 64.
+template <int KW, int MW>
+__device__ __forceinline__ int wave_step(Words<KW>& rv, Words<MW>& mv, int dev, int op, int lg, int ls,
+                                         unsigned long long part, int devs) {
+    const int gm1 = (1 << lg) - 1;
+    const uint32_t gmask = (uint32_t)gm1 << ls;
+    const bool in = ((part >> dev) & 1ull) != 0ull;
+    bool bad = false;
+    if (op == OP_AR || op == OP_RS || op == OP_RD) {
+        // same chunks on every member, no contribution reduced twice: union of the masks along each bit
+        for (int J = ls; J < ls + lg; ++J) {
+            const Words<KW> pr = exchange(rv, 1 << J);
+            const Words<MW> pm = exchange(mv, 1 << J);
+            bad |= in && ((fold_xor(rv, pr) | fold_and(mv, pm)) != 0u);
+            if (in) unite(mv, pm);
+        }
+        if (__any(bad)) return WSTEP_INVALID;
+        if (!__any(in && fold_or(rv) != 0u)) return WSTEP_INVALID;      // only groups of empty devices: nothing changes
+        if (op == OP_RS) {
+            // the member of rank p keeps the p-th block of the chunks in ascending order
+            const int c = popcount(rv);
+            const int per = c >> lg, p = (dev >> ls) & gm1;
+            bad = in && (c & gm1) != 0;
+            const Words<KW> upto = lowest_n(rv, (p + 1) * per), below = lowest_n(rv, p * per);
+            if (in) {
+#pragma unroll
+                for (int i = 0; i < KW; ++i) rv.w[i] = upto.w[i] & ~below.w[i];
+            }
+            if (__any(bad)) return WSTEP_INVALID;
+        } else if (op == OP_RD) {
+            if (in && ((uint32_t)dev & gmask) != 0u) { clear(rv); clear(mv); }
+        }
+        return WSTEP_OK;
+    }
+    if (op == OP_AG) {
+        // nobody empty, every chunk held once: union of the chunk sets along each bit
+        if (__any(in && fold_or(rv) == 0u)) return WSTEP_INVALID;
+        bool differs = false;
+        for (int J = ls; J < ls + lg; ++J) {
+            const Words<KW> pr = exchange(rv, 1 << J);
+            const Words<MW> pm = exchange(mv, 1 << J);
+            bad |= in && fold_and(rv, pr) != 0u;
+            differs |= in && fold_xor(mv, pm) != 0u;
+            if (in) unite(rv, pr);
+        }
+        if (__any(bad)) return WSTEP_INVALID;
+        return __any(differs) ? WSTEP_GIVE_UP : WSTEP_OK;      // rows with different column sets leave this form
+    }
+    // Broadcast as a binomial tree from the member with all group bits clear: a member is compared
+    // with the root's pair right before it takes it
+    bool neq = false;
+    for (int J = ls; J < ls + lg; ++J) {
+        const Words<KW> pr = exchange(rv, 1 << J);
+        const Words<MW> pm = exchange(mv, 1 << J);
+        const bool takes = in && ((dev >> J) & 1) != 0 && ((uint32_t)dev & gmask & (~0u << (J + 1))) == 0u;
+        if (takes) {
+            bad |= (fold_andn(rv, pr) | fold_andn(mv, pm)) != 0u;
+            neq |= (fold_xor(rv, pr) | fold_xor(mv, pm)) != 0u;
+            rv = pr;
+            mv = pm;
+        }
+    }
+    if (__any(bad)) return WSTEP_INVALID;
+    // in every group some member must have differed from the root: fold the flags onto the roots' bits
+    const unsigned long long low = devs >= 64 ? ~0ull : ((1ull << devs) - 1ull);
+    unsigned long long flags = __ballot(neq) & low;
+    const unsigned long long roots = __ballot(in && ((uint32_t)dev & gmask) == 0u) & low;
+    for (int J = ls; J < ls + lg; ++J) flags |= flags >> (1u << J);
+    return (~flags & roots) != 0ull ? WSTEP_INVALID : WSTEP_OK;
+}
+
+// A work item is seg.iters consecutive groups of one stem (a length-1 segment is a single item).
+// Every query has a share of the grid's blocks in proportion to its items; block j of n walks the
+// query's items j, j + n, ..., so the items of a valid stem, which are the expensive ones, go to
+// different blocks.  Lane a holds the candidate of a group whose last instruction has digit a
+// (a + 64 in a second pass for alphabets above 64).
+template <int KW, int MW>
+__global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restrict__ queries,
+                                                       const DevSegment* __restrict__ segs, int n_segs,
+                                                       const DevShare* __restrict__ shares, int n_shares) {
+    __shared__ uint16_t sdig[kMaxPatterns * 5];              // digit -> (pattern id << 3) | op
+    __shared__ uint32_t sshape[kMaxPatterns];                // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
+    __shared__ unsigned long long spart[kMaxPatterns];       // pattern id -> bit d set iff device d takes part
+    __shared__ uint32_t sfirst[kSegCache];                   // first item of every segment, where the table fits
+    const int lane = threadIdx.x;
+    const bool cached = n_segs <= kSegCache;
+    if (cached) {
+        for (int i = lane; i < n_segs; i += kWave) sfirst[i] = segs[i].first_block;
+        __syncthreads();
+    }
+    // the query this block works for
+    DevShare sh;
+    {
+        int a = 0, b = n_shares - 1;                 // last share whose first_block <= blockIdx.x
+        while (a < b) {
+            const int mid = (a + b + 1) >> 1;
+            if (shares[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
+        }
+        sh = shares[a];
+    }
+    DevSegment seg;
+    seg.first_block = 0; seg.query = -1; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
+    uint32_t next_first = 0;                         // first item of the next segment
+    const DevQuery* qp = nullptr;
+    int len = 1, R = 1, devs = 32, dev = lane & 31;
+    uint32_t I = 1;
+    Words<KW> all_rows;
+    Words<MW> all_cols;
+    clear(all_rows); clear(all_cols);
+    uint32_t sum_part = 0;                           // participating devices summed over the alphabet
+    uint32_t items_per_stem = 1;
+    unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
+    const uint32_t end_item = sh.first_item + sh.n_items;
+    for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
+        if (qp == nullptr || item >= next_first) {
+            int a = 0, b = n_segs - 1;               // last segment whose first_block <= item
+            while (a < b) {
+                const int mid = (a + b + 1) >> 1;
+                if ((cached ? sfirst[mid] : segs[mid].first_block) <= item) a = mid; else b = mid - 1;
+            }
+            const int old_query = seg.query;
+            seg = segs[a];
+            next_first = a + 1 < n_segs ? (cached ? sfirst[a + 1] : segs[a + 1].first_block) : 0xffffffffu;
+            if (seg.query != old_query) {
+                // hand the finished query its counts, then load the new query's tables
+                if (lane == 0 && (steps | evaluated) != 0ull) {
+                    atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
+                    atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
+                    atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
+                    atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
+                }
+                steps = 0; members = 0; evaluated = 0; evaluated_members = 0;
+                qp = queries + seg.query;
+                __syncthreads();
+                for (int i = lane; i < qp->n_patterns; i += kWave) { sshape[i] = qp->reg_shape[i]; spart[i] = qp->reg_part[i]; }
+                for (int i = lane; i < qp->alphabet; i += kWave) sdig[i] = qp->instr_of_digit[i];
+                __syncthreads();
+                R = qp->R;
+                devs = R > 32 ? 64 : 32;
+                dev = lane & (devs - 1);
+                I = (uint32_t)qp->alphabet;
+                all_rows = full_mask<KW>(qp->k);
+                all_cols = full_mask<MW>(R);
+                sum_part = qp->reg_sum_part;
+            }
+            len = seg.len;
+            items_per_stem = len >= 2 ? (I + (uint32_t)seg.iters - 1u) / (uint32_t)seg.iters : 1u;
+        }
+        const DevQuery& q = *qp;
+        // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
+        // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
+        const uint32_t rel = item - seg.first_block;
+        const uint32_t S = rel / items_per_stem;
+        const uint32_t dlast0 = len >= 2 ? (rel - S * items_per_stem) * (uint32_t)seg.iters : 0u;
+        const uint32_t n_here = len >= 2 ? (I - dlast0 < (uint32_t)seg.iters ? I - dlast0 : (uint32_t)seg.iters) : 1u;
+        uint32_t dg[P2_MAX_LEN];
+        {
+            uint32_t rem = S;
+#pragma unroll
+            for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
+                if (t < len - 2) { const uint32_t nx = rem / I; dg[t] = rem - nx * I; rem = nx; }
+                else dg[t] = 0;
+            }
+        }
+        // offset in the segment of the first candidate of the item's first group
+        unsigned long long first_off = len >= 2 ? ((unsigned long long)S * I + dlast0) * I : 0ull;
+        // the stem's state; Sec. 3.5: device i holds column i in every row
+        Words<KW> c_rv = all_rows;
+        Words<MW> c_mv;
+#pragma unroll
+        for (int i = 0; i < MW; ++i) c_mv.w[i] = (i == (dev >> 5)) ? (1u << (dev & 31)) : 0u;
+        uint32_t c_ran = 0, c_visited = 0;
+        int c_rc = WSTEP_OK;
+#pragma unroll
+        for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
+            if (t < len - 2 && c_rc == WSTEP_OK) {
+                const uint32_t ins0 = sdig[dg[t]];
+                const uint32_t shape = sshape[ins0 >> 3];
+                ++c_ran;
+                c_visited += shape >> 16;
+                ++evaluated; evaluated_members += shape >> 16;
+                c_rc = wave_step<KW, MW>(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
+            }
+        }
+        if (c_rc == WSTEP_INVALID) {
+            // every candidate of the item stops inside the stem
+            steps += (unsigned long long)(n_here * I) * c_ran;
+            members += (unsigned long long)(n_here * I) * c_visited;
+            continue;
+        }
+        uint32_t item_steps = 0, item_members = 0;   // an item is at most alphabet / 4 groups: these stay below 2^32
+        for (uint32_t gi = 0; gi < n_here; ++gi, first_off += I) {
+            Words<KW> rv = c_rv;
+            Words<MW> mv = c_mv;
+            int rc = c_rc;
+            uint32_t g_ran = c_ran, g_visited = c_visited;
+            if (rc == WSTEP_OK && len >= 2) {
+                const uint32_t ins0 = sdig[dlast0 + gi];
+                const uint32_t shape = sshape[ins0 >> 3];
+                ++g_ran;
+                g_visited += shape >> 16;
+                ++evaluated; evaluated_members += shape >> 16;
+                rc = wave_step<KW, MW>(rv, mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
+            }
+            if (rc == WSTEP_GIVE_UP) {
+                // the literal engine evaluates (and counts) the group from its first instruction: it gets the
+                // index of the group's first candidate
+                if (lane == 0) {
+                    const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
+                    if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + first_off;
+                }
+            } else if (rc == WSTEP_INVALID) {
+                item_steps += I * g_ran;
+                item_members += I * g_visited;
+            } else {
+                // every candidate applies its last instruction
+                item_steps += I * (g_ran + 1u);
+                item_members += I * g_visited + sum_part;
+                // The last instruction matters only through the goal test.  The goal can only come from an
+                // AllReduce on devices that all hold every chunk, from an AllGather on devices whose chunks
+                // all carry every column, or from a Broadcast whose roots (device 0 is one in every pattern)
+                // are at the goal already; ReduceScatter and Reduce leave members short of chunks.
+                // Candidates that pass this test apply their last instruction to a copy of the group's
+                // state, one after the other, again with the wavefront's lanes as devices.
+                const uint32_t rows_off = fold_xor(rv, all_rows), cols_off = fold_xor(mv, all_cols);
+                const bool rows_full = !__any(dev < R && rows_off != 0u);
+                const bool cols_full = !__any(dev < R && cols_off != 0u);
+                const bool root_done = (uint32_t)__builtin_amdgcn_readfirstlane((int)(rows_off | cols_off)) == 0u;   // lane 0 is device 0
+                if (rows_full || cols_full || root_done) {
+                    for (uint32_t a0 = 0; a0 < I; a0 += kWave) {
+                        const uint32_t a = a0 + (uint32_t)lane;
+                        const uint32_t my_ins = a < I ? sdig[a] : 0u;
+                        const int my_op = (int)(my_ins & 7u);
+                        const bool may = a < I && ((my_op == OP_AR && rows_full) || (my_op == OP_AG && cols_full) || (my_op == OP_BC && root_done));
+                        bool goal = false;
+                        for (unsigned long long left = __ballot(may); left != 0ull; left &= left - 1ull) {
+                            const int l = __ffsll((long long)left) - 1;
+                            const uint32_t ins0 = sdig[a0 + (uint32_t)l];
+                            const uint32_t shape = sshape[ins0 >> 3];
+                            Words<KW> r2 = rv;
+                            Words<MW> m2 = mv;
+                            ++evaluated; evaluated_members += shape >> 16;
+                            const int rc2 = wave_step<KW, MW>(r2, m2, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
+                            // goal: every device holds every chunk with the columns of the whole group
+                            const bool reached = rc2 == WSTEP_OK && !__any(dev < R && (fold_xor(r2, all_rows) | fold_xor(m2, all_cols)) != 0u);
+                            if (lane == l) goal = reached;
+                        }
+                        if (goal) {
+                            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+                            if (pos < q.valid_cap) q.valid_idx[pos] = seg.first_index + first_off + a;
+                        }
+                    }
+                }
+            }
+        }
+        steps += item_steps;
+        members += item_members;
+    }
+    if (lane == 0 && (steps | evaluated) != 0ull) {
+        atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
+        atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
+        atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
+        atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
+    }
+}
+
+// Cost of valid programs: one wavefront per program re-runs it with the lanes as devices and adds up
+// the ring alpha-beta step times (hierarchical cost model, see p2.h).  The chunk set that sets a
+// group's bytes is the members' common one before an AllReduce-like step, the root's before a
+// Broadcast, the gathered one after an AllGather.  A program whose state leaves the compact form
+// gets NaN costs; the literal cost kernel fills those rows.
+template <int KW, int MW>
+__global__ __launch_bounds__(kWave) void k_cost_shared(const DevQuery* __restrict__ queries,
+                                                       const DevPostSeg* __restrict__ segs, int n_segs,
+                                                       const unsigned long long* __restrict__ sorted,
+                                                       p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
+    __shared__ uint32_t srows[kWave];                // chunks that set the bytes of the group whose first device is d
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x;
+    const int devs = q.R > 32 ? 64 : 32;
+    const int dev = lane & (devs - 1);
+    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
+    const unsigned long long idx = sorted[i];
+    int len = 1;
+    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
+    uint32_t digit[P2_MAX_LEN];
+    {
+        unsigned long long rem = idx - q.base[len];
+        const unsigned long long I = (unsigned long long)q.alphabet;
+#pragma unroll
+        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
+            if (t < len) { const unsigned long long nx = rem / I; digit[t] = (uint32_t)(rem - nx * I); rem = nx; }
+            else digit[t] = 0;
+        }
+    }
+    // Sec. 3.5: device i holds column i in every row
+    Words<KW> rv = full_mask<KW>(q.k);
+    Words<MW> mv;
+#pragma unroll
+    for (int w = 0; w < MW; ++w) mv.w[w] = (w == (dev >> 5)) ? (1u << (dev & 31)) : 0u;
+    double sum_alpha = 0.0, sum_beta = 0.0;
+    bool ok = true;
+    p2_program pr;
+    pr.index = idx;
+    pr.len = (uint8_t)len;
+#pragma unroll
+    for (int t = 0; t < P2_MAX_LEN; ++t) {
+        pr.instr[t] = 0;
+        if (t < len) {
+            const uint32_t ins = q.instr_of_digit[digit[t]];
+            const int pid = (int)(ins >> 3), op = (int)(ins & 7u);
+            pr.instr[t] = (uint8_t)(pid * 5 + op);
+            if (ok) {
+                const uint32_t shape = q.reg_shape[pid];
+                const int before = popcount(rv);
+                ok = wave_step<KW, MW>(rv, mv, dev, op, (int)(shape & 15u), (int)((shape >> 4) & 15u), q.reg_part[pid], devs) == WSTEP_OK;
+                if (ok) {
+                    __syncthreads();
+                    if (lane < devs) srows[lane] = (uint32_t)(op == OP_AG ? popcount(rv) : before);
+                    __syncthreads();
+                    // bandwidth term: the most loaded uplink
+                    const DevPattern& P = q.pat[pid];
+                    double best = 0.0;
+                    for (int row = P.row_begin + lane; row < P.row_end; row += kWave) {
+                        long long dot = 0;
+                        for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
+                            const uint32_t ent = q.entries[e];
+                            dot += (long long)entry_cnt(ent) * (long long)srows[entry_base(ent)];
+                        }
+                        best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+                    }
+                    for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWave));
+                    const double gm1 = (double)(P.g - 1);
+                    const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
+                    const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)P.g : (op == OP_RS || op == OP_AG) ? gm1 / (double)P.g : 1.0;
+                    sum_alpha += ring_steps * q.alpha[P.span_level];
+                    sum_beta += (mult / (double)q.k) * best;
+                }
+            }
+        }
+    }
+    if (lane == 0) out_prog[i] = pr;
+    if (lane < q.n_msg)
+        out_cost[i * q.n_msg + lane] = ok ? sum_alpha + q.msg_bytes[lane] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
+}
+
+inline int word_class_s(int bits) {
+    const int w = (bits + 31) / 32;
+    return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16;
+}
+
+}  // namespace
+
+#define P2_SHARED_DISPATCH(KW, MW, GO)                  \
+    switch (KW * 10 + MW) {                             \
+    case 11: GO(1, 1) break;                            \
+    case 12: GO(1, 2) break;                            \
+    case 21: GO(2, 1) break;                            \
+    case 22: GO(2, 2) break;                            \
+    case 41: GO(4, 1) break;                            \
+    case 42: GO(4, 2) break;                            \
+    case 81: GO(8, 1) break;                            \
+    case 82: GO(8, 2) break;                            \
+    case 161: GO(16, 1) break;                          \
+    case 162: GO(16, 2) break;                          \
+    default: return hipErrorInvalidValue;               \
+    }
+
+hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
+                              int n_shares, unsigned grid, int max_R, int max_k, hipStream_t stream) {
+    if (n_segs == 0 || n_shares == 0 || grid == 0) return hipSuccess;
+    const int KW = word_class_s(max_k), MW = word_class_s(max_R);
+#define P2_GO(KWV, MWV) \
+    hipLaunchKernelGGL((k_eval_shared<KWV, MWV>), dim3(grid), dim3(kWave), 0, stream, queries, segs, n_segs, shares, n_shares);
+    P2_SHARED_DISPATCH(KW, MW, P2_GO)
+#undef P2_GO
+    return hipGetLastError();
+}
+
+hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks, int max_R,
+                              int max_k, const unsigned long long* sorted, p2_program* progs, double* costs,
+                              hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const int KW = word_class_s(max_k), MW = word_class_s(max_R);
+#define P2_GO(KWV, MWV) \
+    hipLaunchKernelGGL((k_cost_shared<KWV, MWV>), dim3(blocks), dim3(kWave), 0, stream, queries, segs, n_segs, sorted, progs, costs);
+    P2_SHARED_DISPATCH(KW, MW, P2_GO)
+#undef P2_GO
+    return hipGetLastError();
+}
+
+}  // namespace p2

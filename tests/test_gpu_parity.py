@@ -254,6 +254,24 @@ def test_config3_every_query(B, oracle, levels):
     assert len(cache) >= 6
 
 
+def test_config3_compact_engine_matches_default(B, oracle):
+    """The default engine on configuration 3 is the shared-prefix engine (64 devices, power-of-two levels);
+    the LDS-resident compact engine, which evaluates every candidate in a lane of its own, gives the same
+    lists, costs and per-candidate step counts."""
+    cfg, queries = queries_of(3, B)
+    mine = [q for q in queries if _levels(q) == 2][:4] + [dict(q, max_len=4) for q in queries if _levels(q) == 3][:3]
+    auto = B.p2_synthesize_batch(mine, cfg["msg_bytes"])
+    flat = B.p2_synthesize_batch([dict(q, engine=2) for q in mine], cfg["msg_bytes"])
+    for a, b in zip(auto, flat):
+        assert a["stats"]["engine"] == 5 and b["stats"]["engine"] == 2
+        assert a["programs"]["index"].tolist() == b["programs"]["index"].tolist()
+        assert np.allclose(a["cost"], b["cost"], rtol=RTOL)
+        assert a["stats"]["steps_executed"] == b["stats"]["steps_executed"]
+        assert a["stats"]["steps_evaluated"] < b["stats"]["steps_evaluated"] == b["stats"]["steps_executed"]
+    _, ora = oracle_result(oracle, mine[0], cfg["msg_bytes"])
+    assert_same(auto[0], ora, 1)
+
+
 def test_config3_literal_engine_small_queries(B, oracle):
     cfg, queries = queries_of(3, B)
     mine = [dict(q, engine=1) for q in queries if _levels(q) == 1][:6] + \
