@@ -67,20 +67,23 @@ int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int3
 
 /* Evaluation engines.  All give identical results; they differ in the state they keep. */
 #define P2_ENGINE_AUTO 0      /* shared-prefix engine where it applies, else the compact engine; the
-                                 literal engine for the candidates they cannot hold; every
-                                 candidate index is resolved by a lane of its own                 */
+                                 literal engine for the candidates they cannot hold; the frontier
+                                 engine above 2^30 candidates                                     */
 #define P2_ENGINE_LITERAL 1   /* R x k masks of R bits per candidate in LDS, one wavefront each   */
-#define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask               */
+#define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask, in LDS; one
+                                 candidate per lane                                               */
 #define P2_ENGINE_FRONTIER 3  /* enumeration by program size with pruning (Sec. 3.5): only valid
                                  prefixes are extended; AUTO picks it above 2^30 candidates       */
 #define P2_ENGINE_SMALL 4     /* compact form for reduction groups of at most 32 devices, at most
                                  32 chunks and patterns whose group size and stride are powers of
-                                 two: every step is computed in registers; P2_EUNSUPPORTED where
+                                 two: one candidate per lane, every step computed in registers;
+                                 P2_EUNSUPPORTED where it does not apply                          */
+#define P2_ENGINE_SHARED 5    /* reduction groups of at most 64 devices, patterns whose group size
+                                 and stride are powers of two: the instructions that consecutive
+                                 candidates have in common are applied once per wavefront (lanes
+                                 play the devices), each candidate then applies its own last
+                                 instruction where that can reach the goal; P2_EUNSUPPORTED where
                                  it does not apply                                                */
-#define P2_ENGINE_SHARED 5    /* same scope as P2_ENGINE_SMALL; the instructions that the 64
-                                 consecutive candidates of a wavefront have in common are applied
-                                 once per wavefront, each candidate then judges its own last
-                                 instruction                                                      */
 
 typedef struct {
     int32_t n_chunks;    /* k of Sec. 3.2; 0 => number of devices (the paper's choice)           */
