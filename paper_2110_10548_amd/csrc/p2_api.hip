@@ -236,8 +236,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         L.off_segs = off;
         off += align_up(sizeof(DevSegment) * L.segs.size(), 256);
         if (L.kind == 2) {
-            // divide a grid of about 4096 blocks (16 wavefronts per compute unit) among the queries by their items
-            const unsigned long long target = 4096;
+            // divide a grid of about 8192 blocks (32 wavefronts per compute unit) among the queries by their items
+            const unsigned long long target = 8192;
             for (size_t a = 0; a < L.segs.size();) {
                 size_t b = a;
                 while (b < L.segs.size() && L.segs[b].query == L.segs[a].query) ++b;

@@ -254,6 +254,21 @@ def test_config3_every_query(B, oracle, levels):
     assert len(cache) >= 6
 
 
+@pytest.mark.parametrize("engine", [5, 2], ids=["shared", "compact"])
+def test_alphabet_above_one_wavefront(B, oracle, engine):
+    """Four non-unit levels give 16 patterns x 5 rules = 80 instructions, more than the 64 lanes of a
+    wavefront: the shared-prefix engine walks a group's candidates in two passes."""
+    q = dict(card=[2, 2, 2, 2], axes=[2, 2, 2, 2], placement=[[2, 1, 1, 1], [1, 2, 1, 1], [1, 1, 2, 1], [1, 1, 1, 2]],
+             reduce_axes=[0, 1, 2, 3], max_len=3, bw=[10e9, 40e9, 100e9, 300e9], alpha=[20e-6, 10e-6, 5e-6, 2e-6], engine=engine)
+    msg = [1.0e6, 2.5e8]
+    res = B.p2_synthesize_batch([q], msg)[0]
+    assert res["stats"]["alphabet"] == 80 and res["stats"]["engine"] == engine
+    oq, ora = oracle_result(oracle, q, msg)
+    assert_same(res, ora, 2)
+    _, _, steps = oq.eval_indices(q["max_len"], start=0, count=oq.num_candidates(q["max_len"]))
+    assert res["stats"]["steps_executed"] == steps
+
+
 def test_config3_compact_engine_matches_default(B, oracle):
     """The default engine on configuration 3 is the shared-prefix engine (64 devices, power-of-two levels);
     the LDS-resident compact engine, which evaluates every candidate in a lane of its own, gives the same
