@@ -102,7 +102,7 @@ def main():
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: candidate evaluation is embarrassingly parallel and this build "
+        print("bench.py measures one GPU: candidate evaluation is embarrassingly parallel and the library "
               "runs on a single MI355X; --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 

@@ -213,6 +213,22 @@ __device__ __forceinline__ bool first_step(uint2* my, int op, int lg, int ls, ui
     for (int j = ls; j < ls + lg; ++j) gcols |= gcols << (1u << j);
     const int per = k >> lg;
     const uint32_t block = per >= 32 ? 0xffffffffu : ((1u << per) - 1u);
+    if (__ballot(1) == ~0ull) {
+        // the whole wavefront is here: lane d works out the pair of device d (mod 32) once, and every
+        // lane then stores the 32 pairs, read from those lanes, into its own candidate's state
+        const int d = (int)(threadIdx.x & (kRegDevices - 1));
+        uint32_t r = all_rows, m = 1u << d;
+        if ((part >> d) & 1u) {
+            const int p = (d >> ls) & gm1;
+            m = gcols << ((uint32_t)d & ~gmask);
+            if (op == OP_RS) r = block << (p * per);
+            else if (op == OP_RD && p != 0) { r = 0u; m = 0u; }
+        }
+#pragma unroll
+        for (int dd = 0; dd < kRegDevices; ++dd)
+            my[dd * kWaveR] = make_uint2((uint32_t)__builtin_amdgcn_readlane((int)r, dd), (uint32_t)__builtin_amdgcn_readlane((int)m, dd));
+        return true;
+    }
 #pragma unroll
     for (int d = 0; d < kRegDevices; ++d) {
         uint32_t r = all_rows, m = 1u << d;
