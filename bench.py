@@ -83,8 +83,21 @@ def cpu_baseline(queries, budget_s=15.0):
         n_one += len(sub)
         if time.time() - t_begin > 2 * budget_s:
             break
+    # the oracle's enumeration by size with pruning (Sec. 3.5), single-threaded, over whole queries: the
+    # CPU counterpart of an engine that settles candidates under an invalid prefix in bulk
+    t_pruned, covered = 0.0, 0
+    for q in queries:
+        if time.time() - t_begin > 3 * budget_s:
+            break
+        oq = p2_oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
+                             n_chunks=q.get("n_chunks", 0))
+        t0 = time.time()
+        oq.synthesize(q["max_len"], q.get("msg_bytes", ()))
+        t_pruned += time.time() - t0
+        covered += oq.num_candidates(q["max_len"])
     return {"value": total / t_all, "unit": "candidates/s", "cores": cores, "kind": "oracle",
             "value_1core": n_one / t_one,
+            "pruned_enumeration_candidates_covered_per_s_1core": covered / t_pruned if t_pruned > 0 else None,
             "sample": "per query the first %d and %d SplitMix64-random candidate indices (the whole space where "
                       "smaller), flat unpruned evaluation from the init state; %d candidates in %.1f s" % (S, S, total, t_all)}
 

@@ -199,6 +199,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         L->max_R = std::max(L->max_R, pl.R);
         L->max_k = std::max(L->max_k, pl.k);
     }
+    // stems (prefixes of len-2 instructions) of all shared-prefix queries of the batch
+    unsigned long long shared_stems = 0;
+    for (int i = 0; i < n_queries; ++i) {
+        const Plan& pl = runs[i].plan;
+        if (!runs[i].shared || runs[i].frontier || pl.n_candidates == 0 || pl.alphabet == 0) continue;
+        for (int len = 2; len <= pl.max_len; ++len)
+            shared_stems += (pl.base[len + 1] - pl.base[len]) / ((unsigned long long)pl.alphabet * (unsigned long long)pl.alphabet);
+    }
     for (auto& L : launches) {
         const int lanes = L.kind != 0 ? 64 : compact_lanes(L.max_R, L.max_k);
         if (lanes == 0) return fail(P2_EUNSUPPORTED, "state too large for the compact engine");
@@ -214,10 +222,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 sg.first_block = (uint32_t)blocks; sg.query = i; sg.len = len;
                 sg.first_index = pl.base[len]; sg.count = count;
                 if (L.kind == 2) {
-                    // shared-prefix kernel: an item is a quarter of the groups under one stem (the first
-                    // len-2 instructions); small items balance the load of its fixed grid
+                    // shared-prefix kernel: an item is a run of groups under one stem (the first len-2
+                    // instructions).  With few stems a stem is cut into four items, which balances the load
+                    // of the fixed grid; with many stems a whole stem is one item, so its state is worked out once
                     const unsigned long long I = (unsigned long long)pl.alphabet;
-                    const unsigned long long per_item = len >= 2 ? (I + 3) / 4 : 1;
+                    const unsigned long long cut = shared_stems >= (1ull << 17) ? 1 : shared_stems >= (1ull << 15) ? 2 : 4;
+                    const unsigned long long per_item = len >= 2 ? (I + cut - 1) / cut : 1;
                     const unsigned long long items_per_stem = len >= 2 ? (I + per_item - 1) / per_item : 1;
                     sg.iters = (int)per_item;
                     blocks += len >= 2 ? (count / (I * I)) * items_per_stem : 1;
