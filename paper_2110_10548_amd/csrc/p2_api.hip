@@ -68,9 +68,9 @@ struct HostBuf {
 
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
-    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, lit_scratch, post;
+    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
     DevBuf f_entries[2], f_states[2], f_literal[2], f_surv, f_surv_literal, f_ctr, f_valid;   // frontier engine
-    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr;
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs;
 };
 thread_local Ctx g_ctx;
 
@@ -97,6 +97,10 @@ int32_t hip_fail(hipError_t e, const char* what) {
     } while (0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Selections over at most this many valid programs go into one launch for the whole batch
+// (one wavefront each); longer lists take the two-stage selection, one query at a time.
+constexpr size_t kTopkJobMax = 8192;
 
 struct QueryRun {
     p2::Plan plan;
@@ -444,15 +448,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             reran = true;
             if (r.shared) {
                 // the shared-prefix engine hands over whole groups (an entry is a group's first candidate)
-                if (front_literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
-                    add_seg(group_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
-                } else {
-                    unsigned nb = 0;
-                    P2_HIP(C.lit_scratch.ensure(literal_scratch_bytes(r.plan.R, r.plan.k, &nb)));
-                    P2_HIP(launch_eval_literal_groups(reinterpret_cast<const DevQuery*>(db + r.off_query), r.plan.R, r.plan.k,
-                                                      static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, hc[i].n_rerun,
-                                                      C.lit_scratch.p, stream));
-                }
+                // (class: mask width, and whether the state fits in LDS)
+                const int fits = front_literal_lds_bytes(r.plan.R, r.plan.k) != 0 ? 1 : 0;
+                add_seg(group_launches, mask_class(r.plan.R) * 2 + fits, r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
             } else if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
                 add_seg(rerun_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
             } else {
@@ -469,6 +467,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             const uint32_t parts = std::min<uint32_t>(8, std::max<uint32_t>(1, 2048 / std::max(1u, total)));
             L.blocks = 0;
             for (auto& sg : L.segs) { sg.per_block = parts; sg.first_block = L.blocks; L.blocks += sg.count * parts; }
+            if (!(L.cls & 1)) {
+                unsigned nb = 0;
+                P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(L.max_R, L.max_k, &nb)));
+            }
         }
         if (!rerun_launches.empty() || !group_launches.empty()) {
             P2_HIP(upload_segs({&rerun_launches, &group_launches}));
@@ -477,7 +479,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                                 L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
             for (auto& L : group_launches)
                 P2_HIP(launch_eval_literal_groups_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
-                                                       L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
+                                                       L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p),
+                                                       (L.cls & 1) ? nullptr : C.lit_scratch.p, stream));
         }
         if (reran) {
             P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
@@ -605,6 +608,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
     size_t pos_off = 0;
     int post_launches = 0;
+    std::vector<DevTopkJob> topk_jobs;
+    int topk_jobs_k = 0;
     // ordering and costing: one launch per kernel and state-size class
     std::vector<PostLaunch> sort_launches, ccost_launches, scost_launches, lcost_launches;
     for (int i = 0; i < n_queries; ++i) {
@@ -671,13 +676,30 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (r.topk > 0) {
             const size_t kk = std::min<size_t>(r.topk, r.n_valid);
             for (int m = 0; m < n_msg; ++m) {
-                post_launches += 2;
-                P2_HIP(launch_topk(costs + m, n_msg, sorted, r.n_valid, r.topk,
-                                   static_cast<long long*>(C.topk_pos.p) + pos_off, C.topk_scratch.p,
-                                   &static_cast<DevCounters*>(C.counters.p)[i].nan_seen, stream));
+                long long* out_pos = static_cast<long long*>(C.topk_pos.p) + pos_off;
+                uint32_t* nan_flag = &static_cast<DevCounters*>(C.counters.p)[i].nan_seen;
+                if (r.n_valid <= kTopkJobMax) {            // short lists: one launch for all of them, below
+                    DevTopkJob J;
+                    J.cost = costs + m; J.index = sorted; J.out_pos = out_pos; J.nan_flag = nan_flag;
+                    J.n = (long long)r.n_valid; J.stride = n_msg; J.k = r.topk; J.pad = 0;
+                    topk_jobs.push_back(J);
+                    topk_jobs_k = std::max(topk_jobs_k, r.topk);
+                } else {
+                    post_launches += 2;
+                    P2_HIP(launch_topk(costs + m, n_msg, sorted, r.n_valid, r.topk, out_pos, C.topk_scratch.p, nan_flag, stream));
+                }
                 pos_off += kk;
             }
         }
+    }
+    if (!topk_jobs.empty()) {
+        const size_t bytes = sizeof(DevTopkJob) * topk_jobs.size();
+        P2_HIP(C.topk_jobs.ensure(bytes));
+        P2_HIP(C.h_topk_jobs.ensure(bytes));
+        std::memcpy(C.h_topk_jobs.p, topk_jobs.data(), bytes);
+        P2_HIP(hipMemcpyAsync(C.topk_jobs.p, C.h_topk_jobs.p, bytes, hipMemcpyHostToDevice, stream));
+        ++post_launches;
+        P2_HIP(launch_topk_jobs(static_cast<const DevTopkJob*>(C.topk_jobs.p), (unsigned)topk_jobs.size(), topk_jobs_k, stream));
     }
     if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[2], stream)); g_prof.last.post_launches = post_launches; }
     P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));

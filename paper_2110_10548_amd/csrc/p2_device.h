@@ -145,13 +145,14 @@ hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long
 // Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
-// Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate):
-// one block per entry of each segment, or, for one query, blocks striding over n entries with the state
-// in a global buffer when it does not fit in LDS (front_literal_lds_bytes).
-hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                           int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
-hipError_t launch_eval_literal_groups(const DevQuery* q, int R, int k, const unsigned long long* list, uint32_t n,
-                                      void* gscratch, hipStream_t stream);
+// Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate).
+// A unit is one (entry, part) pair of a segment (per_block = parts of an entry; first_block = first unit).
+// States that fit in LDS (front_literal_lds_bytes of max_R, max_k): one block per unit.  Otherwise the
+// blocks stride over the units, each with a slice of gscratch (literal_group_scratch_bytes).
+size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks);
+hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned units,
+                                           int max_R, int max_k, const unsigned long long* list, void* gscratch,
+                                           hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.
 hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
@@ -202,6 +203,21 @@ hipError_t launch_front_materialize(const DevQuery* q, uint32_t query, int R, in
 hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry* entries, const FrontSurvivor* surv,
                              uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
                              unsigned long long* valid_out, FrontCounters* ctr, hipStream_t stream);
+
+// One selection of launch_topk_jobs: the k best of (cost[i * stride], index[i]), i < n, ties by index;
+// positions go to out_pos[min(k, n)], nan_flag is set to 1 when a cost is NaN.  All device pointers.
+struct DevTopkJob {
+    const double* cost;
+    const unsigned long long* index;
+    long long* out_pos;
+    uint32_t* nan_flag;
+    long long n;
+    long long stride;
+    int k;
+    int pad;
+};
+// Block b of the launch does jobs[b] alone: meant for many selections of a few thousand entries each.
+hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream);
 
 // Top-k of (cost[i * stride], index[i]) over i < n: positions into out_pos[min(k, n)].
 // scratch: device buffer of topk_scratch_bytes(n, k) bytes.  nan_flag: device uint32 set to 1 on NaN.

@@ -660,58 +660,39 @@ __device__ inline void literal_group(const DevQuery& q, unsigned long long idx0,
     }
 }
 
-// Groups of many queries (states that fit in LDS).
+// Groups of many queries.  A unit of work is one (list entry, part) pair; blocks stride over the units.
+// States that fit in LDS: one unit per block.  Larger states: a fixed grid, each block with its own
+// slice of a global buffer.
 template <int MW>
 __global__ __launch_bounds__(kWave) void k_eval_literal_groups_list(const DevQuery* __restrict__ queries,
                                                                     const DevPostSeg* __restrict__ segs, int n_segs,
-                                                                    const unsigned long long* __restrict__ list) {
+                                                                    const unsigned long long* __restrict__ list,
+                                                                    unsigned n_units, uint32_t* __restrict__ gscratch,
+                                                                    unsigned long long gwords) {
     extern __shared__ uint32_t lds[];
-    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
-    const DevQuery& q = queries[seg.query];
     const int lane = threadIdx.x;
-    const LitLds L = carve(lds, q.R, q.k, MW);
-    const FrontLit X = carve_front(L.flags + 4, q.k);
-    uint32_t full[MW];
+    uint32_t* const mem = gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds;
+    for (unsigned unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
+        const DevPostSeg seg = find_post_seg(segs, n_segs, unit);
+        const DevQuery& q = queries[seg.query];
+        const LitLds L = carve(mem, q.R, q.k, MW);
+        const FrontLit X = carve_front(L.flags + 4, q.k);
+        uint32_t full[MW];
 #pragma unroll
-    for (int w = 0; w < MW; ++w) {
-        const int bits = q.R - 32 * w;
-        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
-    }
-    unsigned long long steps = 0, members = 0;
-    // seg.per_block blocks share one list entry, each judging its share of the last instructions
-    const uint32_t local = blockIdx.x - seg.first_block;
-    literal_group<MW>(q, list[seg.in_off + local / seg.per_block], L, X, full, lane, (int)(local % seg.per_block), (int)seg.per_block,
-                      steps, members);
-    if (lane == 0 && steps) {
-        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
-        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
-    }
-}
-
-// Groups of one query, blocks striding over the list; the state may live in a global buffer.
-template <int MW>
-__global__ __launch_bounds__(kWave) void k_eval_literal_groups(const DevQuery* __restrict__ qp,
-                                                               const unsigned long long* __restrict__ list, uint32_t n,
-                                                               uint32_t* __restrict__ gscratch, unsigned long long gwords) {
-    extern __shared__ uint32_t lds[];
-    const DevQuery& q = *qp;
-    const int lane = threadIdx.x;
-    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
-    const FrontLit X = carve_front(L.flags + 4, q.k);
-    uint32_t full[MW];
-#pragma unroll
-    for (int w = 0; w < MW; ++w) {
-        const int bits = q.R - 32 * w;
-        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
-    }
-    unsigned long long steps = 0, members = 0;
-    for (uint32_t e = blockIdx.x; e < n; e += gridDim.x) {
-        literal_group<MW>(q, list[e], L, X, full, lane, 0, 1, steps, members);
+        for (int w = 0; w < MW; ++w) {
+            const int bits = q.R - 32 * w;
+            full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+        }
+        unsigned long long steps = 0, members = 0;
+        // seg.per_block units share one list entry, each judging its share of the last instructions
+        const uint32_t local = unit - seg.first_block;
+        literal_group<MW>(q, list[seg.in_off + local / seg.per_block], L, X, full, lane, (int)(local % seg.per_block),
+                          (int)seg.per_block, steps, members);
+        if (lane == 0 && steps) {
+            atomicAdd(&q.counters->steps[unit % kCounterStripes], steps);
+            atomicAdd(&q.counters->members[unit % kCounterStripes], members);
+        }
         __syncthreads();
-    }
-    if (lane == 0 && steps) {
-        atomicAdd(&q.counters->steps[blockIdx.x % kCounterStripes], steps);
-        atomicAdd(&q.counters->members[blockIdx.x % kCounterStripes], members);
     }
 }
 
@@ -897,47 +878,36 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     return hipGetLastError();
 }
 
-hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                           int max_R, int max_k, const unsigned long long* list, hipStream_t stream) {
-    if (n_segs == 0 || blocks == 0) return hipSuccess;
-    const size_t lds = front_literal_lds_bytes(max_R, max_k);
-    if (lds == 0) return hipErrorInvalidValue;
-    hipError_t e = hipSuccess;
-#define P2_LAUNCH(MWV)                                                                                         \
-    e = allow_big_lds(k_eval_literal_groups_list<MWV>, lds);                                                   \
-    if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_eval_literal_groups_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, list);
-    switch (mask_words(max_R)) {
-    case 1: P2_LAUNCH(1) break;
-    case 2: P2_LAUNCH(2) break;
-    case 4: P2_LAUNCH(4) break;
-    case 8: P2_LAUNCH(8) break;
-    default: P2_LAUNCH(16) break;
-    }
-#undef P2_LAUNCH
-    if (e != hipSuccess) return e;
-    return hipGetLastError();
+size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
+    // group states that do not fit in LDS: up to 4096 blocks, each with its own global slice
+    LitLayout lay(max_R, max_k, mask_words(max_R));
+    const size_t per = ((size_t)(lay.total_words() + front_lit_words(max_k)) * 4 + 255) / 256 * 256;
+    unsigned b = 4096;
+    while (b > 1 && per * b > ((size_t)8 << 30)) b >>= 1;
+    *blocks = b;
+    return per * b;
 }
 
-hipError_t launch_eval_literal_groups(const DevQuery* q, int R, int k, const unsigned long long* list, uint32_t n,
-                                      void* gscratch, hipStream_t stream) {
-    if (n == 0) return hipSuccess;
-    size_t lds = front_literal_lds_bytes(R, k);
-    unsigned blocks = n < 16384u ? n : 16384u;
+hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned units,
+                                           int max_R, int max_k, const unsigned long long* list, void* gscratch,
+                                           hipStream_t stream) {
+    if (n_segs == 0 || units == 0) return hipSuccess;
+    size_t lds = front_literal_lds_bytes(max_R, max_k);
+    unsigned blocks = units;
     unsigned long long gwords = 0;
     if (lds == 0) {
         if (!gscratch) return hipErrorInvalidValue;
         unsigned nb = 0;
-        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
-        blocks = nb < n ? nb : n;
+        gwords = literal_group_scratch_bytes(max_R, max_k, &nb) / nb / 4;
+        blocks = nb < units ? nb : units;
     } else gscratch = nullptr;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
-    e = allow_big_lds(k_eval_literal_groups<MWV>, lds);                                                        \
+    e = allow_big_lds(k_eval_literal_groups_list<MWV>, lds);                                                   \
     if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_eval_literal_groups<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, list, n,     \
-                           static_cast<uint32_t*>(gscratch), gwords);
-    switch (mask_words(R)) {
+        hipLaunchKernelGGL(k_eval_literal_groups_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, \
+                           list, units, static_cast<uint32_t*>(gscratch), gwords);
+    switch (mask_words(max_R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
     case 4: P2_LAUNCH(4) break;

@@ -150,6 +150,32 @@ __global__ __launch_bounds__(kWave) void k_topk_merge(const double* __restrict__
     for (int j = lane; j < n_out; j += kWave) out_pos[j] = j < cnt ? L.pos[j] : -1ll;
 }
 
+// Many small selections in one launch: block b does job b from start to end (the list of K best of
+// jobs[b].n entries) and writes the positions itself.
+__global__ __launch_bounds__(kWave) void k_topk_jobs(const DevTopkJob* __restrict__ jobs) {
+    extern __shared__ unsigned char raw[];
+    const DevTopkJob J = jobs[blockIdx.x];
+    const int K = J.k;
+    TopList L;
+    L.c = reinterpret_cast<double*>(raw);
+    L.idx = reinterpret_cast<unsigned long long*>(L.c + K);
+    L.pos = reinterpret_cast<long long*>(L.idx + K);
+    const int lane = threadIdx.x;
+    int cnt = 0;
+    bool nan = false;
+    for (long long t0 = 0; t0 < J.n; t0 += kWave) {
+        const long long i = t0 + lane;
+        Item mine{0.0, 0ull, i};
+        const bool valid = i < J.n;
+        if (valid) { mine.c = J.cost[i * J.stride]; mine.idx = J.index[i]; nan |= mine.c != mine.c; }
+        list_offer(L, cnt, K, mine, valid && !(mine.c != mine.c), lane);
+    }
+    if (nan) atomicOr(J.nan_flag, 1u);
+    __syncthreads();
+    const long long n_out = K < J.n ? K : J.n;
+    for (int j = lane; j < n_out; j += kWave) J.out_pos[j] = j < cnt ? L.pos[j] : -1ll;
+}
+
 inline unsigned topk_blocks(long long n) {
     long long b = (n + 64 * 16 - 1) / (64 * 16);      // at least 16 tiles per block
     if (b < 1) b = 1;
@@ -167,6 +193,12 @@ hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long
 }
 
 size_t topk_scratch_bytes(long long n, int k) { return (size_t)topk_blocks(n) * (size_t)k * 24; }
+
+hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream) {
+    if (n_jobs == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_topk_jobs, dim3(n_jobs), dim3(kWave), (size_t)max_k * 24, stream, jobs);
+    return hipGetLastError();
+}
 
 hipError_t launch_topk(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
                        long long* out_pos, void* scratch, uint32_t* nan_flag, hipStream_t stream) {
