@@ -41,7 +41,7 @@ def measured_traffic(kernel):
     None when there is none or the kernel source has changed since the counters were taken."""
     path = os.path.join(ROOT, "profiles", "%s_cfg2_traffic.json" % kernel)
     src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc",
-                       {"k_eval_shared": "p2_regs.hip", "k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
+                       {"k_eval_shared": "p2_shared.hip", "k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
     try:
         rec = json.load(open(path))
         if rec["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
