@@ -127,6 +127,7 @@ typedef struct {
     p2o_pattern pat[MAXPAT];
     uint32_t form_mask, op_mask;
     int n_ops, ops[5];            /* enabled collectives in the paper's order              */
+    int algo;                     /* cost model of AllReduce: 0 ring, 1 tree (Sec. 4)      */
     char err[256];
 } p2o_query;
 
@@ -382,6 +383,12 @@ int p2o_hierarchy_of_matrix(int m, int n, const int32_t *x, const int32_t *is_re
     return c;
 }
 
+int p2o_set_algo(p2o_query *q, int algo)
+{
+    if (algo != 0 && algo != 1) return -1;
+    q->algo = algo;
+    return 0;
+}
 int p2o_num_devices(const p2o_query *q) { return q->D; }
 int p2o_num_chunks(const p2o_query *q) { return q->k; }
 int p2o_num_patterns(const p2o_query *q) { return q->n_patterns; }
@@ -587,7 +594,21 @@ static int apply_group(const p2o_query *q, int op, const int *mem, int g,
  *              its bytes through that uplink once; T_beta = max over units of
  *              (sum of such bytes) / bw[j]
  *   step time = T_alpha + T_beta.  Groups whose members are all empty cost nothing.
+ *
+ * Tree model (algo 1; Sec. 4 runs the library's ring and tree algorithms, the tree being the
+ * two-tree scheme of its reference, which that library uses for AllReduce only; again a stated
+ * reading, the paper prints no formula): an AllReduce goes up a binary tree and down again,
+ *     AllReduce      2 * ceil(log2 g) steps, 2 * n bytes through each member link
+ * (every device is an inner node of one of the two trees and a leaf of the other, so it forwards
+ * the whole message once per phase); the other collectives keep their ring figures.
  */
+static int ceil_log2(int g)
+{
+    int l = 0;
+    while ((1 << l) < g) l++;
+    return l;
+}
+
 static double step_cost(const p2o_query *q, const p2o_pattern *pt, const group_cost *gcs, double msg)
 {
     int n = q->n, D = q->D;
@@ -601,7 +622,10 @@ static double step_cost(const p2o_query *q, const p2o_pattern *pt, const group_c
         double nbytes = msg * (double)gc->rows / (double)q->k;
         double steps, bytes;
         switch (gc->op) {
-        case OP_ALLREDUCE:     steps = 2.0 * (g - 1); bytes = 2.0 * (g - 1) / g * nbytes; break;
+        case OP_ALLREDUCE:
+            if (q->algo == 1) { steps = 2.0 * ceil_log2(g); bytes = 2.0 * nbytes; }
+            else              { steps = 2.0 * (g - 1);      bytes = 2.0 * (g - 1) / g * nbytes; }
+            break;
         case OP_REDUCESCATTER: steps = (g - 1);       bytes = (double)(g - 1) / g * nbytes; break;
         case OP_ALLGATHER:     steps = (g - 1);       bytes = (double)(g - 1) / g * nbytes; break;
         default:               steps = (g - 1);       bytes = nbytes; break;

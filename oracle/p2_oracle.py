@@ -32,6 +32,8 @@ def lib():
         L.p2o_query_create.argtypes = [C.c_int, i32p, f64p, f64p, C.c_int, i32p, i32p, C.c_int, i32p,
                                        C.c_int, C.c_uint32, C.c_uint32]
         L.p2o_query_free.argtypes = [C.c_void_p]
+        L.p2o_set_algo.restype = C.c_int
+        L.p2o_set_algo.argtypes = [C.c_void_p, C.c_int]
         for name in ("p2o_num_devices", "p2o_num_chunks", "p2o_num_patterns", "p2o_alphabet_size"):
             getattr(L, name).restype = C.c_int
             getattr(L, name).argtypes = [C.c_void_p]
@@ -88,7 +90,8 @@ def enumerate_placements(card, axes):
 class Query:
     """System + placement + reduction axes (+ chunk count and grammar masks)."""
 
-    def __init__(self, card, axes, placement, reduce_axes, bw=None, alpha=None, n_chunks=0, form_mask=7, op_mask=31):
+    def __init__(self, card, axes, placement, reduce_axes, bw=None, alpha=None, n_chunks=0, form_mask=7, op_mask=31,
+                 algo=0):
         card, axes = _i32(card), _i32(axes)
         placement = _i32(placement).reshape(len(axes), len(card))
         reduce_axes = _i32(reduce_axes)
@@ -99,6 +102,8 @@ class Query:
                                          len(reduce_axes), _p(reduce_axes, C.c_int32), n_chunks, form_mask, op_mask)
         if not self._h:
             raise ValueError("invalid query")
+        if lib().p2o_set_algo(self._h, algo) != 0:      # 0 ring, 1 tree (AllReduce only)
+            raise ValueError("unknown cost model")
         self.n_levels = len(card)
         self.D = lib().p2o_num_devices(self._h)
         self.k = lib().p2o_num_chunks(self._h)

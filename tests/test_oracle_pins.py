@@ -417,6 +417,36 @@ def test_rs_ag_costs_the_same_as_ar_when_both_complete(oracle):
     assert ok1 and ok2 and np.allclose(c1, c2, rtol=1e-14)
 
 
+def test_tree_model_closed_forms_and_what_it_leaves_alone(oracle):
+    # Sec. 4 runs both of the library's AllReduce algorithms; the tree one is the two-tree scheme
+    # of its reference: up and down a binary tree, the whole message through every device twice.
+    for g, bw, a in ((8, 300e9, 5e-6), (5, 10e9, 1e-6), (2, 7e9, 3e-6)):
+        q = oracle.Query([g], [g], [[g]], [0], bw=[bw], alpha=[a], algo=1)
+        ok, cost, _ = q.eval_program([AR], [N26])
+        assert ok and cost[0] == pytest.approx(2 * math.ceil(math.log2(g)) * a + 2 * N26 / bw, rel=1e-14)
+    # two levels by hand: [2 nodes x 4 GPUs], AllReduce over all 8: 2*3 tree steps over the network,
+    # 2n through each node's uplink; the hierarchical program only changes in its AllReduce step
+    q = oracle.Query([2, 4], [8], [[2, 4]], [0], bw=[25e9, 300e9], alpha=[20e-6, 5e-6], algo=1)
+    r = oracle.Query([2, 4], [8], [[2, 4]], [0], bw=[25e9, 300e9], alpha=[20e-6, 5e-6])
+    n = N26
+    ok, cost, _ = q.eval_program([AR], [n])
+    assert ok and cost[0] == pytest.approx(6 * 20e-6 + 2 * n / 25e9, rel=1e-13)
+    node = next(pid for pid in range(q.n_patterns) if q.groups(pid)[0] == [0, 1, 2, 3])
+    pairs = next(pid for pid in range(q.n_patterns) if len(q.groups(pid)) == 4)
+    local = 3 * 5e-6 + (3 / 4 * n) / 300e9
+    prog = [node * 5 + RS, pairs * 5 + AR, node * 5 + AG]
+    ok, cost, _ = q.eval_program(prog, [n])
+    assert ok and cost[0] == pytest.approx(local + (2 * 20e-6 + 4 * (2 * n / 4) / 25e9) + local, rel=1e-13)
+    # the model touches AllReduce steps only, and never validity
+    a, b = q.synthesize(4, [n]), r.synthesize(4, [n])
+    assert a["index"].tolist() == b["index"].tolist()
+    for idx, instr, ln, ca, cb in zip(a["index"], a["instr"], a["len"], a["cost"][:, 0], b["cost"][:, 0]):
+        has_ar = any(int(v) % 5 == AR for v in instr[:ln])
+        assert (ca != cb) if has_ar else (ca == cb), (idx, instr[:ln])
+    with pytest.raises(ValueError):
+        oracle.Query([2], [2], [[2]], [0], algo=2)
+
+
 # --------------------------------------------------------------------------- top-k
 def test_topk_against_lexsort(oracle):
     rng = np.random.default_rng(7)
