@@ -8,8 +8,8 @@
  * reduction-axis synthesis hierarchy of a parallelism placement (Sec. 3.4).
  * Every candidate is derived from an integer index, checked against the
  * device-state semantics of Sec. 3.2 from the init state to the goal state
- * of Sec. 3.5, costed with a hierarchical ring alpha-beta model in fp64
- * (Sec. 5 gives the simulator's inputs) and ranked.
+ * of Sec. 3.5, costed with a hierarchical alpha-beta model in fp64 (ring, or
+ * tree for AllReduce; Sec. 5 gives the simulator's inputs) and ranked.
  *
  * Conventions
  *  - Every function returns an int32 status: P2_OK or a negative error.  The
@@ -90,7 +90,10 @@ typedef struct {
     uint32_t form_mask;  /* bit 0 InsideGroup, bit 1 Parallel, bit 2 Master; 0 => all            */
     uint32_t op_mask;    /* bits 0..4 = AllReduce, ReduceScatter, AllGather, Reduce, Broadcast;
                             0 => all                                                             */
-    int32_t algo;        /* 0 = ring (the only cost model)                                       */
+    int32_t algo;        /* cost model of an AllReduce step (Sec. 4 runs both): 0 = ring, 2(g-1)
+                            steps and 2(g-1)/g n bytes per member link; 1 = two-tree, 2 ceil(log2 g)
+                            steps and 2 n bytes.  The other collectives always use the ring figures.
+                            Anything else => P2_EUNSUPPORTED                                     */
     int32_t topk;        /* 0 => return every valid program; else see p2_synthesize              */
     int32_t engine;      /* P2_ENGINE_*                                                          */
     void* hip_stream;    /* hipStream_t to run on; NULL => the default stream                    */

@@ -183,7 +183,7 @@ class Batch:
         for i, q in enumerate(queries):
             h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
             axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
-            opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), 0, q.get("topk", 0),
+            opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), q.get("algo", 0), q.get("topk", 0),
                            q.get("engine", ENGINE_AUTO), stream)
             self._keep.append((h, axes, pl, red, opt))
             self._arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32),
@@ -240,10 +240,10 @@ def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
 
 
 def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=None, alpha=None, n_chunks=0,
-                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None):
+                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None, algo=0):
     """Valid programs of one placement with their simulated costs (through the single-query entry point)."""
     h, axes_a, pl, red = _Hier(card, bw, alpha), _i32(axes), _i32(placement), _i32(reduce_axes)
-    opt = _options(n_chunks, form_mask, op_mask, 0, topk, engine, stream)
+    opt = _options(n_chunks, form_mask, op_mask, algo, topk, engine, stream)
     msg = _f64(list(msg_bytes))
     n_msg = len(msg)
     count, cands, st = C.c_int64(), C.c_uint64(), p2_stats()

@@ -349,7 +349,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             DevQuery* dq = reinterpret_cast<DevQuery*>(hb + r.off_query);
             dq->R = pl.R; dq->k = pl.k;
             dq->MW = (pl.R + 31) / 32; dq->KW = (pl.k + 31) / 32;
-            dq->n_patterns = (int)pl.patterns.size(); dq->n_ops = pl.n_ops; dq->alphabet = pl.alphabet;
+            dq->n_patterns = (int)pl.patterns.size(); dq->n_ops = pl.n_ops; dq->alphabet = pl.alphabet; dq->algo = pl.algo;
             dq->max_len = pl.max_len; dq->n_levels = pl.n; dq->n_msg = n_msg;
             dq->n_candidates = pl.n_candidates;
             for (int l = 0; l <= P2_MAX_LEN + 1; ++l) dq->base[l] = pl.base[l];

@@ -466,9 +466,8 @@ __device__ inline int step_mixed(uint32_t* my, int dstride, const PatLds P, int 
             }
             best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
         }
-        const double gm1 = (double)(P.g - 1);
-        const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
-        const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)P.g : (op == OP_RS || op == OP_AG) ? gm1 / (double)P.g : 1.0;
+        double ring_steps, mult;
+        step_factors(op, P.g, q.algo, ring_steps, mult);
         *sum_alpha += ring_steps * q.alpha[dp->span_level];
         *sum_beta += (mult / (double)q.k) * best;
     }

@@ -76,11 +76,31 @@ struct DevCounters {
     unsigned long long evaluated_members[kCounterStripes];   // devices taking part in those, summed
 };
 
+// Latency steps and bytes through each member's link (as a multiple of the bytes a member holds) of one
+// collective on a group of g devices.  Ring figures; with algo = 1 an AllReduce instead goes up and down a
+// binary tree (2 ceil(log2 g) steps) and every device forwards the whole message once per phase (2 n).
+__host__ __device__ inline void step_factors(int op, int g, int algo, double& steps, double& mult) {
+    const double gm1 = (double)(g - 1);
+    if (op == OP_AR) {
+        if (algo == 1) {
+            int l = 0;
+            while ((1 << l) < g) ++l;
+            steps = 2.0 * (double)l; mult = 2.0;
+        } else {
+            steps = 2.0 * gm1; mult = 2.0 * gm1 / (double)g;
+        }
+    } else {
+        steps = gm1;
+        mult = (op == OP_RS || op == OP_AG) ? gm1 / (double)g : 1.0;
+    }
+}
+
 struct DevQuery {
     int32_t R, k;                  // devices of one reduction group, chunks
     int32_t MW, KW;                // 32-bit words per contribution mask / per chunk set
     int32_t n_patterns, n_ops, alphabet, max_len;
     int32_t n_levels, n_msg;
+    int32_t algo, pad0;            // cost model of AllReduce: 0 ring, 1 tree
     unsigned long long n_candidates;
     unsigned long long base[P2_MAX_LEN + 2];   // base[l]: index of the first program of length l
     uint8_t ops[8];

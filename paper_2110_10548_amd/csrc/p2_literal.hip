@@ -177,9 +177,8 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
             best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
         }
         best = wave_max(best);
-        const double gm1 = (double)(g - 1);
-        const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
-        const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)g : (op == OP_RS || op == OP_AG) ? gm1 / (double)g : 1.0;
+        double ring_steps, mult;
+        step_factors(op, g, q.algo, ring_steps, mult);
         if (lane < q.n_msg) *cost_lane += ring_steps * q.alpha[P.span_level] + q.msg_bytes[lane] * (mult / (double)k) * best;
     }
 

@@ -215,10 +215,11 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     if (n_reduce < 1) { err = "empty set of reduce axes"; return P2_EINVAL; }
     if (max_len < 1) { err = "max_len < 1"; return P2_EINVAL; }
     if (max_len > P2_MAX_LEN) { err = "max_len > 7"; return P2_EUNSUPPORTED; }
-    if (opt && opt->algo != 0) { err = "only the ring cost model (algo 0) exists"; return P2_EUNSUPPORTED; }
+    if (opt && opt->algo != 0 && opt->algo != 1) { err = "unknown cost model (algo is 0 = ring or 1 = tree)"; return P2_EUNSUPPORTED; }
 
     pl = Plan();
     pl.n = h->n_levels; pl.m = n_axes; pl.D = (int)devices; pl.max_len = max_len;
+    pl.algo = opt ? opt->algo : 0;
     for (int j = 0; j < pl.n; ++j) {
         pl.h[j] = h->card[j];
         pl.bw[j] = h->bw_bytes_per_s ? h->bw_bytes_per_s[j] : 1.0;

@@ -41,6 +41,7 @@ struct Plan {
     int D = 0, R = 0, k = 0;
     int f[P2_MAX_LEVELS] = {0};        // reduction-axis factor of each hardware level (collapsed)
     uint32_t form_mask = 7, op_mask = 31;
+    int algo = 0;                  // cost model of AllReduce: 0 ring, 1 tree
     int n_ops = 0, ops[5] = {0};
     std::vector<Pattern> patterns;
     int alphabet = 0;

@@ -385,9 +385,8 @@ __global__ __launch_bounds__(kWave) void k_cost_shared(const DevQuery* __restric
                         best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
                     }
                     for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWave));
-                    const double gm1 = (double)(P.g - 1);
-                    const double ring_steps = (op == OP_AR) ? 2.0 * gm1 : gm1;
-                    const double mult = (op == OP_AR) ? 2.0 * gm1 / (double)P.g : (op == OP_RS || op == OP_AG) ? gm1 / (double)P.g : 1.0;
+                    double ring_steps, mult;
+                    step_factors(op, P.g, q.algo, ring_steps, mult);
                     sum_alpha += ring_steps * q.alpha[P.span_level];
                     sum_beta += (mult / (double)q.k) * best;
                 }

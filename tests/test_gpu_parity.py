@@ -21,7 +21,7 @@ def B():
 
 def oracle_result(oracle, q, msg, form_mask=7, op_mask=31):
     oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q.get("bw"), alpha=q.get("alpha"),
-                      n_chunks=q.get("n_chunks", 0), form_mask=form_mask, op_mask=op_mask)
+                      n_chunks=q.get("n_chunks", 0), form_mask=form_mask, op_mask=op_mask, algo=q.get("algo", 0))
     return oq, oq.synthesize(q["max_len"], msg)
 
 
@@ -140,6 +140,33 @@ def test_small_group_engine_selection(B, oracle):
         with pytest.raises(B.P2Error) as ei:
             B.p2_synthesize_batch([dict(odd, engine=engine)], [1e6])
         assert ei.value.code == B.P2_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("engine", [1, 2, 5], ids=["literal", "compact", "shared"])
+def test_tree_cost_model(B, oracle, engine):
+    """algo = 1 (tree AllReduce): every cost kernel against the oracle, ring and tree queries in one batch."""
+    cfg, queries = queries_of(2, B)
+    mixed = []
+    for i, q in enumerate(queries):
+        mixed.append(dict(q, engine=engine, algo=1))
+        if i % 3 == 0:
+            mixed.append(dict(q, engine=engine, algo=0))
+    cfg3 = workloads.config(3)
+    pl3 = B.p2_enumerate_placements(cfg3["card"], cfg3["axes"])
+    q3 = [q for q in workloads.expand(cfg3, pl3) if q["reduce_axes"] == [1, 2]][:2]      # 32 devices, 64 chunks
+    mixed += [dict(q, engine=engine if engine != 1 else 0, algo=1, max_len=4) for q in q3]
+    results = B.p2_synthesize_batch(mixed, cfg["msg_bytes"])
+    differs = 0
+    for q, res in zip(mixed, results):
+        _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+        assert_same(res, ora, len(cfg["msg_bytes"]))
+        if q["algo"] == 1:
+            _, ring = oracle_result(oracle, dict(q, algo=0), cfg["msg_bytes"])
+            differs += int((ring["cost"] != ora["cost"]).any())
+    assert differs > 0
+    with pytest.raises(B.P2Error) as e:
+        B.p2_synthesize_batch([dict(queries[0], algo=2)], cfg["msg_bytes"])
+    assert e.value.code == B.P2_EUNSUPPORTED
 
 
 @pytest.mark.parametrize("form_mask,op_mask", [(3, 31), (5, 31), (7, 0b01101), (7, 0b11001), (4, 31)])
