@@ -163,10 +163,40 @@ typedef struct {
  * every requested reduction).  All queries share msg_bytes.  Results of query i occupy
  * out_prog[out_offset[i] .. out_offset[i+1]) and the matching rows of out_cost;
  * out_offset has n_queries + 1 entries; stats (optional) has n_queries entries.
- * All device work of the batch is enqueued before the single wait at the end. */
+ * The kernels of all queries share their launches; the call waits for the device after the
+ * evaluation (to size the lists), after the candidates handed to the literal engine, and for
+ * the results. */
 int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
                             p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset,
                             p2_stats* stats);
+
+/* One (placement, reduction) pair of p2_search_placements. */
+typedef struct {
+    p2_program best;         /* the valid program with the smallest (cost, index); len = 0 when there
+                                is none, or when the reduction group is a single device            */
+    double best_cost;        /* its simulated seconds; 0 for a single device; +inf when no program
+                                of length <= max_len is valid                                      */
+    double allreduce_cost;   /* the one-instruction program AllReduce over the whole reduction group
+                                (InsideGroup on the root level; always valid): the baseline that the
+                                evaluation compares synthesized programs with (Sec. 4.2)           */
+    uint64_t valid;          /* valid programs of length <= max_len                                */
+    uint64_t candidates;     /* programs evaluated                                                 */
+} p2_search_row;
+
+/* The synthesizer's outer loop with its ranking (Sec. 2.2 and 4.1): every parallelism matrix of the
+ * system (in the order of p2_enumerate_placements) x every requested reduction, all in one batch on
+ * the GPU.  reduce_sets holds the axis numbers of the n_sets reductions one after another,
+ * reduce_set_len[s] of them for reduction s.  One message size (bytes held per device).
+ * out_rows[p * n_sets + s] describes placement p under reduction s; out_total[p] =
+ * sum_s weights[s] * best_cost (weights NULL => all 1: a mapping is chosen with all of a model's
+ * reductions in view, Sec. 4.1); out_order lists the placements by ascending (total, p).
+ * opt->topk is ignored.  *out_count = number of placements; with cap = 0 only that is written;
+ * cap < *out_count => P2_ENOSPC. */
+int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* reduce_sets,
+                             const int32_t* reduce_set_len, int32_t n_sets, const double* weights, int32_t max_len,
+                             double msg_bytes, const p2_options* opt, int32_t* out_placements /* [cap][n_axes][n_levels] */,
+                             p2_search_row* out_rows /* [cap][n_sets] */, double* out_total /* [cap] */,
+                             int32_t* out_order /* [cap] */, int64_t cap, int64_t* out_count);
 
 /* The device groups of canonical pattern `pattern_id` on the full system (Sec. 3.3 and the
  * table of hierarchical communication patterns): slice level and form level are indices into

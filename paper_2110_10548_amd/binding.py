@@ -49,6 +49,11 @@ class p2_profile(C.Structure):
                 ("host_plan_ms", C.c_float), ("host_total_ms", C.c_float)]
 
 
+class p2_search_row(C.Structure):
+    _fields_ = [("best", p2_program), ("best_cost", C.c_double), ("allreduce_cost", C.c_double), ("valid", C.c_uint64),
+                ("candidates", C.c_uint64)]
+
+
 class p2_query(C.Structure):
     _fields_ = [("h", C.POINTER(p2_hierarchy)), ("axes", C.POINTER(C.c_int32)), ("n_axes", C.c_int32),
                 ("placement", C.POINTER(C.c_int32)), ("reduce_axes", C.POINTER(C.c_int32)), ("n_reduce", C.c_int32),
@@ -59,7 +64,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile")
+           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements")
 
 _lib = None
 
@@ -89,6 +94,10 @@ def lib():
         L.p2_describe_pattern.restype = C.c_int32
         L.p2_describe_pattern.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, i32p, C.c_int32,
                                           C.POINTER(p2_options), C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p]
+        L.p2_search_placements.restype = C.c_int32
+        L.p2_search_placements.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, i32p, C.c_int32, f64p, C.c_int32,
+                                           C.c_double, C.POINTER(p2_options), i32p, C.POINTER(p2_search_row), f64p, i32p,
+                                           C.c_int64, i64p]
         L.p2_topk.restype = C.c_int32
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
@@ -261,6 +270,39 @@ def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=
     n = count.value
     return {"programs": progs[:n].copy(), "cost": cost[:n, :n_msg].copy(), "candidates": cands.value,
             "stats": _stats_dict(st)}
+
+
+def p2_search_placements(card, axes, reduce_sets, max_len, msg_bytes, bw=None, alpha=None, weights=None, n_chunks=0,
+                         form_mask=7, op_mask=31, algo=0, engine=ENGINE_AUTO, stream=None):
+    """Every placement x every requested reduction in one batch: best program, AllReduce baseline, ranking."""
+    h, axes_a = _Hier(card, bw, alpha), _i32(axes)
+    flat = _i32([a for red in reduce_sets for a in red])
+    lens = _i32([len(red) for red in reduce_sets])
+    w = _f64(list(weights)) if weights is not None else None
+    opt = _options(n_chunks, form_mask, op_mask, algo, 0, engine, stream)
+    count = C.c_int64()
+
+    def call(pl_p, rows_p, tot_p, ord_p, cap):
+        return lib().p2_search_placements(C.byref(h.c), _p(axes_a, C.c_int32), len(axes_a), _p(flat, C.c_int32),
+                                          _p(lens, C.c_int32), len(lens), _p(w, C.c_double) if w is not None else None,
+                                          max_len, float(msg_bytes), C.byref(opt), pl_p, rows_p, tot_p, ord_p, cap,
+                                          C.byref(count))
+    _check(call(None, None, None, None, 0))
+    n, ns = count.value, len(lens)
+    pls = np.zeros((max(n, 1), len(axes_a), len(card)), dtype=np.int32)
+    rows = (p2_search_row * max(n * ns, 1))()
+    total = np.zeros(max(n, 1), dtype=np.float64)
+    order = np.zeros(max(n, 1), dtype=np.int32)
+    _check(call(_p(pls, C.c_int32), rows, _p(total, C.c_double), _p(order, C.c_int32), n))
+    out_rows = {}
+    for p in range(n):
+        for s_ in range(ns):
+            r = rows[p * ns + s_]
+            out_rows[(p, s_)] = {"valid": int(r.valid), "candidates": int(r.candidates),
+                                 "best_index": int(r.best.index) if r.best.len else None,
+                                 "best_instr": [int(r.best.instr[t]) for t in range(r.best.len)],
+                                 "best_cost": float(r.best_cost), "allreduce_cost": float(r.allreduce_cost)}
+    return {"placements": pls[:n].tolist(), "rows": out_rows, "total": total[:n].tolist(), "order": order[:n].tolist()}
 
 
 def p2_set_profiling(on):

@@ -4,6 +4,7 @@
 #include <chrono>
 #include <cstddef>
 #include <cstring>
+#include <limits>
 #include <string>
 #include <vector>
 
@@ -814,6 +815,88 @@ int32_t p2_synthesize(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes
         if (stats) *stats = st;
     }
     return rc;
+}
+
+int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* reduce_sets,
+                             const int32_t* reduce_set_len, int32_t n_sets, const double* weights, int32_t max_len,
+                             double msg_bytes, const p2_options* opt, int32_t* out_placements, p2_search_row* out_rows,
+                             double* out_total, int32_t* out_order, int64_t cap, int64_t* out_count) {
+    try {
+        if (!h || !axes || !reduce_sets || !reduce_set_len || !out_count) return fail(P2_EINVAL, "null argument");
+        if (n_sets < 1) return fail(P2_EINVAL, "no reduction requested");
+        if (cap < 0 || (cap > 0 && (!out_placements || !out_rows || !out_total || !out_order)))
+            return fail(P2_EINVAL, "bad output buffer");
+        if (!(msg_bytes >= 0.0)) return fail(P2_EINVAL, "msg_bytes is negative or NaN");
+        std::vector<const int32_t*> set_ptr((size_t)n_sets);
+        {
+            const int32_t* at = reduce_sets;
+            for (int s = 0; s < n_sets; ++s) {
+                if (reduce_set_len[s] < 1) return fail(P2_EINVAL, "empty set of reduce axes");
+                set_ptr[(size_t)s] = at;
+                at += reduce_set_len[s];
+            }
+        }
+        int64_t n_pl = 0;
+        std::string err;
+        int32_t st = p2::enumerate_placements(h, axes, n_axes, nullptr, 0, &n_pl, err);
+        if (st != P2_OK) return fail(st, err);
+        *out_count = n_pl;
+        if (cap == 0) return P2_OK;
+        if (cap < n_pl) return fail(P2_ENOSPC, "output buffers too small: " + std::to_string(n_pl) + " placements");
+        const size_t per = (size_t)n_axes * (size_t)h->n_levels;
+        st = p2::enumerate_placements(h, axes, n_axes, out_placements, n_pl, &n_pl, err);
+        if (st != P2_OK) return fail(st, err);
+        if (n_pl * (int64_t)n_sets * 2 > 0x7fffffff) return fail(P2_EUNSUPPORTED, "too many (placement, reduction) pairs");
+
+        // two queries per (placement, reduction): the search itself, keeping its cheapest program,
+        // and the one-instruction AllReduce over the whole reduction group
+        p2_options main_opt;
+        std::memset(&main_opt, 0, sizeof main_opt);
+        if (opt) main_opt = *opt;
+        main_opt.topk = 1;
+        p2_options base_opt = main_opt;
+        base_opt.form_mask = 1; base_opt.op_mask = 1; base_opt.topk = 0; base_opt.engine = P2_ENGINE_AUTO;
+        const int n_q = (int)(n_pl * n_sets * 2);
+        std::vector<p2_query> qs((size_t)n_q);
+        for (int64_t p = 0; p < n_pl; ++p)
+            for (int s = 0; s < n_sets; ++s) {
+                const size_t at = ((size_t)p * (size_t)n_sets + (size_t)s) * 2;
+                qs[at] = p2_query{h, axes, n_axes, out_placements + (size_t)p * per, set_ptr[(size_t)s], reduce_set_len[s], max_len, &main_opt};
+                qs[at + 1] = p2_query{h, axes, n_axes, out_placements + (size_t)p * per, set_ptr[(size_t)s], reduce_set_len[s], 1, &base_opt};
+            }
+        std::vector<p2_program> progs((size_t)n_q);
+        std::vector<double> costs((size_t)n_q);
+        std::vector<int64_t> offs((size_t)n_q + 1);
+        std::vector<p2_stats> stats((size_t)n_q);
+        int32_t rc = run_batch(qs.data(), n_q, &msg_bytes, 1, progs.data(), costs.data(), n_q, offs.data(), stats.data());
+        if (rc != P2_OK) return rc;
+        const double inf = std::numeric_limits<double>::infinity();
+        for (int64_t p = 0; p < n_pl; ++p) {
+            double total = 0.0;
+            for (int s = 0; s < n_sets; ++s) {
+                const size_t at = ((size_t)p * (size_t)n_sets + (size_t)s) * 2;
+                p2_search_row& row = out_rows[(size_t)p * (size_t)n_sets + (size_t)s];
+                std::memset(&row, 0, sizeof row);
+                row.candidates = stats[at].candidates;
+                row.valid = stats[at].valid;
+                if (stats[at].alphabet == 0) {                  // a reduction over one device: nothing to do
+                    row.best_cost = 0.0; row.allreduce_cost = 0.0;
+                } else {
+                    if (offs[at + 1] > offs[at]) { row.best = progs[(size_t)offs[at]]; row.best_cost = costs[(size_t)offs[at]]; }
+                    else row.best_cost = inf;
+                    if (offs[at + 2] - offs[at + 1] != 1) return fail(P2_EDEVICE, "the AllReduce baseline did not evaluate to one program");
+                    row.allreduce_cost = costs[(size_t)offs[at + 1]];
+                }
+                total += (weights ? weights[s] : 1.0) * row.best_cost;
+            }
+            out_total[p] = total;
+        }
+        for (int64_t p = 0; p < n_pl; ++p) out_order[p] = (int32_t)p;
+        std::stable_sort(out_order, out_order + n_pl, [&](int32_t a, int32_t b) { return out_total[a] < out_total[b]; });
+        return P2_OK;
+    } catch (const std::exception& e) {
+        return fail(P2_EDEVICE, std::string("host failure: ") + e.what());
+    }
 }
 
 int32_t p2_describe_pattern(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,

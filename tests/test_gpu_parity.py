@@ -169,6 +169,54 @@ def test_tree_cost_model(B, oracle, engine):
     assert e.value.code == B.P2_EUNSUPPORTED
 
 
+def _check_search(got, want):
+    assert got["placements"] == want["placements"]
+    assert set(got["rows"]) == set(want["rows"])
+    for key, w in want["rows"].items():
+        g = got["rows"][key]
+        assert g["valid"] == w["valid"], key
+        assert np.isclose(g["best_cost"], w["best_cost"], rtol=RTOL, atol=0.0), key
+        assert np.isclose(g["allreduce_cost"], w["allreduce_cost"], rtol=RTOL, atol=0.0), key
+        assert len(g["best_instr"]) > 0 or w["best_index"] is None
+    assert np.allclose(got["total"], want["total"], rtol=RTOL, atol=0.0)
+    # ranking: ascending in the library's own totals; placements whose totals tie to within rounding may swap
+    tot = got["total"]
+    assert sorted(got["order"]) == list(range(len(tot)))
+    assert [(tot[p], p) for p in got["order"]] == sorted((tot[p], p) for p in range(len(tot)))
+    assert np.allclose([want["total"][p] for p in got["order"]], [want["total"][p] for p in want["order"]], rtol=RTOL, atol=0.0)
+    return got
+
+
+@pytest.mark.parametrize("cfg_id,algo", [(1, 0), (2, 0), (2, 1)])
+def test_placement_search(B, oracle, cfg_id, algo):
+    """Every placement x every reduce set in one call, against the oracle's plain loop (Sec. 4.1)."""
+    from oracle import p2_search
+    cfg = workloads.config(cfg_id)
+    msg = cfg["msg_bytes"][0]
+    kw = dict(bw=cfg["bw"], alpha=cfg["alpha"], algo=algo, weights=[1.0, 0.25][:len(cfg["reduce_sets"])])
+    got = B.p2_search_placements(cfg["card"], cfg["axes"], cfg["reduce_sets"], cfg["max_len"], msg, **kw)
+    want = p2_search.search_placements(cfg["card"], cfg["axes"], cfg["reduce_sets"], cfg["max_len"], msg, **kw)
+    _check_search(got, want)
+    # the best program is a valid one with that cost, and the cheapest up to ties within rounding
+    for (p, s), g in got["rows"].items():
+        oq = oracle.Query(cfg["card"], cfg["axes"], want["placements"][p], cfg["reduce_sets"][s], bw=cfg["bw"],
+                          alpha=cfg["alpha"], algo=algo)
+        ok, cost, _ = oq.eval_program(g["best_instr"], [msg])
+        assert ok and np.isclose(cost[0], g["best_cost"], rtol=RTOL, atol=0.0)
+        w = want["rows"][(p, s)]
+        if g["best_index"] != w["best_index"]:
+            assert np.isclose(w["best_cost"], g["best_cost"], rtol=RTOL, atol=0.0)
+
+
+def test_placement_search_single_device_reduction_and_sizing(B):
+    from oracle import p2_search
+    args = ([2, 4], [1, 8], [[0], [1]], 3, float(2 ** 26))
+    kw = dict(bw=[25e9, 300e9], alpha=[20e-6, 5e-6])
+    got = _check_search(B.p2_search_placements(*args, **kw), p2_search.search_placements(*args, **kw))
+    assert all(got["rows"][(p, 0)]["best_instr"] == [] and got["rows"][(p, 0)]["best_cost"] == 0.0
+               for p in range(len(got["placements"])))
+
+
 @pytest.mark.parametrize("form_mask,op_mask", [(3, 31), (5, 31), (7, 0b01101), (7, 0b11001), (4, 31)])
 def test_grammar_masks(B, oracle, form_mask, op_mask):
     q = dict(card=[2, 2, 2], axes=[8], placement=[[2, 2, 2]], reduce_axes=[0], max_len=4, bw=[1e9, 2e9, 3e9],

@@ -25,7 +25,7 @@ def B():
 def test_every_declared_symbol_is_exported(B):
     header = open(os.path.join(ROOT, "include", "p2.h")).read()
     declared = set(re.findall(r"\b(p2_[a-z_]+)\s*\(", header))
-    declared -= {"p2_hierarchy", "p2_options", "p2_program", "p2_stats", "p2_query"}
+    declared -= {"p2_hierarchy", "p2_options", "p2_program", "p2_stats", "p2_query", "p2_search_row"}
     assert declared == set(B.EXPORTS)
     L = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
@@ -79,6 +79,11 @@ def test_argument_errors(B):
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 8) == B.P2_EUNSUPPORTED      # max_len > 7
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [], 3) == B.P2_EINVAL             # empty reduce set
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, [1e6]) == B.P2_EINVAL     # costs without links
+    # the placement search checks its arguments and counts the placements before any device work
+    assert code(B.p2_search_placements, [2, 4], [3, 3], [[0]], 3, 1e6) == B.P2_EINVAL                # products differ
+    assert code(B.p2_search_placements, [2, 4], [2, 4], [], 3, 1e6) == B.P2_EINVAL                   # no reduction
+    assert code(B.p2_search_placements, [2, 4], [2, 4], [[]], 3, 1e6) == B.P2_EINVAL                 # empty reduction
+    assert code(B.p2_search_placements, [2, 4], [2, 4], [[0]], 3, -1.0) == B.P2_EINVAL               # negative bytes
     assert code(B.p2_topk, [0.0], [0], -1) == B.P2_EINVAL
     assert code(B.p2_topk, [0.0], [0], 5000) == B.P2_EUNSUPPORTED
     assert b"" == b"" and isinstance(B.lib().p2_last_error(), bytes)
