@@ -30,6 +30,7 @@
 #define MAXAX 8            /* parallelism axes                     */
 #define MAXD 512           /* devices                              */
 #define MAXW (MAXD / 64)   /* 64-bit words per D-bit column mask   */
+#define MAXSL (MAXAX * MAXLV) /* levels of a synthesis hierarchy (one per matrix cell at most) */
 #define MAXPAT ((MAXLV + 1) * (MAXLV + 1))
 #define MAXLEN 8           /* program size limit supported         */
 
@@ -120,8 +121,13 @@ typedef struct {
     int D, k, W;
     int (*coord)[MAXLV];          /* [D][n]   hardware coordinate c_j of a device          */
     int (*digit)[MAXAX][MAXLV];   /* [D][m][n] axis digit a_{i,j} of a device              */
-    int f[MAXLV + 1];             /* synthesis hierarchy (d): e_0 = root (1), e_1..e_n     */
-    int (*gd)[MAXLV + 1];         /* [D][n+1] digit of a device at each level of (d)       */
+    int kind;                     /* synthesis hierarchy (Sec. 3.4): 3 = (d), the tool's choice;
+                                     4 = (a) system, 0 = (b) column-based, 1 = (c) row-based,
+                                     2 = reduction-axis factors before they are collapsed  */
+    int sl;                       /* its levels e_1..e_sl; e_0 = root (1) is put in front  */
+    int f[MAXSL + 1];             /* their factors, f[0] = 1                               */
+    int cell_level[MAXAX][MAXLV]; /* level that the factor x[i][j] belongs to; 0 = none:
+                                     the pattern is repeated over that digit (lowering)    */
     uint64_t *goal;               /* [D][W]   mask of the device's reduction group         */
     int n_patterns;
     p2o_pattern pat[MAXPAT];
@@ -141,14 +147,17 @@ void p2o_query_free(p2o_query *q)
 {
     if (!q) return;
     for (int i = 0; i < q->n_patterns; i++) pattern_free(&q->pat[i]);
-    free(q->coord); free(q->digit); free(q->gd); free(q->goal);
+    free(q->coord); free(q->digit); free(q->goal);
     free(q);
 }
 
 /*
  * Device groups of one (slice e_i, form) pair on the full system (Sec. 3.3).
+ * A level of the synthesis hierarchy owns some factors x[i][j] of the matrix
+ * (cell_level); a device's digit at the level is made of its digits a_{i,j}
+ * at those factors.
  *   InsideGroup : devices that agree on everything except the digits of
- *                 levels e_{i+1}..e_n of (d) form one group.
+ *                 levels e_{i+1}..e_last form one group.
  *   Parallel(e_j), j < i : devices that agree on everything except the digits
  *                 of levels e_{j+1}..e_i ("the first device of each e_i-group,
  *                 the second, ..., as far as they connect to the same e_j").
@@ -157,14 +166,15 @@ void p2o_query_free(p2o_query *q)
  *                 Reading: "first" is taken per e_j instance and per replica
  *                 over the non-reduction axes, because lowering applies the
  *                 pattern to the non-reduction axes (Sec. 3.4).
- * "Everything" includes every digit of every non-reduction axis (lowering).
+ * "Everything" includes every digit of every factor outside the hierarchy:
+ * for (d), every digit of every non-reduction axis (lowering).
  * Groups of one device are not reductions and are dropped (Appendix B).
  */
 static int build_pattern(const p2o_query *q, int slice, int form, int form_level, p2o_pattern *pt)
 {
     int D = q->D, n = q->n;
-    int vlo, vhi;                         /* levels of (d) whose digit varies inside a group */
-    if (form == FORM_INSIDEGROUP) { vlo = slice + 1; vhi = n; }
+    int vlo, vhi;                         /* levels whose digit varies inside a group */
+    if (form == FORM_INSIDEGROUP) { vlo = slice + 1; vhi = q->sl; }
     else                          { vlo = form_level + 1; vhi = slice; }
     memset(pt, 0, sizeof *pt);
     pt->slice = slice; pt->form = form; pt->form_level = form_level;
@@ -181,21 +191,20 @@ static int build_pattern(const p2o_query *q, int slice, int form, int form_level
         tgroup[d] = -1;
         if (form == FORM_MASTER) {
             int first = 1;
-            for (int l = slice + 1; l <= n; l++) if (q->gd[d][l] != 0) first = 0;
+            for (int i = 0; i < q->m; i++)
+                for (int j = 0; j < n; j++) if (q->cell_level[i][j] > slice && q->digit[d][i][j] != 0) first = 0;
             if (!first) continue;
         }
         /* look for an earlier group whose leader agrees with d outside the varying levels */
         int g = -1;
         for (int t = 0; t < nt && g < 0; t++) {
             int e = leader[t], same = 1;
-            for (int i = 0; i < q->m && same; i++) {
-                if (q->is_reduce[i]) continue;
-                for (int j = 0; j < n; j++) if (q->digit[d][i][j] != q->digit[e][i][j]) { same = 0; break; }
-            }
-            for (int l = 1; l <= n && same; l++) {
-                if (l >= vlo && l <= vhi) continue;
-                if (q->gd[d][l] != q->gd[e][l]) same = 0;
-            }
+            for (int i = 0; i < q->m && same; i++)
+                for (int j = 0; j < n; j++) {
+                    int l = q->cell_level[i][j];      /* 0: a digit outside the hierarchy never varies */
+                    if (l >= vlo && l <= vhi && l > 0) continue;
+                    if (q->digit[d][i][j] != q->digit[e][i][j]) { same = 0; break; }
+                }
             if (same) g = t;
         }
         if (g < 0) { g = nt++; leader[g] = d; tsize[g] = 0; }
@@ -237,11 +246,30 @@ static int same_groups(const p2o_pattern *a, const p2o_pattern *b, int D)
     return 1;
 }
 
+p2o_query *p2o_query_create_kind(int n_levels, const int32_t *card, const double *bw, const double *alpha,
+                                 int n_axes, const int32_t *axes, const int32_t *placement,
+                                 int n_reduce, const int32_t *reduce_axes,
+                                 int n_chunks, uint32_t form_mask, uint32_t op_mask, int kind);
+
 p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw, const double *alpha,
                             int n_axes, const int32_t *axes, const int32_t *placement,
                             int n_reduce, const int32_t *reduce_axes,
                             int n_chunks, uint32_t form_mask, uint32_t op_mask)
 {
+    /* the tool synthesizes on hierarchy (d) */
+    return p2o_query_create_kind(n_levels, card, bw, alpha, n_axes, axes, placement, n_reduce, reduce_axes,
+                                 n_chunks, form_mask, op_mask, 3);
+}
+
+/* kind: the synthesis hierarchy (Sec. 3.4, Appendix A): 4 = (a) the system's own levels, 0 = (b) the
+ * matrix's factors column by column, 1 = (c) row by row, 2 = the reduction axes' rows only,
+ * 3 = (d) those rows collapsed per hardware level.  Every kind gets a root level in front. */
+p2o_query *p2o_query_create_kind(int n_levels, const int32_t *card, const double *bw, const double *alpha,
+                                 int n_axes, const int32_t *axes, const int32_t *placement,
+                                 int n_reduce, const int32_t *reduce_axes,
+                                 int n_chunks, uint32_t form_mask, uint32_t op_mask, int kind)
+{
+    if (kind < 0 || kind > 4) return NULL;
     if (n_levels < 1 || n_levels > MAXLV || n_axes < 1 || n_axes > MAXAX) return NULL;
     if (n_reduce < 1 || n_reduce > n_axes) return NULL;
     p2o_query *q = calloc(1, sizeof *q);
@@ -282,7 +310,6 @@ p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw,
     int n = q->n, m = q->m;
     q->coord = calloc(q->D, sizeof *q->coord);
     q->digit = calloc(q->D, sizeof *q->digit);
-    q->gd = calloc(q->D, sizeof *q->gd);
     q->goal = calloc((size_t)q->D * q->W, sizeof(uint64_t));
 
     /* Device id = mixed radix of the hardware coordinates, outermost level most
@@ -298,22 +325,26 @@ p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw,
             for (int i = m - 1; i >= 0; i--) { q->digit[d][i][j] = c % q->x[i][j]; c /= q->x[i][j]; }
         }
     }
-    /* Synthesis hierarchy (d): reduction-axis factors only, factors of the same
-     * hardware level collapsed (multiplied), (root,1) put in front. */
+    /* Synthesis hierarchy: which factor of the matrix belongs to which level.
+     * (d): reduction-axis factors only, factors of the same hardware level
+     * collapsed (multiplied); (root,1) is put in front of every kind. */
+    q->kind = kind;
     q->f[0] = 1;
     {
         int32_t flat[MAXAX * MAXLV], red[MAXAX];
-        int64_t col[MAXLV];
+        int64_t col[MAXSL];
         for (int i = 0; i < m; i++) { red[i] = q->is_reduce[i]; for (int j = 0; j < n; j++) flat[i * n + j] = q->x[i][j]; }
-        p2o_hierarchy_of_matrix(m, n, flat, red, 3, col);
-        for (int j = 0; j < n; j++) q->f[j + 1] = (int)col[j];
-    }
-    for (int d = 0; d < q->D; d++) {
-        q->gd[d][0] = 0;
-        for (int j = 0; j < n; j++) {
-            int v = 0;
-            for (int i = 0; i < m; i++) if (q->is_reduce[i]) v = v * q->x[i][j] + q->digit[d][i][j];
-            q->gd[d][j + 1] = v;
+        if (kind == 4) {                                   /* (a): one level per hardware level */
+            q->sl = n;
+            for (int j = 0; j < n; j++) { q->f[j + 1] = q->h[j]; for (int i = 0; i < m; i++) q->cell_level[i][j] = j + 1; }
+        } else {
+            q->sl = p2o_hierarchy_of_matrix(m, n, flat, red, kind, col);
+            for (int l = 0; l < q->sl; l++) q->f[l + 1] = (int)col[l];
+            int l = 0;
+            if (kind == 0) { for (int j = 0; j < n; j++) for (int i = 0; i < m; i++) q->cell_level[i][j] = ++l; }
+            else if (kind == 1) { for (int i = 0; i < m; i++) for (int j = 0; j < n; j++) q->cell_level[i][j] = ++l; }
+            else if (kind == 2) { for (int i = 0; i < m; i++) if (red[i]) for (int j = 0; j < n; j++) q->cell_level[i][j] = ++l; }
+            else { for (int j = 0; j < n; j++) for (int i = 0; i < m; i++) q->cell_level[i][j] = red[i] ? j + 1 : 0; }
         }
     }
     /* Goal (Sec. 3.5): a device ends with the columns of every device it reduces
@@ -331,7 +362,7 @@ p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw,
      * Master(e_0..e_{i-1}); the form's level is a strict ancestor of the slice.
      * A pattern with no group left is dropped; a pattern whose groups equal an
      * earlier pattern's is the same instruction and is dropped too. */
-    for (int i = 0; i <= n; i++) {
+    for (int i = 0; i <= q->sl; i++) {
         for (int form = 0; form < 3; form++) {
             if (!(form_mask & (1u << form))) continue;
             int jlo = (form == FORM_INSIDEGROUP) ? -1 : 0;
@@ -342,6 +373,7 @@ p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw,
                 int dup = 0;
                 for (int t = 0; t < q->n_patterns && !dup; t++) dup = same_groups(&q->pat[t], &pt, q->D);
                 if (ng == 0 || dup) { pattern_free(&pt); continue; }
+                if (q->n_patterns == MAXPAT) { pattern_free(&pt); p2o_query_free(q); return NULL; }
                 q->pat[q->n_patterns++] = pt;
             }
         }
@@ -355,7 +387,7 @@ p2o_query *p2o_query_create(int n_levels, const int32_t *card, const double *bw,
 int p2o_groups_raw(const p2o_query *q, int slice, int form, int form_level,
                    int32_t *group_of_device, int32_t *rank_in_group)
 {
-    if (slice < 0 || slice > q->n || form < 0 || form > 2) return -1;
+    if (slice < 0 || slice > q->sl || form < 0 || form > 2) return -1;
     if (form != FORM_INSIDEGROUP && (form_level < 0 || form_level >= slice)) return -1;
     p2o_pattern pt;
     int ng = build_pattern(q, slice, form, form == FORM_INSIDEGROUP ? -1 : form_level, &pt);
@@ -393,7 +425,8 @@ int p2o_num_devices(const p2o_query *q) { return q->D; }
 int p2o_num_chunks(const p2o_query *q) { return q->k; }
 int p2o_num_patterns(const p2o_query *q) { return q->n_patterns; }
 int p2o_alphabet_size(const p2o_query *q) { return q->n_patterns * q->n_ops; }
-void p2o_synthesis_hierarchy(const p2o_query *q, int32_t *out) { for (int l = 0; l <= q->n; l++) out[l] = q->f[l]; }
+int p2o_synthesis_levels(const p2o_query *q) { return q->sl; }
+void p2o_synthesis_hierarchy(const p2o_query *q, int32_t *out) { for (int l = 0; l <= q->sl; l++) out[l] = q->f[l]; }
 
 int p2o_pattern_info(const p2o_query *q, int pid, int32_t *slice, int32_t *form, int32_t *form_level,
                      int32_t *group_of_device, int32_t *rank_in_group)

@@ -31,6 +31,10 @@ def lib():
         L.p2o_query_create.restype = C.c_void_p
         L.p2o_query_create.argtypes = [C.c_int, i32p, f64p, f64p, C.c_int, i32p, i32p, C.c_int, i32p,
                                        C.c_int, C.c_uint32, C.c_uint32]
+        L.p2o_query_create_kind.restype = C.c_void_p
+        L.p2o_query_create_kind.argtypes = L.p2o_query_create.argtypes + [C.c_int]
+        L.p2o_synthesis_levels.restype = C.c_int
+        L.p2o_synthesis_levels.argtypes = [C.c_void_p]
         L.p2o_query_free.argtypes = [C.c_void_p]
         L.p2o_set_algo.restype = C.c_int
         L.p2o_set_algo.argtypes = [C.c_void_p, C.c_int]
@@ -91,15 +95,18 @@ class Query:
     """System + placement + reduction axes (+ chunk count and grammar masks)."""
 
     def __init__(self, card, axes, placement, reduce_axes, bw=None, alpha=None, n_chunks=0, form_mask=7, op_mask=31,
-                 algo=0):
+                 algo=0, hierarchy="collapsed"):
         card, axes = _i32(card), _i32(axes)
         placement = _i32(placement).reshape(len(axes), len(card))
         reduce_axes = _i32(reduce_axes)
         bw = _f64(bw if bw is not None else [1.0] * len(card))
         alpha = _f64(alpha if alpha is not None else [0.0] * len(card))
-        self._h = lib().p2o_query_create(len(card), _p(card, C.c_int32), _p(bw, C.c_double), _p(alpha, C.c_double),
-                                         len(axes), _p(axes, C.c_int32), _p(placement, C.c_int32),
-                                         len(reduce_axes), _p(reduce_axes, C.c_int32), n_chunks, form_mask, op_mask)
+        # synthesis hierarchy (Sec. 3.4): the tool's own choice is "collapsed" = (d)
+        kind = {"column": 0, "row": 1, "reduction": 2, "collapsed": 3, "system": 4}[hierarchy]
+        self._h = lib().p2o_query_create_kind(len(card), _p(card, C.c_int32), _p(bw, C.c_double), _p(alpha, C.c_double),
+                                              len(axes), _p(axes, C.c_int32), _p(placement, C.c_int32),
+                                              len(reduce_axes), _p(reduce_axes, C.c_int32), n_chunks, form_mask, op_mask,
+                                              kind)
         if not self._h:
             raise ValueError("invalid query")
         if lib().p2o_set_algo(self._h, algo) != 0:      # 0 ring, 1 tree (AllReduce only)
@@ -116,7 +123,7 @@ class Query:
             self._h = None
 
     def synthesis_hierarchy(self):
-        out = np.zeros(self.n_levels + 1, dtype=np.int32)
+        out = np.zeros(lib().p2o_synthesis_levels(self._h) + 1, dtype=np.int32)
         lib().p2o_synthesis_hierarchy(self._h, _p(out, C.c_int32))
         return out.tolist()
 

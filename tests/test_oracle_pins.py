@@ -447,6 +447,88 @@ def test_tree_model_closed_forms_and_what_it_leaves_alone(oracle):
         oracle.Query([2], [2], [[2]], [0], algo=2)
 
 
+# --------------------------------------------------------------------------- synthesis hierarchies (Sec. 3.4)
+def _lowered(q, max_len):
+    """Valid programs as the paper's lowered form: a sequence of (device groups, collective)."""
+    r = q.synthesize(max_len)
+    groups = {pid: frozenset(tuple(g) for g in q.groups(pid)) for pid in range(q.n_patterns)}
+    return {tuple((groups[int(v) // 5], int(v) % 5) for v in ins[:ln]) for ins, ln in zip(r["instr"], r["len"])}
+
+
+def _replicated(program, q, reduce_axis, matrix):
+    """Every instruction's groups repeated over the digits of the non-reduction axes (what lowering does
+    to a pattern of hierarchy (d))."""
+    n = len(matrix[0])
+    other = [i for i in range(len(matrix)) if i != reduce_axis]
+    coords = {}
+    for d in range(q.D):
+        rest, c = d, []
+        for j in reversed(range(n)):
+            hj = 1
+            for row in matrix:
+                hj *= row[j]
+            c.append(rest % hj)
+            rest //= hj
+        c.reverse()
+        dig = {}
+        for j in range(n):
+            v = c[j]
+            for i in reversed(range(len(matrix))):
+                dig[(i, j)] = v % matrix[i][j]
+                v //= matrix[i][j]
+        coords[d] = dig
+    key_of = {d: (tuple(coords[d][(reduce_axis, j)] for j in range(n)),
+                  tuple(coords[d][(i, j)] for i in other for j in range(n))) for d in range(q.D)}
+    dev_of = {v: d for d, v in key_of.items()}
+    replicas = sorted({k[1] for k in key_of.values()})
+    out = []
+    for groups, op in program:
+        rep = set()
+        for g in groups:
+            for r in replicas:
+                rep.add(tuple(sorted(dev_of[(key_of[d][0], r)] for d in g)))
+        out.append((frozenset(rep), op))
+    return tuple(out)
+
+
+@pytest.mark.parametrize("matrix,axis", [([[1, 1, 2, 2], [1, 2, 1, 2]], 1), ([[1, 1, 2, 2], [1, 2, 1, 2]], 0),
+                                         ([[1, 2, 1, 2], [1, 1, 2, 2]], 0), ([[1, 2, 2, 1], [1, 1, 1, 4]], 0)])
+def test_expressive_power_of_the_synthesis_hierarchies(oracle, matrix, axis):
+    """Sec. 3.4, Theorem (d) >= (c) >= (b) >= (a), on the running system with one reduction axis: every
+    valid lowered program of the weaker hierarchy is a lowered program of the stronger one.  One caveat,
+    which the proof sketch passes over: in (a)-(c) a Master instruction keeps only the groups whose later
+    digits are zero, and those digits may belong to a non-reduction axis, so the instruction names the
+    groups of some replicas only (which ones depends on the order of the levels).  Such programs are
+    compared after their groups are repeated over all replicas, which is what lowering does to every
+    pattern of (d); where no digit of another axis follows the reduction row nothing needs repeating.
+    (This bears on the Master reading: with one group in the whole system instead of one per replica,
+    (d) could not express the Master programs of (c) when the reduction row comes last.)"""
+    card, axes = [1, 2, 2, 4], [4, 4]
+    low = {kind: _lowered(oracle.Query(card, axes, matrix, [axis], hierarchy=kind), 4)
+           for kind in ("system", "column", "row", "reduction", "collapsed")}
+    assert low["reduction"] == low["collapsed"]                  # one axis: nothing to collapse
+    qd = oracle.Query(card, axes, matrix, [axis])
+    lifted = {kind: {_replicated(p, qd, axis, matrix) for p in low[kind]} for kind in low}
+    assert lifted["collapsed"] == low["collapsed"]               # (d) is replicated already
+    assert lifted["system"] <= lifted["column"] <= lifted["row"] <= low["collapsed"]
+    if axis == len(matrix) - 1:                                  # the reduction row is the last one
+        assert low["row"] <= low["collapsed"]
+    # and (c) is not as expressive as (d) (the counterexample after Case 1 of the theorem's third part)
+    if matrix == [[1, 1, 2, 2], [1, 2, 1, 2]] and axis == 0:
+        assert not low["collapsed"] <= lifted["row"]
+
+
+def test_hierarchy_kinds_of_the_overview_table_drive_the_patterns(oracle):
+    x = [[1, 1, 2, 2], [1, 2, 1, 2]]
+    want = {"system": [1, 1, 2, 2, 4], "column": [1, 1, 1, 1, 2, 2, 1, 2, 2], "row": [1, 1, 1, 2, 2, 1, 2, 1, 2],
+            "reduction": [1, 1, 2, 1, 2], "collapsed": [1, 1, 2, 1, 2]}
+    for kind, f in want.items():
+        q = oracle.Query([1, 2, 2, 4], [4, 4], x, [1], hierarchy=kind)
+        assert q.synthesis_hierarchy() == f                      # root level in front
+        nonunit = sum(1 for v in f if v > 1)
+        assert q.n_patterns == nonunit * nonunit                 # canonical alphabet: L^2 patterns
+
+
 # --------------------------------------------------------------------------- top-k
 def test_topk_against_lexsort(oracle):
     rng = np.random.default_rng(7)
