@@ -59,7 +59,7 @@ def cpu_baseline(queries, budget_s=15.0):
     from oracle import p2_oracle
     from paper_2110_10548_amd.workloads import SplitMix64
     cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1024")))
-    S = 250_000
+    S = 1_000_000
     total, t_all, t_one, n_one = 0, 0.0, 0.0, 0
     t_begin = time.time()
     for qi, q in enumerate(queries):

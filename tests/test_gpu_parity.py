@@ -297,6 +297,46 @@ def test_empty_and_degenerate(B):
     assert B.p2_topk(np.zeros(0), np.zeros(0, dtype=np.uint64), 5).tolist() == []
 
 
+def test_caller_stream_and_host_threads(B, oracle):
+    """The call runs on the caller's HIP stream (after work already queued there), and calls from
+    different host threads use their own device scratch."""
+    import threading
+    import torch
+    cfg, queries = queries_of(2, B)
+    msg = cfg["msg_bytes"]
+    want = B.p2_synthesize_batch(queries, msg)
+    stream = torch.cuda.Stream()                      # default priority
+    with torch.cuda.stream(stream):
+        x = torch.ones(1 << 20, device="cuda")
+        for _ in range(20):
+            x = x * 1.0001
+        got = B.p2_synthesize_batch(queries, msg, stream=stream.cuda_stream)
+    stream.synchronize()
+    for g, w in zip(got, want):
+        assert g["programs"]["index"].tolist() == w["programs"]["index"].tolist()
+        assert (g["cost"] == w["cost"]).all()
+
+    out, errors = {}, []
+
+    def worker(tag, engine):
+        try:
+            qs = [dict(q, engine=engine) for q in queries]
+            out[tag] = [B.p2_synthesize_batch(qs, msg) for _ in range(3)]
+        except Exception as e:                        # noqa: BLE001 - reported below
+            errors.append((tag, repr(e)))
+    threads = [threading.Thread(target=worker, args=(t, e)) for t, e in (("a", 0), ("b", 4), ("c", 2))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for tag in ("a", "b", "c"):
+        for res in out[tag]:
+            for g, w in zip(res, want):
+                assert g["programs"]["index"].tolist() == w["programs"]["index"].tolist()
+                assert np.allclose(g["cost"], w["cost"], rtol=RTOL, atol=0.0)
+
+
 # --------------------------------------------------------------------------- full-size configurations 3 and 4
 def _levels(q):
     f = [1] * len(q["card"])
