@@ -93,3 +93,51 @@ def expand(cfg: dict, placements) -> list:
             queries.append(dict(base, placement=placements[pi], placement_index=pi, reduce_axes=list(rs),
                                 n_chunks=cfg["n_chunks"][0]))
     return queries
+
+
+def random_queries(seed: int, count: int, max_devices: int = 64) -> list:
+    """Seeded random small queries for parity sweeps: 1-4 hardware levels with cardinalities from
+    {1, 2, 3, 4, 6, 8} (at most max_devices devices), 1-3 axes given by a random split of every level's
+    cardinality (which is a placement), a random non-empty reduce set, chunk counts around the
+    reduction-group size, random grammar masks, link parameters and cost model.  max_len is left to
+    the caller (it depends on the alphabet)."""
+    rng = SplitMix64(seed)
+    out = []
+    while len(out) < count:
+        n = 1 + rng.below(4)
+        card = [[1, 2, 3, 4, 6, 8][rng.below(6)] for _ in range(n)]
+        devices = 1
+        for c in card:
+            devices *= c
+        if devices < 2 or devices > max_devices:
+            continue
+        m = 1 + rng.below(3)
+        placement = [[1] * n for _ in range(m)]
+        for j, c in enumerate(card):
+            rest = c
+            for i in range(m - 1):
+                divisors = [d for d in range(1, rest + 1) if rest % d == 0]
+                placement[i][j] = divisors[rng.below(len(divisors))]
+                rest //= placement[i][j]
+            placement[m - 1][j] = rest
+        axes = []
+        for row in placement:
+            size = 1
+            for v in row:
+                size *= v
+            axes.append(size)
+        subsets = _subsets(m)
+        reduce_axes = subsets[rng.below(len(subsets))]
+        group = 1
+        for a in reduce_axes:
+            group *= axes[a]
+        chunks = [0, 0, group, 1, 2, 2 * group, 12, 3 * group][rng.below(8)]
+        if chunks > 128:
+            chunks = group
+        form_mask = [7, 7, 7, 3, 5, 6, 1][rng.below(7)]
+        op_mask = 31 if rng.below(3) else 1 + rng.below(31)
+        out.append(dict(card=card, axes=axes, placement=placement, reduce_axes=list(reduce_axes), n_chunks=chunks,
+                        form_mask=form_mask, op_mask=op_mask, algo=rng.below(2),
+                        bw=[rng.uniform(10e9, 400e9) for _ in range(n)],
+                        alpha=[rng.uniform(1e-6, 30e-6) for _ in range(n)]))
+    return out

@@ -122,6 +122,36 @@ def test_ragged_shapes_every_placement(B, oracle, card, axes, red, max_len, k, e
         assert_same(res, ora, 2)
 
 
+@pytest.mark.parametrize("seed", [20211020, 7])
+def test_random_queries_every_engine(B, oracle, seed):
+    """Seeded random small systems, placements, reduce sets, chunk counts, grammar masks and cost models:
+    every engine that accepts a query returns the oracle's list and costs."""
+    queries = workloads.random_queries(seed, 150)
+    msg = [float(1 << 22), 3.0e8]
+    ran = {e: 0 for e in (0, 1, 2, 3, 4, 5)}
+    for q in queries:
+        probe = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], form_mask=q["form_mask"],
+                             op_mask=q["op_mask"])
+        q["max_len"] = 1
+        while q["max_len"] < 5 and probe.alphabet > 0 and probe.num_candidates(q["max_len"] + 1) <= 200_000:
+            q["max_len"] += 1
+        _, ora = oracle_result(oracle, q, msg, form_mask=q["form_mask"], op_mask=q["op_mask"])
+        for engine in ran:
+            try:
+                res = B.p2_synthesize_batch([dict(q, engine=engine)], msg)[0]
+            except B.P2Error as e:
+                assert e.code == B.P2_EUNSUPPORTED and engine in (4, 5), (engine, q)
+                continue
+            ran[engine] += 1
+            assert res["stats"]["candidates"] == (probe.num_candidates(q["max_len"]) if probe.alphabet else 0), (engine, q)
+            try:
+                assert_same(res, ora, len(msg))
+            except AssertionError:
+                print("engine", engine, "query", q)
+                raise
+    assert min(ran[e] for e in (0, 1, 2, 3)) == len(queries) and ran[4] > 10 and ran[5] > 10, ran
+
+
 def test_small_group_engine_selection(B, oracle):
     """AUTO evaluates reduction groups of at most 32 devices with power-of-two patterns on the shared-prefix
     engine (engine 5 in the stats); it and the small-group engine (4) can also be asked for, and refuse
