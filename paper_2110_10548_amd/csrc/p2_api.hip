@@ -109,6 +109,7 @@ struct QueryRun {
     bool frontier = false;                // enumeration by size with pruning instead of index by index
     bool regs = false;                    // per-candidate small-group engine (steps computed in registers)
     bool shared = false;                  // shared-prefix engine (the common instructions of a group applied once)
+    bool auto_groups = false;             // its handed-over groups are picked up by the device-driven literal launch
     bool wave_cost = false;               // valid programs costed by the wavefront-per-program kernel
     size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
@@ -270,6 +271,24 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             off += align_up(sizeof(DevShare) * L.shares.size(), 256);
         }
     }
+    // Groups that the shared-prefix engine hands to the literal engine are found on the device, so that kernel
+    // is queued right behind the evaluation: one launch per mask width and per "state fits in LDS", each
+    // with the list of its queries.
+    struct AutoGroups { int cls = 0, max_R = 0, max_k = 0; std::vector<int32_t> qlist; size_t off = 0; };
+    std::vector<AutoGroups> autos;
+    for (int i = 0; i < n_queries; ++i) {
+        QueryRun& r = runs[i];
+        if (!r.shared || r.frontier || r.plan.n_candidates == 0) continue;
+        const int mw = r.plan.R <= 32 ? 1 : 2;
+        const int cls = mw * 2 + (front_literal_lds_bytes(r.plan.R, r.plan.k) != 0 ? 1 : 0);
+        AutoGroups* A = nullptr;
+        for (auto& a : autos) if (a.cls == cls) A = &a;
+        if (!A) { autos.emplace_back(); A = &autos.back(); A->cls = cls; }
+        A->max_R = std::max(A->max_R, r.plan.R); A->max_k = std::max(A->max_k, r.plan.k);
+        A->qlist.push_back(i);
+        r.auto_groups = true;
+    }
+    for (auto& A : autos) { A.off = off; off += align_up(sizeof(int32_t) * A.qlist.size(), 256); }
     const size_t off_msg = off;
     off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
     for (auto& r : runs) {
@@ -405,6 +424,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             std::memcpy(hb + L.off_segs, L.segs.data(), sizeof(DevSegment) * L.segs.size());
             if (!L.shares.empty()) std::memcpy(hb + L.off_shares, L.shares.data(), sizeof(DevShare) * L.shares.size());
         }
+        for (auto& A : autos) std::memcpy(hb + A.off, A.qlist.data(), sizeof(int32_t) * A.qlist.size());
         P2_HIP(hipMemcpyAsync(db, hb, blob_bytes, hipMemcpyHostToDevice, stream));
         P2_HIP(hipMemsetAsync(C.counters.p, 0, sizeof(DevCounters) * (size_t)n_queries, stream));
         // ---- evaluate every candidate of every query
@@ -434,6 +454,16 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
         }
         if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[1], stream)); g_prof.last.eval_launches = eval_launches; }
+        for (auto& A : autos) {
+            void* gs = nullptr;
+            if (!(A.cls & 1)) {
+                unsigned nb = 0;
+                P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(A.max_R, A.max_k, &nb)));
+                gs = C.lit_scratch.p;
+            }
+            P2_HIP(launch_eval_literal_groups_auto(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const int32_t*>(db + A.off),
+                                                   (int)A.qlist.size(), A.max_R, A.max_k, gs, stream));
+        }
         P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
                               hipMemcpyDeviceToHost, stream));
         P2_HIP(hipStreamSynchronize(stream));
@@ -442,17 +472,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         // candidates whose state the compact engine could not hold go through the literal engine:
         // one launch per mask-width class for the states that fit in LDS, one per query otherwise
         bool reran = false;
-        std::vector<PostLaunch> rerun_launches, group_launches;
+        std::vector<PostLaunch> rerun_launches;
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
-            if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap) continue;
+            if (hc[i].n_rerun == 0 || hc[i].n_rerun > r.rerun_cap || r.auto_groups) continue;
             reran = true;
-            if (r.shared) {
-                // the shared-prefix engine hands over whole groups (an entry is a group's first candidate)
-                // (class: mask width, and whether the state fits in LDS)
-                const int fits = front_literal_lds_bytes(r.plan.R, r.plan.k) != 0 ? 1 : 0;
-                add_seg(group_launches, mask_class(r.plan.R) * 2 + fits, r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
-            } else if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
+            if (literal_lds_bytes(r.plan.R, r.plan.k) != 0) {
                 add_seg(rerun_launches, mask_class(r.plan.R), r.plan, i, hc[i].n_rerun, 1, r.off_rerun, 0);
             } else {
                 void* gs = nullptr;
@@ -461,27 +486,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                            hc[i].n_rerun, static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun, nullptr, gs, stream));
             }
         }
-        for (auto& L : group_launches) {
-            // few groups: several blocks share a group, each judging part of the last instructions
-            unsigned total = 0;
-            for (auto& sg : L.segs) total += sg.count;
-            const uint32_t parts = std::min<uint32_t>(8, std::max<uint32_t>(1, 2048 / std::max(1u, total)));
-            L.blocks = 0;
-            for (auto& sg : L.segs) { sg.per_block = parts; sg.first_block = L.blocks; L.blocks += sg.count * parts; }
-            if (!(L.cls & 1)) {
-                unsigned nb = 0;
-                P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(L.max_R, L.max_k, &nb)));
-            }
-        }
-        if (!rerun_launches.empty() || !group_launches.empty()) {
-            P2_HIP(upload_segs({&rerun_launches, &group_launches}));
+        if (!rerun_launches.empty()) {
+            P2_HIP(upload_segs({&rerun_launches}));
             for (auto& L : rerun_launches)
                 P2_HIP(launch_eval_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
                                                 L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
-            for (auto& L : group_launches)
-                P2_HIP(launch_eval_literal_groups_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
-                                                       L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p),
-                                                       (L.cls & 1) ? nullptr : C.lit_scratch.p, stream));
         }
         if (reran) {
             P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,

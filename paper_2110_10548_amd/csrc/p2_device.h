@@ -69,7 +69,7 @@ struct DevCounters {
     uint32_t n_valid;              // entries appended to valid_idx (may exceed valid_cap)
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
     uint32_t nan_seen;
-    uint32_t pad;
+    uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
     unsigned long long steps[kCounterStripes];     // instructions applied
     unsigned long long members[kCounterStripes];   // devices taking part in those instructions, summed
     unsigned long long evaluated[kCounterStripes];           // instruction applications carried out, where they differ from `steps`
@@ -165,14 +165,14 @@ hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long
 // Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
-// Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate).
-// A unit is one (entry, part) pair of a segment (per_block = parts of an entry; first_block = first unit).
-// States that fit in LDS (front_literal_lds_bytes of max_R, max_k): one block per unit.  Otherwise the
-// blocks stride over the units, each with a slice of gscratch (literal_group_scratch_bytes).
+// Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate), for
+// the queries qlist[0 .. n_q) (device array of query numbers): counts and lists are read on the device from
+// each query's counters, so the launch can be queued right behind the evaluation kernel.  States that fit
+// in LDS (front_literal_lds_bytes of max_R, max_k) use 4096 blocks; otherwise the blocks of
+// literal_group_scratch_bytes, each with a slice of gscratch.
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks);
-hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned units,
-                                           int max_R, int max_k, const unsigned long long* list, void* gscratch,
-                                           hipStream_t stream);
+hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
+                                           void* gscratch, hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.
 hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
@@ -202,7 +202,7 @@ struct FrontCounters {
     uint32_t n_surv, n_surv_literal;        // survivors appended by the compact / literal classify kernels
     uint32_t n_goal, n_prefix, n_prefix_literal;
     uint32_t next_compact, next_literal;    // entries written to the next frontiers
-    uint32_t pad;
+    uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
     // running totals of the query
     uint32_t valid_written, pad2;
     unsigned long long steps, members;

@@ -659,21 +659,72 @@ __device__ inline void literal_group(const DevQuery& q, unsigned long long idx0,
     }
 }
 
-// Groups of many queries.  A unit of work is one (list entry, part) pair; blocks stride over the units.
-// States that fit in LDS: one unit per block.  Larger states: a fixed grid, each block with its own
-// slice of a global buffer.
+// The groups that the shared-prefix kernel has just handed over, found on the device: those of the queries
+// qlist[0 .. n_q), read from their counters and lists.  A unit of work is one (group, part) pair; blocks
+// stride over the units.  States that fit in LDS live there; larger ones in the block's slice of a global buffer.  This lets the host queue the kernel
+// right behind the evaluation, without waiting for the counts.  A query whose list overflowed is left
+// out (the host grows the list and runs the query again).  Few groups: up to 8 blocks share one.
 template <int MW>
-__global__ __launch_bounds__(kWave) void k_eval_literal_groups_list(const DevQuery* __restrict__ queries,
-                                                                    const DevPostSeg* __restrict__ segs, int n_segs,
-                                                                    const unsigned long long* __restrict__ list,
-                                                                    unsigned n_units, uint32_t* __restrict__ gscratch,
+__global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQuery* __restrict__ queries,
+                                                                    const int32_t* __restrict__ qlist, int n_q,
+                                                                    uint32_t* __restrict__ gscratch,
                                                                     unsigned long long gwords) {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
     uint32_t* const mem = gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds;
-    for (unsigned unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
-        const DevPostSeg seg = find_post_seg(segs, n_segs, unit);
-        const DevQuery& q = queries[seg.query];
+    auto count_of = [&](int i) -> uint32_t {
+        if (i >= n_q) return 0u;
+        const DevQuery& q = queries[qlist[i]];
+        const uint32_t n = q.counters->n_rerun;
+        return n <= q.rerun_cap ? n : 0u;
+    };
+    uint32_t total = 0;
+    for (int i0 = 0; i0 < n_q; i0 += kWave) {
+        uint32_t c = count_of(i0 + lane);
+        for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, kWave);
+        total += c;
+    }
+    if (total == 0) return;
+    uint32_t parts = gridDim.x / total;
+    parts = parts < 1u ? 1u : parts > 8u ? 8u : parts;
+    const unsigned long long n_units = (unsigned long long)total * parts;
+    // units differ widely in length (a group whose prefix is invalid ends at once): blocks draw them from a
+    // counter (kept with the first query's counters, zero at launch); total * parts < 2^32
+    uint32_t* const next_unit = &queries[qlist[0]].counters->next_unit;
+    // (a block's first unit is its own number, so a launch with fewer units than blocks draws nothing;
+    // later draws take four units at a time)
+    constexpr uint32_t kDraw = 4;
+    uint32_t own_lo = 0, own_hi = 0;                    // entries [own_lo, own_hi) belong to query `owner`
+    int owner = -1;
+    unsigned long long unit = blockIdx.x, unit_end = unit + 1;
+    while (unit < n_units) {
+        const uint32_t e = (uint32_t)(unit / parts);
+        const int part = (int)(unit - (unsigned long long)e * parts);
+        if (owner < 0 || e < own_lo || e >= own_hi) {
+            // the query that owns entry e: running sums of the counts, 64 queries at a time
+            uint32_t base = 0;
+            owner = -1;
+            for (int i0 = 0; i0 < n_q && owner < 0; i0 += kWave) {
+                const uint32_t c = count_of(i0 + lane);
+                uint32_t incl = c;
+                for (int off = 1; off < kWave; off <<= 1) {
+                    const uint32_t up = __shfl_up(incl, off, kWave);
+                    if (lane >= off) incl += up;
+                }
+                const bool mine = c != 0u && e >= base + incl - c && e < base + incl;
+                const unsigned long long hit = __ballot(mine);
+                if (hit != 0ull) {
+                    const int src = __ffsll((long long)hit) - 1;
+                    owner = i0 + src;
+                    own_hi = base + __shfl(incl, src, kWave);
+                    own_lo = base + __shfl(incl - c, src, kWave);
+                } else {
+                    base += __shfl(incl, kWave - 1, kWave);
+                }
+            }
+            if (owner < 0) break;                       // cannot happen: e < total
+        }
+        const DevQuery& q = queries[qlist[owner]];
         const LitLds L = carve(mem, q.R, q.k, MW);
         const FrontLit X = carve_front(L.flags + 4, q.k);
         uint32_t full[MW];
@@ -683,15 +734,18 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_list(const DevQue
             full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
         }
         unsigned long long steps = 0, members = 0;
-        // seg.per_block units share one list entry, each judging its share of the last instructions
-        const uint32_t local = unit - seg.first_block;
-        literal_group<MW>(q, list[seg.in_off + local / seg.per_block], L, X, full, lane, (int)(local % seg.per_block),
-                          (int)seg.per_block, steps, members);
+        literal_group<MW>(q, q.rerun_idx[e - own_lo], L, X, full, lane, part, (int)parts, steps, members);
         if (lane == 0 && steps) {
             atomicAdd(&q.counters->steps[unit % kCounterStripes], steps);
             atomicAdd(&q.counters->members[unit % kCounterStripes], members);
         }
         __syncthreads();
+        if (++unit == unit_end) {
+            uint32_t drawn = 0;
+            if (lane == 0) drawn = atomicAdd(next_unit, kDraw);
+            unit = (unsigned long long)gridDim.x + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn);
+            unit_end = unit + kDraw;
+        }
     }
 }
 
@@ -887,25 +941,24 @@ size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
     return per * b;
 }
 
-hipError_t launch_eval_literal_groups_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned units,
-                                           int max_R, int max_k, const unsigned long long* list, void* gscratch,
-                                           hipStream_t stream) {
-    if (n_segs == 0 || units == 0) return hipSuccess;
+hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
+                                           void* gscratch, hipStream_t stream) {
+    if (n_q == 0) return hipSuccess;
     size_t lds = front_literal_lds_bytes(max_R, max_k);
-    unsigned blocks = units;
+    unsigned blocks = 4096;
     unsigned long long gwords = 0;
     if (lds == 0) {
         if (!gscratch) return hipErrorInvalidValue;
         unsigned nb = 0;
         gwords = literal_group_scratch_bytes(max_R, max_k, &nb) / nb / 4;
-        blocks = nb < units ? nb : units;
+        blocks = nb;
     } else gscratch = nullptr;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
-    e = allow_big_lds(k_eval_literal_groups_list<MWV>, lds);                                                   \
+    e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \
     if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_eval_literal_groups_list<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, \
-                           list, units, static_cast<uint32_t*>(gscratch), gwords);
+        hipLaunchKernelGGL(k_eval_literal_groups_auto<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, qlist, n_q, \
+                           static_cast<uint32_t*>(gscratch), gwords);
     switch (mask_words(max_R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
