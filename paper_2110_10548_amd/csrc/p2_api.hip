@@ -263,6 +263,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 unsigned long long nb = (target * shq.n_items + L.blocks / 2) / std::max(1u, L.blocks);
                 nb = std::min<unsigned long long>(std::max<unsigned long long>(nb, 1), std::max(1u, shq.n_items));
                 shq.first_block = L.grid; shq.n_blocks = (uint32_t)nb;
+                shq.query = L.segs[a].query; shq.first_seg = (int32_t)a; shq.n_segs = (int32_t)(b - a); shq.pad = 0;
                 L.grid += (unsigned)nb;
                 L.shares.push_back(shq);
                 a = b;

@@ -40,6 +40,9 @@ struct DevSegment {
 struct DevShare {
     uint32_t first_block, n_blocks;
     uint32_t first_item, n_items;
+    int32_t query;                 // the query, and its segments [first_seg, first_seg + n_segs) of the launch's table
+    int32_t first_seg, n_segs;
+    int32_t pad;
 };
 
 // Work of the kernels that run after the evaluation (ordering, costing, literal re-runs), which

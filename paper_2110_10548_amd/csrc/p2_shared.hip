@@ -28,8 +28,6 @@ namespace p2 {
 
 namespace {
 
-constexpr int kSegCache = 512;       // segments whose first items the evaluation kernel keeps in LDS
-
 enum : int { WSTEP_INVALID = 0, WSTEP_OK = 1, WSTEP_GIVE_UP = 2 };
 
 template <int N>
@@ -135,72 +133,66 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
     __shared__ uint16_t sdig[kMaxPatterns * 5];              // digit -> (pattern id << 3) | op
     __shared__ uint32_t sshape[kMaxPatterns];                // pattern id -> lg | ls << 4 | master << 8 | participating devices << 16
     __shared__ unsigned long long spart[kMaxPatterns];       // pattern id -> bit d set iff device d takes part
-    __shared__ uint32_t sfirst[kSegCache];                   // first item of every segment, where the table fits
+    __shared__ DevSegment sseg[P2_MAX_LEN + 1];              // the segments of this block's query (one per program length)
     const int lane = threadIdx.x;
-    const bool cached = n_segs <= kSegCache;
-    if (cached) {
-        for (int i = lane; i < n_segs; i += kWave) sfirst[i] = segs[i].first_block;
-        __syncthreads();
-    }
-    // the query this block works for
+    // The share (hence the query) this block works for: the last one whose first_block <= blockIdx.x.
+    // The lanes read 64 table entries at a time, so the search costs one memory round trip per 64 shares.
     DevShare sh;
     {
-        int a = 0, b = n_shares - 1;                 // last share whose first_block <= blockIdx.x
-        while (a < b) {
-            const int mid = (a + b + 1) >> 1;
-            if (shares[mid].first_block <= blockIdx.x) a = mid; else b = mid - 1;
+        static_assert(sizeof(DevShare) == 32, "a share is read as two 16-byte words");
+        sh.first_block = 0; sh.n_blocks = 1; sh.first_item = 0; sh.n_items = 0; sh.query = 0; sh.first_seg = 0; sh.n_segs = 0; sh.pad = 0;
+        for (int base = 0; base < n_shares; base += kWave) {
+            const int i = base + lane;
+            uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
+            if (i < n_shares) {
+                const uint4* sp = reinterpret_cast<const uint4*>(shares + i);
+                lo = sp[0]; hi = sp[1];
+            }
+            const int n_le = __popcll(__ballot(i < n_shares && lo.x <= blockIdx.x));
+            if (n_le > 0) {
+                const int src = n_le - 1;
+                sh.first_block = (uint32_t)__builtin_amdgcn_readlane((int)lo.x, src);
+                sh.n_blocks = (uint32_t)__builtin_amdgcn_readlane((int)lo.y, src);
+                sh.first_item = (uint32_t)__builtin_amdgcn_readlane((int)lo.z, src);
+                sh.n_items = (uint32_t)__builtin_amdgcn_readlane((int)lo.w, src);
+                sh.query = __builtin_amdgcn_readlane((int)hi.x, src);
+                sh.first_seg = __builtin_amdgcn_readlane((int)hi.y, src);
+                sh.n_segs = __builtin_amdgcn_readlane((int)hi.z, src);
+            }
+            if (n_le < kWave) break;
         }
-        sh = shares[a];
     }
+    // everything else the block needs from memory is asked for at once: the query's tables, its segments
+    // and a few scalars
+    const DevQuery* const qp = queries + sh.query;
+    const DevQuery& q = *qp;
+    for (int i = lane; i < q.n_patterns; i += kWave) { sshape[i] = q.reg_shape[i]; spart[i] = q.reg_part[i]; }
+    for (int i = lane; i < q.alphabet; i += kWave) sdig[i] = q.instr_of_digit[i];
+    if (lane < sh.n_segs) sseg[lane] = segs[sh.first_seg + lane];
+    const int R = q.R;
+    const int devs = R > 32 ? 64 : 32;
+    const int dev = lane & (devs - 1);
+    const uint32_t I = (uint32_t)q.alphabet;
+    const Words<KW> all_rows = full_mask<KW>(q.k);
+    const Words<MW> all_cols = full_mask<MW>(R);
+    const uint32_t sum_part = q.reg_sum_part;           // participating devices summed over the alphabet
+    __syncthreads();
+    int cur = -1;                                       // segment of the current item
     DevSegment seg;
-    seg.first_block = 0; seg.query = -1; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
-    uint32_t next_first = 0;                         // first item of the next segment
-    const DevQuery* qp = nullptr;
-    int len = 1, R = 1, devs = 32, dev = lane & 31;
-    uint32_t I = 1;
-    Words<KW> all_rows;
-    Words<MW> all_cols;
-    clear(all_rows); clear(all_cols);
-    uint32_t sum_part = 0;                           // participating devices summed over the alphabet
+    seg.first_block = 0; seg.query = sh.query; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
+    uint32_t next_first = 0;                            // first item of the next segment
+    int len = 1;
     uint32_t items_per_stem = 1;
     unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
     const uint32_t end_item = sh.first_item + sh.n_items;
     for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
-        if (qp == nullptr || item >= next_first) {
-            int a = 0, b = n_segs - 1;               // last segment whose first_block <= item
-            while (a < b) {
-                const int mid = (a + b + 1) >> 1;
-                if ((cached ? sfirst[mid] : segs[mid].first_block) <= item) a = mid; else b = mid - 1;
-            }
-            const int old_query = seg.query;
-            seg = segs[a];
-            next_first = a + 1 < n_segs ? (cached ? sfirst[a + 1] : segs[a + 1].first_block) : 0xffffffffu;
-            if (seg.query != old_query) {
-                // hand the finished query its counts, then load the new query's tables
-                if (lane == 0 && (steps | evaluated) != 0ull) {
-                    atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
-                    atomicAdd(&qp->counters->members[blockIdx.x % kCounterStripes], members);
-                    atomicAdd(&qp->counters->evaluated[blockIdx.x % kCounterStripes], evaluated);
-                    atomicAdd(&qp->counters->evaluated_members[blockIdx.x % kCounterStripes], evaluated_members);
-                }
-                steps = 0; members = 0; evaluated = 0; evaluated_members = 0;
-                qp = queries + seg.query;
-                __syncthreads();
-                for (int i = lane; i < qp->n_patterns; i += kWave) { sshape[i] = qp->reg_shape[i]; spart[i] = qp->reg_part[i]; }
-                for (int i = lane; i < qp->alphabet; i += kWave) sdig[i] = qp->instr_of_digit[i];
-                __syncthreads();
-                R = qp->R;
-                devs = R > 32 ? 64 : 32;
-                dev = lane & (devs - 1);
-                I = (uint32_t)qp->alphabet;
-                all_rows = full_mask<KW>(qp->k);
-                all_cols = full_mask<MW>(R);
-                sum_part = qp->reg_sum_part;
-            }
+        if (item >= next_first) {
+            while (cur + 1 < sh.n_segs && sseg[cur + 1].first_block <= item) ++cur;
+            seg = sseg[cur];
+            next_first = cur + 1 < sh.n_segs ? sseg[cur + 1].first_block : 0xffffffffu;
             len = seg.len;
             items_per_stem = len >= 2 ? (I + (uint32_t)seg.iters - 1u) / (uint32_t)seg.iters : 1u;
         }
-        const DevQuery& q = *qp;
         // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
         // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
         const uint32_t rel = item - seg.first_block;
