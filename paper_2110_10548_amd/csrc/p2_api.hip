@@ -213,6 +213,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (int len = 2; len <= pl.max_len; ++len)
             shared_stems += (pl.base[len + 1] - pl.base[len]) / ((unsigned long long)pl.alphabet * (unsigned long long)pl.alphabet);
     }
+    const unsigned long long shared_cut = shared_stems >= (1ull << 17) ? 1 : shared_stems >= (1ull << 15) ? 2 : 4;
     for (auto& L : launches) {
         const int lanes = L.kind != 0 ? 64 : compact_lanes(L.max_R, L.max_k);
         if (lanes == 0) return fail(P2_EUNSUPPORTED, "state too large for the compact engine");
@@ -232,11 +233,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     // instructions).  With few stems a stem is cut into four items, which balances the load
                     // of the fixed grid; with many stems a whole stem is one item, so its state is worked out once
                     const unsigned long long I = (unsigned long long)pl.alphabet;
-                    const unsigned long long cut = shared_stems >= (1ull << 17) ? 1 : shared_stems >= (1ull << 15) ? 2 : 4;
-                    const unsigned long long per_item = len >= 2 ? (I + cut - 1) / cut : 1;
-                    const unsigned long long items_per_stem = len >= 2 ? (I + per_item - 1) / per_item : 1;
+                    const unsigned long long per_item = len >= 2 ? (I + shared_cut - 1) / shared_cut : 1;
                     sg.iters = (int)per_item;
-                    blocks += len >= 2 ? (count / (I * I)) * items_per_stem : 1;
+                    blocks += len >= 2 ? (count / (I * I)) * shared_cut : 1;     // (items past a short stem's groups are empty)
                 } else {
                     const unsigned long long chunks = (count + lanes - 1) / lanes;
                     unsigned long long iters = (chunks + 4095) / 4096;
@@ -263,7 +262,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 unsigned long long nb = (target * shq.n_items + L.blocks / 2) / std::max(1u, L.blocks);
                 nb = std::min<unsigned long long>(std::max<unsigned long long>(nb, 1), std::max(1u, shq.n_items));
                 shq.first_block = L.grid; shq.n_blocks = (uint32_t)nb;
-                shq.query = L.segs[a].query; shq.first_seg = (int32_t)a; shq.n_segs = (int32_t)(b - a); shq.pad = 0;
+                shq.query = L.segs[a].query; shq.first_seg = (int32_t)a; shq.n_segs = (int32_t)(b - a);
+                shq.cut_log = shared_cut == 4 ? 2 : shared_cut == 2 ? 1 : 0;
                 L.grid += (unsigned)nb;
                 L.shares.push_back(shq);
                 a = b;

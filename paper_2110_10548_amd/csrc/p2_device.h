@@ -42,7 +42,7 @@ struct DevShare {
     uint32_t first_item, n_items;
     int32_t query;                 // the query, and its segments [first_seg, first_seg + n_segs) of the launch's table
     int32_t first_seg, n_segs;
-    int32_t pad;
+    int32_t cut_log;               // a stem of a segment with len >= 2 is 2^cut_log items of seg.iters groups each
 };
 
 // Work of the kernels that run after the evaluation (ordering, costing, literal re-runs), which

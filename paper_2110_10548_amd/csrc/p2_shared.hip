@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
     DevShare sh;
     {
         static_assert(sizeof(DevShare) == 32, "a share is read as two 16-byte words");
-        sh.first_block = 0; sh.n_blocks = 1; sh.first_item = 0; sh.n_items = 0; sh.query = 0; sh.first_seg = 0; sh.n_segs = 0; sh.pad = 0;
+        sh.first_block = 0; sh.n_blocks = 1; sh.first_item = 0; sh.n_items = 0; sh.query = 0; sh.first_seg = 0; sh.n_segs = 0; sh.cut_log = 0;
         for (int base = 0; base < n_shares; base += kWave) {
             const int i = base + lane;
             uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
@@ -158,6 +158,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 sh.query = __builtin_amdgcn_readlane((int)hi.x, src);
                 sh.first_seg = __builtin_amdgcn_readlane((int)hi.y, src);
                 sh.n_segs = __builtin_amdgcn_readlane((int)hi.z, src);
+                sh.cut_log = __builtin_amdgcn_readlane((int)hi.w, src);
             }
             if (n_le < kWave) break;
         }
@@ -173,6 +174,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
     const int devs = R > 32 ? 64 : 32;
     const int dev = lane & (devs - 1);
     const uint32_t I = (uint32_t)q.alphabet;
+    const uint32_t magic = q.magic_alphabet;            // ceil(2^32 / I): v / I == umulhi(v, magic) for v < 2^23
     const Words<KW> all_rows = full_mask<KW>(q.k);
     const Words<MW> all_cols = full_mask<MW>(R);
     const uint32_t sum_part = q.reg_sum_part;           // participating devices summed over the alphabet
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
     seg.first_block = 0; seg.query = sh.query; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
     uint32_t next_first = 0;                            // first item of the next segment
     int len = 1;
-    uint32_t items_per_stem = 1;
+    uint32_t items_log = 0;                             // a stem is cut into 2^items_log items of seg.iters groups
     unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
     const uint32_t end_item = sh.first_item + sh.n_items;
     for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
@@ -191,21 +193,25 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
             seg = sseg[cur];
             next_first = cur + 1 < sh.n_segs ? sseg[cur + 1].first_block : 0xffffffffu;
             len = seg.len;
-            items_per_stem = len >= 2 ? (I + (uint32_t)seg.iters - 1u) / (uint32_t)seg.iters : 1u;
+            items_log = len >= 2 ? (uint32_t)sh.cut_log : 0u;
         }
         // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
         // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
         const uint32_t rel = item - seg.first_block;
-        const uint32_t S = rel / items_per_stem;
-        const uint32_t dlast0 = len >= 2 ? (rel - S * items_per_stem) * (uint32_t)seg.iters : 0u;
+        const uint32_t S = rel >> items_log;
+        const uint32_t dlast0 = (rel - (S << items_log)) * (uint32_t)seg.iters;
+        if (len >= 2 && dlast0 >= I) continue;           // the stem has fewer groups than items: nothing here
         const uint32_t n_here = len >= 2 ? (I - dlast0 < (uint32_t)seg.iters ? I - dlast0 : (uint32_t)seg.iters) : 1u;
         uint32_t dg[P2_MAX_LEN];
         {
             uint32_t rem = S;
+            const bool small = S < (1u << 23);           // then a multiplication divides by the alphabet
 #pragma unroll
             for (int t = P2_MAX_LEN - 3; t >= 0; --t) {
-                if (t < len - 2) { const uint32_t nx = rem / I; dg[t] = rem - nx * I; rem = nx; }
-                else dg[t] = 0;
+                if (t < len - 2) {
+                    const uint32_t nx = small ? __umulhi(rem, magic) : rem / I;
+                    dg[t] = rem - nx * I; rem = nx;
+                } else dg[t] = 0;
             }
         }
         // offset in the segment of the first candidate of the item's first group
