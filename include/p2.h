@@ -163,9 +163,8 @@ typedef struct {
  * every requested reduction).  All queries share msg_bytes.  Results of query i occupy
  * out_prog[out_offset[i] .. out_offset[i+1]) and the matching rows of out_cost;
  * out_offset has n_queries + 1 entries; stats (optional) has n_queries entries.
- * The kernels of all queries share their launches; the call waits for the device after the
- * evaluation (to size the lists), after the candidates handed to the literal engine, and for
- * the results. */
+ * The kernels of all queries share their launches; the call waits for the device twice: after
+ * the evaluation (to size the result lists) and for the results. */
 int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
                             p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset,
                             p2_stats* stats);
