@@ -116,7 +116,7 @@ struct QueryRun {
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
     uint32_t valid_cap = 0, rerun_cap = 0;
     size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
-    uint32_t n_valid = 0, n_rerun = 0;
+    uint32_t n_valid = 0, n_rerun = 0, n_rerun_groups = 0;
     unsigned long long steps = 0, members = 0;
     unsigned long long evaluated = 0, evaluated_members = 0;   // instruction applications carried out where they differ from steps
     size_t out_first = 0;                 // first row of this query in the sorted/prog/cost buffers
@@ -456,14 +456,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[1], stream)); g_prof.last.eval_launches = eval_launches; }
         for (auto& A : autos) {
-            void* gs = nullptr;
-            if (!(A.cls & 1)) {
-                unsigned nb = 0;
-                P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(A.max_R, A.max_k, &nb)));
-                gs = C.lit_scratch.p;
-            }
+            unsigned nb = 0;
+            P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(A.max_R, A.max_k, &nb)));
             P2_HIP(launch_eval_literal_groups_auto(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const int32_t*>(db + A.off),
-                                                   (int)A.qlist.size(), A.max_R, A.max_k, gs, stream));
+                                                   (int)A.qlist.size(), A.max_R, A.max_k, C.lit_scratch.p, stream));
         }
         P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
                               hipMemcpyDeviceToHost, stream));
@@ -500,7 +496,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
-            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun;
+            r.n_valid = hc[i].n_valid; r.n_rerun = hc[i].n_rerun; r.n_rerun_groups = hc[i].n_rerun_groups;
             r.steps = 0; r.members = 0;
             for (int t = 0; t < kCounterStripes; ++t) { r.steps += hc[i].steps[t]; r.members += hc[i].members[t]; }
             r.evaluated = 0; r.evaluated_members = 0;
@@ -761,7 +757,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (stats) {
             p2_stats& s = stats[i];
             s.candidates = r.plan.n_candidates; s.steps_executed = r.steps; s.member_visits = r.members;
-            s.literal_reruns = r.shared ? (uint64_t)r.n_rerun * (uint64_t)r.plan.alphabet : r.n_rerun;
+            s.literal_reruns = r.shared ? (uint64_t)r.n_rerun_groups * (uint64_t)r.plan.alphabet : r.n_rerun;
             s.steps_evaluated = r.shared ? r.evaluated : r.steps;
             s.members_evaluated = r.shared ? r.evaluated_members : r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();

@@ -66,6 +66,13 @@ __device__ inline DevPostSeg find_post_seg(const DevPostSeg* __restrict__ segs, 
     return segs[a];
 }
 
+// Entries of rerun_idx written by the shared-prefix engine: the index of a group's first candidate, or,
+// with kStemEntry set, of the first candidate of the first of `count` consecutive groups under one
+// stem whose own state left the compact form (count in bits 52..62; candidate indices stay below 2^52).
+constexpr unsigned long long kStemEntry = 1ull << 63;
+constexpr int kStemCountShift = 52;
+constexpr unsigned long long kEntryIndexMask = (1ull << kStemCountShift) - 1ull;
+
 // Counters a query's kernels add to.
 constexpr int kCounterStripes = 64;   // blocks add to stripe (blockIdx % 64): same-address atomics serialise
 struct DevCounters {
@@ -73,6 +80,8 @@ struct DevCounters {
     uint32_t n_rerun;              // entries appended to rerun_idx (compact engine gave up)
     uint32_t nan_seen;
     uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
+    uint32_t n_rerun_groups;       // shared-prefix engine: groups behind the rerun_idx entries (a stem entry stands for several)
+    uint32_t pad[3];
     unsigned long long steps[kCounterStripes];     // instructions applied
     unsigned long long members[kCounterStripes];   // devices taking part in those instructions, summed
     unsigned long long evaluated[kCounterStripes];           // instruction applications carried out, where they differ from `steps`
@@ -174,6 +183,7 @@ hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* s
 // in LDS (front_literal_lds_bytes of max_R, max_k) use 4096 blocks; otherwise the blocks of
 // literal_group_scratch_bytes, each with a slice of gscratch.
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks);
+// gscratch (literal_group_scratch_bytes) is needed in both cases: a stem entry keeps a copy of the stem's state there.
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
                                            void* gscratch, hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.

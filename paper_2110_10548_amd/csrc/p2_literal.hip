@@ -659,6 +659,68 @@ __device__ inline void literal_group(const DevQuery& q, unsigned long long idx0,
     }
 }
 
+// `count` consecutive groups under one stem whose state left the compact form (kStemEntry): the stem's
+// literal state is rebuilt once and kept in `backup`; every group then adds its own instruction to it
+// (an invalid instruction leaves the state as it was, a valid one is undone from the copy) and judges all
+// last instructions as literal_group does.  Part `part` of `parts` takes the groups part, part + parts, ...
+// and counts the steps of their candidates.
+template <int MW>
+__device__ inline void literal_stem(const DevQuery& q, unsigned long long idx0, int count, const LitLds& L, const FrontLit& X,
+                                    const uint32_t* full, int lane, int part, int parts, uint32_t* __restrict__ backup,
+                                    unsigned long long& steps, unsigned long long& members) {
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx0, digit);         // len >= 3: digit[len-2] is the first group's instruction
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    lit_init<MW>(q, L, lane);
+    bool ok = true;
+    unsigned long long ran = 0, visited = 0;
+    for (int t = 0; t < len - 2 && ok; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ++ran;
+        visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        ok = lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr);
+    }
+    const int mine = part < count ? (count - part + parts - 1) / parts : 0;      // groups of this part
+    if (!ok) {                                      // every candidate under the stem stops inside it
+        steps += (unsigned long long)mine * I * ran;
+        members += (unsigned long long)mine * I * visited;
+        return;
+    }
+    const int s_words = q.R * q.k * MW;
+    __syncthreads();
+    for (int i = lane; i < s_words; i += kWave) backup[i] = L.S[i];
+    bool dirty = false;
+    for (int gi = part; gi < count; gi += parts) {
+        if (dirty) {
+            __syncthreads();
+            for (int i = lane; i < s_words; i += kWave) L.S[i] = backup[i];
+            __syncthreads();
+            dirty = false;
+        }
+        const int dgt = (int)digit[len - 2] + gi;
+        const int pid = dgt / q.n_ops, op = q.ops[dgt - pid * q.n_ops];
+        const unsigned long long g_ran = ran + 1ull;
+        const unsigned long long g_vis = visited + (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        if (!lit_step<MW, false>(q, q.pat[pid], op, L, lane, nullptr)) {
+            steps += I * g_ran;
+            members += I * g_vis;
+            continue;
+        }
+        dirty = true;
+        const int C = row_classes<MW>(q, L, X, full, lane);
+        const unsigned long long first = idx0 + (unsigned long long)gi * I;
+        for (int a = 0; a < q.alphabet; ++a) {
+            const uint32_t ins = q.instr_of_digit[a];
+            if (lit_classify<MW>(q, q.pat[ins >> 3], (int)(ins & 7u), L, X, C, full, lane) == 2 && lane == 0) {
+                const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+                if (pos < q.valid_cap) q.valid_idx[pos] = first + (unsigned long long)a;
+            }
+        }
+        steps += I * (g_ran + 1ull);
+        members += I * g_vis + (unsigned long long)q.reg_sum_part;
+    }
+}
+
 // The groups that the shared-prefix kernel has just handed over, found on the device: those of the queries
 // qlist[0 .. n_q), read from their counters and lists.  A unit of work is one (group, part) pair; blocks
 // stride over the units.  States that fit in LDS live there; larger ones in the block's slice of a global buffer.  This lets the host queue the kernel
@@ -668,10 +730,12 @@ template <int MW>
 __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQuery* __restrict__ queries,
                                                                     const int32_t* __restrict__ qlist, int n_q,
                                                                     uint32_t* __restrict__ gscratch,
-                                                                    unsigned long long gwords) {
+                                                                    unsigned long long gwords, int state_in_lds) {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
-    uint32_t* const mem = gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds;
+    // the block's slice of the global buffer: the state itself where it does not fit in LDS, then the stem copy
+    uint32_t* const slice = gscratch + (size_t)blockIdx.x * gwords;
+    uint32_t* const mem = state_in_lds ? lds : slice;
     auto count_of = [&](int i) -> uint32_t {
         if (i >= n_q) return 0u;
         const DevQuery& q = queries[qlist[i]];
@@ -734,7 +798,15 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
             full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
         }
         unsigned long long steps = 0, members = 0;
-        literal_group<MW>(q, q.rerun_idx[e - own_lo], L, X, full, lane, part, (int)parts, steps, members);
+        const unsigned long long entry = q.rerun_idx[e - own_lo];
+        if (entry & kStemEntry) {
+            LitLayout lay(q.R, q.k, MW);
+            uint32_t* const backup = state_in_lds ? slice : slice + lay.total_words() + front_lit_words(q.k);
+            literal_stem<MW>(q, entry & kEntryIndexMask, (int)((entry >> kStemCountShift) & 0x7ffull), L, X, full, lane, part,
+                             (int)parts, backup, steps, members);
+        } else {
+            literal_group<MW>(q, entry, L, X, full, lane, part, (int)parts, steps, members);
+        }
         if (lane == 0 && steps) {
             atomicAdd(&q.counters->steps[unit % kCounterStripes], steps);
             atomicAdd(&q.counters->members[unit % kCounterStripes], members);
@@ -932,9 +1004,11 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
 }
 
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
-    // group states that do not fit in LDS: up to 4096 blocks, each with its own global slice
+    // up to 4096 blocks, each with its own global slice: the copy of a stem's state, and in front of it
+    // the state itself with its tables where that does not fit in LDS
     LitLayout lay(max_R, max_k, mask_words(max_R));
-    const size_t per = ((size_t)(lay.total_words() + front_lit_words(max_k)) * 4 + 255) / 256 * 256;
+    const size_t state = front_literal_lds_bytes(max_R, max_k) != 0 ? 0 : (size_t)(lay.total_words() + front_lit_words(max_k));
+    const size_t per = ((state + (size_t)lay.s_words) * 4 + 255) / 256 * 256;
     unsigned b = 4096;
     while (b > 1 && per * b > ((size_t)8 << 30)) b >>= 1;
     *blocks = b;
@@ -944,21 +1018,17 @@ size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
                                            void* gscratch, hipStream_t stream) {
     if (n_q == 0) return hipSuccess;
-    size_t lds = front_literal_lds_bytes(max_R, max_k);
-    unsigned blocks = 4096;
-    unsigned long long gwords = 0;
-    if (lds == 0) {
-        if (!gscratch) return hipErrorInvalidValue;
-        unsigned nb = 0;
-        gwords = literal_group_scratch_bytes(max_R, max_k, &nb) / nb / 4;
-        blocks = nb;
-    } else gscratch = nullptr;
+    const size_t lds = front_literal_lds_bytes(max_R, max_k);
+    if (!gscratch) return hipErrorInvalidValue;
+    unsigned blocks = 0;
+    const unsigned long long gwords = literal_group_scratch_bytes(max_R, max_k, &blocks) / blocks / 4;
+    const int state_in_lds = lds != 0 ? 1 : 0;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_eval_literal_groups_auto<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, qlist, n_q, \
-                           static_cast<uint32_t*>(gscratch), gwords);
+                           static_cast<uint32_t*>(gscratch), gwords, state_in_lds);
     switch (mask_words(max_R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;

@@ -30,6 +30,10 @@ namespace {
 
 enum : int { WSTEP_INVALID = 0, WSTEP_OK = 1, WSTEP_GIVE_UP = 2 };
 
+// Groups per hand-over entry of a stem whose own state leaves the compact form: the literal engine rebuilds
+// the stem once per entry, so more groups save work, fewer keep its units of work short.
+constexpr uint32_t kStemGroups = 4;
+
 template <int N>
 __device__ __forceinline__ Words<N> exchange(const Words<N>& a, int lane_xor) {
     Words<N> o;
@@ -240,6 +244,23 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
             members += (unsigned long long)(n_here * I) * c_visited;
             continue;
         }
+        if (c_rc == WSTEP_GIVE_UP) {
+            // the stem's own state leaves the compact form: the literal engine gets the item's groups in
+            // entries of up to kStemGroups groups, rebuilds the stem once per entry and evaluates (and counts)
+            // every group from there
+            if (lane == 0) {
+                const uint32_t n_entries = (n_here + kStemGroups - 1u) / kStemGroups;
+                const uint32_t pos = atomicAdd(&q.counters->n_rerun, n_entries);
+                for (uint32_t j = 0; j < n_entries; ++j) {
+                    const uint32_t cnt = n_here - kStemGroups * j < kStemGroups ? n_here - kStemGroups * j : kStemGroups;
+                    if (pos + j < q.rerun_cap)
+                        q.rerun_idx[pos + j] = kStemEntry | ((unsigned long long)cnt << kStemCountShift) |
+                                               (seg.first_index + first_off + (unsigned long long)(kStemGroups * j) * I);
+                }
+                atomicAdd(&q.counters->n_rerun_groups, n_here);
+            }
+            continue;
+        }
         uint32_t item_steps = 0, item_members = 0;   // an item is at most alphabet / 4 groups: these stay below 2^32
         for (uint32_t gi = 0; gi < n_here; ++gi, first_off += I) {
             Words<KW> rv = c_rv;
@@ -260,6 +281,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 if (lane == 0) {
                     const uint32_t pos = atomicAdd(&q.counters->n_rerun, 1u);
                     if (pos < q.rerun_cap) q.rerun_idx[pos] = seg.first_index + first_off;
+                    atomicAdd(&q.counters->n_rerun_groups, 1u);
                 }
             } else if (rc == WSTEP_INVALID) {
                 item_steps += I * g_ran;
