@@ -813,6 +813,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
         }
         __syncthreads();
         if (++unit == unit_end) {
+            if (n_units <= gridDim.x) break;            // every unit was some block's first: nothing to draw
             uint32_t drawn = 0;
             if (lane == 0) drawn = atomicAdd(next_unit, kDraw);
             unit = (unsigned long long)gridDim.x + (uint32_t)__builtin_amdgcn_readfirstlane((int)drawn);
