@@ -520,6 +520,30 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         r.off_fvalid = fvalid_used;
         r.n_valid = 0; r.n_rerun = 0; r.steps = 0; r.members = 0;
         if (pl.n_candidates == 0) continue;
+        // Validity depends on the reduction group, the chunks, the patterns and the alphabet only (not on
+        // the links, nor on where the placement puts the group in the system): a query that equals an
+        // earlier one of the batch in these takes over its list of valid programs and its counts.  Its
+        // costs are still worked out from its own bandwidth rows.
+        {
+            int same = -1;
+            for (int j = 0; j < i && same < 0; ++j) {
+                const Plan& o = runs[j].plan;
+                if (!runs[j].frontier || o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet ||
+                    o.n_ops != pl.n_ops || o.patterns.size() != pl.patterns.size() || o.n_candidates != pl.n_candidates)
+                    continue;
+                bool eq = true;
+                for (int t = 0; t < pl.n_ops && eq; ++t) eq = o.ops[t] == pl.ops[t];
+                for (size_t t = 0; t < pl.patterns.size() && eq; ++t)
+                    eq = o.patterns[t].g == pl.patterns[t].g && o.patterns[t].s == pl.patterns[t].s &&
+                         o.patterns[t].master == pl.patterns[t].master && o.patterns[t].n_groups == pl.patterns[t].n_groups;
+                if (eq) same = j;
+            }
+            if (same >= 0) {
+                const QueryRun& o = runs[same];
+                r.off_fvalid = o.off_fvalid; r.n_valid = o.n_valid; r.n_rerun = o.n_rerun; r.steps = o.steps; r.members = o.members;
+                continue;
+            }
+        }
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
         const size_t sw = frontier_state_words(pl.R, pl.k);
         P2_HIP(C.f_ctr.ensure(sizeof(FrontCounters)));

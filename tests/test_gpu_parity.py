@@ -561,3 +561,20 @@ def test_config5_sampled(B, oracle):
             nvalid, _, _ = oq.eval_indices(q["max_len"], indices=near, n_threads=2)
             assert nvalid == 0
     assert checked >= 4
+    # queries that agree in reduction group, chunks, patterns and alphabet take over the first one's list
+    # inside the library; their costs stay their own: check the last such query against the oracle too
+    seen, twin = {}, None
+    for n, (q, res) in enumerate(zip(mine, results)):
+        key = (res["stats"]["group_size"], res["stats"]["n_patterns"], res["stats"]["alphabet"], _levels(q))
+        if key in seen and key[3] >= 2:
+            assert res["programs"]["index"].tolist() == results[seen[key]]["programs"]["index"].tolist()
+            twin = n
+        seen.setdefault(key, n)
+    assert twin is not None
+    q, res = mine[twin], results[twin]
+    progs = res["programs"]
+    oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"])
+    for i in rng.choice(len(progs), size=2, replace=False):
+        instr = progs["instr"][i][:progs["len"][i]].tolist()
+        ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
+        assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
