@@ -73,7 +73,10 @@ int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int3
 #define P2_ENGINE_COMPACT 2   /* per device one chunk set and one contribution mask, in LDS; one
                                  candidate per lane                                               */
 #define P2_ENGINE_FRONTIER 3  /* enumeration by program size with pruning (Sec. 3.5): only valid
-                                 prefixes are extended; AUTO picks it above 2^30 candidates       */
+                                 prefixes are extended; AUTO picks it above 2^30 candidates.
+                                 Queries of one batch with the same reduction-group size, chunk
+                                 count, patterns, alphabet and size limit are enumerated once (the
+                                 later ones report the first one's counts in their stats)        */
 #define P2_ENGINE_SMALL 4     /* compact form for reduction groups of at most 32 devices, at most
                                  32 chunks and patterns whose group size and stride are powers of
                                  two: one candidate per lane, every step computed in registers;
