@@ -237,6 +237,13 @@ typedef struct {
 int32_t p2_set_profiling(int32_t on);
 int32_t p2_get_profile(p2_profile* out);
 
+/* Measurement aid: the best rate, in lane-operations per second, that `reps` (1..100) timed runs of a
+ * stream of independent 32-bit integer vector instructions reach on the current device; the
+ * evaluators' lane-operation rates (Sec. 3.2's rules are bit operations on the device masks) are set
+ * against the ceiling derived from the unit counts and the clock, and this shows how close the
+ * device comes to it.  hip_stream: hipStream_t or NULL.  P2_EINVAL on bad arguments. */
+int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_stream);
+
 const char* p2_last_error(void);
 
 #ifdef __cplusplus

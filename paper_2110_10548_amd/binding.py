@@ -64,7 +64,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements")
+           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak")
 
 _lib = None
 
@@ -98,6 +98,8 @@ def lib():
         L.p2_search_placements.argtypes = [C.POINTER(p2_hierarchy), i32p, C.c_int32, i32p, i32p, C.c_int32, f64p, C.c_int32,
                                            C.c_double, C.POINTER(p2_options), i32p, C.POINTER(p2_search_row), f64p, i32p,
                                            C.c_int64, i64p]
+        L.p2_measure_alu_peak.restype = C.c_int32
+        L.p2_measure_alu_peak.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
         L.p2_topk.restype = C.c_int32
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
@@ -303,6 +305,13 @@ def p2_search_placements(card, axes, reduce_sets, max_len, msg_bytes, bw=None, a
                                  "best_instr": [int(r.best.instr[t]) for t in range(r.best.len)],
                                  "best_cost": float(r.best_cost), "allreduce_cost": float(r.allreduce_cost)}
     return {"placements": pls[:n].tolist(), "rows": out_rows, "total": total[:n].tolist(), "order": order[:n].tolist()}
+
+
+def p2_measure_alu_peak(reps=5, stream=None):
+    """Measured rate of independent 32-bit integer vector instructions, lane-operations per second."""
+    out = C.c_double()
+    _check(lib().p2_measure_alu_peak(reps, C.byref(out), stream))
+    return out.value
 
 
 def p2_set_profiling(on):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libp2.so")
-SOURCES = ["p2_plan.cpp", "p2_literal.hip", "p2_compact.hip", "p2_regs.hip", "p2_shared.hip", "p2_frontier.hip", "p2_select.hip", "p2_api.hip"]
+SOURCES = ["p2_plan.cpp", "p2_literal.hip", "p2_compact.hip", "p2_regs.hip", "p2_shared.hip", "p2_frontier.hip", "p2_select.hip", "p2_peak.hip", "p2_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

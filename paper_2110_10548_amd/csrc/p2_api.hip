@@ -812,6 +812,12 @@ int32_t p2_get_profile(p2_profile* out) {
     return P2_OK;
 }
 
+int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_stream) {
+    if (!out_lane_ops_per_s || reps < 1 || reps > 100) return fail(P2_EINVAL, "bad arguments");
+    P2_HIP(p2::measure_alu_peak(reps, out_lane_ops_per_s, (hipStream_t)hip_stream));
+    return P2_OK;
+}
+
 int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, int32_t* out, int64_t cap,
                                 int64_t* out_count) {
     std::string err;

@@ -327,6 +327,14 @@ def test_empty_and_degenerate(B):
     assert B.p2_topk(np.zeros(0), np.zeros(0, dtype=np.uint64), 5).tolist() == []
 
 
+def test_measured_alu_ceiling(B):
+    """The derived ceiling (256 CUs x 128 lanes per clock x 2.4 GHz) bounds what an instruction stream reaches,
+    and the stream comes within a factor of two of it."""
+    nominal = 256 * 128 * 2.4e9
+    got = B.p2_measure_alu_peak(3)
+    assert 0.5 * nominal < got <= 1.02 * nominal, got
+
+
 def test_caller_stream_and_host_threads(B, oracle):
     """The call runs on the caller's HIP stream (after work already queued there), and calls from
     different host threads use their own device scratch."""
