@@ -231,7 +231,8 @@ typedef struct {
     float post_ms;             /* ordering, cost and top-k kernels                                 */
     int32_t eval_launches;     /* evaluation kernels launched                                      */
     int32_t post_launches;
-    float host_plan_ms;        /* host: planning of all queries (patterns, bandwidth rows)         */
+    float host_plan_ms;        /* host: planning of all queries before the first launch (patterns,
+                                  alphabet; the cost model's tables are built while the GPU runs)  */
     float host_total_ms;       /* host: whole call, wall clock                                     */
 } p2_profile;
 int32_t p2_set_profiling(int32_t on);

@@ -61,6 +61,7 @@ struct HostBuf {
         if (p) (void)hipHostFree(p);
         p = nullptr; cap = 0;
         size_t want = std::max(bytes, (size_t)4096);
+        want = (want + 4095) & ~(size_t)4095;
         hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
         if (e == hipSuccess) cap = want;
         return e;
@@ -69,8 +70,13 @@ struct HostBuf {
 
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
+    DevBuf rows, rows_hdr;
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
     DevBuf f_entries[2], f_states[2], f_literal[2], f_surv, f_surv_literal, f_ctr, f_valid;   // frontier engine
+    HostBuf h_rows, h_rows_hdr;
+    hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
+    hipEvent_t copy_done = nullptr;
+    hipEvent_t wait_ev = nullptr;           // see wait_for_stream
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs;
 };
 thread_local Ctx g_ctx;
@@ -98,6 +104,29 @@ int32_t hip_fail(hipError_t e, const char* what) {
     } while (0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Wait until everything queued on `stream` is done.  The waits of a call are short (tens to hundreds of
+// microseconds).  hipStreamSynchronize and hipStreamQuery showed a per-process mode here in which each wait
+// takes 0.15 ms longer (one fresh process in eight, up to six in ten when polling hipStreamQuery); an event
+// recorded behind the work and polled with hipEventQuery did not (0 of 12), at the price of the marker
+// (about 10 us per wait).  The host polls for up to two milliseconds and then blocks on the event.
+hipError_t wait_for_stream(hipStream_t stream) {
+    Ctx& C = g_ctx;
+    hipError_t e = hipSuccess;
+    if (!C.wait_ev) {
+        e = hipEventCreateWithFlags(&C.wait_ev, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    e = hipEventRecord(C.wait_ev, stream);
+    if (e != hipSuccess) return e;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (;;) {
+        e = hipEventQuery(C.wait_ev);
+        if (e == hipSuccess) return hipSuccess;
+        if (e != hipErrorNotReady) return e;
+        if (std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(2)) return hipEventSynchronize(C.wait_ev);
+    }
+}
 
 // Selections over at most this many valid programs go into one launch for the whole batch
 // (one wavefront each); longer lists take the two-stage selection, one query at a time.
@@ -140,8 +169,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     std::string err;
     for (int i = 0; i < n_queries; ++i) {
         const p2_query& Q = queries[i];
+        // (the bandwidth rows of the cost model are built later, while the GPU evaluates)
         int32_t st = make_plan(Q.h, Q.axes, Q.n_axes, Q.placement, Q.reduce_axes, Q.n_reduce, Q.max_len, Q.opt,
-                               n_msg > 0, runs[i].plan, err);
+                               n_msg > 0, runs[i].plan, err, false);
         if (st != P2_OK) return fail(st, "query " + std::to_string(i) + ": " + err);
         runs[i].topk = Q.opt ? Q.opt->topk : 0;
         if (runs[i].topk < 0) return fail(P2_EINVAL, "topk < 0");
@@ -292,14 +322,65 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& A : autos) { A.off = off; off += align_up(sizeof(int32_t) * A.qlist.size(), 256); }
     const size_t off_msg = off;
     off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
-    for (auto& r : runs) {
-        size_t n_rows = 0, n_ent = 0;
-        for (const Pattern& p : r.plan.patterns) { n_rows += p.row_level.size(); n_ent += p.entries.size(); }
-        r.off_rowptr = off; off += align_up(sizeof(int32_t) * (n_rows + 1), 16);
-        r.off_rowlevel = off; off += align_up(sizeof(int32_t) * std::max<size_t>(n_rows, 1), 16);
-        r.off_entries = off; off += align_up(sizeof(uint32_t) * std::max<size_t>(n_ent, 1), 256);
-    }
     const size_t blob_bytes = off;
+    // The bandwidth rows (cost model) live in buffers of their own: the rows, and per query a header (DevRows)
+    // that the query descriptor points at.  They are built on the host after the evaluation kernels have been
+    // queued and uploaded on a second stream, so both overlap with the evaluation; the call's stream waits
+    // for the upload before its first cost kernel.
+    bool rows_ready = false;
+    P2_HIP(C.rows_hdr.ensure(sizeof(DevRows) * (size_t)std::max(n_queries, 1)));
+    P2_HIP(C.h_rows_hdr.ensure(sizeof(DevRows) * (size_t)std::max(n_queries, 1)));
+    if (!C.copy_stream) {
+        P2_HIP(hipStreamCreateWithFlags(&C.copy_stream, hipStreamNonBlocking));
+        P2_HIP(hipEventCreateWithFlags(&C.copy_done, hipEventDisableTiming));
+    }
+    auto build_and_upload_rows = [&]() -> int32_t {
+        if (rows_ready) return P2_OK;
+        size_t bytes = 0;
+        for (auto& r : runs) {
+            if (n_msg > 0) build_cost_tables(r.plan);         // without message sizes the tables stay empty
+            size_t n_rows = 0, n_ent = 0;
+            for (const Pattern& p : r.plan.patterns) { n_rows += p.row_level.size(); n_ent += p.entries.size(); }
+            r.off_rowptr = bytes; bytes += align_up(sizeof(int32_t) * (n_rows + 1), 16);
+            r.off_rowlevel = bytes; bytes += align_up(sizeof(int32_t) * std::max<size_t>(n_rows, 1), 16);
+            r.off_entries = bytes; bytes += align_up(sizeof(uint32_t) * std::max<size_t>(n_ent, 1), 256);
+        }
+        P2_HIP(C.rows.ensure(bytes));
+        P2_HIP(C.h_rows.ensure(bytes));
+        char* hr = static_cast<char*>(C.h_rows.p);
+        char* dr = static_cast<char*>(C.rows.p);
+        DevRows* hdr = static_cast<DevRows*>(C.h_rows_hdr.p);
+        for (int i = 0; i < n_queries; ++i) {
+            const QueryRun& r = runs[i];
+            const Plan& pl = r.plan;
+            int32_t* rp = reinterpret_cast<int32_t*>(hr + r.off_rowptr);
+            int32_t* rl = reinterpret_cast<int32_t*>(hr + r.off_rowlevel);
+            uint32_t* en = reinterpret_cast<uint32_t*>(hr + r.off_entries);
+            DevRows& H = hdr[i];
+            std::memset(&H, 0, sizeof H);
+            int row = 0, ent = 0;
+            rp[0] = 0;
+            for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
+                const Pattern& p = pl.patterns[pi];
+                H.pat_begin[pi] = row;
+                for (size_t t = 0; t < p.row_level.size(); ++t) {
+                    for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
+                    rl[row] = p.row_level[t];
+                    rp[++row] = ent;
+                }
+            }
+            for (size_t pi = pl.patterns.size(); pi <= (size_t)kMaxPatterns; ++pi) H.pat_begin[pi] = row;
+            H.row_ptr = reinterpret_cast<const int32_t*>(dr + r.off_rowptr);
+            H.row_level = reinterpret_cast<const int32_t*>(dr + r.off_rowlevel);
+            H.entries = reinterpret_cast<const uint32_t*>(dr + r.off_entries);
+        }
+        rows_ready = true;
+        P2_HIP(hipMemcpyAsync(C.rows.p, C.h_rows.p, bytes, hipMemcpyHostToDevice, C.copy_stream));
+        P2_HIP(hipMemcpyAsync(C.rows_hdr.p, C.h_rows_hdr.p, sizeof(DevRows) * (size_t)n_queries, hipMemcpyHostToDevice, C.copy_stream));
+        P2_HIP(hipEventRecord(C.copy_done, C.copy_stream));
+        P2_HIP(hipStreamWaitEvent(stream, C.copy_done, 0));
+        return P2_OK;
+    };
     P2_HIP(C.blob.ensure(blob_bytes));
     P2_HIP(C.h_blob.ensure(blob_bytes));
     P2_HIP(C.counters.ensure(sizeof(DevCounters) * (size_t)n_queries));
@@ -379,24 +460,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (int d = 0; d < pl.alphabet; ++d)
                 dq->instr_of_digit[d] = (uint16_t)(((d / pl.n_ops) << 3) | pl.ops[d % pl.n_ops]);
             for (int j = 0; j < pl.n; ++j) { dq->alpha[j] = pl.alpha[j]; dq->inv_bw[j] = 1.0 / pl.bw[j]; }
-            int32_t* rp = reinterpret_cast<int32_t*>(hb + r.off_rowptr);
-            int32_t* rl = reinterpret_cast<int32_t*>(hb + r.off_rowlevel);
-            uint32_t* en = reinterpret_cast<uint32_t*>(hb + r.off_entries);
-            int row = 0, ent = 0;
-            rp[0] = 0;
             for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
                 const Pattern& p = pl.patterns[pi];
                 DevPattern& dp = dq->pat[pi];
                 dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.lo;
                 dp.reg_shape = reg_shape_of(p.g, p.s, p.master, 5);
-                dp.row_begin = row;
-                for (size_t t = 0; t < p.row_level.size(); ++t) {
-                    for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
-                    rl[row] = p.row_level[t];
-                    rp[++row] = ent;
-                }
-                dp.row_end = row;
+                dp.pad0 = 0; dp.pad1 = 0;
             }
+            dq->rows = static_cast<const DevRows*>(C.rows_hdr.p) + i;
             dq->reg_sum_part = 0;
             for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
                 const Pattern& p = pl.patterns[pi];
@@ -411,9 +482,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 dq->reg_part[pi] = part;
                 dq->reg_sum_part += (uint32_t)(p.n_groups * p.g) * (uint32_t)pl.n_ops;
             }
-            dq->row_ptr = reinterpret_cast<const int32_t*>(db + r.off_rowptr);
-            dq->row_level = reinterpret_cast<const int32_t*>(db + r.off_rowlevel);
-            dq->entries = reinterpret_cast<const uint32_t*>(db + r.off_entries);
             dq->msg_bytes = reinterpret_cast<const double*>(db + off_msg);
             dq->valid_idx = static_cast<unsigned long long*>(C.valid.p) + r.off_valid;
             dq->rerun_idx = static_cast<unsigned long long*>(C.rerun.p) + r.off_rerun;
@@ -461,9 +529,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(launch_eval_literal_groups_auto(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const int32_t*>(db + A.off),
                                                    (int)A.qlist.size(), A.max_R, A.max_k, C.lit_scratch.p, stream));
         }
-        P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
-                              hipMemcpyDeviceToHost, stream));
-        P2_HIP(hipStreamSynchronize(stream));
+        // while the GPU evaluates: the cost model's tables (first attempt only)
+        {
+            const int32_t rc = build_and_upload_rows();
+            if (rc != P2_OK) return rc;
+        }
+        P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
+        P2_HIP(wait_for_stream(stream));
         bool again = false;
         const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
         // candidates whose state the compact engine could not hold go through the literal engine:
@@ -490,9 +562,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                                 L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
         }
         if (reran) {
-            P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries,
-                                  hipMemcpyDeviceToHost, stream));
-            P2_HIP(hipStreamSynchronize(stream));
+            P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
+            P2_HIP(wait_for_stream(stream));
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
@@ -579,15 +650,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, stream));
                 }
-                P2_HIP(hipMemcpyAsync(C.h_fctr.p, dctr, sizeof(FrontCounters), hipMemcpyDeviceToHost, stream));
-                P2_HIP(hipStreamSynchronize(stream));
+                P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
+                P2_HIP(wait_for_stream(stream));
                 if (hctr->n_surv <= cap_c && hctr->n_surv_literal <= cap_l) break;
                 // the repeated classification counts its steps again: take them back
                 cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, hctr->n_surv_literal);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
                 P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
-                P2_HIP(hipStreamSynchronize(stream));
+                P2_HIP(wait_for_stream(stream));
             }
             const uint32_t n_surv = hctr->n_surv, n_surv_l = hctr->n_surv_literal;
             const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_plit = hctr->n_prefix_literal;
@@ -616,8 +687,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             cur = nxt;
         }
         // steps of the last materialisation
-        P2_HIP(hipMemcpyAsync(C.h_fctr.p, dctr, sizeof(FrontCounters), hipMemcpyDeviceToHost, stream));
-        P2_HIP(hipStreamSynchronize(stream));
+        P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
+        P2_HIP(wait_for_stream(stream));
         r.steps = hctr->steps; r.members = hctr->members;
         fvalid_used += r.n_valid;
     }
@@ -737,13 +808,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
     P2_HIP(C.h_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
     if (total_valid > 0) {
-        P2_HIP(hipMemcpyAsync(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid, hipMemcpyDeviceToHost, stream));
+        P2_HIP(launch_copy_out(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid, stream));
         if (n_msg > 0)
-            P2_HIP(hipMemcpyAsync(C.h_costs.p, C.costs.p, sizeof(double) * total_valid * nm, hipMemcpyDeviceToHost, stream));
+            P2_HIP(launch_copy_out(C.h_costs.p, C.costs.p, sizeof(double) * total_valid * nm, stream));
     }
     if (topk_rows > 0)
-        P2_HIP(hipMemcpyAsync(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, hipMemcpyDeviceToHost, stream));
-    P2_HIP(hipStreamSynchronize(stream));
+        P2_HIP(launch_copy_out(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    P2_HIP(wait_for_stream(stream));
 
     if (g_prof.on) {
         P2_HIP(hipEventElapsedTime(&g_prof.last.eval_ms, g_prof.ev[0], g_prof.ev[1]));
@@ -973,8 +1044,8 @@ int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* 
     DevCounters* dc = static_cast<DevCounters*>(C.counters.p);
     P2_HIP(launch_topk(cost, cost_stride, reinterpret_cast<const unsigned long long*>(index), n, k,
                        reinterpret_cast<long long*>(out_pos), C.topk_scratch.p, &dc->nan_seen, stream));
-    P2_HIP(hipMemcpyAsync(C.h_counters.p, C.counters.p, sizeof(DevCounters), hipMemcpyDeviceToHost, stream));
-    P2_HIP(hipStreamSynchronize(stream));
+    P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters), stream));
+    P2_HIP(wait_for_stream(stream));
     if (static_cast<const DevCounters*>(C.h_counters.p)->nan_seen) return fail(P2_EINVAL, "NaN cost");
     return P2_OK;
 }

@@ -457,14 +457,16 @@ __device__ inline int step_mixed(uint32_t* my, int dstride, const PatLds P, int 
         // ring alpha-beta time of the step: the first slot of a group now holds the chunk set that
         // sets its bytes (common rows / rows after the gather / the root's rows)
         double best = 0.0;
-        for (int row = dp->row_begin; row < dp->row_end; ++row) {
+        const DevRows& rw = *q.rows;
+        const int pid = (int)(dp - q.pat);
+        for (int row = rw.pat_begin[pid]; row < rw.pat_begin[pid + 1]; ++row) {
             long long dot = 0;
-            for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
-                const uint32_t ent = q.entries[e];
+            for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                const uint32_t ent = rw.entries[e];
                 const Slot<KW, MW> sl = load_slot<KW, MW>(my, dstride, (int)entry_base(ent));
                 dot += (long long)entry_cnt(ent) * (long long)popcount(sl.r);
             }
-            best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+            best = fmax(best, (double)dot * q.inv_bw[rw.row_level[row]]);
         }
         double ring_steps, mult;
         step_factors(op, P.g, q.algo, ring_steps, mult);

@@ -20,7 +20,7 @@ enum : int { OP_AR = 0, OP_RS = 1, OP_AG = 2, OP_RD = 3, OP_BC = 4 };
 struct DevPattern {
     int32_t g, s, master, n_groups;
     int32_t span_level;            // outermost hardware level at which members differ
-    int32_t row_begin, row_end;    // bandwidth rows of this pattern (indices into row_ptr/row_level)
+    int32_t pad0, pad1;
     int32_t reg_shape;             // shape number of the register engine (p2_regs.hip), -1 if it has none
 };
 
@@ -107,6 +107,17 @@ __host__ __device__ inline void step_factors(int op, int g, int algo, double& st
     }
 }
 
+// Bandwidth rows of one query (cost model): CSR of packed (local group, first device, multiplicity)
+// entries; pattern p owns the rows [pat_begin[p], pat_begin[p + 1]).  Uploaded apart from the query
+// descriptors (the host builds the rows while the evaluation kernels run); only the cost kernels read it.
+struct DevRows {
+    const int32_t* row_ptr;
+    const int32_t* row_level;      // hardware level of the row's unit
+    const uint32_t* entries;       // entry_pack(local group, its first device, groups touching the unit)
+    int32_t pat_begin[kMaxPatterns + 1];
+    int32_t pad;
+};
+
 struct DevQuery {
     int32_t R, k;                  // devices of one reduction group, chunks
     int32_t MW, KW;                // 32-bit words per contribution mask / per chunk set
@@ -125,10 +136,7 @@ struct DevQuery {
     unsigned long long reg_part[kMaxPatterns];
     uint32_t reg_sum_part;
     double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
-    // bandwidth rows (device pointers into the uploaded table blob)
-    const int32_t* row_ptr;
-    const int32_t* row_level;
-    const uint32_t* entries;       // entry_pack(local group, its first device, groups touching the unit)
+    const DevRows* rows;           // bandwidth rows (valid by the time a cost kernel runs)
     const double* msg_bytes;       // [n_msg]
     // outputs of the evaluation kernels
     unsigned long long* valid_idx;
@@ -253,6 +261,11 @@ struct DevTopkJob {
 };
 // Block b of the launch does jobs[b] alone: meant for many selections of a few thousand entries each.
 hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream);
+
+// Results to the host: a kernel copies `bytes` (rounded up to 16; both buffers must hold that) from device
+// memory to pinned, device-accessible host memory.  Used instead of hipMemcpyAsync, whose queueing of a
+// device-to-host copy was seen to take 0.1 ms longer in some processes (never in others).
+hipError_t launch_copy_out(void* dst_host, const void* src_dev, size_t bytes, hipStream_t stream);
 
 // Top-k of (cost[i * stride], index[i]) over i < n: positions into out_pos[min(k, n)].
 // scratch: device buffer of topk_scratch_bytes(n, k) bytes.  nan_flag: device uint32 set to 1 on NaN.

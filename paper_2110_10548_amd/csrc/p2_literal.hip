@@ -168,13 +168,15 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
     if (kCost) {
         // bandwidth term: the most loaded uplink; gcount holds the rows that set a group's bytes
         double best = 0.0;
-        for (int row = P.row_begin + lane; row < P.row_end; row += kWave) {
+        const DevRows& rw = *q.rows;
+        const int pid = (int)(&P - q.pat);
+        for (int row = rw.pat_begin[pid] + lane; row < rw.pat_begin[pid + 1]; row += kWave) {
             long long dot = 0;
-            for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
-                const uint32_t ent = q.entries[e];
+            for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                const uint32_t ent = rw.entries[e];
                 dot += (long long)entry_cnt(ent) * (long long)L.gcount[entry_group(ent)];
             }
-            best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+            best = fmax(best, (double)dot * q.inv_bw[rw.row_level[row]]);
         }
         best = wave_max(best);
         double ring_steps, mult;

@@ -204,7 +204,7 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
 
 int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
                   const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len, const p2_options* opt, bool with_cost,
-                  Plan& pl, std::string& err) {
+                  Plan& pl, std::string& err, bool build_rows) {
     int64_t devices = 0;
     int32_t st = check_hierarchy(h, with_cost, devices, err);
     if (st != P2_OK) return st;
@@ -337,9 +337,13 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
         pl.base[l + 1] = total;
     }
     pl.n_candidates = total;
-    if (with_cost)
+    if (with_cost && build_rows)
         for (Pattern& p : pl.patterns) build_cost_rows(pl, p);
     return P2_OK;
+}
+
+void build_cost_tables(Plan& pl) {
+    for (Pattern& p : pl.patterns) build_cost_rows(pl, p);
 }
 
 void describe_pattern(const Plan& pl, int pattern_id, int32_t* group_of_device, int32_t* rank_in_group) {

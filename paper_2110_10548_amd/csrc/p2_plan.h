@@ -52,12 +52,15 @@ struct Plan {
     std::vector<int32_t> replica_of;       // [D] which copy the device belongs to
 };
 
-// Returns P2_OK or an error code; `err` gets the reason.  with_cost: build the bandwidth rows.
+// Returns P2_OK or an error code; `err` gets the reason.  with_cost: the links must be given, and the
+// bandwidth rows are built (unless build_rows is false: build_cost_tables does that later).
 int32_t enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, int32_t* out, int64_t cap,
                              int64_t* out_count, std::string& err);
 int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
                   const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len, const p2_options* opt, bool with_cost,
-                  Plan& plan, std::string& err);
+                  Plan& plan, std::string& err, bool build_rows = true);
+// The bandwidth rows of every pattern of a plan made without them (make_plan with with_cost = false).
+void build_cost_tables(Plan& plan);
 // Group id / rank of every device of the full system for one canonical pattern.
 void describe_pattern(const Plan& plan, int pattern_id, int32_t* group_of_device, int32_t* rank_in_group);
 

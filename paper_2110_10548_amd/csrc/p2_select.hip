@@ -176,6 +176,11 @@ __global__ __launch_bounds__(kWave) void k_topk_jobs(const DevTopkJob* __restric
     for (int j = lane; j < n_out; j += kWave) J.out_pos[j] = j < cnt ? L.pos[j] : -1ll;
 }
 
+// Device memory -> pinned host memory, written by the GPU itself in 16-byte words.
+__global__ __launch_bounds__(256) void k_copy_out(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 inline unsigned topk_blocks(long long n) {
     long long b = (n + 64 * 16 - 1) / (64 * 16);      // at least 16 tiles per block
     if (b < 1) b = 1;
@@ -184,6 +189,16 @@ inline unsigned topk_blocks(long long n) {
 }
 
 }  // namespace
+
+hipError_t launch_copy_out(void* dst_host, const void* src_dev, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = (bytes + 15) / 16;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL(k_copy_out, dim3(blocks), dim3(256), 0, stream, static_cast<uint4*>(dst_host),
+                       static_cast<const uint4*>(src_dev), n16);
+    return hipGetLastError();
+}
 
 hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long long* valid2, unsigned long long* sorted,
                             const DevPostSeg* segs, int n_segs, unsigned blocks, hipStream_t stream) {

@@ -395,14 +395,15 @@ __global__ __launch_bounds__(kWave) void k_cost_shared(const DevQuery* __restric
                     __syncthreads();
                     // bandwidth term: the most loaded uplink
                     const DevPattern& P = q.pat[pid];
+                    const DevRows& rw = *q.rows;
                     double best = 0.0;
-                    for (int row = P.row_begin + lane; row < P.row_end; row += kWave) {
+                    for (int row = rw.pat_begin[pid] + lane; row < rw.pat_begin[pid + 1]; row += kWave) {
                         long long dot = 0;
-                        for (int e = q.row_ptr[row]; e < q.row_ptr[row + 1]; ++e) {
-                            const uint32_t ent = q.entries[e];
+                        for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                            const uint32_t ent = rw.entries[e];
                             dot += (long long)entry_cnt(ent) * (long long)srows[entry_base(ent)];
                         }
-                        best = fmax(best, (double)dot * q.inv_bw[q.row_level[row]]);
+                        best = fmax(best, (double)dot * q.inv_bw[rw.row_level[row]]);
                     }
                     for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWave));
                     double ring_steps, mult;
