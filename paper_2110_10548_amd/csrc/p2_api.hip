@@ -76,7 +76,6 @@ struct Ctx {
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
     hipEvent_t copy_done = nullptr;
-    hipEvent_t wait_ev = nullptr;           // see wait_for_stream
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs;
 };
 thread_local Ctx g_ctx;
@@ -104,29 +103,6 @@ int32_t hip_fail(hipError_t e, const char* what) {
     } while (0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-// Wait until everything queued on `stream` is done.  The waits of a call are short (tens to hundreds of
-// microseconds).  hipStreamSynchronize and hipStreamQuery showed a per-process mode here in which each wait
-// takes 0.15 ms longer (one fresh process in eight, up to six in ten when polling hipStreamQuery); an event
-// recorded behind the work and polled with hipEventQuery did not (0 of 12), at the price of the marker
-// (about 10 us per wait).  The host polls for up to two milliseconds and then blocks on the event.
-hipError_t wait_for_stream(hipStream_t stream) {
-    Ctx& C = g_ctx;
-    hipError_t e = hipSuccess;
-    if (!C.wait_ev) {
-        e = hipEventCreateWithFlags(&C.wait_ev, hipEventDisableTiming);
-        if (e != hipSuccess) return e;
-    }
-    e = hipEventRecord(C.wait_ev, stream);
-    if (e != hipSuccess) return e;
-    const auto t0 = std::chrono::steady_clock::now();
-    for (;;) {
-        e = hipEventQuery(C.wait_ev);
-        if (e == hipSuccess) return hipSuccess;
-        if (e != hipErrorNotReady) return e;
-        if (std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(2)) return hipEventSynchronize(C.wait_ev);
-    }
-}
 
 // Selections over at most this many valid programs go into one launch for the whole batch
 // (one wavefront each); longer lists take the two-stage selection, one query at a time.
@@ -535,7 +511,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             if (rc != P2_OK) return rc;
         }
         P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
-        P2_HIP(wait_for_stream(stream));
+        P2_HIP(hipStreamSynchronize(stream));
         bool again = false;
         const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
         // candidates whose state the compact engine could not hold go through the literal engine:
@@ -563,7 +539,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         if (reran) {
             P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
-            P2_HIP(wait_for_stream(stream));
+            P2_HIP(hipStreamSynchronize(stream));
         }
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
@@ -651,14 +627,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, stream));
                 }
                 P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
-                P2_HIP(wait_for_stream(stream));
+                P2_HIP(hipStreamSynchronize(stream));
                 if (hctr->n_surv <= cap_c && hctr->n_surv_literal <= cap_l) break;
                 // the repeated classification counts its steps again: take them back
                 cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, hctr->n_surv_literal);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
                 P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
-                P2_HIP(wait_for_stream(stream));
+                P2_HIP(hipStreamSynchronize(stream));
             }
             const uint32_t n_surv = hctr->n_surv, n_surv_l = hctr->n_surv_literal;
             const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_plit = hctr->n_prefix_literal;
@@ -688,7 +664,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         // steps of the last materialisation
         P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
-        P2_HIP(wait_for_stream(stream));
+        P2_HIP(hipStreamSynchronize(stream));
         r.steps = hctr->steps; r.members = hctr->members;
         fvalid_used += r.n_valid;
     }
@@ -814,7 +790,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     }
     if (topk_rows > 0)
         P2_HIP(launch_copy_out(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
-    P2_HIP(wait_for_stream(stream));
+    P2_HIP(hipStreamSynchronize(stream));
 
     if (g_prof.on) {
         P2_HIP(hipEventElapsedTime(&g_prof.last.eval_ms, g_prof.ev[0], g_prof.ev[1]));
@@ -1045,7 +1021,7 @@ int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* 
     P2_HIP(launch_topk(cost, cost_stride, reinterpret_cast<const unsigned long long*>(index), n, k,
                        reinterpret_cast<long long*>(out_pos), C.topk_scratch.p, &dc->nan_seen, stream));
     P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters), stream));
-    P2_HIP(wait_for_stream(stream));
+    P2_HIP(hipStreamSynchronize(stream));
     if (static_cast<const DevCounters*>(C.h_counters.p)->nan_seen) return fail(P2_EINVAL, "NaN cost");
     return P2_OK;
 }
