@@ -693,10 +693,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
-        add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid, r.out_first);
+        const size_t list_at = r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid;
         if (r.wave_cost) {
-            add_seg(scost_launches, word_class(r.plan.k) * 100 + word_class(r.plan.R), r.plan, i, r.n_valid, 1, 0,
-                    r.out_first);                                                  // one wavefront per program
+            // one wavefront per program; it also finds the program's place in the ascending order
+            add_seg(scost_launches, word_class(r.plan.k) * 100 + word_class(r.plan.R), r.plan, i, r.n_valid, 1, list_at,
+                    r.out_first);
+        } else {
+            add_seg(sort_launches, 0, r.plan, i, r.n_valid, 256, list_at, r.out_first);
+        }
+        if (r.wave_cost) {
         } else if (r.engine == P2_ENGINE_COMPACT) {
             const int cls = word_class(r.plan.k) * 100 + word_class(r.plan.R);
             add_seg(ccost_launches, cls, r.plan, i, r.n_valid, 1, 0, r.out_first);     // per_block set below
@@ -729,7 +734,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& L : scost_launches) {
         ++post_launches;
         P2_HIP(launch_cost_shared(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
-                                  L.max_k, sorted_base, progs_base, costs_base, stream));
+                                  L.max_k, static_cast<unsigned long long*>(C.valid.p), static_cast<unsigned long long*>(C.f_valid.p),
+                                  sorted_base, progs_base, costs_base, stream));
     }
     for (auto& L : lcost_launches) {
         ++post_launches;

@@ -171,10 +171,12 @@ hipError_t launch_eval_regs(const DevQuery* queries, const DevSegment* segs, int
 // Shared-prefix engine: `grid` blocks, divided among the queries by the share table.
 hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, int n_segs, const DevShare* shares,
                               int n_shares, unsigned grid, int max_R, int max_k, hipStream_t stream);
-// Program records and costs of the sorted valid candidates of shared-prefix-capable queries, one block per entry.
+// Ordering, program records and costs of the valid candidates of shared-prefix-capable queries, one block per
+// entry of the unordered lists (in_off of a segment: where its list starts in valid, or, with bit 63 set, in
+// valid2): the block finds its entry's rank and writes sorted, progs and costs at out_off + rank.
 hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks, int max_R,
-                              int max_k, const unsigned long long* sorted, p2_program* progs, double* costs,
-                              hipStream_t stream);
+                              int max_k, const unsigned long long* valid, const unsigned long long* valid2,
+                              unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream);
 // Best rate, in lane-operations per second, of a stream of independent 32-bit vector ALU instructions.
 hipError_t measure_alu_peak(int reps, double* lane_ops_per_s, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).

@@ -346,7 +346,9 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
 template <int KW, int MW>
 __global__ __launch_bounds__(kWave) void k_cost_shared(const DevQuery* __restrict__ queries,
                                                        const DevPostSeg* __restrict__ segs, int n_segs,
-                                                       const unsigned long long* __restrict__ sorted,
+                                                       const unsigned long long* __restrict__ valid,
+                                                       const unsigned long long* __restrict__ valid2,
+                                                       unsigned long long* __restrict__ sorted,
                                                        p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
     __shared__ uint32_t srows[kWave];                // chunks that set the bytes of the group whose first device is d
     const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
@@ -354,8 +356,16 @@ __global__ __launch_bounds__(kWave) void k_cost_shared(const DevQuery* __restric
     const int lane = threadIdx.x;
     const int devs = q.R > 32 ? 64 : 32;
     const int dev = lane & (devs - 1);
-    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
-    const unsigned long long idx = sorted[i];
+    // The block's program is entry j of the query's unordered list of valid indices; its place in the
+    // ascending order is the number of smaller entries (distinct keys), counted here by the wavefront, so
+    // no separate sort runs for these queries.  A list whose in_off has bit 63 set is in valid2.
+    const unsigned long long* in = (seg.in_off >> 63) ? valid2 + (seg.in_off & ~(1ull << 63)) : valid + seg.in_off;
+    const unsigned long long idx = in[blockIdx.x - seg.first_block];
+    uint32_t rank = 0;
+    for (uint32_t t = (uint32_t)lane; t < seg.count; t += kWave) rank += in[t] < idx ? 1u : 0u;
+    for (int off = 32; off > 0; off >>= 1) rank += __shfl_xor(rank, off, kWave);
+    const size_t i = seg.out_off + rank;
+    if (lane == 0) sorted[i] = idx;
     int len = 1;
     while (len < q.max_len && idx >= q.base[len + 1]) ++len;
     uint32_t digit[P2_MAX_LEN];
@@ -453,12 +463,12 @@ hipError_t launch_eval_shared(const DevQuery* queries, const DevSegment* segs, i
 }
 
 hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks, int max_R,
-                              int max_k, const unsigned long long* sorted, p2_program* progs, double* costs,
-                              hipStream_t stream) {
+                              int max_k, const unsigned long long* valid, const unsigned long long* valid2,
+                              unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream) {
     if (n_segs == 0 || blocks == 0) return hipSuccess;
     const int KW = word_class_s(max_k), MW = word_class_s(max_R);
 #define P2_GO(KWV, MWV) \
-    hipLaunchKernelGGL((k_cost_shared<KWV, MWV>), dim3(blocks), dim3(kWave), 0, stream, queries, segs, n_segs, sorted, progs, costs);
+    hipLaunchKernelGGL((k_cost_shared<KWV, MWV>), dim3(blocks), dim3(kWave), 0, stream, queries, segs, n_segs, valid, valid2, sorted, progs, costs);
     P2_SHARED_DISPATCH(KW, MW, P2_GO)
 #undef P2_GO
     return hipGetLastError();
