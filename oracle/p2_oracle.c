@@ -20,6 +20,14 @@
  *
  * Only tests, the smoke check and the benchmark's CPU-baseline leg may call
  * into this file.
+ *
+ * What pins it (tests/test_oracle_pins.py): the paper's placement lists and
+ * program totals, its worked examples of the five collectives, its tables of
+ * device groups and synthesis hierarchies, its named programs, its lemmas and
+ * its expressiveness theorem.  Parity unpinned by any value the paper prints,
+ * and held only by closed forms, invariants and hand-worked cases: the
+ * semantics of the Master form, the program sets of three and more levels,
+ * and every cost (ring and tree models are stated readings).
  */
 #include <stdint.h>
 #include <stdlib.h>
