@@ -235,7 +235,11 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 ++c_ran;
                 c_visited += shape >> 16;
                 ++evaluated; evaluated_members += shape >> 16;
-                c_rc = wave_step<KW, MW>(c_rv, c_mv, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
+                const int op0 = (int)(ins0 & 7u);
+                // on the init state (every device holds every chunk, device i column i) an AllGather finds the
+                // chunks held twice and a Broadcast no member inside its root: no need to go through the stages
+                if (t == 0 && (op0 == OP_AG || op0 == OP_BC)) c_rc = WSTEP_INVALID;
+                else c_rc = wave_step<KW, MW>(c_rv, c_mv, dev, op0, (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
             }
         }
         if (c_rc == WSTEP_INVALID) {
