@@ -125,6 +125,35 @@ __device__ __forceinline__ int wave_step(Words<KW>& rv, Words<MW>& mv, int dev, 
     return (~flags & roots) != 0ull ? WSTEP_INVALID : WSTEP_OK;
 }
 
+// The first instruction of a program, on the init state of Sec. 3.5 (every device holds every chunk,
+// device i column i): what the rules give there is known without an exchange.  Members of a group hold
+// the same chunks and disjoint columns, so the AllReduce-like rules apply (ReduceScatter if the group
+// size divides k) and every member ends with the columns of its group, the devices that agree with it
+// outside bits [ls, ls + lg); AllGather and Broadcast never apply.  rv, mv hold the init state on entry.
+template <int KW, int MW>
+__device__ __forceinline__ int first_wave_step(Words<KW>& rv, Words<MW>& mv, int dev, int op, int lg, int ls,
+                                               unsigned long long part, int k) {
+    if (op == OP_AG || op == OP_BC) return WSTEP_INVALID;
+    const int gm1 = (1 << lg) - 1;
+    if (op == OP_RS && (k & gm1) != 0) return WSTEP_INVALID;
+    const bool in = ((part >> dev) & 1ull) != 0ull;
+    if (!in) return WSTEP_OK;                         // (wave-uniform result; this lane's device keeps its state)
+    const uint32_t gmask = (uint32_t)gm1 << ls;
+    unsigned long long cols = 1ull << ((uint32_t)dev & ~gmask);
+    for (int J = ls; J < ls + lg; ++J) cols |= cols << (1u << J);
+    mv.w[0] = (uint32_t)cols;
+    if (MW > 1) mv.w[MW > 1 ? 1 : 0] = (uint32_t)(cols >> 32);
+    if (op == OP_RS) {
+        const int per = k >> lg, p = (dev >> ls) & gm1;
+        const Words<KW> upto = lowest_n(rv, (p + 1) * per), below = lowest_n(rv, p * per);
+#pragma unroll
+        for (int i = 0; i < KW; ++i) rv.w[i] = upto.w[i] & ~below.w[i];
+    } else if (op == OP_RD && ((uint32_t)dev & gmask) != 0u) {
+        clear(rv); clear(mv);
+    }
+    return WSTEP_OK;
+}
+
 // A work item is seg.iters consecutive groups of one stem (a length-1 segment is a single item).
 // Every query has a share of the grid's blocks in proportion to its items; block j of n walks the
 // query's items j, j + n, ..., so the items of a valid stem, which are the expensive ones, go to
@@ -236,9 +265,7 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 c_visited += shape >> 16;
                 ++evaluated; evaluated_members += shape >> 16;
                 const int op0 = (int)(ins0 & 7u);
-                // on the init state (every device holds every chunk, device i column i) an AllGather finds the
-                // chunks held twice and a Broadcast no member inside its root: no need to go through the stages
-                if (t == 0 && (op0 == OP_AG || op0 == OP_BC)) c_rc = WSTEP_INVALID;
+                if (t == 0) c_rc = first_wave_step<KW, MW>(c_rv, c_mv, dev, op0, (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], q.k);
                 else c_rc = wave_step<KW, MW>(c_rv, c_mv, dev, op0, (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
             }
         }
