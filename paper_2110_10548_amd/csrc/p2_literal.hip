@@ -227,6 +227,39 @@ __device__ inline void lit_init(const DevQuery& q, const LitLds& L, int lane) {
     __syncthreads();
 }
 
+// The state after a program's first instruction, written directly (reduction groups of at most 64
+// devices whose patterns have power-of-two group sizes and strides: the queries of the shared-prefix
+// engine).  On the init state the AllReduce-like rules always apply (ReduceScatter if the group size divides
+// k): every member ends with the columns of its group, the devices that agree with it outside bits
+// [ls, ls + lg) of the device number, on all rows (AllReduce), on its block of rows (ReduceScatter), or on
+// all rows of the root only (Reduce); AllGather and Broadcast never apply.  Returns false where the
+// instruction is invalid (the state is then not written).
+template <int MW>
+__device__ inline bool lit_init_first(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, int lane) {
+    static_assert(MW <= 2, "groups of at most 64 devices");
+    if (op == OP_AG || op == OP_BC) return false;
+    if (op == OP_RS && q.k % P.g != 0) return false;
+    const int per = q.k / P.g;
+    const uint32_t gmask = (uint32_t)(P.g - 1) * (uint32_t)P.s;          // g and s are powers of two
+    const int cells = q.R * q.k;
+    for (int c = lane; c < cells; c += kWave) {
+        const int d = c / q.k, r = c - d * q.k;
+        const bool in = !P.master || (d % P.s) == 0;
+        unsigned long long cols = 1ull << d;
+        if (in) {
+            cols = 1ull << ((uint32_t)d & ~gmask);
+            for (uint32_t b = (uint32_t)P.s; b < (uint32_t)(P.g * P.s); b <<= 1) cols |= cols << b;
+            const int p = (int)(((uint32_t)d & gmask) / (uint32_t)P.s);
+            if (op == OP_RS && (r < p * per || r >= (p + 1) * per)) cols = 0ull;
+            if (op == OP_RD && p != 0) cols = 0ull;
+        }
+        L.S[c * MW] = (uint32_t)cols;
+        if (MW > 1) L.S[c * MW + (MW > 1 ? 1 : 0)] = (uint32_t)(cols >> 32);
+    }
+    __syncthreads();
+    return true;
+}
+
 template <int MW>
 __device__ inline bool lit_is_goal(const DevQuery& q, const LitLds& L, int lane) {
     // every device holds, in every row, the columns of its whole reduction group
@@ -634,10 +667,19 @@ __device__ inline void literal_group(const DevQuery& q, unsigned long long idx0,
     uint16_t digit[P2_MAX_LEN + 1];
     const int len = unrank(q, idx0, digit);
     const unsigned long long I = (unsigned long long)q.alphabet;
-    lit_init<MW>(q, L, lane);
     bool ok = true;
     unsigned long long ran = 0, visited = 0;
-    for (int t = 0; t < len - 1 && ok; ++t) {
+    int t0 = 0;
+    if (len - 1 >= 1) {                              // the first instruction: its result is known without a pass
+        const int pid = digit[0] / q.n_ops, op = q.ops[digit[0] - pid * q.n_ops];
+        ran = 1;
+        visited = (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        ok = lit_init_first<MW>(q, q.pat[pid], op, L, lane);
+        t0 = 1;
+    } else {
+        lit_init<MW>(q, L, lane);
+    }
+    for (int t = t0; t < len - 1 && ok; ++t) {
         const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
         ++ran;
         visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
@@ -673,10 +715,19 @@ __device__ inline void literal_stem(const DevQuery& q, unsigned long long idx0, 
     uint16_t digit[P2_MAX_LEN + 1];
     const int len = unrank(q, idx0, digit);         // len >= 3: digit[len-2] is the first group's instruction
     const unsigned long long I = (unsigned long long)q.alphabet;
-    lit_init<MW>(q, L, lane);
     bool ok = true;
     unsigned long long ran = 0, visited = 0;
-    for (int t = 0; t < len - 2 && ok; ++t) {
+    int t0 = 0;
+    if (len - 2 >= 1) {                              // the first instruction: its result is known without a pass
+        const int pid = digit[0] / q.n_ops, op = q.ops[digit[0] - pid * q.n_ops];
+        ran = 1;
+        visited = (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        ok = lit_init_first<MW>(q, q.pat[pid], op, L, lane);
+        t0 = 1;
+    } else {
+        lit_init<MW>(q, L, lane);
+    }
+    for (int t = t0; t < len - 2 && ok; ++t) {
         const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
         ++ran;
         visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
@@ -1032,12 +1083,10 @@ hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_eval_literal_groups_auto<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, qlist, n_q, \
                            static_cast<uint32_t*>(gscratch), gwords, state_in_lds);
-    switch (mask_words(max_R)) {
+    switch (mask_words(max_R)) {              // reduction groups of at most 64 devices
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
-    case 4: P2_LAUNCH(4) break;
-    case 8: P2_LAUNCH(8) break;
-    default: P2_LAUNCH(16) break;
+    default: return hipErrorInvalidValue;
     }
 #undef P2_LAUNCH
     if (e != hipSuccess) return e;
