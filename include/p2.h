@@ -88,6 +88,25 @@ int32_t p2_enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int3
                                  instruction where that can reach the goal; P2_EUNSUPPORTED where
                                  it does not apply                                                */
 
+/* Synthesis hierarchies (Sec. 3.4, Appendix A).  The tool synthesizes on (d); the others are there so
+ * that the section's claim (each hierarchy of the list expresses every program of the one before)
+ * can be checked on this evaluator.  A level of the hierarchy owns factors x[i][j] of the matrix:
+ *   COLLAPSED  (d)  per hardware level j the product of the reduction axes' factors
+ *   SYSTEM     (a)  per hardware level j all its factors (every axis): the system's own levels
+ *   COLUMN     (b)  one level per factor, x00 x10 .. x01 x11 .. (hardware level by hardware level)
+ *   ROW        (c)  one level per factor, x00 x01 .. x10 x11 .. (axis by axis)
+ *   REDUCTION       one level per factor of the reduction axes only, axis by axis ((d) before the
+ *                   factors of one hardware level are multiplied)
+ * Under COLLAPSED and REDUCTION a program runs on one reduction group and is repeated over the
+ * other axes; under the other three it runs on the whole system (group_size in the stats is then
+ * the number of devices, and the goal is per device).  Everything but COLLAPSED is evaluated by the
+ * literal engine (engine AUTO or LITERAL; another engine => P2_EUNSUPPORTED). */
+#define P2_HIERARCHY_COLLAPSED 0
+#define P2_HIERARCHY_SYSTEM 1
+#define P2_HIERARCHY_COLUMN 2
+#define P2_HIERARCHY_ROW 3
+#define P2_HIERARCHY_REDUCTION 4
+
 typedef struct {
     int32_t n_chunks;    /* k of Sec. 3.2; 0 => number of devices (the paper's choice)           */
     uint32_t form_mask;  /* bit 0 InsideGroup, bit 1 Parallel, bit 2 Master; 0 => all            */
@@ -99,6 +118,7 @@ typedef struct {
                             Anything else => P2_EUNSUPPORTED                                     */
     int32_t topk;        /* 0 => return every valid program; else see p2_synthesize              */
     int32_t engine;      /* P2_ENGINE_*                                                          */
+    int32_t hierarchy;   /* P2_HIERARCHY_*; 0 => (d), the tool's own                             */
     void* hip_stream;    /* hipStream_t to run on; NULL => the default stream                    */
 } p2_options;
 

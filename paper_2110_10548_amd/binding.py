@@ -31,7 +31,7 @@ class p2_hierarchy(C.Structure):
 
 class p2_options(C.Structure):
     _fields_ = [("n_chunks", C.c_int32), ("form_mask", C.c_uint32), ("op_mask", C.c_uint32), ("algo", C.c_int32),
-                ("topk", C.c_int32), ("engine", C.c_int32), ("hip_stream", C.c_void_p)]
+                ("topk", C.c_int32), ("engine", C.c_int32), ("hierarchy", C.c_int32), ("hip_stream", C.c_void_p)]
 
 
 class p2_program(C.Structure):
@@ -142,8 +142,11 @@ class _Hier:
                               _p(self.alpha, C.c_double) if self.alpha is not None else None)
 
 
-def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None):
-    return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, stream)
+HIERARCHY = {"collapsed": 0, "system": 1, "column": 2, "row": 3, "reduction": 4}
+
+
+def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None, hierarchy=0):
+    return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, HIERARCHY.get(hierarchy, hierarchy), stream)
 
 
 def p2_enumerate_placements(card, axes):
@@ -156,9 +159,9 @@ def p2_enumerate_placements(card, axes):
     return out[:n.value]
 
 
-def p2_describe_pattern(card, axes, placement, reduce_axes, pattern_id, form_mask=7, op_mask=31):
+def p2_describe_pattern(card, axes, placement, reduce_axes, pattern_id, form_mask=7, op_mask=31, hierarchy=0):
     h, axes, placement, red = _Hier(card), _i32(axes), _i32(placement), _i32(reduce_axes)
-    opt = _options(form_mask=form_mask, op_mask=op_mask)
+    opt = _options(form_mask=form_mask, op_mask=op_mask, hierarchy=hierarchy)
     D = int(np.prod(h.card))
     s, f, fl, npat = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
     g = np.zeros(D, dtype=np.int32)
@@ -169,9 +172,9 @@ def p2_describe_pattern(card, axes, placement, reduce_axes, pattern_id, form_mas
     return {"slice": s.value, "form": f.value, "form_level": fl.value, "group_of": g, "rank": r, "n_patterns": npat.value}
 
 
-def p2_num_patterns(card, axes, placement, reduce_axes, form_mask=7):
+def p2_num_patterns(card, axes, placement, reduce_axes, form_mask=7, hierarchy=0):
     h, axes, placement, red = _Hier(card), _i32(axes), _i32(placement), _i32(reduce_axes)
-    opt = _options(form_mask=form_mask)
+    opt = _options(form_mask=form_mask, hierarchy=hierarchy)
     npat = C.c_int32()
     _check(lib().p2_describe_pattern(C.byref(h.c), _p(axes, C.c_int32), len(axes), _p(placement, C.c_int32),
                                      _p(red, C.c_int32), len(red), C.byref(opt), -1, None, None, None, None, None,
@@ -195,7 +198,7 @@ class Batch:
             h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
             axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
             opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), q.get("algo", 0), q.get("topk", 0),
-                           q.get("engine", ENGINE_AUTO), stream)
+                           q.get("engine", ENGINE_AUTO), stream, q.get("hierarchy", 0))
             self._keep.append((h, axes, pl, red, opt))
             self._arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32),
                                     len(red), int(q["max_len"]), C.pointer(opt))
@@ -238,7 +241,7 @@ class Batch:
 
 def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
     """queries: list of dicts with card, bw, alpha, axes, placement, reduce_axes, max_len and optional
-    n_chunks, form_mask, op_mask, topk, engine.  Returns a list of results, one per query:
+    n_chunks, form_mask, op_mask, algo, topk, engine, hierarchy.  Returns a list of results, one per query:
     {"programs": structured array, "cost": [n][n_msg], "stats": dict}."""
     b = Batch(queries, msg_bytes, stream)
     if cap is not None:
@@ -251,10 +254,11 @@ def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
 
 
 def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=None, alpha=None, n_chunks=0,
-                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None, algo=0):
-    """Valid programs of one placement with their simulated costs (through the single-query entry point)."""
+                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None, algo=0, hierarchy=0):
+    """Valid programs of one placement with their simulated costs (through the single-query entry point).
+    hierarchy: a P2_HIERARCHY_* number or one of "collapsed", "system", "column", "row", "reduction"."""
     h, axes_a, pl, red = _Hier(card, bw, alpha), _i32(axes), _i32(placement), _i32(reduce_axes)
-    opt = _options(n_chunks, form_mask, op_mask, algo, topk, engine, stream)
+    opt = _options(n_chunks, form_mask, op_mask, algo, topk, engine, stream, hierarchy)
     msg = _f64(list(msg_bytes))
     n_msg = len(msg)
     count, cands, st = C.c_int64(), C.c_uint64(), p2_stats()
@@ -275,13 +279,13 @@ def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=
 
 
 def p2_search_placements(card, axes, reduce_sets, max_len, msg_bytes, bw=None, alpha=None, weights=None, n_chunks=0,
-                         form_mask=7, op_mask=31, algo=0, engine=ENGINE_AUTO, stream=None):
+                         form_mask=7, op_mask=31, algo=0, engine=ENGINE_AUTO, stream=None, hierarchy=0):
     """Every placement x every requested reduction in one batch: best program, AllReduce baseline, ranking."""
     h, axes_a = _Hier(card, bw, alpha), _i32(axes)
     flat = _i32([a for red in reduce_sets for a in red])
     lens = _i32([len(red) for red in reduce_sets])
     w = _f64(list(weights)) if weights is not None else None
-    opt = _options(n_chunks, form_mask, op_mask, algo, 0, engine, stream)
+    opt = _options(n_chunks, form_mask, op_mask, algo, 0, engine, stream, hierarchy)
     count = C.c_int64()
 
     def call(pl_p, rows_p, tot_p, ord_p, cap):

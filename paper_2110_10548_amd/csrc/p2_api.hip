@@ -119,6 +119,7 @@ struct QueryRun {
     size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
+    size_t off_goal = 0, off_rank = 0;    // hierarchies other than the collapsed one: goal masks, ranks of members
     uint32_t valid_cap = 0, rerun_cap = 0;
     size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
     uint32_t n_valid = 0, n_rerun = 0, n_rerun_groups = 0;
@@ -157,7 +158,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         const Plan& pl = runs[i].plan;
         const bool lit_ok = true;        // the literal engine falls back to a global state buffer
         const bool cmp_ok = compact_lanes(pl.R, pl.k) != 0;
-        if (want == P2_ENGINE_LITERAL) {
+        if (pl.hierarchy != P2_HIERARCHY_COLLAPSED) {
+            // ranks inside a group and per-device goals are known to the literal engine only
+            if (want != P2_ENGINE_LITERAL && want != P2_ENGINE_AUTO)
+                return fail(P2_EUNSUPPORTED, "query " + std::to_string(i) + ": this synthesis hierarchy runs on the literal engine only");
+            if (pl.n_candidates > (1ull << 30))
+                return fail(P2_EUNSUPPORTED, "query " + std::to_string(i) + ": more than 2^30 candidates under this synthesis hierarchy");
+            runs[i].engine = P2_ENGINE_LITERAL;
+        } else if (want == P2_ENGINE_LITERAL) {
             if (!lit_ok) return fail(P2_EUNSUPPORTED, "state too large for the literal engine");
             runs[i].engine = P2_ENGINE_LITERAL;
         } else if (want == P2_ENGINE_FRONTIER || (want == P2_ENGINE_AUTO && pl.n_candidates > (1ull << 30))) {
@@ -296,6 +304,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         r.auto_groups = true;
     }
     for (auto& A : autos) { A.off = off; off += align_up(sizeof(int32_t) * A.qlist.size(), 256); }
+    for (auto& r : runs) {
+        if (r.plan.hierarchy == P2_HIERARCHY_COLLAPSED) continue;
+        r.off_goal = off;
+        off += align_up(sizeof(uint32_t) * r.plan.goal.size(), 256);
+        r.off_rank = off;
+        size_t n_rank = 0;
+        for (const Pattern& p : r.plan.patterns) n_rank += p.rank.size();
+        off += align_up(sizeof(int32_t) * n_rank, 256);
+    }
     const size_t off_msg = off;
     off += align_up(sizeof(double) * (size_t)std::max(n_msg, 1), 256);
     const size_t blob_bytes = off;
@@ -439,9 +456,26 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
                 const Pattern& p = pl.patterns[pi];
                 DevPattern& dp = dq->pat[pi];
-                dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.lo;
+                dp.g = p.g; dp.s = p.s; dp.master = p.master; dp.n_groups = p.n_groups; dp.span_level = p.span;
                 dp.reg_shape = reg_shape_of(p.g, p.s, p.master, 5);
-                dp.pad0 = 0; dp.pad1 = 0;
+                dp.rank_off = 0; dp.pad1 = 0;
+            }
+            dq->goal_mask = nullptr; dq->rank_tbl = nullptr;
+            if (pl.hierarchy != P2_HIERARCHY_COLLAPSED) {
+                if (!pl.goal.empty()) {
+                    std::memcpy(hb + r.off_goal, pl.goal.data(), sizeof(uint32_t) * pl.goal.size());
+                    dq->goal_mask = reinterpret_cast<const uint32_t*>(db + r.off_goal);
+                }
+                int32_t* ranks = reinterpret_cast<int32_t*>(hb + r.off_rank);
+                int32_t at = 0;
+                for (size_t pi = 0; pi < pl.patterns.size(); ++pi) {
+                    const Pattern& p = pl.patterns[pi];
+                    if (p.rank.empty()) continue;
+                    std::memcpy(ranks + at, p.rank.data(), sizeof(int32_t) * p.rank.size());
+                    dq->pat[pi].rank_off = at + 1;
+                    at += (int32_t)p.rank.size();
+                }
+                dq->rank_tbl = reinterpret_cast<const int32_t*>(db + r.off_rank);
             }
             dq->rows = static_cast<const DevRows*>(C.rows_hdr.p) + i;
             dq->reg_sum_part = 0;
@@ -945,6 +979,7 @@ int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t
         main_opt.topk = 1;
         p2_options base_opt = main_opt;
         base_opt.form_mask = 1; base_opt.op_mask = 1; base_opt.topk = 0; base_opt.engine = P2_ENGINE_AUTO;
+        base_opt.hierarchy = P2_HIERARCHY_COLLAPSED;      // the baseline is one AllReduce per reduction group
         const int n_q = (int)(n_pl * n_sets * 2);
         std::vector<p2_query> qs((size_t)n_q);
         for (int64_t p = 0; p < n_pl; ++p)

@@ -20,7 +20,9 @@ enum : int { OP_AR = 0, OP_RS = 1, OP_AG = 2, OP_RD = 3, OP_BC = 4 };
 struct DevPattern {
     int32_t g, s, master, n_groups;
     int32_t span_level;            // outermost hardware level at which members differ
-    int32_t pad0, pad1;
+    int32_t rank_off;              // 0: the member with the t-th local id has rank t; else its rank is
+                                   // DevQuery::rank_tbl[rank_off - 1 + t] (literal engine only)
+    int32_t pad1;
     int32_t reg_shape;             // shape number of the register engine (p2_regs.hip), -1 if it has none
 };
 
@@ -138,6 +140,9 @@ struct DevQuery {
     double alpha[P2_MAX_LEVELS], inv_bw[P2_MAX_LEVELS];
     const DevRows* rows;           // bandwidth rows (valid by the time a cost kernel runs)
     const double* msg_bytes;       // [n_msg]
+    // synthesis hierarchies other than the collapsed one (literal engine only)
+    const uint32_t* goal_mask;     // [R][MW] goal of each device; nullptr: every device of the group
+    const int32_t* rank_tbl;       // ranks of the patterns with rank_off != 0
     // outputs of the evaluation kernels
     unsigned long long* valid_idx;
     unsigned long long* rerun_idx;

@@ -184,7 +184,8 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
         if (lane < q.n_msg) *cost_lane += ring_steps * q.alpha[P.span_level] + q.msg_bytes[lane] * (mult / (double)k) * best;
     }
 
-    // write the members' new rows
+    // write the members' new rows (block p of a ReduceScatter goes to the member of rank p)
+    const int32_t* rank = P.rank_off ? q.rank_tbl + (P.rank_off - 1) : nullptr;
     for (int it = lane; it < items; it += kWave) {
         const int G = it / k, r = it - G * k;
         const int base = P.master ? G * gs : (G / s) * gs + (G % s);
@@ -206,7 +207,7 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
         }
         for (int p = (op == OP_BC ? 1 : 0); p < g; ++p) {
             uint32_t* x = L.S + ((base + p * s) * k + r) * MW;
-            const bool keep = owner == -2 || owner == p;
+            const bool keep = owner == -2 || owner == (rank ? rank[p] : p);
 #pragma unroll
             for (int w = 0; w < MW; ++w) x[w] = keep ? t[w] : 0u;
         }
@@ -266,10 +267,11 @@ __device__ inline bool lit_is_goal(const DevQuery& q, const LitLds& L, int lane)
     const int cells = q.R * q.k;
     bool ok = true;
     for (int c = lane; c < cells; c += kWave) {
+        const uint32_t* goal = q.goal_mask ? q.goal_mask + (size_t)(c / q.k) * MW : nullptr;
 #pragma unroll
         for (int w = 0; w < MW; ++w) {
             const int bits = q.R - 32 * w;
-            const uint32_t full = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+            const uint32_t full = goal ? goal[w] : bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
             ok &= L.S[c * MW + w] == full;
         }
     }

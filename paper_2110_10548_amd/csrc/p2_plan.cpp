@@ -109,8 +109,8 @@ int32_t enumerate_placements(const p2_hierarchy* h, const int32_t* axes, int32_t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Bandwidth rows of one pattern.  A group whose members first differ at hardware level `lo`
-// crosses the uplink of every level-j unit (j >= lo) that holds one of its members; the load of
+// Bandwidth rows of one pattern.  A group whose members first differ at hardware level `span`
+// crosses the uplink of every level-j unit (j >= span) that holds one of its members; the load of
 // a unit is the sum of the bytes of those groups (they all belong to this pattern).  Groups of
 // different copies with the same local group id carry the same bytes, so a unit is described by
 // how many groups of each local id touch it.  Units with equal descriptions are merged, and a
@@ -142,7 +142,7 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
     int below = pl.D;
     for (int j = 0; j < pl.n; ++j) {
         below /= pl.h[j];
-        if (j < p.lo) continue;
+        if (j < p.span) continue;
         // rows of this level, one after the other in `flat`; row r is flat[row_begin[r] .. row_begin[r + 1])
         flat.clear();
         row_begin.assign(1, 0);
@@ -202,6 +202,107 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
 
 }  // namespace
 
+
+// ---------------------------------------------------------------------------------------------
+// Sec. 3.4: the hierarchies other than (d).  A level is a list of factors (axis i, hardware level
+// j) of the matrix; the local id of a device is the mixed-radix number of its digits a_{i,j} taken
+// level by level (first level and, inside a level, first factor most significant); the digits of
+// the factors that belong to no level number the copy.  Devices: id = mixed radix of hardware
+// coordinates, the coordinate at level j = mixed radix of the a_{i,j}, axis 0 most significant.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+int32_t number_by_levels(Plan& pl, std::vector<int>& lf, std::vector<int>& lspan, std::string& err) {
+    struct Cell { int i, j; };
+    std::vector<std::vector<Cell>> levels;
+    const int m = pl.m, n = pl.n;
+    switch (pl.hierarchy) {
+    case P2_HIERARCHY_SYSTEM:
+        for (int j = 0; j < n; ++j) { levels.emplace_back(); for (int i = 0; i < m; ++i) levels.back().push_back({i, j}); }
+        break;
+    case P2_HIERARCHY_COLUMN:
+        for (int j = 0; j < n; ++j) for (int i = 0; i < m; ++i) levels.push_back({{i, j}});
+        break;
+    case P2_HIERARCHY_ROW:
+        for (int i = 0; i < m; ++i) for (int j = 0; j < n; ++j) levels.push_back({{i, j}});
+        break;
+    default:   // P2_HIERARCHY_REDUCTION
+        for (int i = 0; i < m; ++i) if (pl.is_reduce[i]) for (int j = 0; j < n; ++j) levels.push_back({{i, j}});
+        break;
+    }
+    int owner[P2_MAX_AXES][P2_MAX_LEVELS];
+    for (int i = 0; i < m; ++i) for (int j = 0; j < n; ++j) owner[i][j] = -1;
+    pl.R = 1;
+    bool over_other_axes = false;
+    for (size_t l = 0; l < levels.size(); ++l) {
+        int f = 1, span = n;
+        for (const Cell& c : levels[l]) {
+            owner[c.i][c.j] = (int)l;
+            f *= pl.x[c.i][c.j];
+            if (pl.x[c.i][c.j] > 1) { span = std::min(span, c.j); over_other_axes = over_other_axes || !pl.is_reduce[c.i]; }
+        }
+        lf.push_back(f); lspan.push_back(span);
+        pl.R *= f;
+    }
+    pl.level_f = lf;
+    (void)err;
+
+    pl.local_of.resize(pl.D);
+    pl.replica_of.resize(pl.D);
+    std::vector<int> other(pl.D);                              // number made of the non-reduction digits
+    for (int d = 0; d < pl.D; ++d) {
+        int a[P2_MAX_AXES][P2_MAX_LEVELS], rest = d;
+        for (int j = n - 1; j >= 0; --j) {
+            int c = rest % pl.h[j];
+            rest /= pl.h[j];
+            for (int i = m - 1; i >= 0; --i) { a[i][j] = c % pl.x[i][j]; c /= pl.x[i][j]; }
+        }
+        int local = 0, rep = 0, oth = 0;
+        for (const auto& lv : levels)
+            for (const Cell& c : lv) local = local * pl.x[c.i][c.j] + a[c.i][c.j];
+        for (int j = 0; j < n; ++j)
+            for (int i = 0; i < m; ++i) {
+                if (owner[i][j] < 0) rep = rep * pl.x[i][j] + a[i][j];
+                if (!pl.is_reduce[i]) oth = oth * pl.x[i][j] + a[i][j];
+            }
+        pl.local_of[d] = local; pl.replica_of[d] = rep; other[d] = oth;
+    }
+    // Sec. 3.2, goal: every device holds the sum over its reduction group.  With levels over other axes
+    // the copy holds several reduction groups (the devices with equal digits on the other axes).
+    if (over_other_axes) {
+        const int mw = (pl.R + 31) / 32;
+        pl.goal.assign((size_t)pl.R * mw, 0u);
+        for (int d = 0; d < pl.D; ++d) {
+            if (pl.replica_of[d] != 0) continue;
+            for (int e = 0; e < pl.D; ++e)
+                if (pl.replica_of[e] == 0 && other[e] == other[d])
+                    pl.goal[(size_t)pl.local_of[d] * mw + (pl.local_of[e] >> 5)] |= 1u << (pl.local_of[e] & 31);
+        }
+    }
+    return P2_OK;
+}
+
+// Ranks inside a group (ascending device id) of the members taken in ascending local id; the same for
+// every group of a pattern, because the order of two members depends on the varied digits only.
+void member_ranks(Plan& pl) {
+    std::vector<int> dev_of(pl.R, 0);                          // device of copy 0 with a given local id
+    for (int d = 0; d < pl.D; ++d)
+        if (pl.replica_of[d] == 0) dev_of[pl.local_of[d]] = d;
+    for (Pattern& p : pl.patterns) {
+        p.rank.assign(p.g, 0);
+        bool identity = true;
+        for (int t = 0; t < p.g; ++t) {
+            int r = 0;
+            for (int u = 0; u < p.g; ++u) r += dev_of[u * p.s] < dev_of[t * p.s];
+            p.rank[t] = r;
+            identity = identity && r == t;
+        }
+        if (identity) p.rank.clear();
+    }
+}
+
+}  // namespace
+
 int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* placement,
                   const int32_t* reduce_axes, int32_t n_reduce, int32_t max_len, const p2_options* opt, bool with_cost,
                   Plan& pl, std::string& err, bool build_rows) {
@@ -216,10 +317,12 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     if (max_len < 1) { err = "max_len < 1"; return P2_EINVAL; }
     if (max_len > P2_MAX_LEN) { err = "max_len > 7"; return P2_EUNSUPPORTED; }
     if (opt && opt->algo != 0 && opt->algo != 1) { err = "unknown cost model (algo is 0 = ring or 1 = tree)"; return P2_EUNSUPPORTED; }
+    if (opt && (opt->hierarchy < 0 || opt->hierarchy > P2_HIERARCHY_REDUCTION)) { err = "unknown synthesis hierarchy"; return P2_EUNSUPPORTED; }
 
     pl = Plan();
     pl.n = h->n_levels; pl.m = n_axes; pl.D = (int)devices; pl.max_len = max_len;
     pl.algo = opt ? opt->algo : 0;
+    pl.hierarchy = opt ? opt->hierarchy : P2_HIERARCHY_COLLAPSED;
     for (int j = 0; j < pl.n; ++j) {
         pl.h[j] = h->card[j];
         pl.bw[j] = h->bw_bytes_per_s ? h->bw_bytes_per_s[j] : 1.0;
@@ -263,52 +366,61 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     if (k > 512) { err = "more than 512 chunks"; return P2_EUNSUPPORTED; }
     pl.k = k;
 
-    // Sec. 3.4, hierarchy (d): per hardware level the product of the reduce axes' factors.
-    pl.R = 1;
-    for (int j = 0; j < pl.n; ++j) {
-        pl.f[j] = 1;
-        for (int i = 0; i < n_axes; ++i)
-            if (pl.is_reduce[i]) pl.f[j] *= pl.x[i][j];
-        pl.R *= pl.f[j];
-    }
-    // Devices: id = mixed radix of hardware coordinates; inside a level the coordinate is a mixed
-    // radix of the axis digits, axis 0 most significant.  Split every coordinate into its
-    // reduce-axis part (-> local id) and the rest (-> replica).
-    pl.local_of.resize(pl.D);
-    pl.replica_of.resize(pl.D);
-    for (int d = 0; d < pl.D; ++d) {
-        int coord[P2_MAX_LEVELS], rest = d;
-        for (int j = pl.n - 1; j >= 0; --j) { coord[j] = rest % pl.h[j]; rest /= pl.h[j]; }
-        int local = 0, rep = 0;
+    std::vector<int> lf;                                        // factor of every synthesis level
+    std::vector<int> lspan;                                     // outermost hardware level of its factors > 1
+    if (pl.hierarchy == P2_HIERARCHY_COLLAPSED) {
+        // Sec. 3.4, hierarchy (d): per hardware level the product of the reduce axes' factors.
+        pl.R = 1;
         for (int j = 0; j < pl.n; ++j) {
-            int c = coord[j], gdig = 0, rdig = 0, gmul = 1, rmul = 1;
-            for (int i = n_axes - 1; i >= 0; --i) {          // least significant axis first
-                int a = c % pl.x[i][j];
-                c /= pl.x[i][j];
-                if (pl.is_reduce[i]) { gdig += a * gmul; gmul *= pl.x[i][j]; }
-                else { rdig += a * rmul; rmul *= pl.x[i][j]; }
-            }
-            local = local * pl.f[j] + gdig;
-            rep = rep * (pl.h[j] / pl.f[j]) + rdig;
+            pl.f[j] = 1;
+            for (int i = 0; i < n_axes; ++i)
+                if (pl.is_reduce[i]) pl.f[j] *= pl.x[i][j];
+            pl.R *= pl.f[j];
         }
-        pl.local_of[d] = local;
-        pl.replica_of[d] = rep;
+        // Devices: id = mixed radix of hardware coordinates; inside a level the coordinate is a mixed
+        // radix of the axis digits, axis 0 most significant.  Split every coordinate into its
+        // reduce-axis part (-> local id) and the rest (-> replica).
+        pl.local_of.resize(pl.D);
+        pl.replica_of.resize(pl.D);
+        for (int d = 0; d < pl.D; ++d) {
+            int coord[P2_MAX_LEVELS], rest = d;
+            for (int j = pl.n - 1; j >= 0; --j) { coord[j] = rest % pl.h[j]; rest /= pl.h[j]; }
+            int local = 0, rep = 0;
+            for (int j = 0; j < pl.n; ++j) {
+                int c = coord[j], gdig = 0, rdig = 0, gmul = 1, rmul = 1;
+                for (int i = n_axes - 1; i >= 0; --i) {          // least significant axis first
+                    int a = c % pl.x[i][j];
+                    c /= pl.x[i][j];
+                    if (pl.is_reduce[i]) { gdig += a * gmul; gmul *= pl.x[i][j]; }
+                    else { rdig += a * rmul; rmul *= pl.x[i][j]; }
+                }
+                local = local * pl.f[j] + gdig;
+                rep = rep * (pl.h[j] / pl.f[j]) + rdig;
+            }
+            pl.local_of[d] = local;
+            pl.replica_of[d] = rep;
+        }
+        for (int j = 0; j < pl.n; ++j) { lf.push_back(pl.f[j]); lspan.push_back(j); }
+    } else {
+        st = number_by_levels(pl, lf, lspan, err);
+        if (st != P2_OK) return st;
     }
+    const int sl = (int)lf.size();
 
     // Sec. 3.3 patterns in the order: for every slice e_i (e_0 = root): InsideGroup,
     // Parallel(e_0..e_{i-1}), Master(e_0..e_{i-1}).  Level e_l (l >= 1) is hardware level l-1.
     // A pattern is identified by the levels with factor > 1 that vary inside a group plus whether
     // the Master restriction removes anything; equal identities give equal group sets, and the
     // first occurrence keeps the id.
-    std::vector<int> suffix(pl.n + 1, 1);                       // suffix[j] = prod f[j..n-1]
-    for (int j = pl.n - 1; j >= 0; --j) suffix[j] = suffix[j + 1] * pl.f[j];
-    auto add = [&](int slice, int form, int form_level, int a, int b) {   // hardware levels a..b vary
-        int lo = -1, hi = -1;
+    std::vector<int> suffix(sl + 1, 1);                         // suffix[j] = prod lf[j..sl-1]
+    for (int j = sl - 1; j >= 0; --j) suffix[j] = suffix[j + 1] * lf[j];
+    auto add = [&](int slice, int form, int form_level, int a, int b) {   // synthesis levels a..b vary
+        int lo = -1, hi = -1, span = pl.n;
         for (int j = a; j <= b; ++j)
-            if (pl.f[j] > 1) { if (lo < 0) lo = j; hi = j; }
+            if (lf[j] > 1) { if (lo < 0) lo = j; hi = j; span = std::min(span, lspan[j]); }
         if (lo < 0) return;                                     // only groups of one device
         Pattern p;
-        p.slice = slice; p.form = form; p.form_level = form_level; p.lo = lo; p.hi = hi;
+        p.slice = slice; p.form = form; p.form_level = form_level; p.lo = lo; p.hi = hi; p.span = span;
         p.s = suffix[hi + 1];
         p.g = suffix[lo] / p.s;
         p.master = (form == 2 && p.s > 1) ? 1 : 0;
@@ -317,13 +429,14 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
             if (q.lo == p.lo && q.hi == p.hi && q.master == p.master) return;
         pl.patterns.push_back(p);
     };
-    for (int i = 0; i <= pl.n; ++i) {
-        if (pl.form_mask & 1u) add(i, 0, -1, i, pl.n - 1);
+    for (int i = 0; i <= sl; ++i) {
+        if (pl.form_mask & 1u) add(i, 0, -1, i, sl - 1);
         if (pl.form_mask & 2u)
             for (int j = 0; j < i; ++j) add(i, 1, j, j, i - 1);
         if (pl.form_mask & 4u)
             for (int j = 0; j < i; ++j) add(i, 2, j, j, i - 1);
     }
+    if (pl.hierarchy != P2_HIERARCHY_COLLAPSED) member_ranks(pl);
     pl.alphabet = (int)pl.patterns.size() * pl.n_ops;
 
     // Candidate numbering: by length, then lexicographic.
@@ -356,7 +469,8 @@ void describe_pattern(const Plan& pl, int pattern_id, int32_t* group_of_device, 
         auto it = ids.find(key);
         if (it == ids.end()) it = ids.emplace(key, (int)ids.size()).first;
         group_of_device[d] = it->second;
-        rank_in_group[d] = (loc / p.s) % p.g;
+        const int t = (loc / p.s) % p.g;
+        rank_in_group[d] = p.rank.empty() ? t : p.rank[t];
     }
 }
 

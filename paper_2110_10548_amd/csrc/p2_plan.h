@@ -10,6 +10,15 @@
 // (g, s, master): its groups are the arithmetic progressions {base + t*s : t < g}, and with
 // `master` only those whose base has zero digits below the varied levels take part.
 // Only the cost needs the full system: how many groups share the uplink of a hardware unit.
+//
+// The other synthesis hierarchies of Sec. 3.4 (the system's own levels, the column-based and the
+// row-based factors, the reduction axes' factors before they are collapsed) fit the same tables: a
+// level owns some factors x[i][j] of the matrix, the local id is the mixed-radix number of a device's
+// digits level by level, and the factors that belong to no level number the copies.  Two things are
+// then no longer implied: the members of a group in ascending local id need not be in ascending
+// device id (a ReduceScatter hands block p to the member of *rank* p, so a pattern carries its
+// ranks), and where a hierarchy has levels over non-reduction axes a copy is the whole system and a
+// device's goal is the set of local ids of its own reduction group.
 #pragma once
 #include <cstdint>
 #include <string>
@@ -21,10 +30,13 @@ namespace p2 {
 
 struct Pattern {
     int slice, form, form_level;   // first (slice, form) pair that produced this group set
-    int lo, hi;                    // varied hardware levels lo..hi (both with factor > 1)
+    int lo, hi;                    // varied synthesis levels lo..hi (both with factor > 1); for
+                                   // hierarchy (d) these are the hardware levels
+    int span;                      // outermost hardware level at which members of a group differ
     int g, s;                      // group size, stride of local ids inside a group
     int master;                    // 1: only groups with (local id % s) == 0 take part
     int n_groups;                  // participating groups inside one reduction group
+    std::vector<int32_t> rank;     // [g] rank by device id of the member with the t-th local id; empty: t
     // sparse rows for the bandwidth term: for hardware unit classes that can carry the
     // maximum load, (local group, number of system groups touching the unit) pairs
     std::vector<int32_t> row_ptr;      // [n_rows + 1]
@@ -40,6 +52,9 @@ struct Plan {
     bool is_reduce[P2_MAX_AXES] = {false};
     int D = 0, R = 0, k = 0;
     int f[P2_MAX_LEVELS] = {0};        // reduction-axis factor of each hardware level (collapsed)
+    int hierarchy = 0;                 // P2_HIERARCHY_*
+    std::vector<int> level_f;          // hierarchy != collapsed: factor of each synthesis level
+    std::vector<uint32_t> goal;        // [R][ceil(R/32)] goal mask of each local id; empty: all of the copy
     uint32_t form_mask = 7, op_mask = 31;
     int algo = 0;                  // cost model of AllReduce: 0 ring, 1 tree
     int n_ops = 0, ops[5] = {0};

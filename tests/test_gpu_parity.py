@@ -21,7 +21,8 @@ def B():
 
 def oracle_result(oracle, q, msg, form_mask=7, op_mask=31):
     oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q.get("bw"), alpha=q.get("alpha"),
-                      n_chunks=q.get("n_chunks", 0), form_mask=form_mask, op_mask=op_mask, algo=q.get("algo", 0))
+                      n_chunks=q.get("n_chunks", 0), form_mask=form_mask, op_mask=op_mask, algo=q.get("algo", 0),
+                      hierarchy=q.get("hierarchy", "collapsed"))
     return oq, oq.synthesize(q["max_len"], msg)
 
 
@@ -245,6 +246,77 @@ def test_placement_search_single_device_reduction_and_sizing(B):
     got = _check_search(B.p2_search_placements(*args, **kw), p2_search.search_placements(*args, **kw))
     assert all(got["rows"][(p, 0)]["best_instr"] == [] and got["rows"][(p, 0)]["best_cost"] == 0.0
                for p in range(len(got["placements"])))
+
+
+KINDS = ["system", "column", "row", "reduction"]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_other_synthesis_hierarchies(B, oracle, kind):
+    """Sec. 3.4, hierarchies (a)-(c) and the reduction rows before collapsing, on the full system: valid lists
+    and costs against the oracle, every placement and reduction of small systems (powers of two and not), ring
+    and tree, in one batch with queries of the tool's own hierarchy."""
+    msg = [2.0 ** 20, 2.0 ** 28]
+    queries = []
+    for card, axes, max_len in (([2, 4], [2, 4], 3), ([1, 2, 2, 4], [4, 4], 3), ([2, 3, 2], [6, 2], 3), ([2, 6], [2, 3, 2], 2)):
+        links = dict(bw=[12.5e9, 50e9, 150e9, 300e9][:len(card)], alpha=[2e-5, 1e-5, 5e-6, 2e-6][:len(card)])
+        reds = [[i] for i in range(len(axes))] + [list(range(len(axes)))]
+        for n, x in enumerate(B.p2_enumerate_placements(card, axes).tolist()):
+            for red in reds:
+                queries.append(dict(card=card, axes=axes, placement=x, reduce_axes=red, max_len=max_len, hierarchy=kind,
+                                    algo=n % 2, **links))
+                if n % 4 == 0:
+                    queries.append(dict(queries[-1], hierarchy="collapsed"))
+    results = B.p2_synthesize_batch(queries, msg)
+    n_valid = 0
+    for q, res in zip(queries, results):
+        oq, ora = oracle_result(oracle, q, msg)
+        assert_same(res, ora, len(msg))
+        assert res["stats"]["n_patterns"] == oq.n_patterns and res["stats"]["engine"] in (1, 2, 5)
+        n_valid += len(ora["index"]) if q["hierarchy"] == kind else 0
+    assert n_valid > 100
+    for engine in (2, 3, 4, 5):
+        with pytest.raises(B.P2Error) as e:
+            B.p2_synthesize_batch([dict(queries[0], engine=engine)], msg)
+        assert e.value.code == B.P2_EUNSUPPORTED
+
+
+def _lowered_programs(B, q, res):
+    """Programs as sequences of (device groups on the full system, collective)."""
+    groups = {}
+    for pid in range(res["stats"]["n_patterns"]):
+        d = B.p2_describe_pattern(q["card"], q["axes"], q["placement"], q["reduce_axes"], pid, hierarchy=q["hierarchy"],
+                                  form_mask=q.get("form_mask", 7))
+        by = {}
+        for dev, g in enumerate(d["group_of"].tolist()):
+            if g >= 0:
+                by.setdefault(g, []).append(dev)
+        groups[pid] = frozenset(tuple(v) for v in by.values())
+    return {tuple((groups[int(v) // 5], int(v) % 5) for v in p["instr"][:p["len"]]) for p in res["programs"]}
+
+
+@pytest.mark.parametrize("matrix,axis", [([[1, 1, 2, 2], [1, 2, 1, 2]], 1), ([[1, 2, 1, 2], [1, 1, 2, 2]], 0)])
+def test_expressive_power_of_the_hierarchies_on_the_gpu(B, oracle, matrix, axis):
+    """Sec. 3.4, Theorem: on the running system, with the reduction row placed so that no digit of another
+    axis follows it in hierarchy (c), every lowered program of (a) is one of (b), of (b) one of (c), of (c) one
+    of (d); all five hierarchies through the library, the program sets equal to the oracle's."""
+    card, axes = [1, 2, 2, 4], [4, 4]
+    kinds = KINDS + ["collapsed"]
+    queries = [dict(card=card, axes=axes, placement=matrix, reduce_axes=[axis], max_len=4, hierarchy=k) for k in kinds]
+    low = {}
+    for q, res in zip(queries, B.p2_synthesize_batch(queries)):
+        _, ora = oracle_result(oracle, q, [])
+        assert_same(res, ora, 0)
+        low[q["hierarchy"]] = _lowered_programs(B, q, res)
+    assert low["reduction"] == low["collapsed"] and len(low["column"]) > 0 and len(low["row"]) > len(low["column"])
+    if axis == len(matrix) - 1:
+        assert low["system"] <= low["column"] <= low["row"] <= low["collapsed"]
+    else:
+        # Master groups of (a)-(c) exist in some copies only; without them the chain holds as it stands
+        def no_master(kind):
+            q = dict(queries[kinds.index(kind)], form_mask=3)
+            return _lowered_programs(B, q, B.p2_synthesize_batch([q])[0])
+        assert no_master("system") <= no_master("column") <= no_master("row") <= no_master("collapsed")
 
 
 @pytest.mark.parametrize("form_mask,op_mask", [(3, 31), (5, 31), (7, 0b01101), (7, 0b11001), (4, 31)])

@@ -55,6 +55,25 @@ def test_patterns_match_oracle(B, oracle, card, axes):
                         assert (d["group_of"] == o["group_of"]).all() and (d["rank"] == o["rank"]).all()
 
 
+@pytest.mark.parametrize("kind", ["system", "column", "row", "reduction"])
+@pytest.mark.parametrize("card,axes", [([2, 4], [2, 4]), ([4, 2, 4], [4, 8]), ([3, 2, 4], [6, 4]), ([2, 3, 2], [6, 2]),
+                                       ([2, 2, 2, 2], [4, 4]), ([2, 6], [2, 3, 2])])
+def test_patterns_of_the_other_hierarchies_match_oracle(B, oracle, card, axes, kind):
+    """Sec. 3.4, hierarchies (a)-(c) and the uncollapsed reduction rows: same patterns in the same order, same
+    groups on the full system, same ranks (the library numbers devices by synthesis level internally)."""
+    for r in range(1, len(axes) + 1):
+        for red in itertools.combinations(range(len(axes)), r):
+            for fm in (7, 5):
+                for x in oracle.enumerate_placements(card, axes):
+                    q = oracle.Query(card, axes, x, list(red), form_mask=fm, hierarchy=kind)
+                    assert B.p2_num_patterns(card, axes, x, list(red), form_mask=fm, hierarchy=kind) == q.n_patterns
+                    for pid in range(q.n_patterns):
+                        d = B.p2_describe_pattern(card, axes, x, list(red), pid, form_mask=fm, hierarchy=kind)
+                        o = q.pattern(pid)
+                        assert (d["slice"], d["form"], d["form_level"]) == (o["slice"], o["form"], o["form_level"])
+                        assert (d["group_of"] == o["group_of"]).all() and (d["rank"] == o["rank"]).all()
+
+
 def test_canonical_alphabet_is_L_squared(B):
     # L levels with factor > 1 give L*L distinct group sets
     for f in ([8], [2, 4], [2, 1, 4], [2, 2, 2], [2, 2, 2, 2], [2, 1, 2, 1, 2]):
@@ -79,6 +98,10 @@ def test_argument_errors(B):
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 8) == B.P2_EUNSUPPORTED      # max_len > 7
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [], 3) == B.P2_EINVAL             # empty reduce set
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, [1e6]) == B.P2_EINVAL     # costs without links
+    assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, hierarchy=5) == B.P2_EUNSUPPORTED   # no such hierarchy
+    for engine in (2, 3, 4, 5):       # the other hierarchies of Sec. 3.4 run on the literal engine only
+        assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, hierarchy="row", engine=engine) == B.P2_EUNSUPPORTED
+    assert code(B.p2_synthesize, [2, 4, 4], [2, 4, 4], [[2, 1, 1], [1, 4, 1], [1, 1, 4]], [0], 7, hierarchy="row") == B.P2_EUNSUPPORTED   # > 2^30
     # the placement search checks its arguments and counts the placements before any device work
     assert code(B.p2_search_placements, [2, 4], [3, 3], [[0]], 3, 1e6) == B.P2_EINVAL                # products differ
     assert code(B.p2_search_placements, [2, 4], [2, 4], [], 3, 1e6) == B.P2_EINVAL                   # no reduction
