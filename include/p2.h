@@ -212,8 +212,9 @@ typedef struct {
  * out_rows[p * n_sets + s] describes placement p under reduction s; out_total[p] =
  * sum_s weights[s] * best_cost (weights NULL => all 1: a mapping is chosen with all of a model's
  * reductions in view, Sec. 4.1); out_order lists the placements by ascending (total, p).
- * opt->topk is ignored.  *out_count = number of placements; with cap = 0 only that is written;
- * cap < *out_count => P2_ENOSPC. */
+ * opt->topk is ignored; opt->hierarchy must be P2_HIERARCHY_COLLAPSED (else P2_EUNSUPPORTED).
+ * *out_count = number of placements; with cap = 0 only that is written; cap < *out_count =>
+ * P2_ENOSPC. */
 int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, const int32_t* reduce_sets,
                              const int32_t* reduce_set_len, int32_t n_sets, const double* weights, int32_t max_len,
                              double msg_bytes, const p2_options* opt, int32_t* out_placements /* [cap][n_axes][n_levels] */,

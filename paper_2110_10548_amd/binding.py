@@ -279,13 +279,13 @@ def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=
 
 
 def p2_search_placements(card, axes, reduce_sets, max_len, msg_bytes, bw=None, alpha=None, weights=None, n_chunks=0,
-                         form_mask=7, op_mask=31, algo=0, engine=ENGINE_AUTO, stream=None, hierarchy=0):
+                         form_mask=7, op_mask=31, algo=0, engine=ENGINE_AUTO, stream=None):
     """Every placement x every requested reduction in one batch: best program, AllReduce baseline, ranking."""
     h, axes_a = _Hier(card, bw, alpha), _i32(axes)
     flat = _i32([a for red in reduce_sets for a in red])
     lens = _i32([len(red) for red in reduce_sets])
     w = _f64(list(weights)) if weights is not None else None
-    opt = _options(n_chunks, form_mask, op_mask, algo, 0, engine, stream, hierarchy)
+    opt = _options(n_chunks, form_mask, op_mask, algo, 0, engine, stream)
     count = C.c_int64()
 
     def call(pl_p, rows_p, tot_p, ord_p, cap):

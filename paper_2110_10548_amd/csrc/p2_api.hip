@@ -950,6 +950,8 @@ int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t
         if (cap < 0 || (cap > 0 && (!out_placements || !out_rows || !out_total || !out_order)))
             return fail(P2_EINVAL, "bad output buffer");
         if (!(msg_bytes >= 0.0)) return fail(P2_EINVAL, "msg_bytes is negative or NaN");
+        if (opt && opt->hierarchy != P2_HIERARCHY_COLLAPSED)
+            return fail(P2_EUNSUPPORTED, "the placement search synthesizes on the collapsed hierarchy");
         std::vector<const int32_t*> set_ptr((size_t)n_sets);
         {
             const int32_t* at = reduce_sets;
@@ -979,7 +981,6 @@ int32_t p2_search_placements(const p2_hierarchy* h, const int32_t* axes, int32_t
         main_opt.topk = 1;
         p2_options base_opt = main_opt;
         base_opt.form_mask = 1; base_opt.op_mask = 1; base_opt.topk = 0; base_opt.engine = P2_ENGINE_AUTO;
-        base_opt.hierarchy = P2_HIERARCHY_COLLAPSED;      // the baseline is one AllReduce per reduction group
         const int n_q = (int)(n_pl * n_sets * 2);
         std::vector<p2_query> qs((size_t)n_q);
         for (int64_t p = 0; p < n_pl; ++p)
