@@ -776,6 +776,576 @@ __device__ inline void literal_stem(const DevQuery& q, unsigned long long idx0, 
     }
 }
 
+// ---- the literal state by classes of equal rows ----------------------------------------------------
+// Rows that are equal on every device stay equal under AllReduce, Reduce, AllGather and Broadcast (the
+// rules act row by row), and a ReduceScatter splits a class only where a block boundary of some group
+// falls between two of its rows.  So the handed-over groups are evaluated on one row per class: the
+// state is [R][C] masks plus the class of every row and the class sizes, a step costs C instead of k
+// rows, and it fits in LDS whatever k is.  C is at most 64 here; a ReduceScatter that would need more
+// classes reports an overflow and the caller evaluates that entry on the full literal state instead.
+struct ClsLds {
+    uint32_t* S;        // [R][cm][MW]  mask of class c on device d
+    uint32_t* T;        // [ng][cm][MW] combined rows of each group
+    uint32_t* csize;    // [cm]  rows in the class
+    uint32_t* ncsize;   // [cm]  (ReduceScatter) sizes of the new classes
+    uint32_t* crow;     // [cm]  (ReduceScatter) first row of a new class
+    uint32_t* gcount;   // [ng]  non-empty rows of the group's result
+    uint32_t* gflag;    // [ng]  Broadcast: some member differs from the root
+    uint32_t* gne;      // [ng][2] which classes of the group's result are non-empty
+    uint32_t* devne;    // [64]  AllGather: device holds something
+    uint32_t* flags;    // [4]
+    uint32_t* start;    // [16]  (ReduceScatter) bit r: row r is the first of a new class
+    uint16_t* cls;      // [k]   class of a row
+    uint16_t* ncls;     // [k]
+    uint32_t* rows;     // [cm][kw] (ReduceScatter) bit r of class c: row r belongs to it
+    uint8_t* sig;       // [k][sgs] (ReduceScatter) rank that keeps the row in each group, 0xff: empty there
+    int cm, cs, sgs;    // most classes held; words between the rows of two devices in S (odd: lanes that
+                        // read the same class of different devices hit different banks); bytes per row in sig
+};
+__host__ __device__ inline int cls_cmax(int k) { return k < 64 ? k : 64; }
+__host__ __device__ inline int cls_words(int R, int k, int MW) {
+    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1, sgs = (ng + 3) & ~3, kh = (k + 1) / 2;
+    return R * (cm | 1) * MW + ng * cm * MW + 3 * cm + 4 * ng + 64 + 4 + 16 + 2 * kh + cm * ((k + 31) / 32) + (k * sgs) / 4 + 8;
+}
+// Words of a stem's saved class state: S, the classes of the rows, the class sizes.
+__host__ __device__ inline int cls_backup_words(int R, int k, int MW) { return R * cls_cmax(k) * MW + (k + 1) / 2 + cls_cmax(k) + 8; }
+__device__ inline ClsLds carve_cls(uint32_t* p, int R, int k, int MW) {
+    ClsLds X;
+    X.cm = cls_cmax(k);
+    const int ng = R / 2 > 0 ? R / 2 : 1, kh = (k + 1) / 2;
+    X.sgs = (ng + 3) & ~3;
+    X.cs = X.cm | 1;
+    X.S = p; p += R * X.cs * MW;
+    X.T = p; p += ng * X.cm * MW;
+    X.csize = p; p += X.cm;
+    X.ncsize = p; p += X.cm;
+    X.crow = p; p += X.cm;
+    X.gcount = p; p += ng;
+    X.gflag = p; p += ng;
+    X.gne = p; p += 2 * ng;
+    X.devne = p; p += 64;
+    X.flags = p; p += 4;
+    X.start = p; p += 16;
+    X.cls = reinterpret_cast<uint16_t*>(p); p += kh;
+    X.ncls = reinterpret_cast<uint16_t*>(p); p += kh;
+    X.rows = p; p += X.cm * ((k + 31) / 32);
+    X.sig = reinterpret_cast<uint8_t*>(p);
+    return X;
+}
+
+enum : int { CSTEP_INVALID = 0, CSTEP_OK = 1, CSTEP_OVERFLOW = 2 };
+
+// Sec. 3.5: device i holds column i in every row -- one class.
+template <int MW>
+__device__ inline void cls_init(const DevQuery& q, const ClsLds& X, int& C, int lane) {
+    for (int d = lane; d < q.R; d += kWave) {
+#pragma unroll
+        for (int w = 0; w < MW; ++w) X.S[d * X.cs * MW + w] = (w == (d >> 5)) ? (1u << (d & 31)) : 0u;
+    }
+    for (int r = lane; r < q.k; r += kWave) X.cls[r] = 0;
+    if (lane == 0) X.csize[0] = (uint32_t)q.k;
+    C = 1;
+    __syncthreads();
+}
+
+// The class state after a program's first instruction, written directly (see lit_init_first): one class
+// after an AllReduce or a Reduce, one class per block of rows after a ReduceScatter.
+template <int MW>
+__device__ inline int cls_init_first(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int& C, int lane) {
+    static_assert(MW <= 2, "groups of at most 64 devices");
+    if (op == OP_AG || op == OP_BC) return CSTEP_INVALID;
+    if (op == OP_RS && q.k % P.g != 0) return CSTEP_INVALID;
+    const int nc = op == OP_RS ? P.g : 1;
+    if (nc > X.cm) return CSTEP_OVERFLOW;
+    const int per = q.k / nc;
+    const uint32_t gmask = (uint32_t)(P.g - 1) * (uint32_t)P.s;          // g and s are powers of two
+    for (int it = lane; it < q.R * nc; it += kWave) {
+        const int d = it / nc, c = it - d * nc;
+        const bool in = !P.master || (d % P.s) == 0;
+        unsigned long long cols = 1ull << d;
+        if (in) {
+            cols = 1ull << ((uint32_t)d & ~gmask);
+            for (uint32_t b = (uint32_t)P.s; b < (uint32_t)(P.g * P.s); b <<= 1) cols |= cols << b;
+            const int p = (int)(((uint32_t)d & gmask) / (uint32_t)P.s);
+            if (op == OP_RS && c != p) cols = 0ull;
+            if (op == OP_RD && p != 0) cols = 0ull;
+        }
+        X.S[(d * X.cs + c) * MW] = (uint32_t)cols;
+        if (MW > 1) X.S[(d * X.cs + c) * MW + (MW > 1 ? 1 : 0)] = (uint32_t)(cols >> 32);
+    }
+    for (int r = lane; r < q.k; r += kWave) X.cls[r] = (uint16_t)(r / per);
+    for (int c = lane; c < nc; c += kWave) X.csize[c] = (uint32_t)per;
+    C = nc;
+    __syncthreads();
+    return CSTEP_OK;
+}
+
+// ReduceScatter on the class state, after cls_step has checked the premises and left the groups' combined
+// rows in T, their non-empty classes in gne and their non-empty row counts in gcount.  Row r, the b-th
+// non-empty row of group G, stays with the member of rank b / (gcount[G] / g).  Two rows of a class remain
+// in one class iff they stay with the same rank in every group; the ranks grow with the row number, so the
+// new classes are runs of consecutive rows of an old class, and a row starts a run iff its ranks differ
+// from those of the previous row of its class.
+template <int MW>
+__device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds& X, int& C, int lane) {
+    const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs, sgs = X.sgs;
+    const int kw = (k + 31) / 32;
+    for (int i = lane; i < C * kw; i += kWave) X.rows[i] = 0;
+    __syncthreads();
+    uint32_t carry = 0;                                   // lane G: non-empty rows of group G below the chunk
+    for (int r0 = 0; r0 < k; r0 += kWave) {
+        const int r = r0 + lane;
+        const int c = r < k ? (int)X.cls[r] : 0;
+        if (r < k) atomicOr(&X.rows[c * kw + (r >> 5)], 1u << (r & 31));
+        for (int G = 0; G < sgs; ++G) {
+            if (G >= ng) {                                // (padding, so that ranks compare as whole words)
+                if (r < k) X.sig[r * sgs + G] = 0;
+                continue;
+            }
+            const bool ne = r < k && ((X.gne[2 * G + (c >> 5)] >> (c & 31)) & 1u) != 0u;
+            const unsigned long long bal = __ballot(ne);
+            const uint32_t before = (uint32_t)__shfl((int)carry, G, kWave) + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            const uint32_t per = X.gcount[G] / (uint32_t)g;
+            // before < 512 and per <= 512: the quotient of (before + 1/2) / per is at least 1/1024 away from an
+            // integer, far more than the error of the fast division
+            const uint32_t owner = (uint32_t)__fdividef((float)before + 0.5f, (float)(per ? per : 1u));
+            if (r < k) X.sig[r * sgs + G] = ne ? (uint8_t)owner : (uint8_t)0xff;
+            if (lane == G) carry += (uint32_t)__popcll(bal);
+        }
+    }
+    __syncthreads();
+    // run starts: a row whose ranks differ from those of the previous row of its class (or that has none)
+    int newC = 0;
+    const uint32_t* const sigw = reinterpret_cast<const uint32_t*>(X.sig);
+    for (int r0 = 0; r0 < k; r0 += kWave) {
+        const int r = r0 + lane;
+        bool st = false;
+        if (r < k) {
+            const uint32_t* const mine = X.rows + (int)X.cls[r] * kw;
+            int w = r >> 5;
+            uint32_t m = mine[w] & ((1u << (r & 31)) - 1u);
+            while (m == 0u && w > 0) { --w; m = mine[w]; }
+            st = m == 0u;
+            if (!st) {
+                const int p = w * 32 + 31 - __clz((int)m);
+                for (int i = 0; i < sgs / 4; ++i) st |= sigw[(r * sgs) / 4 + i] != sigw[(p * sgs) / 4 + i];
+            }
+        }
+        const unsigned long long bal = __ballot(st);
+        if (lane == 0) { X.start[r0 >> 5] = (uint32_t)bal; X.start[(r0 >> 5) + 1] = (uint32_t)(bal >> 32); }
+        newC += __popcll(bal);
+    }
+    __syncthreads();
+    if (newC > cm) return CSTEP_OVERFLOW;                 // (nothing of the state has been written yet)
+    for (int i = lane; i < newC; i += kWave) X.ncsize[i] = 0;
+    __syncthreads();
+    // the new class of a row: the number of run starts below the start of its own run
+    for (int r = lane; r < k; r += kWave) {
+        const uint32_t* const mine = X.rows + (int)X.cls[r] * kw;
+        int w = r >> 5;
+        uint32_t m = mine[w] & X.start[w] & (((1u << (r & 31)) << 1) - 1u);
+        while (m == 0u) { --w; m = mine[w] & X.start[w]; }           // (the first row of a class starts a run)
+        const int sr = w * 32 + 31 - __clz((int)m);
+        int id = 0;
+        for (int v = 0; v < (sr >> 5); ++v) id += __popc(X.start[v]);
+        id += __popc(X.start[sr >> 5] & ((1u << (sr & 31)) - 1u));
+        X.ncls[r] = (uint16_t)id;
+        atomicAdd(&X.ncsize[id], 1u);
+        if (sr == r) X.crow[id] = (uint32_t)r;
+    }
+    __syncthreads();
+    // members: the rank that keeps the class takes the group's combined row, the others are left empty
+    for (int it = lane; it < q.R * newC; it += kWave) {
+        const int d = it / newC, c2 = it - d * newC;
+        if (P.master && (d % s) != 0) continue;
+        const int G = P.master ? d / gs : (d / gs) * s + d % s;
+        const int p = (d / s) % g;
+        const int r1 = (int)X.crow[c2], oc = (int)X.cls[r1];
+        const bool keep = (int)X.sig[r1 * sgs + G] == p;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) X.S[(d * cs + c2) * MW + w] = keep ? X.T[(G * cm + oc) * MW + w] : 0u;
+    }
+    // devices outside the pattern keep their rows: move them to the new classes, one device at a time
+    // (a lane per new class reads its old class, then all write)
+    if (P.master) {
+        for (int d = 0; d < q.R; ++d) {
+            if ((d % s) == 0) continue;
+            uint32_t v[MW];
+            if (lane < newC) {
+                const int oc = (int)X.cls[X.crow[lane]];
+#pragma unroll
+                for (int w = 0; w < MW; ++w) v[w] = X.S[(d * cs + oc) * MW + w];
+            }
+            __syncthreads();
+            if (lane < newC) {
+#pragma unroll
+                for (int w = 0; w < MW; ++w) X.S[(d * cs + lane) * MW + w] = v[w];
+            }
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    for (int r = lane; r < k; r += kWave) X.cls[r] = X.ncls[r];
+    for (int i = lane; i < newC; i += kWave) X.csize[i] = X.ncsize[i];
+    C = newC;
+    __syncthreads();
+    return CSTEP_OK;
+}
+
+// One instruction on the class state (the rules of lit_step, a class standing for its rows).  All lanes
+// call it with the same arguments.  An invalid step and an overflow leave the state as it was.
+template <int MW>
+__device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int& C, int lane) {
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs;
+    const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
+    for (int i = lane; i < ng; i += kWave) { X.gcount[i] = 0; X.gflag[i] = 0; X.gne[2 * i] = 0; X.gne[2 * i + 1] = 0; }
+    if (op == OP_AG)
+        for (int i = lane; i < q.R; i += kWave) X.devne[i] = 0;
+    if (lane == 0) { X.flags[0] = 0; X.flags[1] = 0; }
+    __syncthreads();
+    const int items = ng * C;
+    bool bad = false;
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / C, c = it - G * C;
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t acc[MW];
+#pragma unroll
+        for (int w = 0; w < MW; ++w) acc[w] = 0;
+        if (red) {
+            bool ne0 = false;
+            for (int p = 0; p < g; ++p) {
+                const uint32_t* x = X.S + ((base + p * s) * cs + c) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    const uint32_t v = x[w];
+                    any |= v;
+                    bad |= (acc[w] & v) != 0;
+                    acc[w] |= v;
+                }
+                if (p == 0) ne0 = any != 0;
+                else bad |= (any != 0) != ne0;
+            }
+            if (ne0) {
+                atomicAdd(&X.gcount[G], X.csize[c]);
+                atomicOr(&X.gne[2 * G + (c >> 5)], 1u << (c & 31));
+            }
+        } else if (op == OP_AG) {
+            int holders = 0;
+            for (int p = 0; p < g; ++p) {
+                const int dev = base + p * s;
+                const uint32_t* x = X.S + (dev * cs + c) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) { const uint32_t v = x[w]; any |= v; acc[w] |= v; }
+                if (any) { ++holders; X.devne[dev] = 1; }
+            }
+            bad |= holders > 1;
+        } else {
+            const uint32_t* root = X.S + (base * cs + c) * MW;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) acc[w] = root[w];
+            bool differs = false;
+            for (int p = 1; p < g; ++p) {
+                const uint32_t* x = X.S + ((base + p * s) * cs + c) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    const uint32_t v = x[w];
+                    bad |= (v & ~acc[w]) != 0;
+                    differs |= v != acc[w];
+                }
+            }
+            if (differs) X.gflag[G] = 1;
+        }
+#pragma unroll
+        for (int w = 0; w < MW; ++w) X.T[(G * cm + c) * MW + w] = acc[w];
+    }
+    if (bad) X.flags[0] = 1;
+    __syncthreads();
+    for (int G = lane; G < ng; G += kWave) {
+        const uint32_t cnt = X.gcount[G];
+        if (red) {
+            if (op == OP_RS && cnt % (uint32_t)g != 0) X.flags[0] = 1;   // scatter: chunks must divide evenly
+            if (cnt) X.flags[1] = 1;                                    // a group of empty devices is a no-op
+        } else if (op == OP_AG) {
+            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            for (int p = 0; p < g; ++p)
+                if (!X.devne[base + p * s]) X.flags[0] = 1;
+            X.flags[1] = 1;
+        } else {
+            if (!X.gflag[G]) X.flags[0] = 1;                            // no information increase
+            X.flags[1] = 1;
+        }
+    }
+    __syncthreads();
+    if (X.flags[0] || !X.flags[1]) return CSTEP_INVALID;
+    if (op == OP_RS) return cls_scatter<MW>(q, P, X, C, lane);
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / C, c = it - G * C;
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t t[MW];
+#pragma unroll
+        for (int w = 0; w < MW; ++w) t[w] = X.T[(G * cm + c) * MW + w];
+        for (int p = (op == OP_BC ? 1 : 0); p < g; ++p) {
+            uint32_t* x = X.S + ((base + p * s) * cs + c) * MW;
+            const bool keep = op != OP_RD || p == 0;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) x[w] = keep ? t[w] : 0u;
+        }
+    }
+    __syncthreads();
+    return CSTEP_OK;
+}
+
+// One instruction against the class state, read-only (lit_classify on classes): 0 = invalid step,
+// 2 = valid and the result is the goal, 3 = valid.  full_mask: bit d set iff device d is at the goal.
+template <int MW>
+__device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int C, const uint32_t* full,
+                            unsigned long long any_mask, unsigned long long full_mask, int lane) {
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cs = X.cs;
+    const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
+    for (int i = lane; i < ng; i += kWave) { X.gcount[i] = 0; X.gflag[i] = 0; }
+    if (lane == 0) { X.flags[0] = 0; X.flags[1] = 0; X.flags[2] = 0; }
+    __syncthreads();
+    const int items = ng * C;
+    bool bad = false, notfull = false;
+    for (int it = lane; it < items; it += kWave) {
+        const int G = it / C, c = it - G * C;
+        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        uint32_t acc[MW];
+#pragma unroll
+        for (int w = 0; w < MW; ++w) acc[w] = 0;
+        if (red) {
+            bool ne0 = false;
+            for (int p = 0; p < g; ++p) {
+                const uint32_t* x = X.S + ((base + p * s) * cs + c) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    const uint32_t v = x[w];
+                    any |= v;
+                    bad |= (acc[w] & v) != 0;
+                    acc[w] |= v;
+                }
+                if (p == 0) ne0 = any != 0;
+                else bad |= (any != 0) != ne0;
+            }
+            if (ne0) atomicAdd(&X.gcount[G], X.csize[c]);
+        } else if (op == OP_AG) {
+            int holders = 0;
+            for (int p = 0; p < g; ++p) {
+                const int dev = base + p * s;
+                const uint32_t* x = X.S + (dev * cs + c) * MW;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) { const uint32_t v = x[w]; any |= v; acc[w] |= v; }
+                holders += any != 0;
+                if (c == 0) bad |= ((any_mask >> dev) & 1ull) == 0ull;
+            }
+            bad |= holders > 1;
+        } else {
+            const uint32_t* root = X.S + (base * cs + c) * MW;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) acc[w] = root[w];
+            bool differs = false;
+            for (int p = 1; p < g; ++p) {
+                const uint32_t* x = X.S + ((base + p * s) * cs + c) * MW;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) {
+                    const uint32_t v = x[w];
+                    bad |= (v & ~acc[w]) != 0;
+                    differs |= v != acc[w];
+                }
+            }
+            if (differs) X.gflag[G] = 1;
+        }
+#pragma unroll
+        for (int w = 0; w < MW; ++w) notfull |= acc[w] != full[w];
+    }
+    if (bad) X.flags[0] = 1;
+    if (notfull) X.flags[2] = 1;
+    // devices the pattern does not touch must already be at the goal
+    if (P.master)
+        for (int d = lane; d < q.R; d += kWave) {
+            const bool part = d % s == 0 && d / gs < ng;
+            if (!part && ((full_mask >> d) & 1ull) == 0ull) X.flags[2] = 1;
+        }
+    __syncthreads();
+    for (int G = lane; G < ng; G += kWave) {
+        const uint32_t cnt = X.gcount[G];
+        if (red) {
+            if (op == OP_RS && cnt % (uint32_t)g != 0) X.flags[0] = 1;
+            if (cnt) X.flags[1] = 1;
+        } else if (op == OP_BC) {
+            if (!X.gflag[G]) X.flags[0] = 1;
+        }
+    }
+    __syncthreads();
+    const bool invalid = X.flags[0] != 0 || (red && X.flags[1] == 0);
+    const bool goal = (op == OP_AR || op == OP_AG || op == OP_BC) && X.flags[2] == 0;
+    __syncthreads();
+    return invalid ? 0 : goal ? 2 : 3;
+}
+
+// The last instructions a = part, part + parts, ... of a group against the class state; those that are valid
+// and reach the goal are reported.  Only the goal matters here (the candidates' steps are counted by the
+// caller), and the goal can only come from an AllReduce on devices that all hold every row, from an AllGather
+// on devices whose rows all carry every column, or from a Broadcast whose roots (device 0 is one in every
+// pattern) are at the goal already: ReduceScatter and Reduce leave members short of rows, an AllReduce gives
+// nobody a new row, an AllGather leaves every row with its holder's columns, a Broadcast with its root's.
+// So most states need no instruction looked at.
+template <int MW>
+__device__ inline void cls_judge_all(const DevQuery& q, unsigned long long first, const ClsLds& X, int C, const uint32_t* full,
+                                     int lane, int part, int parts) {
+    bool rows_ok = true, cols_ok = true, full_ok = true, any = false;      // lane d looks at device d
+    if (lane < q.R)
+        for (int c = 0; c < C; ++c) {
+            const uint32_t* x = X.S + (lane * X.cs + c) * MW;
+            bool ne = false, fl = true;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) { ne |= x[w] != 0u; fl &= x[w] == full[w]; }
+            rows_ok &= ne; cols_ok &= !ne || fl; full_ok &= fl; any |= ne;
+        }
+    const bool in = lane < q.R;
+    const bool rows_full = !__any(in && !rows_ok), cols_full = !__any(in && !cols_ok);
+    const unsigned long long any_mask = __ballot(in && any), full_mask = __ballot(in && full_ok);
+    const bool root_done = (full_mask & 1ull) != 0ull;
+    if (!(rows_full || cols_full || root_done)) return;
+    for (int a = part; a < q.alphabet; a += parts) {
+        const uint32_t ins = q.instr_of_digit[a];
+        const int op = (int)(ins & 7u);
+        if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
+        if (cls_classify<MW>(q, q.pat[ins >> 3], op, X, C, full, any_mask, full_mask, lane) == 2 && lane == 0) {
+            const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
+            if (pos < q.valid_cap) q.valid_idx[pos] = first + (unsigned long long)a;
+        }
+    }
+}
+
+// literal_group on the class state.  Returns false, with nothing counted or reported, when a step needs more
+// classes than the state holds.
+template <int MW>
+__device__ inline bool cls_group(const DevQuery& q, unsigned long long idx0, const ClsLds& X, const uint32_t* full, int lane,
+                                 int part, int parts, unsigned long long& steps, unsigned long long& members) {
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx0, digit);
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    int rc = CSTEP_OK, C = 1;
+    unsigned long long ran = 0, visited = 0;
+    int t0 = 0;
+    if (len - 1 >= 1) {
+        const int pid = digit[0] / q.n_ops, op = q.ops[digit[0] - pid * q.n_ops];
+        ran = 1;
+        visited = (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        rc = cls_init_first<MW>(q, q.pat[pid], op, X, C, lane);
+        t0 = 1;
+    } else {
+        cls_init<MW>(q, X, C, lane);
+    }
+    for (int t = t0; t < len - 1 && rc == CSTEP_OK; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ++ran;
+        visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        rc = cls_step<MW>(q, q.pat[pid], op, X, C, lane);
+    }
+    if (rc == CSTEP_OVERFLOW) return false;
+    if (rc == CSTEP_INVALID) {
+        if (part == 0) { steps += I * ran; members += I * visited; }
+        return true;
+    }
+    cls_judge_all<MW>(q, idx0, X, C, full, lane, part, parts);
+    if (part == 0) {
+        steps += I * (ran + 1ull);
+        members += I * visited + (unsigned long long)q.reg_sum_part;
+    }
+    return true;
+}
+
+// literal_stem on the class state; the stem's class state is kept in `backup` (global).  Returns false, with
+// nothing counted or reported, when the stem itself needs more classes than the state holds; a group whose
+// own instruction does is evaluated by literal_group on the full state (L, F).
+template <int MW>
+__device__ inline bool cls_stem(const DevQuery& q, unsigned long long idx0, int count, const ClsLds& X, const uint32_t* full,
+                                int lane, int part, int parts, uint32_t* __restrict__ backup, const LitLds& L, const FrontLit& F,
+                                unsigned long long& steps, unsigned long long& members) {
+    uint16_t digit[P2_MAX_LEN + 1];
+    const int len = unrank(q, idx0, digit);         // len >= 3: digit[len-2] is the first group's instruction
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    int rc = CSTEP_OK, C = 1;
+    unsigned long long ran = 0, visited = 0;
+    int t0 = 0;
+    if (len - 2 >= 1) {
+        const int pid = digit[0] / q.n_ops, op = q.ops[digit[0] - pid * q.n_ops];
+        ran = 1;
+        visited = (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        rc = cls_init_first<MW>(q, q.pat[pid], op, X, C, lane);
+        t0 = 1;
+    } else {
+        cls_init<MW>(q, X, C, lane);
+    }
+    for (int t = t0; t < len - 2 && rc == CSTEP_OK; ++t) {
+        const int pid = digit[t] / q.n_ops, op = q.ops[digit[t] - pid * q.n_ops];
+        ++ran;
+        visited += (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        rc = cls_step<MW>(q, q.pat[pid], op, X, C, lane);
+    }
+    if (rc == CSTEP_OVERFLOW) return false;
+    const int mine = part < count ? (count - part + parts - 1) / parts : 0;      // groups of this part
+    if (rc == CSTEP_INVALID) {                      // every candidate under the stem stops inside it
+        steps += (unsigned long long)mine * I * ran;
+        members += (unsigned long long)mine * I * visited;
+        return true;
+    }
+    const int cm = X.cm, cs = X.cs, kh = (q.k + 1) / 2, C0 = C;
+    uint32_t* const b_cls = backup + q.R * cm * MW;
+    uint32_t* const b_size = b_cls + kh;
+    const uint32_t* const cls_w = reinterpret_cast<const uint32_t*>(X.cls);
+    uint32_t* const cls_ww = reinterpret_cast<uint32_t*>(X.cls);
+    for (int it = lane; it < q.R * C0; it += kWave) {
+        const int d = it / C0, c = it - d * C0;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) backup[(d * cm + c) * MW + w] = X.S[(d * cs + c) * MW + w];
+    }
+    for (int i = lane; i < kh; i += kWave) b_cls[i] = cls_w[i];
+    for (int i = lane; i < C0; i += kWave) b_size[i] = X.csize[i];
+    bool dirty = false;
+    for (int gi = part; gi < count; gi += parts) {
+        if (dirty) {
+            __syncthreads();
+            for (int it = lane; it < q.R * C0; it += kWave) {
+                const int d = it / C0, c = it - d * C0;
+#pragma unroll
+                for (int w = 0; w < MW; ++w) X.S[(d * cs + c) * MW + w] = backup[(d * cm + c) * MW + w];
+            }
+            for (int i = lane; i < kh; i += kWave) cls_ww[i] = b_cls[i];
+            for (int i = lane; i < C0; i += kWave) X.csize[i] = b_size[i];
+            C = C0;
+            __syncthreads();
+            dirty = false;
+        }
+        const int dgt = (int)digit[len - 2] + gi;
+        const int pid = dgt / q.n_ops, op = q.ops[dgt - pid * q.n_ops];
+        const unsigned long long g_ran = ran + 1ull;
+        const unsigned long long g_vis = visited + (unsigned long long)(q.pat[pid].n_groups * q.pat[pid].g);
+        const unsigned long long first = idx0 + (unsigned long long)gi * I;
+        const int rg = cls_step<MW>(q, q.pat[pid], op, X, C, lane);
+        if (rg == CSTEP_INVALID) {
+            steps += I * g_ran;
+            members += I * g_vis;
+            continue;
+        }
+        if (rg == CSTEP_OVERFLOW) {                 // (the class state is untouched)
+            literal_group<MW>(q, first, L, F, full, lane, 0, 1, steps, members);
+            continue;
+        }
+        dirty = true;
+        cls_judge_all<MW>(q, first, X, C, full, lane, 0, 1);
+        steps += I * (g_ran + 1ull);
+        members += I * g_vis + (unsigned long long)q.reg_sum_part;
+    }
+    return true;
+}
+
 // The groups that the shared-prefix kernel has just handed over, found on the device: those of the queries
 // qlist[0 .. n_q), read from their counters and lists.  A unit of work is one (group, part) pair; blocks
 // stride over the units.  States that fit in LDS live there; larger ones in the block's slice of a global buffer.  This lets the host queue the kernel
@@ -785,12 +1355,16 @@ template <int MW>
 __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQuery* __restrict__ queries,
                                                                     const int32_t* __restrict__ qlist, int n_q,
                                                                     uint32_t* __restrict__ gscratch,
-                                                                    unsigned long long gwords, int state_in_lds) {
+                                                                    unsigned long long gwords, int state_in_lds,
+                                                                    int cls_lds_words, int cls_backup) {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
-    // the block's slice of the global buffer: the state itself where it does not fit in LDS, then the stem copy
-    uint32_t* const slice = gscratch + (size_t)blockIdx.x * gwords;
-    uint32_t* const mem = state_in_lds ? lds : slice;
+    // LDS: the class state, then the full literal state where that fits as well.  The block's slice of the
+    // global buffer: the copy of a stem's class state, the full state where it is not in LDS, the copy of a
+    // stem's full state.
+    uint32_t* const cls_copy = gscratch + (size_t)blockIdx.x * gwords;
+    uint32_t* const slice = cls_copy + cls_backup;
+    uint32_t* const mem = state_in_lds ? lds + cls_lds_words : slice;
     auto count_of = [&](int i) -> uint32_t {
         if (i >= n_q) return 0u;
         const DevQuery& q = queries[qlist[i]];
@@ -846,6 +1420,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
         const DevQuery& q = queries[qlist[owner]];
         const LitLds L = carve(mem, q.R, q.k, MW);
         const FrontLit X = carve_front(L.flags + 4, q.k);
+        const ClsLds Y = carve_cls(lds, q.R, q.k, MW);
         uint32_t full[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) {
@@ -854,12 +1429,16 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
         }
         unsigned long long steps = 0, members = 0;
         const unsigned long long entry = q.rerun_idx[e - own_lo];
+        // on the class state; on the full literal state where that needs more classes than it holds
         if (entry & kStemEntry) {
-            LitLayout lay(q.R, q.k, MW);
-            uint32_t* const backup = state_in_lds ? slice : slice + lay.total_words() + front_lit_words(q.k);
-            literal_stem<MW>(q, entry & kEntryIndexMask, (int)((entry >> kStemCountShift) & 0x7ffull), L, X, full, lane, part,
-                             (int)parts, backup, steps, members);
-        } else {
+            const unsigned long long idx0 = entry & kEntryIndexMask;
+            const int count = (int)((entry >> kStemCountShift) & 0x7ffull);
+            if (!cls_stem<MW>(q, idx0, count, Y, full, lane, part, (int)parts, cls_copy, L, X, steps, members)) {
+                LitLayout lay(q.R, q.k, MW);
+                uint32_t* const backup = state_in_lds ? slice : slice + lay.total_words() + front_lit_words(q.k);
+                literal_stem<MW>(q, idx0, count, L, X, full, lane, part, (int)parts, backup, steps, members);
+            }
+        } else if (!cls_group<MW>(q, entry, Y, full, lane, part, (int)parts, steps, members)) {
             literal_group<MW>(q, entry, L, X, full, lane, part, (int)parts, steps, members);
         }
         if (lane == 0 && steps) {
@@ -1059,12 +1638,24 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     return hipGetLastError();
 }
 
+// LDS of the hand-over kernel: the class state, and behind it the full literal state with its tables if
+// both fit (*full_in_lds).
+static size_t group_lds_bytes(int max_R, int max_k, bool* full_in_lds) {
+    const int MW = mask_words(max_R);
+    LitLayout lay(max_R, max_k, MW);
+    const size_t cls = (size_t)cls_words(max_R, max_k, MW), full = (size_t)(lay.total_words() + front_lit_words(max_k));
+    *full_in_lds = (cls + full) * 4 <= kLdsLimit;
+    return (cls + (*full_in_lds ? full : 0)) * 4;
+}
+
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
-    // up to 4096 blocks, each with its own global slice: the copy of a stem's state, and in front of it
-    // the state itself with its tables where that does not fit in LDS
+    // up to 4096 blocks, each with its own global slice: the copy of a stem's class state, the full state
+    // with its tables where that does not fit in LDS, the copy of a stem's full state
     LitLayout lay(max_R, max_k, mask_words(max_R));
-    const size_t state = front_literal_lds_bytes(max_R, max_k) != 0 ? 0 : (size_t)(lay.total_words() + front_lit_words(max_k));
-    const size_t per = ((state + (size_t)lay.s_words) * 4 + 255) / 256 * 256;
+    bool in_lds = false;
+    group_lds_bytes(max_R, max_k, &in_lds);
+    const size_t state = in_lds ? 0 : (size_t)(lay.total_words() + front_lit_words(max_k));
+    const size_t per = (((size_t)cls_backup_words(max_R, max_k, mask_words(max_R)) + state + (size_t)lay.s_words) * 4 + 255) / 256 * 256;
     unsigned b = 4096;
     while (b > 1 && per * b > ((size_t)8 << 30)) b >>= 1;
     *blocks = b;
@@ -1074,17 +1665,19 @@ size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
                                            void* gscratch, hipStream_t stream) {
     if (n_q == 0) return hipSuccess;
-    const size_t lds = front_literal_lds_bytes(max_R, max_k);
-    if (!gscratch) return hipErrorInvalidValue;
+    if (!gscratch || max_R > 64) return hipErrorInvalidValue;
+    bool in_lds = false;
+    const size_t lds = group_lds_bytes(max_R, max_k, &in_lds);
     unsigned blocks = 0;
     const unsigned long long gwords = literal_group_scratch_bytes(max_R, max_k, &blocks) / blocks / 4;
-    const int state_in_lds = lds != 0 ? 1 : 0;
+    const int state_in_lds = in_lds ? 1 : 0;
+    const int cls_lds = cls_words(max_R, max_k, mask_words(max_R)), cls_backup = cls_backup_words(max_R, max_k, mask_words(max_R));
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_eval_literal_groups_auto<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, qlist, n_q, \
-                           static_cast<uint32_t*>(gscratch), gwords, state_in_lds);
+                           static_cast<uint32_t*>(gscratch), gwords, state_in_lds, cls_lds, cls_backup);
     switch (mask_words(max_R)) {              // reduction groups of at most 64 devices
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
