@@ -287,15 +287,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
     }
     // Groups that the shared-prefix engine hands to the literal engine are found on the device, so that kernel
-    // is queued right behind the evaluation: one launch per mask width and per "state fits in LDS", each
-    // with the list of its queries.
+    // is queued right behind the evaluation: one launch per mask width, each with the list of its queries.
     struct AutoGroups { int cls = 0, max_R = 0, max_k = 0; std::vector<int32_t> qlist; size_t off = 0; };
     std::vector<AutoGroups> autos;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (!r.shared || r.frontier || r.plan.n_candidates == 0) continue;
         const int mw = r.plan.R <= 32 ? 1 : 2;
-        const int cls = mw * 2 + (front_literal_lds_bytes(r.plan.R, r.plan.k) != 0 ? 1 : 0);
+        const int cls = mw;
         AutoGroups* A = nullptr;
         for (auto& a : autos) if (a.cls == cls) A = &a;
         if (!A) { autos.emplace_back(); A = &autos.back(); A->cls = cls; }

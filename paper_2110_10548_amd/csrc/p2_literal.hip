@@ -6,6 +6,8 @@
 // step times (hierarchical cost model, see p2.h).
 #include "p2_device.h"
 
+#include <cstdlib>
+
 namespace p2 {
 
 namespace {
@@ -623,7 +625,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
     const int lane = threadIdx.x;
     const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
     const FrontLit X = carve_front(L.flags + 4, q.k);
-    const int R = q.R, k = q.k, I = q.alphabet;
+    const int R = q.R, I = q.alphabet;
     uint32_t full[MW];
 #pragma unroll
     for (int w = 0; w < MW; ++w) {
@@ -1348,23 +1350,22 @@ __device__ inline bool cls_stem(const DevQuery& q, unsigned long long idx0, int 
 
 // The groups that the shared-prefix kernel has just handed over, found on the device: those of the queries
 // qlist[0 .. n_q), read from their counters and lists.  A unit of work is one (group, part) pair; blocks
-// stride over the units.  States that fit in LDS live there; larger ones in the block's slice of a global buffer.  This lets the host queue the kernel
+// stride over the units.  This lets the host queue the kernel
 // right behind the evaluation, without waiting for the counts.  A query whose list overflowed is left
 // out (the host grows the list and runs the query again).  Few groups: up to 8 blocks share one.
 template <int MW>
 __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQuery* __restrict__ queries,
                                                                     const int32_t* __restrict__ qlist, int n_q,
                                                                     uint32_t* __restrict__ gscratch,
-                                                                    unsigned long long gwords, int state_in_lds,
-                                                                    int cls_lds_words, int cls_backup) {
+                                                                    unsigned long long gwords, int cls_backup,
+                                                                    int class_cap) {
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
-    // LDS: the class state, then the full literal state where that fits as well.  The block's slice of the
-    // global buffer: the copy of a stem's class state, the full state where it is not in LDS, the copy of a
-    // stem's full state.
+    // LDS holds the class state.  The block's slice of the global buffer: the copy of a stem's class state,
+    // and for the entries that need more classes than the state holds the full literal state with its tables
+    // and the copy of a stem's full state.
     uint32_t* const cls_copy = gscratch + (size_t)blockIdx.x * gwords;
-    uint32_t* const slice = cls_copy + cls_backup;
-    uint32_t* const mem = state_in_lds ? lds + cls_lds_words : slice;
+    uint32_t* const mem = cls_copy + cls_backup;
     auto count_of = [&](int i) -> uint32_t {
         if (i >= n_q) return 0u;
         const DevQuery& q = queries[qlist[i]];
@@ -1420,7 +1421,8 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
         const DevQuery& q = queries[qlist[owner]];
         const LitLds L = carve(mem, q.R, q.k, MW);
         const FrontLit X = carve_front(L.flags + 4, q.k);
-        const ClsLds Y = carve_cls(lds, q.R, q.k, MW);
+        ClsLds Y = carve_cls(lds, q.R, q.k, MW);
+        Y.cm = Y.cm < class_cap ? Y.cm : class_cap;
         uint32_t full[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) {
@@ -1435,7 +1437,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
             const int count = (int)((entry >> kStemCountShift) & 0x7ffull);
             if (!cls_stem<MW>(q, idx0, count, Y, full, lane, part, (int)parts, cls_copy, L, X, steps, members)) {
                 LitLayout lay(q.R, q.k, MW);
-                uint32_t* const backup = state_in_lds ? slice : slice + lay.total_words() + front_lit_words(q.k);
+                uint32_t* const backup = mem + lay.total_words() + front_lit_words(q.k);
                 literal_stem<MW>(q, idx0, count, L, X, full, lane, part, (int)parts, backup, steps, members);
             }
         } else if (!cls_group<MW>(q, entry, Y, full, lane, part, (int)parts, steps, members)) {
@@ -1638,23 +1640,12 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     return hipGetLastError();
 }
 
-// LDS of the hand-over kernel: the class state, and behind it the full literal state with its tables if
-// both fit (*full_in_lds).
-static size_t group_lds_bytes(int max_R, int max_k, bool* full_in_lds) {
-    const int MW = mask_words(max_R);
-    LitLayout lay(max_R, max_k, MW);
-    const size_t cls = (size_t)cls_words(max_R, max_k, MW), full = (size_t)(lay.total_words() + front_lit_words(max_k));
-    *full_in_lds = (cls + full) * 4 <= kLdsLimit;
-    return (cls + (*full_in_lds ? full : 0)) * 4;
-}
-
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
-    // up to 4096 blocks, each with its own global slice: the copy of a stem's class state, the full state
-    // with its tables where that does not fit in LDS, the copy of a stem's full state
+    // up to 4096 blocks, each with its own global slice: the copy of a stem's class state, the full literal
+    // state with its tables, the copy of a stem's full state (LDS holds the class state only: with the full
+    // state beside it fewer blocks fit on a compute unit, and hardly any entry needs it)
     LitLayout lay(max_R, max_k, mask_words(max_R));
-    bool in_lds = false;
-    group_lds_bytes(max_R, max_k, &in_lds);
-    const size_t state = in_lds ? 0 : (size_t)(lay.total_words() + front_lit_words(max_k));
+    const size_t state = (size_t)(lay.total_words() + front_lit_words(max_k));
     const size_t per = (((size_t)cls_backup_words(max_R, max_k, mask_words(max_R)) + state + (size_t)lay.s_words) * 4 + 255) / 256 * 256;
     unsigned b = 4096;
     while (b > 1 && per * b > ((size_t)8 << 30)) b >>= 1;
@@ -1666,18 +1657,24 @@ hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_
                                            void* gscratch, hipStream_t stream) {
     if (n_q == 0) return hipSuccess;
     if (!gscratch || max_R > 64) return hipErrorInvalidValue;
-    bool in_lds = false;
-    const size_t lds = group_lds_bytes(max_R, max_k, &in_lds);
+    const size_t lds = (size_t)cls_words(max_R, max_k, mask_words(max_R)) * 4;
     unsigned blocks = 0;
     const unsigned long long gwords = literal_group_scratch_bytes(max_R, max_k, &blocks) / blocks / 4;
-    const int state_in_lds = in_lds ? 1 : 0;
-    const int cls_lds = cls_words(max_R, max_k, mask_words(max_R)), cls_backup = cls_backup_words(max_R, max_k, mask_words(max_R));
+    const int cls_backup = cls_backup_words(max_R, max_k, mask_words(max_R));
+    // The state holds up to 64 classes of rows, which is all that power-of-two groups can produce; entries
+    // that would need more are evaluated on the full literal state.  P2_HANDOVER_CLASSES (1..64) lowers the
+    // limit, so that tests can send entries down that path.
+    int class_cap = 64;
+    if (const char* env = std::getenv("P2_HANDOVER_CLASSES")) {
+        const int v = std::atoi(env);
+        if (v >= 1 && v < 64) class_cap = v;
+    }
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_eval_literal_groups_auto<MWV>, dim3(blocks), dim3(kWave), lds, stream, queries, qlist, n_q, \
-                           static_cast<uint32_t*>(gscratch), gwords, state_in_lds, cls_lds, cls_backup);
+                           static_cast<uint32_t*>(gscratch), gwords, cls_backup, class_cap);
     switch (mask_words(max_R)) {              // reduction groups of at most 64 devices
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
