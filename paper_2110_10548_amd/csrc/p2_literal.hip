@@ -781,12 +781,12 @@ __device__ inline void literal_stem(const DevQuery& q, unsigned long long idx0, 
 // ---- the literal state by classes of equal rows ----------------------------------------------------
 // Rows that are equal on every device stay equal under AllReduce, Reduce, AllGather and Broadcast (the
 // rules act row by row), and a ReduceScatter splits a class only where a block boundary of some group
-// falls between two of its rows.  So the handed-over groups are evaluated on one row per class: the
-// state is [R][C] masks plus the class of every row and the class sizes, a step costs C instead of k
-// rows, and it fits in LDS whatever k is.  C is at most 64 here; a ReduceScatter that would need more
-// classes reports an overflow and the caller evaluates that entry on the full literal state instead.
+// falls between two of its rows.  So a literal state can be kept as one row per class: [R][C] masks plus
+// the class of every row and the class sizes; a step then costs C instead of k rows.  C is at most 64
+// here; a ReduceScatter that would need more classes reports an overflow and the caller evaluates that
+// entry on the full literal state instead.
 struct ClsLds {
-    uint32_t* S;        // [R][cm][MW]  mask of class c on device d
+    uint32_t* S;        // [R][cs][MW]  mask of class c on device d
     uint32_t* T;        // [ng][cm][MW] combined rows of each group
     uint32_t* csize;    // [cm]  rows in the class
     uint32_t* ncsize;   // [cm]  (ReduceScatter) sizes of the new classes
@@ -794,28 +794,32 @@ struct ClsLds {
     uint32_t* gcount;   // [ng]  non-empty rows of the group's result
     uint32_t* gflag;    // [ng]  Broadcast: some member differs from the root
     uint32_t* gne;      // [ng][2] which classes of the group's result are non-empty
-    uint32_t* devne;    // [64]  AllGather: device holds something
+    uint32_t* devne;    // [R]   AllGather: device holds something
+    uint32_t* devany;   // [R]   device holds something       (for instructions judged read-only)
+    uint32_t* devfull;  // [R]   device is at the goal
     uint32_t* flags;    // [4]
     uint32_t* start;    // [16]  (ReduceScatter) bit r: row r is the first of a new class
     uint16_t* cls;      // [k]   class of a row
     uint16_t* ncls;     // [k]
     uint32_t* rows;     // [cm][kw] (ReduceScatter) bit r of class c: row r belongs to it
-    uint8_t* sig;       // [k][sgs] (ReduceScatter) rank that keeps the row in each group, 0xff: empty there
-    int cm, cs, sgs;    // most classes held; words between the rows of two devices in S (odd: lanes that
-                        // read the same class of different devices hit different banks); bytes per row in sig
+    uint32_t* bnd;      // [cm][kw] (ReduceScatter) bit r of class c: some group in which the class is not empty
+                        //          starts a new block at row r
+    uint8_t* own;       // [cm][ngs] (ReduceScatter) rank that keeps the new class in each group, 0xff: empty there
+    int cm, cs, ngs;    // most classes held; words between the rows of two devices in S (odd: lanes that
+                        // read the same class of different devices hit different banks); bytes per class in own
 };
 __host__ __device__ inline int cls_cmax(int k) { return k < 64 ? k : 64; }
 __host__ __device__ inline int cls_words(int R, int k, int MW) {
-    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1, sgs = (ng + 3) & ~3, kh = (k + 1) / 2;
-    return R * (cm | 1) * MW + ng * cm * MW + 3 * cm + 4 * ng + 64 + 4 + 16 + 2 * kh + cm * ((k + 31) / 32) + (k * sgs) / 4 + 8;
+    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1, ngs = (ng + 3) & ~3, kh = (k + 1) / 2, kw = (k + 31) / 32;
+    return R * (cm | 1) * MW + ng * cm * MW + 3 * cm + 4 * ng + 3 * R + 4 + 16 + 2 * kh + 2 * cm * kw + (cm * ngs) / 4 + 8;
 }
 // Words of a stem's saved class state: S, the classes of the rows, the class sizes.
 __host__ __device__ inline int cls_backup_words(int R, int k, int MW) { return R * cls_cmax(k) * MW + (k + 1) / 2 + cls_cmax(k) + 8; }
 __device__ inline ClsLds carve_cls(uint32_t* p, int R, int k, int MW) {
     ClsLds X;
     X.cm = cls_cmax(k);
-    const int ng = R / 2 > 0 ? R / 2 : 1, kh = (k + 1) / 2;
-    X.sgs = (ng + 3) & ~3;
+    const int ng = R / 2 > 0 ? R / 2 : 1, kh = (k + 1) / 2, kw = (k + 31) / 32;
+    X.ngs = (ng + 3) & ~3;
     X.cs = X.cm | 1;
     X.S = p; p += R * X.cs * MW;
     X.T = p; p += ng * X.cm * MW;
@@ -825,13 +829,16 @@ __device__ inline ClsLds carve_cls(uint32_t* p, int R, int k, int MW) {
     X.gcount = p; p += ng;
     X.gflag = p; p += ng;
     X.gne = p; p += 2 * ng;
-    X.devne = p; p += 64;
+    X.devne = p; p += R;
+    X.devany = p; p += R;
+    X.devfull = p; p += R;
     X.flags = p; p += 4;
     X.start = p; p += 16;
     X.cls = reinterpret_cast<uint16_t*>(p); p += kh;
     X.ncls = reinterpret_cast<uint16_t*>(p); p += kh;
-    X.rows = p; p += X.cm * ((k + 31) / 32);
-    X.sig = reinterpret_cast<uint8_t*>(p);
+    X.rows = p; p += X.cm * kw;
+    X.bnd = p; p += X.cm * kw;
+    X.own = reinterpret_cast<uint8_t*>(p);
     return X;
 }
 
@@ -882,55 +889,68 @@ __device__ inline int cls_init_first(const DevQuery& q, const DevPattern& P, int
     return CSTEP_OK;
 }
 
+// b / per for b < 512 and 0 < per <= 512: the quotient of (b + 1/2) / per is at least 1/1024 away from an
+// integer, far more than the error of the fast division.
+__device__ __forceinline__ uint32_t small_div(uint32_t b, uint32_t per) {
+    return (uint32_t)__fdividef((float)b + 0.5f, (float)per);
+}
+
 // ReduceScatter on the class state, after cls_step has checked the premises and left the groups' combined
 // rows in T, their non-empty classes in gne and their non-empty row counts in gcount.  Row r, the b-th
 // non-empty row of group G, stays with the member of rank b / (gcount[G] / g).  Two rows of a class remain
-// in one class iff they stay with the same rank in every group; the ranks grow with the row number, so the
-// new classes are runs of consecutive rows of an old class, and a row starts a run iff its ranks differ
-// from those of the previous row of its class.
+// in one class iff they stay with the same rank in every group in which the class is not empty; the ranks
+// grow with the row number, so the new classes are runs of consecutive rows of an old class, and a row
+// starts a run iff some such group starts a new block after the previous row of the class, up to the row.
 template <int MW>
 __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds& X, int& C, int lane) {
-    const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs, sgs = X.sgs;
+    const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs, ngs = X.ngs;
     const int kw = (k + 31) / 32;
-    for (int i = lane; i < C * kw; i += kWave) X.rows[i] = 0;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int i = lane; i < C * kw; i += kWave) { X.rows[i] = 0; X.bnd[i] = 0; }
     __syncthreads();
-    uint32_t carry = 0;                                   // lane G: non-empty rows of group G below the chunk
-    for (int r0 = 0; r0 < k; r0 += kWave) {
-        const int r = r0 + lane;
-        const int c = r < k ? (int)X.cls[r] : 0;
-        if (r < k) atomicOr(&X.rows[c * kw + (r >> 5)], 1u << (r & 31));
-        for (int G = 0; G < sgs; ++G) {
-            if (G >= ng) {                                // (padding, so that ranks compare as whole words)
-                if (r < k) X.sig[r * sgs + G] = 0;
-                continue;
-            }
-            const bool ne = r < k && ((X.gne[2 * G + (c >> 5)] >> (c & 31)) & 1u) != 0u;
+    for (int r = lane; r < k; r += kWave) atomicOr(&X.rows[(int)X.cls[r] * kw + (r >> 5)], 1u << (r & 31));
+    // block starts of every group, united per class (lane c keeps the words of class c)
+    for (int G = 0; G < ng; ++G) {
+        const uint32_t per = X.gcount[G] / (uint32_t)g;
+        if (per == 0u) continue;                          // a group of empty devices
+        const unsigned long long gne = (unsigned long long)X.gne[2 * G] | ((unsigned long long)X.gne[2 * G + 1] << 32);
+        const bool mine = lane < C && ((gne >> lane) & 1ull) != 0ull;
+        uint32_t carry = 0;                               // non-empty rows of the group below the chunk
+        for (int r0 = 0; r0 < k; r0 += kWave) {
+            const int r = r0 + lane;
+            const bool ne = r < k && ((gne >> X.cls[r < k ? r : 0]) & 1ull) != 0ull;
             const unsigned long long bal = __ballot(ne);
-            const uint32_t before = (uint32_t)__shfl((int)carry, G, kWave) + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-            const uint32_t per = X.gcount[G] / (uint32_t)g;
-            // before < 512 and per <= 512: the quotient of (before + 1/2) / per is at least 1/1024 away from an
-            // integer, far more than the error of the fast division
-            const uint32_t owner = (uint32_t)__fdividef((float)before + 0.5f, (float)(per ? per : 1u));
-            if (r < k) X.sig[r * sgs + G] = ne ? (uint8_t)owner : (uint8_t)0xff;
-            if (lane == G) carry += (uint32_t)__popcll(bal);
+            const uint32_t before = carry + (uint32_t)__popcll(bal & below);
+            const unsigned long long starts = __ballot(ne && before != 0u && small_div(before, per) * per == before);
+            if (mine) {
+                X.bnd[lane * kw + (r0 >> 5)] |= (uint32_t)starts;
+                if ((r0 >> 5) + 1 < kw) X.bnd[lane * kw + (r0 >> 5) + 1] |= (uint32_t)(starts >> 32);
+            }
+            carry += (uint32_t)__popcll(bal);
         }
     }
     __syncthreads();
-    // run starts: a row whose ranks differ from those of the previous row of its class (or that has none)
+    // run starts
     int newC = 0;
-    const uint32_t* const sigw = reinterpret_cast<const uint32_t*>(X.sig);
     for (int r0 = 0; r0 < k; r0 += kWave) {
         const int r = r0 + lane;
         bool st = false;
         if (r < k) {
-            const uint32_t* const mine = X.rows + (int)X.cls[r] * kw;
+            const int c = (int)X.cls[r];
+            const uint32_t* const mine = X.rows + c * kw;
             int w = r >> 5;
             uint32_t m = mine[w] & ((1u << (r & 31)) - 1u);
             while (m == 0u && w > 0) { --w; m = mine[w]; }
-            st = m == 0u;
+            st = m == 0u;                                  // no earlier row in the class
             if (!st) {
-                const int p = w * 32 + 31 - __clz((int)m);
-                for (int i = 0; i < sgs / 4; ++i) st |= sigw[(r * sgs) / 4 + i] != sigw[(p * sgs) / 4 + i];
+                const int p = w * 32 + 31 - __clz((int)m);  // the previous row of the class: a block start in (p, r]?
+                const uint32_t* const b = X.bnd + c * kw;
+                for (int v = p >> 5; v <= (r >> 5); ++v) {
+                    uint32_t x = b[v];
+                    if (v == (p >> 5)) x &= ~(((1u << (p & 31)) << 1) - 1u);
+                    if (v == (r >> 5)) x &= ((1u << (r & 31)) << 1) - 1u;
+                    st |= x != 0u;
+                }
             }
         }
         const unsigned long long bal = __ballot(st);
@@ -956,14 +976,34 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
         if (sr == r) X.crow[id] = (uint32_t)r;
     }
     __syncthreads();
+    // the rank that keeps each new class in each group: that of the class's first row
+    for (int G = 0; G < ng; ++G) {
+        const uint32_t per = X.gcount[G] / (uint32_t)g;
+        if (per == 0u) {
+            for (int c2 = lane; c2 < newC; c2 += kWave) X.own[c2 * ngs + G] = (uint8_t)0xff;
+            continue;
+        }
+        const unsigned long long gne = (unsigned long long)X.gne[2 * G] | ((unsigned long long)X.gne[2 * G + 1] << 32);
+        uint32_t carry = 0;
+        for (int r0 = 0; r0 < k; r0 += kWave) {
+            const int r = r0 + lane;
+            const bool ne = r < k && ((gne >> X.cls[r < k ? r : 0]) & 1ull) != 0ull;
+            const unsigned long long bal = __ballot(ne);
+            const uint32_t before = carry + (uint32_t)__popcll(bal & below);
+            if (r < k && ((X.start[r >> 5] >> (r & 31)) & 1u) != 0u)
+                X.own[(int)X.ncls[r] * ngs + G] = ne ? (uint8_t)small_div(before, per) : (uint8_t)0xff;
+            carry += (uint32_t)__popcll(bal);
+        }
+    }
+    __syncthreads();
     // members: the rank that keeps the class takes the group's combined row, the others are left empty
     for (int it = lane; it < q.R * newC; it += kWave) {
         const int d = it / newC, c2 = it - d * newC;
         if (P.master && (d % s) != 0) continue;
         const int G = P.master ? d / gs : (d / gs) * s + d % s;
         const int p = (d / s) % g;
-        const int r1 = (int)X.crow[c2], oc = (int)X.cls[r1];
-        const bool keep = (int)X.sig[r1 * sgs + G] == p;
+        const int oc = (int)X.cls[X.crow[c2]];
+        const bool keep = (int)X.own[c2 * ngs + G] == p;
 #pragma unroll
         for (int w = 0; w < MW; ++w) X.S[(d * cs + c2) * MW + w] = keep ? X.T[(G * cm + oc) * MW + w] : 0u;
     }
@@ -1100,10 +1140,10 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
 }
 
 // One instruction against the class state, read-only (lit_classify on classes): 0 = invalid step,
-// 2 = valid and the result is the goal, 3 = valid.  full_mask: bit d set iff device d is at the goal.
+// 2 = valid and the result is the goal, 3 = valid.  Needs devany and devfull.
 template <int MW>
 __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int C, const uint32_t* full,
-                            unsigned long long any_mask, unsigned long long full_mask, int lane) {
+                            int lane) {
     const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cs = X.cs;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
     for (int i = lane; i < ng; i += kWave) { X.gcount[i] = 0; X.gflag[i] = 0; }
@@ -1142,7 +1182,7 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
 #pragma unroll
                 for (int w = 0; w < MW; ++w) { const uint32_t v = x[w]; any |= v; acc[w] |= v; }
                 holders += any != 0;
-                if (c == 0) bad |= ((any_mask >> dev) & 1ull) == 0ull;
+                if (c == 0) bad |= X.devany[dev] == 0;
             }
             bad |= holders > 1;
         } else {
@@ -1170,7 +1210,7 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
     if (P.master)
         for (int d = lane; d < q.R; d += kWave) {
             const bool part = d % s == 0 && d / gs < ng;
-            if (!part && ((full_mask >> d) & 1ull) == 0ull) X.flags[2] = 1;
+            if (!part && !X.devfull[d]) X.flags[2] = 1;
         }
     __syncthreads();
     for (int G = lane; G < ng; G += kWave) {
@@ -1189,6 +1229,29 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
     return invalid ? 0 : goal ? 2 : 3;
 }
 
+// Per device: holds anything (devany), is at the goal (devfull); and over all devices: every row is held
+// everywhere, every held row is complete, device 0 is at the goal.
+template <int MW>
+__device__ inline void cls_device_flags(const DevQuery& q, const ClsLds& X, int C, const uint32_t* full, int lane,
+                                        bool& rows_full, bool& cols_full, bool& root_done) {
+    bool rows_bad = false, cols_bad = false;
+    for (int d = lane; d < q.R; d += kWave) {
+        bool any = false, all = true;
+        for (int c = 0; c < C; ++c) {
+            const uint32_t* x = X.S + (d * X.cs + c) * MW;
+            bool ne = false, fl = true;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) { ne |= x[w] != 0u; fl &= x[w] == full[w]; }
+            rows_bad |= !ne; cols_bad |= ne && !fl; all &= fl; any |= ne;
+        }
+        X.devany[d] = any; X.devfull[d] = all;
+    }
+    rows_full = !__any(rows_bad);
+    cols_full = !__any(cols_bad);
+    __syncthreads();
+    root_done = X.devfull[0] != 0u;
+}
+
 // The last instructions a = part, part + parts, ... of a group against the class state; those that are valid
 // and reach the goal are reported.  Only the goal matters here (the candidates' steps are counted by the
 // caller), and the goal can only come from an AllReduce on devices that all hold every row, from an AllGather
@@ -1199,25 +1262,14 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
 template <int MW>
 __device__ inline void cls_judge_all(const DevQuery& q, unsigned long long first, const ClsLds& X, int C, const uint32_t* full,
                                      int lane, int part, int parts) {
-    bool rows_ok = true, cols_ok = true, full_ok = true, any = false;      // lane d looks at device d
-    if (lane < q.R)
-        for (int c = 0; c < C; ++c) {
-            const uint32_t* x = X.S + (lane * X.cs + c) * MW;
-            bool ne = false, fl = true;
-#pragma unroll
-            for (int w = 0; w < MW; ++w) { ne |= x[w] != 0u; fl &= x[w] == full[w]; }
-            rows_ok &= ne; cols_ok &= !ne || fl; full_ok &= fl; any |= ne;
-        }
-    const bool in = lane < q.R;
-    const bool rows_full = !__any(in && !rows_ok), cols_full = !__any(in && !cols_ok);
-    const unsigned long long any_mask = __ballot(in && any), full_mask = __ballot(in && full_ok);
-    const bool root_done = (full_mask & 1ull) != 0ull;
+    bool rows_full, cols_full, root_done;
+    cls_device_flags<MW>(q, X, C, full, lane, rows_full, cols_full, root_done);
     if (!(rows_full || cols_full || root_done)) return;
     for (int a = part; a < q.alphabet; a += parts) {
         const uint32_t ins = q.instr_of_digit[a];
         const int op = (int)(ins & 7u);
         if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
-        if (cls_classify<MW>(q, q.pat[ins >> 3], op, X, C, full, any_mask, full_mask, lane) == 2 && lane == 0) {
+        if (cls_classify<MW>(q, q.pat[ins >> 3], op, X, C, full, lane) == 2 && lane == 0) {
             const uint32_t pos = atomicAdd(&q.counters->n_valid, 1u);
             if (pos < q.valid_cap) q.valid_idx[pos] = first + (unsigned long long)a;
         }
