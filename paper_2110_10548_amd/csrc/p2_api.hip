@@ -650,12 +650,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                              static_cast<const uint32_t*>(C.f_states[cur].p), n_c,
                                              static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, dctr, stream));
                 if (n_l > 0) {
-                    gs = nullptr;
-                    if (front_literal_lds_bytes(pl.R, pl.k) == 0) {
-                        unsigned nb = 0;
-                        P2_HIP(C.lit_scratch.ensure(literal_scratch_bytes(pl.R, pl.k, &nb)));
-                        gs = C.lit_scratch.p;
-                    }
+                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, n_l)));
+                    gs = C.lit_scratch.p;
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, stream));
                 }

@@ -233,6 +233,7 @@ struct FrontCounters {
     uint32_t n_goal, n_prefix, n_prefix_literal;
     uint32_t next_compact, next_literal;    // entries written to the next frontiers
     uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
+    uint32_t n_overflow, pad3;     // literal prefixes left to the full-state kernel
     // running totals of the query
     uint32_t valid_written, pad2;
     unsigned long long steps, members;
@@ -242,6 +243,8 @@ hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, Fr
                              hipStream_t stream);
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
                                  uint32_t n, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr, hipStream_t stream);
+// Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
+size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
                                          void* gscratch, hipStream_t stream);

@@ -614,50 +614,6 @@ __device__ inline int row_classes(const DevQuery& q, const LitLds& L, const Fron
     return C;
 }
 
-template <int MW>
-__global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery* __restrict__ qp,
-                                                                  const FrontEntry* __restrict__ entries, uint32_t n_entries,
-                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
-                                                                  uint32_t surv_cap, FrontCounters* __restrict__ ctr,
-                                                                  uint32_t* __restrict__ gscratch, unsigned long long gwords) {
-    extern __shared__ uint32_t lds[];
-    const DevQuery& q = *qp;
-    const int lane = threadIdx.x;
-    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
-    const FrontLit X = carve_front(L.flags + 4, q.k);
-    const int R = q.R, I = q.alphabet;
-    uint32_t full[MW];
-#pragma unroll
-    for (int w = 0; w < MW; ++w) {
-        const int bits = R - 32 * w;
-        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
-    }
-    unsigned long long steps = 0, members = 0;
-    for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
-        const unsigned long long digits = entries[e].digits;
-        lit_init<MW>(q, L, lane);
-        for (int t = 0; t < parent_len; ++t) {
-            const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
-            lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
-        }
-        const int C = row_classes<MW>(q, L, X, full, lane);
-        for (int a = 0; a < I; ++a) {
-            const uint32_t ins = q.instr_of_digit[a];
-            const DevPattern& P = q.pat[ins >> 3];
-            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
-            ++steps;
-            members += (unsigned long long)(P.n_groups * P.g);
-            if (code != 0 && lane == 0) {
-                const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
-                if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
-                atomicAdd(code == 2 ? &ctr->n_goal : &ctr->n_prefix_literal, 1u);
-            }
-        }
-        __syncthreads();
-    }
-    if (lane == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
-}
-
 // ---- groups handed over by the shared-prefix engine ------------------------------------------------
 // A list entry is the index of a group's first candidate: `alphabet` consecutive candidates with the
 // same first len-1 instructions, whose common state the compact form could not hold.  The literal
@@ -809,20 +765,27 @@ struct ClsLds {
                         // read the same class of different devices hit different banks); bytes per class in own
 };
 __host__ __device__ inline int cls_cmax(int k) { return k < 64 ? k : 64; }
-__host__ __device__ inline int cls_words(int R, int k, int MW) {
-    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1, ngs = (ng + 3) & ~3, kh = (k + 1) / 2, kw = (k + 31) / 32;
-    return R * (cm | 1) * MW + ng * cm * MW + 3 * cm + 4 * ng + 3 * R + 4 + 16 + 2 * kh + 2 * cm * kw + (cm * ngs) / 4 + 8;
+// Words of the masks (S and T) and of the tables beside them.
+__host__ __device__ inline int cls_mask_words(int R, int k, int MW) {
+    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1;
+    return R * (cm | 1) * MW + ng * cm * MW;
 }
+__host__ __device__ inline int cls_table_words(int R, int k) {
+    const int cm = cls_cmax(k), ng = R / 2 > 0 ? R / 2 : 1, ngs = (ng + 3) & ~3, kh = (k + 1) / 2, kw = (k + 31) / 32;
+    return 3 * cm + 4 * ng + 3 * R + 4 + 16 + 2 * kh + 2 * cm * kw + (cm * ngs) / 4 + 8;
+}
+__host__ __device__ inline int cls_words(int R, int k, int MW) { return cls_mask_words(R, k, MW) + cls_table_words(R, k); }
 // Words of a stem's saved class state: S, the classes of the rows, the class sizes.
 __host__ __device__ inline int cls_backup_words(int R, int k, int MW) { return R * cls_cmax(k) * MW + (k + 1) / 2 + cls_cmax(k) + 8; }
-__device__ inline ClsLds carve_cls(uint32_t* p, int R, int k, int MW) {
+// masks: cls_mask_words words for S and T; p: cls_table_words words for the rest (may follow the masks).
+__device__ inline ClsLds carve_cls(uint32_t* masks, uint32_t* p, int R, int k, int MW) {
     ClsLds X;
     X.cm = cls_cmax(k);
     const int ng = R / 2 > 0 ? R / 2 : 1, kh = (k + 1) / 2, kw = (k + 31) / 32;
     X.ngs = (ng + 3) & ~3;
     X.cs = X.cm | 1;
-    X.S = p; p += R * X.cs * MW;
-    X.T = p; p += ng * X.cm * MW;
+    X.S = masks;
+    X.T = masks + R * X.cs * MW;
     X.csize = p; p += X.cm;
     X.ncsize = p; p += X.cm;
     X.crow = p; p += X.cm;
@@ -1276,6 +1239,111 @@ __device__ inline void cls_judge_all(const DevQuery& q, unsigned long long first
     }
 }
 
+// Frontier level for literal prefixes, on the full literal state: a block rebuilds the state of one
+// prefix and classifies every instruction against it.  With elist, only the entries elist[0 .. *elist_n).
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery* __restrict__ qp,
+                                                                  const FrontEntry* __restrict__ entries, uint32_t n_entries,
+                                                                  const uint32_t* __restrict__ elist,
+                                                                  const uint32_t* __restrict__ elist_n,
+                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
+                                                                  uint32_t surv_cap, FrontCounters* __restrict__ ctr,
+                                                                  uint32_t* __restrict__ gscratch, unsigned long long gwords) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    const LitLds L = carve(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds, q.R, q.k, MW);
+    const FrontLit X = carve_front(L.flags + 4, q.k);
+    const int R = q.R, I = q.alphabet;
+    uint32_t full[MW];
+#pragma unroll
+    for (int w = 0; w < MW; ++w) {
+        const int bits = R - 32 * w;
+        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+    }
+    unsigned long long steps = 0, members = 0;
+    const uint32_t n = elist ? *elist_n : n_entries;
+    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        const uint32_t e = elist ? elist[i] : i;
+        const unsigned long long digits = entries[e].digits;
+        lit_init<MW>(q, L, lane);
+        for (int t = 0; t < parent_len; ++t) {
+            const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
+            lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
+        }
+        const int C = row_classes<MW>(q, L, X, full, lane);
+        for (int a = 0; a < I; ++a) {
+            const uint32_t ins = q.instr_of_digit[a];
+            const DevPattern& P = q.pat[ins >> 3];
+            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
+            ++steps;
+            members += (unsigned long long)(P.n_groups * P.g);
+            if (code != 0 && lane == 0) {
+                const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
+                if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
+                atomicAdd(code == 2 ? &ctr->n_goal : &ctr->n_prefix_literal, 1u);
+            }
+        }
+        __syncthreads();
+    }
+    if (lane == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
+}
+
+// The same on the class state (in LDS, or in the block's slice of a global buffer where it does not fit): a
+// prefix is rebuilt at the cost of its classes instead of its k rows.  A prefix that needs more classes than
+// the state holds is put on the list `over` (ctr->n_overflow entries) for the kernel above.
+template <int MW>
+__global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery* __restrict__ qp,
+                                                                  const FrontEntry* __restrict__ entries, uint32_t n_entries,
+                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
+                                                                  uint32_t surv_cap, FrontCounters* __restrict__ ctr,
+                                                                  uint32_t* __restrict__ over, uint32_t* __restrict__ gscratch,
+                                                                  unsigned long long gwords, int class_cap) {
+    extern __shared__ uint32_t lds[];
+    const DevQuery& q = *qp;
+    const int lane = threadIdx.x;
+    // the tables are always in LDS; the masks follow them there, or are in the block's global slice
+    ClsLds X = carve_cls(gscratch ? gscratch + (size_t)blockIdx.x * gwords : lds + cls_table_words(q.R, q.k), lds, q.R, q.k, MW);
+    X.cm = X.cm < class_cap ? X.cm : class_cap;
+    const int R = q.R, I = q.alphabet;
+    uint32_t full[MW];
+#pragma unroll
+    for (int w = 0; w < MW; ++w) {
+        const int bits = R - 32 * w;
+        full[w] = bits >= 32 ? 0xffffffffu : bits > 0 ? ((1u << bits) - 1u) : 0u;
+    }
+    unsigned long long steps = 0, members = 0;
+    for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
+        const unsigned long long digits = entries[e].digits;
+        int C = 1, rc = CSTEP_OK;
+        cls_init<MW>(q, X, C, lane);
+        for (int t = 0; t < parent_len && rc == CSTEP_OK; ++t) {
+            const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
+            rc = cls_step<MW>(q, q.pat[ins >> 3], (int)(ins & 7u), X, C, lane);
+        }
+        if (rc != CSTEP_OK) {                    // too many classes: the full literal state decides
+            if (lane == 0) over[atomicAdd(&ctr->n_overflow, 1u)] = e;
+            continue;
+        }
+        bool rows_full, cols_full, root_done;
+        cls_device_flags<MW>(q, X, C, full, lane, rows_full, cols_full, root_done);
+        for (int a = 0; a < I; ++a) {
+            const uint32_t ins = q.instr_of_digit[a];
+            const DevPattern& P = q.pat[ins >> 3];
+            const int code = cls_classify<MW>(q, P, (int)(ins & 7u), X, C, full, lane);
+            ++steps;
+            members += (unsigned long long)(P.n_groups * P.g);
+            if (code != 0 && lane == 0) {
+                const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
+                if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
+                atomicAdd(code == 2 ? &ctr->n_goal : &ctr->n_prefix_literal, 1u);
+            }
+        }
+        __syncthreads();
+    }
+    if (lane == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
+}
+
 // literal_group on the class state.  Returns false, with nothing counted or reported, when a step needs more
 // classes than the state holds.
 template <int MW>
@@ -1473,7 +1541,7 @@ __global__ __launch_bounds__(kWave) void k_eval_literal_groups_auto(const DevQue
         const DevQuery& q = queries[qlist[owner]];
         const LitLds L = carve(mem, q.R, q.k, MW);
         const FrontLit X = carve_front(L.flags + 4, q.k);
-        ClsLds Y = carve_cls(lds, q.R, q.k, MW);
+        ClsLds Y = carve_cls(lds, lds + cls_mask_words(q.R, q.k, MW), q.R, q.k, MW);
         Y.cm = Y.cm < class_cap ? Y.cm : class_cap;
         uint32_t full[MW];
 #pragma unroll
@@ -1661,25 +1729,70 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
     return hipGetLastError();
 }
 
+// The state of the class kernels holds up to 64 classes of rows; entries that would need more are evaluated
+// on the full literal state.  P2_ROW_CLASSES (1..63) lowers the limit, so that tests can send entries down
+// that path.
+static int row_class_cap() {
+    if (const char* env = std::getenv("P2_ROW_CLASSES")) {
+        const int v = std::atoi(env);
+        if (v >= 1 && v < 64) return v;
+    }
+    return 64;
+}
+
+// Scratch of launch_front_classify_literal: the slices of the full-state kernel (where that state does not
+// fit in LDS), the slices of the class kernel (likewise), the list of the entries left to the former.
+namespace {
+struct FrontLiteralScratch {
+    size_t full_lds = 0, full_bytes = 0, cls_lds = 0, cls_bytes = 0, cls_per = 0, total = 0;
+    unsigned full_blocks = 16384, cls_blocks = 16384;
+};
+FrontLiteralScratch front_literal_scratch(int R, int k, uint32_t n) {
+    FrontLiteralScratch p;
+    p.full_lds = front_literal_lds_bytes(R, k);
+    if (p.full_lds == 0) p.full_bytes = literal_scratch_bytes(R, k, &p.full_blocks);
+    const size_t cw = (size_t)cls_words(R, k, mask_words(R)) * 4;
+    if (cw <= kLdsLimit) p.cls_lds = cw;
+    else {
+        // the tables stay in LDS, the masks go to global slices
+        p.cls_lds = (size_t)cls_table_words(R, k) * 4;
+        p.cls_per = ((size_t)cls_mask_words(R, k, mask_words(R)) * 4 + 255) / 256 * 256;
+        p.cls_blocks = 2048;
+        while (p.cls_blocks > 1 && p.cls_per * p.cls_blocks > ((size_t)8 << 30)) p.cls_blocks >>= 1;
+        p.cls_bytes = p.cls_per * p.cls_blocks;
+    }
+    p.total = p.full_bytes + p.cls_bytes + ((size_t)n * 4 + 255) / 256 * 256;
+    return p;
+}
+}  // namespace
+
+size_t front_literal_scratch_bytes(int R, int k, uint32_t n) { return front_literal_scratch(R, k, n).total; }
+
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
                                          void* gscratch, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    size_t lds = front_literal_lds_bytes(R, k);
-    unsigned blocks = n < 16384u ? n : 16384u;
-    unsigned long long gwords = 0;
-    if (lds == 0) {
-        if (!gscratch) return hipErrorInvalidValue;
-        unsigned nb = 0;
-        gwords = literal_scratch_bytes(R, k, &nb) / nb / 4;
-        blocks = nb < n ? nb : n;
-    } else gscratch = nullptr;
+    if (!gscratch) return hipErrorInvalidValue;
+    const FrontLiteralScratch sc = front_literal_scratch(R, k, n);
+    char* const base = static_cast<char*>(gscratch);
+    uint32_t* const full_mem = sc.full_lds ? nullptr : reinterpret_cast<uint32_t*>(base);
+    uint32_t* const cls_mem = sc.cls_bytes ? reinterpret_cast<uint32_t*>(base + sc.full_bytes) : nullptr;
+    uint32_t* const over = reinterpret_cast<uint32_t*>(base + sc.full_bytes + sc.cls_bytes);
+    const unsigned cls_blocks = sc.cls_blocks < n ? sc.cls_blocks : n, full_blocks = sc.full_blocks < n ? sc.full_blocks : n;
+    const unsigned long long cls_words_per = sc.cls_per / 4;
+    const unsigned long long full_words_per = sc.full_lds ? 0ull : sc.full_bytes / sc.full_blocks / 4;
+    const int class_cap = row_class_cap();
     hipError_t e = hipSuccess;
+    // first on the class state; what needs more classes than that holds, on the full literal state
 #define P2_LAUNCH(MWV)                                                                                         \
-    e = allow_big_lds(k_front_classify_literal<MWV>, lds);                                                     \
+    e = allow_big_lds(k_front_classify_classes<MWV>, sc.cls_lds);                                              \
     if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(blocks), dim3(kWave), lds, stream, q, entries, n, \
-                           parent_len, surv, surv_cap, ctr, static_cast<uint32_t*>(gscratch), gwords);
+        hipLaunchKernelGGL(k_front_classify_classes<MWV>, dim3(cls_blocks), dim3(kWave), sc.cls_lds, stream, q, entries, n, \
+                           parent_len, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap);          \
+    if (e == hipSuccess) e = allow_big_lds(k_front_classify_literal<MWV>, sc.full_lds);                        \
+    if (e == hipSuccess)                                                                                       \
+        hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(full_blocks), dim3(kWave), sc.full_lds, stream, q, entries, n, \
+                           over, &ctr->n_overflow, parent_len, surv, surv_cap, ctr, full_mem, full_words_per);
     switch (mask_words(R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
@@ -1713,14 +1826,8 @@ hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_
     unsigned blocks = 0;
     const unsigned long long gwords = literal_group_scratch_bytes(max_R, max_k, &blocks) / blocks / 4;
     const int cls_backup = cls_backup_words(max_R, max_k, mask_words(max_R));
-    // The state holds up to 64 classes of rows, which is all that power-of-two groups can produce; entries
-    // that would need more are evaluated on the full literal state.  P2_HANDOVER_CLASSES (1..64) lowers the
-    // limit, so that tests can send entries down that path.
-    int class_cap = 64;
-    if (const char* env = std::getenv("P2_HANDOVER_CLASSES")) {
-        const int v = std::atoi(env);
-        if (v >= 1 && v < 64) class_cap = v;
-    }
+    // (64 classes are all that power-of-two groups can produce)
+    const int class_cap = row_class_cap();
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \

@@ -500,14 +500,14 @@ def test_handed_over_groups_beyond_the_class_limit(B, oracle, classes, monkeypat
     needs more classes than the state holds falls back to the full literal state.  With power-of-two groups
     the real limit (64) is never reached, so the limit is lowered here: stems and groups then take the
     fallback at the first ReduceScatter (limit 1) or at a later one (limit 3), and the results stay the same."""
-    monkeypatch.setenv("P2_HANDOVER_CLASSES", classes)
+    monkeypatch.setenv("P2_ROW_CLASSES", classes)
     cfg, queries = queries_of(2, B)
     cfg3 = workloads.config(3)
     pl3 = B.p2_enumerate_placements(cfg3["card"], cfg3["axes"])
     q3 = [dict(q, max_len=4) for q in workloads.expand(cfg3, pl3) if q["reduce_axes"] == [1, 2]][:2]   # 32 devices, 64 chunks
     batch = [dict(q, engine=5) for q in queries + q3]
     limited = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
-    monkeypatch.delenv("P2_HANDOVER_CLASSES")
+    monkeypatch.delenv("P2_ROW_CLASSES")
     usual = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
     handed = 0
     for q, res, ref in zip(batch, limited, usual):
