@@ -702,6 +702,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     size_t total_valid = 0;
     for (auto& r : runs) { r.out_first = total_valid; total_valid += r.n_valid; }
     const size_t nm = (size_t)std::max(n_msg, 1);
+    // rows the caller gets; without room for them (the sizing call with cap = 0) only the counts are returned,
+    // and nothing is ordered, costed or selected
+    int64_t need = 0;
+    for (auto& r : runs) need += r.topk > 0 ? (int64_t)n_msg * (int64_t)std::min<size_t>(r.topk, r.n_valid) : (int64_t)r.n_valid;
+    const bool store = cap >= need && cap > 0;
+    size_t pos_off = 0;
+    if (store) {
     P2_HIP(C.sorted.ensure(sizeof(unsigned long long) * std::max<size_t>(total_valid, 1)));
     P2_HIP(C.progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
     P2_HIP(C.costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
@@ -713,7 +720,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
     P2_HIP(C.topk_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
     P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
-    size_t pos_off = 0;
     int post_launches = 0;
     std::vector<DevTopkJob> topk_jobs;
     int topk_jobs_k = 0;
@@ -826,29 +832,28 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     if (topk_rows > 0)
         P2_HIP(launch_copy_out(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
     P2_HIP(hipStreamSynchronize(stream));
+    }  // store
 
     if (g_prof.on) {
         P2_HIP(hipEventElapsedTime(&g_prof.last.eval_ms, g_prof.ev[0], g_prof.ev[1]));
-        P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[1], g_prof.ev[2]));
+        g_prof.last.post_ms = 0.0f;
+        if (store) P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[1], g_prof.ev[2]));
     }
     // ---- hand the results over
     const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);
     const double* hcst = static_cast<const double*>(C.h_costs.p);
     const long long* hpos = static_cast<const long long*>(C.h_pos.p);
-    int64_t need = 0;
-    for (auto& r : runs) need += r.topk > 0 ? (int64_t)n_msg * (int64_t)std::min<size_t>(r.topk, r.n_valid) : (int64_t)r.n_valid;
     int64_t w = 0;
     pos_off = 0;
-    const bool store = cap >= need && cap > 0;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         out_offset[i] = w;
         if (r.topk > 0) {
             const size_t kk = std::min<size_t>(r.topk, r.n_valid);
-            for (int m = 0; m < n_msg; ++m)
+            if (!store) w += (int64_t)n_msg * (int64_t)kk;
+            for (int m = 0; m < n_msg && store; ++m)
                 for (size_t t = 0; t < kk; ++t, ++w) {
                     const long long pos = hpos[pos_off++];
-                    if (!store) continue;
                     if (pos < 0 || pos >= (long long)r.n_valid) return fail(P2_EDEVICE, "top-k returned a bad position");
                     out_prog[w] = hp[r.out_first + pos];
                     for (int c = 0; c < n_msg; ++c) out_cost[w * n_msg + c] = hcst[(r.out_first + pos) * nm + c];
