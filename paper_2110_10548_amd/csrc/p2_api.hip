@@ -747,7 +747,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     r.out_first);
     }
     for (auto& L : ccost_launches) {      // a block of the compact cost kernel takes as many entries as it has lanes
-        const uint32_t lanes = (uint32_t)compact_lanes(L.max_R, L.max_k);
+        // (one, with the lanes sharing the work, where only a few states fit in LDS)
+        const uint32_t lanes = cost_wide_applies(L.max_R, L.max_k) ? 1u : (uint32_t)compact_lanes(L.max_R, L.max_k);
         L.blocks = 0;
         for (auto& sg : L.segs) { sg.per_block = lanes; sg.first_block = L.blocks; L.blocks += (sg.count + lanes - 1) / lanes; }
     }
@@ -763,8 +764,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
     for (auto& L : ccost_launches) {
         ++post_launches;
-        P2_HIP(launch_cost_compact_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
-                                        L.max_k, sorted_base, progs_base, costs_base, stream));
+        if (cost_wide_applies(L.max_R, L.max_k))
+            P2_HIP(launch_cost_wide_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
+                                         L.max_k, sorted_base, progs_base, costs_base, stream));
+        else
+            P2_HIP(launch_cost_compact_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
+                                            L.max_k, sorted_base, progs_base, costs_base, stream));
     }
     for (auto& L : scost_launches) {
         ++post_launches;

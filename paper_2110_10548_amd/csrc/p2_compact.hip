@@ -178,6 +178,169 @@ __global__ __launch_bounds__(kWave) void k_cost_compact(const DevQuery* __restri
         out_cost[i * q.n_msg + m] = ok ? sum_alpha + q.msg_bytes[m] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
 }
 
+// Cost of valid programs whose state is too large for more than a few candidates per wavefront in LDS
+// (hundreds of devices): one wavefront per program, the 64 lanes share every step.  State: [R][KW + MW]
+// words in LDS (chunk set, contribution mask of each device).  A step is two passes.  Pass 1, one item per
+// (group, word): fold the word over the members, check the premises that can be seen in one word, leave the
+// result in the first member's slot (the united mask of an AllReduce-like step, the united chunk set of an
+// AllGather) and add the word's share to the number of chunks that sets the group's bytes.  Pass 2, one
+// item per (member, word), or per member for ReduceScatter: take the result from the first member.  The
+// rules and the cost terms are those of step_mixed; a program whose state leaves this form gets NaN costs
+// (the literal cost kernel fills those rows).
+template <int KW, int MW>
+__global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict__ queries,
+                                                     const DevPostSeg* __restrict__ segs, int n_segs,
+                                                     const unsigned long long* __restrict__ sorted,
+                                                     p2_program* __restrict__ out_prog, double* __restrict__ out_cost) {
+    extern __shared__ uint32_t lds[];
+    constexpr int WPD = KW + MW;
+    const DevPostSeg seg = find_post_seg(segs, n_segs, blockIdx.x);
+    const DevQuery& q = queries[seg.query];
+    const int lane = threadIdx.x, R = q.R;
+    uint32_t* const S = lds;                       // [R][WPD]
+    uint32_t* const gcount = S + R * WPD;          // [R / 2] chunks that set a group's bytes
+    uint32_t* const gflag = gcount + (R / 2 > 0 ? R / 2 : 1);   // [R / 2] Broadcast: some member differs from the root
+    uint32_t* const flags = gflag + (R / 2 > 0 ? R / 2 : 1);    // 0: premise failed, 1: something changes, 2: leaves the form
+    const size_t i = seg.out_off + (blockIdx.x - seg.first_block);
+    const unsigned long long idx = sorted[i];
+    int len = 1;
+    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
+    uint32_t digit[P2_MAX_LEN];
+    {
+        unsigned long long rem = idx - q.base[len];
+        const unsigned long long I = (unsigned long long)q.alphabet;
+        for (int t = P2_MAX_LEN - 1; t >= 0; --t) {
+            if (t < len) { const unsigned long long nx = rem / I; digit[t] = (uint32_t)(rem - nx * I); rem = nx; }
+            else digit[t] = 0;
+        }
+    }
+    // Sec. 3.5: device i holds column i in every row
+    const Words<KW> all_rows = full_mask<KW>(q.k);
+    for (int it = lane; it < R * WPD; it += kWave) {
+        const int d = it / WPD, w = it - d * WPD;
+        S[it] = w < KW ? all_rows.w[w] : ((w - KW) == (d >> 5) ? (1u << (d & 31)) : 0u);
+    }
+    __syncthreads();
+    double sum_alpha = 0.0, sum_beta = 0.0;
+    bool ok = true;
+    p2_program pr;
+    pr.index = idx;
+    pr.len = (uint8_t)len;
+    for (int t = 0; t < P2_MAX_LEN; ++t) pr.instr[t] = 0;
+    for (int t = 0; t < len; ++t) {
+        const uint32_t ins = q.instr_of_digit[digit[t]];
+        const int pid = (int)(ins >> 3), op = (int)(ins & 7u);
+        pr.instr[t] = (uint8_t)(pid * 5 + op);
+        if (!ok) continue;
+        const DevPattern& P = q.pat[pid];
+        const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+        const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
+        for (int G = lane; G < ng; G += kWave) { gcount[G] = 0; gflag[G] = 0; }
+        if (lane == 0) { flags[0] = 0; flags[1] = 0; flags[2] = 0; }
+        __syncthreads();
+        bool bad = false, leaves = false;
+        if (op == OP_AG) {
+            // nobody empty
+            for (int j = lane; j < ng * g; j += kWave) {
+                const int G = j / g, p = j - G * g;
+                const int d = (P.master ? G * gs : (G / s) * gs + (G % s)) + p * s;
+                uint32_t any = 0;
+#pragma unroll
+                for (int w = 0; w < KW; ++w) any |= S[d * WPD + w];
+                bad |= any == 0u;
+            }
+        }
+        // ---- pass 1
+        for (int it = lane; it < ng * WPD; it += kWave) {
+            const int G = it / WPD, w = it - G * WPD;
+            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            const uint32_t first = S[base * WPD + w];
+            uint32_t acc = first, dif = 0, over = 0, sub = 0;
+            for (int p = 1; p < g; ++p) {
+                const uint32_t v = S[(base + p * s) * WPD + w];
+                dif |= v ^ first; over |= v & acc; sub |= v & ~first;
+                acc |= v;
+            }
+            if (red) {
+                if (w < KW) { bad |= dif != 0u; atomicAdd(&gcount[G], (uint32_t)__popc(first)); }   // same chunks on every member
+                else { bad |= over != 0u; S[base * WPD + w] = acc; }                                // no contribution reduced twice
+            } else if (op == OP_AG) {
+                if (w < KW) { bad |= over != 0u; S[base * WPD + w] = acc; atomicAdd(&gcount[G], (uint32_t)__popc(acc)); }   // chunks held once
+                else leaves |= dif != 0u;                  // rows with different column sets: not this form
+            } else {
+                bad |= sub != 0u;                          // the root knows what every member knows
+                if (dif != 0u) gflag[G] = 1;
+                if (w < KW) atomicAdd(&gcount[G], (uint32_t)__popc(first));
+            }
+        }
+        if (bad) flags[0] = 1;
+        if (leaves) flags[2] = 1;
+        __syncthreads();
+        for (int G = lane; G < ng; G += kWave) {
+            const uint32_t cnt = gcount[G];
+            if (red) {
+                if (op == OP_RS && cnt % (uint32_t)g != 0u) flags[0] = 1;   // chunks must divide evenly
+                if (cnt) flags[1] = 1;                                     // a group of empty devices is a no-op
+            } else {
+                if (op == OP_BC && !gflag[G]) flags[0] = 1;                // information increase
+                flags[1] = 1;
+            }
+        }
+        __syncthreads();
+        if (flags[0] || !flags[1] || flags[2]) { ok = false; continue; }   // (valid programs only fail by leaving the form)
+        // ---- ring alpha-beta time of the step
+        {
+            double best = 0.0;
+            const DevRows& rw = *q.rows;
+            for (int row = rw.pat_begin[pid] + lane; row < rw.pat_begin[pid + 1]; row += kWave) {
+                long long dot = 0;
+                for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                    const uint32_t ent = rw.entries[e];
+                    dot += (long long)entry_cnt(ent) * (long long)gcount[entry_group(ent)];
+                }
+                best = fmax(best, (double)dot * q.inv_bw[rw.row_level[row]]);
+            }
+            for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, kWave));
+            double ring_steps, mult;
+            step_factors(op, g, q.algo, ring_steps, mult);
+            sum_alpha += ring_steps * q.alpha[P.span_level];
+            sum_beta += (mult / (double)q.k) * best;
+        }
+        // ---- pass 2
+        if (op == OP_RS) {
+            // the member of rank p keeps the p-th block of its chunks in ascending order (all members hold the same)
+            for (int j = lane; j < ng * g; j += kWave) {
+                const int G = j / g, p = j - G * g;
+                const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+                const int d = base + p * s;
+                Words<KW> r;
+#pragma unroll
+                for (int w = 0; w < KW; ++w) r.w[w] = S[d * WPD + w];
+                const int per = (int)(gcount[G] / (uint32_t)g);
+                const Words<KW> upto = lowest_n(r, (p + 1) * per), below = lowest_n(r, p * per);
+#pragma unroll
+                for (int w = 0; w < KW; ++w) S[d * WPD + w] = upto.w[w] & ~below.w[w];
+                if (p != 0) {
+#pragma unroll
+                    for (int w = 0; w < MW; ++w) S[d * WPD + KW + w] = S[base * WPD + KW + w];
+                }
+            }
+        } else {
+            const int w0 = (op == OP_AR) ? KW : 0, w1 = (op == OP_AG) ? KW : WPD, nw = w1 - w0;
+            for (int it = lane; it < ng * (g - 1) * nw; it += kWave) {
+                const int j = it / nw, w = w0 + (it - j * nw);
+                const int G = j / (g - 1), p = 1 + (j - G * (g - 1));
+                const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+                S[(base + p * s) * WPD + w] = op == OP_RD ? 0u : S[base * WPD + w];
+            }
+        }
+        __syncthreads();
+    }
+    if (lane == 0) out_prog[i] = pr;
+    if (lane < q.n_msg)
+        out_cost[i * q.n_msg + lane] = ok ? sum_alpha + q.msg_bytes[lane] * sum_beta : __longlong_as_double(0x7ff8000000000000ll);
+}
+
 inline int round_words(int bits) {
     const int w = (bits + 31) / 32;
     return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16;
@@ -268,6 +431,41 @@ hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* s
     case 8: return cost_mw<8>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
     default: return cost_mw<16>(MW, queries, segs, n_segs, sorted, progs, costs, blocks, LS, lds, stream);
     }
+}
+
+bool cost_wide_applies(int max_R, int max_k) { return max_R > 64 && compact_lanes(max_R, max_k) <= 8; }
+
+hipError_t launch_cost_wide_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                 int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                 double* costs, hipStream_t stream) {
+    if (n_segs == 0 || blocks == 0) return hipSuccess;
+    const int KW = round_words(max_k), MW = round_words(max_R);
+    const size_t lds = ((size_t)max_R * (size_t)(KW + MW) + (size_t)max_R + 8) * 4;
+    hipError_t e = hipSuccess;
+#define P2_GO(KWV, MWV)                                                                                                   \
+    e = allow_lds(k_cost_wide<KWV, MWV>, lds);                                                                            \
+    if (e == hipSuccess) hipLaunchKernelGGL((k_cost_wide<KWV, MWV>), dim3(blocks), dim3(kWave), lds, stream, queries, segs, n_segs, sorted, progs, costs);
+    // (more than 64 devices)
+    switch (KW * 100 + MW) {
+    case 104: P2_GO(1, 4) break;
+    case 204: P2_GO(2, 4) break;
+    case 404: P2_GO(4, 4) break;
+    case 804: P2_GO(8, 4) break;
+    case 1604: P2_GO(16, 4) break;
+    case 108: P2_GO(1, 8) break;
+    case 208: P2_GO(2, 8) break;
+    case 408: P2_GO(4, 8) break;
+    case 808: P2_GO(8, 8) break;
+    case 1608: P2_GO(16, 8) break;
+    case 116: P2_GO(1, 16) break;
+    case 216: P2_GO(2, 16) break;
+    case 416: P2_GO(4, 16) break;
+    case 816: P2_GO(8, 16) break;
+    case 1616: P2_GO(16, 16) break;
+    default: return hipErrorInvalidValue;
+    }
+#undef P2_GO
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 }  // namespace p2

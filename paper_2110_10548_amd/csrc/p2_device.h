@@ -204,6 +204,11 @@ size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks);
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
                                            void* gscratch, hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.
+// The same for states of which only a few fit in LDS (cost_wide_applies): one wavefront per program.
+bool cost_wide_applies(int max_R, int max_k);
+hipError_t launch_cost_wide_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
+                                 int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                 double* costs, hipStream_t stream);
 hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
                                     int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
                                     double* costs, hipStream_t stream);
