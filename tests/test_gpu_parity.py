@@ -519,6 +519,23 @@ def test_handed_over_groups_beyond_the_class_limit(B, oracle, classes, monkeypat
     assert handed > 0
 
 
+@pytest.mark.parametrize("card,axes,k,algo", [([2, 8, 8], [128], 512, 0), ([3, 8, 8], [192], 384, 1), ([4, 8, 8], [256], 256, 0),
+                                              ([2, 4, 8, 8], [2, 256], 256, 0)])
+def test_costs_of_large_reduction_groups(B, oracle, card, axes, k, algo):
+    """Reduction groups of 128 to 256 devices (one of them not a power of two) with many chunks: only a few such
+    states fit in LDS beside each other, so their programs are costed one per wavefront (k_cost_wide), every
+    collective and form among them; lists and costs against the oracle."""
+    links = dict(bw=[12.5e9, 50e9, 150e9, 300e9][:len(card)], alpha=[2e-5, 1e-5, 5e-6, 2e-6][:len(card)])
+    msg = [2.0 ** 20, 2.0 ** 30]
+    x = [list(card)] if len(axes) == 1 else [[2, 1, 1, 1], [1, 4, 8, 8]]
+    q = dict(card=card, axes=axes, placement=x, reduce_axes=[len(axes) - 1], max_len=3, n_chunks=k, algo=algo, engine=2, **links)
+    res = B.p2_synthesize_batch([q], msg)[0]
+    _, ora = oracle_result(oracle, q, msg)
+    assert_same(res, ora, len(msg))
+    ops = {int(v) % 5 for p in res["programs"] for v in p["instr"][:p["len"]]}
+    assert ops == {0, 1, 2, 3, 4} and len(res["programs"]) > 20
+
+
 def test_config3_compact_engine_matches_default(B, oracle):
     """The default engine on configuration 3 is the shared-prefix engine (64 devices, power-of-two levels);
     the LDS-resident compact engine, which evaluates every candidate in a lane of its own, gives the same
