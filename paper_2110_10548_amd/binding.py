@@ -206,7 +206,10 @@ class Batch:
         self.n_msg = len(self._msg)
         self._offs = np.zeros(self.nq + 1, dtype=np.int64)
         self._stats = (p2_stats * self.nq)()
-        self._alloc(0)
+        # with a shortlist asked for in every query the number of rows is bounded beforehand, and the
+        # first call has room for them; otherwise a first call without room returns the counts
+        topks = [int(q.get("topk", 0)) for q in queries]
+        self._alloc(sum(topks) * self.n_msg if all(t > 0 for t in topks) and self.n_msg > 0 else 0)
 
     def _alloc(self, cap):
         self.cap = cap
