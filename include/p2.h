@@ -23,6 +23,8 @@
  *  - Two-call sizing: a call with cap = 0 (and NULL outputs) only writes the
  *    required count.  If cap is too small the call returns P2_ENOSPC, the
  *    required count is still written and the output contents are unspecified.
+ *    Such a call evaluates the candidates (the counts and the stats come from
+ *    that) but does not order, cost or select anything.
  *  - Arrays over hardware levels are outermost level first.
  */
 #ifndef P2_H
