@@ -125,6 +125,61 @@ __device__ __forceinline__ int wave_step(Words<KW>& rv, Words<MW>& mv, int dev, 
     return (~flags & roots) != 0ull ? WSTEP_INVALID : WSTEP_OK;
 }
 
+// The last instruction of a candidate matters only through the goal, and only three kinds of last
+// instruction can reach it; each is judged by what is left of its rule on the states that allow it.
+//
+// AllReduce on a state whose devices all hold every chunk: the goal is reached iff in every group the masks
+// are pairwise disjoint and unite to all columns, and the devices outside the pattern are complete already
+// (the members hold the same chunks, so only masks travel).
+template <int MW>
+__device__ __forceinline__ bool judge_allreduce(Words<MW> mv, int dev, int lg, int ls, unsigned long long part, int R,
+                                                const Words<MW>& all_cols) {
+    const bool in = ((part >> dev) & 1ull) != 0ull;
+    bool bad = false;
+    for (int J = ls; J < ls + lg; ++J) {
+        const Words<MW> pm = exchange(mv, 1 << J);
+        bad |= in && fold_and(mv, pm) != 0u;
+        if (in) unite(mv, pm);
+    }
+    bad |= dev < R && fold_xor(mv, all_cols) != 0u;
+    return !__any(bad);
+}
+// AllGather on a state whose devices all carry every column: the goal is reached iff no member is empty, in
+// every group the chunk sets are pairwise disjoint and unite to all chunks, and the devices outside the
+// pattern hold every chunk already (the masks are equal, so only chunk sets travel).
+template <int KW>
+__device__ __forceinline__ bool judge_allgather(Words<KW> rv, int dev, int lg, int ls, unsigned long long part, int R,
+                                                const Words<KW>& all_rows) {
+    const bool in = ((part >> dev) & 1ull) != 0ull;
+    bool bad = in && fold_or(rv) == 0u;
+    for (int J = ls; J < ls + lg; ++J) {
+        const Words<KW> pr = exchange(rv, 1 << J);
+        bad |= in && fold_and(rv, pr) != 0u;
+        if (in) unite(rv, pr);
+    }
+    bad |= dev < R && fold_xor(rv, all_rows) != 0u;
+    return !__any(bad);
+}
+// Broadcast: every member ends with its root's pair, so the goal is reached iff every root is complete, every
+// group has a member that is not (the information increase the rule asks for; a complete root knows what any
+// member knows), and the devices outside the pattern are complete.  complete: bit d set iff device d < R holds
+// every chunk with every column.
+__device__ __forceinline__ bool judge_broadcast(unsigned long long complete, int lg, int ls, unsigned long long part, int R) {
+    const unsigned long long devices = R >= 64 ? ~0ull : ((1ull << R) - 1ull);
+    // the roots: participating devices whose number has all group bits clear
+    unsigned long long roots = part & devices;
+    for (int J = ls; J < ls + lg; ++J) {
+        const unsigned long long bit_clear = J == 0 ? 0x5555555555555555ull : J == 1 ? 0x3333333333333333ull
+                                           : J == 2 ? 0x0f0f0f0f0f0f0f0full : J == 3 ? 0x00ff00ff00ff00ffull
+                                           : J == 4 ? 0x0000ffff0000ffffull : 0x00000000ffffffffull;
+        roots &= bit_clear;
+    }
+    if ((roots & ~complete) != 0ull || (devices & ~part & ~complete) != 0ull) return false;
+    unsigned long long flags = part & devices & ~complete;  // members that are not complete, folded onto their roots
+    for (int J = ls; J < ls + lg; ++J) flags |= flags >> (1u << J);
+    return (roots & ~flags) == 0ull;
+}
+
 // The first instruction of a program, on the init state of Sec. 3.5 (every device holds every chunk,
 // device i column i): what the rules give there is known without an exchange.  Members of a group hold
 // the same chunks and disjoint columns, so the AllReduce-like rules apply (ReduceScatter if the group
@@ -330,7 +385,8 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 const uint32_t rows_off = fold_xor(rv, all_rows), cols_off = fold_xor(mv, all_cols);
                 const bool rows_full = !__any(dev < R && rows_off != 0u);
                 const bool cols_full = !__any(dev < R && cols_off != 0u);
-                const bool root_done = (uint32_t)__builtin_amdgcn_readfirstlane((int)(rows_off | cols_off)) == 0u;   // lane 0 is device 0
+                const unsigned long long complete = __ballot(dev < R && (rows_off | cols_off) == 0u) & (R >= 64 ? ~0ull : ((1ull << R) - 1ull));
+                const bool root_done = (complete & 1ull) != 0ull;                                 // lane 0 is device 0
                 if (rows_full || cols_full || root_done) {
                     for (uint32_t a0 = 0; a0 < I; a0 += kWave) {
                         const uint32_t a = a0 + (uint32_t)lane;
@@ -342,12 +398,13 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                             const int l = __ffsll((long long)left) - 1;
                             const uint32_t ins0 = sdig[a0 + (uint32_t)l];
                             const uint32_t shape = sshape[ins0 >> 3];
-                            Words<KW> r2 = rv;
-                            Words<MW> m2 = mv;
+                            const int op2 = (int)(ins0 & 7u), lg2 = (int)(shape & 15u), ls2 = (int)((shape >> 4) & 15u);
                             ++evaluated; evaluated_members += shape >> 16;
-                            const int rc2 = wave_step<KW, MW>(r2, m2, dev, (int)(ins0 & 7u), (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
                             // goal: every device holds every chunk with the columns of the whole group
-                            const bool reached = rc2 == WSTEP_OK && !__any(dev < R && (fold_xor(r2, all_rows) | fold_xor(m2, all_cols)) != 0u);
+                            bool reached;
+                            if (op2 == OP_AR) reached = judge_allreduce<MW>(mv, dev, lg2, ls2, spart[ins0 >> 3], R, all_cols);
+                            else if (op2 == OP_AG) reached = judge_allgather<KW>(rv, dev, lg2, ls2, spart[ins0 >> 3], R, all_rows);
+                            else reached = judge_broadcast(complete, lg2, ls2, spart[ins0 >> 3], R);
                             if (lane == l) goal = reached;
                         }
                         if (goal) {
