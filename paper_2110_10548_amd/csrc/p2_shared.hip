@@ -24,6 +24,8 @@
 // reach the goal.
 #include "p2_compact_dev.h"
 
+#include <type_traits>
+
 namespace p2 {
 
 namespace {
@@ -267,22 +269,54 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
     const Words<MW> all_cols = full_mask<MW>(R);
     const uint32_t sum_part = q.reg_sum_part;           // participating devices summed over the alphabet
     __syncthreads();
-    int cur = -1;                                       // segment of the current item
     DevSegment seg;
-    seg.first_block = 0; seg.query = sh.query; seg.len = 1; seg.iters = 1; seg.first_index = 0; seg.count = 0;
-    uint32_t next_first = 0;                            // first item of the next segment
     int len = 1;
     uint32_t items_log = 0;                             // a stem is cut into 2^items_log items of seg.iters groups
     unsigned long long steps = 0, members = 0, evaluated = 0, evaluated_members = 0;   // wave-uniform totals of this block
     const uint32_t end_item = sh.first_item + sh.n_items;
-    for (uint32_t item = sh.first_item + (blockIdx.x - sh.first_block); item < end_item; item += sh.n_blocks) {
-        if (item >= next_first) {
-            while (cur + 1 < sh.n_segs && sseg[cur + 1].first_block <= item) ++cur;
-            seg = sseg[cur];
-            next_first = cur + 1 < sh.n_segs ? sseg[cur + 1].first_block : 0xffffffffu;
-            len = seg.len;
-            items_log = len >= 2 ? (uint32_t)sh.cut_log : 0u;
-        }
+    const uint32_t blk = blockIdx.x - sh.first_block;
+    uint32_t turn = 0;                                  // units of the earlier segments, modulo the share's blocks
+    // The blocks of a share take the units of its segments in turn.  A unit is one item, or, where an item is
+    // a whole stem of at least three instructions, the `alphabet` stems that differ in their last instruction
+    // only: their common part is worked out once per unit, and a unit whose common part is invalid is
+    // settled as a whole.
+    for (int sgi = 0; sgi < sh.n_segs; ++sgi) {
+    seg = sseg[sgi];
+    const uint32_t seg_end = sgi + 1 < sh.n_segs ? sseg[sgi + 1].first_block : end_item;
+    len = seg.len;
+    items_log = len >= 2 ? (uint32_t)sh.cut_log : 0u;
+    const bool runs = items_log == 0u && len >= 5;
+    // (a run of `alphabet` stems is cut into parts where the share would otherwise have fewer than about 32
+    // units per block: long units balance badly)
+    const uint32_t seg_items = seg_end - seg.first_block;
+    uint32_t parts = 1;
+    if (runs) {
+        const uint32_t n_runs = seg_items / I;
+        while (parts < I && n_runs * parts < 32u * sh.n_blocks) parts *= 2u;
+        if (parts > I) parts = I;
+    }
+    const uint32_t ulen = runs ? (I + parts - 1u) / parts : 1u;             // stems of a unit
+    const uint32_t n_units = runs ? (seg_items / I) * parts : seg_items;
+    const uint32_t u0 = (blk + sh.n_blocks - turn) % sh.n_blocks;
+    turn = (turn + n_units % sh.n_blocks) % sh.n_blocks;
+    // one unit; kRuns: its stems share all but their last instruction
+    auto do_unit = [&](auto runs_c, const uint32_t u) {
+    constexpr bool kRuns = decltype(runs_c)::value;
+    // the state after the unit's common instructions (the first len-3 of the stem), once it is known
+    bool have_common = false;
+    Words<KW> p_rv = all_rows;
+    Words<MW> p_mv = all_cols;
+    uint32_t p_ran = 0, p_visited = 0;
+    int p_rc = WSTEP_OK;
+    uint32_t item0 = seg.first_block + u, unit = 1u;
+    if (kRuns) {
+        const uint32_t run = u / parts, piece = u - run * parts;
+        const uint32_t lo = piece * ulen, hi = lo + ulen < I ? lo + ulen : I;
+        item0 = seg.first_block + run * I + lo;
+        unit = hi > lo ? hi - lo : 0u;
+    }
+    for (uint32_t ju = 0; ju < unit; ++ju) {
+        const uint32_t item = item0 + ju;
         // the item's stem (number S, instruction t at digit dg[t], t < len-2) and its groups: the prefix's
         // last instruction runs over the digits dlast0 .. dlast0 + n_here - 1
         const uint32_t rel = item - seg.first_block;
@@ -290,6 +324,13 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
         const uint32_t dlast0 = (rel - (S << items_log)) * (uint32_t)seg.iters;
         if (len >= 2 && dlast0 >= I) continue;           // the stem has fewer groups than items: nothing here
         const uint32_t n_here = len >= 2 ? (I - dlast0 < (uint32_t)seg.iters ? I - dlast0 : (uint32_t)seg.iters) : 1u;
+        if (kRuns && have_common && p_rc == WSTEP_INVALID) {
+            // the common part is invalid: every candidate of the unit's remaining stems stops inside it
+            const unsigned long long rest = (unsigned long long)(unit - ju) * (unsigned long long)(n_here * I);
+            steps += rest * p_ran;
+            members += rest * p_visited;
+            break;
+        }
         uint32_t dg[P2_MAX_LEN];
         {
             uint32_t rem = S;
@@ -311,9 +352,10 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
         for (int i = 0; i < MW; ++i) c_mv.w[i] = (i == (dev >> 5)) ? (1u << (dev & 31)) : 0u;
         uint32_t c_ran = 0, c_visited = 0;
         int c_rc = WSTEP_OK;
+        if (kRuns && have_common) { c_rv = p_rv; c_mv = p_mv; c_ran = p_ran; c_visited = p_visited; c_rc = p_rc; }
 #pragma unroll
         for (int t = 0; t < P2_MAX_LEN - 2; ++t) {
-            if (t < len - 2 && c_rc == WSTEP_OK) {
+            if (t < len - 2 && c_rc == WSTEP_OK && !(kRuns && have_common && t < len - 3)) {
                 const uint32_t ins0 = sdig[dg[t]];
                 const uint32_t shape = sshape[ins0 >> 3];
                 ++c_ran;
@@ -323,7 +365,12 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
                 if (t == 0) c_rc = first_wave_step<KW, MW>(c_rv, c_mv, dev, op0, (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], q.k);
                 else c_rc = wave_step<KW, MW>(c_rv, c_mv, dev, op0, (int)(shape & 15u), (int)((shape >> 4) & 15u), spart[ins0 >> 3], devs);
             }
+            if (kRuns && !have_common && t == len - 4) {
+                // (the common part of the unit's stems ends here)
+                p_rv = c_rv; p_mv = c_mv; p_ran = c_ran; p_visited = c_visited; p_rc = c_rc;
+            }
         }
+        if (kRuns) have_common = true;
         if (c_rc == WSTEP_INVALID) {
             // every candidate of the item stops inside the stem
             steps += (unsigned long long)(n_here * I) * c_ran;
@@ -417,6 +464,12 @@ __global__ __launch_bounds__(kWave) void k_eval_shared(const DevQuery* __restric
         }
         steps += item_steps;
         members += item_members;
+    }
+    };
+    for (uint32_t u = u0; u < n_units; u += sh.n_blocks) {
+        if (runs) do_unit(std::true_type{}, u);
+        else do_unit(std::false_type{}, u);
+    }
     }
     if (lane == 0 && (steps | evaluated) != 0ull) {
         atomicAdd(&qp->counters->steps[blockIdx.x % kCounterStripes], steps);
