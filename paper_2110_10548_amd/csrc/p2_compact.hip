@@ -22,6 +22,8 @@
 // rule-specific parts as selects, so lanes with different rules and group shapes stay together.
 #include "p2_compact_dev.h"
 
+#include <type_traits>
+
 namespace p2 {
 
 namespace {
@@ -235,6 +237,11 @@ __global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict_
         const DevPattern& P = q.pat[pid];
         const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
         const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
+        auto first_of = [&](int G) -> int {               // first device of group G
+            if (P.master) return G * gs;
+            const int hi = div_small(G, s);
+            return hi * gs + (G - hi * s);
+        };
         for (int G = lane; G < ng; G += kWave) { gcount[G] = 0; gflag[G] = 0; }
         if (lane == 0) { flags[0] = 0; flags[1] = 0; flags[2] = 0; }
         __syncthreads();
@@ -242,8 +249,8 @@ __global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict_
         if (op == OP_AG) {
             // nobody empty
             for (int j = lane; j < ng * g; j += kWave) {
-                const int G = j / g, p = j - G * g;
-                const int d = (P.master ? G * gs : (G / s) * gs + (G % s)) + p * s;
+                const int G = div_small(j, g), p = j - G * g;
+                const int d = first_of(G) + p * s;
                 uint32_t any = 0;
 #pragma unroll
                 for (int w = 0; w < KW; ++w) any |= S[d * WPD + w];
@@ -253,7 +260,7 @@ __global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict_
         // ---- pass 1
         for (int it = lane; it < ng * WPD; it += kWave) {
             const int G = it / WPD, w = it - G * WPD;
-            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            const int base = first_of(G);
             const uint32_t first = S[base * WPD + w];
             uint32_t acc = first, dif = 0, over = 0, sub = 0;
             for (int p = 1; p < g; ++p) {
@@ -310,13 +317,13 @@ __global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict_
         if (op == OP_RS) {
             // the member of rank p keeps the p-th block of its chunks in ascending order (all members hold the same)
             for (int j = lane; j < ng * g; j += kWave) {
-                const int G = j / g, p = j - G * g;
-                const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+                const int G = div_small(j, g), p = j - G * g;
+                const int base = first_of(G);
                 const int d = base + p * s;
                 Words<KW> r;
 #pragma unroll
                 for (int w = 0; w < KW; ++w) r.w[w] = S[d * WPD + w];
-                const int per = (int)(gcount[G] / (uint32_t)g);
+                const int per = div_small((int)gcount[G], g);
                 const Words<KW> upto = lowest_n(r, (p + 1) * per), below = lowest_n(r, p * per);
 #pragma unroll
                 for (int w = 0; w < KW; ++w) S[d * WPD + w] = upto.w[w] & ~below.w[w];
@@ -326,13 +333,20 @@ __global__ __launch_bounds__(kWave) void k_cost_wide(const DevQuery* __restrict_
                 }
             }
         } else {
-            const int w0 = (op == OP_AR) ? KW : 0, w1 = (op == OP_AG) ? KW : WPD, nw = w1 - w0;
-            for (int it = lane; it < ng * (g - 1) * nw; it += kWave) {
-                const int j = it / nw, w = w0 + (it - j * nw);
-                const int G = j / (g - 1), p = 1 + (j - G * (g - 1));
-                const int base = P.master ? G * gs : (G / s) * gs + (G % s);
-                S[(base + p * s) * WPD + w] = op == OP_RD ? 0u : S[base * WPD + w];
-            }
+            // (a division by a constant is a multiplication; group and member numbers stay below 512, where
+            // div_small is exact)
+            auto copy_words = [&](auto w0_c, auto nw_c) {
+                constexpr int w0 = decltype(w0_c)::value, nw = decltype(nw_c)::value;
+                for (int it = lane; it < ng * (g - 1) * nw; it += kWave) {
+                    const int j = it / nw, w = w0 + (it - j * nw);
+                    const int G = div_small(j, g - 1), p = 1 + (j - G * (g - 1));
+                    const int base = first_of(G);
+                    S[(base + p * s) * WPD + w] = op == OP_RD ? 0u : S[base * WPD + w];
+                }
+            };
+            if (op == OP_AR) copy_words(std::integral_constant<int, KW>{}, std::integral_constant<int, MW>{});
+            else if (op == OP_AG) copy_words(std::integral_constant<int, 0>{}, std::integral_constant<int, KW>{});
+            else copy_words(std::integral_constant<int, 0>{}, std::integral_constant<int, WPD>{});
         }
         __syncthreads();
     }
