@@ -13,6 +13,20 @@ namespace p2 {
 namespace {
 
 constexpr int kWave = 64;
+
+// v / d for 0 <= v < 2^22 and 1 <= d <= 2^15: a float quotient (off by one at most), then one correction.
+__device__ __forceinline__ int div_fast(int v, int d) {
+    int q = (int)__fdividef((float)v + 0.5f, (float)d);
+    const int r = v - q * d;
+    q += r >= d ? 1 : r < 0 ? -1 : 0;
+    return q;
+}
+// First device of group G of a pattern with stride s and gs = g * s.
+__device__ __forceinline__ int group_base(int master, int G, int s, int gs) {
+    if (master) return G * gs;
+    const int hi = div_fast(G, s);
+    return hi * gs + (G - hi * s);
+}
 constexpr size_t kLdsLimit = 160 * 1024 - 512;
 
 struct LitLayout {
@@ -84,8 +98,8 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
     const int items = ng * k;
     bool bad = false;
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / k, r = it - G * k;
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int G = div_fast(it, k), r = it - G * k;
+        const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) acc[w] = 0;
@@ -155,7 +169,7 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
             if (op == OP_RS && cnt % (uint32_t)g != 0) L.flags[0] = 1;   // scatter: chunks must divide evenly
             if (cnt) L.flags[1] = 1;                                    // a group of empty devices is a no-op
         } else if (op == OP_AG) {
-            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            const int base = group_base(P.master, G, s, gs);
             for (int p = 0; p < g; ++p)
                 if (!L.devne[base + p * s]) L.flags[0] = 1;
             L.flags[1] = 1;
@@ -189,8 +203,8 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
     // write the members' new rows (block p of a ReduceScatter goes to the member of rank p)
     const int32_t* rank = P.rank_off ? q.rank_tbl + (P.rank_off - 1) : nullptr;
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / k, r = it - G * k;
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int G = div_fast(it, k), r = it - G * k;
+        const int base = group_base(P.master, G, s, gs);
         uint32_t t[MW];
         uint32_t any = 0;
 #pragma unroll
@@ -474,9 +488,9 @@ __device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, cons
     const int items = ng * C;
     bool bad = false, notfull = false;
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / C, c = it - G * C;
+        const int G = div_fast(it, C), c = it - G * C;
         const int r = (int)X.reps[c];
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) acc[w] = 0;
@@ -1011,8 +1025,8 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
     const int items = ng * C;
     bool bad = false;
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / C, c = it - G * C;
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int G = div_fast(it, C), c = it - G * C;
+        const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) acc[w] = 0;
@@ -1073,7 +1087,7 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
             if (op == OP_RS && cnt % (uint32_t)g != 0) X.flags[0] = 1;   // scatter: chunks must divide evenly
             if (cnt) X.flags[1] = 1;                                    // a group of empty devices is a no-op
         } else if (op == OP_AG) {
-            const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+            const int base = group_base(P.master, G, s, gs);
             for (int p = 0; p < g; ++p)
                 if (!X.devne[base + p * s]) X.flags[0] = 1;
             X.flags[1] = 1;
@@ -1086,8 +1100,8 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
     if (X.flags[0] || !X.flags[1]) return CSTEP_INVALID;
     if (op == OP_RS) return cls_scatter<MW>(q, P, X, C, lane);
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / C, c = it - G * C;
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int G = div_fast(it, C), c = it - G * C;
+        const int base = group_base(P.master, G, s, gs);
         uint32_t t[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) t[w] = X.T[(G * cm + c) * MW + w];
@@ -1115,8 +1129,8 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
     const int items = ng * C;
     bool bad = false, notfull = false;
     for (int it = lane; it < items; it += kWave) {
-        const int G = it / C, c = it - G * C;
-        const int base = P.master ? G * gs : (G / s) * gs + (G % s);
+        const int G = div_fast(it, C), c = it - G * C;
+        const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
 #pragma unroll
         for (int w = 0; w < MW; ++w) acc[w] = 0;
