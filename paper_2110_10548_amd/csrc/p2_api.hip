@@ -829,13 +829,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
     P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
     P2_HIP(C.h_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
-    if (total_valid > 0) {
-        P2_HIP(launch_copy_out(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid, stream));
-        if (n_msg > 0)
-            P2_HIP(launch_copy_out(C.h_costs.p, C.costs.p, sizeof(double) * total_valid * nm, stream));
-    }
-    if (topk_rows > 0)
-        P2_HIP(launch_copy_out(C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    P2_HIP(launch_copy_out3(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid,
+                            C.h_costs.p, C.costs.p, n_msg > 0 ? sizeof(double) * total_valid * nm : 0,
+                            C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
     P2_HIP(hipStreamSynchronize(stream));
     }  // store
 

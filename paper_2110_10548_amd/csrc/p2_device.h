@@ -281,6 +281,9 @@ hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, 
 // memory to pinned, device-accessible host memory.  Used instead of hipMemcpyAsync, whose queueing of a
 // device-to-host copy was seen to take 0.1 ms longer in some processes (never in others).
 hipError_t launch_copy_out(void* dst_host, const void* src_dev, size_t bytes, hipStream_t stream);
+// Up to three of them in one launch (bytes may be 0).
+hipError_t launch_copy_out3(void* dst0, const void* src0, size_t bytes0, void* dst1, const void* src1, size_t bytes1,
+                            void* dst2, const void* src2, size_t bytes2, hipStream_t stream);
 
 // Top-k of (cost[i * stride], index[i]) over i < n: positions into out_pos[min(k, n)].
 // scratch: device buffer of topk_scratch_bytes(n, k) bytes.  nan_flag: device uint32 set to 1 on NaN.

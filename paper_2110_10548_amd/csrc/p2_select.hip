@@ -181,6 +181,17 @@ __global__ __launch_bounds__(256) void k_copy_out(uint4* __restrict__ dst, const
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Up to three such copies in one launch (a call's programs, costs and shortlist positions).
+struct CopyOut { uint4* dst; const uint4* src; size_t n16; };
+__global__ __launch_bounds__(256) void k_copy_out3(CopyOut a, CopyOut b, CopyOut c) {
+    const size_t ab = a.n16 + b.n16, total = ab + c.n16;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        if (i < a.n16) a.dst[i] = a.src[i];
+        else if (i < ab) b.dst[i - a.n16] = b.src[i - a.n16];
+        else c.dst[i - ab] = c.src[i - ab];
+    }
+}
+
 inline unsigned topk_blocks(long long n) {
     long long b = (n + 64 * 16 - 1) / (64 * 16);      // at least 16 tiles per block
     if (b < 1) b = 1;
@@ -197,6 +208,19 @@ hipError_t launch_copy_out(void* dst_host, const void* src_dev, size_t bytes, hi
     const unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
     hipLaunchKernelGGL(k_copy_out, dim3(blocks), dim3(256), 0, stream, static_cast<uint4*>(dst_host),
                        static_cast<const uint4*>(src_dev), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_out3(void* dst0, const void* src0, size_t bytes0, void* dst1, const void* src1, size_t bytes1,
+                            void* dst2, const void* src2, size_t bytes2, hipStream_t stream) {
+    const CopyOut a{static_cast<uint4*>(dst0), static_cast<const uint4*>(src0), (bytes0 + 15) / 16};
+    const CopyOut b{static_cast<uint4*>(dst1), static_cast<const uint4*>(src1), (bytes1 + 15) / 16};
+    const CopyOut c{static_cast<uint4*>(dst2), static_cast<const uint4*>(src2), (bytes2 + 15) / 16};
+    const size_t n16 = a.n16 + b.n16 + c.n16;
+    if (n16 == 0) return hipSuccess;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL(k_copy_out3, dim3(blocks), dim3(256), 0, stream, a, b, c);
     return hipGetLastError();
 }
 
