@@ -281,6 +281,25 @@ def test_other_synthesis_hierarchies(B, oracle, kind):
         assert e.value.code == B.P2_EUNSUPPORTED
 
 
+def test_random_queries_other_hierarchies(B, oracle):
+    """Seeded random small systems under every other hierarchy of Sec. 3.4, with the random grammar masks, chunk
+    counts and cost models of the generator: lists and costs against the oracle."""
+    msg = [float(1 << 22), 3.0e8]
+    n = 0
+    for q in workloads.random_queries(77, 40, max_devices=32):
+        for kind in KINDS:
+            probe = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], form_mask=q["form_mask"],
+                                 op_mask=q["op_mask"], hierarchy=kind)
+            max_len = 1
+            while max_len < 4 and probe.alphabet > 0 and probe.num_candidates(max_len + 1) <= 60_000:
+                max_len += 1
+            qk = dict(q, max_len=max_len, hierarchy=kind)
+            _, ora = oracle_result(oracle, qk, msg, form_mask=q["form_mask"], op_mask=q["op_mask"])
+            assert_same(B.p2_synthesize_batch([qk], msg)[0], ora, len(msg))
+            n += len(ora["index"])
+    assert n > 1000
+
+
 def _lowered_programs(B, q, res):
     """Programs as sequences of (device groups on the full system, collective)."""
     groups = {}
