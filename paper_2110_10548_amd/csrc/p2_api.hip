@@ -2,8 +2,11 @@
 // copy-back.  All arithmetic of the method runs in the kernels; this file only moves data.
 #include <algorithm>
 #include <chrono>
+#include <cstdlib>
 #include <cstddef>
 #include <cstring>
+#include <atomic>
+#include <thread>
 #include <limits>
 #include <string>
 #include <vector>
@@ -120,6 +123,8 @@ struct QueryRun {
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
     size_t off_goal = 0, off_rank = 0;    // hierarchies other than the collapsed one: goal masks, ranks of members
+    int same_as = -1;                     // an earlier query of the batch with the same reduction group, chunks, patterns,
+                                          // alphabet and size limit: its valid programs are this query's too
     uint32_t valid_cap = 0, rerun_cap = 0;
     size_t off_valid = 0, off_rerun = 0;  // element offsets into the valid / rerun buffers
     uint32_t n_valid = 0, n_rerun = 0, n_rerun_groups = 0;
@@ -195,6 +200,34 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (const Pattern& p : pl.patterns) runs[i].wave_cost = runs[i].wave_cost && reg_shape_of(p.g, p.s, p.master, 6) >= 0;
     }
 
+    // Validity depends on the reduction group, the chunks, the patterns and the alphabet only (not on the
+    // links, nor on where the placement puts the group in the system): a query that equals an earlier one of
+    // the batch in these is not evaluated again; it takes over the list of valid programs and the counts, and
+    // only its costs are worked out, from its own bandwidth rows.  (The frontier engine does the same further
+    // down.)  P2_EVALUATE_EVERY_QUERY=1 in the environment switches this off.
+    {
+        const char* every = std::getenv("P2_EVALUATE_EVERY_QUERY");
+        const bool share_validity = !(every && every[0] == '1');
+        for (int i = 0; i < n_queries && share_validity; ++i) {
+            QueryRun& r = runs[i];
+            const Plan& pl = r.plan;
+            if (r.frontier || pl.hierarchy != P2_HIERARCHY_COLLAPSED || pl.n_candidates == 0) continue;
+            for (int j = 0; j < i && r.same_as < 0; ++j) {
+                const QueryRun& c = runs[j];
+                const Plan& o = c.plan;
+                if (c.same_as >= 0 || c.frontier || o.hierarchy != P2_HIERARCHY_COLLAPSED || c.engine != r.engine || c.shared != r.shared ||
+                    c.regs != r.regs || o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet ||
+                    o.n_ops != pl.n_ops || o.patterns.size() != pl.patterns.size() || o.n_candidates != pl.n_candidates)
+                    continue;
+                bool eq = true;
+                for (int t = 0; t < pl.n_ops && eq; ++t) eq = o.ops[t] == pl.ops[t];
+                for (size_t t = 0; t < pl.patterns.size() && eq; ++t)
+                    eq = o.patterns[t].g == pl.patterns[t].g && o.patterns[t].s == pl.patterns[t].s &&
+                         o.patterns[t].master == pl.patterns[t].master && o.patterns[t].n_groups == pl.patterns[t].n_groups;
+                if (eq) r.same_as = j;
+            }
+        }
+    }
     g_prof.last.host_plan_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     // ---- lay out the table blob: queries, message sizes, bandwidth rows
     size_t off = 0;
@@ -209,7 +242,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     std::vector<Launch> launches;
     auto word_class = [](int bits) { int w = (bits + 31) / 32; return w <= 1 ? 1 : w <= 2 ? 2 : w <= 4 ? 4 : w <= 8 ? 8 : 16; };
     for (int i = 0; i < n_queries; ++i) {
-        if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].plan.n_candidates == 0) continue;
+        if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].same_as >= 0 || runs[i].plan.n_candidates == 0) continue;
         const Plan& pl = runs[i].plan;
         const int kind = runs[i].shared ? 2 : runs[i].regs ? 1 : 0;
         const int kw = kind == 1 ? 1 : word_class(pl.k), mw = kind == 1 ? 1 : word_class(pl.R);
@@ -223,7 +256,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     unsigned long long shared_stems = 0;
     for (int i = 0; i < n_queries; ++i) {
         const Plan& pl = runs[i].plan;
-        if (!runs[i].shared || runs[i].frontier || pl.n_candidates == 0 || pl.alphabet == 0) continue;
+        if (!runs[i].shared || runs[i].frontier || runs[i].same_as >= 0 || pl.n_candidates == 0 || pl.alphabet == 0) continue;
         for (int len = 2; len <= pl.max_len; ++len)
             shared_stems += (pl.base[len + 1] - pl.base[len]) / ((unsigned long long)pl.alphabet * (unsigned long long)pl.alphabet);
     }
@@ -234,7 +267,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         unsigned long long blocks = 0;
         for (int i = 0; i < n_queries; ++i) {
             const Plan& pl = runs[i].plan;
-            if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || pl.n_candidates == 0) continue;
+            if (runs[i].engine != P2_ENGINE_COMPACT || runs[i].frontier || runs[i].same_as >= 0 || pl.n_candidates == 0) continue;
             const int kind = runs[i].shared ? 2 : runs[i].regs ? 1 : 0;
             if (kind != L.kind || (kind == 1 ? 1 : word_class(pl.k)) != L.kw || (kind == 1 ? 1 : word_class(pl.R)) != L.mw) continue;
             for (int len = 1; len <= pl.max_len; ++len) {
@@ -292,7 +325,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     std::vector<AutoGroups> autos;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
-        if (!r.shared || r.frontier || r.plan.n_candidates == 0) continue;
+        if (!r.shared || r.frontier || r.same_as >= 0 || r.plan.n_candidates == 0) continue;
         const int mw = r.plan.R <= 32 ? 1 : 2;
         const int cls = mw;
         AutoGroups* A = nullptr;
@@ -329,8 +362,22 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     auto build_and_upload_rows = [&]() -> int32_t {
         if (rows_ready) return P2_OK;
         size_t bytes = 0;
+        if (n_msg > 0) {                                      // without message sizes the tables stay empty
+            // (large batches: the queries' tables are independent, a few host threads share them)
+            const unsigned hw = std::thread::hardware_concurrency();
+            const int n_threads = n_queries >= 32 ? (int)std::min<unsigned>(std::max(hw, 1u), 8u) : 1;
+            if (n_threads <= 1) {
+                for (auto& r : runs) build_cost_tables(r.plan);
+            } else {
+                std::atomic<int> next{0};
+                auto work = [&]() { for (int i = next.fetch_add(1); i < n_queries; i = next.fetch_add(1)) build_cost_tables(runs[i].plan); };
+                std::vector<std::thread> pool;
+                for (int t = 1; t < n_threads; ++t) pool.emplace_back(work);
+                work();
+                for (auto& th : pool) th.join();
+            }
+        }
         for (auto& r : runs) {
-            if (n_msg > 0) build_cost_tables(r.plan);         // without message sizes the tables stay empty
             size_t n_rows = 0, n_ent = 0;
             for (const Pattern& p : r.plan.patterns) { n_rows += p.row_level.size(); n_ent += p.entries.size(); }
             r.off_rowptr = bytes; bytes += align_up(sizeof(int32_t) * (n_rows + 1), 16);
@@ -386,8 +433,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     };
     for (auto& r : runs) {
         const unsigned long long N = r.plan.n_candidates;
-        r.valid_cap = r.frontier ? 0u : (uint32_t)std::min<unsigned long long>(N, 1u << 15);
-        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT && !r.frontier) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
+        r.valid_cap = (r.frontier || r.same_as >= 0) ? 0u : (uint32_t)std::min<unsigned long long>(N, 1u << 15);
+        r.rerun_cap = (r.engine == P2_ENGINE_COMPACT && !r.frontier && r.same_as < 0) ? (uint32_t)std::min<unsigned long long>(N, 1u << 10) : 0u;
     }
 
     // global state buffer for literal evaluations whose state does not fit in LDS
@@ -524,7 +571,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (int i = 0; i < n_queries; ++i) {
             QueryRun& r = runs[i];
             const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
-            if (r.engine == P2_ENGINE_LITERAL && r.plan.n_candidates > 0) {
+            if (r.engine == P2_ENGINE_LITERAL && r.same_as < 0 && r.plan.n_candidates > 0) {
                 ++eval_launches;
                 void* gs = nullptr;
                 P2_HIP(lit_scratch(r.plan, &gs));
@@ -581,6 +628,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (int t = 0; t < kCounterStripes; ++t) { r.steps += hc[i].steps[t]; r.members += hc[i].members[t]; }
             r.evaluated = 0; r.evaluated_members = 0;
             for (int t = 0; t < kCounterStripes; ++t) { r.evaluated += hc[i].evaluated[t]; r.evaluated_members += hc[i].evaluated_members[t]; }
+            if (r.same_as >= 0) {                       // (the earlier query's figures; nothing was carried out for this one)
+                const QueryRun& o = runs[r.same_as];
+                r.n_valid = o.n_valid; r.n_rerun = o.n_rerun; r.n_rerun_groups = o.n_rerun_groups;
+                r.steps = o.steps; r.members = o.members; r.off_valid = o.off_valid;
+                continue;
+            }
             if (r.n_valid > r.valid_cap || r.n_rerun > r.rerun_cap) {
                 again = true;
                 r.valid_cap = std::max(r.valid_cap, r.n_valid);
