@@ -11,6 +11,9 @@ against the chip's 32-bit integer VALU rate (a small fraction: the kernel is bou
 bookkeeping and dependent lane exchanges, not by arithmetic), and `per_candidate_engine` reports
 the engine that evaluates every candidate on its own, lane by lane, with its own roofline
 fraction.  `cpu_baseline` times the plain CPU oracle on a bounded sample of the same candidates.
+Queries of the batch whose reduction group, chunks, patterns, alphabet and size limit are equal are
+evaluated once by the library (their costs stay their own): `config.queries_evaluated` says how many
+were, and `every_query_evaluated` times the same batch with that switched off.
 """
 import argparse
 import hashlib
@@ -211,6 +214,20 @@ def main():
                      "per_candidate_lane_ops_per_launch": flat_ops_launch,
                      "per_candidate_equivalent_frac": flat_rate / ALU_PEAK_LANE_OPS},
     }
+    # Queries of the batch with the same reduction group, chunks, patterns, alphabet and size limit are evaluated
+    # once (validity does not depend on the links or on where the placement puts the group); every query is still
+    # costed on its own.  The same batch with that switched off, for comparison:
+    out["config"]["queries_evaluated"] = sum(1 for r in results if r["stats"]["steps_evaluated"] > 0) if engines == [5] else None
+    if args.engine == 0 and 3 not in engines:
+        os.environ["P2_EVALUATE_EVERY_QUERY"] = "1"
+        try:
+            every = timed(args.engine, max(args.steps // 2, 2), 2)
+        finally:
+            del os.environ["P2_EVALUATE_EVERY_QUERY"]
+        out["every_query_evaluated"] = {"value": candidates / (every["dt"] / every["steps"]), "unit": "candidates/s",
+                                        "ms_per_step": every["dt"] / every["steps"] * 1e3, "steps": every["steps"],
+                                        "device_ms_per_step": {"evaluate": every["eval_ms"] / every["steps"],
+                                                               "order_cost_topk": every["post_ms"] / every["steps"]}}
     if 3 in engines:
         # the frontier engine's time is spread over many launches per query outside the evaluation events, and
         # its work is pruned enumeration, not candidates visited: no lane-operation rate is quoted for it
@@ -218,6 +235,7 @@ def main():
             out["roofline"][key] = None
     if 5 in engines and args.engine == 0 and candidates <= 1 << 30:
         # the engine that evaluates every candidate on its own, timed the same way (fewer steps)
+        os.environ["P2_EVALUATE_EVERY_QUERY"] = "1"    # (this leg is about the kernel: every candidate is visited)
         try:
             own, own_engine = timed(4, max(args.steps // 2, 2), 2), 4
         except B.P2Error:                          # more than 32 devices or chunks: the LDS-resident compact engine
@@ -225,6 +243,8 @@ def main():
                 own, own_engine = timed(2, max(args.steps // 10, 1), 1), 2
             except B.P2Error:                      # too many candidates to visit one by one (config 5)
                 own = None
+        finally:
+            del os.environ["P2_EVALUATE_EVERY_QUERY"]
     else:
         own = None
     if own is not None:
