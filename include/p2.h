@@ -188,6 +188,11 @@ typedef struct {
  * every requested reduction).  All queries share msg_bytes.  Results of query i occupy
  * out_prog[out_offset[i] .. out_offset[i+1]) and the matching rows of out_cost;
  * out_offset has n_queries + 1 entries; stats (optional) has n_queries entries.
+ * Whether a program is valid depends on the reduction group, the chunks, the patterns, the alphabet
+ * and the size limit only, not on the links nor on where the placement puts the group: queries of
+ * the batch that agree in these are evaluated once and then costed each with its own links (the
+ * later ones report the first one's per-candidate counts in their stats, and steps_evaluated = 0
+ * under the shared-prefix engine).  P2_EVALUATE_EVERY_QUERY=1 in the environment switches this off.
  * The kernels of all queries share their launches; the call waits for the device twice: after
  * the evaluation (to size the result lists) and for the results. */
 int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,

@@ -558,6 +558,27 @@ def test_costs_of_large_reduction_groups(B, oracle, card, axes, k, algo):
     assert ops == {0, 1, 2, 3, 4} and len(res["programs"]) > 20
 
 
+@pytest.mark.parametrize("engine", [0, 2, 4, 1], ids=["auto", "compact", "small", "literal"])
+def test_equal_queries_are_evaluated_once(B, oracle, engine, monkeypatch):
+    """Queries of a batch with the same reduction group, chunks, patterns, alphabet and size limit share one
+    evaluation (validity does not depend on the links or on where the placement puts the group); lists, costs and
+    per-candidate step counts are those of every query evaluated on its own (P2_EVALUATE_EVERY_QUERY=1)."""
+    cfg, queries = queries_of(2 if engine != 1 else 1, B)
+    batch = [dict(q, engine=engine) for q in queries]
+    shared = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
+    monkeypatch.setenv("P2_EVALUATE_EVERY_QUERY", "1")
+    alone = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
+    for q, a, b in zip(batch, shared, alone):
+        _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
+        assert_same(a, ora, len(cfg["msg_bytes"]))
+        assert_same(b, ora, len(cfg["msg_bytes"]))
+        for key in ("steps_executed", "member_visits", "valid", "literal_reruns", "candidates"):
+            assert a["stats"][key] == b["stats"][key]
+    if engine == 0:      # the shared-prefix engine reports what it carried out per query: nothing for a repeated one
+        assert sum(1 for r in shared if r["stats"]["steps_evaluated"] == 0) >= len(batch) // 2
+        assert all(r["stats"]["steps_evaluated"] > 0 for r in alone)
+
+
 def test_config3_compact_engine_matches_default(B, oracle):
     """The default engine on configuration 3 is the shared-prefix engine (64 devices, power-of-two levels);
     the LDS-resident compact engine, which evaluates every candidate in a lane of its own, gives the same
