@@ -116,6 +116,7 @@ def main():
     ap.add_argument("--engine", type=int, default=0,
                     help="0 auto, 1 literal, 2 compact (state in LDS), 3 frontier, 4 small-group, 5 shared-prefix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-compare", action="store_true", help="skip the leg that evaluates every query on its own (profiling runs)")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -218,7 +219,7 @@ def main():
     # once (validity does not depend on the links or on where the placement puts the group); every query is still
     # costed on its own.  The same batch with that switched off, for comparison:
     out["config"]["queries_evaluated"] = sum(1 for r in results if r["stats"]["steps_evaluated"] > 0) if engines == [5] else None
-    if args.engine == 0 and 3 not in engines:
+    if args.engine == 0 and 3 not in engines and not args.no_compare:
         os.environ["P2_EVALUATE_EVERY_QUERY"] = "1"
         try:
             every = timed(args.engine, max(args.steps // 2, 2), 2)
