@@ -339,7 +339,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& r : runs) {
         if (r.plan.hierarchy == P2_HIERARCHY_COLLAPSED) continue;
         r.off_goal = off;
-        off += align_up(sizeof(uint32_t) * r.plan.goal.size(), 256);
+        off += align_up(sizeof(uint32_t) * (r.plan.goal.empty() ? 0 : (size_t)r.plan.R * literal_mask_words(r.plan.R)), 256);
         r.off_rank = off;
         size_t n_rank = 0;
         for (const Pattern& p : r.plan.patterns) n_rank += p.rank.size();
@@ -509,7 +509,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             dq->goal_mask = nullptr; dq->rank_tbl = nullptr;
             if (pl.hierarchy != P2_HIERARCHY_COLLAPSED) {
                 if (!pl.goal.empty()) {
-                    std::memcpy(hb + r.off_goal, pl.goal.data(), sizeof(uint32_t) * pl.goal.size());
+                    // the plan's rows are ceil(R/32) words long, the kernels' a power of two
+                    const int mw = (pl.R + 31) / 32, mwd = literal_mask_words(pl.R);
+                    uint32_t* goal = reinterpret_cast<uint32_t*>(hb + r.off_goal);
+                    for (int d = 0; d < pl.R; ++d)
+                        for (int w = 0; w < mwd; ++w) goal[(size_t)d * mwd + w] = w < mw ? pl.goal[(size_t)d * mw + w] : 0u;
                     dq->goal_mask = reinterpret_cast<const uint32_t*>(db + r.off_goal);
                 }
                 int32_t* ranks = reinterpret_cast<int32_t*>(hb + r.off_rank);

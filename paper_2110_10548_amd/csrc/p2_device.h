@@ -15,6 +15,10 @@ constexpr int kMaxTopK = 1024;
 
 enum : int { OP_AR = 0, OP_RS = 1, OP_AG = 2, OP_RD = 3, OP_BC = 4 };
 
+// Words per device mask in the literal state's kernels (their MW template argument): ceil(R/32) rounded up
+// to a power of two.
+inline int literal_mask_words(int R) { return R <= 32 ? 1 : R <= 64 ? 2 : R <= 128 ? 4 : R <= 256 ? 8 : 16; }
+
 // One canonical pattern inside a reduction group of R devices numbered by local id: group G is
 // {base(G) + t*s : t < g}; with master only bases whose (id % s) == 0 exist.
 struct DevPattern {
@@ -141,7 +145,7 @@ struct DevQuery {
     const DevRows* rows;           // bandwidth rows (valid by the time a cost kernel runs)
     const double* msg_bytes;       // [n_msg]
     // synthesis hierarchies other than the collapsed one (literal engine only)
-    const uint32_t* goal_mask;     // [R][MW] goal of each device; nullptr: every device of the group
+    const uint32_t* goal_mask;     // [R][literal_mask_words(R)] goal of each device; nullptr: every device of the group
     const int32_t* rank_tbl;       // ranks of the patterns with rank_off != 0
     // outputs of the evaluation kernels
     unsigned long long* valid_idx;

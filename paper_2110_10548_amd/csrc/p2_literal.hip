@@ -1598,7 +1598,7 @@ hipError_t allow_big_lds(F func, size_t bytes) {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(func), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-inline int mask_words(int R) { return R <= 32 ? 1 : R <= 64 ? 2 : R <= 128 ? 4 : R <= 256 ? 8 : 16; }
+inline int mask_words(int R) { return literal_mask_words(R); }
 
 }  // namespace
 

@@ -300,6 +300,27 @@ def test_random_queries_other_hierarchies(B, oracle):
     assert n > 1000
 
 
+@pytest.mark.parametrize("card,axes,placement,red,max_len", [
+    ([6, 4, 6], [24, 6], [[6, 4, 1], [1, 1, 6]], [1], 3),             # 144 devices: 5 words per mask
+    ([4, 3, 8], [8, 12, 1], [[2, 1, 4], [2, 3, 2], [1, 1, 1]], [0], 2),   # 96 devices: 3 words
+    ([2, 8, 8], [2, 64], [[2, 1, 1], [1, 8, 8]], [1], 2),             # 128 devices: 4 words
+])
+def test_other_hierarchies_above_64_devices(B, oracle, card, axes, placement, red, max_len):
+    """Sec. 3.4, hierarchies (a)-(c) on systems whose device masks take several words, a power of two or not:
+    the per-device goals (several reduction groups inside the copy) against the oracle."""
+    msg = [2.0 ** 22, 3.0e8]
+    links = dict(bw=[12.5e9, 50e9, 150e9][:len(card)], alpha=[2e-5, 1e-5, 5e-6][:len(card)])
+    n = 0
+    for kind in KINDS:
+        for algo in (0, 1):
+            q = dict(card=card, axes=axes, placement=placement, reduce_axes=red, max_len=max_len, hierarchy=kind, algo=algo,
+                     **links)
+            _, ora = oracle_result(oracle, q, msg)
+            assert_same(B.p2_synthesize_batch([q], msg)[0], ora, len(msg))
+            n += len(ora["index"])
+    assert n >= 8
+
+
 def _lowered_programs(B, q, res):
     """Programs as sequences of (device groups on the full system, collective)."""
     groups = {}
