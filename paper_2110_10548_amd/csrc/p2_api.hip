@@ -448,13 +448,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     };
     // Segment tables for the kernels that serve many queries per launch.  Tables of one phase are
     // packed into C.post and uploaded with one copy; `PostLaunch` remembers where each one starts.
-    struct PostLaunch { int cls = 0; int max_R = 0, max_k = 0; std::vector<DevPostSeg> segs; unsigned blocks = 0; size_t off = 0; };
+    struct PostLaunch { int cls = 0; int max_R = 0, max_k = 0; size_t lit_lds = 0; std::vector<DevPostSeg> segs; unsigned blocks = 0; size_t off = 0; };
     auto add_seg = [](std::vector<PostLaunch>& v, int cls, const Plan& pl, int query, uint32_t count, uint32_t per_block,
                       size_t in_off, size_t out_off) {
         PostLaunch* L = nullptr;
         for (auto& c : v) if (c.cls == cls) L = &c;
         if (!L) { v.emplace_back(); L = &v.back(); L->cls = cls; }
         L->max_R = std::max(L->max_R, pl.R); L->max_k = std::max(L->max_k, pl.k);
+        L->lit_lds = std::max(L->lit_lds, literal_lds_bytes(pl.R, pl.k));     // what the literal kernels would need
         DevPostSeg sg;
         sg.first_block = L->blocks; sg.query = query; sg.count = count; sg.per_block = per_block;
         sg.in_off = in_off; sg.out_off = out_off;
@@ -619,7 +620,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(upload_segs({&rerun_launches}));
             for (auto& L : rerun_launches)
                 P2_HIP(launch_eval_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks,
-                                                L.max_R, L.max_k, static_cast<unsigned long long*>(C.rerun.p), stream));
+                                                L.max_R, L.lit_lds, static_cast<unsigned long long*>(C.rerun.p), stream));
         }
         if (reran) {
             P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
@@ -837,7 +838,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& L : lcost_launches) {
         ++post_launches;
         P2_HIP(launch_cost_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
-                                        L.max_k, sorted_base, progs_base, costs_base, L.cls & 1, stream));
+                                        L.lit_lds, sorted_base, progs_base, costs_base, L.cls & 1, stream));
     }
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];

@@ -196,8 +196,10 @@ int compact_lanes(int R, int k);
 hipError_t launch_rank_sort(const unsigned long long* valid, const unsigned long long* valid2, unsigned long long* sorted,
                             const DevPostSeg* segs, int n_segs, unsigned blocks, hipStream_t stream);
 // Literal evaluation of listed candidates (one per block): list[in_off + i], i < count, of each segment's query.
+// The queries of a launch have the mask width of max_R; lds_bytes = the largest literal_lds_bytes(R, k) among
+// them (each fits on its own; the largest R and the largest k together need not).
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                    int max_R, int max_k, const unsigned long long* list, hipStream_t stream);
+                                    int max_R, size_t lds_bytes, const unsigned long long* list, hipStream_t stream);
 // Groups handed over by the shared-prefix engine (list entries = index of a group's first candidate), for
 // the queries qlist[0 .. n_q) (device array of query numbers): counts and lists are read on the device from
 // each query's counters, so the launch can be queued right behind the evaluation kernel.  States that fit
@@ -217,7 +219,7 @@ hipError_t launch_cost_compact_list(const DevQuery* queries, const DevPostSeg* s
                                     int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
                                     double* costs, hipStream_t stream);
 hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    int max_R, size_t lds_bytes, const unsigned long long* sorted, p2_program* progs,
                                     double* costs, int only_missing, hipStream_t stream);
 // For each of the n sorted valid candidates: its program record and its cost for every message size.
 hipError_t launch_cost(const DevQuery* q, int R, int k, int engine, const unsigned long long* sorted, uint32_t n,

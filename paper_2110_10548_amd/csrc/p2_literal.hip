@@ -1698,10 +1698,10 @@ hipError_t launch_cost_literal(const DevQuery* q, int R, int k, const unsigned l
 }
 
 hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                    int max_R, int max_k, const unsigned long long* list, hipStream_t stream) {
+                                    int max_R, size_t lds_bytes, const unsigned long long* list, hipStream_t stream) {
     if (n_segs == 0 || blocks == 0) return hipSuccess;
-    const size_t lds = literal_lds_bytes(max_R, max_k);
-    if (lds == 0) return hipErrorInvalidValue;
+    const size_t lds = lds_bytes;
+    if (lds == 0 || lds > kLdsLimit) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_list<MWV>, lds);                                                          \
@@ -1720,11 +1720,11 @@ hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* s
 }
 
 hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* segs, int n_segs, unsigned blocks,
-                                    int max_R, int max_k, const unsigned long long* sorted, p2_program* progs,
+                                    int max_R, size_t lds_bytes, const unsigned long long* sorted, p2_program* progs,
                                     double* costs, int only_missing, hipStream_t stream) {
     if (n_segs == 0 || blocks == 0) return hipSuccess;
-    const size_t lds = literal_lds_bytes(max_R, max_k);
-    if (lds == 0) return hipErrorInvalidValue;
+    const size_t lds = lds_bytes;
+    if (lds == 0 || lds > kLdsLimit) return hipErrorInvalidValue;
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_cost_literal_list<MWV>, lds);                                                          \

@@ -321,6 +321,23 @@ def test_other_hierarchies_above_64_devices(B, oracle, card, axes, placement, re
     assert n >= 8
 
 
+def test_literal_states_of_different_shapes_in_one_batch(B, oracle):
+    """Two queries of the literal engine with masks of the same width, one with many devices and one chunk,
+    one with fewer devices and many chunks: each state fits in LDS, a state of the larger device count and the
+    larger chunk count together would not.  They share their launches."""
+    msg = [2.0 ** 22, 3.0e8]
+    links = dict(bw=[12.5e9, 50e9, 150e9], alpha=[2e-5, 1e-5, 5e-6])
+    queries = [dict(card=[4, 8, 8], axes=[256], placement=[[4, 8, 8]], reduce_axes=[0], n_chunks=1, max_len=2, engine=1, **links),
+               dict(card=[6, 4, 6], axes=[144], placement=[[6, 4, 6]], reduce_axes=[0], n_chunks=16, max_len=2, engine=1, **links),
+               dict(card=[6, 4, 6], axes=[144], placement=[[6, 4, 6]], reduce_axes=[0], n_chunks=16, max_len=2, engine=2, **links)]
+    n = 0
+    for q, res in zip(queries, B.p2_synthesize_batch(queries, msg)):
+        _, ora = oracle_result(oracle, q, msg)
+        assert_same(res, ora, len(msg))
+        n += len(ora["index"])
+    assert n >= 6
+
+
 def _lowered_programs(B, q, res):
     """Programs as sequences of (device groups on the full system, collective)."""
     groups = {}
