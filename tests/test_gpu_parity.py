@@ -338,6 +338,62 @@ def test_literal_states_of_different_shapes_in_one_batch(B, oracle):
     assert n >= 6
 
 
+@pytest.mark.parametrize("seed", [17, 170])
+def test_mixed_batches(B, oracle, seed):
+    """One batch of seeded random queries of every kind at once: up to 512 devices, the tool's hierarchy and the
+    others of Sec. 3.4, forced engines, and repeats of a query that differ in links, cost model or shortlist
+    length (their validity is shared, their costs are their own), in shuffled order; each against the oracle."""
+    msg = [float(1 << 20), float(1 << 26), 3.0e8]
+    rng = workloads.SplitMix64(seed * 7 + 1)
+    batch = []
+    for q in workloads.random_queries(seed, 30, max_devices=512):
+        devices = int(np.prod(q["card"]))
+        kind = ["collapsed", "collapsed", "collapsed", "system", "column", "row", "reduction"][rng.below(7)]
+        limit = min(200_000 if devices <= 64 else 20_000, 200_000 if kind == "collapsed" else 30_000)
+        probe = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], form_mask=q["form_mask"],
+                             op_mask=q["op_mask"], hierarchy=kind)
+        max_len = 1
+        while max_len < 5 and probe.alphabet > 0 and probe.num_candidates(max_len + 1) <= limit:
+            max_len += 1
+        q = dict(q, max_len=max_len, hierarchy=kind)
+        batch.append(q)
+        for _ in range(rng.below(4)):
+            d = dict(q)
+            if rng.below(2):
+                d["bw"] = [b * (1 + rng.below(5)) for b in q["bw"]]
+            if rng.below(2):
+                d["alpha"] = [a * (1 + rng.below(3)) for a in q["alpha"]]
+            if rng.below(2):
+                d["algo"] = 1 - q.get("algo", 0)
+            if rng.below(3) == 0:
+                d["topk"] = 1 + rng.below(6)
+            if kind == "collapsed" and rng.below(3) == 0:
+                d["engine"] = [0, 1, 2, 3][rng.below(4)]
+            batch.append(d)
+    for i in range(len(batch) - 1, 0, -1):
+        j = rng.below(i + 1)
+        batch[i], batch[j] = batch[j], batch[i]
+    results = B.p2_synthesize_batch(batch, msg)
+    n_valid = 0
+    for q, res in zip(batch, results):
+        _, ora = oracle_result(oracle, q, msg, form_mask=q["form_mask"], op_mask=q["op_mask"])
+        n_valid += len(ora["index"])
+        k = q.get("topk", 0)
+        if k == 0:
+            assert_same(res, ora, len(msg))
+            continue
+        kk = min(k, len(ora["index"]))
+        assert len(res["programs"]) == kk * len(msg)
+        pos_of = {int(ix): i for i, ix in enumerate(ora["index"])}
+        for m in range(len(msg)):
+            got = res["programs"]["index"][m * kk:(m + 1) * kk].tolist()
+            rows = [pos_of[ix] for ix in got]
+            assert len(set(got)) == kk
+            assert np.allclose(res["cost"][m * kk:(m + 1) * kk], ora["cost"][rows], rtol=RTOL, atol=0.0)
+            assert np.allclose(np.sort(ora["cost"][rows, m]), np.sort(ora["cost"][:, m])[:kk], rtol=RTOL, atol=0.0)
+    assert len(batch) > 50 and n_valid > 300
+
+
 def _lowered_programs(B, q, res):
     """Programs as sequences of (device groups on the full system, collective)."""
     groups = {}
