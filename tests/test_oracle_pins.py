@@ -272,21 +272,57 @@ def test_running_example_named_programs(running):
         assert tuple(prog) in progs
 
 
-def test_valid_programs_obey_the_validity_lemmas(oracle):
-    # Appendix B: an instruction of a valid program only varies levels that are 1 or on the
-    # reduction axes; with hierarchy (d) that is automatic, so check it on the lowered groups:
-    # every group lies inside one reduction group.
-    card, axes = [2, 2, 4], [4, 4]
+def _level_cells(kind, l, m, n, red):
+    """Factors x[i][j] of the parallelism matrix that level e_l (l >= 1) of a synthesis hierarchy owns."""
+    if kind == "system":
+        return [(i, l - 1) for i in range(m)]
+    if kind == "column":
+        return [((l - 1) % m, (l - 1) // m)]
+    if kind == "row":
+        return [((l - 1) // n, (l - 1) % n)]
+    if kind == "reduction":
+        return [(red[(l - 1) // n], (l - 1) % n)]
+    return [(i, l - 1) for i in red]                             # collapsed: the reduction axes' factors of level l-1
+
+
+@pytest.mark.parametrize("kind", ["system", "column", "row", "reduction", "collapsed"])
+def test_valid_programs_obey_the_validity_lemmas(oracle, kind):
+    """Appendix B, "Semantically valid reduction": in a valid program an instruction (x_i, Parallel(x_j))
+    only varies levels x_{j+1..i} that are 1 or on the reduction axes, (x_i, InsideGroup) only such levels
+    x_{i+1..n}, and (x_i, Master(x_j)) only such levels x_{j+1..n}.  Checked on every instruction of every
+    valid program of every placement of the running system, under all five synthesis hierarchies.  The
+    Master lemma has two parts: the levels the groups range over (j+1..i), which must hold, and the
+    levels that pick "the first group" (i+1..n).  With one group per instance of x_j and per digit of the
+    other axes' levels (the reading of Master taken here) the second part can fail under (a)-(c) for a
+    step that happens to be harmless; those are the only exceptions allowed."""
+    card, axes = [1, 2, 2, 4], [4, 4]
+    m, n = len(axes), len(card)
+    exceptions = 0
     for x in oracle.enumerate_placements(card, axes):
-        q = oracle.Query(card, axes, x, [1])
-        _, goal, _ = q.run_state([])
-        for pid in range(q.n_patterns):
-            for g in q.groups(pid):
-                # devices of one group must end up reducing with each other
-                ran, st, ok = q.run_state([0 * 5 + AR])
-                assert ok
-                members = set(np.nonzero(st[g[0], 0])[0])
-                assert set(g) <= members
+        for red in ([0], [1]):
+            q = oracle.Query(card, axes, x, red, hierarchy=kind)
+            top = len(q.synthesis_hierarchy()) - 1
+
+            def fine(l):
+                return all(x[i][j] == 1 or i in red for i, j in _level_cells(kind, l, m, n, red))
+
+            r = q.synthesize(4)
+            assert len(r["index"]) > 0 or kind == "system"
+            for ins, ln in zip(r["instr"], r["len"]):
+                for v in ins[:ln]:
+                    p = q.pattern(int(v) // 5)
+                    i, form, j = p["slice"], p["form"], p["form_level"]
+                    if form == INSIDE:
+                        assert all(fine(l) for l in range(i + 1, top + 1)), (x.tolist(), red, int(v))
+                    elif form == PARALLEL:
+                        assert all(fine(l) for l in range(j + 1, i + 1)), (x.tolist(), red, int(v))
+                    else:
+                        assert all(fine(l) for l in range(j + 1, i + 1)), (x.tolist(), red, int(v))
+                        tail = all(fine(l) for l in range(i + 1, top + 1))
+                        assert tail or kind in ("system", "column", "row"), (x.tolist(), red, int(v))
+                        exceptions += 0 if tail else 1
+    if kind in ("reduction", "collapsed"):
+        assert exceptions == 0                                   # (d): nothing but reduction-axis factors below the root
 
 
 # --------------------------------------------------------------------------- enumeration invariants
@@ -399,14 +435,79 @@ def test_cost_identities_and_independence(oracle):
     assert np.allclose(r0["cost"][:, 1], 2 * r0["cost"][:, 0], rtol=1e-14)         # linear in bytes when alpha = 0
     assert np.allclose(r0["cost"][:, 2], 1024 * r0["cost"][:, 0], rtol=1e-14)
     assert (r["cost"] > r0["cost"]).all()
-    # RS;AG on a pattern costs what AR on it costs (the ring identities add up)
+    # RS;AG on a pattern costs what AR on it costs, per pattern and per message size (the ring figures add
+    # up: (g-1) + (g-1) steps on the same links, (g-1)/g n bytes twice through the same uplinks).  Where the
+    # one-instruction program is not a whole reduction the three are compared as prefixes of valid programs.
+    found = 0
     for pid in range(q.n_patterns):
-        ok1, c1, _ = q.eval_program([pid * 5 + AR], msg)
-        st = q.run_state([pid * 5 + RS, pid * 5 + AG])
-        if st[0] == 2:
-            # cost of the two steps: evaluate through a program that continues to the goal if needed
-            ran, s_ar, _ = q.run_state([pid * 5 + AR])
-            assert (st[1] == s_ar).all()
+        ran_ar, s_ar, _ = q.run_state([pid * 5 + AR])
+        ran_2, s_2, _ = q.run_state([pid * 5 + RS, pid * 5 + AG])
+        assert ran_ar == 1 and ran_2 == 2 and (s_2 == s_ar).all()
+        # a valid program that starts with AR on this pattern, and the same with RS;AG in its place
+        for ins, ln, c_ar in zip(r["instr"], r["len"], r["cost"]):
+            if int(ins[0]) != pid * 5 + AR or ln > 3:
+                continue
+            tail = [int(v) for v in ins[1:ln]]
+            ok2, c2, _ = q.eval_program([pid * 5 + RS, pid * 5 + AG] + tail, msg)
+            ok1, c1, _ = q.eval_program([pid * 5 + AR] + tail, msg)
+            assert ok1 and ok2 and np.allclose(c1, c_ar, rtol=1e-15) and np.allclose(c2, c1, rtol=1e-13), (pid, tail)
+            found += 1
+    assert found >= q.n_patterns
+
+
+def _pattern_named(q, **want):
+    """Pattern id by its groups: n_groups, group size, and optionally a group that must be present."""
+    for pid in range(q.n_patterns):
+        g = q.groups(pid)
+        if len(g) == want["n_groups"] and len(g[0]) == want["size"] and ("has" not in want or want["has"] in g):
+            return pid
+    raise AssertionError(want)
+
+
+def test_hand_worked_three_level_costs_with_replicas(oracle):
+    """Config 2's system [4 nodes x 2 sockets x 4 GPUs] (25 / 100 / 300 GB/s, 20 / 10 / 5 us), matrix
+    [[1,2,2],[4,1,2]], 64 MiB per device, k = 32.  Device (c0, c1, c2): c0 = digit of axis 1, c1 = digit of
+    axis 0, c2 = 2 * (digit of axis 0) + (digit of axis 1).  Every uplink load below is written out by hand,
+    the groups of the other axis' replicas included; ring and tree."""
+    card, axes, x = [4, 2, 4], [4, 8], [[1, 2, 2], [4, 1, 2]]
+    bw, al = [25e9, 100e9, 300e9], [20e-6, 10e-6, 5e-6]
+    n = N26
+    dev = lambda c0, c1, c2: (c0 * 2 + c1) * 4 + c2
+    for algo in (0, 1):
+        # ---- reduce axis 0 (4 devices per reduction group: c1 and the high bit of c2; 8 replicas)
+        q = oracle.Query(card, axes, x, [0], bw=bw, alpha=al, algo=algo)
+        inner = _pattern_named(q, n_groups=16, size=2, has=[dev(0, 0, 0), dev(0, 0, 2)])     # same socket
+        outer = _pattern_named(q, n_groups=16, size=2, has=[dev(0, 0, 0), dev(0, 1, 0)])     # across the sockets of a node
+        whole = _pattern_named(q, n_groups=8, size=4)
+        # ReduceScatter in the socket: 1 step, n/2 bytes through each GPU port
+        t_rs = 1 * 5e-6 + (n / 2) / 300e9
+        # AllReduce across sockets on the n/2 bytes each device kept: every socket holds 4 devices, each in a
+        # group of its own (2 of this reduction group's halves x 2 replicas of the other axis), so 4 groups
+        # share the socket's uplink; ring: 2 steps, 2 * 1/2 * n/2 bytes per group; tree: 2 steps, 2 * n/2
+        per_group = (2 * (1 / 2) * (n / 2)) if algo == 0 else (2 * (n / 2))
+        t_ar = 2 * 10e-6 + max(4 * per_group / 100e9, per_group / 300e9)
+        # AllGather in the socket: n bytes afterwards, 1 step, n/2 through each port
+        t_ag = 1 * 5e-6 + (n / 2) / 300e9
+        ok, cost, _ = q.eval_program([inner * 5 + RS, outer * 5 + AR, inner * 5 + AG], [n])
+        assert ok and cost[0] == pytest.approx(t_rs + t_ar + t_ag, rel=1e-13)
+        # one AllReduce over the 4 devices: 2 of its members in each socket, and the socket also holds the
+        # other replica's 2 members: 2 groups through the socket uplink; nothing leaves the node
+        steps, per_group = (6, 2 * (3 / 4) * n) if algo == 0 else (4, 2 * n)
+        ok, cost, _ = q.eval_program([whole * 5 + AR], [n])
+        assert ok and cost[0] == pytest.approx(steps * 10e-6 + max(2 * per_group / 100e9, per_group / 300e9), rel=1e-13)
+
+        # ---- reduce axis 1 (8 devices per reduction group: c0 and the low bit of c2; 4 replicas)
+        q = oracle.Query(card, axes, x, [1], bw=bw, alpha=al, algo=algo)
+        pair = _pattern_named(q, n_groups=16, size=2, has=[dev(0, 0, 0), dev(0, 0, 1)])       # same socket
+        roots = _pattern_named(q, n_groups=4, size=4, has=[dev(0, 0, 0), dev(1, 0, 0), dev(2, 0, 0), dev(3, 0, 0)])
+        # Reduce onto the pair's first device: 1 step, n bytes into its port; Broadcast back the same
+        t_rd = 1 * 5e-6 + n / 300e9
+        # AllReduce between the 4 nodes' roots: a node holds 4 roots (2 sockets x 2 replicas), each of a group
+        # of its own, so its network uplink carries 4 groups; a socket's uplink carries 2
+        steps, per_group = (6, 2 * (3 / 4) * n) if algo == 0 else (4, 2 * n)
+        t_ar = steps * 20e-6 + max(4 * per_group / 25e9, 2 * per_group / 100e9, per_group / 300e9)
+        ok, cost, _ = q.eval_program([pair * 5 + RD, roots * 5 + AR, pair * 5 + BC], [n])
+        assert ok and cost[0] == pytest.approx(t_rd + t_ar + t_rd, rel=1e-13)
 
 
 def test_rs_ag_costs_the_same_as_ar_when_both_complete(oracle):
