@@ -141,9 +141,9 @@ def main():
         dst.copy_(src)                            # reads and writes copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    def timed(engine, steps, warmup):
+    def timed(engine, steps, warmup, flags=0):
         """K timed steps of the whole path with one engine: wall time, device times, results."""
-        qs = [dict(q, engine=engine) for q in queries]
+        qs = [dict(q, engine=engine, flags=flags) for q in queries]
         batch = B.Batch(qs, msg)                  # argument marshalling only; every step replans on the host
         for _ in range(max(warmup, 1)):
             batch.run_raw()
@@ -220,11 +220,7 @@ def main():
     # costed on its own.  The same batch with that switched off, for comparison:
     out["config"]["queries_evaluated"] = sum(1 for r in results if r["stats"]["steps_evaluated"] > 0) if engines == [5] else None
     if args.engine == 0 and 3 not in engines and not args.no_compare:
-        os.environ["P2_EVALUATE_EVERY_QUERY"] = "1"
-        try:
-            every = timed(args.engine, max(args.steps // 2, 2), 2)
-        finally:
-            del os.environ["P2_EVALUATE_EVERY_QUERY"]
+        every = timed(args.engine, max(args.steps // 2, 2), 2, B.FLAG_EVALUATE_EVERY_QUERY)
         out["every_query_evaluated"] = {"value": candidates / (every["dt"] / every["steps"]), "unit": "candidates/s",
                                         "ms_per_step": every["dt"] / every["steps"] * 1e3, "steps": every["steps"],
                                         "device_ms_per_step": {"evaluate": every["eval_ms"] / every["steps"],
@@ -236,16 +232,14 @@ def main():
             out["roofline"][key] = None
     if 5 in engines and args.engine == 0 and candidates <= 1 << 30:
         # the engine that evaluates every candidate on its own, timed the same way (fewer steps)
-        os.environ["P2_EVALUATE_EVERY_QUERY"] = "1"    # (this leg is about the kernel: every candidate is visited)
+        every_q = B.FLAG_EVALUATE_EVERY_QUERY           # (this leg is about the kernel: every candidate is visited)
         try:
-            own, own_engine = timed(4, max(args.steps // 2, 2), 2), 4
+            own, own_engine = timed(4, max(args.steps // 2, 2), 2, every_q), 4
         except B.P2Error:                          # more than 32 devices or chunks: the LDS-resident compact engine
             try:
-                own, own_engine = timed(2, max(args.steps // 10, 1), 1), 2
+                own, own_engine = timed(2, max(args.steps // 10, 1), 1, every_q), 2
             except B.P2Error:                      # too many candidates to visit one by one (config 5)
                 own = None
-        finally:
-            del os.environ["P2_EVALUATE_EVERY_QUERY"]
     else:
         own = None
     if own is not None:

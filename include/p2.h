@@ -121,8 +121,22 @@ typedef struct {
     int32_t topk;        /* 0 => return every valid program; else see p2_synthesize              */
     int32_t engine;      /* P2_ENGINE_*                                                          */
     int32_t hierarchy;   /* P2_HIERARCHY_*; 0 => (d), the tool's own                             */
+    uint32_t flags;      /* P2_FLAG_* bits; 0 => none                                            */
+    int32_t max_row_classes; /* 0 => 64.  The literal kernels that serve the shared-prefix and the
+                            frontier engine keep a state by classes of equal rows, up to this
+                            many (1..64), and fall back to the full literal state beyond it;
+                            results do not depend on it (a lower limit sends more work down
+                            the fall-back path, which is what tests of that path set it for).
+                            Kernels that serve several queries use the smallest limit among
+                            them.  Outside 0..64 => P2_EINVAL                                    */
+    int32_t reserved;    /* must be 0                                                            */
     void* hip_stream;    /* hipStream_t to run on; NULL => the default stream                    */
 } p2_options;
+
+/* p2_options.flags */
+#define P2_FLAG_EVALUATE_EVERY_QUERY 1u   /* p2_synthesize_batch: do not share the evaluation of queries
+                                             that are equal in everything validity depends on (see
+                                             there); set on any query of the batch, it holds for all  */
 
 /* One program.  instr[t] = pattern_id * 5 + op, op in the order AllReduce, ReduceScatter,
  * AllGather, Reduce, Broadcast; pattern ids are those of p2_describe_pattern.  index is the
@@ -137,7 +151,10 @@ typedef struct {
 
 /* Counters of one query (all optional outputs). */
 typedef struct {
-    uint64_t candidates;       /* programs of length <= max_len over the alphabet, all evaluated  */
+    uint64_t candidates;       /* programs of length <= max_len over the alphabet: the candidate
+                                  space this query's results cover.  A query that shares another
+                                  query's evaluation (p2_synthesize_batch) reports the same number
+                                  although nothing was evaluated for it                           */
     uint64_t steps_executed;   /* instructions applied, counted per candidate (a candidate stops at
                                   its first bad step): what evaluating every candidate on its own
                                   executes, whichever engine ran                                  */
@@ -192,7 +209,8 @@ typedef struct {
  * and the size limit only, not on the links nor on where the placement puts the group: queries of
  * the batch that agree in these are evaluated once and then costed each with its own links (the
  * later ones report the first one's per-candidate counts in their stats, and steps_evaluated = 0
- * under the shared-prefix engine).  P2_EVALUATE_EVERY_QUERY=1 in the environment switches this off.
+ * under the shared-prefix engine).  P2_FLAG_EVALUATE_EVERY_QUERY in the options of any query of the
+ * batch switches this off for the whole batch, on every engine.
  * The kernels of all queries share their launches; the call waits for the device twice: after
  * the evaluation (to size the result lists) and for the results. */
 int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
@@ -272,6 +290,12 @@ int32_t p2_get_profile(p2_profile* out);
  * against the ceiling derived from the unit counts and the clock, and this shows how close the
  * device comes to it.  hip_stream: hipStream_t or NULL.  P2_EINVAL on bad arguments. */
 int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_stream);
+
+/* Gives back what the calling host thread's calls have cached: device buffers, pinned host buffers,
+ * the upload stream and the profiling events (profiling is switched off).  The next call of the thread
+ * allocates afresh.  A host thread that ends gives its cache back by itself; the thread that loaded the
+ * library keeps it until the process ends unless it calls this. */
+int32_t p2_release_thread(void);
 
 const char* p2_last_error(void);
 

@@ -31,7 +31,8 @@ class p2_hierarchy(C.Structure):
 
 class p2_options(C.Structure):
     _fields_ = [("n_chunks", C.c_int32), ("form_mask", C.c_uint32), ("op_mask", C.c_uint32), ("algo", C.c_int32),
-                ("topk", C.c_int32), ("engine", C.c_int32), ("hierarchy", C.c_int32), ("hip_stream", C.c_void_p)]
+                ("topk", C.c_int32), ("engine", C.c_int32), ("hierarchy", C.c_int32), ("flags", C.c_uint32),
+                ("max_row_classes", C.c_int32), ("reserved", C.c_int32), ("hip_stream", C.c_void_p)]
 
 
 class p2_program(C.Structure):
@@ -64,7 +65,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak")
+           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak", "p2_release_thread")
 
 _lib = None
 
@@ -104,6 +105,8 @@ def lib():
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
         L.p2_topk_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.p2_release_thread.restype = C.c_int32
+        L.p2_release_thread.argtypes = []
         L.p2_set_profiling.restype = C.c_int32
         L.p2_set_profiling.argtypes = [C.c_int32]
         L.p2_get_profile.restype = C.c_int32
@@ -145,8 +148,13 @@ class _Hier:
 HIERARCHY = {"collapsed": 0, "system": 1, "column": 2, "row": 3, "reduction": 4}
 
 
-def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None, hierarchy=0):
-    return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, HIERARCHY.get(hierarchy, hierarchy), stream)
+FLAG_EVALUATE_EVERY_QUERY = 1
+
+
+def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None, hierarchy=0, flags=0,
+             max_row_classes=0):
+    return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, HIERARCHY.get(hierarchy, hierarchy), flags,
+                      max_row_classes, 0, stream)
 
 
 def p2_enumerate_placements(card, axes):
@@ -198,7 +206,8 @@ class Batch:
             h = _Hier(q["card"], q.get("bw"), q.get("alpha"))
             axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
             opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), q.get("algo", 0), q.get("topk", 0),
-                           q.get("engine", ENGINE_AUTO), stream, q.get("hierarchy", 0))
+                           q.get("engine", ENGINE_AUTO), stream, q.get("hierarchy", 0), q.get("flags", 0),
+                           q.get("max_row_classes", 0))
             self._keep.append((h, axes, pl, red, opt))
             self._arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32),
                                     len(red), int(q["max_len"]), C.pointer(opt))
@@ -244,7 +253,7 @@ class Batch:
 
 def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
     """queries: list of dicts with card, bw, alpha, axes, placement, reduce_axes, max_len and optional
-    n_chunks, form_mask, op_mask, algo, topk, engine, hierarchy.  Returns a list of results, one per query:
+    n_chunks, form_mask, op_mask, algo, topk, engine, hierarchy, flags, max_row_classes.  Returns a list of results, one per query:
     {"programs": structured array, "cost": [n][n_msg], "stats": dict}."""
     b = Batch(queries, msg_bytes, stream)
     if cap is not None:
@@ -257,11 +266,12 @@ def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
 
 
 def p2_synthesize(card, axes, placement, reduce_axes, max_len, msg_bytes=(), bw=None, alpha=None, n_chunks=0,
-                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None, algo=0, hierarchy=0):
+                  form_mask=7, op_mask=31, topk=0, engine=ENGINE_AUTO, cap=None, stream=None, algo=0, hierarchy=0,
+                  flags=0, max_row_classes=0):
     """Valid programs of one placement with their simulated costs (through the single-query entry point).
     hierarchy: a P2_HIERARCHY_* number or one of "collapsed", "system", "column", "row", "reduction"."""
     h, axes_a, pl, red = _Hier(card, bw, alpha), _i32(axes), _i32(placement), _i32(reduce_axes)
-    opt = _options(n_chunks, form_mask, op_mask, algo, topk, engine, stream, hierarchy)
+    opt = _options(n_chunks, form_mask, op_mask, algo, topk, engine, stream, hierarchy, flags, max_row_classes)
     msg = _f64(list(msg_bytes))
     n_msg = len(msg)
     count, cands, st = C.c_int64(), C.c_uint64(), p2_stats()
@@ -319,6 +329,10 @@ def p2_measure_alu_peak(reps=5, stream=None):
     out = C.c_double()
     _check(lib().p2_measure_alu_peak(reps, C.byref(out), stream))
     return out.value
+
+
+def p2_release_thread():
+    _check(lib().p2_release_thread())
 
 
 def p2_set_profiling(on):

@@ -2,7 +2,6 @@
 // copy-back.  All arithmetic of the method runs in the kernels; this file only moves data.
 #include <algorithm>
 #include <chrono>
-#include <cstdlib>
 #include <cstddef>
 #include <cstring>
 #include <atomic>
@@ -73,6 +72,8 @@ struct HostBuf {
 
 // Device scratch owned by the library, one set per host thread, reused between calls.
 struct Ctx {
+    ~Ctx();
+    void release();
     DevBuf rows, rows_hdr;
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
     DevBuf f_entries[2], f_states[2], f_literal[2], f_surv, f_surv_literal, f_ctr, f_valid;   // frontier engine
@@ -84,21 +85,59 @@ struct Ctx {
 thread_local Ctx g_ctx;
 
 struct Prof {
+    ~Prof();
+    void release();
     bool on = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     p2_profile last = {0.f, 0.f, 0, 0, 0.f, 0.f};
 };
 thread_local Prof g_prof;
 
+// What a host thread's calls have cached on the device is given back when the thread ends, or on request
+// (p2_release_thread).  The thread that loaded the library is left alone at process exit: by then the HIP
+// runtime may be shutting down, and the process's memory goes with it anyway.
+const std::thread::id g_loader_thread = std::this_thread::get_id();
+
+void Ctx::release() {
+    DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
+                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_entries[0], &f_entries[1], &f_states[0], &f_states[1],
+                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_ctr, &f_valid};
+    for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
+    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs};
+    for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
+    if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
+    if (copy_stream) { (void)hipStreamDestroy(copy_stream); copy_stream = nullptr; }
+}
+Ctx::~Ctx() { if (std::this_thread::get_id() != g_loader_thread) release(); }
+void Prof::release() {
+    for (auto& e : ev) { if (e) (void)hipEventDestroy(e); e = nullptr; }
+    on = false;
+}
+Prof::~Prof() { if (std::this_thread::get_id() != g_loader_thread) release(); }
+
 int32_t fail(int32_t code, const std::string& msg) {
     g_err = msg;
     return code;
 }
+// Stream of the call in progress on this thread.  When a HIP call fails, what the call has queued so far
+// (kernels and copies that use the cached pinned and device buffers) is waited for before the error goes
+// back to the caller, so that the next call does not reuse buffers that are still in flight.
+thread_local hipStream_t g_call_stream = nullptr;
+thread_local bool g_call_active = false;
 int32_t hip_fail(hipError_t e, const char* what) {
     g_err = std::string(what) + ": " + hipGetErrorString(e);
     (void)hipGetLastError();
+    if (g_call_active) {
+        (void)hipStreamSynchronize(g_call_stream);
+        if (g_ctx.copy_stream) (void)hipStreamSynchronize(g_ctx.copy_stream);
+        (void)hipGetLastError();
+    }
     return P2_EDEVICE;
 }
+struct CallScope {
+    explicit CallScope(hipStream_t s) { g_call_stream = s; g_call_active = true; }
+    ~CallScope() { g_call_active = false; g_call_stream = nullptr; }
+};
 #define P2_HIP(call)                                      \
     do {                                                  \
         hipError_t e_ = (call);                           \
@@ -144,6 +183,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (!(msg_bytes[m] >= 0.0)) return fail(P2_EINVAL, "message size must be >= 0");
     hipStream_t stream = (queries[0].opt) ? (hipStream_t)queries[0].opt->hip_stream : nullptr;
     Ctx& C = g_ctx;
+    CallScope scope(stream);
 
     // ---- plan every query on the host
     const auto t_begin = std::chrono::steady_clock::now();
@@ -204,10 +244,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     // links, nor on where the placement puts the group in the system): a query that equals an earlier one of
     // the batch in these is not evaluated again; it takes over the list of valid programs and the counts, and
     // only its costs are worked out, from its own bandwidth rows.  (The frontier engine does the same further
-    // down.)  P2_EVALUATE_EVERY_QUERY=1 in the environment switches this off.
+    // down.)  P2_FLAG_EVALUATE_EVERY_QUERY in any query's options switches this off for the batch.
+    bool share_validity = true;
+    for (int i = 0; i < n_queries; ++i)
+        if (queries[i].opt && (queries[i].opt->flags & P2_FLAG_EVALUATE_EVERY_QUERY)) share_validity = false;
     {
-        const char* every = std::getenv("P2_EVALUATE_EVERY_QUERY");
-        const bool share_validity = !(every && every[0] == '1');
         for (int i = 0; i < n_queries && share_validity; ++i) {
             QueryRun& r = runs[i];
             const Plan& pl = r.plan;
@@ -321,7 +362,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     }
     // Groups that the shared-prefix engine hands to the literal engine are found on the device, so that kernel
     // is queued right behind the evaluation: one launch per mask width, each with the list of its queries.
-    struct AutoGroups { int cls = 0, max_R = 0, max_k = 0; std::vector<int32_t> qlist; size_t off = 0; };
+    struct AutoGroups { int cls = 0, max_R = 0, max_k = 0, class_cap = 64; std::vector<int32_t> qlist; size_t off = 0; };
     std::vector<AutoGroups> autos;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
@@ -332,6 +373,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (auto& a : autos) if (a.cls == cls) A = &a;
         if (!A) { autos.emplace_back(); A = &autos.back(); A->cls = cls; }
         A->max_R = std::max(A->max_R, r.plan.R); A->max_k = std::max(A->max_k, r.plan.k);
+        A->class_cap = std::min(A->class_cap, r.plan.max_row_classes);
         A->qlist.push_back(i);
         r.auto_groups = true;
     }
@@ -588,7 +630,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             unsigned nb = 0;
             P2_HIP(C.lit_scratch.ensure(literal_group_scratch_bytes(A.max_R, A.max_k, &nb)));
             P2_HIP(launch_eval_literal_groups_auto(reinterpret_cast<const DevQuery*>(db), reinterpret_cast<const int32_t*>(db + A.off),
-                                                   (int)A.qlist.size(), A.max_R, A.max_k, C.lit_scratch.p, stream));
+                                                   (int)A.qlist.size(), A.max_R, A.max_k, C.lit_scratch.p, A.class_cap, stream));
         }
         // while the GPU evaluates: the cost model's tables (first attempt only)
         {
@@ -664,9 +706,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         // costs are still worked out from its own bandwidth rows.
         {
             int same = -1;
-            for (int j = 0; j < i && same < 0; ++j) {
+            for (int j = 0; j < i && same < 0 && share_validity; ++j) {
                 const Plan& o = runs[j].plan;
-                if (!runs[j].frontier || o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet ||
+                if (!runs[j].frontier || o.max_row_classes != pl.max_row_classes || o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet ||
                     o.n_ops != pl.n_ops || o.patterns.size() != pl.patterns.size() || o.n_candidates != pl.n_candidates)
                     continue;
                 bool eq = true;
@@ -711,7 +753,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, n_l)));
                     gs = C.lit_scratch.p;
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
-                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, stream));
+                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, pl.max_row_classes, stream));
                 }
                 P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                 P2_HIP(hipStreamSynchronize(stream));
@@ -890,7 +932,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(launch_copy_out3(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid,
                             C.h_costs.p, C.costs.p, n_msg > 0 ? sizeof(double) * total_valid * nm : 0,
                             C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    if (topk_rows > 0)      // the selections flag a NaN cost in their query's counters
+        P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
     P2_HIP(hipStreamSynchronize(stream));
+    if (topk_rows > 0) {
+        const DevCounters* hc = static_cast<const DevCounters*>(C.h_counters.p);
+        for (int i = 0; i < n_queries; ++i)
+            if (runs[i].topk > 0 && hc[i].nan_seen)
+                return fail(P2_EINVAL, "query " + std::to_string(i) + ": NaN cost (a message size that is not finite?)");
+    }
     }  // store
 
     if (g_prof.on) {
@@ -955,6 +1005,12 @@ int32_t p2_set_profiling(int32_t on) {
 int32_t p2_get_profile(p2_profile* out) {
     if (!out) return fail(P2_EINVAL, "null argument");
     *out = g_prof.last;
+    return P2_OK;
+}
+
+int32_t p2_release_thread(void) {
+    g_ctx.release();
+    g_prof.release();
     return P2_OK;
 }
 

@@ -207,8 +207,9 @@ hipError_t launch_eval_literal_list(const DevQuery* queries, const DevPostSeg* s
 // literal_group_scratch_bytes, each with a slice of gscratch.
 size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks);
 // gscratch (literal_group_scratch_bytes) is needed in both cases: a stem entry keeps a copy of the stem's state there.
+// class_cap as for launch_front_classify_literal.
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
-                                           void* gscratch, hipStream_t stream);
+                                           void* gscratch, int class_cap, hipStream_t stream);
 // Program records and costs of the sorted valid candidates at out_off + i of each segment.
 // The same for states of which only a few fit in LDS (cost_wide_applies): one wavefront per program.
 bool cost_wide_applies(int max_R, int max_k);
@@ -256,9 +257,11 @@ hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEnt
                                  uint32_t n, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr, hipStream_t stream);
 // Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
+// class_cap: most classes of equal rows the class-state kernel may hold (1..64) before a prefix goes to the
+// full-state kernel.
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
-                                         void* gscratch, hipStream_t stream);
+                                         void* gscratch, int class_cap, hipStream_t stream);
 hipError_t launch_front_materialize(const DevQuery* q, uint32_t query, int R, int k, const FrontEntry* entries,
                                     const uint32_t* states, const FrontSurvivor* surv, uint32_t n_surv, int parent_len,
                                     int keep_prefixes, FrontEntry* next_entries, uint32_t* next_states,

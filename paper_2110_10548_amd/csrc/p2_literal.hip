@@ -1744,15 +1744,9 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
 }
 
 // The state of the class kernels holds up to 64 classes of rows; entries that would need more are evaluated
-// on the full literal state.  P2_ROW_CLASSES (1..63) lowers the limit, so that tests can send entries down
-// that path.
-static int row_class_cap() {
-    if (const char* env = std::getenv("P2_ROW_CLASSES")) {
-        const int v = std::atoi(env);
-        if (v >= 1 && v < 64) return v;
-    }
-    return 64;
-}
+// on the full literal state.  A caller may lower the limit (p2_options.max_row_classes), which sends entries
+// down that path.
+static int row_class_cap(int asked) { return asked >= 1 && asked < 64 ? asked : 64; }
 
 // Scratch of launch_front_classify_literal: the slices of the full-state kernel (where that state does not
 // fit in LDS), the slices of the class kernel (likewise), the list of the entries left to the former.
@@ -1784,7 +1778,7 @@ size_t front_literal_scratch_bytes(int R, int k, uint32_t n) { return front_lite
 
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
-                                         void* gscratch, hipStream_t stream) {
+                                         void* gscratch, int class_cap_asked, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!gscratch) return hipErrorInvalidValue;
     const FrontLiteralScratch sc = front_literal_scratch(R, k, n);
@@ -1795,7 +1789,7 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     const unsigned cls_blocks = sc.cls_blocks < n ? sc.cls_blocks : n, full_blocks = sc.full_blocks < n ? sc.full_blocks : n;
     const unsigned long long cls_words_per = sc.cls_per / 4;
     const unsigned long long full_words_per = sc.full_lds ? 0ull : sc.full_bytes / sc.full_blocks / 4;
-    const int class_cap = row_class_cap();
+    const int class_cap = row_class_cap(class_cap_asked);
     hipError_t e = hipSuccess;
     // first on the class state; what needs more classes than that holds, on the full literal state
 #define P2_LAUNCH(MWV)                                                                                         \
@@ -1833,7 +1827,7 @@ size_t literal_group_scratch_bytes(int max_R, int max_k, unsigned* blocks) {
 }
 
 hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_t* qlist, int n_q, int max_R, int max_k,
-                                           void* gscratch, hipStream_t stream) {
+                                           void* gscratch, int class_cap_asked, hipStream_t stream) {
     if (n_q == 0) return hipSuccess;
     if (!gscratch || max_R > 64) return hipErrorInvalidValue;
     const size_t lds = (size_t)cls_words(max_R, max_k, mask_words(max_R)) * 4;
@@ -1841,7 +1835,7 @@ hipError_t launch_eval_literal_groups_auto(const DevQuery* queries, const int32_
     const unsigned long long gwords = literal_group_scratch_bytes(max_R, max_k, &blocks) / blocks / 4;
     const int cls_backup = cls_backup_words(max_R, max_k, mask_words(max_R));
     // (64 classes are all that power-of-two groups can produce)
-    const int class_cap = row_class_cap();
+    const int class_cap = row_class_cap(class_cap_asked);
     hipError_t e = hipSuccess;
 #define P2_LAUNCH(MWV)                                                                                         \
     e = allow_big_lds(k_eval_literal_groups_auto<MWV>, lds);                                                   \

@@ -558,6 +558,15 @@ def test_caller_stream_and_host_threads(B, oracle):
             for g, w in zip(res, want):
                 assert g["programs"]["index"].tolist() == w["programs"]["index"].tolist()
                 assert np.allclose(g["cost"], w["cost"], rtol=RTOL, atol=0.0)
+    # (the three threads have ended and given their device caches back; this thread does so on request and
+    # its next call allocates afresh)
+    free_before = torch.cuda.mem_get_info()[0]
+    B.p2_release_thread()
+    assert torch.cuda.mem_get_info()[0] >= free_before
+    again = B.p2_synthesize_batch(queries, msg)
+    for g, w in zip(again, want):
+        assert g["programs"]["index"].tolist() == w["programs"]["index"].tolist()
+        assert (g["cost"] == w["cost"]).all()
 
 
 # --------------------------------------------------------------------------- full-size configurations 3 and 4
@@ -607,23 +616,21 @@ def test_alphabet_above_one_wavefront(B, oracle, engine):
     assert res["stats"]["steps_executed"] == steps
 
 
-@pytest.mark.parametrize("classes", ["1", "3"])
-def test_handed_over_groups_beyond_the_class_limit(B, oracle, classes, monkeypatch):
+@pytest.mark.parametrize("classes", [1, 3])
+def test_handed_over_groups_beyond_the_class_limit(B, oracle, classes):
     """The groups that the shared-prefix engine hands over are evaluated on classes of equal rows; an entry that
     needs more classes than the state holds falls back to the full literal state.  With power-of-two groups
     the real limit (64) is never reached, so the limit is lowered here: stems and groups then take the
     fallback at the first ReduceScatter (limit 1) or at a later one (limit 3), and the results stay the same.
     The frontier engine keeps its literal prefixes the same way and sends those beyond the limit to the kernel
     that rebuilds the full literal state."""
-    monkeypatch.setenv("P2_ROW_CLASSES", classes)
     cfg, queries = queries_of(2, B)
     cfg3 = workloads.config(3)
     pl3 = B.p2_enumerate_placements(cfg3["card"], cfg3["axes"])
     q3 = [dict(q, max_len=4) for q in workloads.expand(cfg3, pl3) if q["reduce_axes"] == [1, 2]][:2]   # 32 devices, 64 chunks
     batch = [dict(q, engine=5) for q in queries + q3]
     batch += [dict(q, engine=3) for q in queries[::9] + q3[:1]]      # the frontier engine's literal prefixes as well
-    limited = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
-    monkeypatch.delenv("P2_ROW_CLASSES")
+    limited = B.p2_synthesize_batch([dict(q, max_row_classes=classes) for q in batch], cfg["msg_bytes"])
     usual = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
     handed = 0
     for q, res, ref in zip(batch, limited, usual):
@@ -653,15 +660,14 @@ def test_costs_of_large_reduction_groups(B, oracle, card, axes, k, algo):
 
 
 @pytest.mark.parametrize("engine", [0, 2, 4, 1], ids=["auto", "compact", "small", "literal"])
-def test_equal_queries_are_evaluated_once(B, oracle, engine, monkeypatch):
+def test_equal_queries_are_evaluated_once(B, oracle, engine):
     """Queries of a batch with the same reduction group, chunks, patterns, alphabet and size limit share one
     evaluation (validity does not depend on the links or on where the placement puts the group); lists, costs and
-    per-candidate step counts are those of every query evaluated on its own (P2_EVALUATE_EVERY_QUERY=1)."""
+    per-candidate step counts are those of every query evaluated on its own (P2_FLAG_EVALUATE_EVERY_QUERY)."""
     cfg, queries = queries_of(2 if engine != 1 else 1, B)
     batch = [dict(q, engine=engine) for q in queries]
     shared = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
-    monkeypatch.setenv("P2_EVALUATE_EVERY_QUERY", "1")
-    alone = B.p2_synthesize_batch(batch, cfg["msg_bytes"])
+    alone = B.p2_synthesize_batch([dict(q, flags=B.FLAG_EVALUATE_EVERY_QUERY) for q in batch], cfg["msg_bytes"])
     for q, a, b in zip(batch, shared, alone):
         _, ora = oracle_result(oracle, q, cfg["msg_bytes"])
         assert_same(a, ora, len(cfg["msg_bytes"]))
