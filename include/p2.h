@@ -270,6 +270,18 @@ int32_t p2_topk(const double* cost, const uint64_t* index, int64_t n, int32_t k,
 int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
                        int64_t* out_pos, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): p2_topk_device with its intermediate lists in a fixed 3 MiB array of the
+ * library's device image instead of library-allocated scratch.  Calls no hipMalloc / hipFree / pinned-memory
+ * routine, only queues kernels on `stream` and returns without waiting: out_pos (device, min(k, n)
+ * entries) is complete once the stream has passed this point.  out_nan (device uint32, may be NULL) is
+ * set to 0 by the call and to 1 by its kernels when a cost is NaN (NaN entries are then left out and
+ * trailing positions are -1); nothing is reported to the host.  k > 64 => P2_EUNSUPPORTED.
+ * Every GPU holds one copy of the array until the process ends and all calls on a GPU share it: calls that
+ * overlap on one GPU (different streams or host threads) race; calls on one stream are safe. */
+int32_t p2_topk_device_noalloc(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
+                               int64_t* out_pos, uint32_t* out_nan, void* stream);
+
 /* Timing of the calling thread's last p2_synthesize / p2_synthesize_batch call, taken with HIP
  * events on the call's stream.  Off by default; p2_set_profiling(1) turns the events on. */
 typedef struct {

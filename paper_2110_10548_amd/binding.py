@@ -65,7 +65,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak", "p2_release_thread")
+           "p2_topk_device", "p2_topk_device_noalloc", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak", "p2_release_thread")
 
 _lib = None
 
@@ -105,6 +105,9 @@ def lib():
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
         L.p2_topk_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.p2_topk_device_noalloc.restype = C.c_int32
+        L.p2_topk_device_noalloc.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]
         L.p2_release_thread.restype = C.c_int32
         L.p2_release_thread.argtypes = []
         L.p2_set_profiling.restype = C.c_int32
@@ -356,3 +359,8 @@ def p2_topk(cost, index, k):
 def p2_topk_device(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, stream=None):
     """Device pointers (e.g. torch tensor .data_ptr()); out_pos: int64[min(k, n)] on the device."""
     _check(lib().p2_topk_device(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, stream))
+
+
+def p2_topk_device_noalloc(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, out_nan_ptr=None, stream=None):
+    """Same on the library's fixed scratch (k <= 64): only queues kernels; synchronise the stream before reading."""
+    _check(lib().p2_topk_device_noalloc(cost_ptr, cost_stride, index_ptr, n, k, out_pos_ptr, out_nan_ptr, stream))

@@ -1183,6 +1183,18 @@ int32_t p2_topk_device(const double* cost, int64_t cost_stride, const uint64_t* 
     return P2_OK;
 }
 
+int32_t p2_topk_device_noalloc(const double* cost, int64_t cost_stride, const uint64_t* index, int64_t n, int32_t k,
+                               int64_t* out_pos, uint32_t* out_nan, void* stream_) {
+    using namespace p2;
+    if (n < 0 || k < 0 || cost_stride < 1) return fail(P2_EINVAL, "bad n, k or stride");
+    if (k > topk_fixed_max_k()) return fail(P2_EUNSUPPORTED, "topk > 64 without allocation: the fixed scratch holds lists of at most 64 entries");
+    if (n == 0 || k == 0) return P2_OK;
+    if (!cost || !index || !out_pos) return fail(P2_EINVAL, "null argument");
+    P2_HIP(launch_topk_fixed(cost, cost_stride, reinterpret_cast<const unsigned long long*>(index), n, k,
+                             reinterpret_cast<long long*>(out_pos), out_nan, (hipStream_t)stream_));
+    return P2_OK;
+}
+
 int32_t p2_topk(const double* cost, const uint64_t* index, int64_t n, int32_t k, int64_t* out_pos) {
     using namespace p2;
     if (n < 0 || k < 0) return fail(P2_EINVAL, "bad n or k");

@@ -300,4 +300,11 @@ size_t topk_scratch_bytes(long long n, int k);
 hipError_t launch_topk(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
                        long long* out_pos, void* scratch, uint32_t* nan_flag, hipStream_t stream);
 
+// The same selection with the stage-1 lists in a fixed array of the device image (no allocation): k at most
+// topk_fixed_max_k(); nan_flag (device, may be null) is cleared and then set to 1 when a cost is NaN.
+// Only queues kernels.  hipErrorInvalidValue when k is too large.
+int topk_fixed_max_k();
+hipError_t launch_topk_fixed(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
+                             long long* out_pos, uint32_t* nan_flag, hipStream_t stream);
+
 }  // namespace p2

@@ -2,6 +2,8 @@
 // (cost, index) pairs by wavefront-level filtered insertion (the simulator's shortlist, Sec. 5).
 #include "p2_device.h"
 
+#include <mutex>
+
 namespace p2 {
 
 namespace {
@@ -253,6 +255,60 @@ hipError_t launch_topk(const double* cost, long long stride, const unsigned long
     const long long n_out = k < n ? k : n;
     hipLaunchKernelGGL(k_topk_merge, dim3(1), dim3(kWave), lds, stream, pc, pi, pp, (long long)blocks * k, k, out_pos, n_out);
     return hipGetLastError();
+}
+
+// ---- selection without any allocation ------------------------------------------------------------
+// The two-stage selection keeps its stage-1 lists (blocks x k entries of 24 bytes) in device memory.  For
+// callers that may not allocate, that memory is a fixed array in the library's device image: every GPU the
+// library runs on holds its own copy at its own address for the life of the process, and all calls on one
+// GPU share it.  Host code never uses the array's name as an address: the device address is asked for once
+// per device and kept.
+constexpr int kFixedTopkMaxK = 64;
+constexpr size_t kFixedTopkListBytes = (size_t)2048 * kFixedTopkMaxK * 24;     // topk_blocks() <= 2048
+static __device__ __align__(256) unsigned char scratch[kFixedTopkListBytes + 256];   // lists, then a flag word
+
+namespace {
+constexpr int kMaxGpus = 64;
+std::mutex g_fixed_mutex;
+void* g_fixed_ptr[kMaxGpus] = {nullptr};
+
+__global__ void k_clear_word(uint32_t* w) { *w = 0u; }
+
+// Device address of `scratch` on the current device.
+hipError_t fixed_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxGpus) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_fixed_mutex);
+    if (!g_fixed_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_fixed_ptr[dev] = p;
+    }
+    *out = g_fixed_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+int topk_fixed_max_k() { return kFixedTopkMaxK; }
+
+hipError_t launch_topk_fixed(const double* cost, long long stride, const unsigned long long* index, long long n, int k,
+                             long long* out_pos, uint32_t* nan_flag, hipStream_t stream) {
+    if (n <= 0 || k <= 0) return hipSuccess;
+    if (k > kFixedTopkMaxK || topk_scratch_bytes(n, k) > kFixedTopkListBytes) return hipErrorInvalidValue;
+    void* base = nullptr;
+    hipError_t e = fixed_scratch(&base);
+    if (e != hipSuccess) return e;
+    // the flag starts at zero for this call (a fill kernel, so that the call can be recorded into a graph)
+    uint32_t* flag = nan_flag ? nan_flag : reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(base) + kFixedTopkListBytes);
+    hipLaunchKernelGGL(k_clear_word, dim3(1), dim3(1), 0, stream, flag);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // (stage 1 writes every slot of the lists it hands to stage 2, so the lists need no clearing)
+    return launch_topk(cost, stride, index, n, k, out_pos, base, flag, stream);
 }
 
 }  // namespace p2
