@@ -36,6 +36,52 @@ def assert_same(res, ora, n_msg):
         assert np.allclose(res["cost"], ora["cost"], rtol=RTOL, atol=0.0)
 
 
+def in_threads(fn, items, workers=None):
+    """fn over items on host threads (the oracle's C routines run outside the interpreter lock)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    workers = workers or max(1, min(16, len(os.sched_getaffinity(0))))
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        return list(pool.map(fn, items))
+
+
+def oracle_query(oracle, q):
+    return oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q.get("bw"), alpha=q.get("alpha"),
+                        n_chunks=q.get("n_chunks", 0), algo=q.get("algo", 0))
+
+
+def check_listed_programs(oracle, q, res, rows, msg, probe_unlisted=()):
+    """Rows of a result against the oracle one by one: the listed program is the unranked index, valid, at the
+    oracle's cost; indices in probe_unlisted are invalid."""
+    oq = oracle_query(oracle, q)
+    progs = res["programs"]
+    for i in rows:
+        instr = progs["instr"][i][:progs["len"][i]].tolist()
+        assert oq.unrank(q["max_len"], int(progs["index"][i])) == instr
+        ok, cost, _ = oq.eval_program(instr, msg)
+        assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL, atol=0.0), (q["placement"], q["reduce_axes"], instr)
+    if len(probe_unlisted):
+        nvalid, _, _ = oq.eval_indices(q["max_len"], indices=list(probe_unlisted), n_threads=1)
+        assert nvalid == 0
+    return True
+
+
+def check_shortlist(top, full, n_msg, k):
+    """A query's shortlist (run with topk = k) against its own full list (run with topk = 0): for every message
+    size the k smallest (cost, index) pairs in that order, programs and all their costs copied unchanged."""
+    idx, cost = full["programs"]["index"], full["cost"]
+    kk = min(k, len(idx))
+    assert len(top["programs"]) == kk * n_msg
+    pos_of = {int(ix): i for i, ix in enumerate(idx)}
+    for m in range(n_msg):
+        want = np.lexsort((idx, cost[:, m]))[:kk]
+        got = top["programs"][m * kk:(m + 1) * kk]
+        assert got["index"].tolist() == idx[want].tolist()
+        rows = [pos_of[int(ix)] for ix in got["index"]]
+        assert (got["instr"] == full["programs"]["instr"][rows]).all() and (got["len"] == full["programs"]["len"][rows]).all()
+        assert (top["cost"][m * kk:(m + 1) * kk] == cost[rows]).all()
+
+
 def queries_of(cfg_id, B):
     cfg = workloads.config(cfg_id)
     pls = B.p2_enumerate_placements(cfg["card"], cfg["axes"])
@@ -577,28 +623,19 @@ def _levels(q):
     return sum(1 for v in f if v > 1)
 
 
-@pytest.mark.parametrize("levels", [1, 2, 3])
-def test_config3_every_query(B, oracle, levels):
-    """64 devices, 64-bit masks, every placement x every non-empty reduce-axis subset, length <= 5
-    (up to 1.9e8 candidates per query), all queries with `levels` non-unit hierarchy levels at once."""
+def test_config3_every_query(B, oracle):
+    """64 devices, 64-bit masks, every placement x every non-empty reduce-axis subset, length <= 5 (up to
+    1.9e8 candidates per query): the 84 queries as one batch, every one of them compared with the oracle
+    element by element (lists and costs; the oracle enumerates the 32 three-level queries in about a second
+    each, on host threads)."""
     cfg, queries = queries_of(3, B)
     assert len(queries) == 84
-    mine = [q for q in queries if _levels(q) == levels]
-    assert len(mine) == {1: 20, 2: 32, 3: 32}[levels]
-    results = B.p2_synthesize_batch(mine, cfg["msg_bytes"])
-    want_valid = {1: 3, 2: 110, 3: 2549}[levels]
-    cache = {}
-    for q, res in zip(mine, results):
-        assert res["stats"]["valid"] == want_valid
-        # the oracle works on the full 64-device system; queries whose lowered groups coincide
-        # (same reduce-axis factors per level, same placement of the other axes) are not recomputed
-        key = (tuple(map(tuple, q["placement"])), tuple(q["reduce_axes"]))
-        if levels == 3 and len(cache) >= 6 and key not in cache:
-            continue                       # 6 three-level queries checked element by element (~1 s each)
-        if key not in cache:
-            cache[key] = oracle_result(oracle, q, cfg["msg_bytes"])[1]
-        assert_same(res, cache[key], 1)
-    assert len(cache) >= 6
+    assert sorted(_levels(q) for q in queries) == [1] * 20 + [2] * 32 + [3] * 32
+    results = B.p2_synthesize_batch(queries, cfg["msg_bytes"])
+    oracles = in_threads(lambda q: oracle_result(oracle, q, cfg["msg_bytes"])[1], queries)
+    for q, res, ora in zip(queries, results, oracles):
+        assert res["stats"]["valid"] == {1: 3, 2: 110, 3: 2549}[_levels(q)] == len(ora["index"])
+        assert_same(res, ora, 1)
 
 
 @pytest.mark.parametrize("engine", [5, 2], ids=["shared", "compact"])
@@ -706,60 +743,114 @@ def test_config3_literal_engine_small_queries(B, oracle):
         assert_same(res, oracle_result(oracle, q, cfg["msg_bytes"])[1], 1)
 
 
-def test_config4_chunk_granularities_and_topk(B, oracle):
-    """256 devices, reduction groups of 64, chunk counts 1 / 8 / 64 / 256, top-10."""
+def test_config4_every_query(B, oracle):
+    """256 devices, reduction groups of 64, chunk counts 1 / 8 / 64 / 256, top-10: the 140 queries as the
+    configuration states them (one batch, shortlists of 10) and once more with full lists.
+    Full lists against the oracle element by element for k = 1, 8 and 64 on every placement and for k = 256 on
+    three placements (the oracle needs half a minute for one of those); the other k = 256 lists must equal
+    the k = 64 ones (k a multiple of the group size) and have 300 sampled programs and 2 000 unlisted indices
+    checked one by one on three further placements.  Every shortlist against its query's full list."""
     cfg, queries = queries_of(4, B)
+    msg = cfg["msg_bytes"]
     assert len(queries) == 140
-    by_pl = {}
-    for q in queries:
-        by_pl.setdefault(q["placement_index"], []).append(q)
-    two_level = [p for p, qs in by_pl.items() if _levels(qs[0]) == 2]
-    three_level = [p for p, qs in by_pl.items() if _levels(qs[0]) == 3]
-    assert len(two_level) == 4 and len(three_level) == 31
-    # (a) a two-level placement: all four chunk counts, full lists against the oracle
-    qs = [dict(q, topk=0) for q in by_pl[two_level[0]]]
-    for q, res in zip(qs, B.p2_synthesize_batch(qs, cfg["msg_bytes"])):
-        assert_same(res, oracle_result(oracle, q, cfg["msg_bytes"])[1], 1)
-    # (b) a three-level placement, k = 1 and 8: full lists and the top-10 against the oracle
-    qs = [dict(q, topk=0) for q in by_pl[three_level[0]] if q["n_chunks"] in (1, 8)]
-    full = B.p2_synthesize_batch(qs, cfg["msg_bytes"])
-    top = B.p2_synthesize_batch([dict(q, topk=10) for q in qs], cfg["msg_bytes"])
-    for q, res, tp in zip(qs, full, top):
-        ora = oracle_result(oracle, q, cfg["msg_bytes"])[1]
-        assert_same(res, ora, 1)
-        want = oracle.topk(ora["cost"][:, 0], ora["index"], 10)
-        assert np.allclose(np.sort(tp["cost"][:, 0]), ora["cost"][want, 0], rtol=RTOL)
-        assert set(tp["programs"]["index"].tolist()) <= set(ora["index"].tolist())
-
-
-def test_config4_full_size_sampled(B, oracle):
-    """k = 64 and k = 256 on a three-level placement (1.9e8 candidates each): the oracle needs
-    about a minute for the whole list at k = 256, so outputs are checked one by one: every program
-    the GPU lists is valid for the oracle with the same cost, sampled unlisted indices are invalid."""
-    cfg, queries = queries_of(4, B)
-    qs = [dict(q, topk=0) for q in queries if _levels(q) == 3 and q["n_chunks"] in (64, 256)][:2]
-    assert [q["n_chunks"] for q in qs] == [64, 256]
-    res64, res256 = B.p2_synthesize_batch(qs, cfg["msg_bytes"])
-    assert res64["stats"]["valid"] == res256["stats"]["valid"] == 2549
-    assert res64["programs"]["index"].tolist() == res256["programs"]["index"].tolist()
+    levels = [_levels(q) for q in queries]
+    assert levels.count(2) == 16 and levels.count(3) == 124
+    top = B.p2_synthesize_batch(queries, msg)
+    full = B.p2_synthesize_batch([dict(q, topk=0) for q in queries], msg)
+    for q, t, f in zip(queries, top, full):
+        check_shortlist(t, f, len(msg), 10)
+    big = [i for i, q in enumerate(queries) if q["n_chunks"] == 256 and levels[i] == 3]
+    whole = [i for i, q in enumerate(queries) if q["n_chunks"] != 256 or levels[i] == 2] + big[::13][:3]
+    # the long oracle runs first, so that the threads end together
+    whole.sort(key=lambda i: -queries[i]["n_chunks"] * levels[i])
+    oracles = in_threads(lambda i: oracle_result(oracle, queries[i], msg)[1], whole)
+    for i, ora in zip(whole, oracles):
+        assert_same(full[i], ora, 1)
+        if queries[i]["n_chunks"] >= 64:       # (fewer chunks than devices in the group: scatters drop out by divisibility)
+            assert len(ora["index"]) == {3: 2549, 2: 110}[levels[i]]
+    by_pl = {(q["placement_index"], q["n_chunks"]): i for i, q in enumerate(queries)}
+    for i in big:
+        j = by_pl[(queries[i]["placement_index"], 64)]
+        assert full[i]["programs"]["index"].tolist() == full[j]["programs"]["index"].tolist()
+        assert (full[i]["programs"]["instr"] == full[j]["programs"]["instr"]).all()
     rng = np.random.default_rng(4)
-    for q, res in ((qs[0], res64), (qs[1], res256)):
-        oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
-                          n_chunks=q["n_chunks"])
-        progs = res["programs"]
-        pick = rng.choice(len(progs), size=60 if q["n_chunks"] == 256 else 300, replace=False)
-        for i in pick:
-            instr = progs["instr"][i][:progs["len"][i]].tolist()
-            assert oq.unrank(q["max_len"], int(progs["index"][i])) == instr
-            ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
-            assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
-        listed = set(progs["index"].tolist())
-        N = oq.num_candidates(q["max_len"])
+    jobs = []
+    for i in [b for b in big if b not in whole][::9][:3]:
+        q, res = queries[i], full[i]
+        listed = set(res["programs"]["index"].tolist())
+        N = full[i]["stats"]["candidates"]
+        pick = rng.choice(len(res["programs"]), size=300, replace=False)
         probe = [int(v) for v in rng.integers(0, N, size=2000) if int(v) not in listed]
         # neighbours of valid programs are the likeliest false negatives
-        probe += [int(ix) + d for ix in progs["index"][pick[:40]] for d in (-1, 1) if int(ix) + d not in listed and 0 <= int(ix) + d < N]
-        nvalid, _, _ = oq.eval_indices(q["max_len"], indices=probe, n_threads=8)
-        assert nvalid == 0
+        probe += [int(ix) + d for ix in res["programs"]["index"][pick[:100]] for d in (-1, 1) if int(ix) + d not in listed and 0 <= int(ix) + d < N]
+        for part in range(15):
+            jobs.append((q, res, pick[part::15].tolist(), probe[part::15]))
+    assert len(jobs) == 45
+    assert all(in_threads(lambda j: check_listed_programs(oracle, j[0], j[1], j[2], msg, j[3]), jobs))
+
+
+# --------------------------------------------------------------------------- configuration 5
+def test_config5_every_query(B, oracle):
+    """512 devices, size limit 6, 512 random (placement, reduce-axis subset) queries, top-10: the whole
+    configuration as it is stated (one batch, shortlists of 10) and once more with full lists (13.7 M programs).
+    On all 512 queries: valid counts (one to four levels: 3, 110, 6 794 and 83 920, the oracle's own counts on
+    small systems with as many levels), ascending indices, equal lists for queries that are the same
+    (placement, reduction), the shortlist against the query's own full list, and every entry of every
+    shortlist valid for the oracle at the oracle's cost.  The oracle works on literal 512 x 512 x 512-bit
+    states, so beyond that it checks outputs one by one, on host threads: for one query of every
+    (group size, levels) class 100 listed programs (unranked program, validity, cost) and the unlisted
+    neighbours of their indices; no program of the sample may be cheaper than the tenth of the shortlist."""
+    cfg, queries = queries_of(5, B)
+    msg = cfg["msg_bytes"]
+    assert len(queries) == 512
+    top = B.p2_synthesize_batch(queries, msg)
+    full = B.p2_synthesize_batch([dict(q, topk=0) for q in queries], msg)
+    count_of = {1: 3, 2: 110, 4: 83920}
+    count_of[3] = len(oracle.Query([2, 2, 2], [8], [[2, 2, 2]], [0]).synthesize(6)["index"])
+    assert count_of[3] == 6794
+    assert len(oracle.Query([2, 2, 2, 2], [16], [[2, 2, 2, 2]], [0]).synthesize(6)["index"]) == count_of[4]
+    twins, classes = {}, {}
+    for n, (q, t, f) in enumerate(zip(queries, top, full)):
+        L = _levels(q)
+        if L == 0:
+            assert f["stats"]["candidates"] == 0 and len(f["programs"]) == 0 and len(t["programs"]) == 0
+            continue
+        assert f["stats"]["valid"] == t["stats"]["valid"] == count_of[L] == len(f["programs"])
+        assert (np.diff(f["programs"]["index"].astype(np.int64)) > 0).all()
+        check_shortlist(t, f, 1, 10)
+        key = (tuple(map(tuple, q["placement"])), tuple(q["reduce_axes"]))
+        if key in twins:
+            o = full[twins[key]]
+            assert (f["programs"] == o["programs"]).all() and (f["cost"] == o["cost"]).all()
+        twins.setdefault(key, n)
+        classes.setdefault((f["stats"]["group_size"], L), n)
+    assert len(classes) == 20 and {L for _, L in classes} == {1, 2, 3, 4} and max(R for R, _ in classes) == 512
+    rng = np.random.default_rng(5)
+    jobs = []
+    for n in sorted(twins.values()):                       # the shortlist of every distinct query
+        jobs += [(queries[n], top[n], [i], []) for i in range(len(top[n]["programs"]))]
+    sampled = {}
+    for (R, L), n in sorted(classes.items(), key=lambda kv: -kv[0][0]):     # the slow ones first
+        q, f, t = queries[n], full[n], top[n]
+        listed = set(f["programs"]["index"].tolist())
+        pick = rng.choice(len(f["programs"]), size=min(100, len(f["programs"])), replace=False)
+        sampled[n] = pick
+        near = [int(ix) + d for ix in f["programs"]["index"][pick] for d in (-1, 1)
+                if int(ix) + d not in listed and 0 <= int(ix) + d < f["stats"]["candidates"]]
+        for i in pick:
+            jobs.append((q, f, [int(i)], []))
+        for part in range(0, len(near), 8):
+            jobs.append((q, f, [], near[part:part + 8]))
+    import time
+    t0 = time.time()
+    assert all(in_threads(lambda j: check_listed_programs(oracle, j[0], j[1], j[2], msg, j[3]), jobs))
+    print("config 5: %d oracle jobs (%d programs, %d unlisted indices) in %.1f s" % (
+        len(jobs), sum(len(j[2]) for j in jobs), sum(len(j[3]) for j in jobs), time.time() - t0), flush=True)
+    for n, pick in sampled.items():
+        tenth = top[n]["cost"][-1, 0]
+        listed = set(top[n]["programs"]["index"].tolist())
+        for i in pick:
+            assert full[n]["cost"][i, 0] >= tenth or int(full[n]["programs"]["index"][i]) in listed
 
 
 # --------------------------------------------------------------------------- frontier engine (enumeration by size, Sec. 3.5)
@@ -788,58 +879,3 @@ def test_frontier_matches_flat_engine_on_config3_sample(B):
         assert (a["programs"]["instr"] == b["programs"]["instr"]).all()
         assert np.allclose(a["cost"], b["cost"], rtol=1e-12)
         assert b["stats"]["engine"] == 3 and b["stats"]["steps_executed"] < a["stats"]["steps_executed"]
-
-
-def test_config5_sampled(B, oracle):
-    """512 devices, size limit 6, random (placement, reduce-axis subset) queries: the frontier engine
-    produces the full lists; the oracle (literal 512 x 512 x 512-bit states, ~0.1 s per instruction)
-    checks sampled outputs one by one: listed programs are valid with the same cost, sampled
-    unlisted indices next to them are invalid.  The first 40 of the 512 queries are run here (they
-    span one to four levels and reduction groups of 2 to 512 devices)."""
-    cfg, queries = queries_of(5, B)
-    assert len(queries) == 512
-    mine = [dict(q, topk=0) for q in queries[:40]]
-    results = B.p2_synthesize_batch(mine, cfg["msg_bytes"])
-    want = {1: 3, 2: 110, 3: None, 4: 83920}
-    rng = np.random.default_rng(5)
-    checked = 0
-    for q, res in zip(mine, results):
-        L = _levels(q)
-        if L == 0:
-            assert res["stats"]["candidates"] == 0
-            continue
-        if want[L] is not None:
-            assert res["stats"]["valid"] == want[L]
-        progs = res["programs"]
-        assert (np.diff(progs["index"].astype(np.int64)) > 0).all()
-        if checked >= 6 or len(progs) == 0:
-            continue
-        checked += 1
-        oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"])
-        for i in rng.choice(len(progs), size=min(3, len(progs)), replace=False):
-            instr = progs["instr"][i][:progs["len"][i]].tolist()
-            assert oq.unrank(q["max_len"], int(progs["index"][i])) == instr
-            ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
-            assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
-            listed = set(progs["index"].tolist())
-            near = [int(progs["index"][i]) + d for d in (-1, 1) if int(progs["index"][i]) + d not in listed]
-            nvalid, _, _ = oq.eval_indices(q["max_len"], indices=near, n_threads=2)
-            assert nvalid == 0
-    assert checked >= 4
-    # queries that agree in reduction group, chunks, patterns and alphabet take over the first one's list
-    # inside the library; their costs stay their own: check the last such query against the oracle too
-    seen, twin = {}, None
-    for n, (q, res) in enumerate(zip(mine, results)):
-        key = (res["stats"]["group_size"], res["stats"]["n_patterns"], res["stats"]["alphabet"], _levels(q))
-        if key in seen and key[3] >= 2:
-            assert res["programs"]["index"].tolist() == results[seen[key]]["programs"]["index"].tolist()
-            twin = n
-        seen.setdefault(key, n)
-    assert twin is not None
-    q, res = mine[twin], results[twin]
-    progs = res["programs"]
-    oq = oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"])
-    for i in rng.choice(len(progs), size=2, replace=False):
-        instr = progs["instr"][i][:progs["len"][i]].tolist()
-        ok, cost, _ = oq.eval_program(instr, cfg["msg_bytes"])
-        assert ok and np.allclose(cost, res["cost"][i], rtol=RTOL)
