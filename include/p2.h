@@ -129,9 +129,22 @@ typedef struct {
                             the fall-back path, which is what tests of that path set it for).
                             Kernels that serve several queries use the smallest limit among
                             them.  Outside 0..64 => P2_EINVAL                                    */
-    int32_t reserved;    /* must be 0                                                            */
+    int32_t frontier_pairs; /* P2_FRONTIER_PAIRS_*: state form of the frontier engine; 0 => the default  */
     void* hip_stream;    /* hipStream_t to run on; NULL => the default stream                    */
 } p2_options;
+
+/* p2_options.frontier_pairs.  The frontier engine keeps a prefix's state as up to two (chunk set, mask)
+ * pairs per device and hands what that form cannot hold to kernels that rebuild the literal state from the
+ * prefix's instructions.  Results do not depend on the choice; the other values exist so that every path
+ * can be run on purpose. */
+#define P2_FRONTIER_PAIRS_AUTO 0          /* two pairs where two planes of the state fit in LDS, else one    */
+#define P2_FRONTIER_PAIRS_ONE 1           /* one pair per device; a prefix that needs two goes to the literal kernels */
+#define P2_FRONTIER_PAIRS_TWO 2           /* as AUTO                                                          */
+#define P2_FRONTIER_PAIRS_TWO_HANDOVER 3  /* two pairs are kept, but every two-pair prefix is classified by the
+                                             literal kernels (the path of prefixes whose groups split their rows
+                                             differently)                                                    */
+#define P2_FRONTIER_PAIRS_NONE 4          /* no pair states: every prefix is a literal prefix, and valid programs
+                                             are costed by re-running them                                   */
 
 /* p2_options.flags */
 #define P2_FLAG_EVALUATE_EVERY_QUERY 1u   /* p2_synthesize_batch: do not share the evaluation of queries

@@ -32,7 +32,7 @@ class p2_hierarchy(C.Structure):
 class p2_options(C.Structure):
     _fields_ = [("n_chunks", C.c_int32), ("form_mask", C.c_uint32), ("op_mask", C.c_uint32), ("algo", C.c_int32),
                 ("topk", C.c_int32), ("engine", C.c_int32), ("hierarchy", C.c_int32), ("flags", C.c_uint32),
-                ("max_row_classes", C.c_int32), ("reserved", C.c_int32), ("hip_stream", C.c_void_p)]
+                ("max_row_classes", C.c_int32), ("frontier_pairs", C.c_int32), ("hip_stream", C.c_void_p)]
 
 
 class p2_program(C.Structure):
@@ -155,9 +155,9 @@ FLAG_EVALUATE_EVERY_QUERY = 1
 
 
 def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None, hierarchy=0, flags=0,
-             max_row_classes=0):
+             max_row_classes=0, frontier_pairs=0):
     return p2_options(n_chunks, form_mask, op_mask, algo, topk, engine, HIERARCHY.get(hierarchy, hierarchy), flags,
-                      max_row_classes, 0, stream)
+                      max_row_classes, frontier_pairs, stream)
 
 
 def p2_enumerate_placements(card, axes):
@@ -210,7 +210,7 @@ class Batch:
             axes, pl, red = _i32(q["axes"]), _i32(q["placement"]), _i32(q["reduce_axes"])
             opt = _options(q.get("n_chunks", 0), q.get("form_mask", 7), q.get("op_mask", 31), q.get("algo", 0), q.get("topk", 0),
                            q.get("engine", ENGINE_AUTO), stream, q.get("hierarchy", 0), q.get("flags", 0),
-                           q.get("max_row_classes", 0))
+                           q.get("max_row_classes", 0), q.get("frontier_pairs", 0))
             self._keep.append((h, axes, pl, red, opt))
             self._arr[i] = p2_query(C.pointer(h.c), _p(axes, C.c_int32), len(axes), _p(pl, C.c_int32), _p(red, C.c_int32),
                                     len(red), int(q["max_len"]), C.pointer(opt))
@@ -256,7 +256,7 @@ class Batch:
 
 def p2_synthesize_batch(queries, msg_bytes=(), cap=None, stream=None):
     """queries: list of dicts with card, bw, alpha, axes, placement, reduce_axes, max_len and optional
-    n_chunks, form_mask, op_mask, algo, topk, engine, hierarchy, flags, max_row_classes.  Returns a list of results, one per query:
+    n_chunks, form_mask, op_mask, algo, topk, engine, hierarchy, flags, max_row_classes, frontier_pairs.  Returns a list of results, one per query:
     {"programs": structured array, "cost": [n][n_msg], "stats": dict}."""
     b = Batch(queries, msg_bytes, stream)
     if cap is not None:

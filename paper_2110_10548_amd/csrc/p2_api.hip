@@ -76,11 +76,12 @@ struct Ctx {
     void release();
     DevBuf rows, rows_hdr;
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
-    DevBuf f_entries[2], f_states[2], f_literal[2], f_surv, f_surv_literal, f_ctr, f_valid;   // frontier engine
+    DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];   // frontier engine
+    DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, f_valid, f_gsums, f_rank, f_share;
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
     hipEvent_t copy_done = nullptr;
-    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs;
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs, h_fshare;
 };
 thread_local Ctx g_ctx;
 
@@ -101,9 +102,10 @@ const std::thread::id g_loader_thread = std::this_thread::get_id();
 void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
                      &topk_in, &topk_jobs, &lit_scratch, &post, &f_entries[0], &f_entries[1], &f_states[0], &f_states[1],
-                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_ctr, &f_valid};
+                     &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1], &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1],
+                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_unknown, &f_ctr, &f_valid, &f_gsums, &f_rank, &f_share};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
-    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs};
+    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs, &h_fshare};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
     if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
     if (copy_stream) { (void)hipStreamDestroy(copy_stream); copy_stream = nullptr; }
@@ -158,7 +160,7 @@ struct QueryRun {
     bool shared = false;                  // shared-prefix engine (the common instructions of a group applied once)
     bool auto_groups = false;             // its handed-over groups are picked up by the device-driven literal launch
     bool wave_cost = false;               // valid programs costed by the wavefront-per-program kernel
-    size_t off_fvalid = 0;                // frontier: element offset of its valid list in the frontier list buffer
+    int enum_id = -1, share_pos = 0;      // frontier: its enumeration, and its place among the enumeration's queries
     int topk = 0;
     size_t off_query = 0, off_rowptr = 0, off_rowlevel = 0, off_entries = 0;
     size_t off_goal = 0, off_rank = 0;    // hierarchies other than the collapsed one: goal masks, ranks of members
@@ -691,41 +693,63 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (attempt == 3) return fail(P2_EDEVICE, "result lists kept overflowing");
     }
 
-    // ---- frontier queries: enumeration by program size, one query at a time, one wait per level
-    size_t fvalid_used = 0;
+    // ---- frontier queries: enumeration by program size (Sec. 3.5).  Queries that agree in everything validity
+    //      depends on form one enumeration; its prefixes carry the running cost sums of every member query.
+    struct Enum {
+        int leader = -1;
+        std::vector<int32_t> members;
+        size_t off_valid = 0, off_sums = 0, off_share = 0;     // element offsets into f_valid / f_rank, f_gsums, f_share
+        uint32_t n_valid = 0, n_goal_literal = 0;
+    };
+    std::vector<Enum> enums;
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (!r.frontier) continue;
         const Plan& pl = r.plan;
-        r.off_fvalid = fvalid_used;
         r.n_valid = 0; r.n_rerun = 0; r.steps = 0; r.members = 0;
         if (pl.n_candidates == 0) continue;
-        // Validity depends on the reduction group, the chunks, the patterns and the alphabet only (not on
-        // the links, nor on where the placement puts the group in the system): a query that equals an
-        // earlier one of the batch in these takes over its list of valid programs and its counts.  Its
-        // costs are still worked out from its own bandwidth rows.
-        {
-            int same = -1;
-            for (int j = 0; j < i && same < 0 && share_validity; ++j) {
-                const Plan& o = runs[j].plan;
-                if (!runs[j].frontier || o.max_row_classes != pl.max_row_classes || o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet ||
-                    o.n_ops != pl.n_ops || o.patterns.size() != pl.patterns.size() || o.n_candidates != pl.n_candidates)
-                    continue;
-                bool eq = true;
-                for (int t = 0; t < pl.n_ops && eq; ++t) eq = o.ops[t] == pl.ops[t];
-                for (size_t t = 0; t < pl.patterns.size() && eq; ++t)
-                    eq = o.patterns[t].g == pl.patterns[t].g && o.patterns[t].s == pl.patterns[t].s &&
-                         o.patterns[t].master == pl.patterns[t].master && o.patterns[t].n_groups == pl.patterns[t].n_groups;
-                if (eq) same = j;
-            }
-            if (same >= 0) {
-                const QueryRun& o = runs[same];
-                r.off_fvalid = o.off_fvalid; r.n_valid = o.n_valid; r.n_rerun = o.n_rerun; r.steps = o.steps; r.members = o.members;
+        int found = -1;
+        for (size_t e = 0; e < enums.size() && found < 0 && share_validity; ++e) {
+            const Plan& o = runs[enums[e].leader].plan;
+            if (o.R != pl.R || o.k != pl.k || o.max_len != pl.max_len || o.alphabet != pl.alphabet || o.n_ops != pl.n_ops ||
+                o.patterns.size() != pl.patterns.size() || o.n_candidates != pl.n_candidates ||
+                o.max_row_classes != pl.max_row_classes || o.frontier_pairs != pl.frontier_pairs)
                 continue;
-            }
+            bool eq = true;
+            for (int t = 0; t < pl.n_ops && eq; ++t) eq = o.ops[t] == pl.ops[t];
+            for (size_t t = 0; t < pl.patterns.size() && eq; ++t)
+                eq = o.patterns[t].g == pl.patterns[t].g && o.patterns[t].s == pl.patterns[t].s &&
+                     o.patterns[t].master == pl.patterns[t].master && o.patterns[t].n_groups == pl.patterns[t].n_groups;
+            if (eq) found = (int)e;
         }
+        if (found < 0) { enums.emplace_back(); found = (int)enums.size() - 1; enums[found].leader = i; }
+        r.enum_id = found;
+        r.share_pos = (int)enums[found].members.size();
+        enums[found].members.push_back(i);
+    }
+    if (!enums.empty()) {
+        size_t n_share_all = 0;
+        for (auto& E : enums) { E.off_share = n_share_all; n_share_all += E.members.size(); }
+        P2_HIP(C.f_share.ensure(sizeof(int32_t) * n_share_all));
+        P2_HIP(C.h_fshare.ensure(sizeof(int32_t) * n_share_all));
+        for (auto& E : enums) std::memcpy(static_cast<int32_t*>(C.h_fshare.p) + E.off_share, E.members.data(), sizeof(int32_t) * E.members.size());
+        P2_HIP(hipMemcpyAsync(C.f_share.p, C.h_fshare.p, sizeof(int32_t) * n_share_all, hipMemcpyHostToDevice, stream));
+    }
+    size_t fvalid_used = 0, fsums_used = 0;
+    for (auto& E : enums) {
+        const int i = E.leader;
+        QueryRun& r = runs[i];
+        const Plan& pl = r.plan;
+        const int n_share = (int)E.members.size();
+        const size_t sum_doubles = n_msg > 0 ? (size_t)2 * n_share : 0;      // per prefix / per goal
+        E.off_valid = fvalid_used; E.off_sums = fsums_used;
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
         const size_t sw = frontier_state_words(pl.R, pl.k);
+        // state pairs per device: 2 where two planes fit in LDS; the option can lower it (1: as the compact form;
+        // 4: no pair states at all, every prefix on the literal list) or, with 3, have every two-pair prefix
+        // classified by the literal kernels (the path of prefixes whose groups are not aligned)
+        const int fp = pl.frontier_pairs;
+        const int max_pairs = fp == P2_FRONTIER_PAIRS_NONE ? 0 : fp == P2_FRONTIER_PAIRS_ONE ? 1 : frontier_max_pairs(pl.R, pl.k);
         P2_HIP(C.f_ctr.ensure(sizeof(FrontCounters)));
         P2_HIP(C.h_fctr.ensure(sizeof(FrontCounters)));
         FrontCounters* dctr = static_cast<FrontCounters*>(C.f_ctr.p);
@@ -734,60 +758,117 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         int cur = 0;
         P2_HIP(C.f_entries[cur].ensure(sizeof(FrontEntry)));
         P2_HIP(C.f_states[cur].ensure(sw * 4));
-        P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(C.f_entries[cur].p),
-                                 static_cast<uint32_t*>(C.f_states[cur].p), stream));
-        uint32_t n_c = 1, n_l = 0;
+        P2_HIP(C.f_sums[cur].ensure(std::max<size_t>(sum_doubles, 1) * 8));
+        P2_HIP(C.f_literal[cur].ensure(sizeof(FrontEntry)));
+        uint32_t n_c = 0, n_c2 = 0, n_l = 0;
+        if (max_pairs >= 1) {
+            P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(C.f_entries[cur].p),
+                                     static_cast<uint32_t*>(C.f_states[cur].p), static_cast<double*>(C.f_sums[cur].p),
+                                     (int)sum_doubles / 2, stream));
+            n_c = 1;
+        } else {
+            const FrontEntry root{(uint32_t)i, 0u, 0ull};
+            P2_HIP(hipMemcpyAsync(C.f_literal[cur].p, &root, sizeof root, hipMemcpyHostToDevice, stream));
+            P2_HIP(hipStreamSynchronize(stream));
+            n_l = 1;
+        }
         void* gs = nullptr;
-        for (int len = 0; len < pl.max_len && (n_c > 0 || n_l > 0); ++len) {
+        for (int len = 0; len < pl.max_len && (n_c > 0 || n_c2 > 0 || n_l > 0); ++len) {
             const int keep = len + 1 < pl.max_len ? 1 : 0;
-            size_t cap_c = std::max<size_t>(1024, (size_t)n_c * pl.alphabet / 8);
-            size_t cap_l = std::max<size_t>(1024, (size_t)n_l * pl.alphabet / 2);
+            size_t cap_c = std::max<size_t>(1024, ((size_t)n_c + n_c2) * pl.alphabet / 8);
+            size_t cap_l = std::max<size_t>(1024, ((size_t)n_l + n_c2 / 8) * pl.alphabet / 2);
+            uint32_t n_surv_l_first = 0;
+            P2_HIP(C.f_unknown.ensure(std::max<size_t>(n_c2, 1) * sizeof(FrontEntry)));
             for (;;) {     // classify; repeat with larger survivor lists if they overflow
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
                 P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, valid_written), stream));
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
-                                             static_cast<const uint32_t*>(C.f_states[cur].p), n_c,
-                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, dctr, stream));
+                                             static_cast<const uint32_t*>(C.f_states[cur].p), n_c, 1, max_pairs, 0,
+                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
+                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries2[cur].p),
+                                             static_cast<const uint32_t*>(C.f_states2[cur].p), n_c2,
+                                             2, max_pairs, fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0,
+                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
+                                             static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
                 if (n_l > 0) {
-                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, n_l)));
+                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
                     gs = C.lit_scratch.p;
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
-                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs, pl.max_row_classes, stream));
+                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
+                                                         pl.max_row_classes, stream));
                 }
                 P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                 P2_HIP(hipStreamSynchronize(stream));
+                n_surv_l_first = hctr->n_surv_literal;
+                if (hctr->n_unknown > 0 && hctr->n_surv_literal <= cap_l) {
+                    // two-pair prefixes that this form could not judge: the literal kernels classify them from their
+                    // instructions; their survivors follow those of the literal list
+                    const uint32_t n_u = hctr->n_unknown;
+                    P2_HIP(hipMemsetAsync(&dctr->n_overflow, 0, sizeof(uint32_t), stream));
+                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(std::max(n_l, n_c2), n_u))));
+                    gs = C.lit_scratch.p;
+                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_unknown.p), n_u, len,
+                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
+                                                         pl.max_row_classes, stream));
+                    P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
+                    P2_HIP(hipStreamSynchronize(stream));
+                }
                 if (hctr->n_surv <= cap_c && hctr->n_surv_literal <= cap_l) break;
                 // the repeated classification counts its steps again: take them back
-                cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, hctr->n_surv_literal);
+                cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, (size_t)hctr->n_surv_literal * 2);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
                 P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
                 P2_HIP(hipStreamSynchronize(stream));
             }
             const uint32_t n_surv = hctr->n_surv, n_surv_l = hctr->n_surv_literal;
-            const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_plit = hctr->n_prefix_literal;
+            const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_prefix2 = hctr->n_prefix2, n_plit = hctr->n_prefix_literal;
             r.steps = hctr->steps; r.members = hctr->members;
-            r.n_rerun += n_plit;
-            P2_HIP(grow_keep(C.f_valid, (fvalid_used + r.n_valid + n_goal + 1) * sizeof(unsigned long long),
-                             (fvalid_used + r.n_valid) * sizeof(unsigned long long), stream));
+            r.n_rerun += n_plit + hctr->n_unknown;
+            P2_HIP(grow_keep(C.f_valid, (fvalid_used + E.n_valid + n_goal + 1) * sizeof(unsigned long long),
+                             (fvalid_used + E.n_valid) * sizeof(unsigned long long), stream));
+            P2_HIP(grow_keep(C.f_gsums, (fsums_used + ((size_t)E.n_valid + n_goal) * sum_doubles + 1) * sizeof(double),
+                             (fsums_used + (size_t)E.n_valid * sum_doubles) * sizeof(double), stream));
             const int nxt = cur ^ 1;
             if (keep) {
                 P2_HIP(C.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
                 P2_HIP(C.f_states[nxt].ensure(std::max<size_t>(n_prefix, 1) * sw * 4));
+                P2_HIP(C.f_sums[nxt].ensure(std::max<size_t>((size_t)n_prefix * sum_doubles, 1) * 8));
+                P2_HIP(C.f_entries2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(FrontEntry)));
+                P2_HIP(C.f_states2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sw * 8));
+                P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
                 P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
             }
             unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used;
-            P2_HIP(launch_front_materialize(dq, (uint32_t)i, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
-                                            static_cast<const uint32_t*>(C.f_states[cur].p),
-                                            static_cast<const FrontSurvivor*>(C.f_surv.p), n_surv, len, keep,
-                                            static_cast<FrontEntry*>(C.f_entries[nxt].p), static_cast<uint32_t*>(C.f_states[nxt].p),
-                                            static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, dctr, stream));
+            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used;
+            FrontLevel lv;
+            std::memset(&lv, 0, sizeof lv);
+            lv.query = (uint32_t)i;
+            lv.share = static_cast<const int32_t*>(C.f_share.p) + E.off_share;
+            lv.n_share = n_share; lv.n_msg = n_msg;
+            lv.entries1 = static_cast<const FrontEntry*>(C.f_entries[cur].p); lv.states1 = static_cast<const uint32_t*>(C.f_states[cur].p);
+            lv.sums1 = static_cast<const double*>(C.f_sums[cur].p);
+            lv.entries2 = static_cast<const FrontEntry*>(C.f_entries2[cur].p); lv.states2 = static_cast<const uint32_t*>(C.f_states2[cur].p);
+            lv.sums2 = static_cast<const double*>(C.f_sums2[cur].p);
+            lv.surv = static_cast<const FrontSurvivor*>(C.f_surv.p); lv.n_surv = n_surv;
+            lv.parent_len = len; lv.keep_prefixes = keep;
+            lv.next_entries1 = static_cast<FrontEntry*>(C.f_entries[nxt].p); lv.next_states1 = static_cast<uint32_t*>(C.f_states[nxt].p);
+            lv.next_sums1 = static_cast<double*>(C.f_sums[nxt].p);
+            lv.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);
+            lv.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
+            lv.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
+            lv.valid_out = vout; lv.goal_sums = gsums; lv.ctr = dctr;
+            P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
             P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
-                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l, len, keep,
-                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, dctr, stream));
-            r.n_valid += n_goal;
+                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l_first, len, keep,
+                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, gsums, (int)sum_doubles / 2, dctr, stream));
+            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_unknown.p),
+                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p) + n_surv_l_first, n_surv_l - n_surv_l_first, len, keep,
+                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, gsums, (int)sum_doubles / 2, dctr, stream));
+            E.n_valid += n_goal;
             n_c = keep ? n_prefix : 0;
+            n_c2 = keep ? n_prefix2 : 0;
             n_l = keep ? n_plit : 0;
             cur = nxt;
         }
@@ -795,7 +876,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
         P2_HIP(hipStreamSynchronize(stream));
         r.steps = hctr->steps; r.members = hctr->members;
-        fvalid_used += r.n_valid;
+        E.n_goal_literal = hctr->n_goal_literal;
+        if (hctr->valid_written != E.n_valid) return fail(P2_EDEVICE, "the frontier wrote another number of programs than it counted");
+        fvalid_used += E.n_valid;
+        fsums_used += (size_t)E.n_valid * sum_doubles;
+        for (int32_t m : E.members) {        // every query of the enumeration reports its counts
+            QueryRun& o = runs[m];
+            o.n_valid = E.n_valid; o.n_rerun = r.n_rerun; o.steps = r.steps; o.members = r.members;
+        }
     }
 
     // ---- order, cost, select
@@ -828,7 +916,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (int i = 0; i < n_queries; ++i) {
         QueryRun& r = runs[i];
         if (r.n_valid == 0) continue;
-        const size_t list_at = r.frontier ? (r.off_fvalid | ((size_t)1 << 63)) : r.off_valid;
+        if (r.frontier) {
+            // ordered and costed from the enumeration's sums (below); programs that came from literal prefixes
+            // have no sums and are costed by the literal kernel
+            const bool lit_cost = enums[r.enum_id].n_goal_literal > 0 && n_msg > 0;
+            if (lit_cost && literal_lds_bytes(r.plan.R, r.plan.k) != 0)
+                add_seg(lcost_launches, mask_class(r.plan.R) * 2 + 1, r.plan, i, r.n_valid, 1, 0, r.out_first);
+            continue;
+        }
+        const size_t list_at = r.off_valid;
         if (r.wave_cost) {
             // one wavefront per program; it also finds the program's place in the ascending order
             add_seg(scost_launches, word_class(r.plan.k) * 100 + word_class(r.plan.R), r.plan, i, r.n_valid, 1, list_at,
@@ -877,6 +973,29 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                   L.max_k, static_cast<unsigned long long*>(C.valid.p), static_cast<unsigned long long*>(C.f_valid.p),
                                   sorted_base, progs_base, costs_base, stream));
     }
+    // frontier enumerations: the place of every program in ascending index order, once per enumeration; then
+    // every query of the enumeration writes its rows (programs, and costs from its own sums)
+    if (!enums.empty()) {
+        P2_HIP(C.f_rank.ensure(sizeof(uint32_t) * std::max<size_t>(fvalid_used, 1)));
+        for (auto& E : enums) {
+            if (E.n_valid == 0) continue;
+            const unsigned long long* list = static_cast<const unsigned long long*>(C.f_valid.p) + E.off_valid;
+            uint32_t* rank = static_cast<uint32_t*>(C.f_rank.p) + E.off_valid;
+            ++post_launches;
+            P2_HIP(launch_front_rank(list, E.n_valid, rank, stream));
+            for (size_t m = 0; m < E.members.size(); ++m) {
+                FrontFinish F;
+                std::memset(&F, 0, sizeof F);
+                F.query = (uint32_t)E.members[m]; F.n_share = (int32_t)E.members.size(); F.share_pos = (int32_t)m;
+                F.n_valid = E.n_valid; F.valid = list; F.rank = rank;
+                F.goal_sums = static_cast<const double*>(C.f_gsums.p) + E.off_sums;
+                F.out_first = runs[E.members[m]].out_first;
+                F.sorted = sorted_base; F.progs = progs_base; F.costs = costs_base;
+                ++post_launches;
+                P2_HIP(launch_front_finish(reinterpret_cast<const DevQuery*>(db), F, stream));
+            }
+        }
+    }
     for (auto& L : lcost_launches) {
         ++post_launches;
         P2_HIP(launch_cost_literal_list(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
@@ -889,7 +1008,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         unsigned long long* sorted = sorted_base + r.out_first;
         p2_program* progs = progs_base + r.out_first;
         double* costs = costs_base + r.out_first * nm;
-        const bool lit_cost = r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0);
+        const bool lit_cost = r.frontier ? (enums[r.enum_id].n_goal_literal > 0 && n_msg > 0)
+                                         : (r.engine == P2_ENGINE_LITERAL || (r.n_rerun > 0 && n_msg > 0));
         if (lit_cost && literal_lds_bytes(r.plan.R, r.plan.k) == 0) {      // literal state too large for LDS
             void* gs = nullptr;
             P2_HIP(lit_scratch(r.plan, &gs));

@@ -232,8 +232,9 @@ struct FrontEntry {
     uint32_t len;
     unsigned long long digits;
 };
-// A valid extension of a prefix: code 1 = prefix with a compact state, 2 = goal, 3 = prefix whose
-// state only the literal engine can hold.
+// A valid extension of a prefix: code 1 = prefix whose devices hold one (chunk set, mask) pair each, 4 = prefix
+// with a device that holds two, 2 = goal, 3 = prefix whose state only the literal engine can hold; bit 8 set:
+// `entry` counts in the two-pair list.
 struct FrontSurvivor {
     uint32_t entry;
     uint16_t digit;
@@ -241,20 +242,51 @@ struct FrontSurvivor {
 };
 struct FrontCounters {
     // reset before every level
-    uint32_t n_surv, n_surv_literal;        // survivors appended by the compact / literal classify kernels
+    uint32_t n_surv, n_surv_literal;        // survivors appended by the pair-state / literal classify kernels
     uint32_t n_goal, n_prefix, n_prefix_literal;
     uint32_t next_compact, next_literal;    // entries written to the next frontiers
     uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
-    uint32_t n_overflow, pad3;     // literal prefixes left to the full-state kernel
-    // running totals of the query
-    uint32_t valid_written, pad2;
+    uint32_t n_overflow, n_prefix2;         // literal prefixes left to the full-state kernel; two-pair children
+    uint32_t next_compact2, n_unknown;      // entries written to the next two-pair list; two-pair prefixes handed to the literal kernels
+    // running totals of the enumeration
+    uint32_t valid_written, n_goal_literal; // goals written; those among them that came from literal prefixes (no sums)
     unsigned long long steps, members;
 };
+// One level of one enumeration, for the materialize kernel.
+struct FrontLevel {
+    uint32_t query;                // the enumerating query (its DevQuery describes the patterns)
+    const int32_t* share;          // [n_share] the queries of the enumeration (indices into the DevQuery array)
+    int32_t n_share, n_msg;
+    const FrontEntry* entries1; const uint32_t* states1; const double* sums1;     // one-pair list of this level
+    const FrontEntry* entries2; const uint32_t* states2; const double* sums2;     // two-pair list
+    const FrontSurvivor* surv; uint32_t n_surv;
+    int32_t parent_len, keep_prefixes;
+    FrontEntry* next_entries1; uint32_t* next_states1; double* next_sums1;
+    FrontEntry* next_entries2; uint32_t* next_states2; double* next_sums2;
+    FrontEntry* next_literal;
+    unsigned long long* valid_out; double* goal_sums;      // goals: candidate index and [n_share][2] sums
+    FrontCounters* ctr;
+};
+// The valid programs of an enumeration written out for one of its queries.
+struct FrontFinish {
+    uint32_t query;                // whose rows are written (its links set the costs)
+    int32_t n_share, share_pos;    // its place among the enumeration's queries
+    uint32_t n_valid;
+    const unsigned long long* valid; const uint32_t* rank; const double* goal_sums;
+    unsigned long long out_first;  // first row of the query in the batch-wide buffers
+    unsigned long long* sorted; p2_program* progs; double* costs;
+};
 size_t frontier_state_words(int R, int k);
+// 2 where two planes of the state fit in LDS, else 1.
+int frontier_max_pairs(int R, int k);
 hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
-                             hipStream_t stream);
+                             double* sums, int n_share, hipStream_t stream);
+// np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends children that need
+// two pairs to the literal list.  unknown_out (np = 2): entries the pair form cannot judge (counted in n_unknown);
+// handover != 0 treats every entry so (the hand-over path, for tests).
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
-                                 uint32_t n, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr, hipStream_t stream);
+                                 uint32_t n, int np, int max_pairs, int handover, FrontSurvivor* surv, uint32_t surv_cap,
+                                 FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream);
 // Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 // class_cap: most classes of equal rows the class-state kernel may hold (1..64) before a prefix goes to the
@@ -262,14 +294,13 @@ size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
                                          void* gscratch, int class_cap, hipStream_t stream);
-hipError_t launch_front_materialize(const DevQuery* q, uint32_t query, int R, int k, const FrontEntry* entries,
-                                    const uint32_t* states, const FrontSurvivor* surv, uint32_t n_surv, int parent_len,
-                                    int keep_prefixes, FrontEntry* next_entries, uint32_t* next_states,
-                                    FrontEntry* next_literal, unsigned long long* valid_out, FrontCounters* ctr,
-                                    hipStream_t stream);
+hipError_t launch_front_materialize(const DevQuery* queries, int R, int k, const FrontLevel& level, hipStream_t stream);
 hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry* entries, const FrontSurvivor* surv,
                              uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
-                             unsigned long long* valid_out, FrontCounters* ctr, hipStream_t stream);
+                             unsigned long long* valid_out, double* goal_sums, int n_share, FrontCounters* ctr,
+                             hipStream_t stream);
+hipError_t launch_front_rank(const unsigned long long* valid, uint32_t n, uint32_t* rank, hipStream_t stream);
+hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish& F, hipStream_t stream);
 
 // One selection of launch_topk_jobs: the k best of (cost[i * stride], index[i]), i < n, ties by index;
 // positions go to out_pos[min(k, n)], nan_flag is set to 1 when a cost is NaN.  All device pointers.

@@ -2,17 +2,37 @@
 // whose step violates a rule is never extended -- for candidate spaces too large to walk index by
 // index (10^11 programs per query at four hierarchy levels and size limit 6).
 //
-// A frontier holds the valid, non-goal prefixes of one length.  Prefixes whose state has the
-// compact form (one chunk set + one mask per device, see p2_compact.hip) keep that state in HBM,
-// R * (KW + MW) words each; the others ("literal" prefixes, reached through an AllGather of
-// members with different masks) keep only their instructions and are re-run by the literal engine.
+// A frontier holds the valid, non-goal prefixes of one length of one *enumeration*: the queries of
+// a batch that agree in everything validity depends on (reduction group, chunks, patterns, alphabet,
+// size limit) are enumerated together, and every prefix carries, for each of them, the simulated time
+// of its instructions so far (one latency sum and one per-byte sum in fp64), because the time of a
+// step depends on the state before it and on the query's links only.  A program's cost is therefore
+// complete the moment it reaches the goal, and no valid program is ever simulated a second time.
+//
+// State of a prefix.  From the init state every rule of Sec. 3.2 keeps the non-empty rows of a device
+// equal to each other unless an AllGather joins members whose rows carry different column sets
+// (p2_compact.hip).  Here a device holds up to TWO (chunk set, contribution mask) pairs: the rows of
+// pair 0 all carry mask 0, the rows of pair 1 mask 1; the chunk sets are disjoint, pair 0 owns the
+// lowest row, an empty pair has an empty mask, and two pairs never carry the same mask.  Prefixes
+// whose devices all have one pair keep one plane of R x (KW + MW) words in HBM ("one-pair list"),
+// the others two planes ("two-pair list").  The rules on two-pair states:
+//   AllReduce-like : members must hold the same rows.  Their pairs must be *aligned*: every member
+//                    with two pairs splits the rows the same way (members with one pair fit any
+//                    split).  Then the rule is checked and carried out plane by plane.  A group
+//                    that is not aligned cannot be judged in this form: the whole prefix is handed
+//                    to the literal kernels, which rebuild the literal state from its instructions.
+//   AllGather      : rows pairwise disjoint, nobody empty; the result has one pair per distinct
+//                    mask among the members' pairs.  More than two: the child is a "literal"
+//                    prefix (it keeps only its instructions; p2_literal.hip takes it from there).
+//   Broadcast      : compared pair against pair (a row's mask is its pair's mask).
 // One level is two kernels:
 //   classify    : block = one prefix, its state copied to LDS; thread = one instruction, which
-//                 decides read-only whether the step is valid and whether its result is the goal.
+//                 decides read-only whether the step is valid and what its result is.
 //                 Survivors (valid steps) are appended to a list and counted by kind.
-//   materialize : one wavefront per survivor: a goal becomes a valid program (its candidate index
-//                 is appended), anything else a prefix of the next frontier; for compact results
-//                 the new state is built from the parent's and written to HBM.
+//   materialize : one wavefront per survivor: the new state is built from the parent's, the
+//                 step's time is added to the parent's sums for every query of the enumeration, and
+//                 a goal becomes a valid program (candidate index + its sums), anything else a
+//                 prefix of the next frontier.
 // The host sizes the next level's buffers from the counts between the two, so nothing overflows.
 #include "p2_compact_dev.h"
 
@@ -22,23 +42,270 @@ namespace {
 
 constexpr int kClassifyThreads = 128;
 
-enum : int { CODE_INVALID = 0, CODE_PREFIX = 1, CODE_GOAL = 2, CODE_PREFIX_LITERAL = 3 };
+enum : int { CODE_INVALID = 0, CODE_PREFIX = 1, CODE_GOAL = 2, CODE_PREFIX_LITERAL = 3, CODE_PREFIX2 = 4, CODE_UNKNOWN = 5 };
+constexpr int kFromTwoPair = 0x100;       // survivor code bit: the parent is an entry of the two-pair list
 
-// Is the step valid, and what does it lead to?  Reads the state only.  n_goal: devices of the
-// state that are already at the goal.
+template <int N>
+__device__ inline Words<N> zero_words() {
+    Words<N> z;
+#pragma unroll
+    for (int i = 0; i < N; ++i) z.w[i] = 0u;
+    return z;
+}
+template <int N>
+__device__ inline Words<N> or_words(const Words<N>& a, const Words<N>& b) {
+    Words<N> o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o.w[i] = a.w[i] | b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline Words<N> and_words(const Words<N>& a, const Words<N>& b) {
+    Words<N> o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o.w[i] = a.w[i] & b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline Words<N> andn_words(const Words<N>& a, const Words<N>& b) {      // a without b
+    Words<N> o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o.w[i] = a.w[i] & ~b.w[i];
+    return o;
+}
+template <int N>
+__device__ inline Words<N> select_words(bool c, const Words<N>& a, const Words<N>& b) {
+    Words<N> o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o.w[i] = c ? a.w[i] : b.w[i];
+    return o;
+}
+// position of the lowest set bit (N * 32 if there is none)
+template <int N>
+__device__ inline int lowest_bit(const Words<N>& a) {
+    int pos = N * 32;
+#pragma unroll
+    for (int i = N - 1; i >= 0; --i)
+        if (a.w[i]) pos = i * 32 + __ffs((int)a.w[i]) - 1;
+    return pos;
+}
+
+// The (up to) two pairs of a device: x1 empty <=> one pair.
+template <int KW, int MW>
+struct Pairs {
+    Words<KW> x0, x1;
+    Words<MW> m0, m1;
+};
+template <int KW, int MW>
+__device__ inline Pairs<KW, MW> load_pairs(const uint32_t* st, int R, int np, int dev) {
+    constexpr int WPD = KW + MW;
+    const Slot<KW, MW> a = load_slot<KW, MW>(st, WPD, dev);
+    Pairs<KW, MW> p;
+    p.x0 = a.r; p.m0 = a.m;
+    if (np == 2) {
+        const Slot<KW, MW> b = load_slot<KW, MW>(st + R * WPD, WPD, dev);
+        p.x1 = b.r; p.m1 = b.m;
+    } else {
+        p.x1 = zero_words<KW>(); p.m1 = zero_words<MW>();
+    }
+    return p;
+}
+// Writes a device in canonical form: equal masks merged, empty pairs cleared, the pair with the lowest
+// row first.  np = planes of the destination (with one plane the second pair must come out empty).
+template <int KW, int MW>
+__device__ inline void store_pairs(uint32_t* st, int R, int np, int dev, Words<KW> x0, Words<MW> m0, Words<KW> x1, Words<MW> m1) {
+    constexpr int WPD = KW + MW;
+    if (fold_or(x0) == 0u) m0 = zero_words<MW>();
+    if (fold_or(x1) == 0u) m1 = zero_words<MW>();
+    if (fold_or(x1) != 0u && fold_xor(m0, m1) == 0u) { x0 = or_words(x0, x1); x1 = zero_words<KW>(); m1 = zero_words<MW>(); }
+    if (lowest_bit(x1) < lowest_bit(x0)) {
+        const Words<KW> tx = x0; x0 = x1; x1 = tx;
+        const Words<MW> tm = m0; m0 = m1; m1 = tm;
+    }
+    store_slot<KW, MW>(st, WPD, dev, x0, m0);
+    if (np == 2) store_slot<KW, MW>(st + R * WPD, WPD, dev, x1, m1);
+}
+
+// ---- one AllReduce-like group on (up to) two-pair members --------------------------------------------
+template <int KW, int MW>
+struct RedFold {
+    Words<KW> u0;         // rows every member holds
+    Words<KW> xa;         // rows of plane A where the group is split (pair 0 of the members with two pairs)
+    Words<MW> accA, accB; // united masks of plane A (rows xa) and plane B (rows u0 \ xa); equal when not split
+    bool split;           // some member has two pairs
+    uint32_t bad;         // rows differ between members, or a contribution would be reduced twice
+    uint32_t unaligned;   // two members split their rows differently
+};
+template <int KW, int MW>
+__device__ inline RedFold<KW, MW> fold_red(const uint32_t* st, int R, int np, int base, int g, int s) {
+    RedFold<KW, MW> f;
+    Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base);
+    f.u0 = or_words(p.x0, p.x1);
+    f.split = fold_or(p.x1) != 0u;
+    f.xa = p.x0;
+    f.accA = p.m0;
+    f.accB = f.split ? p.m1 : p.m0;
+    f.bad = 0; f.unaligned = 0;
+    for (int t = 1; t < g; ++t) {
+        p = load_pairs<KW, MW>(st, R, np, base + t * s);
+        const bool two = fold_or(p.x1) != 0u;
+        f.bad |= fold_xor(or_words(p.x0, p.x1), f.u0);
+        if (two) {
+            if (f.split) f.unaligned |= fold_xor(p.x0, f.xa);
+            else { f.split = true; f.xa = p.x0; }
+        }
+        const Words<MW> mB = two ? p.m1 : p.m0;
+        f.bad |= fold_and(p.m0, f.accA) | fold_and(mB, f.accB);
+        f.accA = or_words(f.accA, p.m0);
+        f.accB = or_words(f.accB, mB);
+    }
+    return f;
+}
+
+// ---- one AllGather group ---------------------------------------------------------------------------
+template <int KW, int MW>
+struct GatherFold {
+    Words<KW> u;          // rows after the gather
+    Words<KW> xd0, xd1;   // rows carrying the first / second distinct mask
+    Words<MW> d0, d1;
+    int n_masks;          // distinct masks seen (3 = more than two)
+    uint32_t bad;         // a row held twice, or an empty member
+};
+template <int KW, int MW>
+__device__ inline void gather_add(GatherFold<KW, MW>& f, const Words<KW>& x, const Words<MW>& m) {
+    if (fold_or(x) == 0u) return;
+    if (f.n_masks == 0) { f.d0 = m; f.xd0 = x; f.n_masks = 1; }
+    else if (fold_xor(m, f.d0) == 0u) f.xd0 = or_words(f.xd0, x);
+    else if (f.n_masks == 1) { f.d1 = m; f.xd1 = x; f.n_masks = 2; }
+    else if (f.n_masks >= 2 && fold_xor(m, f.d1) == 0u) f.xd1 = or_words(f.xd1, x);
+    else f.n_masks = 3;
+}
+template <int KW, int MW>
+__device__ inline GatherFold<KW, MW> fold_gather(const uint32_t* st, int R, int np, int base, int g, int s) {
+    GatherFold<KW, MW> f;
+    f.u = zero_words<KW>(); f.xd0 = zero_words<KW>(); f.xd1 = zero_words<KW>();
+    f.d0 = zero_words<MW>(); f.d1 = zero_words<MW>();
+    f.n_masks = 0; f.bad = 0;
+    for (int t = 0; t < g; ++t) {
+        const Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base + t * s);
+        const Words<KW> u = or_words(p.x0, p.x1);
+        f.bad |= fold_and(u, f.u) | (uint32_t)(fold_or(u) == 0u);
+        f.u = or_words(f.u, u);
+        gather_add(f, p.x0, p.m0);
+        gather_add(f, p.x1, p.m1);
+    }
+    return f;
+}
+
+// ---- Broadcast: root against one member, pair by pair -------------------------------------------------
+template <int KW, int MW>
+__device__ inline void bcast_compare(const Pairs<KW, MW>& root, const Pairs<KW, MW>& mem, uint32_t& not_sub, bool& differs) {
+    const Words<KW> ur = or_words(root.x0, root.x1), um = or_words(mem.x0, mem.x1);
+    not_sub |= fold_andn(um, ur);
+    uint32_t dif = fold_xor(um, ur);
+    if (fold_and(root.x0, mem.x0)) { not_sub |= fold_andn(mem.m0, root.m0); dif |= fold_xor(mem.m0, root.m0); }
+    if (fold_and(root.x0, mem.x1)) { not_sub |= fold_andn(mem.m1, root.m0); dif |= fold_xor(mem.m1, root.m0); }
+    if (fold_and(root.x1, mem.x0)) { not_sub |= fold_andn(mem.m0, root.m1); dif |= fold_xor(mem.m0, root.m1); }
+    if (fold_and(root.x1, mem.x1)) { not_sub |= fold_andn(mem.m1, root.m1); dif |= fold_xor(mem.m1, root.m1); }
+    differs |= dif != 0u;
+}
+
+__device__ inline int first_of_group(const PatLds& P, int G) {
+    const int gs = P.g * P.s;
+    return P.master ? G * gs : (G / P.s) * gs + (G % P.s);
+}
+
+// Is the step valid, and what does it lead to?  Reads the state only.  np: planes of the state.
+// n_goal / n_two: devices of the state that are at the goal / that hold two pairs.
+template <int KW, int MW>
+__device__ inline int classify_pairs(const uint32_t* st, const PatLds P, int op, int R, int np, const Words<KW>& all_rows,
+                                     const Words<MW>& all_cols, int n_goal, int n_two) {
+    bool bad = false, changed = false, all_goal = true, unknown = false, overflow = false, any_two = false;
+    int goal_part = 0, two_part = 0;
+    for (int G = 0; G < P.n_groups; ++G) {
+        const int base = first_of_group(P, G);
+        for (int t = 0; t < P.g; ++t) {
+            const Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base + t * P.s);
+            const bool two = fold_or(p.x1) != 0u;
+            two_part += two ? 1 : 0;
+            goal_part += (!two && (fold_xor(p.x0, all_rows) | fold_xor(p.m0, all_cols)) == 0u) ? 1 : 0;
+        }
+        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+            const RedFold<KW, MW> f = fold_red<KW, MW>(st, R, np, base, P.g, P.s);
+            bad |= f.bad != 0u;
+            unknown |= f.bad == 0u && f.unaligned != 0u;
+            const bool some = fold_or(f.u0) != 0u;
+            changed |= some;
+            const bool two_masks = f.split && fold_xor(f.accA, f.accB) != 0u;
+            if (op == OP_RS) {
+                const int rows = popcount(f.u0);
+                const int per = div_small(rows, P.g);
+                bad |= per * P.g != rows;
+                // a member's block may fall on both sides of the split
+                if (two_masks && some && per * P.g == rows) {
+                    Words<KW> prev = zero_words<KW>();
+                    const Words<KW> xb = andn_words(f.u0, f.xa);
+                    for (int t = 0; t < P.g; ++t) {
+                        const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
+                        const Words<KW> blk = andn_words(upto, prev);
+                        prev = upto;
+                        any_two |= fold_and(blk, f.xa) != 0u && fold_and(blk, xb) != 0u;
+                    }
+                }
+                all_goal = false;
+            } else if (op == OP_RD) {
+                any_two |= two_masks && some;
+                all_goal = false;
+            } else {
+                any_two |= two_masks && some;
+                all_goal &= !two_masks && (fold_xor(f.u0, all_rows) | fold_xor(f.accA, all_cols)) == 0u;
+            }
+        } else if (op == OP_AG) {
+            const GatherFold<KW, MW> f = fold_gather<KW, MW>(st, R, np, base, P.g, P.s);
+            bad |= f.bad != 0u;
+            changed = true;
+            overflow |= f.n_masks > 2;
+            any_two |= f.n_masks == 2;
+            all_goal &= f.n_masks == 1 && (fold_xor(f.u, all_rows) | fold_xor(f.d0, all_cols)) == 0u;
+        } else {
+            const Pairs<KW, MW> root = load_pairs<KW, MW>(st, R, np, base);
+            uint32_t not_sub = 0;
+            bool differs = false;
+            for (int t = 1; t < P.g; ++t)
+                bcast_compare(root, load_pairs<KW, MW>(st, R, np, base + t * P.s), not_sub, differs);
+            bad |= not_sub != 0u || !differs;
+            changed = true;
+            const bool two = fold_or(root.x1) != 0u;
+            any_two |= two;
+            all_goal &= !two && (fold_xor(root.x0, all_rows) | fold_xor(root.m0, all_cols)) == 0u;
+        }
+    }
+    if (bad || !changed) return CODE_INVALID;
+    if (unknown) return CODE_UNKNOWN;
+    if (overflow) return CODE_PREFIX_LITERAL;       // a device with three different masks: never the goal
+    const int n_part = P.n_groups * P.g;
+    if (any_two || n_two - two_part > 0) return CODE_PREFIX2;
+    const bool rest_done = (n_goal - goal_part) == (R - n_part);     // devices left untouched
+    return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
+}
+
+// The same on a one-pair state, every rule folded in one pass over the participating devices (threads of a
+// wavefront hold different instructions: no branch on the rule inside the loop).
 template <int KW, int MW>
 __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, int R, const Words<KW>& all_rows,
                                     const Words<MW>& all_cols, int n_goal) {
     constexpr int WPD = KW + MW;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
     uint32_t badx = 0;
-    bool changed = false, give_up = false, all_goal = true;
+    bool changed = false, two_masks = false, over = false, all_goal = true;
     int goal_part = 0;                      // participants that are at the goal before the step
     GroupWalk wk;
     wk.start();
     Slot<KW, MW> first, acc;
+    Words<MW> second;                       // AllGather: a mask that differs from the first member's
+    bool have_second = false;
     uint32_t eqx = 0, dmx = 0, drx = 0, smx = 0, subx = 0;
-    bool anyzero = false;
+    bool anyzero = false, third = false;
     const int n_part = P.n_groups * P.g;
     for (int j = 0; j < n_part; ++j) {
         const Slot<KW, MW> cur = load_slot<KW, MW>(st, WPD, wk.dev);
@@ -47,11 +314,17 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
             first = cur; acc = cur;
             eqx = 0; dmx = 0; drx = 0; smx = 0; subx = 0;
             anyzero = fold_or(cur.r) == 0;
+            have_second = false; third = false;
         } else {
             eqx |= fold_xor(cur.r, first.r);
             dmx |= fold_and(cur.m, acc.m);
             drx |= fold_and(cur.r, acc.r);
-            smx |= fold_xor(cur.m, first.m);
+            const uint32_t dm = fold_xor(cur.m, first.m);
+            smx |= dm;
+            if (dm != 0u) {                                  // (only an AllGather looks at these)
+                if (!have_second) { second = cur.m; have_second = true; }
+                else third |= fold_xor(cur.m, second) != 0u;
+            }
             subx |= fold_andn(cur.r, first.r) | fold_andn(cur.m, first.m);
             anyzero |= fold_or(cur.r) == 0;
 #pragma unroll
@@ -72,7 +345,8 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
                 all_goal &= op == OP_AR && (fold_xor(first.r, all_rows) | fold_xor(acc.m, all_cols)) == 0;
             } else if (op == OP_AG) {
                 badx |= drx | (uint32_t)anyzero;
-                give_up |= smx != 0;
+                two_masks |= smx != 0;                       // rows with different column sets: two pairs per member
+                over |= third;                               // ... or more than two
                 changed = true;
                 all_goal &= (fold_xor(acc.r, all_rows) | fold_xor(first.m, all_cols)) == 0;
             } else {
@@ -84,25 +358,30 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
         }
     }
     if (badx != 0 || !changed) return CODE_INVALID;
-    if (give_up) return CODE_PREFIX_LITERAL;        // rows with different column sets: never the goal
+    if (over) return CODE_PREFIX_LITERAL;           // three different masks on a device: never the goal
+    if (two_masks) return CODE_PREFIX2;
     const bool rest_done = (n_goal - goal_part) == (R - n_part);     // devices left untouched
     return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
 }
 
+// np = 1: entries of the one-pair list, np = 2: of the two-pair list.  max_pairs < 2 sends every child that
+// needs two pairs to the literal list instead (and the two-pair list stays empty).
 template <int KW, int MW>
 __global__ __launch_bounds__(kClassifyThreads) void k_front_classify(const DevQuery* __restrict__ qp,
                                                                      const FrontEntry* __restrict__ entries,
                                                                      const uint32_t* __restrict__ states, uint32_t n_entries,
+                                                                     int np, int max_pairs, int handover,
                                                                      FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
+                                                                     FrontEntry* __restrict__ unknown_out,
                                                                      FrontCounters* __restrict__ ctr) {
     extern __shared__ uint32_t lds[];
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint16_t sdig[kMaxPatterns * 5];
-    __shared__ int s_goal;
+    __shared__ int s_goal, s_two, s_unknown;
     const DevQuery& q = *qp;
     constexpr int WPD = KW + MW;
     const int R = q.R, I = q.alphabet;
-    const int words = R * WPD;
+    const int words = np * R * WPD;
     for (int i = threadIdx.x; i < q.n_patterns; i += kClassifyThreads) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
@@ -116,26 +395,51 @@ __global__ __launch_bounds__(kClassifyThreads) void k_front_classify(const DevQu
         __syncthreads();
         const uint32_t* src = states + (size_t)e * words;
         for (int i = threadIdx.x; i < words; i += kClassifyThreads) lds[i] = src[i];
-        if (threadIdx.x == 0) s_goal = 0;
+        if (threadIdx.x == 0) { s_goal = 0; s_two = 0; s_unknown = 0; }
         __syncthreads();
-        int mine = 0;
+        int mine = 0, two = 0;
         for (int d = threadIdx.x; d < R; d += kClassifyThreads) {
             const Slot<KW, MW> sl = load_slot<KW, MW>(lds, WPD, d);
-            mine += (fold_xor(sl.r, all_rows) | fold_xor(sl.m, all_cols)) == 0 ? 1 : 0;
+            const bool has_two = np == 2 && fold_or(load_slot<KW, MW>(lds + R * WPD, WPD, d).r) != 0u;
+            two += has_two ? 1 : 0;
+            mine += (!has_two && (fold_xor(sl.r, all_rows) | fold_xor(sl.m, all_cols)) == 0) ? 1 : 0;
         }
         if (mine) atomicAdd(&s_goal, mine);
+        if (two) atomicAdd(&s_two, two);
         __syncthreads();
-        const int n_goal = s_goal;
-        for (int a = threadIdx.x; a < I; a += kClassifyThreads) {
+        const int n_goal = s_goal, n_two = s_two;
+        // (an alphabet of more than kClassifyThreads instructions takes several rounds; a round's codes are kept)
+        int codes[(kMaxPatterns * 5 + kClassifyThreads - 1) / kClassifyThreads];
+        int n_mine = 0;
+        for (int a = threadIdx.x; a < I; a += kClassifyThreads, ++n_mine) {
             const uint32_t ins = sdig[a];
             const PatLds P = spat[ins >> 3];
-            const int code = classify_step<KW, MW>(lds, P, (int)(ins & 7u), R, all_rows, all_cols, n_goal);
+            int code = np == 2 ? classify_pairs<KW, MW>(lds, P, (int)(ins & 7u), R, 2, all_rows, all_cols, n_goal, n_two)
+                               : classify_step<KW, MW>(lds, P, (int)(ins & 7u), R, all_rows, all_cols, n_goal);
+            if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
+            if (code == CODE_UNKNOWN || handover) s_unknown = 1;
+            codes[n_mine] = code;
+        }
+        __syncthreads();
+        if (s_unknown) {
+            // this form cannot judge one of the instructions: the literal kernels take the whole prefix
+            if (threadIdx.x == 0) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[e];
+            continue;
+        }
+        n_mine = 0;
+        for (int a = threadIdx.x; a < I; a += kClassifyThreads, ++n_mine) {
+            const int code = codes[n_mine];
+            const PatLds P = spat[sdig[a] >> 3];
             ++steps;
             members += (unsigned long long)(P.n_groups * P.g);
             if (code != CODE_INVALID) {
                 const uint32_t pos = atomicAdd(&ctr->n_surv, 1u);
-                if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
-                atomicAdd(code == CODE_GOAL ? &ctr->n_goal : code == CODE_PREFIX ? &ctr->n_prefix : &ctr->n_prefix_literal, 1u);
+                if (pos < surv_cap) {
+                    FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (np == 2 ? kFromTwoPair : 0));
+                    surv[pos] = sv;
+                }
+                atomicAdd(code == CODE_GOAL ? &ctr->n_goal : code == CODE_PREFIX ? &ctr->n_prefix
+                          : code == CODE_PREFIX2 ? &ctr->n_prefix2 : &ctr->n_prefix_literal, 1u);
             }
         }
     }
@@ -149,112 +453,159 @@ __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long lo
     return q.base[len] + v;
 }
 
-// One wavefront per survivor of the compact frontier.
+// One wavefront per survivor of the one-pair and two-pair frontiers.
 template <int KW, int MW>
-__global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __restrict__ qp, uint32_t query,
-                                                          const FrontEntry* __restrict__ entries,
-                                                          const uint32_t* __restrict__ states,
-                                                          const FrontSurvivor* __restrict__ surv, uint32_t n_surv,
-                                                          int parent_len, int keep_prefixes,
-                                                          FrontEntry* __restrict__ next_entries, uint32_t* __restrict__ next_states,
-                                                          FrontEntry* __restrict__ next_literal,
-                                                          unsigned long long* __restrict__ valid_out,
-                                                          FrontCounters* __restrict__ ctr) {
+__global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint32_t s_slot;
-    const DevQuery& q = *qp;
+    __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];        // rows that set a group's bytes
+    const DevQuery& q = queries[A.query];
     constexpr int WPD = KW + MW;
     const int lane = threadIdx.x;
     const int R = q.R;
-    const int words = R * WPD;
+    const int plane = R * WPD;
     for (int i = lane; i < q.n_patterns; i += 64) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
     }
     __syncthreads();
-    for (uint32_t i = blockIdx.x; i < n_surv; i += gridDim.x) {
-        const FrontSurvivor sv = surv[i];
-        const FrontEntry pe = entries[sv.entry];
-        const unsigned long long digits = pe.digits | ((unsigned long long)sv.digit << (9 * parent_len));
-        if (sv.code == CODE_GOAL) {
-            if (lane == 0) valid_out[atomicAdd(&ctr->valid_written, 1u)] = rank_of(q, digits, parent_len + 1);
-            continue;
-        }
-        if (!keep_prefixes) continue;                 // the size limit is reached: nothing extends this prefix
+    for (uint32_t i = blockIdx.x; i < A.n_surv; i += gridDim.x) {
+        const FrontSurvivor sv = A.surv[i];
+        const int code = sv.code & 0xff;
+        const int np = (sv.code & kFromTwoPair) ? 2 : 1;
+        const FrontEntry pe = (np == 2 ? A.entries2 : A.entries1)[sv.entry];
+        const unsigned long long digits = pe.digits | ((unsigned long long)sv.digit << (9 * A.parent_len));
         FrontEntry ce;
-        ce.query = query; ce.len = (uint32_t)(parent_len + 1); ce.digits = digits;
-        if (sv.code == CODE_PREFIX_LITERAL) {
-            if (lane == 0) next_literal[atomicAdd(&ctr->next_literal, 1u)] = ce;
+        ce.query = A.query; ce.len = (uint32_t)(A.parent_len + 1); ce.digits = digits;
+        if (code == CODE_PREFIX_LITERAL) {
+            if (A.keep_prefixes && lane == 0) A.next_literal[atomicAdd(&A.ctr->next_literal, 1u)] = ce;
             continue;
         }
+        if (code != CODE_GOAL && !A.keep_prefixes) continue;     // the size limit is reached: nothing extends this prefix
+        const uint32_t* parent = (np == 2 ? A.states2 + (size_t)sv.entry * 2 * plane : A.states1 + (size_t)sv.entry * plane);
+        const double* psum = (np == 2 ? A.sums2 : A.sums1) + (size_t)sv.entry * 2 * A.n_share;
+        const int cnp = code == CODE_PREFIX2 ? 2 : 1;
         __syncthreads();
-        if (lane == 0) { s_slot = atomicAdd(&ctr->next_compact, 1u); next_entries[s_slot] = ce; }
+        if (lane == 0) {
+            if (code == CODE_GOAL) {
+                s_slot = atomicAdd(&A.ctr->valid_written, 1u);
+                A.valid_out[s_slot] = rank_of(q, digits, A.parent_len + 1);
+            } else if (code == CODE_PREFIX2) {
+                s_slot = atomicAdd(&A.ctr->next_compact2, 1u);
+                A.next_entries2[s_slot] = ce;
+            } else {
+                s_slot = atomicAdd(&A.ctr->next_compact, 1u);
+                A.next_entries1[s_slot] = ce;
+            }
+        }
         __syncthreads();
-        const uint32_t* parent = states + (size_t)sv.entry * words;
-        uint32_t* child = next_states + (size_t)s_slot * words;
-        for (int w = lane; w < words; w += 64) child[w] = parent[w];
+        const uint32_t slot = s_slot;
+        uint32_t* child = nullptr;
+        if (code == CODE_PREFIX2) child = A.next_states2 + (size_t)slot * 2 * plane;
+        else if (code == CODE_PREFIX) child = A.next_states1 + (size_t)slot * plane;
+        if (child) {
+            // the devices that take no part keep their pairs (a device that needs its second pair keeps it:
+            // the child then has two planes)
+            for (int w = lane; w < plane; w += 64) child[w] = parent[w];
+            if (cnp == 2) for (int w = lane; w < plane; w += 64) child[plane + w] = np == 2 ? parent[plane + w] : 0u;
+        }
         __syncthreads();
         // apply the instruction: lanes over groups, members in order; reads the parent, writes the child
         const uint32_t ins = q.instr_of_digit[sv.digit];
-        const PatLds P = spat[ins >> 3];
+        const int pid = (int)(ins >> 3);
+        const PatLds P = spat[pid];
         const int op = (int)(ins & 7u);
-        const int gs = P.g * P.s;
         for (int G = lane; G < P.n_groups; G += 64) {
-            const int base = P.master ? G * gs : (G / P.s) * gs + (G % P.s);
-            const Slot<KW, MW> first = load_slot<KW, MW>(parent, WPD, base);
-            Slot<KW, MW> acc = first;
-            for (int p = 1; p < P.g; ++p) {
-                const Slot<KW, MW> cur = load_slot<KW, MW>(parent, WPD, base + p * P.s);
-#pragma unroll
-                for (int w = 0; w < KW; ++w) acc.r.w[w] |= cur.r.w[w];
-#pragma unroll
-                for (int w = 0; w < MW; ++w) acc.m.w[w] |= cur.m.w[w];
-            }
-            Words<KW> prev;
-#pragma unroll
-            for (int w = 0; w < KW; ++w) prev.w[w] = 0;
-            const int per = op == OP_RS ? div_small(popcount(first.r), P.g) : 0;
-            for (int p = 0; p < P.g; ++p) {
-                Words<KW> nr = first.r;
-                Words<MW> nm = acc.m;
-                if (op == OP_RS) {
-                    const Words<KW> upto = lowest_n(first.r, (p + 1) * per);
-#pragma unroll
-                    for (int w = 0; w < KW; ++w) { nr.w[w] = upto.w[w] & ~prev.w[w]; prev.w[w] = upto.w[w]; }
-                } else if (op == OP_RD) {
-                    if (p != 0) {
-#pragma unroll
-                        for (int w = 0; w < KW; ++w) nr.w[w] = 0;
-#pragma unroll
-                        for (int w = 0; w < MW; ++w) nm.w[w] = 0;
+            const int base = first_of_group(P, G);
+            int rows_held = 0;
+            if (op == OP_AR || op == OP_RS || op == OP_RD) {
+                const RedFold<KW, MW> f = fold_red<KW, MW>(parent, R, np, base, P.g, P.s);
+                rows_held = popcount(f.u0);
+                if (child && rows_held) {
+                    const Words<KW> xb = f.split ? andn_words(f.u0, f.xa) : zero_words<KW>();
+                    const Words<KW> xa = f.split ? f.xa : f.u0;
+                    if (op == OP_AR) {
+                        for (int t = 0; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, xa, f.accA, xb, f.accB);
+                    } else if (op == OP_RD) {
+                        store_pairs<KW, MW>(child, R, cnp, base, xa, f.accA, xb, f.accB);
+                        for (int t = 1; t < P.g; ++t)
+                            store_pairs<KW, MW>(child, R, cnp, base + t * P.s, zero_words<KW>(), zero_words<MW>(), zero_words<KW>(), zero_words<MW>());
+                    } else {
+                        // rank t keeps the t-th block of the rows in ascending order, on both sides of the split
+                        const int per = div_small(rows_held, P.g);
+                        Words<KW> prev = zero_words<KW>();
+                        for (int t = 0; t < P.g; ++t) {
+                            const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
+                            const Words<KW> blk = andn_words(upto, prev);
+                            prev = upto;
+                            store_pairs<KW, MW>(child, R, cnp, base + t * P.s, and_words(blk, xa), f.accA, and_words(blk, xb), f.accB);
+                        }
                     }
-                } else if (op == OP_AG) {
-                    nr = acc.r; nm = first.m;
-                } else if (op == OP_BC) {
-                    nm = first.m;
                 }
-                store_slot<KW, MW>(child, WPD, base + p * P.s, nr, nm);
+            } else if (op == OP_AG) {
+                const GatherFold<KW, MW> f = fold_gather<KW, MW>(parent, R, np, base, P.g, P.s);
+                rows_held = popcount(f.u);
+                if (child)
+                    for (int t = 0; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, f.xd0, f.d0, f.xd1, f.d1);
+            } else {
+                const Pairs<KW, MW> root = load_pairs<KW, MW>(parent, R, np, base);
+                rows_held = popcount(or_words(root.x0, root.x1));
+                if (child)
+                    for (int t = 1; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, root.x0, root.m0, root.x1, root.m1);
+            }
+            s_count[G] = (uint32_t)rows_held;
+        }
+        __syncthreads();
+        // ---- the step's time for every query of the enumeration (alpha-beta model: latency steps of the
+        //      slowest group's link; bytes through the busiest uplink, from the query's bandwidth rows)
+        double* out = code == CODE_GOAL ? A.goal_sums + (size_t)slot * 2 * A.n_share
+                                        : (code == CODE_PREFIX2 ? A.next_sums2 : A.next_sums1) + (size_t)slot * 2 * A.n_share;
+        if (A.n_msg > 0) {
+            for (int j = 0; j < A.n_share; ++j) {
+                const DevQuery& cq = queries[A.share[j]];
+                const DevRows& rw = *cq.rows;
+                double best = 0.0;
+                for (int row = rw.pat_begin[pid] + lane; row < rw.pat_begin[pid + 1]; row += 64) {
+                    long long dot = 0;
+                    for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                        const uint32_t ent = rw.entries[e];
+                        dot += (long long)entry_cnt(ent) * (long long)s_count[entry_group(ent)];
+                    }
+                    best = fmax(best, (double)dot * cq.inv_bw[rw.row_level[row]]);
+                }
+                for (int off = 32; off > 0; off >>= 1) best = fmax(best, __shfl_xor(best, off, 64));
+                if (lane == 0) {
+                    double ring_steps, mult;
+                    step_factors(op, P.g, cq.algo, ring_steps, mult);
+                    out[2 * j] = psum[2 * j] + ring_steps * cq.alpha[cq.pat[pid].span_level];
+                    out[2 * j + 1] = psum[2 * j + 1] + (mult / (double)cq.k) * best;
+                }
             }
         }
-        if (lane == 0) { atomicAdd(&ctr->steps, 1ull); atomicAdd(&ctr->members, (unsigned long long)(P.n_groups * P.g)); }
+        if (lane == 0 && code != CODE_GOAL) { atomicAdd(&A.ctr->steps, 1ull); atomicAdd(&A.ctr->members, (unsigned long long)(P.n_groups * P.g)); }
     }
 }
 
 // Survivors of the literal frontier carry no state: a goal becomes a valid program, the rest
-// prefixes of the next literal frontier.
+// prefixes of the next literal frontier.  Such a goal has no sums (NaN: its cost is worked out by
+// the cost kernels that re-run a program).
 __global__ __launch_bounds__(256) void k_front_emit(const DevQuery* __restrict__ qp, uint32_t query,
                                                     const FrontEntry* __restrict__ entries,
                                                     const FrontSurvivor* __restrict__ surv, uint32_t n_surv, int parent_len,
                                                     int keep_prefixes, FrontEntry* __restrict__ next_literal,
-                                                    unsigned long long* __restrict__ valid_out, FrontCounters* __restrict__ ctr) {
+                                                    unsigned long long* __restrict__ valid_out, double* __restrict__ goal_sums,
+                                                    int n_share, FrontCounters* __restrict__ ctr) {
     const DevQuery& q = *qp;
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= n_surv) return;
     const FrontSurvivor sv = surv[i];
     const unsigned long long digits = entries[sv.entry].digits | ((unsigned long long)sv.digit << (9 * parent_len));
     if (sv.code == CODE_GOAL) {
-        valid_out[atomicAdd(&ctr->valid_written, 1u)] = rank_of(q, digits, parent_len + 1);
+        const uint32_t slot = atomicAdd(&ctr->valid_written, 1u);
+        valid_out[slot] = rank_of(q, digits, parent_len + 1);
+        atomicAdd(&ctr->n_goal_literal, 1u);
+        for (int j = 0; j < 2 * n_share; ++j) goal_sums[(size_t)slot * 2 * n_share + j] = __longlong_as_double(0x7ff8000000000000ll);
     } else if (keep_prefixes) {
         FrontEntry ce;
         ce.query = query; ce.len = (uint32_t)(parent_len + 1); ce.digits = digits;
@@ -264,7 +615,7 @@ __global__ __launch_bounds__(256) void k_front_emit(const DevQuery* __restrict__
 
 template <int KW, int MW>
 __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ qp, uint32_t query, FrontEntry* entries,
-                                                   uint32_t* states) {
+                                                   uint32_t* states, double* sums, int n_share) {
     // Sec. 3.5: the empty program; device i holds column i in every row
     const DevQuery& q = *qp;
     constexpr int WPD = KW + MW;
@@ -275,7 +626,53 @@ __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ 
         for (int i = 0; i < MW; ++i) m.w[i] = (i == (d >> 5)) ? (1u << (d & 31)) : 0u;
         store_slot<KW, MW>(states, WPD, d, all_rows, m);
     }
+    for (int j = threadIdx.x; j < 2 * n_share; j += 64) sums[j] = 0.0;
     if (threadIdx.x == 0) { FrontEntry e; e.query = query; e.len = 0; e.digits = 0ull; entries[0] = e; }
+}
+
+// Programs and costs of an enumeration's valid programs for one of its queries: entry i of the unordered
+// list, whose place in ascending index order is rank[i], becomes row out_first + rank[i].
+__global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict__ queries, FrontFinish F) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= F.n_valid) return;
+    const DevQuery& q = queries[F.query];
+    const unsigned long long idx = F.valid[i];
+    const size_t row = F.out_first + F.rank[i];
+    int len = 1;
+    while (len < q.max_len && idx >= q.base[len + 1]) ++len;
+    p2_program pr;
+    pr.index = idx;
+    pr.len = (uint8_t)len;
+    for (int t = 0; t < P2_MAX_LEN; ++t) pr.instr[t] = 0;
+    unsigned long long rem = idx - q.base[len];
+    const unsigned long long I = (unsigned long long)q.alphabet;
+    for (int t = len - 1; t >= 0; --t) {
+        const unsigned long long nx = rem / I;
+        const uint32_t ins = q.instr_of_digit[(uint32_t)(rem - nx * I)];
+        pr.instr[t] = (uint8_t)((ins >> 3) * 5u + (ins & 7u));
+        rem = nx;
+    }
+    F.sorted[row] = idx;
+    F.progs[row] = pr;
+    const double sa = F.goal_sums[((size_t)i * F.n_share + F.share_pos) * 2], sb = F.goal_sums[((size_t)i * F.n_share + F.share_pos) * 2 + 1];
+    for (int m = 0; m < q.n_msg; ++m) F.costs[row * q.n_msg + m] = sa + q.msg_bytes[m] * sb;
+}
+
+// rank[i] = number of entries of the list smaller than entry i (distinct keys).
+__global__ __launch_bounds__(256) void k_front_rank(const unsigned long long* __restrict__ in, uint32_t n, uint32_t* __restrict__ rank) {
+    __shared__ unsigned long long tile[256];
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    const unsigned long long key = i < n ? in[i] : 0ull;
+    uint32_t r = 0;
+    for (uint32_t t0 = 0; t0 < n; t0 += 256u) {
+        const uint32_t j = t0 + threadIdx.x;
+        tile[threadIdx.x] = j < n ? in[j] : ~0ull;
+        __syncthreads();
+        const uint32_t lim = n - t0 < 256u ? n - t0 : 256u;
+        for (uint32_t u = 0; u < lim; ++u) r += tile[u] < key;
+        __syncthreads();
+    }
+    if (i < n) rank[i] = r;
 }
 
 inline int round_words_f(int bits) {
@@ -292,10 +689,11 @@ hipError_t allow_lds_f(F func, size_t bytes) {
 struct FrontArgs {
     const DevQuery* q; uint32_t query;
     const FrontEntry* entries; const uint32_t* states; uint32_t n;
-    FrontSurvivor* surv; uint32_t surv_cap; uint32_t n_surv;
-    int parent_len, keep_prefixes;
-    FrontEntry* next_entries; uint32_t* next_states; FrontEntry* next_literal;
-    unsigned long long* valid_out; FrontCounters* ctr;
+    int np, max_pairs, handover;
+    FrontSurvivor* surv; uint32_t surv_cap;
+    FrontEntry* unknown_out; FrontCounters* ctr;
+    double* sums; int n_share;
+    const DevQuery* queries; const FrontLevel* level;
     int R;
 };
 
@@ -303,19 +701,17 @@ template <int KW, int MW>
 hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
     if (what == 0) {
         hipLaunchKernelGGL((k_front_init<KW, MW>), dim3(1), dim3(64), 0, stream, A.q, A.query, const_cast<FrontEntry*>(A.entries),
-                           const_cast<uint32_t*>(A.states));
+                           const_cast<uint32_t*>(A.states), A.sums, A.n_share);
     } else if (what == 1) {
-        const size_t lds = (size_t)A.R * (KW + MW) * 4;
+        const size_t lds = (size_t)A.np * A.R * (KW + MW) * 4;
         hipError_t e = allow_lds_f(k_front_classify<KW, MW>, lds);
         if (e != hipSuccess) return e;
         const unsigned blocks = A.n < 65536u ? A.n : 65536u;
         hipLaunchKernelGGL((k_front_classify<KW, MW>), dim3(blocks), dim3(kClassifyThreads), lds, stream, A.q, A.entries, A.states,
-                           A.n, A.surv, A.surv_cap, A.ctr);
+                           A.n, A.np, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
     } else {
-        const unsigned blocks = A.n_surv < 65536u ? A.n_surv : 65536u;
-        hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(64), 0, stream, A.q, A.query, A.entries, A.states,
-                           A.surv, A.n_surv, A.parent_len, A.keep_prefixes, A.next_entries, A.next_states, A.next_literal,
-                           A.valid_out, A.ctr);
+        const unsigned blocks = A.level->n_surv < 65536u ? A.level->n_surv : 65536u;
+        hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(64), 0, stream, A.queries, *A.level);
     }
     return hipGetLastError();
 }
@@ -346,40 +742,52 @@ hipError_t front_dispatch(int R, int k, int what, const FrontArgs& A, hipStream_
 
 size_t frontier_state_words(int R, int k) { return (size_t)R * (size_t)(round_words_f(k) + round_words_f(R)); }
 
+// Two planes must fit in LDS for the two-pair list to be used.
+int frontier_max_pairs(int R, int k) { return frontier_state_words(R, k) * 2 * 4 + 2048 <= kLdsBudget ? 2 : 1; }
+
 hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
-                             hipStream_t stream) {
+                             double* sums, int n_share, hipStream_t stream) {
     FrontArgs A{};
-    A.q = q; A.query = query; A.entries = entries; A.states = states; A.R = R;
+    A.q = q; A.query = query; A.entries = entries; A.states = states; A.R = R; A.sums = sums; A.n_share = n_share;
     return front_dispatch(R, k, 0, A, stream);
 }
 
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
-                                 uint32_t n, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr, hipStream_t stream) {
+                                 uint32_t n, int np, int max_pairs, int handover, FrontSurvivor* surv, uint32_t surv_cap,
+                                 FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
-    A.q = q; A.entries = entries; A.states = states; A.n = n; A.surv = surv; A.surv_cap = surv_cap; A.ctr = ctr; A.R = R;
+    A.q = q; A.entries = entries; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.handover = handover; A.surv = surv;
+    A.surv_cap = surv_cap; A.unknown_out = unknown_out; A.ctr = ctr; A.R = R;
     return front_dispatch(R, k, 1, A, stream);
 }
 
-hipError_t launch_front_materialize(const DevQuery* q, uint32_t query, int R, int k, const FrontEntry* entries,
-                                    const uint32_t* states, const FrontSurvivor* surv, uint32_t n_surv, int parent_len,
-                                    int keep_prefixes, FrontEntry* next_entries, uint32_t* next_states,
-                                    FrontEntry* next_literal, unsigned long long* valid_out, FrontCounters* ctr,
-                                    hipStream_t stream) {
-    if (n_surv == 0) return hipSuccess;
+hipError_t launch_front_materialize(const DevQuery* queries, int R, int k, const FrontLevel& level, hipStream_t stream) {
+    if (level.n_surv == 0) return hipSuccess;
     FrontArgs A{};
-    A.q = q; A.query = query; A.entries = entries; A.states = states; A.surv = const_cast<FrontSurvivor*>(surv); A.n_surv = n_surv;
-    A.parent_len = parent_len; A.keep_prefixes = keep_prefixes; A.next_entries = next_entries; A.next_states = next_states;
-    A.next_literal = next_literal; A.valid_out = valid_out; A.ctr = ctr; A.R = R;
+    A.queries = queries; A.level = &level; A.R = R;
     return front_dispatch(R, k, 2, A, stream);
 }
 
 hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry* entries, const FrontSurvivor* surv,
                              uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
-                             unsigned long long* valid_out, FrontCounters* ctr, hipStream_t stream) {
+                             unsigned long long* valid_out, double* goal_sums, int n_share, FrontCounters* ctr,
+                             hipStream_t stream) {
     if (n_surv == 0) return hipSuccess;
     hipLaunchKernelGGL(k_front_emit, dim3((n_surv + 255u) / 256u), dim3(256), 0, stream, q, query, entries, surv, n_surv, parent_len,
-                       keep_prefixes, next_literal, valid_out, ctr);
+                       keep_prefixes, next_literal, valid_out, goal_sums, n_share, ctr);
+    return hipGetLastError();
+}
+
+hipError_t launch_front_rank(const unsigned long long* valid, uint32_t n, uint32_t* rank, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_front_rank, dim3((n + 255u) / 256u), dim3(256), 0, stream, valid, n, rank);
+    return hipGetLastError();
+}
+
+hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish& F, hipStream_t stream) {
+    if (F.n_valid == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_front_finish, dim3((F.n_valid + 255u) / 256u), dim3(256), 0, stream, queries, F);
     return hipGetLastError();
 }
 

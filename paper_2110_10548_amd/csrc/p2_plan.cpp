@@ -319,7 +319,7 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     if (opt && opt->algo != 0 && opt->algo != 1) { err = "unknown cost model (algo is 0 = ring or 1 = tree)"; return P2_EUNSUPPORTED; }
     if (opt && (opt->hierarchy < 0 || opt->hierarchy > P2_HIERARCHY_REDUCTION)) { err = "unknown synthesis hierarchy"; return P2_EUNSUPPORTED; }
     if (opt && (opt->max_row_classes < 0 || opt->max_row_classes > 64)) { err = "max_row_classes outside 0..64"; return P2_EINVAL; }
-    if (opt && opt->reserved != 0) { err = "reserved option field is not 0"; return P2_EINVAL; }
+    if (opt && (opt->frontier_pairs < 0 || opt->frontier_pairs > P2_FRONTIER_PAIRS_NONE)) { err = "unknown frontier_pairs"; return P2_EINVAL; }
     if (opt && (opt->flags & ~P2_FLAG_EVALUATE_EVERY_QUERY) != 0) { err = "unknown option flag"; return P2_EINVAL; }
 
     pl = Plan();
@@ -327,6 +327,7 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     pl.algo = opt ? opt->algo : 0;
     pl.hierarchy = opt ? opt->hierarchy : P2_HIERARCHY_COLLAPSED;
     pl.max_row_classes = (opt && opt->max_row_classes > 0) ? opt->max_row_classes : 64;
+    pl.frontier_pairs = opt ? opt->frontier_pairs : P2_FRONTIER_PAIRS_AUTO;
     for (int j = 0; j < pl.n; ++j) {
         pl.h[j] = h->card[j];
         pl.bw[j] = h->bw_bytes_per_s ? h->bw_bytes_per_s[j] : 1.0;

@@ -57,6 +57,7 @@ struct Plan {
     std::vector<uint32_t> goal;        // [R][ceil(R/32)] goal mask of each local id; empty: all of the copy
     uint32_t form_mask = 7, op_mask = 31;
     int algo = 0;                  // cost model of AllReduce: 0 ring, 1 tree
+    int frontier_pairs = 0;        // P2_FRONTIER_PAIRS_*
     int max_row_classes = 64;      // limit of the literal kernels' state by classes of equal rows (1..64)
     int n_ops = 0, ops[5] = {0};
     std::vector<Pattern> patterns;

@@ -869,6 +869,31 @@ def test_frontier_four_levels_size_limit_six(B, oracle):
     assert res["stats"]["steps_executed"] < 1e8
 
 
+@pytest.mark.parametrize("pairs", [1, 2, 3, 4], ids=["one-pair", "two-pairs", "two-pairs-handed-over", "literal-only"])
+def test_frontier_state_forms(B, oracle, pairs):
+    """The frontier engine keeps a prefix as up to two (chunk set, mask) pairs per device.  The same lists and
+    costs must come out with one pair (what needs two goes to the literal kernels), with every two-pair prefix
+    handed to the literal kernels for classification (the path of prefixes whose groups are not aligned), and
+    with no pair states at all (every prefix literal, every program costed by re-running it)."""
+    cfg, queries = queries_of(2, B)
+    msg = cfg["msg_bytes"]
+    batch = [dict(q, engine=3, frontier_pairs=pairs) for q in queries]
+    four = dict(card=[2, 2, 2, 2], axes=[16], placement=[[2, 2, 2, 2]], reduce_axes=[0], max_len=5 if pairs != 4 else 4,
+                bw=[10e9, 40e9, 100e9, 300e9], alpha=[20e-6, 10e-6, 5e-6, 2e-6], engine=3, frontier_pairs=pairs)
+    odd = dict(card=[3, 2, 2], axes=[6, 2], placement=[[3, 2, 1], [1, 1, 2]], reduce_axes=[0], max_len=4, n_chunks=12,
+               bw=[10e9, 40e9, 100e9], alpha=[20e-6, 10e-6, 5e-6], engine=3, frontier_pairs=pairs)
+    batch += [four, dict(four, bw=[40e9, 10e9, 300e9, 100e9], algo=1), odd]
+    results = B.p2_synthesize_batch(batch, msg)
+    reruns = 0
+    for q, res in zip(batch, results):
+        _, ora = oracle_result(oracle, q, msg)
+        assert_same(res, ora, len(msg))
+        assert res["stats"]["engine"] == 3
+        reruns += res["stats"]["literal_reruns"]
+    # the two-pair form holds every prefix of these queries but a handful at five instructions
+    assert (reruns > 0) == (pairs != 2) or reruns < 200
+
+
 def test_frontier_matches_flat_engine_on_config3_sample(B):
     cfg, queries = queries_of(3, B)
     mine = [q for q in queries if _levels(q) == 3][:4] + [q for q in queries if _levels(q) == 2][:4]
