@@ -782,7 +782,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (;;) {     // classify; repeat with larger survivor lists if they overflow
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
-                P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, valid_written), stream));
+                P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
                                              static_cast<const uint32_t*>(C.f_states[cur].p), n_c, 1, max_pairs, 0,
                                              static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
@@ -814,18 +814,20 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                     P2_HIP(hipStreamSynchronize(stream));
                 }
-                if (hctr->n_surv <= cap_c && hctr->n_surv_literal <= cap_l) break;
+                if ((uint32_t)hctr->surv_goal <= cap_c && hctr->n_surv_literal <= cap_l) break;
                 // the repeated classification counts its steps again: take them back
-                cap_c = std::max<size_t>(cap_c, hctr->n_surv); cap_l = std::max<size_t>(cap_l, (size_t)hctr->n_surv_literal * 2);
+                cap_c = std::max<size_t>(cap_c, (uint32_t)hctr->surv_goal); cap_l = std::max<size_t>(cap_l, (size_t)hctr->n_surv_literal * 2);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
                 P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
                 P2_HIP(hipStreamSynchronize(stream));
             }
-            const uint32_t n_surv = hctr->n_surv, n_surv_l = hctr->n_surv_literal;
-            const uint32_t n_goal = hctr->n_goal, n_prefix = hctr->n_prefix, n_prefix2 = hctr->n_prefix2, n_plit = hctr->n_prefix_literal;
+            const uint32_t n_surv = (uint32_t)hctr->surv_goal, n_surv_l = hctr->n_surv_literal;
+            const uint32_t n_goal_pair = (uint32_t)(hctr->surv_goal >> 32), n_goal_lit = hctr->n_goal, n_goal = n_goal_pair + n_goal_lit;
+            const uint32_t n_prefix = (uint32_t)hctr->pref_pref2, n_prefix2 = (uint32_t)(hctr->pref_pref2 >> 32), n_plit = hctr->n_prefix_literal;
             r.steps = hctr->steps; r.members = hctr->members;
             r.n_rerun += n_plit + hctr->n_unknown;
+            E.n_goal_literal += n_goal_lit;
             P2_HIP(grow_keep(C.f_valid, (fvalid_used + E.n_valid + n_goal + 1) * sizeof(unsigned long long),
                              (fvalid_used + E.n_valid) * sizeof(unsigned long long), stream));
             P2_HIP(grow_keep(C.f_gsums, (fsums_used + ((size_t)E.n_valid + n_goal) * sum_doubles + 1) * sizeof(double),
@@ -840,8 +842,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
                 P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
             }
-            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used;
-            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used;
+            // goals of this level: those of the pair kernels at the places the classification gave them, then those of
+            // literal prefixes
+            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used + E.n_valid;
+            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used + (size_t)E.n_valid * sum_doubles;
+            unsigned long long* vout_lit = vout + n_goal_pair;
+            double* gsums_lit = gsums + (size_t)n_goal_pair * sum_doubles;
             FrontLevel lv;
             std::memset(&lv, 0, sizeof lv);
             lv.query = (uint32_t)i;
@@ -862,10 +868,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
             P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
                                      static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l_first, len, keep,
-                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, gsums, (int)sum_doubles / 2, dctr, stream));
+                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
             P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_unknown.p),
                                      static_cast<const FrontSurvivor*>(C.f_surv_literal.p) + n_surv_l_first, n_surv_l - n_surv_l_first, len, keep,
-                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout, gsums, (int)sum_doubles / 2, dctr, stream));
+                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
             E.n_valid += n_goal;
             n_c = keep ? n_prefix : 0;
             n_c2 = keep ? n_prefix2 : 0;
@@ -876,8 +882,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
         P2_HIP(hipStreamSynchronize(stream));
         r.steps = hctr->steps; r.members = hctr->members;
-        E.n_goal_literal = hctr->n_goal_literal;
-        if (hctr->valid_written != E.n_valid) return fail(P2_EDEVICE, "the frontier wrote another number of programs than it counted");
         fvalid_used += E.n_valid;
         fsums_used += (size_t)E.n_valid * sum_doubles;
         for (int32_t m : E.members) {        // every query of the enumeration reports its counts

@@ -239,17 +239,22 @@ struct FrontSurvivor {
     uint32_t entry;
     uint16_t digit;
     uint16_t code;
+    uint32_t slot;                 // pair kernels: the child's place in the next frontier list of its kind, or the
+                                   // goal's place among this level's goals
 };
 struct FrontCounters {
     // reset before every level
-    uint32_t n_surv, n_surv_literal;        // survivors appended by the pair-state / literal classify kernels
-    uint32_t n_goal, n_prefix, n_prefix_literal;
-    uint32_t next_compact, next_literal;    // entries written to the next frontiers
+    unsigned long long surv_goal;  // low half: survivors the pair kernels appended; high half: goals among them
+    unsigned long long pref_pref2; // low half: one-pair children; high half: two-pair children
+    uint32_t n_surv_literal;       // survivors appended by the literal classify kernels
+    uint32_t n_goal;               // goals among those
+    uint32_t n_prefix_literal;     // literal children (of any kernel)
+    uint32_t next_literal;         // entries written to the next literal list
     uint32_t next_unit;            // work counter of the device-driven literal launch whose first query this is
-    uint32_t n_overflow, n_prefix2;         // literal prefixes left to the full-state kernel; two-pair children
-    uint32_t next_compact2, n_unknown;      // entries written to the next two-pair list; two-pair prefixes handed to the literal kernels
+    uint32_t n_overflow;           // literal prefixes left to the full-state kernel
+    uint32_t n_unknown;            // two-pair prefixes handed to the literal kernels
+    uint32_t next_goal_literal;    // goals of literal prefixes written so far
     // running totals of the enumeration
-    uint32_t valid_written, n_goal_literal; // goals written; those among them that came from literal prefixes (no sums)
     unsigned long long steps, members;
 };
 // One level of one enumeration, for the materialize kernel.

@@ -40,7 +40,6 @@ namespace p2 {
 
 namespace {
 
-constexpr int kClassifyThreads = 128;
 
 enum : int { CODE_INVALID = 0, CODE_PREFIX = 1, CODE_GOAL = 2, CODE_PREFIX_LITERAL = 3, CODE_PREFIX2 = 4, CODE_UNKNOWN = 5 };
 constexpr int kFromTwoPair = 0x100;       // survivor code bit: the parent is an entry of the two-pair list
@@ -90,6 +89,33 @@ __device__ inline int lowest_bit(const Words<N>& a) {
     return pos;
 }
 
+// Layout of a state plane, in HBM and in LDS: per device the chunk set padded to whole 16-byte quads, then the
+// contribution mask padded likewise (the padding stays zero), so that a device is WQ quads and the
+// wavefront-wide kernels read it with 128-bit accesses.
+template <int KW, int MW>
+struct FL {
+    static constexpr int QK = (KW + 3) / 4, QM = (MW + 3) / 4, WQ = QK + QM;   // quads: rows, mask, device
+    static constexpr int WS = WQ * 4, MO = QK * 4;                             // words per device, offset of the mask
+};
+template <int KW, int MW>
+__device__ inline Slot<KW, MW> fload(const uint32_t* plane, int dev) {
+    const uint32_t* p = plane + dev * FL<KW, MW>::WS;
+    Slot<KW, MW> s;
+#pragma unroll
+    for (int i = 0; i < KW; ++i) s.r.w[i] = p[i];
+#pragma unroll
+    for (int i = 0; i < MW; ++i) s.m.w[i] = p[FL<KW, MW>::MO + i];
+    return s;
+}
+template <int KW, int MW>
+__device__ inline void fstore(uint32_t* plane, int dev, const Words<KW>& r, const Words<MW>& m) {
+    uint32_t* p = plane + dev * FL<KW, MW>::WS;
+#pragma unroll
+    for (int i = 0; i < KW; ++i) p[i] = r.w[i];
+#pragma unroll
+    for (int i = 0; i < MW; ++i) p[FL<KW, MW>::MO + i] = m.w[i];
+}
+
 // The (up to) two pairs of a device: x1 empty <=> one pair.
 template <int KW, int MW>
 struct Pairs {
@@ -98,12 +124,11 @@ struct Pairs {
 };
 template <int KW, int MW>
 __device__ inline Pairs<KW, MW> load_pairs(const uint32_t* st, int R, int np, int dev) {
-    constexpr int WPD = KW + MW;
-    const Slot<KW, MW> a = load_slot<KW, MW>(st, WPD, dev);
+    const Slot<KW, MW> a = fload<KW, MW>(st, dev);
     Pairs<KW, MW> p;
     p.x0 = a.r; p.m0 = a.m;
     if (np == 2) {
-        const Slot<KW, MW> b = load_slot<KW, MW>(st + R * WPD, WPD, dev);
+        const Slot<KW, MW> b = fload<KW, MW>(st + R * FL<KW, MW>::WS, dev);
         p.x1 = b.r; p.m1 = b.m;
     } else {
         p.x1 = zero_words<KW>(); p.m1 = zero_words<MW>();
@@ -114,7 +139,6 @@ __device__ inline Pairs<KW, MW> load_pairs(const uint32_t* st, int R, int np, in
 // row first.  np = planes of the destination (with one plane the second pair must come out empty).
 template <int KW, int MW>
 __device__ inline void store_pairs(uint32_t* st, int R, int np, int dev, Words<KW> x0, Words<MW> m0, Words<KW> x1, Words<MW> m1) {
-    constexpr int WPD = KW + MW;
     if (fold_or(x0) == 0u) m0 = zero_words<MW>();
     if (fold_or(x1) == 0u) m1 = zero_words<MW>();
     if (fold_or(x1) != 0u && fold_xor(m0, m1) == 0u) { x0 = or_words(x0, x1); x1 = zero_words<KW>(); m1 = zero_words<MW>(); }
@@ -122,8 +146,8 @@ __device__ inline void store_pairs(uint32_t* st, int R, int np, int dev, Words<K
         const Words<KW> tx = x0; x0 = x1; x1 = tx;
         const Words<MW> tm = m0; m0 = m1; m1 = tm;
     }
-    store_slot<KW, MW>(st, WPD, dev, x0, m0);
-    if (np == 2) store_slot<KW, MW>(st + R * WPD, WPD, dev, x1, m1);
+    fstore<KW, MW>(st, dev, x0, m0);
+    if (np == 2) fstore<KW, MW>(st + R * FL<KW, MW>::WS, dev, x1, m1);
 }
 
 // ---- one AllReduce-like group on (up to) two-pair members --------------------------------------------
@@ -133,7 +157,9 @@ struct RedFold {
     Words<KW> xa;         // rows of plane A where the group is split (pair 0 of the members with two pairs)
     Words<MW> accA, accB; // united masks of plane A (rows xa) and plane B (rows u0 \ xa); equal when not split
     bool split;           // some member has two pairs
-    uint32_t bad;         // rows differ between members, or a contribution would be reduced twice
+    uint32_t bad;         // rows differ between members, or a contribution would be reduced twice in plane A (every
+                          // member's pair 0 holds the lowest row, so an overlap there is one whatever the split)
+    uint32_t badB;        // a contribution reduced twice in plane B: means something only if the group is aligned
     uint32_t unaligned;   // two members split their rows differently
 };
 template <int KW, int MW>
@@ -145,7 +171,7 @@ __device__ inline RedFold<KW, MW> fold_red(const uint32_t* st, int R, int np, in
     f.xa = p.x0;
     f.accA = p.m0;
     f.accB = f.split ? p.m1 : p.m0;
-    f.bad = 0; f.unaligned = 0;
+    f.bad = 0; f.badB = 0; f.unaligned = 0;
     for (int t = 1; t < g; ++t) {
         p = load_pairs<KW, MW>(st, R, np, base + t * s);
         const bool two = fold_or(p.x1) != 0u;
@@ -155,7 +181,8 @@ __device__ inline RedFold<KW, MW> fold_red(const uint32_t* st, int R, int np, in
             else { f.split = true; f.xa = p.x0; }
         }
         const Words<MW> mB = two ? p.m1 : p.m0;
-        f.bad |= fold_and(p.m0, f.accA) | fold_and(mB, f.accB);
+        f.bad |= fold_and(p.m0, f.accA);
+        f.badB |= fold_and(mB, f.accB);
         f.accA = or_words(f.accA, p.m0);
         f.accB = or_words(f.accB, mB);
     }
@@ -232,7 +259,7 @@ __device__ inline int classify_pairs(const uint32_t* st, const PatLds P, int op,
         }
         if (op == OP_AR || op == OP_RS || op == OP_RD) {
             const RedFold<KW, MW> f = fold_red<KW, MW>(st, R, np, base, P.g, P.s);
-            bad |= f.bad != 0u;
+            bad |= f.bad != 0u || (f.unaligned == 0u && f.badB != 0u);
             unknown |= f.bad == 0u && f.unaligned != 0u;
             const bool some = fold_or(f.u0) != 0u;
             changed |= some;
@@ -294,7 +321,6 @@ __device__ inline int classify_pairs(const uint32_t* st, const PatLds P, int op,
 template <int KW, int MW>
 __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, int R, const Words<KW>& all_rows,
                                     const Words<MW>& all_cols, int n_goal) {
-    constexpr int WPD = KW + MW;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
     uint32_t badx = 0;
     bool changed = false, two_masks = false, over = false, all_goal = true;
@@ -308,7 +334,7 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
     bool anyzero = false, third = false;
     const int n_part = P.n_groups * P.g;
     for (int j = 0; j < n_part; ++j) {
-        const Slot<KW, MW> cur = load_slot<KW, MW>(st, WPD, wk.dev);
+        const Slot<KW, MW> cur = fload<KW, MW>(st, wk.dev);
         goal_part += (fold_xor(cur.r, all_rows) | fold_xor(cur.m, all_cols)) == 0 ? 1 : 0;
         if (wk.p == 0) {
             first = cur; acc = cur;
@@ -364,87 +390,332 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
     return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
 }
 
-// np = 1: entries of the one-pair list, np = 2: of the two-pair list.  max_pairs < 2 sends every child that
-// needs two pairs to the literal list instead (and the two-pair list stays empty).
-template <int KW, int MW>
-__global__ __launch_bounds__(kClassifyThreads) void k_front_classify(const DevQuery* __restrict__ qp,
-                                                                     const FrontEntry* __restrict__ entries,
-                                                                     const uint32_t* __restrict__ states, uint32_t n_entries,
-                                                                     int np, int max_pairs, int handover,
-                                                                     FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
-                                                                     FrontEntry* __restrict__ unknown_out,
-                                                                     FrontCounters* __restrict__ ctr) {
-    extern __shared__ uint32_t lds[];
+// ---- classification, a wavefront per pattern ----------------------------------------------------------
+// Block = one prefix (its planes in LDS), wavefront = one pattern at a time, all rules of that pattern at
+// once.  A lane is (slot, quad): the 8 lanes of a slot read one device with one 128-bit access each, so a
+// wavefront has 8 devices in flight; the slots of a wavefront walk 8 groups of the pattern side by side,
+// member after member (patterns with fewer than 8 groups give every group several slots, which share
+// its members).  Per 32-bit word of the state a lane keeps, over the members of its group: the union,
+// the intersection, the bits seen in two members, and the first member's word.  Every premise of Sec. 3.2
+// on one-pair states is a statement about those:
+//   same rows on every member        union == intersection (chunk-set words)
+//   no contribution reduced twice    no mask bit seen twice
+//   AllGather: rows held once        no chunk-set bit seen twice;  nobody empty: a flag per device
+//   Broadcast: root knows more       union == the first member's words, and union != intersection somewhere
+//   results: AllReduce leaves (rows, united mask), AllGather (united rows, mask), Broadcast the root's pair
+// On two-pair states the AllReduce-like rules are the same statements plane by plane (plane B of a member
+// with one pair is its only pair), plus: the members that have two pairs split their rows alike.  What
+// these word-wise accumulators cannot decide is rare and goes to the single-lane routines above, which walk
+// the pairs: an AllGather of members with different masks (how many masks?), a ReduceScatter of a split
+// group (does a block straddle the split?), a Broadcast among two-pair devices that passes the
+// necessary conditions checked here.
+// Survivors of kClsBatch prefixes are written together: one reservation of list positions and of the
+// children's places in the next frontier per batch, so that the few counters are not hammered.
+constexpr int kClsThreads = 512, kClsWaves = kClsThreads / 64, kClsBatch = 8;
+
+__device__ inline uint4 q_or(uint4 a, uint4 b) { return make_uint4(a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w); }
+__device__ inline uint4 q_and(uint4 a, uint4 b) { return make_uint4(a.x & b.x, a.y & b.y, a.z & b.z, a.w & b.w); }
+__device__ inline uint4 q_andn(uint4 a, uint4 b) { return make_uint4(a.x & ~b.x, a.y & ~b.y, a.z & ~b.z, a.w & ~b.w); }
+__device__ inline uint4 q_xor(uint4 a, uint4 b) { return make_uint4(a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w); }
+__device__ inline bool q_any(uint4 a) { return (a.x | a.y | a.z | a.w) != 0u; }
+__device__ inline int q_popc(uint4 a) { return __popc(a.x) + __popc(a.y) + __popc(a.z) + __popc(a.w); }
+__device__ inline uint4 q_zero() { return make_uint4(0u, 0u, 0u, 0u); }
+__device__ inline uint4 q_ones() { return make_uint4(~0u, ~0u, ~0u, ~0u); }
+__device__ inline uint4 q_shfl_xor(uint4 a, int m) {
+    return make_uint4(__shfl_xor(a.x, m, 64), __shfl_xor(a.y, m, 64), __shfl_xor(a.z, m, 64), __shfl_xor(a.w, m, 64));
+}
+__device__ inline uint4 q_shfl(uint4 a, int src) {
+    return make_uint4(__shfl(a.x, src, 64), __shfl(a.y, src, 64), __shfl(a.z, src, 64), __shfl(a.w, src, 64));
+}
+// union / intersection / seen-twice of a run of members; two runs put together
+struct QAcc {
+    uint4 o, a, t;
+    __device__ inline void init() { o = q_zero(); a = q_ones(); t = q_zero(); }
+    __device__ inline void add(uint4 v) { t = q_or(t, q_and(v, o)); o = q_or(o, v); a = q_and(a, v); }
+    __device__ inline void merge_xor(int m) {
+        const uint4 oo = q_shfl_xor(o, m), oa = q_shfl_xor(a, m), ot = q_shfl_xor(t, m);
+        t = q_or(q_or(t, ot), q_and(o, oo)); o = q_or(o, oo); a = q_and(a, oa);
+    }
+    __device__ inline bool differ() const { return q_any(q_xor(o, a)); }
+};
+
+constexpr uint32_t kFlagEmpty = 1u, kFlagGoal = 2u, kFlagTwo = 4u;
+
+template <int KW, int MW, int NP>
+__global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* __restrict__ qp,
+                                                                const FrontEntry* __restrict__ entries,
+                                                                const uint32_t* __restrict__ states, uint32_t n_entries,
+                                                                int max_pairs, int handover, FrontSurvivor* __restrict__ surv,
+                                                                uint32_t surv_cap, FrontEntry* __restrict__ unknown_out,
+                                                                FrontCounters* __restrict__ ctr) {
+    extern __shared__ uint4 ldsq[];                      // NP planes of [R][WQ] quads, then R flag bytes
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint16_t sdig[kMaxPatterns * 5];
-    __shared__ int s_goal, s_two, s_unknown;
+    __shared__ uint8_t s_code[kClsBatch][kMaxPatterns * 5];
+    __shared__ uint32_t s_entry[kClsBatch];
+    __shared__ int s_unknown[kClsBatch];
+    __shared__ int s_goal, s_two;
+    using L = FL<KW, MW>;
     const DevQuery& q = *qp;
-    constexpr int WPD = KW + MW;
-    const int R = q.R, I = q.alphabet;
-    const int words = np * R * WPD;
-    for (int i = threadIdx.x; i < q.n_patterns; i += kClassifyThreads) {
+    const int R = q.R, I = q.alphabet, n_ops = q.n_ops, n_pat = q.n_patterns;
+    const int plane_q = R * L::WQ;                       // quads per plane
+    uint8_t* const flags = reinterpret_cast<uint8_t*>(ldsq + (size_t)NP * plane_q);
+    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(ldsq);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = lane >> 3, qd = lane & 7;
+    const bool is_row = qd < L::QK, is_mask = qd >= L::QK && qd < L::WQ, has_quad = qd < L::WQ;
+    for (int i = tid; i < n_pat; i += kClsThreads) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
     }
-    for (int i = threadIdx.x; i < I; i += kClassifyThreads) sdig[i] = q.instr_of_digit[i];
+    for (int i = tid; i < I; i += kClsThreads) sdig[i] = q.instr_of_digit[i];
     const Words<KW> all_rows = full_mask<KW>(q.k);
     const Words<MW> all_cols = full_mask<MW>(R);
-    unsigned long long steps = 0, members = 0;
+    // this lane's quad of a device at the goal: every row, every column of the reduction group
+    uint4 goal_quad;
+    {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int i = 0; i < KW; ++i) if (is_row && i == qd * 4 + j) w[j] = all_rows.w[i];
+#pragma unroll
+            for (int i = 0; i < MW; ++i) if (is_mask && i == (qd - L::QK) * 4 + j) w[j] = all_cols.w[i];
+        }
+        goal_quad = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    unsigned long long judged = 0;                       // prefixes this block judged itself (thread 0 counts)
+    int pending = 0;
     for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
         __syncthreads();
-        const uint32_t* src = states + (size_t)e * words;
-        for (int i = threadIdx.x; i < words; i += kClassifyThreads) lds[i] = src[i];
-        if (threadIdx.x == 0) { s_goal = 0; s_two = 0; s_unknown = 0; }
+        const uint4* src = reinterpret_cast<const uint4*>(states) + (size_t)e * NP * plane_q;
+        for (int i = tid; i < NP * plane_q; i += kClsThreads) ldsq[i] = src[i];
+        if (tid == 0) { s_goal = 0; s_two = 0; s_entry[pending] = e; s_unknown[pending] = (NP == 2 && handover) ? 1 : 0; }
         __syncthreads();
-        int mine = 0, two = 0;
-        for (int d = threadIdx.x; d < R; d += kClassifyThreads) {
-            const Slot<KW, MW> sl = load_slot<KW, MW>(lds, WPD, d);
-            const bool has_two = np == 2 && fold_or(load_slot<KW, MW>(lds + R * WPD, WPD, d).r) != 0u;
-            two += has_two ? 1 : 0;
-            mine += (!has_two && (fold_xor(sl.r, all_rows) | fold_xor(sl.m, all_cols)) == 0) ? 1 : 0;
+        // ---- per device: is it empty, is it at the goal, does it hold two pairs
+        {
+            int at_goal = 0, with_two = 0;
+            for (int d0 = wave * 8; d0 < R; d0 += kClsWaves * 8) {
+                const int d = d0 + slot;
+                const bool act = d < R && has_quad;
+                const uint4 v = act ? ldsq[d * L::WQ + qd] : q_zero();
+                const uint4 v1 = (NP == 2 && act) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+                const unsigned long long nz = __ballot(act && is_row && q_any(v));
+                const unsigned long long ng = __ballot(act && q_any(q_xor(v, goal_quad)));
+                const unsigned long long n2 = NP == 2 ? __ballot(act && is_row && q_any(v1)) : 0ull;
+                if (qd == 0 && d < R) {
+                    const bool empty = ((nz >> (slot * 8)) & 0xffull) == 0ull, two = ((n2 >> (slot * 8)) & 0xffull) != 0ull;
+                    const bool goal = ((ng >> (slot * 8)) & 0xffull) == 0ull && !two;
+                    flags[d] = (uint8_t)((empty ? kFlagEmpty : 0u) | (goal ? kFlagGoal : 0u) | (two ? kFlagTwo : 0u));
+                    at_goal += goal ? 1 : 0;
+                    with_two += two ? 1 : 0;
+                }
+            }
+            for (int o = 32; o > 0; o >>= 1) { at_goal += __shfl_xor(at_goal, o, 64); with_two += __shfl_xor(with_two, o, 64); }
+            if (lane == 0 && at_goal) atomicAdd(&s_goal, at_goal);
+            if (lane == 0 && with_two) atomicAdd(&s_two, with_two);
         }
-        if (mine) atomicAdd(&s_goal, mine);
-        if (two) atomicAdd(&s_two, two);
         __syncthreads();
         const int n_goal = s_goal, n_two = s_two;
-        // (an alphabet of more than kClassifyThreads instructions takes several rounds; a round's codes are kept)
-        int codes[(kMaxPatterns * 5 + kClassifyThreads - 1) / kClassifyThreads];
-        int n_mine = 0;
-        for (int a = threadIdx.x; a < I; a += kClassifyThreads, ++n_mine) {
-            const uint32_t ins = sdig[a];
-            const PatLds P = spat[ins >> 3];
-            int code = np == 2 ? classify_pairs<KW, MW>(lds, P, (int)(ins & 7u), R, 2, all_rows, all_cols, n_goal, n_two)
-                               : classify_step<KW, MW>(lds, P, (int)(ins & 7u), R, all_rows, all_cols, n_goal);
-            if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
-            if (code == CODE_UNKNOWN || handover) s_unknown = 1;
-            codes[n_mine] = code;
-        }
-        __syncthreads();
-        if (s_unknown) {
-            // this form cannot judge one of the instructions: the literal kernels take the whole prefix
-            if (threadIdx.x == 0) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[e];
-            continue;
-        }
-        n_mine = 0;
-        for (int a = threadIdx.x; a < I; a += kClassifyThreads, ++n_mine) {
-            const int code = codes[n_mine];
-            const PatLds P = spat[sdig[a] >> 3];
-            ++steps;
-            members += (unsigned long long)(P.n_groups * P.g);
-            if (code != CODE_INVALID) {
-                const uint32_t pos = atomicAdd(&ctr->n_surv, 1u);
-                if (pos < surv_cap) {
-                    FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (np == 2 ? kFromTwoPair : 0));
-                    surv[pos] = sv;
+        // ---- patterns
+        for (int pid = wave; pid < n_pat; pid += kClsWaves) {
+            const PatLds P = spat[pid];
+            const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+            int spg = 1;                                         // slots that share a group
+            while (spg * 2 * ng <= 8) spg *= 2;
+            const int gpb = 8 / spg;                             // groups side by side
+            const int my_g = slot / spg, part = slot - my_g * spg;
+            const int trips = (g + spg - 1) / spg;
+            bool bad_red = false, bad_b = false, unal = false, bad_rs = false, bad_ag = false, changed = false, ag_uneq = false;
+            bool bad_bc1 = false, bc_fail = false, any_two = false;
+            bool ng_ar = false, ng_ag = false, ng_bc = false;    // some device is not at the goal afterwards
+            uint32_t fl_pat = 0;
+            int goal_part = 0, two_part = 0;
+            for (int G0 = 0; G0 < ng; G0 += gpb) {
+                const int G = G0 + my_g;
+                const bool act = G < ng && has_quad;
+                int base = 0;
+                if (P.master) base = G * gs;
+                else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+                // row lanes: p = rows (both pairs), al = pair-0 rows of the members with two pairs
+                // mask lanes: p = plane A (pair 0), sB = plane B, al = every pair's mask
+                QAcc p, sB, al, i0, i1;
+                p.init(); sB.init(); al.init(); i0.init(); i1.init();
+                uint4 first0 = q_zero(), first1 = q_zero();
+                uint32_t fl_or = 0;
+                for (int it = 0; it < trips; ++it) {
+                    const int t = it * spg + part;
+                    if (act && t < g) {
+                        const int d = base + t * s;
+                        const uint4 v0 = ldsq[d * L::WQ + qd];
+                        const uint32_t f = flags[d];
+                        fl_or |= f;
+                        goal_part += (qd == 0 && (f & kFlagGoal)) ? 1 : 0;
+                        if constexpr (NP == 2) {
+                            const uint4 v1 = ldsq[plane_q + d * L::WQ + qd];
+                            const bool two = (f & kFlagTwo) != 0u;
+                            two_part += (qd == 0 && two) ? 1 : 0;
+                            i0.add(v0); i1.add(v1);
+                            if (is_row) {
+                                p.add(q_or(v0, v1));
+                                if (two) al.add(v0);
+                            } else {
+                                p.add(v0);
+                                sB.add(two ? v1 : v0);
+                                al.add(v0);
+                                if (two) al.add(v1);
+                            }
+                            if (t == 0) { first0 = v0; first1 = v1; }
+                        } else {
+                            p.add(v0);
+                            if (t == 0) first0 = v0;
+                        }
+                    }
                 }
-                atomicAdd(code == CODE_GOAL ? &ctr->n_goal : code == CODE_PREFIX ? &ctr->n_prefix
-                          : code == CODE_PREFIX2 ? &ctr->n_prefix2 : &ctr->n_prefix_literal, 1u);
+                for (int m = 8; m < 8 * spg; m <<= 1) {          // the slots of one group put their members together
+                    p.merge_xor(m);
+                    if constexpr (NP == 2) { sB.merge_xor(m); al.merge_xor(m); i0.merge_xor(m); i1.merge_xor(m); }
+                    fl_or |= (uint32_t)__shfl_xor((int)fl_or, m, 64);
+                }
+                if (spg > 1) {
+                    first0 = q_shfl(first0, (slot - part) * 8 + qd);
+                    if constexpr (NP == 2) first1 = q_shfl(first1, (slot - part) * 8 + qd);
+                }
+                fl_pat |= act ? fl_or : 0u;
+                int rows = (act && is_row) ? q_popc(p.o) : 0;
+                rows += __shfl_xor(rows, 1, 64); rows += __shfl_xor(rows, 2, 64); rows += __shfl_xor(rows, 4, 64);
+                const int sh = slot * 8;
+                if constexpr (NP == 1) {
+                    const unsigned long long dif_slots = __ballot(act && p.differ());
+                    if (act) {
+                        const bool twice = q_any(p.t), differ = p.differ();
+                        if (is_row) { bad_red |= differ; bad_ag |= twice; changed |= q_any(p.o); }
+                        else { bad_red |= twice; ag_uneq |= differ; }
+                        bad_rs |= div_small(rows, g) * g != rows;
+                        bad_ag |= (fl_or & kFlagEmpty) != 0u;
+                        bad_bc1 |= q_any(q_xor(p.o, first0)) || ((dif_slots >> sh) & 0xffull) == 0ull;
+                        ng_ar |= q_any(q_xor(p.o, goal_quad));
+                        ng_ag |= q_any(q_xor(is_row ? p.o : first0, goal_quad));
+                        ng_bc |= q_any(q_xor(first0, goal_quad));
+                    }
+                } else {
+                    const bool g_two = (fl_or & kFlagTwo) != 0u;
+                    const unsigned long long unal_slots = __ballot(act && is_row && g_two && al.differ());
+                    const unsigned long long split_slots = __ballot(act && is_mask && g_two && q_any(q_xor(p.o, sB.o)));
+                    const unsigned long long dif_slots = __ballot(act && (i0.differ() || i1.differ()));
+                    if (act) {
+                        const bool unal_g = ((unal_slots >> sh) & 0xffull) != 0ull, split_g = ((split_slots >> sh) & 0xffull) != 0ull;
+                        const bool differs_g = ((dif_slots >> sh) & 0xffull) != 0ull;
+                        if (is_row) { bad_red |= p.differ(); bad_ag |= q_any(p.t); changed |= q_any(p.o); }
+                        else { bad_red |= q_any(p.t); bad_b |= !unal_g && q_any(sB.t); ag_uneq |= al.differ(); }
+                        unal |= unal_g;
+                        any_two |= split_g;
+                        bad_rs |= div_small(rows, g) * g != rows;
+                        bad_ag |= (fl_or & kFlagEmpty) != 0u;
+                        // Broadcast, exact where no member of the pattern holds two pairs ...
+                        bad_bc1 |= q_any(q_xor(p.o, first0)) || !differs_g;
+                        // ... and otherwise what must hold at least: rows and masks inside the root's, someone differs
+                        if (is_row) bc_fail |= q_any(q_xor(p.o, q_or(first0, first1)));
+                        else bc_fail |= q_any(q_andn(al.o, q_or(first0, first1)));
+                        bc_fail |= !differs_g;
+                        ng_ar |= q_any(q_xor(p.o, goal_quad)) || split_g;
+                        ng_ag |= q_any(q_xor(is_row ? p.o : al.o, goal_quad));
+                        ng_bc |= q_any(q_xor(first0, goal_quad)) || q_any(first1);
+                    }
+                }
+            }
+            const bool BAD_RED = __any(bad_red), BAD_B = __any(bad_b), UNAL = __any(unal), BAD_RS = __any(bad_rs);
+            const bool BAD_AG = __any(bad_ag), CHANGED = __any(changed), AG_UNEQ = __any(ag_uneq);
+            const bool BAD_BC1 = __any(bad_bc1), BC_FAIL = __any(bc_fail), ANY_TWO = __any(any_two);
+            const bool NG_AR = __any(ng_ar), NG_AG = __any(ng_ag), NG_BC = __any(ng_bc);
+            const bool PAT_TWO = __any((fl_pat & kFlagTwo) != 0u);
+            for (int o = 32; o > 0; o >>= 1) { goal_part += __shfl_xor(goal_part, o, 64); two_part += __shfl_xor(two_part, o, 64); }
+            const bool rest_done = (n_goal - goal_part) == (R - ng * g);        // the devices left untouched are at the goal
+            const bool rest_two = n_two - two_part > 0;                         // ... or one of them holds two pairs
+            if (lane == 0) {
+                for (int oi = 0; oi < n_ops; ++oi) {
+                    const int op = q.ops[oi];
+                    int code;
+                    if (op == OP_AR || op == OP_RS || op == OP_RD) {
+                        if (BAD_RED || !CHANGED || (op == OP_RS && BAD_RS)) code = CODE_INVALID;
+                        else if (UNAL) code = CODE_UNKNOWN;
+                        else if (BAD_B) code = CODE_INVALID;
+                        else if (op == OP_RS) {
+                            if (ANY_TWO) code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
+                            else code = rest_two ? CODE_PREFIX2 : CODE_PREFIX;
+                        } else if (ANY_TWO || rest_two) code = CODE_PREFIX2;
+                        else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
+                    } else if (op == OP_AG) {
+                        if (BAD_AG) code = CODE_INVALID;
+                        else if (AG_UNEQ) {
+                            // members with different masks: two pairs per device, or more (count them)
+                            code = NP == 2 ? classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two)
+                                           : classify_step<KW, MW>(lds_words, P, op, R, all_rows, all_cols, n_goal);
+                        } else if (rest_two) code = CODE_PREFIX2;
+                        else code = (!NG_AG && rest_done) ? CODE_GOAL : CODE_PREFIX;
+                    } else {
+                        if (!PAT_TWO) code = BAD_BC1 ? CODE_INVALID : rest_two ? CODE_PREFIX2 : (!NG_BC && rest_done) ? CODE_GOAL : CODE_PREFIX;
+                        else if (BC_FAIL) code = CODE_INVALID;
+                        else code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
+                    }
+                    if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
+                    if (code == CODE_UNKNOWN) s_unknown[pending] = 1;
+                    s_code[pending][pid * n_ops + oi] = (uint8_t)code;
+                }
             }
         }
+        ++pending;
+        if (pending < kClsBatch && e + gridDim.x < n_entries) continue;
+        // ---- write the batch's survivors: wavefront 0 counts them by kind, reserves once, writes
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t c_surv = 0, c_goal = 0, c_p1 = 0, c_p2 = 0;
+            for (int b = 0; b < pending; ++b) {
+                if (s_unknown[b]) continue;
+                for (int a = lane; a < I; a += 64) {
+                    const int code = s_code[b][a];
+                    c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
+                }
+            }
+            uint32_t x_surv = c_surv, x_goal = c_goal, x_p1 = c_p1, x_p2 = c_p2;          // inclusive sums over the lanes
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t a0 = __shfl_up(x_surv, o, 64), a1 = __shfl_up(x_goal, o, 64), a2 = __shfl_up(x_p1, o, 64), a3 = __shfl_up(x_p2, o, 64);
+                if (lane >= o) { x_surv += a0; x_goal += a1; x_p1 += a2; x_p2 += a3; }
+            }
+            const uint32_t t_surv = __shfl(x_surv, 63, 64), t_goal = __shfl(x_goal, 63, 64), t_p1 = __shfl(x_p1, 63, 64), t_p2 = __shfl(x_p2, 63, 64);
+            unsigned long long b0 = 0, b1 = 0;
+            if (lane == 0) {
+                if (t_surv) b0 = atomicAdd(&ctr->surv_goal, (unsigned long long)t_surv | ((unsigned long long)t_goal << 32));
+                if (t_p1 | t_p2) b1 = atomicAdd(&ctr->pref_pref2, (unsigned long long)t_p1 | ((unsigned long long)t_p2 << 32));
+                for (int b = 0; b < pending; ++b) {
+                    if (s_unknown[b]) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[s_entry[b]];
+                    else ++judged;
+                }
+            }
+            b0 = __shfl(b0, 0, 64); b1 = __shfl(b1, 0, 64);
+            uint32_t at_surv = (uint32_t)b0 + x_surv - c_surv, at_goal = (uint32_t)(b0 >> 32) + x_goal - c_goal;
+            uint32_t at_p1 = (uint32_t)b1 + x_p1 - c_p1, at_p2 = (uint32_t)(b1 >> 32) + x_p2 - c_p2;
+            for (int b = 0; b < pending; ++b) {
+                if (s_unknown[b]) continue;
+                for (int a = lane; a < I; a += 64) {
+                    const int code = s_code[b][a];
+                    if (code == CODE_INVALID) continue;
+                    FrontSurvivor sv;
+                    sv.entry = s_entry[b]; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
+                    sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
+                    if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
+                    if (at_surv < surv_cap) surv[at_surv] = sv;
+                    ++at_surv;
+                }
+            }
+        }
+        pending = 0;
     }
-    for (int o = 32; o > 0; o >>= 1) { steps += __shfl_xor(steps, o, 64); members += __shfl_xor(members, o, 64); }
-    if ((threadIdx.x & 63) == 0 && steps) { atomicAdd(&ctr->steps, steps); atomicAdd(&ctr->members, members); }
+    if (tid == 0 && judged) {
+        atomicAdd(&ctr->steps, judged * (unsigned long long)I);
+        atomicAdd(&ctr->members, judged * (unsigned long long)q.reg_sum_part);
+    }
 }
 
 __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long long digits, int len) {
@@ -457,10 +728,9 @@ __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long lo
 template <int KW, int MW>
 __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
     __shared__ PatLds spat[kMaxPatterns];
-    __shared__ uint32_t s_slot;
     __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];        // rows that set a group's bytes
     const DevQuery& q = queries[A.query];
-    constexpr int WPD = KW + MW;
+    constexpr int WPD = FL<KW, MW>::WS;
     const int lane = threadIdx.x;
     const int R = q.R;
     const int plane = R * WPD;
@@ -470,6 +740,7 @@ __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __rest
         spat[i] = p;
     }
     __syncthreads();
+    unsigned long long made = 0, made_members = 0;       // children built (an instruction application each)
     for (uint32_t i = blockIdx.x; i < A.n_surv; i += gridDim.x) {
         const FrontSurvivor sv = A.surv[i];
         const int code = sv.code & 0xff;
@@ -486,21 +757,14 @@ __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __rest
         const uint32_t* parent = (np == 2 ? A.states2 + (size_t)sv.entry * 2 * plane : A.states1 + (size_t)sv.entry * plane);
         const double* psum = (np == 2 ? A.sums2 : A.sums1) + (size_t)sv.entry * 2 * A.n_share;
         const int cnp = code == CODE_PREFIX2 ? 2 : 1;
-        __syncthreads();
+        // (the classification gave every child its place in the next frontier, every goal its place in the list)
+        const uint32_t slot = sv.slot;
         if (lane == 0) {
-            if (code == CODE_GOAL) {
-                s_slot = atomicAdd(&A.ctr->valid_written, 1u);
-                A.valid_out[s_slot] = rank_of(q, digits, A.parent_len + 1);
-            } else if (code == CODE_PREFIX2) {
-                s_slot = atomicAdd(&A.ctr->next_compact2, 1u);
-                A.next_entries2[s_slot] = ce;
-            } else {
-                s_slot = atomicAdd(&A.ctr->next_compact, 1u);
-                A.next_entries1[s_slot] = ce;
-            }
+            if (code == CODE_GOAL) A.valid_out[slot] = rank_of(q, digits, A.parent_len + 1);
+            else if (code == CODE_PREFIX2) A.next_entries2[slot] = ce;
+            else A.next_entries1[slot] = ce;
         }
         __syncthreads();
-        const uint32_t slot = s_slot;
         uint32_t* child = nullptr;
         if (code == CODE_PREFIX2) child = A.next_states2 + (size_t)slot * 2 * plane;
         else if (code == CODE_PREFIX) child = A.next_states1 + (size_t)slot * plane;
@@ -583,8 +847,9 @@ __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __rest
                 }
             }
         }
-        if (lane == 0 && code != CODE_GOAL) { atomicAdd(&A.ctr->steps, 1ull); atomicAdd(&A.ctr->members, (unsigned long long)(P.n_groups * P.g)); }
+        if (code != CODE_GOAL) { ++made; made_members += (unsigned long long)(P.n_groups * P.g); }
     }
+    if (lane == 0 && made) { atomicAdd(&A.ctr->steps, made); atomicAdd(&A.ctr->members, made_members); }
 }
 
 // Survivors of the literal frontier carry no state: a goal becomes a valid program, the rest
@@ -596,15 +861,15 @@ __global__ __launch_bounds__(256) void k_front_emit(const DevQuery* __restrict__
                                                     int keep_prefixes, FrontEntry* __restrict__ next_literal,
                                                     unsigned long long* __restrict__ valid_out, double* __restrict__ goal_sums,
                                                     int n_share, FrontCounters* __restrict__ ctr) {
+    // (valid_out / goal_sums start behind the goals of this level that the pair kernels found)
     const DevQuery& q = *qp;
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= n_surv) return;
     const FrontSurvivor sv = surv[i];
     const unsigned long long digits = entries[sv.entry].digits | ((unsigned long long)sv.digit << (9 * parent_len));
     if (sv.code == CODE_GOAL) {
-        const uint32_t slot = atomicAdd(&ctr->valid_written, 1u);
+        const uint32_t slot = atomicAdd(&ctr->next_goal_literal, 1u);
         valid_out[slot] = rank_of(q, digits, parent_len + 1);
-        atomicAdd(&ctr->n_goal_literal, 1u);
         for (int j = 0; j < 2 * n_share; ++j) goal_sums[(size_t)slot * 2 * n_share + j] = __longlong_as_double(0x7ff8000000000000ll);
     } else if (keep_prefixes) {
         FrontEntry ce;
@@ -618,13 +883,15 @@ __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ 
                                                    uint32_t* states, double* sums, int n_share) {
     // Sec. 3.5: the empty program; device i holds column i in every row
     const DevQuery& q = *qp;
-    constexpr int WPD = KW + MW;
+    constexpr int WPD = FL<KW, MW>::WS;
     const Words<KW> all_rows = full_mask<KW>(q.k);
+    for (int i = threadIdx.x; i < q.R * WPD; i += 64) states[i] = 0u;         // (the padding stays zero for good)
+    __syncthreads();
     for (int d = threadIdx.x; d < q.R; d += 64) {
         Words<MW> m;
 #pragma unroll
         for (int i = 0; i < MW; ++i) m.w[i] = (i == (d >> 5)) ? (1u << (d & 31)) : 0u;
-        store_slot<KW, MW>(states, WPD, d, all_rows, m);
+        fstore<KW, MW>(states, d, all_rows, m);
     }
     for (int j = threadIdx.x; j < 2 * n_share; j += 64) sums[j] = 0.0;
     if (threadIdx.x == 0) { FrontEntry e; e.query = query; e.len = 0; e.digits = 0ull; entries[0] = e; }
@@ -703,12 +970,16 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
         hipLaunchKernelGGL((k_front_init<KW, MW>), dim3(1), dim3(64), 0, stream, A.q, A.query, const_cast<FrontEntry*>(A.entries),
                            const_cast<uint32_t*>(A.states), A.sums, A.n_share);
     } else if (what == 1) {
-        const size_t lds = (size_t)A.np * A.R * (KW + MW) * 4;
-        hipError_t e = allow_lds_f(k_front_classify<KW, MW>, lds);
-        if (e != hipSuccess) return e;
+        const size_t lds = (size_t)A.np * A.R * FL<KW, MW>::WS * 4 + (((size_t)A.R + 15) & ~(size_t)15);
         const unsigned blocks = A.n < 65536u ? A.n : 65536u;
-        hipLaunchKernelGGL((k_front_classify<KW, MW>), dim3(blocks), dim3(kClassifyThreads), lds, stream, A.q, A.entries, A.states,
-                           A.n, A.np, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
+        hipError_t e = A.np == 2 ? allow_lds_f(k_front_classify<KW, MW, 2>, lds) : allow_lds_f(k_front_classify<KW, MW, 1>, lds);
+        if (e != hipSuccess) return e;
+        if (A.np == 2)
+            hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.entries, A.states,
+                               A.n, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
+        else
+            hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.entries, A.states,
+                               A.n, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
     } else {
         const unsigned blocks = A.level->n_surv < 65536u ? A.level->n_surv : 65536u;
         hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(64), 0, stream, A.queries, *A.level);
@@ -740,7 +1011,9 @@ hipError_t front_dispatch(int R, int k, int what, const FrontArgs& A, hipStream_
 
 }  // namespace
 
-size_t frontier_state_words(int R, int k) { return (size_t)R * (size_t)(round_words_f(k) + round_words_f(R)); }
+size_t frontier_state_words(int R, int k) {
+    return (size_t)R * 4 * (size_t)((round_words_f(k) + 3) / 4 + (round_words_f(R) + 3) / 4);      // FL<KW, MW>::WS per device
+}
 
 // Two planes must fit in LDS for the two-pair list to be used.
 int frontier_max_pairs(int R, int k) { return frontier_state_words(R, k) * 2 * 4 + 2048 <= kLdsBudget ? 2 : 1; }
