@@ -432,6 +432,11 @@ struct QAcc {
     uint4 o, a, t;
     __device__ inline void init() { o = q_zero(); a = q_ones(); t = q_zero(); }
     __device__ inline void add(uint4 v) { t = q_or(t, q_and(v, o)); o = q_or(o, v); a = q_and(a, v); }
+    // the same, or nothing at all (v must be zero where `on` is false)
+    __device__ inline void add_if(uint4 v, bool on) {
+        t = q_or(t, q_and(v, o)); o = q_or(o, v);
+        a = make_uint4(a.x & (on ? v.x : ~0u), a.y & (on ? v.y : ~0u), a.z & (on ? v.z : ~0u), a.w & (on ? v.w : ~0u));
+    }
     __device__ inline void merge_xor(int m) {
         const uint4 oo = q_shfl_xor(o, m), oa = q_shfl_xor(a, m), ot = q_shfl_xor(t, m);
         t = q_or(q_or(t, ot), q_and(o, oo)); o = q_or(o, oo); a = q_and(a, oa);
@@ -440,9 +445,25 @@ struct QAcc {
 };
 
 constexpr uint32_t kFlagEmpty = 1u, kFlagGoal = 2u, kFlagTwo = 4u;
+// what the groups of a pattern have shown so far (one word per pattern)
+constexpr uint32_t kPfBadRed = 1u, kPfBadB = 2u, kPfUnal = 4u, kPfBadRs = 8u, kPfBadAg = 16u, kPfChanged = 32u, kPfAgUneq = 64u,
+                   kPfBadBc1 = 128u, kPfBcFail = 256u, kPfAnyTwo = 512u, kPfNgAr = 1024u, kPfNgAg = 2048u, kPfNgBc = 4096u,
+                   kPfPatTwo = 8192u;
+constexpr int kClsChunks = 8;          // a pattern's groups go to the wavefronts in at most this many runs
+struct ClsItem { uint16_t pid, first_batch, n_batches; };
+
+// Sum over the 8 lanes of a slot, in every lane of the slot, with data-parallel-primitive moves (all lanes active):
+// swap neighbours, swap pairs, mirror the half row.
+__device__ inline int sum_slot(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);      // quad_perm [1, 0, 3, 2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);      // quad_perm [2, 3, 0, 1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);     // row_half_mirror
+    return v;
+}
 
 template <int KW, int MW, int NP>
-__global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* __restrict__ qp,
+// (second bound: wavefronts per SIMD, so that two blocks of one-plane states share a compute unit)
+__global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify(const DevQuery* __restrict__ qp,
                                                                 const FrontEntry* __restrict__ entries,
                                                                 const uint32_t* __restrict__ states, uint32_t n_entries,
                                                                 int max_pairs, int handover, FrontSurvivor* __restrict__ surv,
@@ -454,7 +475,10 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
     __shared__ uint8_t s_code[kClsBatch][kMaxPatterns * 5];
     __shared__ uint32_t s_entry[kClsBatch];
     __shared__ int s_unknown[kClsBatch];
-    __shared__ int s_goal, s_two;
+    __shared__ int s_goal, s_two, s_next, s_n_items;
+    __shared__ uint32_t s_pflags[kMaxPatterns];
+    __shared__ int s_pgoal[kMaxPatterns], s_ptwo[kMaxPatterns];
+    __shared__ ClsItem s_items[kMaxPatterns * kClsChunks];
     using L = FL<KW, MW>;
     const DevQuery& q = *qp;
     const int R = q.R, I = q.alphabet, n_ops = q.n_ops, n_pat = q.n_patterns;
@@ -470,6 +494,24 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
         spat[i] = p;
     }
     for (int i = tid; i < I; i += kClsThreads) sdig[i] = q.instr_of_digit[i];
+    if (tid == 0) {
+        // work items: a pattern's batches of groups in up to kClsChunks runs; the long items first
+        int n = 0;
+        for (int pass = 0; pass < 2; ++pass)
+            for (int i = 0; i < n_pat; ++i) {
+                const int ng = q.pat[i].n_groups;
+                int spg = 1;
+                while (spg * 2 * ng <= 8) spg *= 2;
+                const int batches = (ng + 8 / spg - 1) / (8 / spg);
+                const int per = batches >= 2 * kClsChunks ? (batches + kClsChunks - 1) / kClsChunks : batches >= 4 ? 2 : batches;
+                if ((pass == 0) != (per == batches)) continue;       // (whole patterns are the long items)
+                for (int b = 0; b < batches; b += per) {
+                    ClsItem w; w.pid = (uint16_t)i; w.first_batch = (uint16_t)b; w.n_batches = (uint16_t)min(per, batches - b);
+                    s_items[n++] = w;
+                }
+            }
+        s_n_items = n;
+    }
     const Words<KW> all_rows = full_mask<KW>(q.k);
     const Words<MW> all_cols = full_mask<MW>(R);
     // this lane's quad of a device at the goal: every row, every column of the reduction group
@@ -485,13 +527,24 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
         }
         goal_quad = make_uint4(w[0], w[1], w[2], w[3]);
     }
+    int ops_r[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) ops_r[i] = i < n_ops ? q.ops[i] : -1;
     unsigned long long judged = 0;                       // prefixes this block judged itself (thread 0 counts)
     int pending = 0;
     for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
         __syncthreads();
         const uint4* src = reinterpret_cast<const uint4*>(states) + (size_t)e * NP * plane_q;
-        for (int i = tid; i < NP * plane_q; i += kClsThreads) ldsq[i] = src[i];
-        if (tid == 0) { s_goal = 0; s_two = 0; s_entry[pending] = e; s_unknown[pending] = (NP == 2 && handover) ? 1 : 0; }
+        // (all of a thread's loads are issued before the first store: one trip to HBM, not one per quad)
+        for (int i0 = tid; i0 < NP * plane_q; i0 += 8 * kClsThreads) {
+            uint4 tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const int i = i0 + u * kClsThreads; tmp[u] = i < NP * plane_q ? src[i] : q_zero(); }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const int i = i0 + u * kClsThreads; if (i < NP * plane_q) ldsq[i] = tmp[u]; }
+        }
+        if (tid == 0) { s_goal = 0; s_two = 0; s_next = 0; s_entry[pending] = e; s_unknown[pending] = (NP == 2 && handover) ? 1 : 0; }
+        for (int i = tid; i < n_pat; i += kClsThreads) { s_pflags[i] = 0u; s_pgoal[i] = 0; s_ptwo[i] = 0; }
         __syncthreads();
         // ---- per device: is it empty, is it at the goal, does it hold two pairs
         {
@@ -517,9 +570,18 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
             if (lane == 0 && with_two) atomicAdd(&s_two, with_two);
         }
         __syncthreads();
-        const int n_goal = s_goal, n_two = s_two;
-        // ---- patterns
-        for (int pid = wave; pid < n_pat; pid += kClsWaves) {
+        const int n_goal = s_goal, n_two = s_two, n_items = s_n_items;
+        // ---- stage A: the patterns' groups, cut into work items that the wavefronts take as they come (patterns
+        //      differ widely in cost, and a pattern whose rules have all failed is dropped at once); what an item
+        //      finds goes into its pattern's flag word
+        for (;;) {
+            // (all 64 lanes add one, so the counter runs in steps of 64: a fetch under `if (lane == 0)` followed by
+            //  a cross-lane read is a lane-dependent branch inside the loop, and the compiler has been seen to split
+            //  the loop on it, so that the other lanes read lane 0 while it is away and get item 0 for ever)
+            const int item = __builtin_amdgcn_readfirstlane(atomicAdd(&s_next, 1)) >> 6;
+            if (item >= n_items) break;
+            const ClsItem W = s_items[item];
+            const int pid = W.pid;
             const PatLds P = spat[pid];
             const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
             int spg = 1;                                         // slots that share a group
@@ -527,12 +589,17 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
             const int gpb = 8 / spg;                             // groups side by side
             const int my_g = slot / spg, part = slot - my_g * spg;
             const int trips = (g + spg - 1) / spg;
+            {
+                const uint32_t pf = s_pflags[pid];
+                if ((pf & kPfBadRed) && (pf & kPfBadAg) && (pf & kPfBadBc1) && (NP == 1 || (pf & kPfBcFail))) continue;
+            }
             bool bad_red = false, bad_b = false, unal = false, bad_rs = false, bad_ag = false, changed = false, ag_uneq = false;
             bool bad_bc1 = false, bc_fail = false, any_two = false;
             bool ng_ar = false, ng_ag = false, ng_bc = false;    // some device is not at the goal afterwards
             uint32_t fl_pat = 0;
             int goal_part = 0, two_part = 0;
-            for (int G0 = 0; G0 < ng; G0 += gpb) {
+            const int G_end = min(ng, (W.first_batch + W.n_batches) * gpb);
+            for (int G0 = W.first_batch * gpb; G0 < G_end; G0 += gpb) {
                 const int G = G0 + my_g;
                 const bool act = G < ng && has_quad;
                 int base = 0;
@@ -544,32 +611,43 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
                 p.init(); sB.init(); al.init(); i0.init(); i1.init();
                 uint4 first0 = q_zero(), first1 = q_zero();
                 uint32_t fl_or = 0;
-                for (int it = 0; it < trips; ++it) {
-                    const int t = it * spg + part;
-                    if (act && t < g) {
+                for (int it0 = 0; it0 < trips; it0 += 4) {       // four members in flight
+                    uint4 a0[4], a1[4];
+                    uint32_t ff[4];
+                    bool on[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int t = (it0 + u) * spg + part;
+                        on[u] = act && t < g;
                         const int d = base + t * s;
-                        const uint4 v0 = ldsq[d * L::WQ + qd];
-                        const uint32_t f = flags[d];
+                        a0[u] = on[u] ? ldsq[d * L::WQ + qd] : q_zero();
+                        a1[u] = (NP == 2 && on[u]) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+                        ff[u] = on[u] ? (uint32_t)flags[d] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint4 v0 = a0[u];
+                        const uint32_t f = ff[u];
                         fl_or |= f;
                         goal_part += (qd == 0 && (f & kFlagGoal)) ? 1 : 0;
                         if constexpr (NP == 2) {
-                            const uint4 v1 = ldsq[plane_q + d * L::WQ + qd];
+                            const uint4 v1 = a1[u];
                             const bool two = (f & kFlagTwo) != 0u;
                             two_part += (qd == 0 && two) ? 1 : 0;
-                            i0.add(v0); i1.add(v1);
+                            i0.add_if(v0, on[u]); i1.add_if(v1, on[u]);
                             if (is_row) {
-                                p.add(q_or(v0, v1));
-                                if (two) al.add(v0);
+                                p.add_if(q_or(v0, v1), on[u]);
+                                al.add_if(two ? v0 : q_zero(), two);
                             } else {
-                                p.add(v0);
-                                sB.add(two ? v1 : v0);
-                                al.add(v0);
-                                if (two) al.add(v1);
+                                p.add_if(v0, on[u]);
+                                sB.add_if(two ? v1 : v0, on[u]);
+                                al.add_if(v0, on[u]);
+                                al.add_if(two ? v1 : q_zero(), two);
                             }
-                            if (t == 0) { first0 = v0; first1 = v1; }
+                            if (it0 + u == 0 && part == 0) { first0 = v0; first1 = v1; }
                         } else {
-                            p.add(v0);
-                            if (t == 0) first0 = v0;
+                            p.add_if(v0, on[u]);
+                            if (it0 + u == 0 && part == 0) first0 = v0;
                         }
                     }
                 }
@@ -583,8 +661,7 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
                     if constexpr (NP == 2) first1 = q_shfl(first1, (slot - part) * 8 + qd);
                 }
                 fl_pat |= act ? fl_or : 0u;
-                int rows = (act && is_row) ? q_popc(p.o) : 0;
-                rows += __shfl_xor(rows, 1, 64); rows += __shfl_xor(rows, 2, 64); rows += __shfl_xor(rows, 4, 64);
+                const int rows = sum_slot((act && is_row) ? q_popc(p.o) : 0);
                 const int sh = slot * 8;
                 if constexpr (NP == 1) {
                     const unsigned long long dif_slots = __ballot(act && p.differ());
@@ -624,18 +701,90 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
                         ng_bc |= q_any(q_xor(first0, goal_quad)) || q_any(first1);
                     }
                 }
+                // every rule of the pattern has failed already: the other groups cannot change that
+                if (__any(bad_red) && __any(bad_ag) && __any(bad_bc1 && (NP == 1 || bc_fail))) break;
             }
-            const bool BAD_RED = __any(bad_red), BAD_B = __any(bad_b), UNAL = __any(unal), BAD_RS = __any(bad_rs);
-            const bool BAD_AG = __any(bad_ag), CHANGED = __any(changed), AG_UNEQ = __any(ag_uneq);
-            const bool BAD_BC1 = __any(bad_bc1), BC_FAIL = __any(bc_fail), ANY_TWO = __any(any_two);
-            const bool NG_AR = __any(ng_ar), NG_AG = __any(ng_ag), NG_BC = __any(ng_bc);
-            const bool PAT_TWO = __any((fl_pat & kFlagTwo) != 0u);
+            uint32_t bits = 0;
+            bits |= __any(bad_red) ? kPfBadRed : 0u; bits |= __any(bad_b) ? kPfBadB : 0u; bits |= __any(unal) ? kPfUnal : 0u;
+            bits |= __any(bad_rs) ? kPfBadRs : 0u; bits |= __any(bad_ag) ? kPfBadAg : 0u; bits |= __any(changed) ? kPfChanged : 0u;
+            bits |= __any(ag_uneq) ? kPfAgUneq : 0u; bits |= __any(bad_bc1) ? kPfBadBc1 : 0u; bits |= __any(bc_fail) ? kPfBcFail : 0u;
+            bits |= __any(any_two) ? kPfAnyTwo : 0u; bits |= __any(ng_ar) ? kPfNgAr : 0u; bits |= __any(ng_ag) ? kPfNgAg : 0u;
+            bits |= __any(ng_bc) ? kPfNgBc : 0u; bits |= __any((fl_pat & kFlagTwo) != 0u) ? kPfPatTwo : 0u;
             for (int o = 32; o > 0; o >>= 1) { goal_part += __shfl_xor(goal_part, o, 64); two_part += __shfl_xor(two_part, o, 64); }
+            if (lane == 0) {
+                if (bits) atomicOr(&s_pflags[pid], bits);
+                if (goal_part) atomicAdd(&s_pgoal[pid], goal_part);
+                if (two_part) atomicAdd(&s_ptwo[pid], two_part);
+            }
+        }
+        __syncthreads();
+        // ---- stage B: a pattern's flag word gives the codes of its instructions
+        for (int pid = wave; pid < n_pat; pid += kClsWaves) {
+            const PatLds P = spat[pid];
+            const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+            int spg = 1;
+            while (spg * 2 * ng <= 8) spg *= 2;
+            const int gpb = 8 / spg;
+            const int my_g = slot / spg, part = slot - my_g * spg;
+            const int trips = (g + spg - 1) / spg;
+            const uint32_t pf = s_pflags[pid];
+            const bool BAD_RED = pf & kPfBadRed, BAD_B = pf & kPfBadB, UNAL = pf & kPfUnal, BAD_RS = pf & kPfBadRs;
+            const bool BAD_AG = pf & kPfBadAg, CHANGED = pf & kPfChanged, AG_UNEQ = pf & kPfAgUneq;
+            const bool BAD_BC1 = pf & kPfBadBc1, BC_FAIL = pf & kPfBcFail, ANY_TWO = pf & kPfAnyTwo;
+            const bool NG_AR = pf & kPfNgAr, NG_AG = pf & kPfNgAg, NG_BC = pf & kPfNgBc, PAT_TWO = pf & kPfPatTwo;
+            const int goal_part = s_pgoal[pid], two_part = s_ptwo[pid];
             const bool rest_done = (n_goal - goal_part) == (R - ng * g);        // the devices left untouched are at the goal
             const bool rest_two = n_two - two_part > 0;                         // ... or one of them holds two pairs
+            // A valid AllGather of members with different masks: how many masks does a device hold afterwards?
+            // Second walk, the wavefront together: per group the first pair's mask, the first mask that differs
+            // from it, and whether a third one shows up (the child then needs the literal state).
+            bool MANY_MASKS = false;
+            if (!BAD_AG && AG_UNEQ) {
+                bool many = false;
+                for (int G0 = 0; G0 < ng; G0 += gpb) {
+                    const int G = G0 + my_g;
+                    const bool act = G < ng && is_mask;
+                    int base = 0;
+                    if (P.master) base = G * gs;
+                    else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+                    const uint4 d0 = act ? ldsq[base * L::WQ + qd] : q_zero();
+                    uint4 d1 = q_zero();
+                    bool have1 = false;
+                    const int sh = slot * 8;
+                    for (int it = 0; it < trips; ++it) {
+                        const int t = it * spg + part;
+                        const bool on = act && t < g;
+                        const int d = base + t * s;
+#pragma unroll
+                        for (int pl = 0; pl < NP; ++pl) {
+                            const uint4 m = on ? ldsq[pl * plane_q + d * L::WQ + qd] : q_zero();
+                            // (an empty second pair has an empty mask; the first pair of a member is never empty here)
+                            const bool there = on && (pl == 0 || (flags[d] & kFlagTwo) != 0u);
+                            const unsigned long long ne0 = __ballot(there && q_any(q_xor(m, d0)));
+                            const unsigned long long ne1 = __ballot(there && q_any(q_xor(m, d1)));
+                            if (there && ((ne0 >> sh) & 0xffull) != 0ull) {
+                                if (!have1) { d1 = m; have1 = true; }
+                                else if (((ne1 >> sh) & 0xffull) != 0ull) many = true;
+                            }
+                        }
+                    }
+                    for (int m = 8; m < 8 * spg; m <<= 1) {      // the slots of one group compare what they found
+                        const uint4 o1 = q_shfl_xor(d1, m);
+                        const bool o_have = __shfl_xor((int)have1, m, 64) != 0;
+                        const unsigned long long ne = __ballot(act && have1 && o_have && q_any(q_xor(d1, o1)));
+                        if (act && o_have) {
+                            if (!have1) { d1 = o1; have1 = true; }
+                            else if (((ne >> sh) & 0xffull) != 0ull) many = true;
+                        }
+                    }
+                }
+                MANY_MASKS = __any(many);
+            }
             if (lane == 0) {
-                for (int oi = 0; oi < n_ops; ++oi) {
-                    const int op = q.ops[oi];
+#pragma unroll
+                for (int oi = 0; oi < 5; ++oi) {
+                    const int op = ops_r[oi];
+                    if (op < 0) continue;
                     int code;
                     if (op == OP_AR || op == OP_RS || op == OP_RD) {
                         if (BAD_RED || !CHANGED || (op == OP_RS && BAD_RS)) code = CODE_INVALID;
@@ -648,11 +797,8 @@ __global__ __launch_bounds__(kClsThreads) void k_front_classify(const DevQuery* 
                         else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
                     } else if (op == OP_AG) {
                         if (BAD_AG) code = CODE_INVALID;
-                        else if (AG_UNEQ) {
-                            // members with different masks: two pairs per device, or more (count them)
-                            code = NP == 2 ? classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two)
-                                           : classify_step<KW, MW>(lds_words, P, op, R, all_rows, all_cols, n_goal);
-                        } else if (rest_two) code = CODE_PREFIX2;
+                        else if (AG_UNEQ) code = MANY_MASKS ? CODE_PREFIX_LITERAL : CODE_PREFIX2;   // members with different masks
+                        else if (rest_two) code = CODE_PREFIX2;
                         else code = (!NG_AG && rest_done) ? CODE_GOAL : CODE_PREFIX;
                     } else {
                         if (!PAT_TWO) code = BAD_BC1 ? CODE_INVALID : rest_two ? CODE_PREFIX2 : (!NG_BC && rest_done) ? CODE_GOAL : CODE_PREFIX;
@@ -971,7 +1117,8 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
                            const_cast<uint32_t*>(A.states), A.sums, A.n_share);
     } else if (what == 1) {
         const size_t lds = (size_t)A.np * A.R * FL<KW, MW>::WS * 4 + (((size_t)A.R + 15) & ~(size_t)15);
-        const unsigned blocks = A.n < 65536u ? A.n : 65536u;
+        // (a block keeps going over prefixes: what it sets up at its start is paid once)
+        const unsigned blocks = A.n < 2048u ? A.n : 2048u;
         hipError_t e = A.np == 2 ? allow_lds_f(k_front_classify<KW, MW, 2>, lds) : allow_lds_f(k_front_classify<KW, MW, 1>, lds);
         if (e != hipSuccess) return e;
         if (A.np == 2)
