@@ -1,19 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark: one step = one pass of the whole hot path (plan, unrank, semantic evaluation,
-goal test, cost, compaction, ordering, top-k) over every query of the workload.
+goal test, cost, compaction, ordering, top-k) over every query of the workload: one
+p2_synthesize_batch call.
 
-Prints ONE JSON line.  `value` is candidate programs resolved per second (valid or not, cost and
-rank for the valid ones) by the library's default engine.  On this workload that is the
-shared-prefix engine: the instructions that the candidates of a wavefront have in common are
-applied once, so it carries out far fewer instruction applications than there are candidates.
-The `roofline` object therefore prices the lane-operations that kernel really carried out
-against the chip's 32-bit integer VALU rate (a small fraction: the kernel is bound by
-bookkeeping and dependent lane exchanges, not by arithmetic), and `per_candidate_engine` reports
-the engine that evaluates every candidate on its own, lane by lane, with its own roofline
-fraction.  `cpu_baseline` times the plain CPU oracle on a bounded sample of the same candidates.
-Queries of the batch whose reduction group, chunks, patterns, alphabet and size limit are equal are
-evaluated once by the library (their costs stay their own): `config.queries_evaluated` says how many
-were, and `every_query_evaluated` times the same batch with that switched off.
+Prints ONE JSON line.  The default workload is configuration 5, the largest (512 devices, 512
+queries, programs of up to six instructions): its candidate spaces (up to 2.65e11 programs per
+query) are resolved by enumeration by program size with pruning (Sec. 3.5), the frontier engine.
+`value` counts the candidate programs whose status (valid or not; cost and rank for the valid
+ones) one step settles, per second, and counts a query's candidate space only where the library
+evaluated that query itself: queries of the batch whose validity results are equal by construction
+(same reduction group, chunks, patterns, alphabet, size limit) are enumerated once and only costed
+on their own (`config.queries_evaluated` of `config.queries`; `value_all_queries` counts every query).
+
+`roofline` prices the dominant kernel family of the step.  For the frontier engine that is the
+classification of valid prefixes against every instruction of the alphabet (k_front_classify):
+its algorithmic work per judged prefix is 4 lane-operations (read, union, intersection /
+seen-twice, compare) per 32-bit word of the (chunk set, mask) pairs of every device that a pattern
+of the alphabet visits, set against the chip's 32-bit integer vector rate; the same words are read
+from LDS once per pattern (`roofline.lds`, against 128 bytes per clock and compute unit) and the
+prefix's state comes from device memory once (`roofline.hbm`).  `materialize` prices the kernel
+that writes the surviving children against HBM.  Times are HIP-event times around every launch
+of the family on the call's stream, taken inside the timed steps (p2_get_profile).
+For the flat engines (configurations 1-4 with the default engine) the roofline is the lane-operation
+rate of the evaluation kernel, as `other_configs` reports per configuration.
+`cpu_baseline` times the plain CPU oracle on a bounded sample of the same workload.
 """
 import argparse
 import hashlib
@@ -29,6 +39,14 @@ sys.path.insert(0, ROOT)
 # the published 157.3 TFLOP/s of fp32 vector arithmetic (one fused multiply-add = 2 flops per lane and clock).
 # A stream of independent v_xor_b32 reaches about 0.8 of it (roofline.peak_measured, p2_measure_alu_peak).
 ALU_PEAK_LANE_OPS = 256 * 128 * 2.4e9
+# local data share: 128 bytes per clock and compute unit
+LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+HBM_PEAK_BYTES = 8.0e12
+
+ENGINE_NAMES = {0: "auto", 1: "literal", 2: "compact", 3: "frontier", 4: "small-group", 5: "shared-prefix"}
+KERNEL = {1: "k_eval_literal", 2: "k_eval_compact", 4: "k_eval_regs", 5: "k_eval_shared", 3: "k_front_classify"}
+KERNEL_SOURCE = {"k_eval_shared": "p2_shared.hip", "k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip",
+                 "k_front_classify": "p2_frontier.hip", "k_front_materialize": "p2_frontier.hip"}
 
 
 def algorithmic_lane_ops(stats, n_chunks, key="member_visits"):
@@ -41,12 +59,11 @@ def algorithmic_lane_ops(stats, n_chunks, key="member_visits"):
     return 4.0 * words * stats[key]
 
 
-def measured_traffic(kernel):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or
-    None when there is none or the kernel source has changed since the counters were taken."""
-    path = os.path.join(ROOT, "profiles", "%s_cfg2_traffic.json" % kernel)
-    src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc",
-                       {"k_eval_shared": "p2_shared.hip", "k_eval_regs": "p2_regs.hip", "k_eval_compact": "p2_compact.hip"}.get(kernel, "p2_literal.hip"))
+def measured_traffic(kernel, cfg_index):
+    """HBM bytes per launch of a kernel family from the committed rocprofv3 counter summary, or None when
+    there is none or the kernel source has changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "%s_cfg%d_traffic.json" % (kernel, cfg_index))
+    src = os.path.join(ROOT, "paper_2110_10548_amd", "csrc", KERNEL_SOURCE.get(kernel, "p2_literal.hip"))
     try:
         rec = json.load(open(path))
         if rec["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
@@ -56,55 +73,85 @@ def measured_traffic(kernel):
         return None
 
 
-def cpu_baseline(queries, budget_s=15.0):
-    """The oracle as it stands: flat, unpruned evaluation of a bounded sample of each query's
-    candidate indices (the first S and S seeded-random ones; all of them where the space is smaller),
-    OpenMP over all host cores this process may use."""
+def oracle_build_flags():
+    """The gcc command line the oracle library is built with (read from its build script)."""
+    try:
+        import re
+        text = open(os.path.join(ROOT, "oracle", "build.py")).read()
+        m = re.search(r'cmd = \[(.*?)\]', text, re.S)
+        return " ".join(t for t in re.findall(r'"([^"]+)"', m.group(1)) if t != "-o") if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(queries, budget_s=12.0):
+    """The oracle as it stands, on a bounded sample of the workload, OpenMP over the host cores this
+    process may use: flat, unpruned evaluation of seeded-random candidate indices of queries spread
+    over the batch, sized from a short probe so that it takes about budget_s; and, single-threaded,
+    the oracle's own enumeration by size with pruning (Sec. 3.5) of whole queries, smallest spaces
+    first, while the budget lasts."""
     import numpy as np
     from oracle import p2_oracle
     from paper_2110_10548_amd.workloads import SplitMix64
     cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "1024")))
-    S = 1_000_000
-    total, t_all, t_one, n_one = 0, 0.0, 0.0, 0
-    t_begin = time.time()
-    for qi, q in enumerate(queries):
-        oq = p2_oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
-                             n_chunks=q.get("n_chunks", 0))
-        N = oq.num_candidates(q["max_len"])
-        if N <= 2 * S:
-            idx = np.arange(N, dtype=np.uint64)
-        else:
-            rng = SplitMix64(1000 + qi)
-            idx = np.concatenate([np.arange(S, dtype=np.uint64),
-                                  np.array([rng.below(N) for _ in range(S)], dtype=np.uint64)])
+
+    def oracle_query(q):
+        return p2_oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
+                               n_chunks=q.get("n_chunks", 0))
+
+    picks = list(range(0, len(queries), max(len(queries) // 8, 1)))[:8]
+    oqs = [(qi, oracle_query(queries[qi])) for qi in picks]
+
+    def sample(qi, oq, n):
+        N = oq.num_candidates(queries[qi]["max_len"])
+        if N <= n:
+            return np.arange(N, dtype=np.uint64)
+        rng = SplitMix64(1000 + qi)
+        return np.array([rng.below(N) for _ in range(n)], dtype=np.uint64)
+
+    # probe: a few candidates per picked query
+    t0 = time.time()
+    probe = 0
+    for qi, oq in oqs:
+        idx = sample(qi, oq, 4 * cores)
+        oq.eval_indices(queries[qi]["max_len"], indices=idx, n_threads=cores)
+        probe += len(idx)
+    t_probe = max(time.time() - t0, 1e-6)
+    per_query = int(min(max(budget_s / t_probe * 4 * cores, 4 * cores), 1_000_000))
+    total, t_all = 0, 0.0
+    for qi, oq in oqs:
+        idx = sample(qi, oq, per_query)
         t0 = time.time()
-        oq.eval_indices(q["max_len"], indices=idx, n_threads=cores)
+        oq.eval_indices(queries[qi]["max_len"], indices=idx, n_threads=cores)
         t_all += time.time() - t0
         total += len(idx)
-        sub = idx[::16]
-        t0 = time.time()
-        oq.eval_indices(q["max_len"], indices=sub, n_threads=1)
-        t_one += time.time() - t0
-        n_one += len(sub)
-        if time.time() - t_begin > 2 * budget_s:
+        if t_all > 2 * budget_s:
             break
-    # the oracle's enumeration by size with pruning (Sec. 3.5), single-threaded, over whole queries: the
-    # CPU counterpart of an engine that settles candidates under an invalid prefix in bulk
-    t_pruned, covered = 0.0, 0
-    for q in queries:
-        if time.time() - t_begin > 3 * budget_s:
+    # pruned enumeration of whole queries, one core, smallest candidate spaces first
+    order = sorted(range(len(queries)), key=lambda i: (oracle_query(queries[i]).num_candidates(queries[i]["max_len"]), i))
+    t_pruned, covered, n_pruned, seen = 0.0, 0, 0, set()
+    for i in order:
+        q = queries[i]
+        key = (tuple(map(tuple, q["placement"])), tuple(q["reduce_axes"]), q.get("n_chunks", 0))
+        if key in seen:
+            continue
+        seen.add(key)
+        if t_pruned > budget_s:
             break
-        oq = p2_oracle.Query(q["card"], q["axes"], q["placement"], q["reduce_axes"], bw=q["bw"], alpha=q["alpha"],
-                             n_chunks=q.get("n_chunks", 0))
+        oq = oracle_query(q)
         t0 = time.time()
         oq.synthesize(q["max_len"], q.get("msg_bytes", ()))
         t_pruned += time.time() - t0
         covered += oq.num_candidates(q["max_len"])
+        n_pruned += 1
+        if oq.num_candidates(q["max_len"]) > 1_000_000:      # (one large space is enough: the next ones take minutes)
+            break
     return {"value": total / t_all, "unit": "candidates/s", "cores": cores, "kind": "oracle",
-            "value_1core": n_one / t_one,
+            "nproc": os.cpu_count(), "build": oracle_build_flags(),
             "pruned_enumeration_candidates_covered_per_s_1core": covered / t_pruned if t_pruned > 0 else None,
-            "sample": "per query the first %d and %d SplitMix64-random candidate indices (the whole space where "
-                      "smaller), flat unpruned evaluation from the init state; %d candidates in %.1f s" % (S, S, total, t_all)}
+            "sample": "flat unpruned evaluation from the init state of %d SplitMix64-random candidate indices of each of the "
+                      "queries %s (%d candidates in %.1f s, %d threads); pruned enumeration of the %d distinct queries with the "
+                      "smallest candidate spaces, 1 thread, %.1f s" % (per_query, picks, total, t_all, cores, n_pruned, t_pruned)}
 
 
 def main():
@@ -112,11 +159,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (2 is the benchmark)")
+    ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (5, the largest, is the benchmark)")
     ap.add_argument("--engine", type=int, default=0,
                     help="0 auto, 1 literal, 2 compact (state in LDS), 3 frontier, 4 small-group, 5 shared-prefix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--no-compare", action="store_true", help="skip the leg that evaluates every query on its own (profiling runs)")
+    ap.add_argument("--no-compare", action="store_true", help="skip the legs that run other engines or other configurations (profiling runs)")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -130,9 +177,6 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible: the evaluator has no CPU fallback", file=sys.stderr)
         sys.exit(3)
-    cfg = workloads.config(args.config)
-    queries = workloads.expand(cfg, B.p2_enumerate_placements(cfg["card"], cfg["axes"]))
-    msg = cfg["msg_bytes"]
     B.p2_set_profiling(True)
 
     if args.copy_mib > 0:
@@ -141,116 +185,175 @@ def main():
         dst.copy_(src)                            # reads and writes copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    def timed(engine, steps, warmup, flags=0):
+
+    PROFILE_SUMS = ("eval_ms", "post_ms", "eval_launches", "front_ms", "front_classify_ms", "front_literal_ms",
+                    "front_materialize_ms", "front_classify_launches", "front_literal_launches", "front_materialize_launches",
+                    "front_prefixes", "front_classify_state_bytes", "front_classify_lane_ops", "front_survivors",
+                    "front_materialize_bytes")
+
+    def load(cfg_index):
+        cfg = workloads.config(cfg_index)
+        return cfg, workloads.expand(cfg, B.p2_enumerate_placements(cfg["card"], cfg["axes"]))
+
+    def timed(queries, msg, engine, steps, warmup, flags=0):
         """K timed steps of the whole path with one engine: wall time, device times, results."""
         qs = [dict(q, engine=engine, flags=flags) for q in queries]
         batch = B.Batch(qs, msg)                  # argument marshalling only; every step replans on the host
         for _ in range(max(warmup, 1)):
             batch.run_raw()
         torch.cuda.synchronize()
-        eval_ms, post_ms, launches = 0.0, 0.0, 0
+        acc = {k: 0.0 for k in PROFILE_SUMS}
         t0 = time.perf_counter()
         for _ in range(steps):
             batch.run_raw()                       # one p2_synthesize_batch call; returns after its stream sync
             prof = B.p2_get_profile()
-            eval_ms += prof["eval_ms"]
-            post_ms += prof["post_ms"]
-            launches += prof["eval_launches"]
+            for k in PROFILE_SUMS:
+                acc[k] += prof[k]
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        return {"dt": dt, "eval_ms": eval_ms, "post_ms": post_ms, "launches": launches, "results": batch.results(), "steps": steps}
+        return dict(acc, dt=dt, results=batch.results(), steps=steps, queries=queries)
 
-    def summarise(run, key):
-        """Throughput and the evaluation kernel's lane-operation rate; key selects which applications count."""
-        results = run["results"]
-        candidates = sum(r["stats"]["candidates"] for r in results)
+    def flat_summary(run, key):
+        """Lane-operation rate of the flat engines' evaluation kernel; key selects which applications count."""
+        results, queries = run["results"], run["queries"]
         ops = sum(algorithmic_lane_ops(r["stats"], q["n_chunks"] or int(torch.tensor(q["card"]).prod()), key)
                   for q, r in zip(queries, results))
-        launch_ms = run["eval_ms"] / max(run["launches"], 1)
-        ops_per_launch = ops / (run["launches"] / run["steps"])
-        return candidates, ops_per_launch, launch_ms, ops_per_launch / (launch_ms * 1e-3)
+        launches = max(run["eval_launches"], 1)
+        launch_ms = run["eval_ms"] / launches
+        ops_per_launch = ops / (launches / run["steps"])
+        return ops_per_launch, launch_ms, ops_per_launch / (launch_ms * 1e-3)
 
+    def report(run, cfg_index, engine_asked):
+        """The figures of one timed run: throughput, device times, roofline of its dominant kernel family."""
+        results, steps = run["results"], run["steps"]
+        step_s = run["dt"] / steps
+        own = [r for r in results if r["stats"]["evaluated_with"] < 0]
+        candidates_all = sum(r["stats"]["candidates"] for r in results)
+        candidates = sum(r["stats"]["candidates"] for r in own)
+        engines = sorted({r["stats"]["engine"] for r in results})
+        main_engine = max(engines, key=lambda e: sum(r["stats"]["candidates"] for r in own if r["stats"]["engine"] == e))
+        out = {"value": candidates / step_s, "unit": "candidates/s", "value_all_queries": candidates_all / step_s,
+               "ms_per_step": step_s * 1e3, "steps": steps,
+               "queries": len(results), "queries_evaluated": len(own),
+               "candidates_per_step": candidates, "candidates_per_step_all_queries": candidates_all,
+               "valid_per_step": sum(r["stats"]["valid"] for r in results),
+               "engine": ENGINE_NAMES[engine_asked], "engines_used": engines,
+               "device_ms_per_step": {"evaluate": run["eval_ms"] / steps, "frontier": run["front_ms"] / steps,
+                                      "order_cost_topk": run["post_ms"] / steps}}
+        if main_engine == 3:
+            cls_s = run["front_classify_ms"] * 1e-3
+            n_launch = max(run["front_classify_launches"], 1)
+            rate = run["front_classify_lane_ops"] / cls_s
+            lds_rate = run["front_classify_lane_ops"] / cls_s           # 4 lane-operations per 4-byte word read from LDS
+            hbm_rate = run["front_classify_state_bytes"] / cls_s
+            mat_s = max(run["front_materialize_ms"] * 1e-3, 1e-12)
+            out["prefixes_judged_per_step"] = run["front_prefixes"] / steps
+            out["prefixes_judged_per_s"] = run["front_prefixes"] / cls_s
+            out["device_ms_per_step"].update({"front_classify": run["front_classify_ms"] / steps,
+                                              "front_literal": run["front_literal_ms"] / steps,
+                                              "front_materialize": run["front_materialize_ms"] / steps})
+            out["roofline"] = {
+                "bound": "alu", "kernel": "k_front_classify", "achieved": rate / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
+                "unit": "Tlane-op/s", "frac": rate / ALU_PEAK_LANE_OPS,
+                "traffic": measured_traffic("k_front_classify", cfg_index),
+                "launch_ms": run["front_classify_ms"] / n_launch, "launches_per_step": n_launch / steps,
+                "algorithmic_lane_ops_per_launch": run["front_classify_lane_ops"] / n_launch,
+                "algorithmic_hbm_bytes_per_launch": run["front_classify_state_bytes"] / n_launch,
+                "lds": {"achieved": lds_rate / 1e9, "peak": LDS_PEAK_BYTES / 1e9, "unit": "GB/s", "frac": lds_rate / LDS_PEAK_BYTES},
+                "hbm": {"achieved": hbm_rate / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s", "frac": hbm_rate / HBM_PEAK_BYTES},
+                "share_of_device_time": run["front_classify_ms"] / max(run["front_ms"] + run["post_ms"] + run["eval_ms"], 1e-9)}
+            n_mat = max(run["front_materialize_launches"], 1)
+            out["materialize"] = {
+                "bound": "hbm", "kernel": "k_front_materialize", "achieved": run["front_materialize_bytes"] / mat_s / 1e9,
+                "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s", "frac": run["front_materialize_bytes"] / mat_s / HBM_PEAK_BYTES,
+                "traffic": measured_traffic("k_front_materialize", cfg_index),
+                "launch_ms": run["front_materialize_ms"] / n_mat, "launches_per_step": n_mat / steps,
+                "algorithmic_hbm_bytes_per_launch": run["front_materialize_bytes"] / n_mat,
+                "survivors_per_step": run["front_survivors"] / steps}
+        else:
+            kernel = KERNEL[main_engine]
+            ops_launch, launch_ms, achieved = flat_summary(run, "members_evaluated")
+            flat_ops_launch, _, flat_rate = flat_summary(run, "member_visits")
+            out["steps_executed_per_step"] = sum(r["stats"]["steps_executed"] for r in own)
+            out["steps_evaluated_per_step"] = sum(r["stats"]["steps_evaluated"] for r in own)
+            # lane-operations of the instruction applications the kernel carried out (shared ones once)
+            out["roofline"] = {"bound": "alu", "kernel": kernel, "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
+                               "unit": "Tlane-op/s", "frac": achieved / ALU_PEAK_LANE_OPS,
+                               "traffic": measured_traffic(kernel, cfg_index),
+                               "launch_ms": launch_ms, "algorithmic_lane_ops_per_launch": ops_launch,
+                               # the same launch priced with every candidate's applications counted on their own
+                               "per_candidate_lane_ops_per_launch": flat_ops_launch,
+                               "per_candidate_equivalent_frac": flat_rate / ALU_PEAK_LANE_OPS}
+        return out
+
+    cfg, queries = load(args.config)
+    msg = cfg["msg_bytes"]
     peak_measured = B.p2_measure_alu_peak(5)        # independent v_xor_b32 stream, lane-operations per second
-    KERNEL = {1: "k_eval_literal", 2: "k_eval_compact", 4: "k_eval_regs", 5: "k_eval_shared", 3: "k_front_classify"}
-    run = timed(args.engine, args.steps, args.warmup)
-    results = run["results"]
-    dt = run["dt"]
-    engines = sorted({r["stats"]["engine"] for r in results})
-    kernel = KERNEL[max(engines, key=lambda e: sum(r["stats"]["candidates"] for r in results if r["stats"]["engine"] == e))]
-    steps_exec = sum(r["stats"]["steps_executed"] for r in results)
-    steps_eval = sum(r["stats"]["steps_evaluated"] for r in results)
-    valid = sum(r["stats"]["valid"] for r in results)
-    reruns = sum(r["stats"]["literal_reruns"] for r in results)
-    candidates, ops_launch, launch_ms, achieved = summarise(run, "members_evaluated")
-    _, flat_ops_launch, _, flat_rate = summarise(run, "member_visits")
-    ms_per_step = dt / args.steps * 1e3
-    eval_ms, post_ms = run["eval_ms"], run["post_ms"]
-
+    lds_measured = B.p2_measure_lds_peak(5)         # 128-bit LDS reads, bytes per second
+    run = timed(queries, msg, args.engine, args.steps, args.warmup)
+    head = report(run, args.config, args.engine)
+    placements = len({q["placement_index"] for q in queries})
+    if cfg["placements"] == "all":
+        what = "all %d placements x reduce sets %s x chunk counts %s" % (placements, cfg["reduce_sets"], cfg["n_chunks"])
+    else:
+        what = ("%d (placement, reduce-axis subset) draws with replacement, seed %d: %d of the %d placements, %d distinct queries"
+                % (len(queries), cfg["seed"], placements, len(B.p2_enumerate_placements(cfg["card"], cfg["axes"])),
+                   len({(q["placement_index"], tuple(q["reduce_axes"])) for q in queries})))
     out = {
         "metric": "candidate programs evaluated/sec (validity+cost)",
-        "value": candidates / (dt / args.steps),
-        "unit": "candidates/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "value": head["value"], "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "%s: hierarchy %s, axes %s, all %d placements x reduce sets %s, max_len %d, %d message sizes"
-                               % (cfg["name"], cfg["card"], cfg["axes"], len(queries) // max(len(cfg["reduce_sets"]) * len(cfg["n_chunks"]), 1),
-                                  cfg["reduce_sets"], cfg["max_len"], len(msg)),
-                   "queries": len(queries), "candidates_per_step": candidates, "valid_per_step": valid,
-                   "steps_executed_per_step": steps_exec, "steps_evaluated_per_step": steps_eval,
-                   "literal_reruns_per_step": reruns,
-                   "engine": {0: "auto", 1: "literal", 2: "compact", 3: "frontier", 4: "small-group", 5: "shared-prefix"}[args.engine],
-                   "engines_used": engines},
-        "device_ms_per_step": {"evaluate": eval_ms / args.steps, "order_cost_topk": post_ms / args.steps},
-        "evaluate_only_candidates_per_s": candidates / (eval_ms / args.steps * 1e-3),
-        "steps_executed_per_s": steps_exec / (eval_ms / args.steps * 1e-3),
-        "steps_evaluated_per_s": steps_eval / (eval_ms / args.steps * 1e-3),
-        # lane-operations of the instruction applications the kernel carried out (shared ones once)
-        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-                     "frac": achieved / ALU_PEAK_LANE_OPS, "peak_measured": peak_measured / 1e12,
-                     "traffic": measured_traffic(kernel) if args.config == 2 else None,
-                     "kernel": kernel,
-                     "launch_ms": launch_ms, "algorithmic_lane_ops_per_launch": ops_launch,
-                     # the same launch priced with every candidate's applications counted on their own
-                     "per_candidate_lane_ops_per_launch": flat_ops_launch,
-                     "per_candidate_equivalent_frac": flat_rate / ALU_PEAK_LANE_OPS},
+        "config": {"workload": "%s: hierarchy %s, axes %s, %s, max_len %d, top-%d, %d message size(s)"
+                               % (cfg["name"], cfg["card"], cfg["axes"], what, cfg["max_len"], cfg["topk"], len(msg)),
+                   "queries": head["queries"], "queries_evaluated": head["queries_evaluated"],
+                   "candidates_per_step": head["candidates_per_step"],
+                   "candidates_per_step_all_queries": head["candidates_per_step_all_queries"],
+                   "valid_per_step": head["valid_per_step"], "engine": head["engine"], "engines_used": head["engines_used"]},
+        "value_all_queries": head["value_all_queries"],
+        "device_ms_per_step": head["device_ms_per_step"],
+        "roofline": dict(head["roofline"], peak_measured=peak_measured / 1e12),
     }
-    # Queries of the batch with the same reduction group, chunks, patterns, alphabet and size limit are evaluated
-    # once (validity does not depend on the links or on where the placement puts the group); every query is still
-    # costed on its own.  The same batch with that switched off, for comparison:
-    out["config"]["queries_evaluated"] = sum(1 for r in results if r["stats"]["steps_evaluated"] > 0) if engines == [5] else None
-    if args.engine == 0 and 3 not in engines and not args.no_compare:
-        every = timed(args.engine, max(args.steps // 2, 2), 2, B.FLAG_EVALUATE_EVERY_QUERY)
-        out["every_query_evaluated"] = {"value": candidates / (every["dt"] / every["steps"]), "unit": "candidates/s",
-                                        "ms_per_step": every["dt"] / every["steps"] * 1e3, "steps": every["steps"],
-                                        "device_ms_per_step": {"evaluate": every["eval_ms"] / every["steps"],
-                                                               "order_cost_topk": every["post_ms"] / every["steps"]}}
-    if 3 in engines:
-        # the frontier engine's time is spread over many launches per query outside the evaluation events, and
-        # its work is pruned enumeration, not candidates visited: no lane-operation rate is quoted for it
-        for key in ("achieved", "frac", "launch_ms", "per_candidate_equivalent_frac"):
-            out["roofline"][key] = None
-    if 5 in engines and args.engine == 0 and candidates <= 1 << 30:
-        # the engine that evaluates every candidate on its own, timed the same way (fewer steps)
-        every_q = B.FLAG_EVALUATE_EVERY_QUERY           # (this leg is about the kernel: every candidate is visited)
-        try:
-            own, own_engine = timed(4, max(args.steps // 2, 2), 2, every_q), 4
-        except B.P2Error:                          # more than 32 devices or chunks: the LDS-resident compact engine
-            try:
-                own, own_engine = timed(2, max(args.steps // 10, 1), 1, every_q), 2
-            except B.P2Error:                      # too many candidates to visit one by one (config 5)
-                own = None
-    else:
-        own = None
-    if own is not None:
-        c2, ops2, ms2, rate2 = summarise(own, "member_visits")
-        out["per_candidate_engine"] = {
-            "engine": {4: "small-group", 2: "compact"}[own_engine], "kernel": KERNEL[own_engine],
-            "value": c2 / (own["dt"] / own["steps"]), "unit": "candidates/s",
-            "ms_per_step": own["dt"] / own["steps"] * 1e3, "steps": own["steps"],
-            "roofline": {"bound": "alu", "achieved": rate2 / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-                         "frac": rate2 / ALU_PEAK_LANE_OPS, "launch_ms": ms2, "algorithmic_lane_ops_per_launch": ops2,
-                         "traffic": measured_traffic(KERNEL[own_engine]) if args.config == 2 else None}}
+    if "lds" in out["roofline"]:
+        out["roofline"]["lds"]["peak_measured"] = lds_measured / 1e9
+    for key in ("materialize", "prefixes_judged_per_step", "prefixes_judged_per_s", "steps_executed_per_step", "steps_evaluated_per_step"):
+        if key in head:
+            out[key] = head[key]
+
+    if not args.no_compare:
+        # the other configurations, a few steps each with the default engine, and where that is the shared-prefix
+        # engine also the engine that evaluates every candidate on its own, lane by lane
+        others = {}
+        for ci in (1, 2, 3, 4, 5):
+            if ci == args.config:
+                continue
+            c2, q2 = load(ci)
+            steps2 = 3 if ci == 5 else 10
+            r2 = report(timed(q2, c2["msg_bytes"], 0, steps2, 2), ci, 0)
+            entry = {k: r2[k] for k in ("value", "unit", "value_all_queries", "ms_per_step", "steps", "queries", "queries_evaluated",
+                                        "candidates_per_step", "valid_per_step", "engines_used", "device_ms_per_step", "roofline")}
+            if r2["engines_used"] == [5] and r2["candidates_per_step"] <= 1 << 30:
+                every_q = B.FLAG_EVALUATE_EVERY_QUERY           # (this leg is about the kernel: every candidate is visited)
+                own, own_engine = None, None
+                for eng, st in ((4, 5), (2, 2)):                # small-group engine; else the LDS-resident compact engine
+                    try:
+                        own, own_engine = timed(q2, c2["msg_bytes"], eng, st, 1, every_q), eng
+                        break
+                    except B.P2Error:
+                        continue
+                if own is not None:
+                    ops2, ms2, rate2 = flat_summary(own, "member_visits")
+                    c_all = sum(r["stats"]["candidates"] for r in own["results"])
+                    entry["per_candidate_engine"] = {
+                        "engine": ENGINE_NAMES[own_engine], "kernel": KERNEL[own_engine],
+                        "value": c_all / (own["dt"] / own["steps"]), "unit": "candidates/s",
+                        "ms_per_step": own["dt"] / own["steps"] * 1e3, "steps": own["steps"],
+                        "roofline": {"bound": "alu", "achieved": rate2 / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+                                     "frac": rate2 / ALU_PEAK_LANE_OPS, "launch_ms": ms2, "algorithmic_lane_ops_per_launch": ops2,
+                                     "traffic": measured_traffic(KERNEL[own_engine], ci)}}
+            others[c2["name"]] = entry
+        out["other_configs"] = others
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(queries)
     print(json.dumps(out))

@@ -183,6 +183,11 @@ typedef struct {
                                   candidates handed to the literal engine not included), so it is
                                   at most steps_executed                                          */
     uint64_t members_evaluated;/* devices taking part in those applications, summed               */
+    int32_t evaluated_with;    /* p2_synthesize_batch: index of the earlier query of the batch whose
+                                  evaluation this one shares (its validity results are that
+                                  query's, its costs its own; steps_* and members_* repeat that
+                                  query's figures), or -1: evaluated for itself                   */
+    int32_t reserved0;
 } p2_stats;
 
 /* Sec. 3.5 on one placement: evaluate every program of length <= max_len.  A program is valid
@@ -305,6 +310,26 @@ typedef struct {
     float host_plan_ms;        /* host: planning of all queries before the first launch (patterns,
                                   alphabet; the cost model's tables are built while the GPU runs)  */
     float host_total_ms;       /* host: whole call, wall clock                                     */
+    /* Enumeration by program size (Sec. 3.5; the frontier engine): device time of the whole
+     * enumeration (not part of eval_ms / post_ms) and, from an event pair around every launch,
+     * of its three kernel families, with what those launches worked on.                            */
+    float front_ms;
+    float front_classify_ms;          /* prefixes held as (chunk set, mask) pairs judged against the
+                                         alphabet (Sec. 3.2's rules on every instruction)          */
+    float front_literal_ms;           /* prefixes held literally, judged from their instructions    */
+    float front_materialize_ms;       /* surviving children: state and running cost sums written    */
+    int32_t front_classify_launches, front_literal_launches, front_materialize_launches;
+    int32_t reserved0;
+    double front_prefixes;            /* prefixes the pair classification judged                    */
+    double front_classify_state_bytes;/* bytes of their states, R * (ceil(k/32) + ceil(R/32)) words
+                                         per pair plane: what the classification must read from
+                                         device memory                                              */
+    double front_classify_lane_ops;   /* 4 lane-operations (read, union, intersection / seen-twice,
+                                         compare) per state word of every device that a pattern of
+                                         the alphabet visits, per judged prefix and plane           */
+    double front_survivors;           /* valid children handed to the materialisation               */
+    double front_materialize_bytes;   /* bytes it must move: a parent plane read per survivor, the
+                                         planes of every kept child written, the cost sums of both  */
 } p2_profile;
 int32_t p2_set_profiling(int32_t on);
 int32_t p2_get_profile(p2_profile* out);
@@ -315,6 +340,15 @@ int32_t p2_get_profile(p2_profile* out);
  * against the ceiling derived from the unit counts and the clock, and this shows how close the
  * device comes to it.  hip_stream: hipStream_t or NULL.  P2_EINVAL on bad arguments. */
 int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_stream);
+
+/* Measurement aid: the best rate, in bytes per second, that `reps` (1..100) timed runs of a stream of
+ * 128-bit reads from the local data share reach on the current device (every lane 16 bytes per
+ * instruction, all banks, many reads in flight): the frontier engine's classification (Sec. 3.5: every
+ * valid prefix is judged against every instruction of the alphabet) reads the prefix's state from LDS
+ * once per pattern, and its LDS byte rate is set against 256 compute units x 128 bytes per clock x
+ * 2.4 GHz; this shows how close the device comes to that.  hip_stream: hipStream_t or NULL.
+ * P2_EINVAL on bad arguments. */
+int32_t p2_measure_lds_peak(int32_t reps, double* out_bytes_per_s, void* hip_stream);
 
 /* Gives back what the calling host thread's calls have cached: device buffers, pinned host buffers,
  * the upload stream and the profiling events (profiling is switched off).  The next call of the thread

@@ -42,12 +42,19 @@ class p2_program(C.Structure):
 class p2_stats(C.Structure):
     _fields_ = [("candidates", C.c_uint64), ("steps_executed", C.c_uint64), ("literal_reruns", C.c_uint64),
                 ("member_visits", C.c_uint64), ("valid", C.c_int64), ("group_size", C.c_int32), ("n_patterns", C.c_int32), ("alphabet", C.c_int32),
-                ("engine", C.c_int32), ("steps_evaluated", C.c_uint64), ("members_evaluated", C.c_uint64)]
+                ("engine", C.c_int32), ("steps_evaluated", C.c_uint64), ("members_evaluated", C.c_uint64),
+                ("evaluated_with", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class p2_profile(C.Structure):
     _fields_ = [("eval_ms", C.c_float), ("post_ms", C.c_float), ("eval_launches", C.c_int32), ("post_launches", C.c_int32),
-                ("host_plan_ms", C.c_float), ("host_total_ms", C.c_float)]
+                ("host_plan_ms", C.c_float), ("host_total_ms", C.c_float),
+                ("front_ms", C.c_float), ("front_classify_ms", C.c_float), ("front_literal_ms", C.c_float),
+                ("front_materialize_ms", C.c_float), ("front_classify_launches", C.c_int32),
+                ("front_literal_launches", C.c_int32), ("front_materialize_launches", C.c_int32), ("reserved0", C.c_int32),
+                ("front_prefixes", C.c_double), ("front_classify_state_bytes", C.c_double),
+                ("front_classify_lane_ops", C.c_double), ("front_survivors", C.c_double),
+                ("front_materialize_bytes", C.c_double)]
 
 
 class p2_search_row(C.Structure):
@@ -65,7 +72,7 @@ PROGRAM_DTYPE = np.dtype([("index", np.uint64), ("len", np.uint8), ("instr", np.
 assert PROGRAM_DTYPE.itemsize == C.sizeof(p2_program) == 16
 
 EXPORTS = ("p2_enumerate_placements", "p2_synthesize", "p2_synthesize_batch", "p2_describe_pattern", "p2_topk",
-           "p2_topk_device", "p2_topk_device_noalloc", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak", "p2_release_thread")
+           "p2_topk_device", "p2_topk_device_noalloc", "p2_last_error", "p2_set_profiling", "p2_get_profile", "p2_search_placements", "p2_measure_alu_peak", "p2_measure_lds_peak", "p2_release_thread")
 
 _lib = None
 
@@ -101,6 +108,8 @@ def lib():
                                            C.c_int64, i64p]
         L.p2_measure_alu_peak.restype = C.c_int32
         L.p2_measure_alu_peak.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+        L.p2_measure_lds_peak.restype = C.c_int32
+        L.p2_measure_lds_peak.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
         L.p2_topk.restype = C.c_int32
         L.p2_topk.argtypes = [f64p, u64p, C.c_int64, C.c_int32, i64p]
         L.p2_topk_device.restype = C.c_int32
@@ -331,6 +340,13 @@ def p2_measure_alu_peak(reps=5, stream=None):
     """Measured rate of independent 32-bit integer vector instructions, lane-operations per second."""
     out = C.c_double()
     _check(lib().p2_measure_alu_peak(reps, C.byref(out), stream))
+    return out.value
+
+
+def p2_measure_lds_peak(reps=5, stream=None):
+    """Measured rate of 128-bit reads from the local data share, bytes per second."""
+    out = C.c_double()
+    _check(lib().p2_measure_lds_peak(reps, C.byref(out), stream))
     return out.value
 
 

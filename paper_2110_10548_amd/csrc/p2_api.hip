@@ -89,8 +89,41 @@ struct Prof {
     ~Prof();
     void release();
     bool on = false;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    p2_profile last = {0.f, 0.f, 0, 0, 0.f, 0.f};
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};     // evaluation begin / end, post end, frontier begin / end
+    p2_profile last = {};
+    // events around single launches of the frontier engine: a pool that grows on demand and is kept
+    enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kKinds = 3 };
+    struct Span { int kind; size_t first; };
+    std::vector<hipEvent_t> pool;
+    std::vector<Span> spans;
+    size_t used = 0;
+    hipError_t begin(int kind, hipStream_t stream) {
+        if (!on) return hipSuccess;
+        while (pool.size() < used + 2) {
+            hipEvent_t e = nullptr;
+            const hipError_t rc = hipEventCreate(&e);
+            if (rc != hipSuccess) return rc;
+            pool.push_back(e);
+        }
+        spans.push_back(Span{kind, used});
+        used += 2;
+        return hipEventRecord(pool[used - 2], stream);
+    }
+    hipError_t end(hipStream_t stream) { return on ? hipEventRecord(pool[used - 1], stream) : hipSuccess; }
+    // after the stream has been waited for: time per kind, launches per kind
+    hipError_t collect(float ms[kKinds], int32_t launches[kKinds]) {
+        for (int k = 0; k < kKinds; ++k) { ms[k] = 0.f; launches[k] = 0; }
+        for (const Span& sp : spans) {
+            float t = 0.f;
+            const hipError_t rc = hipEventElapsedTime(&t, pool[sp.first], pool[sp.first + 1]);
+            if (rc != hipSuccess) return rc;
+            ms[sp.kind] += t;
+            ++launches[sp.kind];
+        }
+        spans.clear();
+        used = 0;
+        return hipSuccess;
+    }
 };
 thread_local Prof g_prof;
 
@@ -113,6 +146,8 @@ void Ctx::release() {
 Ctx::~Ctx() { if (std::this_thread::get_id() != g_loader_thread) release(); }
 void Prof::release() {
     for (auto& e : ev) { if (e) (void)hipEventDestroy(e); e = nullptr; }
+    for (auto& e : pool) (void)hipEventDestroy(e);
+    pool.clear(); spans.clear(); used = 0;
     on = false;
 }
 Prof::~Prof() { if (std::this_thread::get_id() != g_loader_thread) release(); }
@@ -271,6 +306,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
         }
     }
+    g_prof.spans.clear(); g_prof.used = 0;       // (a call that failed half-way leaves its spans behind)
     g_prof.last.host_plan_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     // ---- lay out the table blob: queries, message sizes, bandwidth rows
     size_t off = 0;
@@ -736,6 +772,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(hipMemcpyAsync(C.f_share.p, C.h_fshare.p, sizeof(int32_t) * n_share_all, hipMemcpyHostToDevice, stream));
     }
     size_t fvalid_used = 0, fsums_used = 0;
+    // what the frontier kernels' launches of this call worked on (the figures of p2_profile)
+    double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0;
+    if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[3], stream));
     for (auto& E : enums) {
         const int i = E.leader;
         QueryRun& r = runs[i];
@@ -745,6 +784,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         E.off_valid = fvalid_used; E.off_sums = fsums_used;
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
         const size_t sw = frontier_state_words(pl.R, pl.k);
+        // words of a device's (chunk set, mask) pair, and the devices that the alphabet's patterns visit per prefix
+        const double pair_words = (double)((pl.k + 31) / 32 + (pl.R + 31) / 32);
+        double pattern_members = 0.0;
+        for (const auto& pt : pl.patterns) pattern_members += (double)pt.g * pt.n_groups;
         // state pairs per device: 2 where two planes fit in LDS; the option can lower it (1: as the compact form;
         // 4: no pair states at all, every prefix on the literal list) or, with 3, have every two-pair prefix
         // classified by the literal kernels (the path of prefixes whose groups are not aligned)
@@ -783,6 +826,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
                 P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+                if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
                                              static_cast<const uint32_t*>(C.f_states[cur].p), n_c, 1, max_pairs, 0,
                                              static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
@@ -791,12 +835,21 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                              2, max_pairs, fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0,
                                              static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
                                              static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
+                if (n_c + n_c2 > 0) {
+                    P2_HIP(g_prof.end(stream));
+                    const double planes = (double)n_c + 2.0 * n_c2;
+                    prof_prefixes += (double)n_c + n_c2;
+                    prof_state_bytes += planes * pl.R * pair_words * 4.0;
+                    prof_lane_ops += planes * pattern_members * pair_words * 4.0;
+                }
                 if (n_l > 0) {
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
                     gs = C.lit_scratch.p;
+                    P2_HIP(g_prof.begin(Prof::kLiteral, stream));
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
                                                          pl.max_row_classes, stream));
+                    P2_HIP(g_prof.end(stream));
                 }
                 P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                 P2_HIP(hipStreamSynchronize(stream));
@@ -808,9 +861,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(hipMemsetAsync(&dctr->n_overflow, 0, sizeof(uint32_t), stream));
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(std::max(n_l, n_c2), n_u))));
                     gs = C.lit_scratch.p;
+                    P2_HIP(g_prof.begin(Prof::kLiteral, stream));
                     P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_unknown.p), n_u, len,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
                                                          pl.max_row_classes, stream));
+                    P2_HIP(g_prof.end(stream));
                     P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                     P2_HIP(hipStreamSynchronize(stream));
                 }
@@ -865,7 +920,16 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             lv.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
             lv.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
             lv.valid_out = vout; lv.goal_sums = gsums; lv.ctr = dctr;
+            if (n_surv > 0) P2_HIP(g_prof.begin(Prof::kMaterialize, stream));
             P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
+            if (n_surv > 0) {
+                P2_HIP(g_prof.end(stream));
+                // every survivor reads its parent (one plane at least), every kept child is written: states and sums
+                const double kept = keep ? (double)n_prefix + 2.0 * n_prefix2 : 0.0;
+                prof_children += (double)n_surv;
+                prof_mat_bytes += ((double)n_surv + kept) * pl.R * pair_words * 4.0 +
+                                  ((double)n_surv + (keep ? (double)n_prefix + n_prefix2 : 0.0) + n_goal_pair) * (double)sum_doubles * 8.0;
+            }
             P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
                                      static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l_first, len, keep,
                                      static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
@@ -888,6 +952,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             QueryRun& o = runs[m];
             o.n_valid = E.n_valid; o.n_rerun = r.n_rerun; o.steps = r.steps; o.members = r.members;
         }
+    }
+
+    if (g_prof.on) {
+        P2_HIP(hipEventRecord(g_prof.ev[4], stream));
+        g_prof.last.front_prefixes = prof_prefixes; g_prof.last.front_classify_state_bytes = prof_state_bytes;
+        g_prof.last.front_classify_lane_ops = prof_lane_ops; g_prof.last.front_survivors = prof_children;
+        g_prof.last.front_materialize_bytes = prof_mat_bytes;
     }
 
     // ---- order, cost, select
@@ -1070,7 +1141,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     if (g_prof.on) {
         P2_HIP(hipEventElapsedTime(&g_prof.last.eval_ms, g_prof.ev[0], g_prof.ev[1]));
         g_prof.last.post_ms = 0.0f;
-        if (store) P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[1], g_prof.ev[2]));
+        if (store) P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[4], g_prof.ev[2]));
+        P2_HIP(hipEventSynchronize(g_prof.ev[4]));      // (a call that only sizes its result has not waited since)
+        P2_HIP(hipEventElapsedTime(&g_prof.last.front_ms, g_prof.ev[3], g_prof.ev[4]));
+        float ms[Prof::kKinds];
+        int32_t launches[Prof::kKinds];
+        P2_HIP(g_prof.collect(ms, launches));
+        g_prof.last.front_classify_ms = ms[Prof::kClassify]; g_prof.last.front_classify_launches = launches[Prof::kClassify];
+        g_prof.last.front_literal_ms = ms[Prof::kLiteral]; g_prof.last.front_literal_launches = launches[Prof::kLiteral];
+        g_prof.last.front_materialize_ms = ms[Prof::kMaterialize]; g_prof.last.front_materialize_launches = launches[Prof::kMaterialize];
     }
     // ---- hand the results over
     const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);
@@ -1105,6 +1184,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             s.steps_evaluated = r.shared ? r.evaluated : r.steps;
             s.members_evaluated = r.shared ? r.evaluated_members : r.members;
             s.valid = r.n_valid; s.group_size = r.plan.R; s.n_patterns = (int32_t)r.plan.patterns.size();
+            s.evaluated_with = r.frontier ? (r.enum_id >= 0 && enums[r.enum_id].leader != i ? enums[r.enum_id].leader : -1) : r.same_as;
+            s.reserved0 = 0;
             s.alphabet = r.plan.alphabet; s.engine = r.frontier ? P2_ENGINE_FRONTIER : r.shared ? P2_ENGINE_SHARED : r.regs ? P2_ENGINE_SMALL : r.engine;
         }
     }
@@ -1141,6 +1222,12 @@ int32_t p2_release_thread(void) {
 int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_stream) {
     if (!out_lane_ops_per_s || reps < 1 || reps > 100) return fail(P2_EINVAL, "bad arguments");
     P2_HIP(p2::measure_alu_peak(reps, out_lane_ops_per_s, (hipStream_t)hip_stream));
+    return P2_OK;
+}
+
+int32_t p2_measure_lds_peak(int32_t reps, double* out_bytes_per_s, void* hip_stream) {
+    if (!out_bytes_per_s || reps < 1 || reps > 100) return fail(P2_EINVAL, "bad arguments");
+    P2_HIP(p2::measure_lds_peak(reps, out_bytes_per_s, (hipStream_t)hip_stream));
     return P2_OK;
 }
 

@@ -188,6 +188,7 @@ hipError_t launch_cost_shared(const DevQuery* queries, const DevPostSeg* segs, i
                               unsigned long long* sorted, p2_program* progs, double* costs, hipStream_t stream);
 // Best rate, in lane-operations per second, of a stream of independent 32-bit vector ALU instructions.
 hipError_t measure_alu_peak(int reps, double* lane_ops_per_s, hipStream_t stream);
+hipError_t measure_lds_peak(int reps, double* bytes_per_s, hipStream_t stream);
 // Candidates per wavefront the compact engine can keep in LDS for this state size (0 = none).
 int compact_lanes(int R, int k);
 // Per segment: sorted[out_off + i] = i-th smallest of valid[in_off .. in_off + count)  (distinct keys).

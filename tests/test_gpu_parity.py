@@ -566,6 +566,15 @@ def test_measured_alu_ceiling(B):
     assert 0.5 * nominal < got <= 1.02 * nominal, got
 
 
+def test_measured_lds_ceiling(B):
+    """The derived ceiling of the local data share (256 CUs x 128 bytes per clock x 2.4 GHz) bounds what a stream
+    of 128-bit reads reaches, and the stream comes within a factor of three of it."""
+    nominal = 256 * 128 * 2.4e9
+    got = B.p2_measure_lds_peak(3)
+    print("LDS read stream: %.1f TB/s of %.1f" % (got / 1e12, nominal / 1e12))
+    assert nominal / 3 < got <= 1.02 * nominal, got
+
+
 def test_caller_stream_and_host_threads(B, oracle):
     """The call runs on the caller's HIP stream (after work already queued there), and calls from
     different host threads use their own device scratch."""
