@@ -483,9 +483,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 const Pattern& p = pl.patterns[pi];
                 H.pat_begin[pi] = row;
                 for (size_t t = 0; t < p.row_level.size(); ++t) {
-                    for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) en[ent++] = p.entries[e];
+                    uint32_t sum = 0;
+                    for (int e = p.row_ptr[t]; e < p.row_ptr[t + 1]; ++e) { en[ent++] = p.entries[e]; sum += entry_cnt(p.entries[e]); }
                     rl[row] = p.row_level[t];
                     rp[++row] = ent;
+                    H.level_max[pi][p.row_level[t]] = std::max(H.level_max[pi][p.row_level[t]], sum);
                 }
             }
             for (size_t pi = pl.patterns.size(); pi <= (size_t)kMaxPatterns; ++pi) H.pat_begin[pi] = row;
@@ -914,6 +916,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             lv.sums2 = static_cast<const double*>(C.f_sums2[cur].p);
             lv.surv = static_cast<const FrontSurvivor*>(C.f_surv.p); lv.n_surv = n_surv;
             lv.parent_len = len; lv.keep_prefixes = keep;
+            lv.lds_planes = (n_c2 > 0 || n_prefix2 > 0) ? 2 : 1;
             lv.next_entries1 = static_cast<FrontEntry*>(C.f_entries[nxt].p); lv.next_states1 = static_cast<uint32_t*>(C.f_states[nxt].p);
             lv.next_sums1 = static_cast<double*>(C.f_sums[nxt].p);
             lv.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);

@@ -122,6 +122,9 @@ struct DevRows {
     const uint32_t* entries;       // entry_pack(local group, its first device, groups touching the unit)
     int32_t pat_begin[kMaxPatterns + 1];
     int32_t pad;
+    // per pattern and hardware level the largest sum of multiplicities over the level's rows: where every group
+    // of the pattern holds the same number of rows c, the busiest unit of a level carries c times this
+    uint32_t level_max[kMaxPatterns][P2_MAX_LEVELS];
 };
 
 struct DevQuery {
@@ -267,6 +270,7 @@ struct FrontLevel {
     const FrontEntry* entries2; const uint32_t* states2; const double* sums2;     // two-pair list
     const FrontSurvivor* surv; uint32_t n_surv;
     int32_t parent_len, keep_prefixes;
+    int32_t lds_planes;            // 2 if a parent or a child of this level has two pairs, else 1
     FrontEntry* next_entries1; uint32_t* next_states1; double* next_sums1;
     FrontEntry* next_entries2; uint32_t* next_states2; double* next_sums2;
     FrontEntry* next_literal;

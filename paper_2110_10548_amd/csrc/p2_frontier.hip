@@ -870,17 +870,67 @@ __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long lo
     return q.base[len] + v;
 }
 
-// One wavefront per survivor of the one-pair and two-pair frontiers.
+// ---- children of the survivors -----------------------------------------------------------------------
+constexpr int kMatThreads = 256, kMatWaves = kMatThreads / 64;
+
+// Smallest over the 8 lanes of a slot, in every lane of the slot (all lanes active).
+__device__ inline int min_slot(int v) {
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));
+    return v;
+}
+// The lowest n set bits of w (none for n <= 0, all for n >= popcount).
+__device__ inline uint32_t low_bits(uint32_t w, int n) {
+    if (n <= 0) return 0u;
+    if (n >= __popc(w)) return w;
+    int pos = 0;                                   // position of the n-th set bit: binary search on prefix counts
+#pragma unroll
+    for (int step = 16; step > 0; step >>= 1)
+        if (__popc(w & ((1u << (pos + step)) - 1u)) < n) pos += step;
+    return w & ((2u << pos) - 1u);
+}
+// A device's two pairs, a lane per quad (a: first pair, b: second), brought into the stored form by the 8 lanes
+// of its slot together: an empty pair has an empty mask, pairs with equal masks are one pair, the pair that
+// holds the lowest row comes first.  Every lane of the wavefront calls it.
+__device__ inline void canonical_slot(uint4& a, uint4& b, bool is_row, bool is_mask, int qd, int sh) {
+    const unsigned long long nz0 = __ballot(is_row && q_any(a)), nz1 = __ballot(is_row && q_any(b));
+    const bool e0 = ((nz0 >> sh) & 0xffull) == 0ull, e1 = ((nz1 >> sh) & 0xffull) == 0ull;
+    if (is_mask) { if (e0) a = q_zero(); if (e1) b = q_zero(); }
+    const unsigned long long md = __ballot(is_mask && q_any(q_xor(a, b)));
+    if (!e1 && ((md >> sh) & 0xffull) == 0ull) {
+        if (is_row) a = q_or(a, b);
+        b = q_zero();
+    }
+    int l0 = 1 << 20, l1 = 1 << 20;
+    if (is_row) {
+        if (q_any(a)) l0 = qd * 128 + (a.x ? __ffs((int)a.x) - 1 : a.y ? 31 + __ffs((int)a.y) : a.z ? 63 + __ffs((int)a.z) : 95 + __ffs((int)a.w));
+        if (q_any(b)) l1 = qd * 128 + (b.x ? __ffs((int)b.x) - 1 : b.y ? 31 + __ffs((int)b.y) : b.z ? 63 + __ffs((int)b.z) : 95 + __ffs((int)b.w));
+    }
+    l0 = min_slot(l0); l1 = min_slot(l1);
+    if (l1 < l0) { const uint4 t = a; a = b; b = t; }
+}
+
+// A block per survivor of the one-pair and two-pair frontiers at a time: the parent's planes come into LDS with
+// 128-bit loads, the instruction is applied there in place (a lane is (slot, quad) as in the classification; the
+// slots of a wavefront take 8 groups side by side, or share the members of a group where the pattern has fewer
+// groups: first the members are put together, then every member's new pairs are written), and the child's planes
+// go out with 128-bit stores.  Groups are disjoint sets of devices, so the wavefronts do not meet.  The rows that
+// a group's members hold set the bytes of the step (s_count), from which the wavefronts then work out the step's
+// time for every query of the enumeration.
 template <int KW, int MW>
-__global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
+__global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
+    extern __shared__ uint4 ldsq[];                      // A.lds_planes planes of [R][WQ] quads
     __shared__ PatLds spat[kMaxPatterns];
-    __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];        // rows that set a group's bytes
+    __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];     // rows that set a group's bytes
+    using L = FL<KW, MW>;
     const DevQuery& q = queries[A.query];
-    constexpr int WPD = FL<KW, MW>::WS;
-    const int lane = threadIdx.x;
     const int R = q.R;
-    const int plane = R * WPD;
-    for (int i = lane; i < q.n_patterns; i += 64) {
+    const int plane_q = R * L::WQ;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = lane >> 3, qd = lane & 7, sh = slot * 8;
+    const bool is_row = qd < L::QK, is_mask = qd >= L::QK && qd < L::WQ, has_quad = qd < L::WQ;
+    for (int i = tid; i < q.n_patterns; i += kMatThreads) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
@@ -896,83 +946,188 @@ __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __rest
         FrontEntry ce;
         ce.query = A.query; ce.len = (uint32_t)(A.parent_len + 1); ce.digits = digits;
         if (code == CODE_PREFIX_LITERAL) {
-            if (A.keep_prefixes && lane == 0) A.next_literal[atomicAdd(&A.ctr->next_literal, 1u)] = ce;
+            if (A.keep_prefixes && tid == 0) A.next_literal[atomicAdd(&A.ctr->next_literal, 1u)] = ce;
             continue;
         }
         if (code != CODE_GOAL && !A.keep_prefixes) continue;     // the size limit is reached: nothing extends this prefix
-        const uint32_t* parent = (np == 2 ? A.states2 + (size_t)sv.entry * 2 * plane : A.states1 + (size_t)sv.entry * plane);
+        const size_t plane_w = (size_t)plane_q * 4;
+        const uint4* parent = reinterpret_cast<const uint4*>(np == 2 ? A.states2 + (size_t)sv.entry * 2 * plane_w
+                                                                      : A.states1 + (size_t)sv.entry * plane_w);
         const double* psum = (np == 2 ? A.sums2 : A.sums1) + (size_t)sv.entry * 2 * A.n_share;
         const int cnp = code == CODE_PREFIX2 ? 2 : 1;
         // (the classification gave every child its place in the next frontier, every goal its place in the list)
-        const uint32_t slot = sv.slot;
-        if (lane == 0) {
-            if (code == CODE_GOAL) A.valid_out[slot] = rank_of(q, digits, A.parent_len + 1);
-            else if (code == CODE_PREFIX2) A.next_entries2[slot] = ce;
-            else A.next_entries1[slot] = ce;
+        const uint32_t place = sv.slot;
+        if (tid == 0) {
+            if (code == CODE_GOAL) A.valid_out[place] = rank_of(q, digits, A.parent_len + 1);
+            else if (code == CODE_PREFIX2) A.next_entries2[place] = ce;
+            else A.next_entries1[place] = ce;
         }
-        __syncthreads();
-        uint32_t* child = nullptr;
-        if (code == CODE_PREFIX2) child = A.next_states2 + (size_t)slot * 2 * plane;
-        else if (code == CODE_PREFIX) child = A.next_states1 + (size_t)slot * plane;
-        if (child) {
-            // the devices that take no part keep their pairs (a device that needs its second pair keeps it:
-            // the child then has two planes)
-            for (int w = lane; w < plane; w += 64) child[w] = parent[w];
-            if (cnp == 2) for (int w = lane; w < plane; w += 64) child[plane + w] = np == 2 ? parent[plane + w] : 0u;
+        __syncthreads();                                 // (the block is done with the planes and counts of its last survivor)
+        for (int i0 = tid; i0 < np * plane_q; i0 += 8 * kMatThreads) {
+            uint4 tmp[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const int w = i0 + u * kMatThreads; tmp[u] = w < np * plane_q ? parent[w] : q_zero(); }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const int w = i0 + u * kMatThreads; if (w < np * plane_q) ldsq[w] = tmp[u]; }
         }
+        if (np == 1 && cnp == 2)                         // the devices that take no part have no second pair
+            for (int w = tid; w < plane_q; w += kMatThreads) ldsq[plane_q + w] = q_zero();
         __syncthreads();
-        // apply the instruction: lanes over groups, members in order; reads the parent, writes the child
+        // ---- apply the instruction in LDS
         const uint32_t ins = q.instr_of_digit[sv.digit];
         const int pid = (int)(ins >> 3);
         const PatLds P = spat[pid];
         const int op = (int)(ins & 7u);
-        for (int G = lane; G < P.n_groups; G += 64) {
-            const int base = first_of_group(P, G);
+        const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+        int spg = 1;                                     // slots that share a group
+        while (spg * 2 * ng <= 8) spg *= 2;
+        const int gpb = 8 / spg;                         // groups side by side
+        const int my_g = slot / spg, part = slot - my_g * spg;
+        const int trips = (g + spg - 1) / spg;
+        const bool both = np == 2;                       // the parent has a second plane
+        for (int G0 = wave * gpb; G0 < ng; G0 += kMatWaves * gpb) {
+            const int G = G0 + my_g;
+            const bool act = G < ng && has_quad;
+            int base = 0;
+            if (P.master) base = G * gs;
+            else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
             int rows_held = 0;
             if (op == OP_AR || op == OP_RS || op == OP_RD) {
-                const RedFold<KW, MW> f = fold_red<KW, MW>(parent, R, np, base, P.g, P.s);
-                rows_held = popcount(f.u0);
-                if (child && rows_held) {
-                    const Words<KW> xb = f.split ? andn_words(f.u0, f.xa) : zero_words<KW>();
-                    const Words<KW> xa = f.split ? f.xa : f.u0;
-                    if (op == OP_AR) {
-                        for (int t = 0; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, xa, f.accA, xb, f.accB);
-                    } else if (op == OP_RD) {
-                        store_pairs<KW, MW>(child, R, cnp, base, xa, f.accA, xb, f.accB);
-                        for (int t = 1; t < P.g; ++t)
-                            store_pairs<KW, MW>(child, R, cnp, base + t * P.s, zero_words<KW>(), zero_words<MW>(), zero_words<KW>(), zero_words<MW>());
-                    } else {
-                        // rank t keeps the t-th block of the rows in ascending order, on both sides of the split
-                        const int per = div_small(rows_held, P.g);
-                        Words<KW> prev = zero_words<KW>();
-                        for (int t = 0; t < P.g; ++t) {
-                            const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
-                            const Words<KW> blk = andn_words(upto, prev);
-                            prev = upto;
-                            store_pairs<KW, MW>(child, R, cnp, base + t * P.s, and_words(blk, xa), f.accA, and_words(blk, xb), f.accB);
+                // row lanes: u = the rows (every member holds the same), xa = first-pair rows of the members with two pairs;
+                // mask lanes: u = united first masks, mb = united masks of the other side of the split
+                uint4 u = q_zero(), xa = q_zero(), mb = q_zero();
+                bool split = false;
+                for (int it = 0; it < trips; ++it) {
+                    const int t = it * spg + part;
+                    const bool on = act && t < g;
+                    const int d = base + t * s;
+                    const uint4 v0 = on ? ldsq[d * L::WQ + qd] : q_zero();
+                    const uint4 v1 = (both && on) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+                    const bool two = ((__ballot(is_row && q_any(v1)) >> sh) & 0xffull) != 0ull;
+                    split |= two;
+                    if (is_row) { u = q_or(u, q_or(v0, v1)); if (two) xa = q_or(xa, v0); }
+                    else { u = q_or(u, v0); mb = q_or(mb, two ? v1 : v0); }
+                }
+                for (int m = 8; m < 8 * spg; m <<= 1) {
+                    u = q_or(u, q_shfl_xor(u, m)); xa = q_or(xa, q_shfl_xor(xa, m)); mb = q_or(mb, q_shfl_xor(mb, m));
+                    split |= __shfl_xor((int)split, m, 64) != 0;
+                }
+                rows_held = sum_slot((act && is_row) ? q_popc(u) : 0);
+                // the group's result: rows xa (or all of them) with the united first masks, the other rows with mb
+                const uint4 ra = is_row ? (split ? xa : u) : u;
+                const uint4 rb = is_row ? (split ? q_andn(u, xa) : q_zero()) : mb;
+                if (op == OP_RS) {
+                    // rank t keeps the t-th block of the rows in ascending order, on both sides of the split
+                    const int per = div_small(rows_held, g);
+                    const int mine = (act && is_row) ? q_popc(u) : 0;
+                    int before = 0;                      // rows in the quads below this lane's
+#pragma unroll
+                    for (int j = 0; j < L::QK; ++j) { const int c = __shfl(mine, sh + j, 64); if (j < qd) before += c; }
+                    for (int it = 0; it < trips; ++it) {
+                        const int t = it * spg + part;
+                        const bool on = act && t < g;
+                        const int d = base + t * s;
+                        const int lo = t * per, hi = lo + per;
+                        uint4 blk = q_zero();
+                        if (is_row) {
+                            int p0 = before;
+                            blk.x = low_bits(u.x, hi - p0) & ~low_bits(u.x, lo - p0); p0 += __popc(u.x);
+                            blk.y = low_bits(u.y, hi - p0) & ~low_bits(u.y, lo - p0); p0 += __popc(u.y);
+                            blk.z = low_bits(u.z, hi - p0) & ~low_bits(u.z, lo - p0); p0 += __popc(u.z);
+                            blk.w = low_bits(u.w, hi - p0) & ~low_bits(u.w, lo - p0);
                         }
+                        uint4 a = is_row ? q_and(blk, ra) : ra, b = is_row ? q_and(blk, rb) : rb;
+                        canonical_slot(a, b, is_row, is_mask, qd, sh);
+                        if (on) { ldsq[d * L::WQ + qd] = a; if (cnp == 2) ldsq[plane_q + d * L::WQ + qd] = b; }
+                    }
+                } else {
+                    uint4 a = ra, b = rb;
+                    canonical_slot(a, b, is_row, is_mask, qd, sh);
+                    for (int it = 0; it < trips; ++it) {
+                        const int t = it * spg + part;
+                        const bool on = act && t < g;
+                        const int d = base + t * s;
+                        const bool keeps = op == OP_AR || t == 0;        // Reduce: the root alone keeps the result
+                        if (on) { ldsq[d * L::WQ + qd] = keeps ? a : q_zero(); if (cnp == 2) ldsq[plane_q + d * L::WQ + qd] = keeps ? b : q_zero(); }
                     }
                 }
             } else if (op == OP_AG) {
-                const GatherFold<KW, MW> f = fold_gather<KW, MW>(parent, R, np, base, P.g, P.s);
-                rows_held = popcount(f.u);
-                if (child)
-                    for (int t = 0; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, f.xd0, f.d0, f.xd1, f.d1);
+                // the first member's first mask, and whatever differs from it (at most one other mask: the
+                // classification has counted); row lanes collect the rows that carry each
+                const uint4 d0 = (act && is_mask) ? ldsq[base * L::WQ + qd] : q_zero();
+                uint4 x0 = q_zero(), x1 = q_zero(), d1 = q_zero();
+                for (int it = 0; it < trips; ++it) {
+                    const int t = it * spg + part;
+                    const bool on = act && t < g;
+                    const int d = base + t * s;
+#pragma unroll
+                    for (int pl = 0; pl < 2; ++pl) {
+                        const uint4 v = (on && (pl == 0 || both)) ? ldsq[pl * plane_q + d * L::WQ + qd] : q_zero();
+                        const bool there = ((__ballot(is_row && q_any(v)) >> sh) & 0xffull) != 0ull;
+                        const bool other = ((__ballot(is_mask && q_any(q_xor(v, d0))) >> sh) & 0xffull) != 0ull;
+                        if (there) {
+                            if (is_row) { if (other) x1 = q_or(x1, v); else x0 = q_or(x0, v); }
+                            else if (other) d1 = q_or(d1, v);
+                        }
+                    }
+                }
+                for (int m = 8; m < 8 * spg; m <<= 1) {
+                    x0 = q_or(x0, q_shfl_xor(x0, m)); x1 = q_or(x1, q_shfl_xor(x1, m)); d1 = q_or(d1, q_shfl_xor(d1, m));
+                }
+                rows_held = sum_slot((act && is_row) ? q_popc(q_or(x0, x1)) : 0);
+                uint4 a = is_row ? x0 : d0, b = is_row ? x1 : d1;
+                canonical_slot(a, b, is_row, is_mask, qd, sh);
+                for (int it = 0; it < trips; ++it) {
+                    const int t = it * spg + part;
+                    const bool on = act && t < g;
+                    const int d = base + t * s;
+                    if (on) { ldsq[d * L::WQ + qd] = a; if (cnp == 2) ldsq[plane_q + d * L::WQ + qd] = b; }
+                }
             } else {
-                const Pairs<KW, MW> root = load_pairs<KW, MW>(parent, R, np, base);
-                rows_held = popcount(or_words(root.x0, root.x1));
-                if (child)
-                    for (int t = 1; t < P.g; ++t) store_pairs<KW, MW>(child, R, cnp, base + t * P.s, root.x0, root.m0, root.x1, root.m1);
+                // Broadcast: the root's pairs, as they are
+                const uint4 a = act ? ldsq[base * L::WQ + qd] : q_zero();
+                const uint4 b = (act && both) ? ldsq[plane_q + base * L::WQ + qd] : q_zero();
+                rows_held = sum_slot((act && is_row) ? q_popc(q_or(a, b)) : 0);
+                for (int it = 0; it < trips; ++it) {
+                    const int t = it * spg + part;
+                    const bool on = act && t < g && t > 0;
+                    const int d = base + t * s;
+                    if (on) { ldsq[d * L::WQ + qd] = a; if (cnp == 2) ldsq[plane_q + d * L::WQ + qd] = b; }
+                }
             }
-            s_count[G] = (uint32_t)rows_held;
+            if (qd == 0 && part == 0 && G < ng) s_count[G] = (uint32_t)rows_held;
         }
         __syncthreads();
+        if (code != CODE_GOAL) {
+            uint4* child = reinterpret_cast<uint4*>(cnp == 2 ? A.next_states2 + (size_t)place * 2 * plane_w
+                                                             : A.next_states1 + (size_t)place * plane_w);
+            for (int w = tid; w < cnp * plane_q; w += kMatThreads) child[w] = ldsq[w];
+        }
         // ---- the step's time for every query of the enumeration (alpha-beta model: latency steps of the
         //      slowest group's link; bytes through the busiest uplink, from the query's bandwidth rows)
-        double* out = code == CODE_GOAL ? A.goal_sums + (size_t)slot * 2 * A.n_share
-                                        : (code == CODE_PREFIX2 ? A.next_sums2 : A.next_sums1) + (size_t)slot * 2 * A.n_share;
-        if (A.n_msg > 0) {
-            for (int j = 0; j < A.n_share; ++j) {
+        double* out = code == CODE_GOAL ? A.goal_sums + (size_t)place * 2 * A.n_share
+                                        : (code == CODE_PREFIX2 ? A.next_sums2 : A.next_sums1) + (size_t)place * 2 * A.n_share;
+        // Where every group holds the same number of rows c (the usual case), the busiest unit of a hardware level
+        // carries c times the largest multiplicity sum of that level's rows, which the row tables carry per pattern:
+        // the same maximum, term by term, without walking the rows; a lane per query then.
+        const uint32_t c0 = s_count[0];
+        bool same = true;
+        for (int G = lane; G < ng; G += 64) same &= s_count[G] == c0;
+        const bool uniform = __all(same) != 0;
+        if (A.n_msg > 0 && uniform) {
+            for (int j = tid; j < A.n_share; j += kMatThreads) {
+                const DevQuery& cq = queries[A.share[j]];
+                const DevRows& rw = *cq.rows;
+                double best = 0.0;
+                for (int l = 0; l < cq.n_levels; ++l)
+                    best = fmax(best, (double)((long long)c0 * (long long)rw.level_max[pid][l]) * cq.inv_bw[l]);
+                double ring_steps, mult;
+                step_factors(op, P.g, cq.algo, ring_steps, mult);
+                out[2 * j] = psum[2 * j] + ring_steps * cq.alpha[cq.pat[pid].span_level];
+                out[2 * j + 1] = psum[2 * j + 1] + (mult / (double)cq.k) * best;
+            }
+        } else if (A.n_msg > 0) {
+            for (int j = wave; j < A.n_share; j += kMatWaves) {
                 const DevQuery& cq = queries[A.share[j]];
                 const DevRows& rw = *cq.rows;
                 double best = 0.0;
@@ -995,7 +1150,7 @@ __global__ __launch_bounds__(64) void k_front_materialize(const DevQuery* __rest
         }
         if (code != CODE_GOAL) { ++made; made_members += (unsigned long long)(P.n_groups * P.g); }
     }
-    if (lane == 0 && made) { atomicAdd(&A.ctr->steps, made); atomicAdd(&A.ctr->members, made_members); }
+    if (tid == 0 && made) { atomicAdd(&A.ctr->steps, made); atomicAdd(&A.ctr->members, made_members); }
 }
 
 // Survivors of the literal frontier carry no state: a goal becomes a valid program, the rest
@@ -1128,8 +1283,11 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
             hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.entries, A.states,
                                A.n, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
     } else {
-        const unsigned blocks = A.level->n_surv < 65536u ? A.level->n_surv : 65536u;
-        hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(64), 0, stream, A.queries, *A.level);
+        const size_t lds = (size_t)A.level->lds_planes * A.R * FL<KW, MW>::WS * 4;
+        const unsigned blocks = A.level->n_surv < 8192u ? A.level->n_surv : 8192u;
+        const hipError_t e = allow_lds_f(k_front_materialize<KW, MW>, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(kMatThreads), lds, stream, A.queries, *A.level);
     }
     return hipGetLastError();
 }
