@@ -17,7 +17,7 @@ classification of valid prefixes against every instruction of the alphabet (k_fr
 its algorithmic work per judged prefix is 4 lane-operations (read, union, intersection /
 seen-twice, compare) per 32-bit word of the (chunk set, mask) pairs of every device that a pattern
 of the alphabet visits, set against the chip's 32-bit integer vector rate; the same words are read
-from LDS once per pattern (`roofline.lds`, against 128 bytes per clock and compute unit) and the
+from LDS once per pattern (`roofline.lds`, against 256 bytes per clock and compute unit) and the
 prefix's state comes from device memory once (`roofline.hbm`).  `materialize` prices the kernel
 that writes the surviving children against HBM.  Times are HIP-event times around every launch
 of the family on the call's stream, taken inside the timed steps (p2_get_profile).
@@ -39,8 +39,9 @@ sys.path.insert(0, ROOT)
 # the published 157.3 TFLOP/s of fp32 vector arithmetic (one fused multiply-add = 2 flops per lane and clock).
 # A stream of independent v_xor_b32 reaches about 0.8 of it (roofline.peak_measured, p2_measure_alu_peak).
 ALU_PEAK_LANE_OPS = 256 * 128 * 2.4e9
-# local data share: 128 bytes per clock and compute unit
-LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+# local data share: 256 bytes per clock and compute unit with 128-bit reads (a read stream reaches 0.98 of it:
+# roofline.lds.peak_measured, p2_measure_lds_peak)
+LDS_PEAK_BYTES = 256 * 256 * 2.4e9
 HBM_PEAK_BYTES = 8.0e12
 
 ENGINE_NAMES = {0: "auto", 1: "literal", 2: "compact", 3: "frontier", 4: "small-group", 5: "shared-prefix"}

@@ -319,8 +319,10 @@ typedef struct {
     float front_literal_ms;           /* prefixes held literally, judged from their instructions    */
     float front_materialize_ms;       /* surviving children: state and running cost sums written    */
     int32_t front_classify_launches, front_literal_launches, front_materialize_launches;
-    int32_t reserved0;
-    double front_prefixes;            /* prefixes the pair classification judged                    */
+    float front_group_ms;             /* the search for entries with equal states, and the listing of
+                                         every entry's survivors from the codes of its state       */
+    double front_prefixes;            /* prefixes the pair classification judged: one per distinct
+                                         state of a frontier list                                   */
     double front_classify_state_bytes;/* bytes of their states, R * (ceil(k/32) + ceil(R/32)) words
                                          per pair plane: what the classification must read from
                                          device memory                                              */
@@ -330,6 +332,8 @@ typedef struct {
     double front_survivors;           /* valid children handed to the materialisation               */
     double front_materialize_bytes;   /* bytes it must move: a parent plane read per survivor, the
                                          planes of every kept child written, the cost sums of both  */
+    double front_entries;             /* entries of the pair lists, all levels (front_prefixes of them
+                                         were judged, the others share the codes of an equal state) */
 } p2_profile;
 int32_t p2_set_profiling(int32_t on);
 int32_t p2_get_profile(p2_profile* out);
@@ -345,7 +349,7 @@ int32_t p2_measure_alu_peak(int32_t reps, double* out_lane_ops_per_s, void* hip_
  * 128-bit reads from the local data share reach on the current device (every lane 16 bytes per
  * instruction, all banks, many reads in flight): the frontier engine's classification (Sec. 3.5: every
  * valid prefix is judged against every instruction of the alphabet) reads the prefix's state from LDS
- * once per pattern, and its LDS byte rate is set against 256 compute units x 128 bytes per clock x
+ * once per pattern, and its LDS byte rate is set against 256 compute units x 256 bytes per clock x
  * 2.4 GHz; this shows how close the device comes to that.  hip_stream: hipStream_t or NULL.
  * P2_EINVAL on bad arguments. */
 int32_t p2_measure_lds_peak(int32_t reps, double* out_bytes_per_s, void* hip_stream);

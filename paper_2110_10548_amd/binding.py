@@ -51,10 +51,10 @@ class p2_profile(C.Structure):
                 ("host_plan_ms", C.c_float), ("host_total_ms", C.c_float),
                 ("front_ms", C.c_float), ("front_classify_ms", C.c_float), ("front_literal_ms", C.c_float),
                 ("front_materialize_ms", C.c_float), ("front_classify_launches", C.c_int32),
-                ("front_literal_launches", C.c_int32), ("front_materialize_launches", C.c_int32), ("reserved0", C.c_int32),
+                ("front_literal_launches", C.c_int32), ("front_materialize_launches", C.c_int32), ("front_group_ms", C.c_float),
                 ("front_prefixes", C.c_double), ("front_classify_state_bytes", C.c_double),
                 ("front_classify_lane_ops", C.c_double), ("front_survivors", C.c_double),
-                ("front_materialize_bytes", C.c_double)]
+                ("front_materialize_bytes", C.c_double), ("front_entries", C.c_double)]
 
 
 class p2_search_row(C.Structure):

@@ -78,12 +78,16 @@ struct Ctx {
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
     DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];   // frontier engine
     DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, f_valid, f_gsums, f_rank, f_share;
+    DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
     hipEvent_t copy_done = nullptr;
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs, h_fshare;
 };
 thread_local Ctx g_ctx;
+
+// Frontier lists shorter than this are judged entry by entry: grouping them by state would cost more than it saves.
+constexpr uint32_t kGroupMin = 256;
 
 struct Prof {
     ~Prof();
@@ -92,7 +96,7 @@ struct Prof {
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};     // evaluation begin / end, post end, frontier begin / end
     p2_profile last = {};
     // events around single launches of the frontier engine: a pool that grows on demand and is kept
-    enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kKinds = 3 };
+    enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kGroup = 3, kKinds = 4 };
     struct Span { int kind; size_t first; };
     std::vector<hipEvent_t> pool;
     std::vector<Span> spans;
@@ -136,7 +140,9 @@ void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
                      &topk_in, &topk_jobs, &lit_scratch, &post, &f_entries[0], &f_entries[1], &f_states[0], &f_states[1],
                      &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1], &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1],
-                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_unknown, &f_ctr, &f_valid, &f_gsums, &f_rank, &f_share};
+                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_unknown, &f_ctr, &f_valid, &f_gsums, &f_rank, &f_share,
+                     &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1], &f_replist[0], &f_replist[1],
+                     &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1]};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
     HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs, &h_fshare};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
@@ -775,7 +781,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     }
     size_t fvalid_used = 0, fsums_used = 0;
     // what the frontier kernels' launches of this call worked on (the figures of p2_profile)
-    double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0;
+    double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0, prof_entries = 0.0;
     if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[3], stream));
     for (auto& E : enums) {
         const int i = E.leader;
@@ -824,26 +830,59 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             size_t cap_l = std::max<size_t>(1024, ((size_t)n_l + n_c2 / 8) * pl.alphabet / 2);
             uint32_t n_surv_l_first = 0;
             P2_HIP(C.f_unknown.ensure(std::max<size_t>(n_c2, 1) * sizeof(FrontEntry)));
-            for (;;) {     // classify; repeat with larger survivor lists if they overflow
+            // ---- the entries of the two lists grouped by state (many prefixes end in the same state, and what the
+            //      rules say about the next instruction depends on the state alone); one entry per distinct state
+            //      is judged against the alphabet, into a row of codes
+            const uint32_t n_list[2] = {n_c, n_c2};
+            const DevBuf* list_states[2] = {&C.f_states[cur], &C.f_states2[cur]};
+            const DevBuf* list_hash[2] = {&C.f_hash[cur], &C.f_hash2[cur]};
+            bool grouped[2] = {false, false};
+            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, stream));
+            for (int li = 0; li < 2; ++li) {
+                const uint32_t n = n_list[li];
+                if (n == 0) continue;
+                P2_HIP(C.f_codes[li].ensure((size_t)n * pl.alphabet));
+                P2_HIP(C.f_unk[li].ensure(n));
+                grouped[li] = n >= kGroupMin && n < (1u << 24);
+                if (grouped[li]) {
+                    size_t table = 1024;
+                    while (table < (size_t)n * 2) table *= 2;
+                    P2_HIP(C.f_table.ensure(table * sizeof(unsigned long long)));
+                    P2_HIP(C.f_rep[li].ensure((size_t)n * sizeof(uint32_t)));
+                    P2_HIP(C.f_replist[li].ensure((size_t)n * sizeof(uint32_t)));
+                    P2_HIP(g_prof.begin(Prof::kGroup, stream));
+                    P2_HIP(hipMemsetAsync(C.f_table.p, 0xff, table * sizeof(unsigned long long), stream));
+                    P2_HIP(launch_front_dedup(static_cast<const uint32_t*>(list_states[li]->p), sw * (li + 1),
+                                              static_cast<const unsigned long long*>(list_hash[li]->p), n,
+                                              static_cast<unsigned long long*>(C.f_table.p), (uint32_t)table,
+                                              static_cast<uint32_t*>(C.f_rep[li].p), static_cast<uint32_t*>(C.f_replist[li].p),
+                                              &dctr->n_reps[li], stream));
+                    P2_HIP(g_prof.end(stream));
+                }
+            }
+            if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
+            for (int li = 0; li < 2; ++li)
+                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_list[li],
+                                             grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
+                                             grouped[li] ? &dctr->n_reps[li] : nullptr, li + 1, max_pairs,
+                                             static_cast<uint8_t*>(C.f_codes[li].p), static_cast<uint8_t*>(C.f_unk[li].p), stream));
+            if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
+            for (;;) {     // list the survivors; repeat with larger lists if they overflow
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
                 P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
-                if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
-                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries[cur].p),
-                                             static_cast<const uint32_t*>(C.f_states[cur].p), n_c, 1, max_pairs, 0,
-                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
-                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_entries2[cur].p),
-                                             static_cast<const uint32_t*>(C.f_states2[cur].p), n_c2,
-                                             2, max_pairs, fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0,
-                                             static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
-                                             static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
-                if (n_c + n_c2 > 0) {
-                    P2_HIP(g_prof.end(stream));
-                    const double planes = (double)n_c + 2.0 * n_c2;
-                    prof_prefixes += (double)n_c + n_c2;
-                    prof_state_bytes += planes * pl.R * pair_words * 4.0;
-                    prof_lane_ops += planes * pattern_members * pair_words * 4.0;
-                }
+                if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
+                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries[cur].p), n_c,
+                                           grouped[0] ? static_cast<const uint32_t*>(C.f_rep[0].p) : nullptr,
+                                           static_cast<const uint8_t*>(C.f_codes[0].p), static_cast<const uint8_t*>(C.f_unk[0].p), 1, 0,
+                                           static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
+                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries2[cur].p), n_c2,
+                                           grouped[1] ? static_cast<const uint32_t*>(C.f_rep[1].p) : nullptr,
+                                           static_cast<const uint8_t*>(C.f_codes[1].p), static_cast<const uint8_t*>(C.f_unk[1].p), 2,
+                                           fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0,
+                                           static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
+                                           static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
+                if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
                 if (n_l > 0) {
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
                     gs = C.lit_scratch.p;
@@ -879,6 +918,14 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
                 P2_HIP(hipStreamSynchronize(stream));
             }
+            {   // what the classification launches of this level worked on
+                const double j1 = grouped[0] ? (double)hctr->n_reps[0] : (double)n_c, j2 = grouped[1] ? (double)hctr->n_reps[1] : (double)n_c2;
+                const double planes = j1 + 2.0 * j2;
+                prof_entries += (double)n_c + n_c2;
+                prof_prefixes += j1 + j2;
+                prof_state_bytes += planes * pl.R * pair_words * 4.0;
+                prof_lane_ops += planes * pattern_members * pair_words * 4.0;
+            }
             const uint32_t n_surv = (uint32_t)hctr->surv_goal, n_surv_l = hctr->n_surv_literal;
             const uint32_t n_goal_pair = (uint32_t)(hctr->surv_goal >> 32), n_goal_lit = hctr->n_goal, n_goal = n_goal_pair + n_goal_lit;
             const uint32_t n_prefix = (uint32_t)hctr->pref_pref2, n_prefix2 = (uint32_t)(hctr->pref_pref2 >> 32), n_plit = hctr->n_prefix_literal;
@@ -898,6 +945,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(C.f_states2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sw * 8));
                 P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
                 P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
+                // (the materialisation adds every child's hash up from zero)
+                P2_HIP(C.f_hash[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(unsigned long long)));
+                P2_HIP(C.f_hash2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(unsigned long long)));
+                P2_HIP(hipMemsetAsync(C.f_hash[nxt].p, 0, std::max<size_t>(n_prefix, 1) * sizeof(unsigned long long), stream));
+                P2_HIP(hipMemsetAsync(C.f_hash2[nxt].p, 0, std::max<size_t>(n_prefix2, 1) * sizeof(unsigned long long), stream));
             }
             // goals of this level: those of the pair kernels at the places the classification gave them, then those of
             // literal prefixes
@@ -922,6 +974,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             lv.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);
             lv.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
             lv.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
+            lv.next_hash1 = static_cast<unsigned long long*>(C.f_hash[nxt].p); lv.next_hash2 = static_cast<unsigned long long*>(C.f_hash2[nxt].p);
             lv.valid_out = vout; lv.goal_sums = gsums; lv.ctr = dctr;
             if (n_surv > 0) P2_HIP(g_prof.begin(Prof::kMaterialize, stream));
             P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
@@ -962,6 +1015,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         g_prof.last.front_prefixes = prof_prefixes; g_prof.last.front_classify_state_bytes = prof_state_bytes;
         g_prof.last.front_classify_lane_ops = prof_lane_ops; g_prof.last.front_survivors = prof_children;
         g_prof.last.front_materialize_bytes = prof_mat_bytes;
+        g_prof.last.front_entries = prof_entries;
     }
 
     // ---- order, cost, select
@@ -1153,6 +1207,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         g_prof.last.front_classify_ms = ms[Prof::kClassify]; g_prof.last.front_classify_launches = launches[Prof::kClassify];
         g_prof.last.front_literal_ms = ms[Prof::kLiteral]; g_prof.last.front_literal_launches = launches[Prof::kLiteral];
         g_prof.last.front_materialize_ms = ms[Prof::kMaterialize]; g_prof.last.front_materialize_launches = launches[Prof::kMaterialize];
+        g_prof.last.front_group_ms = ms[Prof::kGroup];
     }
     // ---- hand the results over
     const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);

@@ -260,6 +260,8 @@ struct FrontCounters {
     uint32_t next_goal_literal;    // goals of literal prefixes written so far
     // running totals of the enumeration
     unsigned long long steps, members;
+    // distinct states found among the entries of the one-pair / two-pair list (cleared before each level's search)
+    uint32_t n_reps[2];
 };
 // One level of one enumeration, for the materialize kernel.
 struct FrontLevel {
@@ -273,6 +275,7 @@ struct FrontLevel {
     int32_t lds_planes;            // 2 if a parent or a child of this level has two pairs, else 1
     FrontEntry* next_entries1; uint32_t* next_states1; double* next_sums1;
     FrontEntry* next_entries2; uint32_t* next_states2; double* next_sums2;
+    unsigned long long* next_hash1; unsigned long long* next_hash2;      // hash of every child's state (zero on entry)
     FrontEntry* next_literal;
     unsigned long long* valid_out; double* goal_sums;      // goals: candidate index and [n_share][2] sums
     FrontCounters* ctr;
@@ -291,12 +294,28 @@ size_t frontier_state_words(int R, int k);
 int frontier_max_pairs(int R, int k);
 hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
                              double* sums, int n_share, hipStream_t stream);
-// np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends children that need
-// two pairs to the literal list.  unknown_out (np = 2): entries the pair form cannot judge (counted in n_unknown);
-// handover != 0 treats every entry so (the hand-over path, for tests).
-hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
-                                 uint32_t n, int np, int max_pairs, int handover, FrontSurvivor* surv, uint32_t surv_cap,
-                                 FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream);
+// Many prefixes of a frontier list have the same state (instructions that commute, detours that end alike), and
+// what the rules say about the next instruction depends on the state alone.  The entries of a list are therefore
+// grouped by state first: rep[p] = an entry with the same state as p (itself for one entry per distinct state,
+// which are also listed in reps_list / counted in *n_reps).  Equal hashes only propose a pair; it is the
+// comparison of the two states, word by word, that decides.  table: table_size (a power of two, at least 2 n)
+// words, all ones on entry.  n < 2^24.
+hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const unsigned long long* hash, uint32_t n,
+                              unsigned long long* table, uint32_t table_size, uint32_t* rep, uint32_t* reps_list,
+                              uint32_t* n_reps, hipStream_t stream);
+// Judges the entries list[0 .. *n_list) of a frontier list (every entry 0 .. n - 1 if list is null) against the
+// alphabet: codes[e * alphabet + digit] = CODE_* of that extension of entry e, unknown[e] = 1 where the pair form
+// cannot judge the entry.  np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends
+// children that need two pairs to the literal list.
+hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
+                                 const uint32_t* n_list, int np, int max_pairs, uint8_t* codes, uint8_t* unknown,
+                                 hipStream_t stream);
+// The survivors of every entry of a list from the codes of the entry that stands for its state (rep null: its own):
+// appended to surv with their places in the next frontier; entries that cannot be judged go to unknown_out
+// (counted in n_unknown); handover != 0 treats every entry so (the hand-over path, for tests).
+hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uint32_t n, const uint32_t* rep,
+                               const uint8_t* codes, const uint8_t* unknown, int np, int handover, FrontSurvivor* surv,
+                               uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream);
 // Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 // class_cap: most classes of equal rows the class-state kernel may hold (1..64) before a prefix goes to the

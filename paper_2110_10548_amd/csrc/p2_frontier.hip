@@ -316,80 +316,6 @@ __device__ inline int classify_pairs(const uint32_t* st, const PatLds P, int op,
     return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
 }
 
-// The same on a one-pair state, every rule folded in one pass over the participating devices (threads of a
-// wavefront hold different instructions: no branch on the rule inside the loop).
-template <int KW, int MW>
-__device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, int R, const Words<KW>& all_rows,
-                                    const Words<MW>& all_cols, int n_goal) {
-    const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
-    uint32_t badx = 0;
-    bool changed = false, two_masks = false, over = false, all_goal = true;
-    int goal_part = 0;                      // participants that are at the goal before the step
-    GroupWalk wk;
-    wk.start();
-    Slot<KW, MW> first, acc;
-    Words<MW> second;                       // AllGather: a mask that differs from the first member's
-    bool have_second = false;
-    uint32_t eqx = 0, dmx = 0, drx = 0, smx = 0, subx = 0;
-    bool anyzero = false, third = false;
-    const int n_part = P.n_groups * P.g;
-    for (int j = 0; j < n_part; ++j) {
-        const Slot<KW, MW> cur = fload<KW, MW>(st, wk.dev);
-        goal_part += (fold_xor(cur.r, all_rows) | fold_xor(cur.m, all_cols)) == 0 ? 1 : 0;
-        if (wk.p == 0) {
-            first = cur; acc = cur;
-            eqx = 0; dmx = 0; drx = 0; smx = 0; subx = 0;
-            anyzero = fold_or(cur.r) == 0;
-            have_second = false; third = false;
-        } else {
-            eqx |= fold_xor(cur.r, first.r);
-            dmx |= fold_and(cur.m, acc.m);
-            drx |= fold_and(cur.r, acc.r);
-            const uint32_t dm = fold_xor(cur.m, first.m);
-            smx |= dm;
-            if (dm != 0u) {                                  // (only an AllGather looks at these)
-                if (!have_second) { second = cur.m; have_second = true; }
-                else third |= fold_xor(cur.m, second) != 0u;
-            }
-            subx |= fold_andn(cur.r, first.r) | fold_andn(cur.m, first.m);
-            anyzero |= fold_or(cur.r) == 0;
-#pragma unroll
-            for (int i = 0; i < KW; ++i) acc.r.w[i] |= cur.r.w[i];
-#pragma unroll
-            for (int i = 0; i < MW; ++i) acc.m.w[i] |= cur.m.w[i];
-        }
-        if (wk.next(P)) {
-            if (red) {
-                badx |= eqx | dmx;
-                changed |= fold_or(first.r) != 0;
-                if (op == OP_RS) {
-                    const int rows = popcount(first.r);
-                    badx |= (uint32_t)(div_small(rows, P.g) * P.g != rows);
-                }
-                // AllReduce leaves (same chunks, union) on every member; ReduceScatter and Reduce leave
-                // members with fewer chunks than the goal has
-                all_goal &= op == OP_AR && (fold_xor(first.r, all_rows) | fold_xor(acc.m, all_cols)) == 0;
-            } else if (op == OP_AG) {
-                badx |= drx | (uint32_t)anyzero;
-                two_masks |= smx != 0;                       // rows with different column sets: two pairs per member
-                over |= third;                               // ... or more than two
-                changed = true;
-                all_goal &= (fold_xor(acc.r, all_rows) | fold_xor(first.m, all_cols)) == 0;
-            } else {
-                badx |= subx | (uint32_t)((eqx | smx) == 0);
-                changed = true;
-                all_goal &= (fold_xor(first.r, all_rows) | fold_xor(first.m, all_cols)) == 0;
-            }
-            wk.next_group(P);
-        }
-    }
-    if (badx != 0 || !changed) return CODE_INVALID;
-    if (over) return CODE_PREFIX_LITERAL;           // three different masks on a device: never the goal
-    if (two_masks) return CODE_PREFIX2;
-    const bool rest_done = (n_goal - goal_part) == (R - n_part);     // devices left untouched
-    return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
-}
-
 // ---- classification, a wavefront per pattern ----------------------------------------------------------
 // Block = one prefix (its planes in LDS), wavefront = one pattern at a time, all rules of that pattern at
 // once.  A lane is (slot, quad): the 8 lanes of a slot read one device with one 128-bit access each, so a
@@ -409,9 +335,9 @@ __device__ inline int classify_step(const uint32_t* st, const PatLds P, int op, 
 // the pairs: an AllGather of members with different masks (how many masks?), a ReduceScatter of a split
 // group (does a block straddle the split?), a Broadcast among two-pair devices that passes the
 // necessary conditions checked here.
-// Survivors of kClsBatch prefixes are written together: one reservation of list positions and of the
-// children's places in the next frontier per batch, so that the few counters are not hammered.
-constexpr int kClsThreads = 512, kClsWaves = kClsThreads / 64, kClsBatch = 8;
+// The kernel writes a code per instruction of the alphabet for every entry it judges; the survivors are listed
+// afterwards (k_front_expand), for every entry of the list from the codes of the entry that stands for its state.
+constexpr int kClsThreads = 512, kClsWaves = kClsThreads / 64;
 
 __device__ inline uint4 q_or(uint4 a, uint4 b) { return make_uint4(a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w); }
 __device__ inline uint4 q_and(uint4 a, uint4 b) { return make_uint4(a.x & b.x, a.y & b.y, a.z & b.z, a.w & b.w); }
@@ -461,20 +387,439 @@ __device__ inline int sum_slot(int v) {
     return v;
 }
 
+// ---- pieces of the classification kernel ------------------------------------------------------------------
+// What a lane knows about its place in the wavefront and about the prefix whose planes lie in LDS.
+template <int KW, int MW, int NP>
+struct ClsLane {
+    const uint4* ldsq;             // NP planes of [R][WQ] quads
+    const uint8_t* flags;          // per device: kFlag* bits
+    int R, plane_q;
+    int lane, slot, qd;
+    bool is_row, is_mask, has_quad;
+    uint4 goal_quad;               // this lane's quad of a device at the goal
+};
+// what a run of a pattern's groups has shown (the same in every lane)
+struct ClsFound { uint32_t bits; int goal_part, two_part; };
+
+// Per device: is it empty, is it at the goal, does it hold two pairs.  The wavefront takes the devices
+// first + slot, first + stride + slot, ...; at_goal and with_two come back summed over the wavefront.
+template <int KW, int MW, int NP>
+__device__ inline void cls_flags(const ClsLane<KW, MW, NP>& c, uint8_t* flags, int first, int stride, int& at_goal, int& with_two) {
+    using L = FL<KW, MW>;
+    at_goal = 0; with_two = 0;
+    for (int d0 = first; d0 < c.R; d0 += stride) {
+        const int d = d0 + c.slot;
+        const bool act = d < c.R && c.has_quad;
+        const uint4 v = act ? c.ldsq[d * L::WQ + c.qd] : q_zero();
+        const uint4 v1 = (NP == 2 && act) ? c.ldsq[c.plane_q + d * L::WQ + c.qd] : q_zero();
+        const unsigned long long nz = __ballot(act && c.is_row && q_any(v));
+        const unsigned long long ng = __ballot(act && q_any(q_xor(v, c.goal_quad)));
+        const unsigned long long n2 = NP == 2 ? __ballot(act && c.is_row && q_any(v1)) : 0ull;
+        if (c.qd == 0 && d < c.R) {
+            const int sh = c.slot * 8;
+            const bool empty = ((nz >> sh) & 0xffull) == 0ull, two = ((n2 >> sh) & 0xffull) != 0ull;
+            const bool goal = ((ng >> sh) & 0xffull) == 0ull && !two;
+            flags[d] = (uint8_t)((empty ? kFlagEmpty : 0u) | (goal ? kFlagGoal : 0u) | (two ? kFlagTwo : 0u));
+            at_goal += goal ? 1 : 0;
+            with_two += two ? 1 : 0;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) { at_goal += __shfl_xor(at_goal, o, 64); with_two += __shfl_xor(with_two, o, 64); }
+}
+
+// The batches [first_batch, first_batch + n_batches) of a pattern's groups (8 slots side by side: a batch is
+// 8 groups, or fewer groups with several slots each), every rule at once.  Stops early once every rule of the
+// pattern has failed.
+template <int KW, int MW, int NP>
+__device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P, int first_batch, int n_batches) {
+    using L = FL<KW, MW>;
+    const uint4* const ldsq = c.ldsq;
+    const int plane_q = c.plane_q, slot = c.slot, qd = c.qd;
+    const bool is_row = c.is_row, is_mask = c.is_mask;
+    const uint4 goal_quad = c.goal_quad;
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    int spg = 1;                                         // slots that share a group
+    while (spg * 2 * ng <= 8) spg *= 2;
+    const int gpb = 8 / spg;                             // groups side by side
+    const int my_g = slot / spg, part = slot - my_g * spg;
+    const int trips = (g + spg - 1) / spg;
+    bool bad_red = false, bad_b = false, unal = false, bad_rs = false, bad_ag = false, changed = false, ag_uneq = false;
+    bool bad_bc1 = false, bc_fail = false, any_two = false;
+    bool ng_ar = false, ng_ag = false, ng_bc = false;    // some device is not at the goal afterwards
+    uint32_t fl_pat = 0;
+    int goal_part = 0, two_part = 0;
+    const int G_end = min(ng, (first_batch + n_batches) * gpb);
+    for (int G0 = first_batch * gpb; G0 < G_end; G0 += gpb) {
+        const int G = G0 + my_g;
+        const bool act = G < ng && c.has_quad;
+        int base = 0;
+        if (P.master) base = G * gs;
+        else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+        // row lanes: p = rows (both pairs), al = pair-0 rows of the members with two pairs
+        // mask lanes: p = plane A (pair 0), sB = plane B, al = every pair's mask
+        QAcc p, sB, al, i0, i1;
+        p.init(); sB.init(); al.init(); i0.init(); i1.init();
+        uint4 first0 = q_zero(), first1 = q_zero();
+        uint32_t fl_or = 0;
+        for (int it0 = 0; it0 < trips; it0 += 4) {       // four members in flight
+            uint4 a0[4], a1[4];
+            uint32_t ff[4];
+            bool on[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int t = (it0 + u) * spg + part;
+                on[u] = act && t < g;
+                const int d = base + t * s;
+                a0[u] = on[u] ? ldsq[d * L::WQ + qd] : q_zero();
+                a1[u] = (NP == 2 && on[u]) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+                ff[u] = on[u] ? (uint32_t)c.flags[d] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint4 v0 = a0[u];
+                const uint32_t f = ff[u];
+                fl_or |= f;
+                goal_part += (qd == 0 && (f & kFlagGoal)) ? 1 : 0;
+                if constexpr (NP == 2) {
+                    const uint4 v1 = a1[u];
+                    const bool two = (f & kFlagTwo) != 0u;
+                    two_part += (qd == 0 && two) ? 1 : 0;
+                    i0.add_if(v0, on[u]); i1.add_if(v1, on[u]);
+                    if (is_row) {
+                        p.add_if(q_or(v0, v1), on[u]);
+                        al.add_if(two ? v0 : q_zero(), two);
+                    } else {
+                        p.add_if(v0, on[u]);
+                        sB.add_if(two ? v1 : v0, on[u]);
+                        al.add_if(v0, on[u]);
+                        al.add_if(two ? v1 : q_zero(), two);
+                    }
+                    if (it0 + u == 0 && part == 0) { first0 = v0; first1 = v1; }
+                } else {
+                    p.add_if(v0, on[u]);
+                    if (it0 + u == 0 && part == 0) first0 = v0;
+                }
+            }
+        }
+        for (int m = 8; m < 8 * spg; m <<= 1) {          // the slots of one group put their members together
+            p.merge_xor(m);
+            if constexpr (NP == 2) { sB.merge_xor(m); al.merge_xor(m); i0.merge_xor(m); i1.merge_xor(m); }
+            fl_or |= (uint32_t)__shfl_xor((int)fl_or, m, 64);
+        }
+        if (spg > 1) {
+            first0 = q_shfl(first0, (slot - part) * 8 + qd);
+            if constexpr (NP == 2) first1 = q_shfl(first1, (slot - part) * 8 + qd);
+        }
+        fl_pat |= act ? fl_or : 0u;
+        const int rows = sum_slot((act && is_row) ? q_popc(p.o) : 0);
+        const int sh = slot * 8;
+        if constexpr (NP == 1) {
+            const unsigned long long dif_slots = __ballot(act && p.differ());
+            if (act) {
+                const bool twice = q_any(p.t), differ = p.differ();
+                if (is_row) { bad_red |= differ; bad_ag |= twice; changed |= q_any(p.o); }
+                else { bad_red |= twice; ag_uneq |= differ; }
+                bad_rs |= div_small(rows, g) * g != rows;
+                bad_ag |= (fl_or & kFlagEmpty) != 0u;
+                bad_bc1 |= q_any(q_xor(p.o, first0)) || ((dif_slots >> sh) & 0xffull) == 0ull;
+                ng_ar |= q_any(q_xor(p.o, goal_quad));
+                ng_ag |= q_any(q_xor(is_row ? p.o : first0, goal_quad));
+                ng_bc |= q_any(q_xor(first0, goal_quad));
+            }
+        } else {
+            const bool g_two = (fl_or & kFlagTwo) != 0u;
+            const unsigned long long unal_slots = __ballot(act && is_row && g_two && al.differ());
+            const unsigned long long split_slots = __ballot(act && is_mask && g_two && q_any(q_xor(p.o, sB.o)));
+            const unsigned long long dif_slots = __ballot(act && (i0.differ() || i1.differ()));
+            if (act) {
+                const bool unal_g = ((unal_slots >> sh) & 0xffull) != 0ull, split_g = ((split_slots >> sh) & 0xffull) != 0ull;
+                const bool differs_g = ((dif_slots >> sh) & 0xffull) != 0ull;
+                if (is_row) { bad_red |= p.differ(); bad_ag |= q_any(p.t); changed |= q_any(p.o); }
+                else { bad_red |= q_any(p.t); bad_b |= !unal_g && q_any(sB.t); ag_uneq |= al.differ(); }
+                unal |= unal_g;
+                any_two |= split_g;
+                bad_rs |= div_small(rows, g) * g != rows;
+                bad_ag |= (fl_or & kFlagEmpty) != 0u;
+                // Broadcast, exact where no member of the pattern holds two pairs ...
+                bad_bc1 |= q_any(q_xor(p.o, first0)) || !differs_g;
+                // ... and otherwise what must hold at least: rows and masks inside the root's, someone differs
+                if (is_row) bc_fail |= q_any(q_xor(p.o, q_or(first0, first1)));
+                else bc_fail |= q_any(q_andn(al.o, q_or(first0, first1)));
+                bc_fail |= !differs_g;
+                ng_ar |= q_any(q_xor(p.o, goal_quad)) || split_g;
+                ng_ag |= q_any(q_xor(is_row ? p.o : al.o, goal_quad));
+                ng_bc |= q_any(q_xor(first0, goal_quad)) || q_any(first1);
+            }
+        }
+        // every rule of the pattern has failed already: the other groups cannot change that
+        if (__any(bad_red) && __any(bad_ag) && __any(bad_bc1 && (NP == 1 || bc_fail))) break;
+    }
+    ClsFound f;
+    uint32_t bits = 0;
+    bits |= __any(bad_red) ? kPfBadRed : 0u; bits |= __any(bad_b) ? kPfBadB : 0u; bits |= __any(unal) ? kPfUnal : 0u;
+    bits |= __any(bad_rs) ? kPfBadRs : 0u; bits |= __any(bad_ag) ? kPfBadAg : 0u; bits |= __any(changed) ? kPfChanged : 0u;
+    bits |= __any(ag_uneq) ? kPfAgUneq : 0u; bits |= __any(bad_bc1) ? kPfBadBc1 : 0u; bits |= __any(bc_fail) ? kPfBcFail : 0u;
+    bits |= __any(any_two) ? kPfAnyTwo : 0u; bits |= __any(ng_ar) ? kPfNgAr : 0u; bits |= __any(ng_ag) ? kPfNgAg : 0u;
+    bits |= __any(ng_bc) ? kPfNgBc : 0u; bits |= __any((fl_pat & kFlagTwo) != 0u) ? kPfPatTwo : 0u;
+    for (int o = 32; o > 0; o >>= 1) { goal_part += __shfl_xor(goal_part, o, 64); two_part += __shfl_xor(two_part, o, 64); }
+    f.bits = bits; f.goal_part = goal_part; f.two_part = two_part;
+    return f;
+}
+
+// A valid AllGather of members with different masks: does some device hold more than two masks afterwards?
+// Second walk, the wavefront together: per group the first pair's mask, the first mask that differs from it,
+// and whether a third one shows up (the child then needs the literal state).
+template <int KW, int MW, int NP>
+__device__ inline bool cls_many_masks(const ClsLane<KW, MW, NP>& c, const PatLds P) {
+    using L = FL<KW, MW>;
+    const uint4* const ldsq = c.ldsq;
+    const int plane_q = c.plane_q, slot = c.slot, qd = c.qd;
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    int spg = 1;
+    while (spg * 2 * ng <= 8) spg *= 2;
+    const int gpb = 8 / spg;
+    const int my_g = slot / spg, part = slot - my_g * spg;
+    const int trips = (g + spg - 1) / spg;
+    bool many = false;
+    for (int G0 = 0; G0 < ng; G0 += gpb) {
+        const int G = G0 + my_g;
+        const bool act = G < ng && c.is_mask;
+        int base = 0;
+        if (P.master) base = G * gs;
+        else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+        const uint4 d0 = act ? ldsq[base * L::WQ + qd] : q_zero();
+        uint4 d1 = q_zero();
+        bool have1 = false;
+        const int sh = slot * 8;
+        for (int it = 0; it < trips; ++it) {
+            const int t = it * spg + part;
+            const bool on = act && t < g;
+            const int d = base + t * s;
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) {
+                const uint4 m = on ? ldsq[pl * plane_q + d * L::WQ + qd] : q_zero();
+                // (an empty second pair has an empty mask; the first pair of a member is never empty here)
+                const bool there = on && (pl == 0 || (c.flags[d] & kFlagTwo) != 0u);
+                const unsigned long long ne0 = __ballot(there && q_any(q_xor(m, d0)));
+                const unsigned long long ne1 = __ballot(there && q_any(q_xor(m, d1)));
+                if (there && ((ne0 >> sh) & 0xffull) != 0ull) {
+                    if (!have1) { d1 = m; have1 = true; }
+                    else if (((ne1 >> sh) & 0xffull) != 0ull) many = true;
+                }
+            }
+        }
+        for (int m = 8; m < 8 * spg; m <<= 1) {      // the slots of one group compare what they found
+            const uint4 o1 = q_shfl_xor(d1, m);
+            const bool o_have = __shfl_xor((int)have1, m, 64) != 0;
+            const unsigned long long ne = __ballot(act && have1 && o_have && q_any(q_xor(d1, o1)));
+            if (act && o_have) {
+                if (!have1) { d1 = o1; have1 = true; }
+                else if (((ne >> sh) & 0xffull) != 0ull) many = true;
+            }
+        }
+    }
+    return __any(many) != 0;
+}
+
+// One lane: the codes of a pattern's instructions from what its groups have shown.
+template <int KW, int MW, int NP>
+__device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, int pid, uint32_t pf, int goal_part, int two_part,
+                                 int n_goal, int n_two, bool MANY_MASKS, const int (&ops_r)[5], int n_ops, int max_pairs,
+                                 const Words<KW>& all_rows, const Words<MW>& all_cols, uint8_t* __restrict__ codes,
+                                 uint8_t* __restrict__ unknown) {
+    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(c.ldsq);
+    const int R = c.R;
+    const bool BAD_RED = pf & kPfBadRed, BAD_B = pf & kPfBadB, UNAL = pf & kPfUnal, BAD_RS = pf & kPfBadRs;
+    const bool BAD_AG = pf & kPfBadAg, CHANGED = pf & kPfChanged, AG_UNEQ = pf & kPfAgUneq;
+    const bool BAD_BC1 = pf & kPfBadBc1, BC_FAIL = pf & kPfBcFail, ANY_TWO = pf & kPfAnyTwo;
+    const bool NG_AR = pf & kPfNgAr, NG_AG = pf & kPfNgAg, NG_BC = pf & kPfNgBc, PAT_TWO = pf & kPfPatTwo;
+    const bool rest_done = (n_goal - goal_part) == (R - P.n_groups * P.g);      // the devices left untouched are at the goal
+    const bool rest_two = n_two - two_part > 0;                                 // ... or one of them holds two pairs
+#pragma unroll
+    for (int oi = 0; oi < 5; ++oi) {
+        const int op = ops_r[oi];
+        if (op < 0) continue;
+        int code;
+        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+            if (BAD_RED || !CHANGED || (op == OP_RS && BAD_RS)) code = CODE_INVALID;
+            else if (UNAL) code = CODE_UNKNOWN;
+            else if (BAD_B) code = CODE_INVALID;
+            else if (op == OP_RS) {
+                if (ANY_TWO) code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
+                else code = rest_two ? CODE_PREFIX2 : CODE_PREFIX;
+            } else if (ANY_TWO || rest_two) code = CODE_PREFIX2;
+            else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
+        } else if (op == OP_AG) {
+            if (BAD_AG) code = CODE_INVALID;
+            else if (AG_UNEQ) code = MANY_MASKS ? CODE_PREFIX_LITERAL : CODE_PREFIX2;   // members with different masks
+            else if (rest_two) code = CODE_PREFIX2;
+            else code = (!NG_AG && rest_done) ? CODE_GOAL : CODE_PREFIX;
+        } else {
+            if (!PAT_TWO) code = BAD_BC1 ? CODE_INVALID : rest_two ? CODE_PREFIX2 : (!NG_BC && rest_done) ? CODE_GOAL : CODE_PREFIX;
+            else if (BC_FAIL) code = CODE_INVALID;
+            else code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
+        }
+        if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
+        if (code == CODE_UNKNOWN) *unknown = 1;          // (after the block's barriers that follow the clearing)
+        codes[pid * n_ops + oi] = (uint8_t)code;
+    }
+}
+
+// ---- survivors of every entry from the codes of its state ------------------------------------------------
+// A wavefront takes kExpBatch entries at a time: counts their survivors by kind, reserves list positions and the
+// children's places in the next frontier once (so that the few counters are not hammered), writes.
+constexpr int kExpThreads = 256, kExpBatch = 8;
+template <int NP>
+__global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __restrict__ qp, const FrontEntry* __restrict__ entries,
+                                                             uint32_t n, const uint32_t* __restrict__ rep,
+                                                             const uint8_t* __restrict__ codes, const uint8_t* __restrict__ unknown,
+                                                             int handover, FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
+                                                             FrontEntry* __restrict__ unknown_out, FrontCounters* __restrict__ ctr) {
+    const DevQuery& q = *qp;
+    const int I = q.alphabet;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = (blockIdx.x * kExpThreads + threadIdx.x) >> 6, n_waves = gridDim.x * (kExpThreads / 64);
+    unsigned long long judged = 0;                       // entries with survivors written here (lane 0 counts)
+    for (uint32_t p0 = wave * kExpBatch; p0 < n; p0 += n_waves * kExpBatch) {
+        const int pending = (int)min((uint32_t)kExpBatch, n - p0);
+        uint32_t row_of[kExpBatch];
+        bool unk[kExpBatch];
+#pragma unroll
+        for (int b = 0; b < kExpBatch; ++b) {
+            const uint32_t p = p0 + (uint32_t)min(b, pending - 1);
+            row_of[b] = rep ? rep[p] : p;
+            unk[b] = handover != 0 || unknown[row_of[b]] != 0;
+        }
+        uint32_t c_surv = 0, c_goal = 0, c_p1 = 0, c_p2 = 0;
+#pragma unroll
+        for (int b = 0; b < kExpBatch; ++b) {
+            if (b >= pending || unk[b]) continue;
+            for (int a = lane; a < I; a += 64) {
+                const int code = codes[(size_t)row_of[b] * I + a];
+                c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
+            }
+        }
+        uint32_t x_surv = c_surv, x_goal = c_goal, x_p1 = c_p1, x_p2 = c_p2;          // inclusive sums over the lanes
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t a0 = __shfl_up(x_surv, o, 64), a1 = __shfl_up(x_goal, o, 64), a2 = __shfl_up(x_p1, o, 64), a3 = __shfl_up(x_p2, o, 64);
+            if (lane >= o) { x_surv += a0; x_goal += a1; x_p1 += a2; x_p2 += a3; }
+        }
+        const uint32_t t_surv = __shfl(x_surv, 63, 64), t_goal = __shfl(x_goal, 63, 64), t_p1 = __shfl(x_p1, 63, 64), t_p2 = __shfl(x_p2, 63, 64);
+        unsigned long long b0 = 0, b1 = 0;
+        if (lane == 0) {
+            if (t_surv) b0 = atomicAdd(&ctr->surv_goal, (unsigned long long)t_surv | ((unsigned long long)t_goal << 32));
+            if (t_p1 | t_p2) b1 = atomicAdd(&ctr->pref_pref2, (unsigned long long)t_p1 | ((unsigned long long)t_p2 << 32));
+#pragma unroll
+            for (int b = 0; b < kExpBatch; ++b) {
+                if (b >= pending) continue;
+                if (unk[b]) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[p0 + b];
+                else ++judged;
+            }
+        }
+        b0 = __shfl(b0, 0, 64); b1 = __shfl(b1, 0, 64);
+        uint32_t at_surv = (uint32_t)b0 + x_surv - c_surv, at_goal = (uint32_t)(b0 >> 32) + x_goal - c_goal;
+        uint32_t at_p1 = (uint32_t)b1 + x_p1 - c_p1, at_p2 = (uint32_t)(b1 >> 32) + x_p2 - c_p2;
+#pragma unroll
+        for (int b = 0; b < kExpBatch; ++b) {
+            if (b >= pending || unk[b]) continue;
+            for (int a = lane; a < I; a += 64) {
+                const int code = codes[(size_t)row_of[b] * I + a];
+                if (code == CODE_INVALID) continue;
+                FrontSurvivor sv;
+                sv.entry = p0 + b; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
+                sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
+                if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
+                if (at_surv < surv_cap) surv[at_surv] = sv;
+                ++at_surv;
+            }
+        }
+    }
+    if (lane == 0 && judged) {
+        atomicAdd(&ctr->steps, judged * (unsigned long long)I);
+        atomicAdd(&ctr->members, judged * (unsigned long long)q.reg_sum_part);
+    }
+}
+
+// ---- entries with equal states ---------------------------------------------------------------------------
+// 64 bits of a state: a sum over its 16-byte quads, so that the lanes that stream a state can each hash their own
+// quads.  (It only proposes which entries to compare.)
+__device__ inline unsigned long long hash_quad(uint4 v, uint32_t idx) {
+    uint32_t a = v.x * 0x9e3779b1u + v.y * 0x85ebca77u + v.z * 0xc2b2ae3du + v.w * 0x27d4eb2fu + idx * 0x165667b1u;
+    uint32_t b = v.x * 0x7feb352du + v.y * 0x846ca68bu + v.z * 0x9e3779b9u + v.w * 0x85ebca6bu + idx * 0xc2b2ae35u;
+    a ^= a >> 15; a *= 0x2c1b3c6du; a ^= a >> 12; a *= 0x297a2d39u; a ^= a >> 15;
+    b ^= b >> 16; b *= 0x7feb352du; b ^= b >> 15; b *= 0x846ca68bu; b ^= b >> 16;
+    return ((unsigned long long)a << 32) | b;
+}
+constexpr unsigned long long kTableEmpty = ~0ull;
+// Open addressing on the upper 40 bits of the hash; a table word is (those bits << 24) | entry.  The first entry
+// to claim a word stands for the hash; the others take it as their candidate.
+__global__ __launch_bounds__(256) void k_front_dedup(const unsigned long long* __restrict__ hash, uint32_t n,
+                                                     unsigned long long* __restrict__ table, uint32_t mask, uint32_t* __restrict__ rep,
+                                                     uint32_t* __restrict__ reps_list, uint32_t* __restrict__ n_reps) {
+    const uint32_t p = blockIdx.x * 256u + threadIdx.x;
+    if (p >= n) return;
+    const unsigned long long h = hash[p];
+    const unsigned long long key = h >> 24;
+    uint32_t at = (uint32_t)((h * 0x9e3779b97f4a7c15ull) >> 32) & mask;
+    for (uint32_t probe = 0; probe <= mask; ++probe) {        // (the table has room for every entry: an empty word turns up)
+        const unsigned long long old = atomicCAS(&table[at], kTableEmpty, (key << 24) | p);
+        if (old == kTableEmpty) { rep[p] = p; reps_list[atomicAdd(n_reps, 1u)] = p; return; }
+        if ((old >> 24) == key) { rep[p] = (uint32_t)(old & 0xffffffull); return; }
+        at = (at + 1u) & mask;
+    }
+    rep[p] = p; reps_list[atomicAdd(n_reps, 1u)] = p;         // never reached with a table of 2 n words
+}
+// A wavefront per entry that took a candidate: the two states word by word; an entry that differs stands for itself.
+__global__ __launch_bounds__(256) void k_front_verify(const uint4* __restrict__ states, uint32_t quads, uint32_t n,
+                                                      uint32_t* __restrict__ rep, uint32_t* __restrict__ reps_list,
+                                                      uint32_t* __restrict__ n_reps) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = gridDim.x * 4u;
+    for (uint32_t p = wave; p < n; p += n_waves) {
+        const uint32_t r = rep[p];
+        if (r == p) continue;
+        const uint4* a = states + (size_t)p * quads;
+        const uint4* b = states + (size_t)r * quads;
+        bool differ = false;
+        for (uint32_t i0 = (uint32_t)lane; i0 < quads; i0 += 256u) {
+            uint4 x[4], y[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t i = i0 + 64u * u;
+                x[u] = i < quads ? a[i] : q_zero(); y[u] = i < quads ? b[i] : q_zero();
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) differ |= q_any(q_xor(x[u], y[u]));
+        }
+        if (__any(differ) && lane == 0) { rep[p] = p; reps_list[atomicAdd(n_reps, 1u)] = p; }
+    }
+}
+
+// this lane's quad of a device at the goal: every row, every column of the reduction group
+template <int KW, int MW>
+__device__ inline uint4 goal_quad_of(const Words<KW>& all_rows, const Words<MW>& all_cols, int qd, bool is_row, bool is_mask) {
+    using L = FL<KW, MW>;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int i = 0; i < KW; ++i) if (is_row && i == qd * 4 + j) w[j] = all_rows.w[i];
+#pragma unroll
+        for (int i = 0; i < MW; ++i) if (is_mask && i == (qd - L::QK) * 4 + j) w[j] = all_cols.w[i];
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ---- a block per prefix ---------------------------------------------------------------------------------
 template <int KW, int MW, int NP>
 // (second bound: wavefronts per SIMD, so that two blocks of one-plane states share a compute unit)
 __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify(const DevQuery* __restrict__ qp,
-                                                                const FrontEntry* __restrict__ entries,
                                                                 const uint32_t* __restrict__ states, uint32_t n_entries,
-                                                                int max_pairs, int handover, FrontSurvivor* __restrict__ surv,
-                                                                uint32_t surv_cap, FrontEntry* __restrict__ unknown_out,
-                                                                FrontCounters* __restrict__ ctr) {
+                                                                const uint32_t* __restrict__ list, const uint32_t* __restrict__ n_list,
+                                                                int max_pairs, uint8_t* __restrict__ codes,
+                                                                uint8_t* __restrict__ unknown) {
     extern __shared__ uint4 ldsq[];                      // NP planes of [R][WQ] quads, then R flag bytes
     __shared__ PatLds spat[kMaxPatterns];
-    __shared__ uint16_t sdig[kMaxPatterns * 5];
-    __shared__ uint8_t s_code[kClsBatch][kMaxPatterns * 5];
-    __shared__ uint32_t s_entry[kClsBatch];
-    __shared__ int s_unknown[kClsBatch];
     __shared__ int s_goal, s_two, s_next, s_n_items;
     __shared__ uint32_t s_pflags[kMaxPatterns];
     __shared__ int s_pgoal[kMaxPatterns], s_ptwo[kMaxPatterns];
@@ -484,22 +829,19 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     const int R = q.R, I = q.alphabet, n_ops = q.n_ops, n_pat = q.n_patterns;
     const int plane_q = R * L::WQ;                       // quads per plane
     uint8_t* const flags = reinterpret_cast<uint8_t*>(ldsq + (size_t)NP * plane_q);
-    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(ldsq);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int slot = lane >> 3, qd = lane & 7;
-    const bool is_row = qd < L::QK, is_mask = qd >= L::QK && qd < L::WQ, has_quad = qd < L::WQ;
     for (int i = tid; i < n_pat; i += kClsThreads) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
     }
-    for (int i = tid; i < I; i += kClsThreads) sdig[i] = q.instr_of_digit[i];
+    __syncthreads();
     if (tid == 0) {
         // work items: a pattern's batches of groups in up to kClsChunks runs; the long items first
         int n = 0;
         for (int pass = 0; pass < 2; ++pass)
             for (int i = 0; i < n_pat; ++i) {
-                const int ng = q.pat[i].n_groups;
+                const int ng = spat[i].n_groups;
                 int spg = 1;
                 while (spg * 2 * ng <= 8) spg *= 2;
                 const int batches = (ng + 8 / spg - 1) / (8 / spg);
@@ -514,25 +856,17 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     }
     const Words<KW> all_rows = full_mask<KW>(q.k);
     const Words<MW> all_cols = full_mask<MW>(R);
-    // this lane's quad of a device at the goal: every row, every column of the reduction group
-    uint4 goal_quad;
-    {
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int i = 0; i < KW; ++i) if (is_row && i == qd * 4 + j) w[j] = all_rows.w[i];
-#pragma unroll
-            for (int i = 0; i < MW; ++i) if (is_mask && i == (qd - L::QK) * 4 + j) w[j] = all_cols.w[i];
-        }
-        goal_quad = make_uint4(w[0], w[1], w[2], w[3]);
-    }
+    ClsLane<KW, MW, NP> c;
+    c.ldsq = ldsq; c.flags = flags; c.R = R; c.plane_q = plane_q;
+    c.lane = lane; c.slot = lane >> 3; c.qd = lane & 7;
+    c.is_row = c.qd < L::QK; c.is_mask = c.qd >= L::QK && c.qd < L::WQ; c.has_quad = c.qd < L::WQ;
+    c.goal_quad = goal_quad_of<KW, MW>(all_rows, all_cols, c.qd, c.is_row, c.is_mask);
     int ops_r[5];
 #pragma unroll
     for (int i = 0; i < 5; ++i) ops_r[i] = i < n_ops ? q.ops[i] : -1;
-    unsigned long long judged = 0;                       // prefixes this block judged itself (thread 0 counts)
-    int pending = 0;
-    for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
+    const uint32_t n_work = list ? *n_list : n_entries;
+    for (uint32_t at = blockIdx.x; at < n_work; at += gridDim.x) {
+        const uint32_t e = list ? list[at] : at;
         __syncthreads();
         const uint4* src = reinterpret_cast<const uint4*>(states) + (size_t)e * NP * plane_q;
         // (all of a thread's loads are issued before the first store: one trip to HBM, not one per quad)
@@ -543,29 +877,12 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
 #pragma unroll
             for (int u = 0; u < 8; ++u) { const int i = i0 + u * kClsThreads; if (i < NP * plane_q) ldsq[i] = tmp[u]; }
         }
-        if (tid == 0) { s_goal = 0; s_two = 0; s_next = 0; s_entry[pending] = e; s_unknown[pending] = (NP == 2 && handover) ? 1 : 0; }
+        if (tid == 0) { s_goal = 0; s_two = 0; s_next = 0; unknown[e] = 0; }
         for (int i = tid; i < n_pat; i += kClsThreads) { s_pflags[i] = 0u; s_pgoal[i] = 0; s_ptwo[i] = 0; }
         __syncthreads();
-        // ---- per device: is it empty, is it at the goal, does it hold two pairs
         {
-            int at_goal = 0, with_two = 0;
-            for (int d0 = wave * 8; d0 < R; d0 += kClsWaves * 8) {
-                const int d = d0 + slot;
-                const bool act = d < R && has_quad;
-                const uint4 v = act ? ldsq[d * L::WQ + qd] : q_zero();
-                const uint4 v1 = (NP == 2 && act) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
-                const unsigned long long nz = __ballot(act && is_row && q_any(v));
-                const unsigned long long ng = __ballot(act && q_any(q_xor(v, goal_quad)));
-                const unsigned long long n2 = NP == 2 ? __ballot(act && is_row && q_any(v1)) : 0ull;
-                if (qd == 0 && d < R) {
-                    const bool empty = ((nz >> (slot * 8)) & 0xffull) == 0ull, two = ((n2 >> (slot * 8)) & 0xffull) != 0ull;
-                    const bool goal = ((ng >> (slot * 8)) & 0xffull) == 0ull && !two;
-                    flags[d] = (uint8_t)((empty ? kFlagEmpty : 0u) | (goal ? kFlagGoal : 0u) | (two ? kFlagTwo : 0u));
-                    at_goal += goal ? 1 : 0;
-                    with_two += two ? 1 : 0;
-                }
-            }
-            for (int o = 32; o > 0; o >>= 1) { at_goal += __shfl_xor(at_goal, o, 64); with_two += __shfl_xor(with_two, o, 64); }
+            int at_goal, with_two;
+            cls_flags<KW, MW, NP>(c, flags, wave * 8, kClsWaves * 8, at_goal, with_two);
             if (lane == 0 && at_goal) atomicAdd(&s_goal, at_goal);
             if (lane == 0 && with_two) atomicAdd(&s_two, with_two);
         }
@@ -582,285 +899,27 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             if (item >= n_items) break;
             const ClsItem W = s_items[item];
             const int pid = W.pid;
-            const PatLds P = spat[pid];
-            const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
-            int spg = 1;                                         // slots that share a group
-            while (spg * 2 * ng <= 8) spg *= 2;
-            const int gpb = 8 / spg;                             // groups side by side
-            const int my_g = slot / spg, part = slot - my_g * spg;
-            const int trips = (g + spg - 1) / spg;
             {
                 const uint32_t pf = s_pflags[pid];
                 if ((pf & kPfBadRed) && (pf & kPfBadAg) && (pf & kPfBadBc1) && (NP == 1 || (pf & kPfBcFail))) continue;
             }
-            bool bad_red = false, bad_b = false, unal = false, bad_rs = false, bad_ag = false, changed = false, ag_uneq = false;
-            bool bad_bc1 = false, bc_fail = false, any_two = false;
-            bool ng_ar = false, ng_ag = false, ng_bc = false;    // some device is not at the goal afterwards
-            uint32_t fl_pat = 0;
-            int goal_part = 0, two_part = 0;
-            const int G_end = min(ng, (W.first_batch + W.n_batches) * gpb);
-            for (int G0 = W.first_batch * gpb; G0 < G_end; G0 += gpb) {
-                const int G = G0 + my_g;
-                const bool act = G < ng && has_quad;
-                int base = 0;
-                if (P.master) base = G * gs;
-                else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
-                // row lanes: p = rows (both pairs), al = pair-0 rows of the members with two pairs
-                // mask lanes: p = plane A (pair 0), sB = plane B, al = every pair's mask
-                QAcc p, sB, al, i0, i1;
-                p.init(); sB.init(); al.init(); i0.init(); i1.init();
-                uint4 first0 = q_zero(), first1 = q_zero();
-                uint32_t fl_or = 0;
-                for (int it0 = 0; it0 < trips; it0 += 4) {       // four members in flight
-                    uint4 a0[4], a1[4];
-                    uint32_t ff[4];
-                    bool on[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int t = (it0 + u) * spg + part;
-                        on[u] = act && t < g;
-                        const int d = base + t * s;
-                        a0[u] = on[u] ? ldsq[d * L::WQ + qd] : q_zero();
-                        a1[u] = (NP == 2 && on[u]) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
-                        ff[u] = on[u] ? (uint32_t)flags[d] : 0u;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const uint4 v0 = a0[u];
-                        const uint32_t f = ff[u];
-                        fl_or |= f;
-                        goal_part += (qd == 0 && (f & kFlagGoal)) ? 1 : 0;
-                        if constexpr (NP == 2) {
-                            const uint4 v1 = a1[u];
-                            const bool two = (f & kFlagTwo) != 0u;
-                            two_part += (qd == 0 && two) ? 1 : 0;
-                            i0.add_if(v0, on[u]); i1.add_if(v1, on[u]);
-                            if (is_row) {
-                                p.add_if(q_or(v0, v1), on[u]);
-                                al.add_if(two ? v0 : q_zero(), two);
-                            } else {
-                                p.add_if(v0, on[u]);
-                                sB.add_if(two ? v1 : v0, on[u]);
-                                al.add_if(v0, on[u]);
-                                al.add_if(two ? v1 : q_zero(), two);
-                            }
-                            if (it0 + u == 0 && part == 0) { first0 = v0; first1 = v1; }
-                        } else {
-                            p.add_if(v0, on[u]);
-                            if (it0 + u == 0 && part == 0) first0 = v0;
-                        }
-                    }
-                }
-                for (int m = 8; m < 8 * spg; m <<= 1) {          // the slots of one group put their members together
-                    p.merge_xor(m);
-                    if constexpr (NP == 2) { sB.merge_xor(m); al.merge_xor(m); i0.merge_xor(m); i1.merge_xor(m); }
-                    fl_or |= (uint32_t)__shfl_xor((int)fl_or, m, 64);
-                }
-                if (spg > 1) {
-                    first0 = q_shfl(first0, (slot - part) * 8 + qd);
-                    if constexpr (NP == 2) first1 = q_shfl(first1, (slot - part) * 8 + qd);
-                }
-                fl_pat |= act ? fl_or : 0u;
-                const int rows = sum_slot((act && is_row) ? q_popc(p.o) : 0);
-                const int sh = slot * 8;
-                if constexpr (NP == 1) {
-                    const unsigned long long dif_slots = __ballot(act && p.differ());
-                    if (act) {
-                        const bool twice = q_any(p.t), differ = p.differ();
-                        if (is_row) { bad_red |= differ; bad_ag |= twice; changed |= q_any(p.o); }
-                        else { bad_red |= twice; ag_uneq |= differ; }
-                        bad_rs |= div_small(rows, g) * g != rows;
-                        bad_ag |= (fl_or & kFlagEmpty) != 0u;
-                        bad_bc1 |= q_any(q_xor(p.o, first0)) || ((dif_slots >> sh) & 0xffull) == 0ull;
-                        ng_ar |= q_any(q_xor(p.o, goal_quad));
-                        ng_ag |= q_any(q_xor(is_row ? p.o : first0, goal_quad));
-                        ng_bc |= q_any(q_xor(first0, goal_quad));
-                    }
-                } else {
-                    const bool g_two = (fl_or & kFlagTwo) != 0u;
-                    const unsigned long long unal_slots = __ballot(act && is_row && g_two && al.differ());
-                    const unsigned long long split_slots = __ballot(act && is_mask && g_two && q_any(q_xor(p.o, sB.o)));
-                    const unsigned long long dif_slots = __ballot(act && (i0.differ() || i1.differ()));
-                    if (act) {
-                        const bool unal_g = ((unal_slots >> sh) & 0xffull) != 0ull, split_g = ((split_slots >> sh) & 0xffull) != 0ull;
-                        const bool differs_g = ((dif_slots >> sh) & 0xffull) != 0ull;
-                        if (is_row) { bad_red |= p.differ(); bad_ag |= q_any(p.t); changed |= q_any(p.o); }
-                        else { bad_red |= q_any(p.t); bad_b |= !unal_g && q_any(sB.t); ag_uneq |= al.differ(); }
-                        unal |= unal_g;
-                        any_two |= split_g;
-                        bad_rs |= div_small(rows, g) * g != rows;
-                        bad_ag |= (fl_or & kFlagEmpty) != 0u;
-                        // Broadcast, exact where no member of the pattern holds two pairs ...
-                        bad_bc1 |= q_any(q_xor(p.o, first0)) || !differs_g;
-                        // ... and otherwise what must hold at least: rows and masks inside the root's, someone differs
-                        if (is_row) bc_fail |= q_any(q_xor(p.o, q_or(first0, first1)));
-                        else bc_fail |= q_any(q_andn(al.o, q_or(first0, first1)));
-                        bc_fail |= !differs_g;
-                        ng_ar |= q_any(q_xor(p.o, goal_quad)) || split_g;
-                        ng_ag |= q_any(q_xor(is_row ? p.o : al.o, goal_quad));
-                        ng_bc |= q_any(q_xor(first0, goal_quad)) || q_any(first1);
-                    }
-                }
-                // every rule of the pattern has failed already: the other groups cannot change that
-                if (__any(bad_red) && __any(bad_ag) && __any(bad_bc1 && (NP == 1 || bc_fail))) break;
-            }
-            uint32_t bits = 0;
-            bits |= __any(bad_red) ? kPfBadRed : 0u; bits |= __any(bad_b) ? kPfBadB : 0u; bits |= __any(unal) ? kPfUnal : 0u;
-            bits |= __any(bad_rs) ? kPfBadRs : 0u; bits |= __any(bad_ag) ? kPfBadAg : 0u; bits |= __any(changed) ? kPfChanged : 0u;
-            bits |= __any(ag_uneq) ? kPfAgUneq : 0u; bits |= __any(bad_bc1) ? kPfBadBc1 : 0u; bits |= __any(bc_fail) ? kPfBcFail : 0u;
-            bits |= __any(any_two) ? kPfAnyTwo : 0u; bits |= __any(ng_ar) ? kPfNgAr : 0u; bits |= __any(ng_ag) ? kPfNgAg : 0u;
-            bits |= __any(ng_bc) ? kPfNgBc : 0u; bits |= __any((fl_pat & kFlagTwo) != 0u) ? kPfPatTwo : 0u;
-            for (int o = 32; o > 0; o >>= 1) { goal_part += __shfl_xor(goal_part, o, 64); two_part += __shfl_xor(two_part, o, 64); }
+            const ClsFound f = cls_walk<KW, MW, NP>(c, spat[pid], W.first_batch, W.n_batches);
             if (lane == 0) {
-                if (bits) atomicOr(&s_pflags[pid], bits);
-                if (goal_part) atomicAdd(&s_pgoal[pid], goal_part);
-                if (two_part) atomicAdd(&s_ptwo[pid], two_part);
+                if (f.bits) atomicOr(&s_pflags[pid], f.bits);
+                if (f.goal_part) atomicAdd(&s_pgoal[pid], f.goal_part);
+                if (f.two_part) atomicAdd(&s_ptwo[pid], f.two_part);
             }
         }
         __syncthreads();
         // ---- stage B: a pattern's flag word gives the codes of its instructions
         for (int pid = wave; pid < n_pat; pid += kClsWaves) {
             const PatLds P = spat[pid];
-            const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
-            int spg = 1;
-            while (spg * 2 * ng <= 8) spg *= 2;
-            const int gpb = 8 / spg;
-            const int my_g = slot / spg, part = slot - my_g * spg;
-            const int trips = (g + spg - 1) / spg;
             const uint32_t pf = s_pflags[pid];
-            const bool BAD_RED = pf & kPfBadRed, BAD_B = pf & kPfBadB, UNAL = pf & kPfUnal, BAD_RS = pf & kPfBadRs;
-            const bool BAD_AG = pf & kPfBadAg, CHANGED = pf & kPfChanged, AG_UNEQ = pf & kPfAgUneq;
-            const bool BAD_BC1 = pf & kPfBadBc1, BC_FAIL = pf & kPfBcFail, ANY_TWO = pf & kPfAnyTwo;
-            const bool NG_AR = pf & kPfNgAr, NG_AG = pf & kPfNgAg, NG_BC = pf & kPfNgBc, PAT_TWO = pf & kPfPatTwo;
-            const int goal_part = s_pgoal[pid], two_part = s_ptwo[pid];
-            const bool rest_done = (n_goal - goal_part) == (R - ng * g);        // the devices left untouched are at the goal
-            const bool rest_two = n_two - two_part > 0;                         // ... or one of them holds two pairs
-            // A valid AllGather of members with different masks: how many masks does a device hold afterwards?
-            // Second walk, the wavefront together: per group the first pair's mask, the first mask that differs
-            // from it, and whether a third one shows up (the child then needs the literal state).
-            bool MANY_MASKS = false;
-            if (!BAD_AG && AG_UNEQ) {
-                bool many = false;
-                for (int G0 = 0; G0 < ng; G0 += gpb) {
-                    const int G = G0 + my_g;
-                    const bool act = G < ng && is_mask;
-                    int base = 0;
-                    if (P.master) base = G * gs;
-                    else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
-                    const uint4 d0 = act ? ldsq[base * L::WQ + qd] : q_zero();
-                    uint4 d1 = q_zero();
-                    bool have1 = false;
-                    const int sh = slot * 8;
-                    for (int it = 0; it < trips; ++it) {
-                        const int t = it * spg + part;
-                        const bool on = act && t < g;
-                        const int d = base + t * s;
-#pragma unroll
-                        for (int pl = 0; pl < NP; ++pl) {
-                            const uint4 m = on ? ldsq[pl * plane_q + d * L::WQ + qd] : q_zero();
-                            // (an empty second pair has an empty mask; the first pair of a member is never empty here)
-                            const bool there = on && (pl == 0 || (flags[d] & kFlagTwo) != 0u);
-                            const unsigned long long ne0 = __ballot(there && q_any(q_xor(m, d0)));
-                            const unsigned long long ne1 = __ballot(there && q_any(q_xor(m, d1)));
-                            if (there && ((ne0 >> sh) & 0xffull) != 0ull) {
-                                if (!have1) { d1 = m; have1 = true; }
-                                else if (((ne1 >> sh) & 0xffull) != 0ull) many = true;
-                            }
-                        }
-                    }
-                    for (int m = 8; m < 8 * spg; m <<= 1) {      // the slots of one group compare what they found
-                        const uint4 o1 = q_shfl_xor(d1, m);
-                        const bool o_have = __shfl_xor((int)have1, m, 64) != 0;
-                        const unsigned long long ne = __ballot(act && have1 && o_have && q_any(q_xor(d1, o1)));
-                        if (act && o_have) {
-                            if (!have1) { d1 = o1; have1 = true; }
-                            else if (((ne >> sh) & 0xffull) != 0ull) many = true;
-                        }
-                    }
-                }
-                MANY_MASKS = __any(many);
-            }
-            if (lane == 0) {
-#pragma unroll
-                for (int oi = 0; oi < 5; ++oi) {
-                    const int op = ops_r[oi];
-                    if (op < 0) continue;
-                    int code;
-                    if (op == OP_AR || op == OP_RS || op == OP_RD) {
-                        if (BAD_RED || !CHANGED || (op == OP_RS && BAD_RS)) code = CODE_INVALID;
-                        else if (UNAL) code = CODE_UNKNOWN;
-                        else if (BAD_B) code = CODE_INVALID;
-                        else if (op == OP_RS) {
-                            if (ANY_TWO) code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
-                            else code = rest_two ? CODE_PREFIX2 : CODE_PREFIX;
-                        } else if (ANY_TWO || rest_two) code = CODE_PREFIX2;
-                        else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
-                    } else if (op == OP_AG) {
-                        if (BAD_AG) code = CODE_INVALID;
-                        else if (AG_UNEQ) code = MANY_MASKS ? CODE_PREFIX_LITERAL : CODE_PREFIX2;   // members with different masks
-                        else if (rest_two) code = CODE_PREFIX2;
-                        else code = (!NG_AG && rest_done) ? CODE_GOAL : CODE_PREFIX;
-                    } else {
-                        if (!PAT_TWO) code = BAD_BC1 ? CODE_INVALID : rest_two ? CODE_PREFIX2 : (!NG_BC && rest_done) ? CODE_GOAL : CODE_PREFIX;
-                        else if (BC_FAIL) code = CODE_INVALID;
-                        else code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
-                    }
-                    if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
-                    if (code == CODE_UNKNOWN) s_unknown[pending] = 1;
-                    s_code[pending][pid * n_ops + oi] = (uint8_t)code;
-                }
-            }
+            const bool many = (!(pf & kPfBadAg) && (pf & kPfAgUneq)) ? cls_many_masks<KW, MW, NP>(c, P) : false;
+            if (lane == 0)
+                cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, ops_r, n_ops, max_pairs,
+                                      all_rows, all_cols, codes + (size_t)e * I, unknown + e);
         }
-        ++pending;
-        if (pending < kClsBatch && e + gridDim.x < n_entries) continue;
-        // ---- write the batch's survivors: wavefront 0 counts them by kind, reserves once, writes
-        __syncthreads();
-        if (wave == 0) {
-            uint32_t c_surv = 0, c_goal = 0, c_p1 = 0, c_p2 = 0;
-            for (int b = 0; b < pending; ++b) {
-                if (s_unknown[b]) continue;
-                for (int a = lane; a < I; a += 64) {
-                    const int code = s_code[b][a];
-                    c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
-                }
-            }
-            uint32_t x_surv = c_surv, x_goal = c_goal, x_p1 = c_p1, x_p2 = c_p2;          // inclusive sums over the lanes
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t a0 = __shfl_up(x_surv, o, 64), a1 = __shfl_up(x_goal, o, 64), a2 = __shfl_up(x_p1, o, 64), a3 = __shfl_up(x_p2, o, 64);
-                if (lane >= o) { x_surv += a0; x_goal += a1; x_p1 += a2; x_p2 += a3; }
-            }
-            const uint32_t t_surv = __shfl(x_surv, 63, 64), t_goal = __shfl(x_goal, 63, 64), t_p1 = __shfl(x_p1, 63, 64), t_p2 = __shfl(x_p2, 63, 64);
-            unsigned long long b0 = 0, b1 = 0;
-            if (lane == 0) {
-                if (t_surv) b0 = atomicAdd(&ctr->surv_goal, (unsigned long long)t_surv | ((unsigned long long)t_goal << 32));
-                if (t_p1 | t_p2) b1 = atomicAdd(&ctr->pref_pref2, (unsigned long long)t_p1 | ((unsigned long long)t_p2 << 32));
-                for (int b = 0; b < pending; ++b) {
-                    if (s_unknown[b]) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[s_entry[b]];
-                    else ++judged;
-                }
-            }
-            b0 = __shfl(b0, 0, 64); b1 = __shfl(b1, 0, 64);
-            uint32_t at_surv = (uint32_t)b0 + x_surv - c_surv, at_goal = (uint32_t)(b0 >> 32) + x_goal - c_goal;
-            uint32_t at_p1 = (uint32_t)b1 + x_p1 - c_p1, at_p2 = (uint32_t)(b1 >> 32) + x_p2 - c_p2;
-            for (int b = 0; b < pending; ++b) {
-                if (s_unknown[b]) continue;
-                for (int a = lane; a < I; a += 64) {
-                    const int code = s_code[b][a];
-                    if (code == CODE_INVALID) continue;
-                    FrontSurvivor sv;
-                    sv.entry = s_entry[b]; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
-                    sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
-                    if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
-                    if (at_surv < surv_cap) surv[at_surv] = sv;
-                    ++at_surv;
-                }
-            }
-        }
-        pending = 0;
-    }
-    if (tid == 0 && judged) {
-        atomicAdd(&ctr->steps, judged * (unsigned long long)I);
-        atomicAdd(&ctr->members, judged * (unsigned long long)q.reg_sum_part);
     }
 }
 
@@ -1101,7 +1160,19 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         if (code != CODE_GOAL) {
             uint4* child = reinterpret_cast<uint4*>(cnp == 2 ? A.next_states2 + (size_t)place * 2 * plane_w
                                                              : A.next_states1 + (size_t)place * plane_w);
-            for (int w = tid; w < cnp * plane_q; w += kMatThreads) child[w] = ldsq[w];
+            unsigned long long h = 0;                    // (what the search for equal states goes by)
+            for (int w = tid; w < cnp * plane_q; w += kMatThreads) {
+                const uint4 v = ldsq[w];
+                child[w] = v;
+                if (q_any(v)) h += hash_quad(v, (uint32_t)w);
+            }
+            uint32_t hl = (uint32_t)h, hh = (uint32_t)(h >> 32);
+            for (int o = 32; o > 0; o >>= 1) {
+                const unsigned long long other = ((unsigned long long)(uint32_t)__shfl_xor((int)hh, o, 64) << 32) | (uint32_t)__shfl_xor((int)hl, o, 64);
+                h += other;
+                hl = (uint32_t)h; hh = (uint32_t)(h >> 32);
+            }
+            if (lane == 0) atomicAdd((cnp == 2 ? A.next_hash2 : A.next_hash1) + place, h);
         }
         // ---- the step's time for every query of the enumeration (alpha-beta model: latency steps of the
         //      slowest group's link; bytes through the busiest uplink, from the query's bandwidth rows)
@@ -1257,9 +1328,9 @@ hipError_t allow_lds_f(F func, size_t bytes) {
 struct FrontArgs {
     const DevQuery* q; uint32_t query;
     const FrontEntry* entries; const uint32_t* states; uint32_t n;
-    int np, max_pairs, handover;
-    FrontSurvivor* surv; uint32_t surv_cap;
-    FrontEntry* unknown_out; FrontCounters* ctr;
+    int np, max_pairs;
+    const uint32_t* list; const uint32_t* n_list;
+    uint8_t* codes; uint8_t* unknown;
     double* sums; int n_share;
     const DevQuery* queries; const FrontLevel* level;
     int R;
@@ -1272,16 +1343,18 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
                            const_cast<uint32_t*>(A.states), A.sums, A.n_share);
     } else if (what == 1) {
         const size_t lds = (size_t)A.np * A.R * FL<KW, MW>::WS * 4 + (((size_t)A.R + 15) & ~(size_t)15);
-        // (a block keeps going over prefixes: what it sets up at its start is paid once)
-        const unsigned blocks = A.n < 2048u ? A.n : 2048u;
+        // (a block keeps going over entries: what it sets up at its start is paid once; with a list of distinct
+        //  states the number of entries is only known on the device, at most n)
+        const unsigned want = A.list ? (A.n + 1u) / 2u : A.n;
+        const unsigned blocks = want < 2048u ? want : 2048u;
         hipError_t e = A.np == 2 ? allow_lds_f(k_front_classify<KW, MW, 2>, lds) : allow_lds_f(k_front_classify<KW, MW, 1>, lds);
         if (e != hipSuccess) return e;
         if (A.np == 2)
-            hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.entries, A.states,
-                               A.n, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
+            hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
+                               A.n_list, A.max_pairs, A.codes, A.unknown);
         else
-            hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.entries, A.states,
-                               A.n, A.max_pairs, A.handover, A.surv, A.surv_cap, A.unknown_out, A.ctr);
+            hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
+                               A.n_list, A.max_pairs, A.codes, A.unknown);
     } else {
         const size_t lds = (size_t)A.level->lds_planes * A.R * FL<KW, MW>::WS * 4;
         const unsigned blocks = A.level->n_surv < 8192u ? A.level->n_surv : 8192u;
@@ -1330,14 +1403,42 @@ hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, Fr
     return front_dispatch(R, k, 0, A, stream);
 }
 
-hipError_t launch_front_classify(const DevQuery* q, int R, int k, const FrontEntry* entries, const uint32_t* states,
-                                 uint32_t n, int np, int max_pairs, int handover, FrontSurvivor* surv, uint32_t surv_cap,
-                                 FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
+hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
+                                 const uint32_t* n_list, int np, int max_pairs, uint8_t* codes, uint8_t* unknown,
+                                 hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
-    A.q = q; A.entries = entries; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.handover = handover; A.surv = surv;
-    A.surv_cap = surv_cap; A.unknown_out = unknown_out; A.ctr = ctr; A.R = R;
+    A.q = q; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.list = list; A.n_list = n_list;
+    A.codes = codes; A.unknown = unknown; A.R = R;
     return front_dispatch(R, k, 1, A, stream);
+}
+
+hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const unsigned long long* hash, uint32_t n,
+                              unsigned long long* table, uint32_t table_size, uint32_t* rep, uint32_t* reps_list,
+                              uint32_t* n_reps, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_front_dedup, dim3((n + 255u) / 256u), dim3(256), 0, stream, hash, n, table, table_size - 1u, rep, reps_list, n_reps);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const unsigned waves = n, blocks = (waves + 3u) / 4u;
+    hipLaunchKernelGGL(k_front_verify, dim3(blocks < 8192u ? blocks : 8192u), dim3(256), 0, stream,
+                       reinterpret_cast<const uint4*>(states), (uint32_t)(state_words / 4), n, rep, reps_list, n_reps);
+    return hipGetLastError();
+}
+
+hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uint32_t n, const uint32_t* rep,
+                               const uint8_t* codes, const uint8_t* unknown, int np, int handover, FrontSurvivor* surv,
+                               uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const unsigned waves = (n + kExpBatch - 1) / kExpBatch, want = (waves + 3u) / 4u;
+    const unsigned blocks = want < 4096u ? want : 4096u;
+    if (np == 2)
+        hipLaunchKernelGGL(k_front_expand<2>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, unknown, handover, surv,
+                           surv_cap, unknown_out, ctr);
+    else
+        hipLaunchKernelGGL(k_front_expand<1>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, unknown, handover, surv,
+                           surv_cap, unknown_out, ctr);
+    return hipGetLastError();
 }
 
 hipError_t launch_front_materialize(const DevQuery* queries, int R, int k, const FrontLevel& level, hipStream_t stream) {

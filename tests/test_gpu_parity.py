@@ -567,9 +567,9 @@ def test_measured_alu_ceiling(B):
 
 
 def test_measured_lds_ceiling(B):
-    """The derived ceiling of the local data share (256 CUs x 128 bytes per clock x 2.4 GHz) bounds what a stream
-    of 128-bit reads reaches, and the stream comes within a factor of three of it."""
-    nominal = 256 * 128 * 2.4e9
+    """The derived ceiling of the local data share (256 CUs x 256 bytes per clock for 128-bit reads x 2.4 GHz) bounds
+    what a stream of such reads reaches, and the stream comes within a factor of three of it."""
+    nominal = 256 * 256 * 2.4e9
     got = B.p2_measure_lds_peak(3)
     print("LDS read stream: %.1f TB/s of %.1f" % (got / 1e12, nominal / 1e12))
     assert nominal / 3 < got <= 1.02 * nominal, got
