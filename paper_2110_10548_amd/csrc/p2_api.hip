@@ -79,6 +79,7 @@ struct Ctx {
     DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];   // frontier engine
     DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, f_valid, f_gsums, f_rank, f_share;
     DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
+    DevBuf f_sid[2], f_sid2[2], f_delta[3], f_childof[2], f_ssurv;                           // prefixes -> states -> children
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
     hipEvent_t copy_done = nullptr;
@@ -142,7 +143,8 @@ void Ctx::release() {
                      &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1], &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1],
                      &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_unknown, &f_ctr, &f_valid, &f_gsums, &f_rank, &f_share,
                      &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1], &f_replist[0], &f_replist[1],
-                     &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1]};
+                     &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1], &f_sid[0], &f_sid[1], &f_sid2[0], &f_sid2[1], &f_delta[0], &f_delta[1],
+                     &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
     HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs, &h_fshare};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
@@ -810,13 +812,18 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         P2_HIP(C.f_entries[cur].ensure(sizeof(FrontEntry)));
         P2_HIP(C.f_states[cur].ensure(sw * 4));
         P2_HIP(C.f_sums[cur].ensure(std::max<size_t>(sum_doubles, 1) * 8));
+        P2_HIP(C.f_sid[cur].ensure(sizeof(uint32_t)));
         P2_HIP(C.f_literal[cur].ensure(sizeof(FrontEntry)));
-        uint32_t n_c = 0, n_c2 = 0, n_l = 0;
+        // A level: two lists of states (one pair per device; up to two) with n_s entries, of which the distinct ones
+        // are judged; two lists of prefixes (n_c, n_c2 entries), each prefix with the index of its state; the
+        // literal list (n_l prefixes that are judged from their instructions).
+        uint32_t n_s[2] = {0, 0}, n_c = 0, n_c2 = 0, n_l = 0;
+        bool grouped[2] = {false, false};            // the state list has been searched for equal states
         if (max_pairs >= 1) {
             P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(C.f_entries[cur].p),
                                      static_cast<uint32_t*>(C.f_states[cur].p), static_cast<double*>(C.f_sums[cur].p),
-                                     (int)sum_doubles / 2, stream));
-            n_c = 1;
+                                     static_cast<uint32_t*>(C.f_sid[cur].p), (int)sum_doubles / 2, stream));
+            n_c = 1; n_s[0] = 1;
         } else {
             const FrontEntry root{(uint32_t)i, 0u, 0ull};
             P2_HIP(hipMemcpyAsync(C.f_literal[cur].p, &root, sizeof root, hipMemcpyHostToDevice, stream));
@@ -824,64 +831,48 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             n_l = 1;
         }
         void* gs = nullptr;
+        const int handover = fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0;
         for (int len = 0; len < pl.max_len && (n_c > 0 || n_c2 > 0 || n_l > 0); ++len) {
             const int keep = len + 1 < pl.max_len ? 1 : 0;
             size_t cap_c = std::max<size_t>(1024, ((size_t)n_c + n_c2) * pl.alphabet / 8);
             size_t cap_l = std::max<size_t>(1024, ((size_t)n_l + n_c2 / 8) * pl.alphabet / 2);
             uint32_t n_surv_l_first = 0;
             P2_HIP(C.f_unknown.ensure(std::max<size_t>(n_c2, 1) * sizeof(FrontEntry)));
-            // ---- the entries of the two lists grouped by state (many prefixes end in the same state, and what the
-            //      rules say about the next instruction depends on the state alone); one entry per distinct state
-            //      is judged against the alphabet, into a row of codes
-            const uint32_t n_list[2] = {n_c, n_c2};
             const DevBuf* list_states[2] = {&C.f_states[cur], &C.f_states2[cur]};
-            const DevBuf* list_hash[2] = {&C.f_hash[cur], &C.f_hash2[cur]};
-            bool grouped[2] = {false, false};
-            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, stream));
+            // ---- one state of every group of equal states is judged against the alphabet, into a row of codes
             for (int li = 0; li < 2; ++li) {
-                const uint32_t n = n_list[li];
-                if (n == 0) continue;
-                P2_HIP(C.f_codes[li].ensure((size_t)n * pl.alphabet));
-                P2_HIP(C.f_unk[li].ensure(n));
-                grouped[li] = n >= kGroupMin && n < (1u << 24);
-                if (grouped[li]) {
-                    size_t table = 1024;
-                    while (table < (size_t)n * 2) table *= 2;
-                    P2_HIP(C.f_table.ensure(table * sizeof(unsigned long long)));
-                    P2_HIP(C.f_rep[li].ensure((size_t)n * sizeof(uint32_t)));
-                    P2_HIP(C.f_replist[li].ensure((size_t)n * sizeof(uint32_t)));
-                    P2_HIP(g_prof.begin(Prof::kGroup, stream));
-                    P2_HIP(hipMemsetAsync(C.f_table.p, 0xff, table * sizeof(unsigned long long), stream));
-                    P2_HIP(launch_front_dedup(static_cast<const uint32_t*>(list_states[li]->p), sw * (li + 1),
-                                              static_cast<const unsigned long long*>(list_hash[li]->p), n,
-                                              static_cast<unsigned long long*>(C.f_table.p), (uint32_t)table,
-                                              static_cast<uint32_t*>(C.f_rep[li].p), static_cast<uint32_t*>(C.f_replist[li].p),
-                                              &dctr->n_reps[li], stream));
-                    P2_HIP(g_prof.end(stream));
-                }
+                if (n_s[li] == 0) continue;
+                P2_HIP(C.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
+                P2_HIP(C.f_unk[li].ensure(n_s[li]));
             }
-            if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
+            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
             for (int li = 0; li < 2; ++li)
-                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_list[li],
+                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li],
                                              grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
                                              grouped[li] ? &dctr->n_reps[li] : nullptr, li + 1, max_pairs,
                                              static_cast<uint8_t*>(C.f_codes[li].p), static_cast<uint8_t*>(C.f_unk[li].p), stream));
-            if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
-            for (;;) {     // list the survivors; repeat with larger lists if they overflow
+            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.end(stream));
+            for (;;) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
                 P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
                 if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
                 P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries[cur].p), n_c,
-                                           grouped[0] ? static_cast<const uint32_t*>(C.f_rep[0].p) : nullptr,
+                                           static_cast<const uint32_t*>(C.f_sid[cur].p),
                                            static_cast<const uint8_t*>(C.f_codes[0].p), static_cast<const uint8_t*>(C.f_unk[0].p), 1, 0,
                                            static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
                 P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries2[cur].p), n_c2,
-                                           grouped[1] ? static_cast<const uint32_t*>(C.f_rep[1].p) : nullptr,
-                                           static_cast<const uint8_t*>(C.f_codes[1].p), static_cast<const uint8_t*>(C.f_unk[1].p), 2,
-                                           fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0,
+                                           static_cast<const uint32_t*>(C.f_sid2[cur].p),
+                                           static_cast<const uint8_t*>(C.f_codes[1].p), static_cast<const uint8_t*>(C.f_unk[1].p), 2, handover,
                                            static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
                                            static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
+                // (how many children the judged states have, by kind)
+                for (int li = 0; li < 2; ++li) {
+                    if (li == 1 && handover) continue;
+                    P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
+                                                 grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(C.f_codes[li].p),
+                                                 static_cast<const uint8_t*>(C.f_unk[li].p), li + 1, keep, 0, nullptr, nullptr, dctr, stream));
+                }
                 if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
                 if (n_l > 0) {
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
@@ -911,7 +902,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(hipStreamSynchronize(stream));
                 }
                 if ((uint32_t)hctr->surv_goal <= cap_c && hctr->n_surv_literal <= cap_l) break;
-                // the repeated classification counts its steps again: take them back
+                // the repeated listing counts its steps again: take them back
                 cap_c = std::max<size_t>(cap_c, (uint32_t)hctr->surv_goal); cap_l = std::max<size_t>(cap_l, (size_t)hctr->n_surv_literal * 2);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
@@ -919,7 +910,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(hipStreamSynchronize(stream));
             }
             {   // what the classification launches of this level worked on
-                const double j1 = grouped[0] ? (double)hctr->n_reps[0] : (double)n_c, j2 = grouped[1] ? (double)hctr->n_reps[1] : (double)n_c2;
+                const double j1 = grouped[0] ? (double)hctr->n_reps[0] : (double)n_s[0], j2 = grouped[1] ? (double)hctr->n_reps[1] : (double)n_s[1];
                 const double planes = j1 + 2.0 * j2;
                 prof_entries += (double)n_c + n_c2;
                 prof_prefixes += j1 + j2;
@@ -929,6 +920,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             const uint32_t n_surv = (uint32_t)hctr->surv_goal, n_surv_l = hctr->n_surv_literal;
             const uint32_t n_goal_pair = (uint32_t)(hctr->surv_goal >> 32), n_goal_lit = hctr->n_goal, n_goal = n_goal_pair + n_goal_lit;
             const uint32_t n_prefix = (uint32_t)hctr->pref_pref2, n_prefix2 = (uint32_t)(hctr->pref_pref2 >> 32), n_plit = hctr->n_prefix_literal;
+            const uint32_t t1 = hctr->t_count[0], t2 = hctr->t_count[1], tg = hctr->t_count[2], n_ss = t1 + t2 + tg;
             r.steps = hctr->steps; r.members = hctr->members;
             r.n_rerun += n_plit + hctr->n_unknown;
             E.n_goal_literal += n_goal_lit;
@@ -937,55 +929,108 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(grow_keep(C.f_gsums, (fsums_used + ((size_t)E.n_valid + n_goal) * sum_doubles + 1) * sizeof(double),
                              (fsums_used + (size_t)E.n_valid * sum_doubles) * sizeof(double), stream));
             const int nxt = cur ^ 1;
-            if (keep) {
-                P2_HIP(C.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
-                P2_HIP(C.f_states[nxt].ensure(std::max<size_t>(n_prefix, 1) * sw * 4));
-                P2_HIP(C.f_sums[nxt].ensure(std::max<size_t>((size_t)n_prefix * sum_doubles, 1) * 8));
-                P2_HIP(C.f_entries2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(FrontEntry)));
-                P2_HIP(C.f_states2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sw * 8));
-                P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
-                P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
-                // (the materialisation adds every child's hash up from zero)
-                P2_HIP(C.f_hash[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(unsigned long long)));
-                P2_HIP(C.f_hash2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(unsigned long long)));
-                P2_HIP(hipMemsetAsync(C.f_hash[nxt].p, 0, std::max<size_t>(n_prefix, 1) * sizeof(unsigned long long), stream));
-                P2_HIP(hipMemsetAsync(C.f_hash2[nxt].p, 0, std::max<size_t>(n_prefix2, 1) * sizeof(unsigned long long), stream));
+            // the next level's prefixes ...
+            P2_HIP(C.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
+            P2_HIP(C.f_sums[nxt].ensure(std::max<size_t>((size_t)n_prefix * sum_doubles, 1) * 8));
+            P2_HIP(C.f_sid[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(uint32_t)));
+            P2_HIP(C.f_entries2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(FrontEntry)));
+            P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
+            P2_HIP(C.f_sid2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(uint32_t)));
+            P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
+            // ... and states: a child per (judged state, valid instruction), its hash (added up from zero), what the step
+            // adds to the cost sums; where a state's children are
+            P2_HIP(C.f_states[nxt].ensure(std::max<size_t>(t1, 1) * sw * 4));
+            P2_HIP(C.f_states2[nxt].ensure(std::max<size_t>(t2, 1) * sw * 8));
+            P2_HIP(C.f_hash[nxt].ensure(std::max<size_t>(t1, 1) * sizeof(unsigned long long)));
+            P2_HIP(C.f_hash2[nxt].ensure(std::max<size_t>(t2, 1) * sizeof(unsigned long long)));
+            P2_HIP(hipMemsetAsync(C.f_hash[nxt].p, 0, std::max<size_t>(t1, 1) * sizeof(unsigned long long), stream));
+            P2_HIP(hipMemsetAsync(C.f_hash2[nxt].p, 0, std::max<size_t>(t2, 1) * sizeof(unsigned long long), stream));
+            P2_HIP(C.f_delta[0].ensure(std::max<size_t>((size_t)t1 * sum_doubles, 1) * 8));
+            P2_HIP(C.f_delta[1].ensure(std::max<size_t>((size_t)t2 * sum_doubles, 1) * 8));
+            P2_HIP(C.f_delta[2].ensure(std::max<size_t>((size_t)tg * sum_doubles, 1) * 8));
+            P2_HIP(C.f_ssurv.ensure(std::max<size_t>(n_ss, 1) * sizeof(FrontSurvivor)));
+            for (int li = 0; li < 2; ++li) P2_HIP(C.f_childof[li].ensure(std::max<size_t>((size_t)n_s[li] * pl.alphabet, 1) * sizeof(uint32_t)));
+            if (n_ss > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
+            for (int li = 0; li < 2; ++li) {
+                if (li == 1 && handover) continue;
+                P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
+                                             grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(C.f_codes[li].p),
+                                             static_cast<const uint8_t*>(C.f_unk[li].p), li + 1, keep, 1, static_cast<uint32_t*>(C.f_childof[li].p),
+                                             static_cast<FrontSurvivor*>(C.f_ssurv.p), dctr, stream));
             }
-            // goals of this level: those of the pair kernels at the places the classification gave them, then those of
-            // literal prefixes
-            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used + E.n_valid;
-            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used + (size_t)E.n_valid * sum_doubles;
-            unsigned long long* vout_lit = vout + n_goal_pair;
-            double* gsums_lit = gsums + (size_t)n_goal_pair * sum_doubles;
+            if (n_ss > 0) P2_HIP(g_prof.end(stream));
             FrontLevel lv;
             std::memset(&lv, 0, sizeof lv);
             lv.query = (uint32_t)i;
             lv.share = static_cast<const int32_t*>(C.f_share.p) + E.off_share;
             lv.n_share = n_share; lv.n_msg = n_msg;
-            lv.entries1 = static_cast<const FrontEntry*>(C.f_entries[cur].p); lv.states1 = static_cast<const uint32_t*>(C.f_states[cur].p);
-            lv.sums1 = static_cast<const double*>(C.f_sums[cur].p);
-            lv.entries2 = static_cast<const FrontEntry*>(C.f_entries2[cur].p); lv.states2 = static_cast<const uint32_t*>(C.f_states2[cur].p);
-            lv.sums2 = static_cast<const double*>(C.f_sums2[cur].p);
-            lv.surv = static_cast<const FrontSurvivor*>(C.f_surv.p); lv.n_surv = n_surv;
-            lv.parent_len = len; lv.keep_prefixes = keep;
-            lv.lds_planes = (n_c2 > 0 || n_prefix2 > 0) ? 2 : 1;
-            lv.next_entries1 = static_cast<FrontEntry*>(C.f_entries[nxt].p); lv.next_states1 = static_cast<uint32_t*>(C.f_states[nxt].p);
-            lv.next_sums1 = static_cast<double*>(C.f_sums[nxt].p);
-            lv.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);
-            lv.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
-            lv.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
+            lv.states1 = static_cast<const uint32_t*>(C.f_states[cur].p); lv.states2 = static_cast<const uint32_t*>(C.f_states2[cur].p);
+            lv.surv = static_cast<const FrontSurvivor*>(C.f_ssurv.p); lv.n_surv = n_ss;
+            lv.lds_planes = (n_s[1] > 0 || t2 > 0) ? 2 : 1;
+            lv.next_states1 = static_cast<uint32_t*>(C.f_states[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);
             lv.next_hash1 = static_cast<unsigned long long*>(C.f_hash[nxt].p); lv.next_hash2 = static_cast<unsigned long long*>(C.f_hash2[nxt].p);
-            lv.valid_out = vout; lv.goal_sums = gsums; lv.ctr = dctr;
-            if (n_surv > 0) P2_HIP(g_prof.begin(Prof::kMaterialize, stream));
+            lv.delta1 = static_cast<double*>(C.f_delta[0].p); lv.delta2 = static_cast<double*>(C.f_delta[1].p);
+            lv.delta_goal = static_cast<double*>(C.f_delta[2].p);
+            if (n_ss > 0) P2_HIP(g_prof.begin(Prof::kMaterialize, stream));
             P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
-            if (n_surv > 0) {
+            if (n_ss > 0) {
                 P2_HIP(g_prof.end(stream));
-                // every survivor reads its parent (one plane at least), every kept child is written: states and sums
-                const double kept = keep ? (double)n_prefix + 2.0 * n_prefix2 : 0.0;
-                prof_children += (double)n_surv;
-                prof_mat_bytes += ((double)n_surv + kept) * pl.R * pair_words * 4.0 +
-                                  ((double)n_surv + (keep ? (double)n_prefix + n_prefix2 : 0.0) + n_goal_pair) * (double)sum_doubles * 8.0;
+                // every child reads its parent (one plane at least) and is written: state and what the step costs
+                prof_children += (double)n_ss;
+                prof_mat_bytes += ((double)n_ss + (double)t1 + 2.0 * t2) * pl.R * pair_words * 4.0 + (double)n_ss * (double)sum_doubles * 8.0;
             }
+            // ---- the next state lists searched for equal states (hashes propose, a word-by-word comparison decides)
+            const uint32_t n_next[2] = {t1, t2};
+            const DevBuf* next_states[2] = {&C.f_states[nxt], &C.f_states2[nxt]};
+            const DevBuf* next_hash[2] = {&C.f_hash[nxt], &C.f_hash2[nxt]};
+            bool grouped_next[2] = {false, false};
+            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, stream));
+            for (int li = 0; li < 2; ++li) {
+                const uint32_t n = n_next[li];
+                grouped_next[li] = n >= kGroupMin && n < (1u << 24);
+                if (!grouped_next[li]) continue;
+                size_t table = 1024;
+                while (table < (size_t)n * 2) table *= 2;
+                P2_HIP(C.f_table.ensure(table * sizeof(unsigned long long)));
+                P2_HIP(C.f_rep[li].ensure((size_t)n * sizeof(uint32_t)));
+                P2_HIP(C.f_replist[li].ensure((size_t)n * sizeof(uint32_t)));
+                P2_HIP(g_prof.begin(Prof::kGroup, stream));
+                P2_HIP(hipMemsetAsync(C.f_table.p, 0xff, table * sizeof(unsigned long long), stream));
+                P2_HIP(launch_front_dedup(static_cast<const uint32_t*>(next_states[li]->p), sw * (li + 1),
+                                          static_cast<const unsigned long long*>(next_hash[li]->p), n,
+                                          static_cast<unsigned long long*>(C.f_table.p), (uint32_t)table,
+                                          static_cast<uint32_t*>(C.f_rep[li].p), static_cast<uint32_t*>(C.f_replist[li].p),
+                                          &dctr->n_reps[li], stream));
+                P2_HIP(g_prof.end(stream));
+            }
+            // ---- the next level's prefixes and this level's goals: those of the pair kernels at the places the listing
+            //      gave them, then those of literal prefixes
+            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used + E.n_valid;
+            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used + (size_t)E.n_valid * sum_doubles;
+            unsigned long long* vout_lit = vout + n_goal_pair;
+            double* gsums_lit = gsums + (size_t)n_goal_pair * sum_doubles;
+            FrontPrefixes px;
+            std::memset(&px, 0, sizeof px);
+            px.query = (uint32_t)i; px.n_share = n_share; px.n_msg = n_msg;
+            px.surv = static_cast<const FrontSurvivor*>(C.f_surv.p); px.n_surv = n_surv;
+            px.parent_len = len; px.keep_prefixes = keep;
+            px.entries1 = static_cast<const FrontEntry*>(C.f_entries[cur].p); px.sid1 = static_cast<const uint32_t*>(C.f_sid[cur].p);
+            px.sums1 = static_cast<const double*>(C.f_sums[cur].p);
+            px.entries2 = static_cast<const FrontEntry*>(C.f_entries2[cur].p); px.sid2 = static_cast<const uint32_t*>(C.f_sid2[cur].p);
+            px.sums2 = static_cast<const double*>(C.f_sums2[cur].p);
+            px.child_of1 = static_cast<const uint32_t*>(C.f_childof[0].p); px.child_of2 = static_cast<const uint32_t*>(C.f_childof[1].p);
+            px.rep1 = grouped_next[0] ? static_cast<const uint32_t*>(C.f_rep[0].p) : nullptr;
+            px.rep2 = grouped_next[1] ? static_cast<const uint32_t*>(C.f_rep[1].p) : nullptr;
+            px.delta1 = lv.delta1; px.delta2 = lv.delta2; px.delta_goal = lv.delta_goal;
+            px.next_entries1 = static_cast<FrontEntry*>(C.f_entries[nxt].p); px.next_sid1 = static_cast<uint32_t*>(C.f_sid[nxt].p);
+            px.next_sums1 = static_cast<double*>(C.f_sums[nxt].p);
+            px.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); px.next_sid2 = static_cast<uint32_t*>(C.f_sid2[nxt].p);
+            px.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
+            px.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
+            px.valid_out = vout; px.goal_sums = gsums; px.ctr = dctr;
+            if (n_surv > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
+            P2_HIP(launch_front_prefixes(reinterpret_cast<const DevQuery*>(db), px, stream));
+            if (n_surv > 0) P2_HIP(g_prof.end(stream));
             P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
                                      static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l_first, len, keep,
                                      static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
@@ -996,9 +1041,11 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             n_c = keep ? n_prefix : 0;
             n_c2 = keep ? n_prefix2 : 0;
             n_l = keep ? n_plit : 0;
+            n_s[0] = keep ? t1 : 0; n_s[1] = keep ? t2 : 0;
+            grouped[0] = grouped_next[0]; grouped[1] = grouped_next[1];
             cur = nxt;
         }
-        // steps of the last materialisation
+        // steps of the last level
         P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
         P2_HIP(hipStreamSynchronize(stream));
         r.steps = hctr->steps; r.members = hctr->members;

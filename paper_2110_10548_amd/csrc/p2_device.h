@@ -258,24 +258,44 @@ struct FrontCounters {
     uint32_t n_overflow;           // literal prefixes left to the full-state kernel
     uint32_t n_unknown;            // two-pair prefixes handed to the literal kernels
     uint32_t next_goal_literal;    // goals of literal prefixes written so far
+    uint32_t t_count[3];           // children of the judged states, by kind: one-pair states, two-pair states, goals
+    uint32_t t_next[3];            // ... places handed out so far
+    uint32_t n_ssurv;              // ... entries of their list
+    uint32_t pad0;
     // running totals of the enumeration
     unsigned long long steps, members;
     // distinct states found among the entries of the one-pair / two-pair list (cleared before each level's search)
     uint32_t n_reps[2];
 };
-// One level of one enumeration, for the materialize kernel.
+// One level of one enumeration.  A level has two lists of states (devices with one (chunk set, mask) pair each;
+// devices with up to two) and two lists of prefixes, one per state list; a prefix is its instructions, its running
+// cost sums for every query of the enumeration, and the index of its state (many prefixes share a state).
+// For the kernel that builds the children of the judged states:
 struct FrontLevel {
     uint32_t query;                // the enumerating query (its DevQuery describes the patterns)
     const int32_t* share;          // [n_share] the queries of the enumeration (indices into the DevQuery array)
     int32_t n_share, n_msg;
-    const FrontEntry* entries1; const uint32_t* states1; const double* sums1;     // one-pair list of this level
-    const FrontEntry* entries2; const uint32_t* states2; const double* sums2;     // two-pair list
-    const FrontSurvivor* surv; uint32_t n_surv;
-    int32_t parent_len, keep_prefixes;
+    const uint32_t* states1; const uint32_t* states2;      // the level's state lists
+    const FrontSurvivor* surv; uint32_t n_surv;            // (state, instruction) pairs: entry = state, slot = the child's
+                                                           // place in the next state list of its kind / among the goals
     int32_t lds_planes;            // 2 if a parent or a child of this level has two pairs, else 1
-    FrontEntry* next_entries1; uint32_t* next_states1; double* next_sums1;
-    FrontEntry* next_entries2; uint32_t* next_states2; double* next_sums2;
+    uint32_t* next_states1; uint32_t* next_states2;
     unsigned long long* next_hash1; unsigned long long* next_hash2;      // hash of every child's state (zero on entry)
+    double* delta1; double* delta2; double* delta_goal;   // [child][n_share][2]: what the step adds to the cost sums
+};
+// For the kernel that writes the prefixes of the next level (and the goals) from the survivors of this level's prefixes:
+struct FrontPrefixes {
+    uint32_t query;
+    int32_t n_share, n_msg;
+    const FrontSurvivor* surv; uint32_t n_surv;            // entry = prefix (in the list the code names), slot = its place
+    int32_t parent_len, keep_prefixes;
+    const FrontEntry* entries1; const uint32_t* sid1; const double* sums1;        // the level's prefix lists
+    const FrontEntry* entries2; const uint32_t* sid2; const double* sums2;
+    const uint32_t* child_of1; const uint32_t* child_of2;  // [state][instruction] -> child (place of its kind)
+    const uint32_t* rep1; const uint32_t* rep2;            // next state lists: child -> the state that stands for it (null: itself)
+    const double* delta1; const double* delta2; const double* delta_goal;
+    FrontEntry* next_entries1; uint32_t* next_sid1; double* next_sums1;
+    FrontEntry* next_entries2; uint32_t* next_sid2; double* next_sums2;
     FrontEntry* next_literal;
     unsigned long long* valid_out; double* goal_sums;      // goals: candidate index and [n_share][2] sums
     FrontCounters* ctr;
@@ -293,7 +313,7 @@ size_t frontier_state_words(int R, int k);
 // 2 where two planes of the state fit in LDS, else 1.
 int frontier_max_pairs(int R, int k);
 hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
-                             double* sums, int n_share, hipStream_t stream);
+                             double* sums, uint32_t* sid, int n_share, hipStream_t stream);
 // Many prefixes of a frontier list have the same state (instructions that commute, detours that end alike), and
 // what the rules say about the next instruction depends on the state alone.  The entries of a list are therefore
 // grouped by state first: rep[p] = an entry with the same state as p (itself for one entry per distinct state,
@@ -323,7 +343,14 @@ size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
                                          int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
                                          void* gscratch, int class_cap, hipStream_t stream);
+// The children of the judged states of a list (every state 0 .. n - 1 if list is null), from their codes: counted by
+// kind (write = 0: t_count), or given their places (write = 1: child_of[state * alphabet + digit], t_next) and
+// listed in ssurv (n_ssurv).  keep = 0: goals only.
+hipError_t launch_front_children(const DevQuery* q, uint32_t n, const uint32_t* list, const uint32_t* n_list, const uint8_t* codes,
+                                 const uint8_t* unknown, int np, int keep, int write, uint32_t* child_of, FrontSurvivor* ssurv,
+                                 FrontCounters* ctr, hipStream_t stream);
 hipError_t launch_front_materialize(const DevQuery* queries, int R, int k, const FrontLevel& level, hipStream_t stream);
+hipError_t launch_front_prefixes(const DevQuery* queries, const FrontPrefixes& P, hipStream_t stream);
 hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry* entries, const FrontSurvivor* surv,
                              uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
                              unsigned long long* valid_out, double* goal_sums, int n_share, FrontCounters* ctr,

@@ -995,32 +995,15 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         spat[i] = p;
     }
     __syncthreads();
-    unsigned long long made = 0, made_members = 0;       // children built (an instruction application each)
     for (uint32_t i = blockIdx.x; i < A.n_surv; i += gridDim.x) {
         const FrontSurvivor sv = A.surv[i];
         const int code = sv.code & 0xff;
         const int np = (sv.code & kFromTwoPair) ? 2 : 1;
-        const FrontEntry pe = (np == 2 ? A.entries2 : A.entries1)[sv.entry];
-        const unsigned long long digits = pe.digits | ((unsigned long long)sv.digit << (9 * A.parent_len));
-        FrontEntry ce;
-        ce.query = A.query; ce.len = (uint32_t)(A.parent_len + 1); ce.digits = digits;
-        if (code == CODE_PREFIX_LITERAL) {
-            if (A.keep_prefixes && tid == 0) A.next_literal[atomicAdd(&A.ctr->next_literal, 1u)] = ce;
-            continue;
-        }
-        if (code != CODE_GOAL && !A.keep_prefixes) continue;     // the size limit is reached: nothing extends this prefix
         const size_t plane_w = (size_t)plane_q * 4;
         const uint4* parent = reinterpret_cast<const uint4*>(np == 2 ? A.states2 + (size_t)sv.entry * 2 * plane_w
                                                                       : A.states1 + (size_t)sv.entry * plane_w);
-        const double* psum = (np == 2 ? A.sums2 : A.sums1) + (size_t)sv.entry * 2 * A.n_share;
         const int cnp = code == CODE_PREFIX2 ? 2 : 1;
-        // (the classification gave every child its place in the next frontier, every goal its place in the list)
-        const uint32_t place = sv.slot;
-        if (tid == 0) {
-            if (code == CODE_GOAL) A.valid_out[place] = rank_of(q, digits, A.parent_len + 1);
-            else if (code == CODE_PREFIX2) A.next_entries2[place] = ce;
-            else A.next_entries1[place] = ce;
-        }
+        const uint32_t place = sv.slot;                  // the child's place in the next state list of its kind
         __syncthreads();                                 // (the block is done with the planes and counts of its last survivor)
         for (int i0 = tid; i0 < np * plane_q; i0 += 8 * kMatThreads) {
             uint4 tmp[8];
@@ -1176,8 +1159,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         }
         // ---- the step's time for every query of the enumeration (alpha-beta model: latency steps of the
         //      slowest group's link; bytes through the busiest uplink, from the query's bandwidth rows)
-        double* out = code == CODE_GOAL ? A.goal_sums + (size_t)place * 2 * A.n_share
-                                        : (code == CODE_PREFIX2 ? A.next_sums2 : A.next_sums1) + (size_t)place * 2 * A.n_share;
+        double* out = (code == CODE_GOAL ? A.delta_goal : code == CODE_PREFIX2 ? A.delta2 : A.delta1) + (size_t)place * 2 * A.n_share;
         // Where every group holds the same number of rows c (the usual case), the busiest unit of a hardware level
         // carries c times the largest multiplicity sum of that level's rows, which the row tables carry per pattern:
         // the same maximum, term by term, without walking the rows; a lane per query then.
@@ -1194,8 +1176,8 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
                     best = fmax(best, (double)((long long)c0 * (long long)rw.level_max[pid][l]) * cq.inv_bw[l]);
                 double ring_steps, mult;
                 step_factors(op, P.g, cq.algo, ring_steps, mult);
-                out[2 * j] = psum[2 * j] + ring_steps * cq.alpha[cq.pat[pid].span_level];
-                out[2 * j + 1] = psum[2 * j + 1] + (mult / (double)cq.k) * best;
+                out[2 * j] = ring_steps * cq.alpha[cq.pat[pid].span_level];
+                out[2 * j + 1] = (mult / (double)cq.k) * best;
             }
         } else if (A.n_msg > 0) {
             for (int j = wave; j < A.n_share; j += kMatWaves) {
@@ -1214,14 +1196,131 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
                 if (lane == 0) {
                     double ring_steps, mult;
                     step_factors(op, P.g, cq.algo, ring_steps, mult);
-                    out[2 * j] = psum[2 * j] + ring_steps * cq.alpha[cq.pat[pid].span_level];
-                    out[2 * j + 1] = psum[2 * j + 1] + (mult / (double)cq.k) * best;
+                    out[2 * j] = ring_steps * cq.alpha[cq.pat[pid].span_level];
+                    out[2 * j + 1] = (mult / (double)cq.k) * best;
                 }
             }
         }
-        if (code != CODE_GOAL) { ++made; made_members += (unsigned long long)(P.n_groups * P.g); }
     }
-    if (tid == 0 && made) { atomicAdd(&A.ctr->steps, made); atomicAdd(&A.ctr->members, made_members); }
+}
+
+// ---- the children of the judged states, from their codes ----------------------------------------------
+constexpr int kChildChunk = 8;
+__global__ __launch_bounds__(256) void k_front_children(const DevQuery* __restrict__ qp, uint32_t n_states,
+                                                        const uint32_t* __restrict__ list, const uint32_t* __restrict__ n_list,
+                                                        const uint8_t* __restrict__ codes, const uint8_t* __restrict__ unknown, int np,
+                                                        int keep, int write, uint32_t* __restrict__ child_of,
+                                                        FrontSurvivor* __restrict__ ssurv, FrontCounters* __restrict__ ctr) {
+    const uint32_t I = (uint32_t)qp->alphabet;
+    const uint32_t n_work = list ? *n_list : n_states;
+    // A wavefront takes kChildChunk states at a time, a lane per instruction: it counts the chunk's children by kind,
+    // reserves their places once (the counters are few, and every reservation of the same word waits for the one
+    // before it), and hands them out in a second pass over the chunk.
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = gridDim.x * 4u;
+    for (uint32_t c0 = wave * kChildChunk; c0 < n_work; c0 += n_waves * kChildChunk) {
+        const uint32_t c1 = min(c0 + (uint32_t)kChildChunk, n_work);
+        uint32_t mine[3] = {0u, 0u, 0u};
+        for (uint32_t i = c0; i < c1; ++i) {
+            const uint32_t st = list ? list[i] : i;
+            if (unknown[st]) continue;               // (its prefixes go to the literal kernels)
+            for (uint32_t a = (uint32_t)lane; a < I; a += 64u) {
+                const int code = codes[(size_t)st * I + a];
+                mine[0] += (code == CODE_PREFIX && keep) ? 1u : 0u;
+                mine[1] += (code == CODE_PREFIX2 && keep) ? 1u : 0u;
+                mine[2] += code == CODE_GOAL ? 1u : 0u;
+            }
+        }
+        uint32_t before[3], total[3];                // over the lanes: exclusive sums, totals
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd) {
+            uint32_t x = mine[kd];
+            for (int o = 1; o < 64; o <<= 1) { const uint32_t y = __shfl_up(x, o, 64); if (lane >= o) x += y; }
+            before[kd] = x - mine[kd];
+            total[kd] = __shfl(x, 63, 64);
+        }
+        uint32_t* const counts = write ? ctr->t_next : ctr->t_count;
+        uint32_t base[3];
+        // (every lane takes part in the reservation, lane 0 alone adds: no lane-dependent branch around a cross-lane read)
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+            base[kd] = total[kd] ? __builtin_amdgcn_readfirstlane(atomicAdd(&counts[kd], lane == 0 ? total[kd] : 0u)) : 0u;
+        if (!write) continue;
+        const uint32_t all = total[0] + total[1] + total[2];
+        if (all == 0) continue;
+        uint32_t at_list = __builtin_amdgcn_readfirstlane(atomicAdd(&ctr->n_ssurv, lane == 0 ? all : 0u)) + before[0] + before[1] + before[2];
+        uint32_t next[3] = {base[0] + before[0], base[1] + before[1], base[2] + before[2]};
+        for (uint32_t i = c0; i < c1; ++i) {
+            const uint32_t st = list ? list[i] : i;
+            if (unknown[st]) continue;
+            for (uint32_t a = (uint32_t)lane; a < I; a += 64u) {
+                const int code = codes[(size_t)st * I + a];
+                const int kind = (code == CODE_PREFIX && keep) ? 0 : (code == CODE_PREFIX2 && keep) ? 1 : code == CODE_GOAL ? 2 : -1;
+                if (kind < 0) continue;
+                const uint32_t t = kind == 0 ? next[0]++ : kind == 1 ? next[1]++ : next[2]++;
+                child_of[(size_t)st * I + a] = t;
+                FrontSurvivor sv;
+                sv.entry = st; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (np == 2 ? kFromTwoPair : 0)); sv.slot = t;
+                ssurv[at_list++] = sv;
+            }
+        }
+    }
+}
+
+// ---- the prefixes of the next level and the goals, from the survivors of this level's prefixes ------------
+// A thread per (survivor, cost sum): the child's sums are the parent's plus what the step adds, which the kernel
+// above worked out once per (state, instruction); the thread of the first sum also writes the record.
+__global__ __launch_bounds__(256) void k_front_prefixes(const DevQuery* __restrict__ queries, FrontPrefixes A) {
+    __shared__ unsigned long long s_made[2];
+    if (threadIdx.x < 2) s_made[threadIdx.x] = 0ull;
+    __syncthreads();
+    const DevQuery& q = queries[A.query];
+    const uint32_t I = (uint32_t)q.alphabet;
+    const uint32_t per = A.n_msg > 0 ? 2u * (uint32_t)A.n_share : 1u;
+    const unsigned long long total = (unsigned long long)A.n_surv * per;
+    for (unsigned long long at = (unsigned long long)blockIdx.x * 256u + threadIdx.x; at < total; at += (unsigned long long)gridDim.x * 256u) {
+        const uint32_t i = (uint32_t)(at / per), j = (uint32_t)(at - (unsigned long long)i * per);
+        const FrontSurvivor sv = A.surv[i];
+        const int code = sv.code & 0xff;
+        const bool two = (sv.code & kFromTwoPair) != 0;
+        const uint32_t place = sv.slot;
+        if (code == CODE_PREFIX_LITERAL) {
+            if (j == 0 && A.keep_prefixes) {
+                const FrontEntry pe = (two ? A.entries2 : A.entries1)[sv.entry];
+                FrontEntry ce;
+                ce.query = A.query; ce.len = (uint32_t)(A.parent_len + 1);
+                ce.digits = pe.digits | ((unsigned long long)sv.digit << (9 * A.parent_len));
+                A.next_literal[atomicAdd(&A.ctr->next_literal, 1u)] = ce;
+            }
+            continue;
+        }
+        if (code != CODE_GOAL && !A.keep_prefixes) continue;     // the size limit is reached: nothing extends this prefix
+        const uint32_t st = (two ? A.sid2 : A.sid1)[sv.entry];
+        const uint32_t t = (two ? A.child_of2 : A.child_of1)[(size_t)st * I + sv.digit];
+        if (A.n_msg > 0) {
+            const double parent = (two ? A.sums2 : A.sums1)[(size_t)sv.entry * per + j];
+            const double step = (code == CODE_GOAL ? A.delta_goal : code == CODE_PREFIX2 ? A.delta2 : A.delta1)[(size_t)t * per + j];
+            double* out = code == CODE_GOAL ? A.goal_sums : code == CODE_PREFIX2 ? A.next_sums2 : A.next_sums1;
+            out[(size_t)place * per + j] = parent + step;
+        }
+        if (j != 0) continue;
+        const FrontEntry pe = (two ? A.entries2 : A.entries1)[sv.entry];
+        const unsigned long long digits = pe.digits | ((unsigned long long)sv.digit << (9 * A.parent_len));
+        if (code == CODE_GOAL) {
+            A.valid_out[place] = rank_of(q, digits, A.parent_len + 1);
+            continue;
+        }
+        FrontEntry ce;
+        ce.query = A.query; ce.len = (uint32_t)(A.parent_len + 1); ce.digits = digits;
+        if (code == CODE_PREFIX2) { A.next_entries2[place] = ce; A.next_sid2[place] = A.rep2 ? A.rep2[t] : t; }
+        else { A.next_entries1[place] = ce; A.next_sid1[place] = A.rep1 ? A.rep1[t] : t; }
+        // (an instruction application per child built, as if every prefix had its own state)
+        const uint32_t ins = q.instr_of_digit[sv.digit];
+        atomicAdd(&s_made[0], 1ull);
+        atomicAdd(&s_made[1], (unsigned long long)(q.pat[ins >> 3].n_groups * q.pat[ins >> 3].g));
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && s_made[0]) { atomicAdd(&A.ctr->steps, s_made[0]); atomicAdd(&A.ctr->members, s_made[1]); }
 }
 
 // Survivors of the literal frontier carry no state: a goal becomes a valid program, the rest
@@ -1252,7 +1351,7 @@ __global__ __launch_bounds__(256) void k_front_emit(const DevQuery* __restrict__
 
 template <int KW, int MW>
 __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ qp, uint32_t query, FrontEntry* entries,
-                                                   uint32_t* states, double* sums, int n_share) {
+                                                   uint32_t* states, double* sums, uint32_t* sid, int n_share) {
     // Sec. 3.5: the empty program; device i holds column i in every row
     const DevQuery& q = *qp;
     constexpr int WPD = FL<KW, MW>::WS;
@@ -1266,7 +1365,7 @@ __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ 
         fstore<KW, MW>(states, d, all_rows, m);
     }
     for (int j = threadIdx.x; j < 2 * n_share; j += 64) sums[j] = 0.0;
-    if (threadIdx.x == 0) { FrontEntry e; e.query = query; e.len = 0; e.digits = 0ull; entries[0] = e; }
+    if (threadIdx.x == 0) { FrontEntry e; e.query = query; e.len = 0; e.digits = 0ull; entries[0] = e; sid[0] = 0u; }
 }
 
 // Programs and costs of an enumeration's valid programs for one of its queries: entry i of the unordered
@@ -1331,7 +1430,7 @@ struct FrontArgs {
     int np, max_pairs;
     const uint32_t* list; const uint32_t* n_list;
     uint8_t* codes; uint8_t* unknown;
-    double* sums; int n_share;
+    double* sums; uint32_t* sid; int n_share;
     const DevQuery* queries; const FrontLevel* level;
     int R;
 };
@@ -1340,7 +1439,7 @@ template <int KW, int MW>
 hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
     if (what == 0) {
         hipLaunchKernelGGL((k_front_init<KW, MW>), dim3(1), dim3(64), 0, stream, A.q, A.query, const_cast<FrontEntry*>(A.entries),
-                           const_cast<uint32_t*>(A.states), A.sums, A.n_share);
+                           const_cast<uint32_t*>(A.states), A.sums, A.sid, A.n_share);
     } else if (what == 1) {
         const size_t lds = (size_t)A.np * A.R * FL<KW, MW>::WS * 4 + (((size_t)A.R + 15) & ~(size_t)15);
         // (a block keeps going over entries: what it sets up at its start is paid once; with a list of distinct
@@ -1397,10 +1496,28 @@ size_t frontier_state_words(int R, int k) {
 int frontier_max_pairs(int R, int k) { return frontier_state_words(R, k) * 2 * 4 + 2048 <= kLdsBudget ? 2 : 1; }
 
 hipError_t launch_front_init(const DevQuery* q, uint32_t query, int R, int k, FrontEntry* entries, uint32_t* states,
-                             double* sums, int n_share, hipStream_t stream) {
+                             double* sums, uint32_t* sid, int n_share, hipStream_t stream) {
     FrontArgs A{};
-    A.q = q; A.query = query; A.entries = entries; A.states = states; A.R = R; A.sums = sums; A.n_share = n_share;
+    A.q = q; A.query = query; A.entries = entries; A.states = states; A.R = R; A.sums = sums; A.sid = sid; A.n_share = n_share;
     return front_dispatch(R, k, 0, A, stream);
+}
+
+hipError_t launch_front_children(const DevQuery* q, uint32_t n, const uint32_t* list, const uint32_t* n_list, const uint8_t* codes,
+                                 const uint8_t* unknown, int np, int keep, int write, uint32_t* child_of, FrontSurvivor* ssurv,
+                                 FrontCounters* ctr, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const unsigned want = (n + 4u * kChildChunk - 1u) / (4u * kChildChunk);      // (a wavefront per chunk of states)
+    hipLaunchKernelGGL(k_front_children, dim3(want < 4096u ? want : 4096u), dim3(256), 0, stream, q, n, list, n_list, codes, unknown, np,
+                       keep, write, child_of, ssurv, ctr);
+    return hipGetLastError();
+}
+
+hipError_t launch_front_prefixes(const DevQuery* queries, const FrontPrefixes& P, hipStream_t stream) {
+    if (P.n_surv == 0) return hipSuccess;
+    const unsigned long long total = (unsigned long long)P.n_surv * (P.n_msg > 0 ? 2ull * (unsigned long long)P.n_share : 1ull);
+    const unsigned long long want = (total + 255ull) / 256ull;
+    hipLaunchKernelGGL(k_front_prefixes, dim3((unsigned)(want < 16384ull ? want : 16384ull)), dim3(256), 0, stream, queries, P);
+    return hipGetLastError();
 }
 
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
