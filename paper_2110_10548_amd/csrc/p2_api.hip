@@ -878,7 +878,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
                     gs = C.lit_scratch.p;
                     P2_HIP(g_prof.begin(Prof::kLiteral, stream));
-                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len,
+                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len, keep ? 0 : 1,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
                                                          pl.max_row_classes, stream));
                     P2_HIP(g_prof.end(stream));
@@ -894,7 +894,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(std::max(n_l, n_c2), n_u))));
                     gs = C.lit_scratch.p;
                     P2_HIP(g_prof.begin(Prof::kLiteral, stream));
-                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_unknown.p), n_u, len,
+                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_unknown.p), n_u, len, keep ? 0 : 1,
                                                          static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
                                                          pl.max_row_classes, stream));
                     P2_HIP(g_prof.end(stream));
@@ -1088,8 +1088,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     P2_HIP(C.topk_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
     P2_HIP(C.topk_scratch.ensure(std::max<size_t>(topk_scratch, 256)));
     int post_launches = 0;
-    std::vector<DevTopkJob> topk_jobs;
-    int topk_jobs_k = 0;
+    std::vector<DevTopkJob> topk_jobs, topk_big;          // short lists (a block each); long lists (cut into shares)
+    int topk_jobs_k = 0, topk_big_k = 0;
     // ordering and costing: one launch per kernel and state-size class
     std::vector<PostLaunch> sort_launches, ccost_launches, scost_launches, lcost_launches;
     for (int i = 0; i < n_queries; ++i) {
@@ -1160,13 +1160,18 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             if (E.n_valid == 0) continue;
             const unsigned long long* list = static_cast<const unsigned long long*>(C.f_valid.p) + E.off_valid;
             uint32_t* rank = static_cast<uint32_t*>(C.f_rank.p) + E.off_valid;
-            ++post_launches;
-            P2_HIP(launch_front_rank(list, E.n_valid, rank, stream));
+            // (a query that asks for the cheapest programs only has them selected by (cost, index): its rows need no order)
+            bool ordered = false;
+            for (int32_t m : E.members) ordered |= runs[m].topk == 0;
+            if (ordered) {
+                ++post_launches;
+                P2_HIP(launch_front_rank(list, E.n_valid, rank, stream));
+            }
             for (size_t m = 0; m < E.members.size(); ++m) {
                 FrontFinish F;
                 std::memset(&F, 0, sizeof F);
                 F.query = (uint32_t)E.members[m]; F.n_share = (int32_t)E.members.size(); F.share_pos = (int32_t)m;
-                F.n_valid = E.n_valid; F.valid = list; F.rank = rank;
+                F.n_valid = E.n_valid; F.valid = list; F.rank = runs[E.members[m]].topk == 0 ? rank : nullptr;
                 F.goal_sums = static_cast<const double*>(C.f_gsums.p) + E.off_sums;
                 F.out_first = runs[E.members[m]].out_first;
                 F.sorted = sorted_base; F.progs = progs_base; F.costs = costs_base;
@@ -1208,21 +1213,37 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     topk_jobs.push_back(J);
                     topk_jobs_k = std::max(topk_jobs_k, r.topk);
                 } else {
-                    post_launches += 2;
-                    P2_HIP(launch_topk(costs + m, n_msg, sorted, r.n_valid, r.topk, out_pos, C.topk_scratch.p, nan_flag, stream));
+                    DevTopkJob J;
+                    J.cost = costs + m; J.index = sorted; J.out_pos = out_pos; J.nan_flag = nan_flag;
+                    J.n = (long long)r.n_valid; J.stride = n_msg; J.k = r.topk; J.pad = 0;
+                    topk_big.push_back(J);
+                    topk_big_k = std::max(topk_big_k, r.topk);
                 }
                 pos_off += kk;
             }
         }
     }
-    if (!topk_jobs.empty()) {
-        const size_t bytes = sizeof(DevTopkJob) * topk_jobs.size();
+    if (!topk_jobs.empty() || !topk_big.empty()) {
+        const size_t n_small = topk_jobs.size(), n_big = topk_big.size();
+        const size_t bytes = sizeof(DevTopkJob) * (n_small + n_big);
         P2_HIP(C.topk_jobs.ensure(bytes));
         P2_HIP(C.h_topk_jobs.ensure(bytes));
-        std::memcpy(C.h_topk_jobs.p, topk_jobs.data(), bytes);
+        DevTopkJob* hj = static_cast<DevTopkJob*>(C.h_topk_jobs.p);
+        if (n_small) std::memcpy(hj, topk_jobs.data(), sizeof(DevTopkJob) * n_small);
+        if (n_big) std::memcpy(hj + n_small, topk_big.data(), sizeof(DevTopkJob) * n_big);
         P2_HIP(hipMemcpyAsync(C.topk_jobs.p, C.h_topk_jobs.p, bytes, hipMemcpyHostToDevice, stream));
-        ++post_launches;
-        P2_HIP(launch_topk_jobs(static_cast<const DevTopkJob*>(C.topk_jobs.p), (unsigned)topk_jobs.size(), topk_jobs_k, stream));
+        const DevTopkJob* dj = static_cast<const DevTopkJob*>(C.topk_jobs.p);
+        if (n_small) {
+            ++post_launches;
+            P2_HIP(launch_topk_jobs(dj, (unsigned)n_small, topk_jobs_k, stream));
+        }
+        // long lists: two launches per 16384 of them
+        for (size_t at = 0; at < n_big; at += 16384) {
+            const unsigned n = (unsigned)std::min<size_t>(16384, n_big - at);
+            P2_HIP(C.topk_scratch.ensure(topk_big_scratch_bytes(n, topk_big_k)));
+            post_launches += 2;
+            P2_HIP(launch_topk_big(dj + n_small + at, n, topk_big_k, C.topk_scratch.p, stream));
+        }
     }
     if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[2], stream)); g_prof.last.post_launches = post_launches; }
     P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));

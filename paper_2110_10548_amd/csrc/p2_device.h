@@ -339,10 +339,11 @@ hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uin
 // Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 // class_cap: most classes of equal rows the class-state kernel may hold (1..64) before a prefix goes to the
-// full-state kernel.
+// full-state kernel.  goals_only != 0 (the level at the size limit): only the instructions that can reach the
+// goal from the prefix's state are judged, and only goals are reported.
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
-                                         int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
-                                         void* gscratch, int class_cap, hipStream_t stream);
+                                         int parent_len, int goals_only, FrontSurvivor* surv, uint32_t surv_cap,
+                                         FrontCounters* ctr, void* gscratch, int class_cap, hipStream_t stream);
 // The children of the judged states of a list (every state 0 .. n - 1 if list is null), from their codes: counted by
 // kind (write = 0: t_count), or given their places (write = 1: child_of[state * alphabet + digit], t_next) and
 // listed in ssurv (n_ssurv).  keep = 0: goals only.
@@ -372,6 +373,10 @@ struct DevTopkJob {
 };
 // Block b of the launch does jobs[b] alone: meant for many selections of a few thousand entries each.
 hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream);
+// Many selections of many entries each: two launches for all of them (every job cut into strided shares, then a
+// merge per job).  scratch: topk_big_scratch_bytes(n_jobs, max_k) bytes.  Grid limit: n_jobs <= 65535.
+size_t topk_big_scratch_bytes(unsigned n_jobs, int max_k);
+hipError_t launch_topk_big(const DevTopkJob* jobs, unsigned n_jobs, int max_k, void* scratch, hipStream_t stream);
 
 // Results to the host: a kernel copies `bytes` (rounded up to 16; both buffers must hold that) from device
 // memory to pinned, device-accessible host memory.  Used instead of hipMemcpyAsync, whose queueing of a

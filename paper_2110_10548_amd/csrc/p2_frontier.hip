@@ -1369,13 +1369,14 @@ __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ 
 }
 
 // Programs and costs of an enumeration's valid programs for one of its queries: entry i of the unordered
-// list, whose place in ascending index order is rank[i], becomes row out_first + rank[i].
+// list, whose place in ascending index order is rank[i], becomes row out_first + rank[i] (row out_first + i where
+// no order is asked for: rank null).
 __global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict__ queries, FrontFinish F) {
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
     if (i >= F.n_valid) return;
     const DevQuery& q = queries[F.query];
     const unsigned long long idx = F.valid[i];
-    const size_t row = F.out_first + F.rank[i];
+    const size_t row = F.out_first + (F.rank ? F.rank[i] : i);
     int len = 1;
     while (len < q.max_len && idx >= q.base[len + 1]) ++len;
     p2_program pr;

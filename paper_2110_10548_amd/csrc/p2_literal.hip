@@ -1260,7 +1260,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
                                                                   const FrontEntry* __restrict__ entries, uint32_t n_entries,
                                                                   const uint32_t* __restrict__ elist,
                                                                   const uint32_t* __restrict__ elist_n,
-                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
+                                                                  int parent_len, int goals_only, FrontSurvivor* __restrict__ surv,
                                                                   uint32_t surv_cap, FrontCounters* __restrict__ ctr,
                                                                   uint32_t* __restrict__ gscratch, unsigned long long gwords) {
     extern __shared__ uint32_t lds[];
@@ -1286,12 +1286,33 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
             lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
         }
         const int C = row_classes<MW>(q, L, X, full, lane);
+        // At the size limit only goals count, and few instructions can reach the goal from a given state (see
+        // cls_judge_all): the others are not looked at.
+        bool rows_full = true, cols_full = true, root_done = true;
+        if (goals_only) {
+            bool rows_bad = false, cols_bad = false;
+            for (int d = lane; d < R; d += kWave)
+                for (int row = 0; row < q.k; ++row) {
+                    const uint32_t* x = L.S + ((size_t)d * q.k + row) * MW;
+                    bool ne = false, fl = true;
+#pragma unroll
+                    for (int w = 0; w < MW; ++w) { ne |= x[w] != 0u; fl &= x[w] == full[w]; }
+                    rows_bad |= !ne; cols_bad |= ne && !fl;
+                }
+            rows_full = !__any(rows_bad);
+            cols_full = !__any(cols_bad);
+            root_done = X.devfull[0] != 0u;
+        }
         for (int a = 0; a < I; ++a) {
             const uint32_t ins = q.instr_of_digit[a];
             const DevPattern& P = q.pat[ins >> 3];
-            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
             ++steps;
             members += (unsigned long long)(P.n_groups * P.g);
+            if (goals_only) {
+                const int op = (int)(ins & 7u);
+                if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
+            }
+            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
             if (code != 0 && lane == 0) {
                 const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
                 if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
@@ -1309,7 +1330,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
 template <int MW>
 __global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery* __restrict__ qp,
                                                                   const FrontEntry* __restrict__ entries, uint32_t n_entries,
-                                                                  int parent_len, FrontSurvivor* __restrict__ surv,
+                                                                  int parent_len, int goals_only, FrontSurvivor* __restrict__ surv,
                                                                   uint32_t surv_cap, FrontCounters* __restrict__ ctr,
                                                                   uint32_t* __restrict__ over, uint32_t* __restrict__ gscratch,
                                                                   unsigned long long gwords, int class_cap) {
@@ -1344,9 +1365,13 @@ __global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery
         for (int a = 0; a < I; ++a) {
             const uint32_t ins = q.instr_of_digit[a];
             const DevPattern& P = q.pat[ins >> 3];
-            const int code = cls_classify<MW>(q, P, (int)(ins & 7u), X, C, full, lane);
             ++steps;
             members += (unsigned long long)(P.n_groups * P.g);
+            if (goals_only) {        // (at the size limit only goals count: see cls_judge_all)
+                const int op = (int)(ins & 7u);
+                if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
+            }
+            const int code = cls_classify<MW>(q, P, (int)(ins & 7u), X, C, full, lane);
             if (code != 0 && lane == 0) {
                 const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
                 if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
@@ -1777,7 +1802,7 @@ FrontLiteralScratch front_literal_scratch(int R, int k, uint32_t n) {
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n) { return front_literal_scratch(R, k, n).total; }
 
 hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const FrontEntry* entries, uint32_t n,
-                                         int parent_len, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
+                                         int parent_len, int goals_only, FrontSurvivor* surv, uint32_t surv_cap, FrontCounters* ctr,
                                          void* gscratch, int class_cap_asked, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     if (!gscratch) return hipErrorInvalidValue;
@@ -1796,11 +1821,11 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     e = allow_big_lds(k_front_classify_classes<MWV>, sc.cls_lds);                                              \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_front_classify_classes<MWV>, dim3(cls_blocks), dim3(kWave), sc.cls_lds, stream, q, entries, n, \
-                           parent_len, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap);          \
+                           parent_len, goals_only, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap); \
     if (e == hipSuccess) e = allow_big_lds(k_front_classify_literal<MWV>, sc.full_lds);                        \
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(full_blocks), dim3(kWave), sc.full_lds, stream, q, entries, n, \
-                           over, &ctr->n_overflow, parent_len, surv, surv_cap, ctr, full_mem, full_words_per);
+                           over, &ctr->n_overflow, parent_len, goals_only, surv, surv_cap, ctr, full_mem, full_words_per);
     switch (mask_words(R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;

@@ -178,6 +178,63 @@ __global__ __launch_bounds__(kWave) void k_topk_jobs(const DevTopkJob* __restric
     for (int j = lane; j < n_out; j += kWave) J.out_pos[j] = j < cnt ? L.pos[j] : -1ll;
 }
 
+// Many large selections in two launches: job j is cut into kBigParts strided shares, block (part, j) keeps the K best
+// of its share in the job's piece of the scratch buffer (kBigParts lists of max_k entries), then block j of the
+// second launch merges the job's lists.
+constexpr int kBigParts = 64;
+__global__ __launch_bounds__(kWave) void k_topk_big_partial(const DevTopkJob* __restrict__ jobs, int max_k, double* __restrict__ part_c,
+                                                            unsigned long long* __restrict__ part_i, long long* __restrict__ part_p) {
+    extern __shared__ unsigned char raw[];
+    const DevTopkJob J = jobs[blockIdx.y];
+    const int K = J.k;
+    TopList L;
+    L.c = reinterpret_cast<double*>(raw);
+    L.idx = reinterpret_cast<unsigned long long*>(L.c + K);
+    L.pos = reinterpret_cast<long long*>(L.idx + K);
+    const int lane = threadIdx.x;
+    int cnt = 0;
+    bool nan = false;
+    for (long long t0 = (long long)blockIdx.x * kWave; t0 < J.n; t0 += (long long)kBigParts * kWave) {
+        const long long i = t0 + lane;
+        Item mine{0.0, 0ull, i};
+        const bool valid = i < J.n;
+        if (valid) { mine.c = J.cost[i * J.stride]; mine.idx = J.index[i]; nan |= mine.c != mine.c; }
+        list_offer(L, cnt, K, mine, valid && !(mine.c != mine.c), lane);
+    }
+    if (nan) atomicOr(J.nan_flag, 1u);
+    __syncthreads();
+    const size_t o0 = ((size_t)blockIdx.y * kBigParts + blockIdx.x) * (size_t)max_k;
+    for (int j = lane; j < K; j += kWave) {
+        part_c[o0 + j] = j < cnt ? L.c[j] : 0.0;
+        part_i[o0 + j] = j < cnt ? L.idx[j] : 0ull;
+        part_p[o0 + j] = j < cnt ? L.pos[j] : -1ll;
+    }
+}
+__global__ __launch_bounds__(kWave) void k_topk_big_merge(const DevTopkJob* __restrict__ jobs, int max_k, const double* __restrict__ part_c,
+                                                          const unsigned long long* __restrict__ part_i,
+                                                          const long long* __restrict__ part_p) {
+    extern __shared__ unsigned char raw[];
+    const DevTopkJob J = jobs[blockIdx.x];
+    const int K = J.k;
+    TopList L;
+    L.c = reinterpret_cast<double*>(raw);
+    L.idx = reinterpret_cast<unsigned long long*>(L.c + K);
+    L.pos = reinterpret_cast<long long*>(L.idx + K);
+    const int lane = threadIdx.x;
+    int cnt = 0;
+    const size_t o0 = (size_t)blockIdx.x * kBigParts * (size_t)max_k;
+    for (int part = 0; part < kBigParts; ++part)
+        for (int t0 = 0; t0 < K; t0 += kWave) {
+            const int j = t0 + lane;
+            Item mine{0.0, 0ull, -1ll};
+            if (j < K) { const size_t o = o0 + (size_t)part * max_k + j; mine = Item{part_c[o], part_i[o], part_p[o]}; }
+            list_offer(L, cnt, K, mine, j < K && mine.pos >= 0, lane);
+        }
+    __syncthreads();
+    const long long n_out = K < J.n ? K : J.n;
+    for (int j = lane; j < n_out; j += kWave) J.out_pos[j] = j < cnt ? L.pos[j] : -1ll;
+}
+
 // Device memory -> pinned host memory, written by the GPU itself in 16-byte words.
 __global__ __launch_bounds__(256) void k_copy_out(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
@@ -238,6 +295,22 @@ size_t topk_scratch_bytes(long long n, int k) { return (size_t)topk_blocks(n) * 
 hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream) {
     if (n_jobs == 0) return hipSuccess;
     hipLaunchKernelGGL(k_topk_jobs, dim3(n_jobs), dim3(kWave), (size_t)max_k * 24, stream, jobs);
+    return hipGetLastError();
+}
+
+size_t topk_big_scratch_bytes(unsigned n_jobs, int max_k) { return (size_t)n_jobs * kBigParts * (size_t)max_k * 24; }
+
+hipError_t launch_topk_big(const DevTopkJob* jobs, unsigned n_jobs, int max_k, void* scratch, hipStream_t stream) {
+    if (n_jobs == 0) return hipSuccess;
+    const size_t per = (size_t)n_jobs * kBigParts * (size_t)max_k;
+    double* pc = reinterpret_cast<double*>(scratch);
+    unsigned long long* pi = reinterpret_cast<unsigned long long*>(pc + per);
+    long long* pp = reinterpret_cast<long long*>(pi + per);
+    const size_t lds = (size_t)max_k * 24;
+    hipLaunchKernelGGL(k_topk_big_partial, dim3(kBigParts, n_jobs), dim3(kWave), lds, stream, jobs, max_k, pc, pi, pp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_topk_big_merge, dim3(n_jobs), dim3(kWave), lds, stream, jobs, max_k, pc, pi, pp);
     return hipGetLastError();
 }
 
