@@ -621,10 +621,75 @@ __device__ inline bool cls_many_masks(const ClsLane<KW, MW, NP>& c, const PatLds
     return __any(many) != 0;
 }
 
+// Broadcast on a pattern with two-pair members that has passed the necessary conditions of the walk above, the
+// wavefront together (the rule of bcast_compare): every member's rows lie inside the root's; where a pair of the
+// member shares rows with a pair of the root, the member's mask lies inside the root's; and in every group some
+// member differs from its root.  Returns 0 (invalid), else 1 | 2 (some root holds two pairs) | 4 (every root is
+// at the goal).
+template <int KW, int MW, int NP>
+__device__ inline int cls_bcast_pairs(const ClsLane<KW, MW, NP>& c, const PatLds P) {
+    using L = FL<KW, MW>;
+    const uint4* const ldsq = c.ldsq;
+    const int plane_q = c.plane_q, slot = c.slot, qd = c.qd, sh = slot * 8;
+    const bool is_row = c.is_row, is_mask = c.is_mask;
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    int spg = 1;
+    while (spg * 2 * ng <= 8) spg *= 2;
+    const int gpb = 8 / spg;
+    const int my_g = slot / spg, part = slot - my_g * spg;
+    const int trips = (g + spg - 1) / spg;
+    bool bad = false, any_two = false, not_goal = false;
+    for (int G0 = 0; G0 < ng; G0 += gpb) {
+        const int G = G0 + my_g;
+        const bool act = G < ng && c.has_quad;
+        int base = 0;
+        if (P.master) base = G * gs;
+        else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+        const uint4 r0 = act ? ldsq[base * L::WQ + qd] : q_zero();
+        const uint4 r1 = (NP == 2 && act) ? ldsq[plane_q + base * L::WQ + qd] : q_zero();
+        bool not_sub = false, dif = false;
+        for (int it = 0; it < trips; ++it) {
+            const int t = it * spg + part;
+            const bool on = act && t < g && t > 0;
+            const int d = base + t * s;
+            const uint4 v0 = on ? ldsq[d * L::WQ + qd] : q_zero();
+            const uint4 v1 = (NP == 2 && on) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+            // which pairs of the member share rows with which pairs of the root (row lanes tell the slot)
+            const bool o00 = ((__ballot(on && is_row && q_any(q_and(r0, v0))) >> sh) & 0xffull) != 0ull;
+            const bool o01 = ((__ballot(on && is_row && q_any(q_and(r0, v1))) >> sh) & 0xffull) != 0ull;
+            const bool o10 = ((__ballot(on && is_row && q_any(q_and(r1, v0))) >> sh) & 0xffull) != 0ull;
+            const bool o11 = ((__ballot(on && is_row && q_any(q_and(r1, v1))) >> sh) & 0xffull) != 0ull;
+            if (on) {
+                if (is_row) {
+                    const uint4 um = q_or(v0, v1), ur = q_or(r0, r1);
+                    not_sub |= q_any(q_andn(um, ur));
+                    dif |= q_any(q_xor(um, ur));
+                } else if (is_mask) {
+                    if (o00) { not_sub |= q_any(q_andn(v0, r0)); dif |= q_any(q_xor(v0, r0)); }
+                    if (o01) { not_sub |= q_any(q_andn(v1, r0)); dif |= q_any(q_xor(v1, r0)); }
+                    if (o10) { not_sub |= q_any(q_andn(v0, r1)); dif |= q_any(q_xor(v0, r1)); }
+                    if (o11) { not_sub |= q_any(q_andn(v1, r1)); dif |= q_any(q_xor(v1, r1)); }
+                }
+            }
+        }
+        // a group's verdict: nothing outside the root's, and a difference in some slot of the group
+        const unsigned long long dif_slots = __ballot(dif);
+        const unsigned long long group_bits = (spg == 8 ? ~0ull : ((1ull << (8 * spg)) - 1ull) << ((slot - part) * 8));
+        const bool root_two = ((__ballot(act && is_row && q_any(r1)) >> sh) & 0xffull) != 0ull;
+        if (act) {
+            bad |= not_sub || (dif_slots & group_bits) == 0ull;
+            any_two |= root_two;
+            not_goal |= root_two || q_any(q_xor(r0, c.goal_quad));
+        }
+    }
+    if (__any(bad)) return 0;
+    return 1 | (__any(any_two) ? 2 : 0) | (__any(not_goal) ? 0 : 4);
+}
+
 // One lane: the codes of a pattern's instructions from what its groups have shown.
 template <int KW, int MW, int NP>
 __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, int pid, uint32_t pf, int goal_part, int two_part,
-                                 int n_goal, int n_two, bool MANY_MASKS, const int (&ops_r)[5], int n_ops, int max_pairs,
+                                 int n_goal, int n_two, bool MANY_MASKS, int bc_pairs, const int (&ops_r)[5], int n_ops, int max_pairs,
                                  const Words<KW>& all_rows, const Words<MW>& all_cols, uint8_t* __restrict__ codes,
                                  uint8_t* __restrict__ unknown) {
     const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(c.ldsq);
@@ -656,8 +721,8 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
             else code = (!NG_AG && rest_done) ? CODE_GOAL : CODE_PREFIX;
         } else {
             if (!PAT_TWO) code = BAD_BC1 ? CODE_INVALID : rest_two ? CODE_PREFIX2 : (!NG_BC && rest_done) ? CODE_GOAL : CODE_PREFIX;
-            else if (BC_FAIL) code = CODE_INVALID;
-            else code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
+            else if (BC_FAIL || bc_pairs == 0) code = CODE_INVALID;
+            else code = ((bc_pairs & 2) || rest_two) ? CODE_PREFIX2 : ((bc_pairs & 4) && rest_done) ? CODE_GOAL : CODE_PREFIX;
         }
         if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
         if (code == CODE_UNKNOWN) *unknown = 1;          // (after the block's barriers that follow the clearing)
@@ -862,8 +927,9 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     c.is_row = c.qd < L::QK; c.is_mask = c.qd >= L::QK && c.qd < L::WQ; c.has_quad = c.qd < L::WQ;
     c.goal_quad = goal_quad_of<KW, MW>(all_rows, all_cols, c.qd, c.is_row, c.is_mask);
     int ops_r[5];
+    bool has_bcast = false;
 #pragma unroll
-    for (int i = 0; i < 5; ++i) ops_r[i] = i < n_ops ? q.ops[i] : -1;
+    for (int i = 0; i < 5; ++i) { ops_r[i] = i < n_ops ? q.ops[i] : -1; has_bcast |= ops_r[i] == OP_BC; }
     const uint32_t n_work = list ? *n_list : n_entries;
     for (uint32_t at = blockIdx.x; at < n_work; at += gridDim.x) {
         const uint32_t e = list ? list[at] : at;
@@ -916,8 +982,10 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             const PatLds P = spat[pid];
             const uint32_t pf = s_pflags[pid];
             const bool many = (!(pf & kPfBadAg) && (pf & kPfAgUneq)) ? cls_many_masks<KW, MW, NP>(c, P) : false;
+            int bc_pairs = 0;                            // (Broadcast among two-pair devices: the pairs compared)
+            if (NP == 2 && has_bcast && (pf & kPfPatTwo) && !(pf & kPfBcFail)) bc_pairs = cls_bcast_pairs<KW, MW, NP>(c, P);
             if (lane == 0)
-                cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, ops_r, n_ops, max_pairs,
+                cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, ops_r, n_ops, max_pairs,
                                       all_rows, all_cols, codes + (size_t)e * I, unknown + e);
         }
     }
