@@ -13,14 +13,17 @@ evaluated that query itself: queries of the batch whose validity results are equ
 on their own (`config.queries_evaluated` of `config.queries`; `value_all_queries` counts every query).
 
 `roofline` prices the dominant kernel family of the step.  For the frontier engine that is the
-classification of valid prefixes against every instruction of the alphabet (k_front_classify):
-its algorithmic work per judged prefix is 4 lane-operations (read, union, intersection /
-seen-twice, compare) per 32-bit word of the (chunk set, mask) pairs of every device that a pattern
-of the alphabet visits, set against the chip's 32-bit integer vector rate; the same words are read
-from LDS once per pattern (`roofline.lds`, against 256 bytes per clock and compute unit) and the
-prefix's state comes from device memory once (`roofline.hbm`).  `materialize` prices the kernel
-that writes the surviving children against HBM.  Times are HIP-event times around every launch
-of the family on the call's stream, taken inside the timed steps (p2_get_profile).
+classification of the states of valid prefixes against every instruction of the alphabet
+(k_front_classify; prefixes that end in the same state share one classification:
+`states_judged_per_step` of `prefixes_per_step`): its algorithmic work per judged state is 4
+lane-operations (read, union, intersection / seen-twice, compare) per 32-bit word of the (chunk
+set, mask) pairs of every device that a pattern of the alphabet visits, set against the chip's
+32-bit integer vector rate (`per_prefix_equivalent_frac` prices the same time as if every prefix had
+been judged on its own); the same words are read from LDS once per pattern (`roofline.lds`, against
+256 bytes per clock and compute unit) and the state comes from device memory once (`roofline.hbm`).
+`materialize` prices the kernel that builds the children of the judged states against HBM.  Times
+are HIP-event times around every launch of the family on the call's stream, taken inside the timed
+steps (p2_get_profile).
 For the flat engines (configurations 1-4 with the default engine) the roofline is the lane-operation
 rate of the evaluation kernel, as `other_configs` reports per configuration.
 `cpu_baseline` times the plain CPU oracle on a bounded sample of the same workload.
@@ -188,7 +191,7 @@ def main():
         del src, dst
 
     PROFILE_SUMS = ("eval_ms", "post_ms", "eval_launches", "front_ms", "front_classify_ms", "front_literal_ms",
-                    "front_materialize_ms", "front_classify_launches", "front_literal_launches", "front_materialize_launches",
+                    "front_materialize_ms", "front_group_ms", "front_entries", "front_classify_launches", "front_literal_launches", "front_materialize_launches",
                     "front_prefixes", "front_classify_state_bytes", "front_classify_lane_ops", "front_survivors",
                     "front_materialize_bytes")
 
@@ -248,11 +251,13 @@ def main():
             lds_rate = run["front_classify_lane_ops"] / cls_s           # 4 lane-operations per 4-byte word read from LDS
             hbm_rate = run["front_classify_state_bytes"] / cls_s
             mat_s = max(run["front_materialize_ms"] * 1e-3, 1e-12)
-            out["prefixes_judged_per_step"] = run["front_prefixes"] / steps
-            out["prefixes_judged_per_s"] = run["front_prefixes"] / cls_s
+            out["states_judged_per_step"] = run["front_prefixes"] / steps
+            out["prefixes_per_step"] = run["front_entries"] / steps
+            out["states_judged_per_s"] = run["front_prefixes"] / cls_s
             out["device_ms_per_step"].update({"front_classify": run["front_classify_ms"] / steps,
                                               "front_literal": run["front_literal_ms"] / steps,
-                                              "front_materialize": run["front_materialize_ms"] / steps})
+                                              "front_materialize": run["front_materialize_ms"] / steps,
+                                              "front_group_and_list": run["front_group_ms"] / steps})
             out["roofline"] = {
                 "bound": "alu", "kernel": "k_front_classify", "achieved": rate / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
                 "unit": "Tlane-op/s", "frac": rate / ALU_PEAK_LANE_OPS,
@@ -262,6 +267,7 @@ def main():
                 "algorithmic_hbm_bytes_per_launch": run["front_classify_state_bytes"] / n_launch,
                 "lds": {"achieved": lds_rate / 1e9, "peak": LDS_PEAK_BYTES / 1e9, "unit": "GB/s", "frac": lds_rate / LDS_PEAK_BYTES},
                 "hbm": {"achieved": hbm_rate / 1e9, "peak": HBM_PEAK_BYTES / 1e9, "unit": "GB/s", "frac": hbm_rate / HBM_PEAK_BYTES},
+                "per_prefix_equivalent_frac": rate / ALU_PEAK_LANE_OPS * run["front_entries"] / max(run["front_prefixes"], 1.0),
                 "share_of_device_time": run["front_classify_ms"] / max(run["front_ms"] + run["post_ms"] + run["eval_ms"], 1e-9)}
             n_mat = max(run["front_materialize_launches"], 1)
             out["materialize"] = {
@@ -270,7 +276,7 @@ def main():
                 "traffic": measured_traffic("k_front_materialize", cfg_index),
                 "launch_ms": run["front_materialize_ms"] / n_mat, "launches_per_step": n_mat / steps,
                 "algorithmic_hbm_bytes_per_launch": run["front_materialize_bytes"] / n_mat,
-                "survivors_per_step": run["front_survivors"] / steps}
+                "children_per_step": run["front_survivors"] / steps}
         else:
             kernel = KERNEL[main_engine]
             ops_launch, launch_ms, achieved = flat_summary(run, "members_evaluated")
@@ -318,7 +324,8 @@ def main():
     }
     if "lds" in out["roofline"]:
         out["roofline"]["lds"]["peak_measured"] = lds_measured / 1e9
-    for key in ("materialize", "prefixes_judged_per_step", "prefixes_judged_per_s", "steps_executed_per_step", "steps_evaluated_per_step"):
+    for key in ("materialize", "states_judged_per_step", "prefixes_per_step", "states_judged_per_s", "steps_executed_per_step",
+                "steps_evaluated_per_step"):
         if key in head:
             out[key] = head[key]
 

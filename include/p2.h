@@ -317,7 +317,7 @@ typedef struct {
     float front_classify_ms;          /* prefixes held as (chunk set, mask) pairs judged against the
                                          alphabet (Sec. 3.2's rules on every instruction)          */
     float front_literal_ms;           /* prefixes held literally, judged from their instructions    */
-    float front_materialize_ms;       /* surviving children: state and running cost sums written    */
+    float front_materialize_ms;       /* children of the judged states: state and step costs        */
     int32_t front_classify_launches, front_literal_launches, front_materialize_launches;
     float front_group_ms;             /* the search for entries with equal states, and the listing of
                                          every entry's survivors from the codes of its state       */
@@ -329,11 +329,12 @@ typedef struct {
     double front_classify_lane_ops;   /* 4 lane-operations (read, union, intersection / seen-twice,
                                          compare) per state word of every device that a pattern of
                                          the alphabet visits, per judged prefix and plane           */
-    double front_survivors;           /* valid children handed to the materialisation               */
-    double front_materialize_bytes;   /* bytes it must move: a parent plane read per survivor, the
-                                         planes of every kept child written, the cost sums of both  */
-    double front_entries;             /* entries of the pair lists, all levels (front_prefixes of them
-                                         were judged, the others share the codes of an equal state) */
+    double front_survivors;           /* children built: one per (judged state, valid instruction)  */
+    double front_materialize_bytes;   /* bytes that must move for them: a parent plane read per child,
+                                         the planes of every kept child written, what the step adds
+                                         to the cost sums                                           */
+    double front_entries;             /* prefixes of the pair lists, all levels (they end in
+                                         front_prefixes distinct states, which were judged)         */
 } p2_profile;
 int32_t p2_set_profiling(int32_t on);
 int32_t p2_get_profile(p2_profile* out);

@@ -98,11 +98,11 @@ struct Prof {
     p2_profile last = {};
     // events around single launches of the frontier engine: a pool that grows on demand and is kept
     enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kGroup = 3, kKinds = 4 };
-    struct Span { int kind; size_t first; };
+    struct Span { int kind; size_t first; int dispatches; };
     std::vector<hipEvent_t> pool;
     std::vector<Span> spans;
     size_t used = 0;
-    hipError_t begin(int kind, hipStream_t stream) {
+    hipError_t begin(int kind, hipStream_t stream, int dispatches = 1) {
         if (!on) return hipSuccess;
         while (pool.size() < used + 2) {
             hipEvent_t e = nullptr;
@@ -110,7 +110,7 @@ struct Prof {
             if (rc != hipSuccess) return rc;
             pool.push_back(e);
         }
-        spans.push_back(Span{kind, used});
+        spans.push_back(Span{kind, used, dispatches});
         used += 2;
         return hipEventRecord(pool[used - 2], stream);
     }
@@ -123,7 +123,7 @@ struct Prof {
             const hipError_t rc = hipEventElapsedTime(&t, pool[sp.first], pool[sp.first + 1]);
             if (rc != hipSuccess) return rc;
             ms[sp.kind] += t;
-            ++launches[sp.kind];
+            launches[sp.kind] += sp.dispatches;
         }
         spans.clear();
         used = 0;
@@ -845,7 +845,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(C.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
                 P2_HIP(C.f_unk[li].ensure(n_s[li]));
             }
-            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream));
+            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream, (n_s[0] > 0) + (n_s[1] > 0)));
             for (int li = 0; li < 2; ++li)
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li],
                                              grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
