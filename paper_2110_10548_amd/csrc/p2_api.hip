@@ -83,6 +83,8 @@ struct Ctx {
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
     hipEvent_t copy_done = nullptr;
+    hipStream_t side_stream = nullptr;      // frontier engine: the literal prefixes of a level, beside the pair states
+    hipEvent_t side_go = nullptr, side_done = nullptr;
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs, h_fshare;
 };
 thread_local Ctx g_ctx;
@@ -150,6 +152,9 @@ void Ctx::release() {
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
     if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
     if (copy_stream) { (void)hipStreamDestroy(copy_stream); copy_stream = nullptr; }
+    if (side_go) { (void)hipEventDestroy(side_go); side_go = nullptr; }
+    if (side_done) { (void)hipEventDestroy(side_done); side_done = nullptr; }
+    if (side_stream) { (void)hipStreamDestroy(side_stream); side_stream = nullptr; }
 }
 Ctx::~Ctx() { if (std::this_thread::get_id() != g_loader_thread) release(); }
 void Prof::release() {
@@ -175,6 +180,7 @@ int32_t hip_fail(hipError_t e, const char* what) {
     if (g_call_active) {
         (void)hipStreamSynchronize(g_call_stream);
         if (g_ctx.copy_stream) (void)hipStreamSynchronize(g_ctx.copy_stream);
+        if (g_ctx.side_stream) (void)hipStreamSynchronize(g_ctx.side_stream);
         (void)hipGetLastError();
     }
     return P2_EDEVICE;
@@ -446,6 +452,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     if (!C.copy_stream) {
         P2_HIP(hipStreamCreateWithFlags(&C.copy_stream, hipStreamNonBlocking));
         P2_HIP(hipEventCreateWithFlags(&C.copy_done, hipEventDisableTiming));
+        P2_HIP(hipStreamCreateWithFlags(&C.side_stream, hipStreamNonBlocking));
+        P2_HIP(hipEventCreateWithFlags(&C.side_go, hipEventDisableTiming));
+        P2_HIP(hipEventCreateWithFlags(&C.side_done, hipEventDisableTiming));
     }
     auto build_and_upload_rows = [&]() -> int32_t {
         if (rows_ready) return P2_OK;
@@ -845,6 +854,25 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(C.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
                 P2_HIP(C.f_unk[li].ensure(n_s[li]));
             }
+            // The literal prefixes of the level are judged on a second stream while the pair states are (their kernels are
+            // a wavefront per prefix and leave most of the chip idle); the two meet before the counters go to the host.
+            auto literal_on_side = [&]() -> int32_t {
+                if (n_l == 0) return P2_OK;
+                P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
+                P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
+                gs = C.lit_scratch.p;
+                P2_HIP(hipEventRecord(C.side_go, stream));
+                P2_HIP(hipStreamWaitEvent(C.side_stream, C.side_go, 0));
+                P2_HIP(g_prof.begin(Prof::kLiteral, C.side_stream));
+                P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len, keep ? 0 : 1,
+                                                     static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
+                                                     pl.max_row_classes, C.side_stream));
+                P2_HIP(g_prof.end(C.side_stream));
+                P2_HIP(hipEventRecord(C.side_done, C.side_stream));
+                return P2_OK;
+            };
+            P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+            { const int32_t rc = literal_on_side(); if (rc != P2_OK) return rc; }
             if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream, (n_s[0] > 0) + (n_s[1] > 0)));
             for (int li = 0; li < 2; ++li)
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li],
@@ -852,10 +880,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                              grouped[li] ? &dctr->n_reps[li] : nullptr, li + 1, max_pairs,
                                              static_cast<uint8_t*>(C.f_codes[li].p), static_cast<uint8_t*>(C.f_unk[li].p), stream));
             if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.end(stream));
-            for (;;) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
+            for (int attempt = 0;; ++attempt) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
                 P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
-                P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
-                P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+                if (attempt > 0) {
+                    P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+                    const int32_t rc = literal_on_side();
+                    if (rc != P2_OK) return rc;
+                }
                 if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
                 P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries[cur].p), n_c,
                                            static_cast<const uint32_t*>(C.f_sid[cur].p),
@@ -874,15 +905,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                                  static_cast<const uint8_t*>(C.f_unk[li].p), li + 1, keep, 0, nullptr, nullptr, dctr, stream));
                 }
                 if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
-                if (n_l > 0) {
-                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
-                    gs = C.lit_scratch.p;
-                    P2_HIP(g_prof.begin(Prof::kLiteral, stream));
-                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len, keep ? 0 : 1,
-                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
-                                                         pl.max_row_classes, stream));
-                    P2_HIP(g_prof.end(stream));
-                }
+                if (n_l > 0) P2_HIP(hipStreamWaitEvent(stream, C.side_done, 0));
                 P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
                 P2_HIP(hipStreamSynchronize(stream));
                 n_surv_l_first = hctr->n_surv_literal;
