@@ -22,8 +22,10 @@ set, mask) pairs of every device that a pattern of the alphabet visits, set agai
 been judged on its own); the same words are read from LDS once per pattern (`roofline.lds`, against
 256 bytes per clock and compute unit) and the state comes from device memory once (`roofline.hbm`).
 `materialize` prices the kernel that builds the children of the judged states against HBM.  Times
-are HIP-event times around every launch of the family on the call's stream, taken inside the timed
-steps (p2_get_profile).
+are HIP-event times around every launch of the family on the stream it is launched on, taken inside
+the timed steps (p2_get_profile).  The library runs up to four enumerations of a batch side by
+side, so those are times of kernels that share the chip; `one_enumeration_at_a_time` gives the same
+objects for a few steps with the enumerations one after the other.
 For the flat engines (configurations 1-4 with the default engine) the roofline is the lane-operation
 rate of the evaluation kernel, as `other_configs` reports per configuration.
 `cpu_baseline` times the plain CPU oracle on a bounded sample of the same workload.
@@ -328,6 +330,14 @@ def main():
                 "steps_evaluated_per_step"):
         if key in head:
             out[key] = head[key]
+    if 3 in head["engines_used"]:
+        # The timed steps run up to four enumerations side by side, so the event time of a launch there is the time of
+        # a kernel that shares the chip.  The same batch with the enumerations one after the other, a few steps: what
+        # the kernels reach with the chip to themselves.
+        alone = report(timed(queries, msg, args.engine, max(args.steps // 5, 2), 1, B.FLAG_ONE_ENUMERATION_AT_A_TIME), args.config, args.engine)
+        out["one_enumeration_at_a_time"] = {"ms_per_step": alone["ms_per_step"], "steps": alone["steps"],
+                                            "device_ms_per_step": alone["device_ms_per_step"], "roofline": alone["roofline"],
+                                            "materialize": alone["materialize"]}
 
     if not args.no_compare:
         # the other configurations, a few steps each with the default engine, and where that is the shared-prefix

@@ -150,6 +150,11 @@ typedef struct {
 #define P2_FLAG_EVALUATE_EVERY_QUERY 1u   /* p2_synthesize_batch: do not share the evaluation of queries
                                              that are equal in everything validity depends on (see
                                              there); set on any query of the batch, it holds for all  */
+#define P2_FLAG_ONE_ENUMERATION_AT_A_TIME 2u /* frontier engine: run the enumerations of the batch one after
+                                             the other on one stream instead of several side by side
+                                             (results are the same; the per-kernel times of p2_profile are
+                                             then those of kernels that have the chip to themselves); set
+                                             on any query of the batch, it holds for all                */
 
 /* One program.  instr[t] = pattern_id * 5 + op, op in the order AllReduce, ReduceScatter,
  * AllGather, Reduce, Broadcast; pattern ids are those of p2_describe_pattern.  index is the

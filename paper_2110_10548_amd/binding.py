@@ -161,6 +161,7 @@ HIERARCHY = {"collapsed": 0, "system": 1, "column": 2, "row": 3, "reduction": 4}
 
 
 FLAG_EVALUATE_EVERY_QUERY = 1
+FLAG_ONE_ENUMERATION_AT_A_TIME = 2
 
 
 def _options(n_chunks=0, form_mask=7, op_mask=31, algo=0, topk=0, engine=ENGINE_AUTO, stream=None, hierarchy=0, flags=0,

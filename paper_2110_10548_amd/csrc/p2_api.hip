@@ -70,37 +70,11 @@ struct HostBuf {
     }
 };
 
-// Device scratch owned by the library, one set per host thread, reused between calls.
-struct Ctx {
-    ~Ctx();
-    void release();
-    DevBuf rows, rows_hdr;
-    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
-    DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];   // frontier engine
-    DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, f_valid, f_gsums, f_rank, f_share;
-    DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
-    DevBuf f_sid[2], f_sid2[2], f_delta[3], f_childof[2], f_ssurv;                           // prefixes -> states -> children
-    HostBuf h_rows, h_rows_hdr;
-    hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
-    hipEvent_t copy_done = nullptr;
-    hipStream_t side_stream = nullptr;      // frontier engine: the literal prefixes of a level, beside the pair states
-    hipEvent_t side_go = nullptr, side_done = nullptr;
-    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_fctr, h_topk_jobs, h_fshare;
-};
-thread_local Ctx g_ctx;
-
-// Frontier lists shorter than this are judged entry by entry: grouping them by state would cost more than it saves.
-constexpr uint32_t kGroupMin = 256;
-
-struct Prof {
-    ~Prof();
-    void release();
-    bool on = false;
-    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};     // evaluation begin / end, post end, frontier begin / end
-    p2_profile last = {};
-    // events around single launches of the frontier engine: a pool that grows on demand and is kept
+// Event pairs around single launches: a pool that grows on demand and is kept.
+struct SpanRec {
     enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kGroup = 3, kKinds = 4 };
     struct Span { int kind; size_t first; int dispatches; };
+    bool on = false;
     std::vector<hipEvent_t> pool;
     std::vector<Span> spans;
     size_t used = 0;
@@ -117,9 +91,9 @@ struct Prof {
         return hipEventRecord(pool[used - 2], stream);
     }
     hipError_t end(hipStream_t stream) { return on ? hipEventRecord(pool[used - 1], stream) : hipSuccess; }
-    // after the stream has been waited for: time per kind, launches per kind
+    void reset() { spans.clear(); used = 0; }
+    // after the stream has been waited for: time and launches per kind, added to what is there
     hipError_t collect(float ms[kKinds], int32_t launches[kKinds]) {
-        for (int k = 0; k < kKinds; ++k) { ms[k] = 0.f; launches[k] = 0; }
         for (const Span& sp : spans) {
             float t = 0.f;
             const hipError_t rc = hipEventElapsedTime(&t, pool[sp.first], pool[sp.first + 1]);
@@ -127,10 +101,84 @@ struct Prof {
             ms[sp.kind] += t;
             launches[sp.kind] += sp.dispatches;
         }
-        spans.clear();
-        used = 0;
+        reset();
         return hipSuccess;
     }
+    void release() {
+        for (auto& e : pool) (void)hipEventDestroy(e);
+        pool.clear(); reset();
+    }
+};
+
+// What one enumeration of the frontier engine works in: its own stream (and a second one for the literal prefixes
+// of a level), its lists, its counters.  A call runs as many enumerations side by side as there are slots, a host
+// thread each: an enumeration is a chain of small launches with one host wait per level, and several chains fill
+// the chip where one does not.
+constexpr int kFrontSlots = 4;
+struct FrontSlot {
+    hipStream_t stream = nullptr, side_stream = nullptr;
+    hipEvent_t side_go = nullptr, side_done = nullptr;
+    DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];
+    DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, lit_scratch;
+    DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
+    DevBuf f_sid[2], f_sid2[2], f_delta[3], f_childof[2], f_ssurv;                           // prefixes -> states -> children
+    HostBuf h_fctr;
+    SpanRec spans;
+    // what the slot's launches of this call worked on (the figures of p2_profile)
+    double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0, prof_entries = 0.0;
+    int32_t rc = 0;
+    std::string err;
+    hipError_t open() {
+        if (stream) return hipSuccess;
+        hipError_t e = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipStreamCreateWithFlags(&side_stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&side_go, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&side_done, hipEventDisableTiming);
+        return e;
+    }
+    void release() {
+        DevBuf* dev[] = {&f_entries[0], &f_entries[1], &f_states[0], &f_states[1], &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1],
+                         &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1], &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal,
+                         &f_unknown, &f_ctr, &lit_scratch, &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1],
+                         &f_replist[0], &f_replist[1], &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1], &f_sid[0], &f_sid[1], &f_sid2[0],
+                         &f_sid2[1], &f_delta[0], &f_delta[1], &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv};
+        for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
+        if (h_fctr.p) (void)hipHostFree(h_fctr.p);
+        h_fctr.p = nullptr; h_fctr.cap = 0;
+        spans.release();
+        if (side_go) { (void)hipEventDestroy(side_go); side_go = nullptr; }
+        if (side_done) { (void)hipEventDestroy(side_done); side_done = nullptr; }
+        if (side_stream) { (void)hipStreamDestroy(side_stream); side_stream = nullptr; }
+        if (stream) { (void)hipStreamDestroy(stream); stream = nullptr; }
+    }
+};
+
+// Device scratch owned by the library, one set per host thread, reused between calls.
+struct Ctx {
+    ~Ctx();
+    void release();
+    DevBuf rows, rows_hdr;
+    DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
+    DevBuf f_rank, f_share;                                 // frontier engine: ranks of the valid programs, queries of the enumerations
+    std::vector<DevBuf> f_evalid, f_egsums;                 // ... per enumeration: valid candidate indices, their cost sums
+    FrontSlot slots[kFrontSlots];
+    hipEvent_t front_go = nullptr;                          // the call's stream has reached the enumerations
+    HostBuf h_rows, h_rows_hdr;
+    hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
+    hipEvent_t copy_done = nullptr;
+    HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_topk_jobs, h_fshare;
+};
+thread_local Ctx g_ctx;
+
+// Frontier lists shorter than this are judged entry by entry: grouping them by state would cost more than it saves.
+constexpr uint32_t kGroupMin = 256;
+
+struct Prof {
+    ~Prof();
+    void release();
+    bool on = false;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};     // evaluation begin / end, post end, frontier begin / end
+    p2_profile last = {};
 };
 thread_local Prof g_prof;
 
@@ -141,26 +189,22 @@ const std::thread::id g_loader_thread = std::this_thread::get_id();
 
 void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
-                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_entries[0], &f_entries[1], &f_states[0], &f_states[1],
-                     &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1], &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1],
-                     &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal, &f_unknown, &f_ctr, &f_valid, &f_gsums, &f_rank, &f_share,
-                     &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1], &f_replist[0], &f_replist[1],
-                     &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1], &f_sid[0], &f_sid[1], &f_sid2[0], &f_sid2[1], &f_delta[0], &f_delta[1],
-                     &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv};
+                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
-    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_fctr, &h_topk_jobs, &h_fshare};
+    for (auto* v : {&f_evalid, &f_egsums}) {
+        for (DevBuf& b : *v) if (b.p) (void)hipFree(b.p);
+        v->clear();
+    }
+    for (FrontSlot& sl : slots) sl.release();
+    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
+    if (front_go) { (void)hipEventDestroy(front_go); front_go = nullptr; }
     if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
     if (copy_stream) { (void)hipStreamDestroy(copy_stream); copy_stream = nullptr; }
-    if (side_go) { (void)hipEventDestroy(side_go); side_go = nullptr; }
-    if (side_done) { (void)hipEventDestroy(side_done); side_done = nullptr; }
-    if (side_stream) { (void)hipStreamDestroy(side_stream); side_stream = nullptr; }
 }
 Ctx::~Ctx() { if (std::this_thread::get_id() != g_loader_thread) release(); }
 void Prof::release() {
     for (auto& e : ev) { if (e) (void)hipEventDestroy(e); e = nullptr; }
-    for (auto& e : pool) (void)hipEventDestroy(e);
-    pool.clear(); spans.clear(); used = 0;
     on = false;
 }
 Prof::~Prof() { if (std::this_thread::get_id() != g_loader_thread) release(); }
@@ -180,7 +224,6 @@ int32_t hip_fail(hipError_t e, const char* what) {
     if (g_call_active) {
         (void)hipStreamSynchronize(g_call_stream);
         if (g_ctx.copy_stream) (void)hipStreamSynchronize(g_ctx.copy_stream);
-        if (g_ctx.side_stream) (void)hipStreamSynchronize(g_ctx.side_stream);
         (void)hipGetLastError();
     }
     return P2_EDEVICE;
@@ -320,7 +363,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
         }
     }
-    g_prof.spans.clear(); g_prof.used = 0;       // (a call that failed half-way leaves its spans behind)
     g_prof.last.host_plan_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     // ---- lay out the table blob: queries, message sizes, bandwidth rows
     size_t off = 0;
@@ -452,9 +494,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     if (!C.copy_stream) {
         P2_HIP(hipStreamCreateWithFlags(&C.copy_stream, hipStreamNonBlocking));
         P2_HIP(hipEventCreateWithFlags(&C.copy_done, hipEventDisableTiming));
-        P2_HIP(hipStreamCreateWithFlags(&C.side_stream, hipStreamNonBlocking));
-        P2_HIP(hipEventCreateWithFlags(&C.side_go, hipEventDisableTiming));
-        P2_HIP(hipEventCreateWithFlags(&C.side_done, hipEventDisableTiming));
+        P2_HIP(hipEventCreateWithFlags(&C.front_go, hipEventDisableTiming));
     }
     auto build_and_upload_rows = [&]() -> int32_t {
         if (rows_ready) return P2_OK;
@@ -751,9 +791,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     // ---- frontier queries: enumeration by program size (Sec. 3.5).  Queries that agree in everything validity
     //      depends on form one enumeration; its prefixes carry the running cost sums of every member query.
     struct Enum {
-        int leader = -1;
+        int leader = -1, id = 0;
         std::vector<int32_t> members;
-        size_t off_valid = 0, off_sums = 0, off_share = 0;     // element offsets into f_valid / f_rank, f_gsums, f_share
+        size_t off_valid = 0, off_share = 0;     // element offsets into f_rank, f_share
         uint32_t n_valid = 0, n_goal_literal = 0;
     };
     std::vector<Enum> enums;
@@ -790,17 +830,16 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         for (auto& E : enums) std::memcpy(static_cast<int32_t*>(C.h_fshare.p) + E.off_share, E.members.data(), sizeof(int32_t) * E.members.size());
         P2_HIP(hipMemcpyAsync(C.f_share.p, C.h_fshare.p, sizeof(int32_t) * n_share_all, hipMemcpyHostToDevice, stream));
     }
-    size_t fvalid_used = 0, fsums_used = 0;
-    // what the frontier kernels' launches of this call worked on (the figures of p2_profile)
-    double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0, prof_entries = 0.0;
-    if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[3], stream));
-    for (auto& E : enums) {
+    // ---- the enumerations, up to kFrontSlots of them side by side (a host thread and a stream each); they start
+    //      once the call's stream has got here, and the call's stream goes on when they are all through
+    auto run_enum = [&](Enum& E, FrontSlot& S) -> int32_t {
         const int i = E.leader;
+        DevBuf& EV = C.f_evalid[E.id];
+        DevBuf& EG = C.f_egsums[E.id];
         QueryRun& r = runs[i];
         const Plan& pl = r.plan;
         const int n_share = (int)E.members.size();
         const size_t sum_doubles = n_msg > 0 ? (size_t)2 * n_share : 0;      // per prefix / per goal
-        E.off_valid = fvalid_used; E.off_sums = fsums_used;
         const DevQuery* dq = reinterpret_cast<const DevQuery*>(db + r.off_query);
         const size_t sw = frontier_state_words(pl.R, pl.k);
         // words of a device's (chunk set, mask) pair, and the devices that the alphabet's patterns visit per prefix
@@ -812,31 +851,31 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         // classified by the literal kernels (the path of prefixes whose groups are not aligned)
         const int fp = pl.frontier_pairs;
         const int max_pairs = fp == P2_FRONTIER_PAIRS_NONE ? 0 : fp == P2_FRONTIER_PAIRS_ONE ? 1 : frontier_max_pairs(pl.R, pl.k);
-        P2_HIP(C.f_ctr.ensure(sizeof(FrontCounters)));
-        P2_HIP(C.h_fctr.ensure(sizeof(FrontCounters)));
-        FrontCounters* dctr = static_cast<FrontCounters*>(C.f_ctr.p);
-        const FrontCounters* hctr = static_cast<const FrontCounters*>(C.h_fctr.p);
-        P2_HIP(hipMemsetAsync(dctr, 0, sizeof(FrontCounters), stream));
+        P2_HIP(S.f_ctr.ensure(sizeof(FrontCounters)));
+        P2_HIP(S.h_fctr.ensure(sizeof(FrontCounters)));
+        FrontCounters* dctr = static_cast<FrontCounters*>(S.f_ctr.p);
+        const FrontCounters* hctr = static_cast<const FrontCounters*>(S.h_fctr.p);
+        P2_HIP(hipMemsetAsync(dctr, 0, sizeof(FrontCounters), S.stream));
         int cur = 0;
-        P2_HIP(C.f_entries[cur].ensure(sizeof(FrontEntry)));
-        P2_HIP(C.f_states[cur].ensure(sw * 4));
-        P2_HIP(C.f_sums[cur].ensure(std::max<size_t>(sum_doubles, 1) * 8));
-        P2_HIP(C.f_sid[cur].ensure(sizeof(uint32_t)));
-        P2_HIP(C.f_literal[cur].ensure(sizeof(FrontEntry)));
+        P2_HIP(S.f_entries[cur].ensure(sizeof(FrontEntry)));
+        P2_HIP(S.f_states[cur].ensure(sw * 4));
+        P2_HIP(S.f_sums[cur].ensure(std::max<size_t>(sum_doubles, 1) * 8));
+        P2_HIP(S.f_sid[cur].ensure(sizeof(uint32_t)));
+        P2_HIP(S.f_literal[cur].ensure(sizeof(FrontEntry)));
         // A level: two lists of states (one pair per device; up to two) with n_s entries, of which the distinct ones
         // are judged; two lists of prefixes (n_c, n_c2 entries), each prefix with the index of its state; the
         // literal list (n_l prefixes that are judged from their instructions).
         uint32_t n_s[2] = {0, 0}, n_c = 0, n_c2 = 0, n_l = 0;
         bool grouped[2] = {false, false};            // the state list has been searched for equal states
         if (max_pairs >= 1) {
-            P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(C.f_entries[cur].p),
-                                     static_cast<uint32_t*>(C.f_states[cur].p), static_cast<double*>(C.f_sums[cur].p),
-                                     static_cast<uint32_t*>(C.f_sid[cur].p), (int)sum_doubles / 2, stream));
+            P2_HIP(launch_front_init(dq, (uint32_t)i, pl.R, pl.k, static_cast<FrontEntry*>(S.f_entries[cur].p),
+                                     static_cast<uint32_t*>(S.f_states[cur].p), static_cast<double*>(S.f_sums[cur].p),
+                                     static_cast<uint32_t*>(S.f_sid[cur].p), (int)sum_doubles / 2, S.stream));
             n_c = 1; n_s[0] = 1;
         } else {
             const FrontEntry root{(uint32_t)i, 0u, 0ull};
-            P2_HIP(hipMemcpyAsync(C.f_literal[cur].p, &root, sizeof root, hipMemcpyHostToDevice, stream));
-            P2_HIP(hipStreamSynchronize(stream));
+            P2_HIP(hipMemcpyAsync(S.f_literal[cur].p, &root, sizeof root, hipMemcpyHostToDevice, S.stream));
+            P2_HIP(hipStreamSynchronize(S.stream));
             n_l = 1;
         }
         void* gs = nullptr;
@@ -846,99 +885,99 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             size_t cap_c = std::max<size_t>(1024, ((size_t)n_c + n_c2) * pl.alphabet / 8);
             size_t cap_l = std::max<size_t>(1024, ((size_t)n_l + n_c2 / 8) * pl.alphabet / 2);
             uint32_t n_surv_l_first = 0;
-            P2_HIP(C.f_unknown.ensure(std::max<size_t>(n_c2, 1) * sizeof(FrontEntry)));
-            const DevBuf* list_states[2] = {&C.f_states[cur], &C.f_states2[cur]};
+            P2_HIP(S.f_unknown.ensure(std::max<size_t>(n_c2, 1) * sizeof(FrontEntry)));
+            const DevBuf* list_states[2] = {&S.f_states[cur], &S.f_states2[cur]};
             // ---- one state of every group of equal states is judged against the alphabet, into a row of codes
             for (int li = 0; li < 2; ++li) {
                 if (n_s[li] == 0) continue;
-                P2_HIP(C.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
-                P2_HIP(C.f_unk[li].ensure(n_s[li]));
+                P2_HIP(S.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
+                P2_HIP(S.f_unk[li].ensure(n_s[li]));
             }
-            // The literal prefixes of the level are judged on a second stream while the pair states are (their kernels are
+            // The literal prefixes of the level are judged on a second S.stream while the pair states are (their kernels are
             // a wavefront per prefix and leave most of the chip idle); the two meet before the counters go to the host.
             auto literal_on_side = [&]() -> int32_t {
                 if (n_l == 0) return P2_OK;
-                P2_HIP(C.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
-                P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
-                gs = C.lit_scratch.p;
-                P2_HIP(hipEventRecord(C.side_go, stream));
-                P2_HIP(hipStreamWaitEvent(C.side_stream, C.side_go, 0));
-                P2_HIP(g_prof.begin(Prof::kLiteral, C.side_stream));
-                P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_literal[cur].p), n_l, len, keep ? 0 : 1,
-                                                     static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
-                                                     pl.max_row_classes, C.side_stream));
-                P2_HIP(g_prof.end(C.side_stream));
-                P2_HIP(hipEventRecord(C.side_done, C.side_stream));
+                P2_HIP(S.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
+                P2_HIP(S.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
+                gs = S.lit_scratch.p;
+                P2_HIP(hipEventRecord(S.side_go, S.stream));
+                P2_HIP(hipStreamWaitEvent(S.side_stream, S.side_go, 0));
+                P2_HIP(S.spans.begin(SpanRec::kLiteral, S.side_stream));
+                P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(S.f_literal[cur].p), n_l, len, keep ? 0 : 1,
+                                                     static_cast<FrontSurvivor*>(S.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
+                                                     pl.max_row_classes, S.side_stream));
+                P2_HIP(S.spans.end(S.side_stream));
+                P2_HIP(hipEventRecord(S.side_done, S.side_stream));
                 return P2_OK;
             };
-            P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+            P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
             { const int32_t rc = literal_on_side(); if (rc != P2_OK) return rc; }
-            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.begin(Prof::kClassify, stream, (n_s[0] > 0) + (n_s[1] > 0)));
+            if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.begin(SpanRec::kClassify, S.stream, (n_s[0] > 0) + (n_s[1] > 0)));
             for (int li = 0; li < 2; ++li)
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li],
-                                             grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
+                                             grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr,
                                              grouped[li] ? &dctr->n_reps[li] : nullptr, li + 1, max_pairs,
-                                             static_cast<uint8_t*>(C.f_codes[li].p), static_cast<uint8_t*>(C.f_unk[li].p), stream));
-            if (n_s[0] + n_s[1] > 0) P2_HIP(g_prof.end(stream));
+                                             static_cast<uint8_t*>(S.f_codes[li].p), static_cast<uint8_t*>(S.f_unk[li].p), S.stream));
+            if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.end(S.stream));
             for (int attempt = 0;; ++attempt) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
-                P2_HIP(C.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
+                P2_HIP(S.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 if (attempt > 0) {
-                    P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), stream));
+                    P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
                     const int32_t rc = literal_on_side();
                     if (rc != P2_OK) return rc;
                 }
-                if (n_c + n_c2 > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
-                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries[cur].p), n_c,
-                                           static_cast<const uint32_t*>(C.f_sid[cur].p),
-                                           static_cast<const uint8_t*>(C.f_codes[0].p), static_cast<const uint8_t*>(C.f_unk[0].p), 1, 0,
-                                           static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c, nullptr, dctr, stream));
-                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(C.f_entries2[cur].p), n_c2,
-                                           static_cast<const uint32_t*>(C.f_sid2[cur].p),
-                                           static_cast<const uint8_t*>(C.f_codes[1].p), static_cast<const uint8_t*>(C.f_unk[1].p), 2, handover,
-                                           static_cast<FrontSurvivor*>(C.f_surv.p), (uint32_t)cap_c,
-                                           static_cast<FrontEntry*>(C.f_unknown.p), dctr, stream));
+                if (n_c + n_c2 > 0) P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
+                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(S.f_entries[cur].p), n_c,
+                                           static_cast<const uint32_t*>(S.f_sid[cur].p),
+                                           static_cast<const uint8_t*>(S.f_codes[0].p), static_cast<const uint8_t*>(S.f_unk[0].p), 1, 0,
+                                           static_cast<FrontSurvivor*>(S.f_surv.p), (uint32_t)cap_c, nullptr, dctr, S.stream));
+                P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(S.f_entries2[cur].p), n_c2,
+                                           static_cast<const uint32_t*>(S.f_sid2[cur].p),
+                                           static_cast<const uint8_t*>(S.f_codes[1].p), static_cast<const uint8_t*>(S.f_unk[1].p), 2, handover,
+                                           static_cast<FrontSurvivor*>(S.f_surv.p), (uint32_t)cap_c,
+                                           static_cast<FrontEntry*>(S.f_unknown.p), dctr, S.stream));
                 // (how many children the judged states have, by kind)
                 for (int li = 0; li < 2; ++li) {
                     if (li == 1 && handover) continue;
-                    P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
-                                                 grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(C.f_codes[li].p),
-                                                 static_cast<const uint8_t*>(C.f_unk[li].p), li + 1, keep, 0, nullptr, nullptr, dctr, stream));
+                    P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr,
+                                                 grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(S.f_codes[li].p),
+                                                 static_cast<const uint8_t*>(S.f_unk[li].p), li + 1, keep, 0, nullptr, nullptr, dctr, S.stream));
                 }
-                if (n_c + n_c2 > 0) P2_HIP(g_prof.end(stream));
-                if (n_l > 0) P2_HIP(hipStreamWaitEvent(stream, C.side_done, 0));
-                P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
-                P2_HIP(hipStreamSynchronize(stream));
+                if (n_c + n_c2 > 0) P2_HIP(S.spans.end(S.stream));
+                if (n_l > 0) P2_HIP(hipStreamWaitEvent(S.stream, S.side_done, 0));
+                P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
+                P2_HIP(hipStreamSynchronize(S.stream));
                 n_surv_l_first = hctr->n_surv_literal;
                 if (hctr->n_unknown > 0 && hctr->n_surv_literal <= cap_l) {
                     // two-pair prefixes that this form could not judge: the literal kernels classify them from their
                     // instructions; their survivors follow those of the literal list
                     const uint32_t n_u = hctr->n_unknown;
-                    P2_HIP(hipMemsetAsync(&dctr->n_overflow, 0, sizeof(uint32_t), stream));
-                    P2_HIP(C.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(std::max(n_l, n_c2), n_u))));
-                    gs = C.lit_scratch.p;
-                    P2_HIP(g_prof.begin(Prof::kLiteral, stream));
-                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(C.f_unknown.p), n_u, len, keep ? 0 : 1,
-                                                         static_cast<FrontSurvivor*>(C.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
-                                                         pl.max_row_classes, stream));
-                    P2_HIP(g_prof.end(stream));
-                    P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
-                    P2_HIP(hipStreamSynchronize(stream));
+                    P2_HIP(hipMemsetAsync(&dctr->n_overflow, 0, sizeof(uint32_t), S.stream));
+                    P2_HIP(S.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(std::max(n_l, n_c2), n_u))));
+                    gs = S.lit_scratch.p;
+                    P2_HIP(S.spans.begin(SpanRec::kLiteral, S.stream));
+                    P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(S.f_unknown.p), n_u, len, keep ? 0 : 1,
+                                                         static_cast<FrontSurvivor*>(S.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
+                                                         pl.max_row_classes, S.stream));
+                    P2_HIP(S.spans.end(S.stream));
+                    P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
+                    P2_HIP(hipStreamSynchronize(S.stream));
                 }
                 if ((uint32_t)hctr->surv_goal <= cap_c && hctr->n_surv_literal <= cap_l) break;
                 // the repeated listing counts its steps again: take them back
                 cap_c = std::max<size_t>(cap_c, (uint32_t)hctr->surv_goal); cap_l = std::max<size_t>(cap_l, (size_t)hctr->n_surv_literal * 2);
                 FrontCounters fix = *hctr;
                 fix.steps = r.steps; fix.members = r.members;
-                P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, stream));
-                P2_HIP(hipStreamSynchronize(stream));
+                P2_HIP(hipMemcpyAsync(dctr, &fix, sizeof(FrontCounters), hipMemcpyHostToDevice, S.stream));
+                P2_HIP(hipStreamSynchronize(S.stream));
             }
             {   // what the classification launches of this level worked on
                 const double j1 = grouped[0] ? (double)hctr->n_reps[0] : (double)n_s[0], j2 = grouped[1] ? (double)hctr->n_reps[1] : (double)n_s[1];
                 const double planes = j1 + 2.0 * j2;
-                prof_entries += (double)n_c + n_c2;
-                prof_prefixes += j1 + j2;
-                prof_state_bytes += planes * pl.R * pair_words * 4.0;
-                prof_lane_ops += planes * pattern_members * pair_words * 4.0;
+                S.prof_entries += (double)n_c + n_c2;
+                S.prof_prefixes += j1 + j2;
+                S.prof_state_bytes += planes * pl.R * pair_words * 4.0;
+                S.prof_lane_ops += planes * pattern_members * pair_words * 4.0;
             }
             const uint32_t n_surv = (uint32_t)hctr->surv_goal, n_surv_l = hctr->n_surv_literal;
             const uint32_t n_goal_pair = (uint32_t)(hctr->surv_goal >> 32), n_goal_lit = hctr->n_goal, n_goal = n_goal_pair + n_goal_lit;
@@ -947,119 +986,117 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             r.steps = hctr->steps; r.members = hctr->members;
             r.n_rerun += n_plit + hctr->n_unknown;
             E.n_goal_literal += n_goal_lit;
-            P2_HIP(grow_keep(C.f_valid, (fvalid_used + E.n_valid + n_goal + 1) * sizeof(unsigned long long),
-                             (fvalid_used + E.n_valid) * sizeof(unsigned long long), stream));
-            P2_HIP(grow_keep(C.f_gsums, (fsums_used + ((size_t)E.n_valid + n_goal) * sum_doubles + 1) * sizeof(double),
-                             (fsums_used + (size_t)E.n_valid * sum_doubles) * sizeof(double), stream));
+            P2_HIP(grow_keep(EV, ((size_t)E.n_valid + n_goal + 1) * sizeof(unsigned long long), (size_t)E.n_valid * sizeof(unsigned long long), S.stream));
+            P2_HIP(grow_keep(EG, (((size_t)E.n_valid + n_goal) * sum_doubles + 1) * sizeof(double), (size_t)E.n_valid * sum_doubles * sizeof(double), S.stream));
             const int nxt = cur ^ 1;
             // the next level's prefixes ...
-            P2_HIP(C.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
-            P2_HIP(C.f_sums[nxt].ensure(std::max<size_t>((size_t)n_prefix * sum_doubles, 1) * 8));
-            P2_HIP(C.f_sid[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(uint32_t)));
-            P2_HIP(C.f_entries2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(FrontEntry)));
-            P2_HIP(C.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
-            P2_HIP(C.f_sid2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(uint32_t)));
-            P2_HIP(C.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
+            P2_HIP(S.f_entries[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(FrontEntry)));
+            P2_HIP(S.f_sums[nxt].ensure(std::max<size_t>((size_t)n_prefix * sum_doubles, 1) * 8));
+            P2_HIP(S.f_sid[nxt].ensure(std::max<size_t>(n_prefix, 1) * sizeof(uint32_t)));
+            P2_HIP(S.f_entries2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(FrontEntry)));
+            P2_HIP(S.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
+            P2_HIP(S.f_sid2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(uint32_t)));
+            P2_HIP(S.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
             // ... and states: a child per (judged state, valid instruction), its hash (added up from zero), what the step
             // adds to the cost sums; where a state's children are
-            P2_HIP(C.f_states[nxt].ensure(std::max<size_t>(t1, 1) * sw * 4));
-            P2_HIP(C.f_states2[nxt].ensure(std::max<size_t>(t2, 1) * sw * 8));
-            P2_HIP(C.f_hash[nxt].ensure(std::max<size_t>(t1, 1) * sizeof(unsigned long long)));
-            P2_HIP(C.f_hash2[nxt].ensure(std::max<size_t>(t2, 1) * sizeof(unsigned long long)));
-            P2_HIP(hipMemsetAsync(C.f_hash[nxt].p, 0, std::max<size_t>(t1, 1) * sizeof(unsigned long long), stream));
-            P2_HIP(hipMemsetAsync(C.f_hash2[nxt].p, 0, std::max<size_t>(t2, 1) * sizeof(unsigned long long), stream));
-            P2_HIP(C.f_delta[0].ensure(std::max<size_t>((size_t)t1 * sum_doubles, 1) * 8));
-            P2_HIP(C.f_delta[1].ensure(std::max<size_t>((size_t)t2 * sum_doubles, 1) * 8));
-            P2_HIP(C.f_delta[2].ensure(std::max<size_t>((size_t)tg * sum_doubles, 1) * 8));
-            P2_HIP(C.f_ssurv.ensure(std::max<size_t>(n_ss, 1) * sizeof(FrontSurvivor)));
-            for (int li = 0; li < 2; ++li) P2_HIP(C.f_childof[li].ensure(std::max<size_t>((size_t)n_s[li] * pl.alphabet, 1) * sizeof(uint32_t)));
-            if (n_ss > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
+            P2_HIP(S.f_states[nxt].ensure(std::max<size_t>(t1, 1) * sw * 4));
+            P2_HIP(S.f_states2[nxt].ensure(std::max<size_t>(t2, 1) * sw * 8));
+            P2_HIP(S.f_hash[nxt].ensure(std::max<size_t>(t1, 1) * sizeof(unsigned long long)));
+            P2_HIP(S.f_hash2[nxt].ensure(std::max<size_t>(t2, 1) * sizeof(unsigned long long)));
+            P2_HIP(hipMemsetAsync(S.f_hash[nxt].p, 0, std::max<size_t>(t1, 1) * sizeof(unsigned long long), S.stream));
+            P2_HIP(hipMemsetAsync(S.f_hash2[nxt].p, 0, std::max<size_t>(t2, 1) * sizeof(unsigned long long), S.stream));
+            P2_HIP(S.f_delta[0].ensure(std::max<size_t>((size_t)t1 * sum_doubles, 1) * 8));
+            P2_HIP(S.f_delta[1].ensure(std::max<size_t>((size_t)t2 * sum_doubles, 1) * 8));
+            P2_HIP(S.f_delta[2].ensure(std::max<size_t>((size_t)tg * sum_doubles, 1) * 8));
+            P2_HIP(S.f_ssurv.ensure(std::max<size_t>(n_ss, 1) * sizeof(FrontSurvivor)));
+            for (int li = 0; li < 2; ++li) P2_HIP(S.f_childof[li].ensure(std::max<size_t>((size_t)n_s[li] * pl.alphabet, 1) * sizeof(uint32_t)));
+            if (n_ss > 0) P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
             for (int li = 0; li < 2; ++li) {
                 if (li == 1 && handover) continue;
-                P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(C.f_replist[li].p) : nullptr,
-                                             grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(C.f_codes[li].p),
-                                             static_cast<const uint8_t*>(C.f_unk[li].p), li + 1, keep, 1, static_cast<uint32_t*>(C.f_childof[li].p),
-                                             static_cast<FrontSurvivor*>(C.f_ssurv.p), dctr, stream));
+                P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr,
+                                             grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(S.f_codes[li].p),
+                                             static_cast<const uint8_t*>(S.f_unk[li].p), li + 1, keep, 1, static_cast<uint32_t*>(S.f_childof[li].p),
+                                             static_cast<FrontSurvivor*>(S.f_ssurv.p), dctr, S.stream));
             }
-            if (n_ss > 0) P2_HIP(g_prof.end(stream));
+            if (n_ss > 0) P2_HIP(S.spans.end(S.stream));
             FrontLevel lv;
             std::memset(&lv, 0, sizeof lv);
             lv.query = (uint32_t)i;
             lv.share = static_cast<const int32_t*>(C.f_share.p) + E.off_share;
             lv.n_share = n_share; lv.n_msg = n_msg;
-            lv.states1 = static_cast<const uint32_t*>(C.f_states[cur].p); lv.states2 = static_cast<const uint32_t*>(C.f_states2[cur].p);
-            lv.surv = static_cast<const FrontSurvivor*>(C.f_ssurv.p); lv.n_surv = n_ss;
+            lv.states1 = static_cast<const uint32_t*>(S.f_states[cur].p); lv.states2 = static_cast<const uint32_t*>(S.f_states2[cur].p);
+            lv.surv = static_cast<const FrontSurvivor*>(S.f_ssurv.p); lv.n_surv = n_ss;
             lv.lds_planes = (n_s[1] > 0 || t2 > 0) ? 2 : 1;
-            lv.next_states1 = static_cast<uint32_t*>(C.f_states[nxt].p); lv.next_states2 = static_cast<uint32_t*>(C.f_states2[nxt].p);
-            lv.next_hash1 = static_cast<unsigned long long*>(C.f_hash[nxt].p); lv.next_hash2 = static_cast<unsigned long long*>(C.f_hash2[nxt].p);
-            lv.delta1 = static_cast<double*>(C.f_delta[0].p); lv.delta2 = static_cast<double*>(C.f_delta[1].p);
-            lv.delta_goal = static_cast<double*>(C.f_delta[2].p);
-            if (n_ss > 0) P2_HIP(g_prof.begin(Prof::kMaterialize, stream));
-            P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, stream));
+            lv.next_states1 = static_cast<uint32_t*>(S.f_states[nxt].p); lv.next_states2 = static_cast<uint32_t*>(S.f_states2[nxt].p);
+            lv.next_hash1 = static_cast<unsigned long long*>(S.f_hash[nxt].p); lv.next_hash2 = static_cast<unsigned long long*>(S.f_hash2[nxt].p);
+            lv.delta1 = static_cast<double*>(S.f_delta[0].p); lv.delta2 = static_cast<double*>(S.f_delta[1].p);
+            lv.delta_goal = static_cast<double*>(S.f_delta[2].p);
+            if (n_ss > 0) P2_HIP(S.spans.begin(SpanRec::kMaterialize, S.stream));
+            P2_HIP(launch_front_materialize(reinterpret_cast<const DevQuery*>(db), pl.R, pl.k, lv, S.stream));
             if (n_ss > 0) {
-                P2_HIP(g_prof.end(stream));
+                P2_HIP(S.spans.end(S.stream));
                 // every child reads its parent (one plane at least) and is written: state and what the step costs
-                prof_children += (double)n_ss;
-                prof_mat_bytes += ((double)n_ss + (double)t1 + 2.0 * t2) * pl.R * pair_words * 4.0 + (double)n_ss * (double)sum_doubles * 8.0;
+                S.prof_children += (double)n_ss;
+                S.prof_mat_bytes += ((double)n_ss + (double)t1 + 2.0 * t2) * pl.R * pair_words * 4.0 + (double)n_ss * (double)sum_doubles * 8.0;
             }
             // ---- the next state lists searched for equal states (hashes propose, a word-by-word comparison decides)
             const uint32_t n_next[2] = {t1, t2};
-            const DevBuf* next_states[2] = {&C.f_states[nxt], &C.f_states2[nxt]};
-            const DevBuf* next_hash[2] = {&C.f_hash[nxt], &C.f_hash2[nxt]};
+            const DevBuf* next_states[2] = {&S.f_states[nxt], &S.f_states2[nxt]};
+            const DevBuf* next_hash[2] = {&S.f_hash[nxt], &S.f_hash2[nxt]};
             bool grouped_next[2] = {false, false};
-            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, stream));
+            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, S.stream));
             for (int li = 0; li < 2; ++li) {
                 const uint32_t n = n_next[li];
                 grouped_next[li] = n >= kGroupMin && n < (1u << 24);
                 if (!grouped_next[li]) continue;
                 size_t table = 1024;
                 while (table < (size_t)n * 2) table *= 2;
-                P2_HIP(C.f_table.ensure(table * sizeof(unsigned long long)));
-                P2_HIP(C.f_rep[li].ensure((size_t)n * sizeof(uint32_t)));
-                P2_HIP(C.f_replist[li].ensure((size_t)n * sizeof(uint32_t)));
-                P2_HIP(g_prof.begin(Prof::kGroup, stream));
-                P2_HIP(hipMemsetAsync(C.f_table.p, 0xff, table * sizeof(unsigned long long), stream));
+                P2_HIP(S.f_table.ensure(table * sizeof(unsigned long long)));
+                P2_HIP(S.f_rep[li].ensure((size_t)n * sizeof(uint32_t)));
+                P2_HIP(S.f_replist[li].ensure((size_t)n * sizeof(uint32_t)));
+                P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
+                P2_HIP(hipMemsetAsync(S.f_table.p, 0xff, table * sizeof(unsigned long long), S.stream));
                 P2_HIP(launch_front_dedup(static_cast<const uint32_t*>(next_states[li]->p), sw * (li + 1),
                                           static_cast<const unsigned long long*>(next_hash[li]->p), n,
-                                          static_cast<unsigned long long*>(C.f_table.p), (uint32_t)table,
-                                          static_cast<uint32_t*>(C.f_rep[li].p), static_cast<uint32_t*>(C.f_replist[li].p),
-                                          &dctr->n_reps[li], stream));
-                P2_HIP(g_prof.end(stream));
+                                          static_cast<unsigned long long*>(S.f_table.p), (uint32_t)table,
+                                          static_cast<uint32_t*>(S.f_rep[li].p), static_cast<uint32_t*>(S.f_replist[li].p),
+                                          &dctr->n_reps[li], S.stream));
+                P2_HIP(S.spans.end(S.stream));
             }
             // ---- the next level's prefixes and this level's goals: those of the pair kernels at the places the listing
             //      gave them, then those of literal prefixes
-            unsigned long long* vout = static_cast<unsigned long long*>(C.f_valid.p) + fvalid_used + E.n_valid;
-            double* gsums = static_cast<double*>(C.f_gsums.p) + fsums_used + (size_t)E.n_valid * sum_doubles;
+            unsigned long long* vout = static_cast<unsigned long long*>(EV.p) + E.n_valid;
+            double* gsums = static_cast<double*>(EG.p) + (size_t)E.n_valid * sum_doubles;
             unsigned long long* vout_lit = vout + n_goal_pair;
             double* gsums_lit = gsums + (size_t)n_goal_pair * sum_doubles;
             FrontPrefixes px;
             std::memset(&px, 0, sizeof px);
             px.query = (uint32_t)i; px.n_share = n_share; px.n_msg = n_msg;
-            px.surv = static_cast<const FrontSurvivor*>(C.f_surv.p); px.n_surv = n_surv;
+            px.surv = static_cast<const FrontSurvivor*>(S.f_surv.p); px.n_surv = n_surv;
             px.parent_len = len; px.keep_prefixes = keep;
-            px.entries1 = static_cast<const FrontEntry*>(C.f_entries[cur].p); px.sid1 = static_cast<const uint32_t*>(C.f_sid[cur].p);
-            px.sums1 = static_cast<const double*>(C.f_sums[cur].p);
-            px.entries2 = static_cast<const FrontEntry*>(C.f_entries2[cur].p); px.sid2 = static_cast<const uint32_t*>(C.f_sid2[cur].p);
-            px.sums2 = static_cast<const double*>(C.f_sums2[cur].p);
-            px.child_of1 = static_cast<const uint32_t*>(C.f_childof[0].p); px.child_of2 = static_cast<const uint32_t*>(C.f_childof[1].p);
-            px.rep1 = grouped_next[0] ? static_cast<const uint32_t*>(C.f_rep[0].p) : nullptr;
-            px.rep2 = grouped_next[1] ? static_cast<const uint32_t*>(C.f_rep[1].p) : nullptr;
+            px.entries1 = static_cast<const FrontEntry*>(S.f_entries[cur].p); px.sid1 = static_cast<const uint32_t*>(S.f_sid[cur].p);
+            px.sums1 = static_cast<const double*>(S.f_sums[cur].p);
+            px.entries2 = static_cast<const FrontEntry*>(S.f_entries2[cur].p); px.sid2 = static_cast<const uint32_t*>(S.f_sid2[cur].p);
+            px.sums2 = static_cast<const double*>(S.f_sums2[cur].p);
+            px.child_of1 = static_cast<const uint32_t*>(S.f_childof[0].p); px.child_of2 = static_cast<const uint32_t*>(S.f_childof[1].p);
+            px.rep1 = grouped_next[0] ? static_cast<const uint32_t*>(S.f_rep[0].p) : nullptr;
+            px.rep2 = grouped_next[1] ? static_cast<const uint32_t*>(S.f_rep[1].p) : nullptr;
             px.delta1 = lv.delta1; px.delta2 = lv.delta2; px.delta_goal = lv.delta_goal;
-            px.next_entries1 = static_cast<FrontEntry*>(C.f_entries[nxt].p); px.next_sid1 = static_cast<uint32_t*>(C.f_sid[nxt].p);
-            px.next_sums1 = static_cast<double*>(C.f_sums[nxt].p);
-            px.next_entries2 = static_cast<FrontEntry*>(C.f_entries2[nxt].p); px.next_sid2 = static_cast<uint32_t*>(C.f_sid2[nxt].p);
-            px.next_sums2 = static_cast<double*>(C.f_sums2[nxt].p);
-            px.next_literal = static_cast<FrontEntry*>(C.f_literal[nxt].p);
+            px.next_entries1 = static_cast<FrontEntry*>(S.f_entries[nxt].p); px.next_sid1 = static_cast<uint32_t*>(S.f_sid[nxt].p);
+            px.next_sums1 = static_cast<double*>(S.f_sums[nxt].p);
+            px.next_entries2 = static_cast<FrontEntry*>(S.f_entries2[nxt].p); px.next_sid2 = static_cast<uint32_t*>(S.f_sid2[nxt].p);
+            px.next_sums2 = static_cast<double*>(S.f_sums2[nxt].p);
+            px.next_literal = static_cast<FrontEntry*>(S.f_literal[nxt].p);
             px.valid_out = vout; px.goal_sums = gsums; px.ctr = dctr;
-            if (n_surv > 0) P2_HIP(g_prof.begin(Prof::kGroup, stream));
-            P2_HIP(launch_front_prefixes(reinterpret_cast<const DevQuery*>(db), px, stream));
-            if (n_surv > 0) P2_HIP(g_prof.end(stream));
-            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_literal[cur].p),
-                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p), n_surv_l_first, len, keep,
-                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
-            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(C.f_unknown.p),
-                                     static_cast<const FrontSurvivor*>(C.f_surv_literal.p) + n_surv_l_first, n_surv_l - n_surv_l_first, len, keep,
-                                     static_cast<FrontEntry*>(C.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, stream));
+            if (n_surv > 0) P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
+            P2_HIP(launch_front_prefixes(reinterpret_cast<const DevQuery*>(db), px, S.stream));
+            if (n_surv > 0) P2_HIP(S.spans.end(S.stream));
+            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(S.f_literal[cur].p),
+                                     static_cast<const FrontSurvivor*>(S.f_surv_literal.p), n_surv_l_first, len, keep,
+                                     static_cast<FrontEntry*>(S.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, S.stream));
+            P2_HIP(launch_front_emit(dq, (uint32_t)i, static_cast<const FrontEntry*>(S.f_unknown.p),
+                                     static_cast<const FrontSurvivor*>(S.f_surv_literal.p) + n_surv_l_first, n_surv_l - n_surv_l_first, len, keep,
+                                     static_cast<FrontEntry*>(S.f_literal[nxt].p), vout_lit, gsums_lit, (int)sum_doubles / 2, dctr, S.stream));
             E.n_valid += n_goal;
             n_c = keep ? n_prefix : 0;
             n_c2 = keep ? n_prefix2 : 0;
@@ -1069,23 +1106,76 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             cur = nxt;
         }
         // steps of the last level
-        P2_HIP(launch_copy_out(C.h_fctr.p, dctr, sizeof(FrontCounters), stream));
-        P2_HIP(hipStreamSynchronize(stream));
+        P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
+        P2_HIP(hipStreamSynchronize(S.stream));
         r.steps = hctr->steps; r.members = hctr->members;
-        fvalid_used += E.n_valid;
-        fsums_used += (size_t)E.n_valid * sum_doubles;
         for (int32_t m : E.members) {        // every query of the enumeration reports its counts
             QueryRun& o = runs[m];
             o.n_valid = E.n_valid; o.n_rerun = r.n_rerun; o.steps = r.steps; o.members = r.members;
         }
+        return P2_OK;
+    };
+    if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[3], stream));
+    if (!enums.empty()) {
+        for (size_t e = 0; e < enums.size(); ++e) enums[e].id = (int)e;
+        if (C.f_evalid.size() < enums.size()) { C.f_evalid.resize(enums.size()); C.f_egsums.resize(enums.size()); }
+        bool one_at_a_time = false;
+        for (int i = 0; i < n_queries; ++i)
+            one_at_a_time |= queries[i].opt && (queries[i].opt->flags & P2_FLAG_ONE_ENUMERATION_AT_A_TIME) != 0u;
+        const int n_slots = one_at_a_time ? 1 : (int)std::min<size_t>(kFrontSlots, enums.size());
+        P2_HIP(hipEventRecord(C.front_go, stream));
+        for (int t = 0; t < n_slots; ++t) {
+            FrontSlot& S = C.slots[t];
+            P2_HIP(S.open());
+            P2_HIP(hipStreamWaitEvent(S.stream, C.front_go, 0));
+            S.spans.on = g_prof.on; S.spans.reset();
+            S.prof_prefixes = S.prof_state_bytes = S.prof_lane_ops = S.prof_children = S.prof_mat_bytes = S.prof_entries = 0.0;
+            S.rc = P2_OK; S.err.clear();
+        }
+        // the long chains first: large reduction groups, large alphabets
+        std::vector<int> order(enums.size());
+        for (size_t e = 0; e < enums.size(); ++e) order[e] = (int)e;
+        std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+            const Plan& px = runs[enums[x].leader].plan; const Plan& py = runs[enums[y].leader].plan;
+            if (px.R != py.R) return px.R > py.R;
+            return px.alphabet > py.alphabet;
+        });
+        std::atomic<size_t> next{0};
+        int device = 0;
+        P2_HIP(hipGetDevice(&device));
+        auto work = [&](int t, bool own_thread) {
+            FrontSlot& S = C.slots[t];
+            if (own_thread && hipSetDevice(device) != hipSuccess) { S.rc = P2_EDEVICE; S.err = "hipSetDevice failed in a worker thread"; return; }
+            for (size_t at = next.fetch_add(1); at < order.size(); at = next.fetch_add(1)) {
+                const int32_t rc = run_enum(enums[order[at]], S);
+                if (rc != P2_OK) { S.rc = rc; S.err = g_err; break; }
+            }
+            // (whatever the slot has queued is waited for, also after a failure: its buffers are reused)
+            (void)hipStreamSynchronize(S.stream);
+            (void)hipStreamSynchronize(S.side_stream);
+        };
+        if (n_slots == 1) {
+            work(0, false);
+        } else {
+            std::vector<std::thread> pool;
+            for (int t = 1; t < n_slots; ++t) pool.emplace_back(work, t, true);
+            work(0, false);
+            for (auto& th : pool) th.join();
+        }
+        for (int t = 0; t < n_slots; ++t)
+            if (C.slots[t].rc != P2_OK) return fail(C.slots[t].rc, C.slots[t].err);
     }
 
     if (g_prof.on) {
         P2_HIP(hipEventRecord(g_prof.ev[4], stream));
-        g_prof.last.front_prefixes = prof_prefixes; g_prof.last.front_classify_state_bytes = prof_state_bytes;
-        g_prof.last.front_classify_lane_ops = prof_lane_ops; g_prof.last.front_survivors = prof_children;
-        g_prof.last.front_materialize_bytes = prof_mat_bytes;
-        g_prof.last.front_entries = prof_entries;
+        p2_profile& L = g_prof.last;
+        L.front_prefixes = L.front_classify_state_bytes = L.front_classify_lane_ops = L.front_survivors = 0.0;
+        L.front_materialize_bytes = L.front_entries = 0.0;
+        for (const FrontSlot& S : C.slots) {
+            L.front_prefixes += S.prof_prefixes; L.front_classify_state_bytes += S.prof_state_bytes;
+            L.front_classify_lane_ops += S.prof_lane_ops; L.front_survivors += S.prof_children;
+            L.front_materialize_bytes += S.prof_mat_bytes; L.front_entries += S.prof_entries;
+        }
     }
 
     // ---- order, cost, select
@@ -1156,7 +1246,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     double* costs_base = static_cast<double*>(C.costs.p);
     for (auto& L : sort_launches) {
         ++post_launches;
-        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p), static_cast<unsigned long long*>(C.f_valid.p), sorted_base,
+        P2_HIP(launch_rank_sort(static_cast<unsigned long long*>(C.valid.p), nullptr, sorted_base,
                                 segs_of(L), (int)L.segs.size(), L.blocks, stream));
     }
     // the compact engine costs what it can hold and marks the rest with NaN for the literal engine
@@ -1172,16 +1262,18 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     for (auto& L : scost_launches) {
         ++post_launches;
         P2_HIP(launch_cost_shared(reinterpret_cast<const DevQuery*>(db), segs_of(L), (int)L.segs.size(), L.blocks, L.max_R,
-                                  L.max_k, static_cast<unsigned long long*>(C.valid.p), static_cast<unsigned long long*>(C.f_valid.p),
+                                  L.max_k, static_cast<unsigned long long*>(C.valid.p), nullptr,
                                   sorted_base, progs_base, costs_base, stream));
     }
     // frontier enumerations: the place of every program in ascending index order, once per enumeration; then
     // every query of the enumeration writes its rows (programs, and costs from its own sums)
     if (!enums.empty()) {
-        P2_HIP(C.f_rank.ensure(sizeof(uint32_t) * std::max<size_t>(fvalid_used, 1)));
+        size_t ranked = 0;
+        for (auto& E : enums) { E.off_valid = ranked; ranked += E.n_valid; }
+        P2_HIP(C.f_rank.ensure(sizeof(uint32_t) * std::max<size_t>(ranked, 1)));
         for (auto& E : enums) {
             if (E.n_valid == 0) continue;
-            const unsigned long long* list = static_cast<const unsigned long long*>(C.f_valid.p) + E.off_valid;
+            const unsigned long long* list = static_cast<const unsigned long long*>(C.f_evalid[E.id].p);
             uint32_t* rank = static_cast<uint32_t*>(C.f_rank.p) + E.off_valid;
             // (a query that asks for the cheapest programs only has them selected by (cost, index): its rows need no order)
             bool ordered = false;
@@ -1195,7 +1287,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 std::memset(&F, 0, sizeof F);
                 F.query = (uint32_t)E.members[m]; F.n_share = (int32_t)E.members.size(); F.share_pos = (int32_t)m;
                 F.n_valid = E.n_valid; F.valid = list; F.rank = runs[E.members[m]].topk == 0 ? rank : nullptr;
-                F.goal_sums = static_cast<const double*>(C.f_gsums.p) + E.off_sums;
+                F.goal_sums = static_cast<const double*>(C.f_egsums[E.id].p);
                 F.out_first = runs[E.members[m]].out_first;
                 F.sorted = sorted_base; F.progs = progs_base; F.costs = costs_base;
                 ++post_launches;
@@ -1292,13 +1384,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         if (store) P2_HIP(hipEventElapsedTime(&g_prof.last.post_ms, g_prof.ev[4], g_prof.ev[2]));
         P2_HIP(hipEventSynchronize(g_prof.ev[4]));      // (a call that only sizes its result has not waited since)
         P2_HIP(hipEventElapsedTime(&g_prof.last.front_ms, g_prof.ev[3], g_prof.ev[4]));
-        float ms[Prof::kKinds];
-        int32_t launches[Prof::kKinds];
-        P2_HIP(g_prof.collect(ms, launches));
-        g_prof.last.front_classify_ms = ms[Prof::kClassify]; g_prof.last.front_classify_launches = launches[Prof::kClassify];
-        g_prof.last.front_literal_ms = ms[Prof::kLiteral]; g_prof.last.front_literal_launches = launches[Prof::kLiteral];
-        g_prof.last.front_materialize_ms = ms[Prof::kMaterialize]; g_prof.last.front_materialize_launches = launches[Prof::kMaterialize];
-        g_prof.last.front_group_ms = ms[Prof::kGroup];
+        float ms[SpanRec::kKinds] = {0.f, 0.f, 0.f, 0.f};
+        int32_t launches[SpanRec::kKinds] = {0, 0, 0, 0};
+        for (FrontSlot& S : C.slots) P2_HIP(S.spans.collect(ms, launches));
+        g_prof.last.front_classify_ms = ms[SpanRec::kClassify]; g_prof.last.front_classify_launches = launches[SpanRec::kClassify];
+        g_prof.last.front_literal_ms = ms[SpanRec::kLiteral]; g_prof.last.front_literal_launches = launches[SpanRec::kLiteral];
+        g_prof.last.front_materialize_ms = ms[SpanRec::kMaterialize]; g_prof.last.front_materialize_launches = launches[SpanRec::kMaterialize];
+        g_prof.last.front_group_ms = ms[SpanRec::kGroup];
     }
     // ---- hand the results over
     const p2_program* hp = static_cast<const p2_program*>(C.h_progs.p);

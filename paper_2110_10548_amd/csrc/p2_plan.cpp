@@ -320,7 +320,7 @@ int32_t make_plan(const p2_hierarchy* h, const int32_t* axes, int32_t n_axes, co
     if (opt && (opt->hierarchy < 0 || opt->hierarchy > P2_HIERARCHY_REDUCTION)) { err = "unknown synthesis hierarchy"; return P2_EUNSUPPORTED; }
     if (opt && (opt->max_row_classes < 0 || opt->max_row_classes > 64)) { err = "max_row_classes outside 0..64"; return P2_EINVAL; }
     if (opt && (opt->frontier_pairs < 0 || opt->frontier_pairs > P2_FRONTIER_PAIRS_NONE)) { err = "unknown frontier_pairs"; return P2_EINVAL; }
-    if (opt && (opt->flags & ~P2_FLAG_EVALUATE_EVERY_QUERY) != 0) { err = "unknown option flag"; return P2_EINVAL; }
+    if (opt && (opt->flags & ~(P2_FLAG_EVALUATE_EVERY_QUERY | P2_FLAG_ONE_ENUMERATION_AT_A_TIME)) != 0) { err = "unknown option flag"; return P2_EINVAL; }
 
     pl = Plan();
     pl.n = h->n_levels; pl.m = n_axes; pl.D = (int)devices; pl.max_len = max_len;

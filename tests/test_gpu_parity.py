@@ -903,6 +903,27 @@ def test_frontier_state_forms(B, oracle, pairs):
     assert (reruns > 0) == (pairs != 2) or reruns < 200
 
 
+def test_enumerations_side_by_side_or_one_after_the_other(B, oracle):
+    """A batch's enumerations run on several streams at once (a host thread each); with
+    FLAG_ONE_ENUMERATION_AT_A_TIME they run one after the other.  Same lists, same costs, to the bit; the
+    oracle agrees on every query."""
+    cfg, queries = queries_of(3, B)
+    msg = cfg["msg_bytes"]
+    mine = [q for q in queries if _levels(q) == 3][:6] + [q for q in queries if _levels(q) == 2][:6] + [q for q in queries if _levels(q) == 1][:3]
+    # different placements and reduce sets give different (R, patterns): several enumerations in the batch
+    together = B.p2_synthesize_batch([dict(q, engine=3) for q in mine], msg)
+    alone = B.p2_synthesize_batch([dict(q, engine=3, flags=B.FLAG_ONE_ENUMERATION_AT_A_TIME) for q in mine], msg)
+    assert len({r["stats"]["evaluated_with"] for r in together}) > 1
+    assert sum(1 for r in together if r["stats"]["evaluated_with"] < 0) >= 3
+    for q, a, b in zip(mine, together, alone):
+        assert a["programs"]["index"].tolist() == b["programs"]["index"].tolist()
+        assert (a["programs"]["instr"] == b["programs"]["instr"]).all()
+        assert (a["cost"] == b["cost"]).all()
+        assert a["stats"]["steps_executed"] == b["stats"]["steps_executed"]
+        _, ora = oracle_result(oracle, q, msg)
+        assert_same(a, ora, len(msg))
+
+
 def test_frontier_matches_flat_engine_on_config3_sample(B):
     cfg, queries = queries_of(3, B)
     mine = [q for q in queries if _levels(q) == 3][:4] + [q for q in queries if _levels(q) == 2][:4]

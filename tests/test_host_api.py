@@ -100,7 +100,7 @@ def test_argument_errors(B):
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, [1e6]) == B.P2_EINVAL     # costs without links
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, max_row_classes=65) == B.P2_EINVAL
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, max_row_classes=-1) == B.P2_EINVAL
-    assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, flags=2) == B.P2_EINVAL   # unknown flag
+    assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, flags=4) == B.P2_EINVAL   # unknown flag
     assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, hierarchy=5) == B.P2_EUNSUPPORTED   # no such hierarchy
     for engine in (2, 3, 4, 5):       # the other hierarchies of Sec. 3.4 run on the literal engine only
         assert code(B.p2_synthesize, [2, 4], [2, 4], [[2, 1], [1, 4]], [0], 3, hierarchy="row", engine=engine) == B.P2_EUNSUPPORTED
