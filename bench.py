@@ -372,6 +372,28 @@ def main():
                                      "traffic": measured_traffic(KERNEL[own_engine], ci)}}
             others[c2["name"]] = entry
         out["other_configs"] = others
+        # flat evaluation outside the power-of-two fast paths: a hierarchy with levels of 3 and 6 (72 devices) and a
+        # reduction group of 128 devices, every candidate visited by the LDS-resident compact engine
+        paths = {}
+        for name, card, bw, alpha in (("radix_3_4_6", [3, 4, 6], [25e9, 100e9, 300e9], [20e-6, 10e-6, 5e-6]),
+                                      ("r128_compact", [2, 8, 8], [25e9, 100e9, 300e9], [20e-6, 10e-6, 5e-6])):
+            devices = card[0] * card[1] * card[2]
+            q = dict(card=card, bw=bw, alpha=alpha, axes=[devices], placement=[card], placement_index=0, reduce_axes=[0],
+                     max_len=4, n_chunks=0, topk=0)
+            try:
+                r = timed([q], [float(1 << 26)], 2, 3, 1, B.FLAG_EVALUATE_EVERY_QUERY)
+            except B.P2Error as e:
+                paths[name] = {"error": str(e)}
+                continue
+            ops, launch_ms, rate = flat_summary(r, "member_visits")
+            st = r["results"][0]["stats"]
+            paths[name] = {"hierarchy": card, "devices": devices, "engine": ENGINE_NAMES[st["engine"]], "kernel": KERNEL[st["engine"]],
+                           "candidates_per_step": st["candidates"], "valid_per_step": st["valid"],
+                           "value": st["candidates"] / (r["dt"] / r["steps"]), "unit": "candidates/s",
+                           "ms_per_step": r["dt"] / r["steps"] * 1e3, "steps": r["steps"],
+                           "roofline": {"bound": "alu", "achieved": rate / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+                                        "frac": rate / ALU_PEAK_LANE_OPS, "launch_ms": launch_ms, "algorithmic_lane_ops_per_launch": ops}}
+        out["other_paths"] = paths
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(queries)
     print(json.dumps(out))

@@ -1116,6 +1116,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         return P2_OK;
     };
     if (g_prof.on) P2_HIP(hipEventRecord(g_prof.ev[3], stream));
+    for (FrontSlot& S : C.slots) {       // (also the slots that this call leaves idle: their figures are summed below)
+        S.prof_prefixes = S.prof_state_bytes = S.prof_lane_ops = S.prof_children = S.prof_mat_bytes = S.prof_entries = 0.0;
+        S.spans.reset();
+    }
     if (!enums.empty()) {
         for (size_t e = 0; e < enums.size(); ++e) enums[e].id = (int)e;
         if (C.f_evalid.size() < enums.size()) { C.f_evalid.resize(enums.size()); C.f_egsums.resize(enums.size()); }
@@ -1129,7 +1133,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(S.open());
             P2_HIP(hipStreamWaitEvent(S.stream, C.front_go, 0));
             S.spans.on = g_prof.on; S.spans.reset();
-            S.prof_prefixes = S.prof_state_bytes = S.prof_lane_ops = S.prof_children = S.prof_mat_bytes = S.prof_entries = 0.0;
             S.rc = P2_OK; S.err.clear();
         }
         // the long chains first: large reduction groups, large alphabets
