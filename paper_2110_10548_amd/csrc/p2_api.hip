@@ -159,6 +159,8 @@ struct Ctx {
     void release();
     DevBuf rows, rows_hdr;
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
+    DevBuf sel_progs, sel_costs, gather;                    // the rows that shortlists picked, and whose they are
+    HostBuf h_gather;
     DevBuf f_rank, f_share;                                 // frontier engine: ranks of the valid programs, queries of the enumerations
     std::vector<DevBuf> f_evalid, f_egsums;                 // ... per enumeration: valid candidate indices, their cost sums
     FrontSlot slots[kFrontSlots];
@@ -189,14 +191,14 @@ const std::thread::id g_loader_thread = std::this_thread::get_id();
 
 void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
-                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share};
+                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share, &sel_progs, &sel_costs, &gather};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
     for (auto* v : {&f_evalid, &f_egsums}) {
         for (DevBuf& b : *v) if (b.p) (void)hipFree(b.p);
         v->clear();
     }
     for (FrontSlot& sl : slots) sl.release();
-    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare};
+    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare, &h_gather};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
     if (front_go) { (void)hipEventDestroy(front_go); front_go = nullptr; }
     if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
@@ -282,13 +284,33 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     // ---- plan every query on the host
     const auto t_begin = std::chrono::steady_clock::now();
     std::vector<QueryRun> runs(n_queries);
-    std::string err;
+    {
+        // (the bandwidth rows of the cost model are built later, while the GPU evaluates; large batches: the
+        //  queries' plans are independent, a few host threads share them)
+        std::vector<int32_t> plan_st((size_t)n_queries, P2_OK);
+        std::vector<std::string> plan_err((size_t)n_queries);
+        auto plan_one = [&](int i) {
+            const p2_query& Q = queries[i];
+            plan_st[i] = make_plan(Q.h, Q.axes, Q.n_axes, Q.placement, Q.reduce_axes, Q.n_reduce, Q.max_len, Q.opt, n_msg > 0,
+                                   runs[i].plan, plan_err[i], false);
+        };
+        const unsigned hw = std::thread::hardware_concurrency();
+        const int n_threads = n_queries >= 64 ? (int)std::min<unsigned>(std::max(hw, 1u), 8u) : 1;
+        if (n_threads <= 1) {
+            for (int i = 0; i < n_queries; ++i) plan_one(i);
+        } else {
+            std::atomic<int> next{0};
+            auto work = [&]() { for (int i = next.fetch_add(1); i < n_queries; i = next.fetch_add(1)) plan_one(i); };
+            std::vector<std::thread> pool;
+            for (int t = 1; t < n_threads; ++t) pool.emplace_back(work);
+            work();
+            for (auto& th : pool) th.join();
+        }
+        for (int i = 0; i < n_queries; ++i)
+            if (plan_st[i] != P2_OK) return fail(plan_st[i], "query " + std::to_string(i) + ": " + plan_err[i]);
+    }
     for (int i = 0; i < n_queries; ++i) {
         const p2_query& Q = queries[i];
-        // (the bandwidth rows of the cost model are built later, while the GPU evaluates)
-        int32_t st = make_plan(Q.h, Q.axes, Q.n_axes, Q.placement, Q.reduce_axes, Q.n_reduce, Q.max_len, Q.opt,
-                               n_msg > 0, runs[i].plan, err, false);
-        if (st != P2_OK) return fail(st, "query " + std::to_string(i) + ": " + err);
         runs[i].topk = Q.opt ? Q.opt->topk : 0;
         if (runs[i].topk < 0) return fail(P2_EINVAL, "topk < 0");
         if (runs[i].topk > kMaxTopK) return fail(P2_EUNSUPPORTED, "topk > 1024");
@@ -1190,6 +1212,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     int64_t need = 0;
     for (auto& r : runs) need += r.topk > 0 ? (int64_t)n_msg * (int64_t)std::min<size_t>(r.topk, r.n_valid) : (int64_t)r.n_valid;
     const bool store = cap >= need && cap > 0;
+    // (every query with valid programs asks for a shortlist: only the rows that are picked go back to the host)
+    bool only_shortlists = n_msg > 0;
+    for (const auto& r : runs) only_shortlists = only_shortlists && (r.n_valid == 0 || r.topk > 0);
     size_t pos_off = 0;
     if (store) {
     P2_HIP(C.sorted.ensure(sizeof(unsigned long long) * std::max<size_t>(total_valid, 1)));
@@ -1364,12 +1389,41 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
     }
     if (g_prof.on) { P2_HIP(hipEventRecord(g_prof.ev[2], stream)); g_prof.last.post_launches = post_launches; }
-    P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
-    P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
     P2_HIP(C.h_pos.ensure(sizeof(long long) * std::max<size_t>(topk_rows, 1)));
-    P2_HIP(launch_copy_out3(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid,
-                            C.h_costs.p, C.costs.p, n_msg > 0 ? sizeof(double) * total_valid * nm : 0,
-                            C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    if (only_shortlists) {
+        // every query asks for a shortlist: the rows that were picked are gathered on the device, and only they go back
+        std::vector<DevGatherSeg> segs;
+        size_t at = 0;
+        for (int i = 0; i < n_queries; ++i) {
+            const QueryRun& r = runs[i];
+            if (r.n_valid == 0) continue;
+            const size_t rows = (size_t)n_msg * std::min<size_t>(r.topk, r.n_valid);
+            segs.push_back(DevGatherSeg{(unsigned long long)r.out_first, (unsigned long long)at, (uint32_t)rows, 0u});
+            at += rows;
+        }
+        P2_HIP(C.gather.ensure(sizeof(DevGatherSeg) * std::max<size_t>(segs.size(), 1)));
+        P2_HIP(C.h_gather.ensure(sizeof(DevGatherSeg) * std::max<size_t>(segs.size(), 1)));
+        P2_HIP(C.sel_progs.ensure(sizeof(p2_program) * std::max<size_t>(topk_rows, 1)));
+        P2_HIP(C.sel_costs.ensure(sizeof(double) * std::max<size_t>(topk_rows, 1) * nm));
+        P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(topk_rows, 1)));
+        P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(topk_rows, 1) * nm));
+        if (!segs.empty()) {
+            std::memcpy(C.h_gather.p, segs.data(), sizeof(DevGatherSeg) * segs.size());
+            P2_HIP(hipMemcpyAsync(C.gather.p, C.h_gather.p, sizeof(DevGatherSeg) * segs.size(), hipMemcpyHostToDevice, stream));
+            P2_HIP(launch_gather_rows(static_cast<const DevGatherSeg*>(C.gather.p), (unsigned)segs.size(), progs_base, costs_base, n_msg,
+                                      static_cast<const long long*>(C.topk_pos.p), static_cast<p2_program*>(C.sel_progs.p),
+                                      static_cast<double*>(C.sel_costs.p), stream));
+        }
+        P2_HIP(launch_copy_out3(C.h_progs.p, C.sel_progs.p, sizeof(p2_program) * topk_rows,
+                                C.h_costs.p, C.sel_costs.p, sizeof(double) * topk_rows * nm,
+                                C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    } else {
+        P2_HIP(C.h_progs.ensure(sizeof(p2_program) * std::max<size_t>(total_valid, 1)));
+        P2_HIP(C.h_costs.ensure(sizeof(double) * std::max<size_t>(total_valid, 1) * nm));
+        P2_HIP(launch_copy_out3(C.h_progs.p, C.progs.p, sizeof(p2_program) * total_valid,
+                                C.h_costs.p, C.costs.p, n_msg > 0 ? sizeof(double) * total_valid * nm : 0,
+                                C.h_pos.p, C.topk_pos.p, sizeof(long long) * topk_rows, stream));
+    }
     if (topk_rows > 0)      // the selections flag a NaN cost in their query's counters
         P2_HIP(launch_copy_out(C.h_counters.p, C.counters.p, sizeof(DevCounters) * (size_t)n_queries, stream));
     P2_HIP(hipStreamSynchronize(stream));
@@ -1409,10 +1463,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             if (!store) w += (int64_t)n_msg * (int64_t)kk;
             for (int m = 0; m < n_msg && store; ++m)
                 for (size_t t = 0; t < kk; ++t, ++w) {
+                    const size_t sel = pos_off;
                     const long long pos = hpos[pos_off++];
                     if (pos < 0 || pos >= (long long)r.n_valid) return fail(P2_EDEVICE, "top-k returned a bad position");
-                    out_prog[w] = hp[r.out_first + pos];
-                    for (int c = 0; c < n_msg; ++c) out_cost[w * n_msg + c] = hcst[(r.out_first + pos) * nm + c];
+                    const size_t row = only_shortlists ? sel : r.out_first + (size_t)pos;
+                    out_prog[w] = hp[row];
+                    for (int c = 0; c < n_msg; ++c) out_cost[w * n_msg + c] = hcst[row * nm + c];
                 }
         } else {
             if (store) {

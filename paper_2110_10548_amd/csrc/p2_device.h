@@ -373,6 +373,15 @@ struct DevTopkJob {
 };
 // Block b of the launch does jobs[b] alone: meant for many selections of a few thousand entries each.
 hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, hipStream_t stream);
+// The rows that the selections of a batch picked, gathered so that only they go back to the host: segment s (one
+// per query) has `rows` positions from pos[pos_first] on, relative to row out_first of the batch-wide program and
+// cost arrays; selected row pos_first + t gets program and costs of row out_first + pos[pos_first + t].
+struct DevGatherSeg {
+    unsigned long long out_first, pos_first;
+    uint32_t rows, pad;
+};
+hipError_t launch_gather_rows(const DevGatherSeg* segs, unsigned n_segs, const p2_program* progs, const double* costs, int n_cost,
+                              const long long* pos, p2_program* sel_progs, double* sel_costs, hipStream_t stream);
 // Many selections of many entries each: two launches for all of them (every job cut into strided shares, then a
 // merge per job).  scratch: topk_big_scratch_bytes(n_jobs, max_k) bytes.  Grid limit: n_jobs <= 65535.
 size_t topk_big_scratch_bytes(unsigned n_jobs, int max_k);

@@ -298,6 +298,26 @@ hipError_t launch_topk_jobs(const DevTopkJob* jobs, unsigned n_jobs, int max_k, 
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(kWave) void k_gather_rows(const DevGatherSeg* __restrict__ segs, const p2_program* __restrict__ progs,
+                                                       const double* __restrict__ costs, int n_cost, const long long* __restrict__ pos,
+                                                       p2_program* __restrict__ sel_progs, double* __restrict__ sel_costs) {
+    const DevGatherSeg S = segs[blockIdx.x];
+    for (uint32_t t = threadIdx.x; t < S.rows; t += kWave) {
+        const long long p = pos[S.pos_first + t];
+        if (p < 0) continue;                         // (the host reports a selection that came back short)
+        const size_t src = (size_t)(S.out_first + (unsigned long long)p), dst = (size_t)(S.pos_first + t);
+        sel_progs[dst] = progs[src];
+        for (int c = 0; c < n_cost; ++c) sel_costs[dst * n_cost + c] = costs[src * n_cost + c];
+    }
+}
+
+hipError_t launch_gather_rows(const DevGatherSeg* segs, unsigned n_segs, const p2_program* progs, const double* costs, int n_cost,
+                              const long long* pos, p2_program* sel_progs, double* sel_costs, hipStream_t stream) {
+    if (n_segs == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_rows, dim3(n_segs), dim3(kWave), 0, stream, segs, progs, costs, n_cost, pos, sel_progs, sel_costs);
+    return hipGetLastError();
+}
+
 size_t topk_big_scratch_bytes(unsigned n_jobs, int max_k) { return (size_t)n_jobs * kBigParts * (size_t)max_k * 24; }
 
 hipError_t launch_topk_big(const DevTopkJob* jobs, unsigned n_jobs, int max_k, void* scratch, hipStream_t stream) {
