@@ -9,31 +9,39 @@
 // step depends on the state before it and on the query's links only.  A program's cost is therefore
 // complete the moment it reaches the goal, and no valid program is ever simulated a second time.
 //
-// State of a prefix.  From the init state every rule of Sec. 3.2 keeps the non-empty rows of a device
-// equal to each other unless an AllGather joins members whose rows carry different column sets
+// States and prefixes are kept apart.  What the rules say about the next instruction depends on the
+// state alone, and many prefixes end in the same state, so a level holds its distinct states once
+// (two lists, see below) and its prefixes as records: instructions, sums, index of the state.
+//
+// State.  From the init state every rule of Sec. 3.2 keeps the non-empty rows of a device equal to
+// each other unless an AllGather joins members whose rows carry different column sets
 // (p2_compact.hip).  Here a device holds up to TWO (chunk set, contribution mask) pairs: the rows of
 // pair 0 all carry mask 0, the rows of pair 1 mask 1; the chunk sets are disjoint, pair 0 owns the
-// lowest row, an empty pair has an empty mask, and two pairs never carry the same mask.  Prefixes
-// whose devices all have one pair keep one plane of R x (KW + MW) words in HBM ("one-pair list"),
+// lowest row, an empty pair has an empty mask, and two pairs never carry the same mask.  States
+// whose devices all have one pair are one plane of R x WQ 16-byte quads in HBM ("one-pair list"),
 // the others two planes ("two-pair list").  The rules on two-pair states:
 //   AllReduce-like : members must hold the same rows.  Their pairs must be *aligned*: every member
 //                    with two pairs splits the rows the same way (members with one pair fit any
 //                    split).  Then the rule is checked and carried out plane by plane.  A group
-//                    that is not aligned cannot be judged in this form: the whole prefix is handed
-//                    to the literal kernels, which rebuild the literal state from its instructions.
+//                    that is not aligned cannot be judged in this form: the prefixes of the state
+//                    are handed to the literal kernels, which rebuild the literal state from the
+//                    instructions.
 //   AllGather      : rows pairwise disjoint, nobody empty; the result has one pair per distinct
 //                    mask among the members' pairs.  More than two: the child is a "literal"
 //                    prefix (it keeps only its instructions; p2_literal.hip takes it from there).
 //   Broadcast      : compared pair against pair (a row's mask is its pair's mask).
-// One level is two kernels:
-//   classify    : block = one prefix, its state copied to LDS; thread = one instruction, which
-//                 decides read-only whether the step is valid and what its result is.
-//                 Survivors (valid steps) are appended to a list and counted by kind.
-//   materialize : one wavefront per survivor: the new state is built from the parent's, the
-//                 step's time is added to the parent's sums for every query of the enumeration, and
-//                 a goal becomes a valid program (candidate index + its sums), anything else a
-//                 prefix of the next frontier.
-// The host sizes the next level's buffers from the counts between the two, so nothing overflows.
+// One level, in launch order (the host waits once, after `children (count)`, and sizes the next
+// level's buffers exactly from the counts, so nothing overflows):
+//   classify         : block = one distinct state, its planes in LDS, wavefronts over patterns,
+//                      lanes = (device slot, 16-byte quad); writes a code per instruction.
+//   expand           : for every prefix, the survivors among its extensions (from its state's codes)
+//                      with their places in the next prefix lists / among the goals.
+//   children         : for every (state, valid instruction), the child's place in the next state lists.
+//   materialize      : block = one child: parent planes into LDS, the instruction applied in place,
+//                      the child streamed out with its hash; what the step adds to every query's sums.
+//   dedup + verify   : children with equal hashes are compared word by word; one of every group of
+//                      equal states stands for the others.
+//   prefixes         : the next level's prefix records (sums = parent's + step's) and the goals.
 #include "p2_compact_dev.h"
 
 namespace p2 {
@@ -72,23 +80,6 @@ __device__ inline Words<N> andn_words(const Words<N>& a, const Words<N>& b) {   
     for (int i = 0; i < N; ++i) o.w[i] = a.w[i] & ~b.w[i];
     return o;
 }
-template <int N>
-__device__ inline Words<N> select_words(bool c, const Words<N>& a, const Words<N>& b) {
-    Words<N> o;
-#pragma unroll
-    for (int i = 0; i < N; ++i) o.w[i] = c ? a.w[i] : b.w[i];
-    return o;
-}
-// position of the lowest set bit (N * 32 if there is none)
-template <int N>
-__device__ inline int lowest_bit(const Words<N>& a) {
-    int pos = N * 32;
-#pragma unroll
-    for (int i = N - 1; i >= 0; --i)
-        if (a.w[i]) pos = i * 32 + __ffs((int)a.w[i]) - 1;
-    return pos;
-}
-
 // Layout of a state plane, in HBM and in LDS: per device the chunk set padded to whole 16-byte quads, then the
 // contribution mask padded likewise (the padding stays zero), so that a device is WQ quads and the
 // wavefront-wide kernels read it with 128-bit accesses.
@@ -135,21 +126,6 @@ __device__ inline Pairs<KW, MW> load_pairs(const uint32_t* st, int R, int np, in
     }
     return p;
 }
-// Writes a device in canonical form: equal masks merged, empty pairs cleared, the pair with the lowest
-// row first.  np = planes of the destination (with one plane the second pair must come out empty).
-template <int KW, int MW>
-__device__ inline void store_pairs(uint32_t* st, int R, int np, int dev, Words<KW> x0, Words<MW> m0, Words<KW> x1, Words<MW> m1) {
-    if (fold_or(x0) == 0u) m0 = zero_words<MW>();
-    if (fold_or(x1) == 0u) m1 = zero_words<MW>();
-    if (fold_or(x1) != 0u && fold_xor(m0, m1) == 0u) { x0 = or_words(x0, x1); x1 = zero_words<KW>(); m1 = zero_words<MW>(); }
-    if (lowest_bit(x1) < lowest_bit(x0)) {
-        const Words<KW> tx = x0; x0 = x1; x1 = tx;
-        const Words<MW> tm = m0; m0 = m1; m1 = tm;
-    }
-    fstore<KW, MW>(st, dev, x0, m0);
-    if (np == 2) fstore<KW, MW>(st + R * FL<KW, MW>::WS, dev, x1, m1);
-}
-
 // ---- one AllReduce-like group on (up to) two-pair members --------------------------------------------
 template <int KW, int MW>
 struct RedFold {
@@ -189,131 +165,33 @@ __device__ inline RedFold<KW, MW> fold_red(const uint32_t* st, int R, int np, in
     return f;
 }
 
-// ---- one AllGather group ---------------------------------------------------------------------------
-template <int KW, int MW>
-struct GatherFold {
-    Words<KW> u;          // rows after the gather
-    Words<KW> xd0, xd1;   // rows carrying the first / second distinct mask
-    Words<MW> d0, d1;
-    int n_masks;          // distinct masks seen (3 = more than two)
-    uint32_t bad;         // a row held twice, or an empty member
-};
-template <int KW, int MW>
-__device__ inline void gather_add(GatherFold<KW, MW>& f, const Words<KW>& x, const Words<MW>& m) {
-    if (fold_or(x) == 0u) return;
-    if (f.n_masks == 0) { f.d0 = m; f.xd0 = x; f.n_masks = 1; }
-    else if (fold_xor(m, f.d0) == 0u) f.xd0 = or_words(f.xd0, x);
-    else if (f.n_masks == 1) { f.d1 = m; f.xd1 = x; f.n_masks = 2; }
-    else if (f.n_masks >= 2 && fold_xor(m, f.d1) == 0u) f.xd1 = or_words(f.xd1, x);
-    else f.n_masks = 3;
-}
-template <int KW, int MW>
-__device__ inline GatherFold<KW, MW> fold_gather(const uint32_t* st, int R, int np, int base, int g, int s) {
-    GatherFold<KW, MW> f;
-    f.u = zero_words<KW>(); f.xd0 = zero_words<KW>(); f.xd1 = zero_words<KW>();
-    f.d0 = zero_words<MW>(); f.d1 = zero_words<MW>();
-    f.n_masks = 0; f.bad = 0;
-    for (int t = 0; t < g; ++t) {
-        const Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base + t * s);
-        const Words<KW> u = or_words(p.x0, p.x1);
-        f.bad |= fold_and(u, f.u) | (uint32_t)(fold_or(u) == 0u);
-        f.u = or_words(f.u, u);
-        gather_add(f, p.x0, p.m0);
-        gather_add(f, p.x1, p.m1);
-    }
-    return f;
-}
-
-// ---- Broadcast: root against one member, pair by pair -------------------------------------------------
-template <int KW, int MW>
-__device__ inline void bcast_compare(const Pairs<KW, MW>& root, const Pairs<KW, MW>& mem, uint32_t& not_sub, bool& differs) {
-    const Words<KW> ur = or_words(root.x0, root.x1), um = or_words(mem.x0, mem.x1);
-    not_sub |= fold_andn(um, ur);
-    uint32_t dif = fold_xor(um, ur);
-    if (fold_and(root.x0, mem.x0)) { not_sub |= fold_andn(mem.m0, root.m0); dif |= fold_xor(mem.m0, root.m0); }
-    if (fold_and(root.x0, mem.x1)) { not_sub |= fold_andn(mem.m1, root.m0); dif |= fold_xor(mem.m1, root.m0); }
-    if (fold_and(root.x1, mem.x0)) { not_sub |= fold_andn(mem.m0, root.m1); dif |= fold_xor(mem.m0, root.m1); }
-    if (fold_and(root.x1, mem.x1)) { not_sub |= fold_andn(mem.m1, root.m1); dif |= fold_xor(mem.m1, root.m1); }
-    differs |= dif != 0u;
-}
-
 __device__ inline int first_of_group(const PatLds& P, int G) {
     const int gs = P.g * P.s;
     return P.master ? G * gs : (G / P.s) * gs + (G % P.s);
 }
 
-// Is the step valid, and what does it lead to?  Reads the state only.  np: planes of the state.
-// n_goal / n_two: devices of the state that are at the goal / that hold two pairs.
+// A ReduceScatter on a pattern whose groups are valid, aligned and split (some member holds two pairs): rank t keeps
+// the t-th block of the rows in ascending order; does a block fall on both sides of a split with different masks?
+// (Then that member holds two pairs afterwards.)  One lane walks the pairs; reads the state only.
 template <int KW, int MW>
-__device__ inline int classify_pairs(const uint32_t* st, const PatLds P, int op, int R, int np, const Words<KW>& all_rows,
-                                     const Words<MW>& all_cols, int n_goal, int n_two) {
-    bool bad = false, changed = false, all_goal = true, unknown = false, overflow = false, any_two = false;
-    int goal_part = 0, two_part = 0;
+__device__ inline bool rs_straddles_split(const uint32_t* st, const PatLds P, int R, int np) {
+    bool straddles = false;
     for (int G = 0; G < P.n_groups; ++G) {
-        const int base = first_of_group(P, G);
+        const RedFold<KW, MW> f = fold_red<KW, MW>(st, R, np, first_of_group(P, G), P.g, P.s);
+        if (!f.split || fold_xor(f.accA, f.accB) == 0u) continue;
+        const int rows = popcount(f.u0);
+        if (rows == 0) continue;
+        const int per = div_small(rows, P.g);
+        Words<KW> prev = zero_words<KW>();
+        const Words<KW> xb = andn_words(f.u0, f.xa);
         for (int t = 0; t < P.g; ++t) {
-            const Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base + t * P.s);
-            const bool two = fold_or(p.x1) != 0u;
-            two_part += two ? 1 : 0;
-            goal_part += (!two && (fold_xor(p.x0, all_rows) | fold_xor(p.m0, all_cols)) == 0u) ? 1 : 0;
-        }
-        if (op == OP_AR || op == OP_RS || op == OP_RD) {
-            const RedFold<KW, MW> f = fold_red<KW, MW>(st, R, np, base, P.g, P.s);
-            bad |= f.bad != 0u || (f.unaligned == 0u && f.badB != 0u);
-            unknown |= f.bad == 0u && f.unaligned != 0u;
-            const bool some = fold_or(f.u0) != 0u;
-            changed |= some;
-            const bool two_masks = f.split && fold_xor(f.accA, f.accB) != 0u;
-            if (op == OP_RS) {
-                const int rows = popcount(f.u0);
-                const int per = div_small(rows, P.g);
-                bad |= per * P.g != rows;
-                // a member's block may fall on both sides of the split
-                if (two_masks && some && per * P.g == rows) {
-                    Words<KW> prev = zero_words<KW>();
-                    const Words<KW> xb = andn_words(f.u0, f.xa);
-                    for (int t = 0; t < P.g; ++t) {
-                        const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
-                        const Words<KW> blk = andn_words(upto, prev);
-                        prev = upto;
-                        any_two |= fold_and(blk, f.xa) != 0u && fold_and(blk, xb) != 0u;
-                    }
-                }
-                all_goal = false;
-            } else if (op == OP_RD) {
-                any_two |= two_masks && some;
-                all_goal = false;
-            } else {
-                any_two |= two_masks && some;
-                all_goal &= !two_masks && (fold_xor(f.u0, all_rows) | fold_xor(f.accA, all_cols)) == 0u;
-            }
-        } else if (op == OP_AG) {
-            const GatherFold<KW, MW> f = fold_gather<KW, MW>(st, R, np, base, P.g, P.s);
-            bad |= f.bad != 0u;
-            changed = true;
-            overflow |= f.n_masks > 2;
-            any_two |= f.n_masks == 2;
-            all_goal &= f.n_masks == 1 && (fold_xor(f.u, all_rows) | fold_xor(f.d0, all_cols)) == 0u;
-        } else {
-            const Pairs<KW, MW> root = load_pairs<KW, MW>(st, R, np, base);
-            uint32_t not_sub = 0;
-            bool differs = false;
-            for (int t = 1; t < P.g; ++t)
-                bcast_compare(root, load_pairs<KW, MW>(st, R, np, base + t * P.s), not_sub, differs);
-            bad |= not_sub != 0u || !differs;
-            changed = true;
-            const bool two = fold_or(root.x1) != 0u;
-            any_two |= two;
-            all_goal &= !two && (fold_xor(root.x0, all_rows) | fold_xor(root.m0, all_cols)) == 0u;
+            const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
+            const Words<KW> blk = andn_words(upto, prev);
+            prev = upto;
+            straddles |= fold_and(blk, f.xa) != 0u && fold_and(blk, xb) != 0u;
         }
     }
-    if (bad || !changed) return CODE_INVALID;
-    if (unknown) return CODE_UNKNOWN;
-    if (overflow) return CODE_PREFIX_LITERAL;       // a device with three different masks: never the goal
-    const int n_part = P.n_groups * P.g;
-    if (any_two || n_two - two_part > 0) return CODE_PREFIX2;
-    const bool rest_done = (n_goal - goal_part) == (R - n_part);     // devices left untouched
-    return (all_goal && rest_done) ? CODE_GOAL : CODE_PREFIX;
+    return straddles;
 }
 
 // ---- classification, a wavefront per pattern ----------------------------------------------------------
@@ -710,8 +588,7 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
             else if (UNAL) code = CODE_UNKNOWN;
             else if (BAD_B) code = CODE_INVALID;
             else if (op == OP_RS) {
-                if (ANY_TWO) code = classify_pairs<KW, MW>(lds_words, P, op, R, NP, all_rows, all_cols, n_goal, n_two);
-                else code = rest_two ? CODE_PREFIX2 : CODE_PREFIX;
+                code = ((ANY_TWO && rs_straddles_split<KW, MW>(lds_words, P, R, NP)) || rest_two) ? CODE_PREFIX2 : CODE_PREFIX;
             } else if (ANY_TWO || rest_two) code = CODE_PREFIX2;
             else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
         } else if (op == OP_AG) {
