@@ -330,7 +330,7 @@ def main():
                 "steps_evaluated_per_step"):
         if key in head:
             out[key] = head[key]
-    if 3 in head["engines_used"]:
+    if 3 in head["engines_used"] and not args.no_compare:
         # The timed steps run up to four enumerations side by side, so the event time of a launch there is the time of
         # a kernel that shares the chip.  The same batch with the enumerations one after the other, a few steps: what
         # the kernels reach with the chip to themselves.
