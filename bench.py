@@ -24,8 +24,10 @@ been judged on its own); the same words are read from LDS once per pattern (`roo
 `materialize` prices the kernel that builds the children of the judged states against HBM.  Times
 are HIP-event times around every launch of the family on the stream it is launched on, taken inside
 the timed steps (p2_get_profile).  The library runs up to four enumerations of a batch side by
-side, so those are times of kernels that share the chip; `one_enumeration_at_a_time` gives the same
-objects for a few steps with the enumerations one after the other.
+side, so those are times of kernels that share the chip, and an event pair on one stream also sees
+the time its kernel waits for a turn behind the other streams' kernels, which a profiler's kernel
+duration does not; `one_enumeration_at_a_time` gives the same objects for a few steps with the
+enumerations one after the other (there the two agree), and `--one-at-a-time` times the whole run so.
 For the flat engines (configurations 1-4 with the default engine) the roofline is the lane-operation
 rate of the evaluation kernel, as `other_configs` reports per configuration.
 `cpu_baseline` times the plain CPU oracle on a bounded sample of the same workload.
@@ -170,6 +172,10 @@ def main():
                     help="0 auto, 1 literal, 2 compact (state in LDS), 3 frontier, 4 small-group, 5 shared-prefix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-compare", action="store_true", help="skip the legs that run other engines or other configurations (profiling runs)")
+    ap.add_argument("--one-at-a-time", action="store_true",
+                    help="time the steps with the enumerations of a batch one after the other (P2_FLAG_ONE_ENUMERATION_AT_A_TIME): "
+                         "every kernel then has the chip to itself, which is the setting in which an event time around a launch "
+                         "and a profiler's kernel duration are the same thing")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibration of HBM byte counters under rocprofv3)")
     args = ap.parse_args()
@@ -299,7 +305,7 @@ def main():
     msg = cfg["msg_bytes"]
     peak_measured = B.p2_measure_alu_peak(5)        # independent v_xor_b32 stream, lane-operations per second
     lds_measured = B.p2_measure_lds_peak(5)         # 128-bit LDS reads, bytes per second
-    run = timed(queries, msg, args.engine, args.steps, args.warmup)
+    run = timed(queries, msg, args.engine, args.steps, args.warmup, B.FLAG_ONE_ENUMERATION_AT_A_TIME if args.one_at_a_time else 0)
     head = report(run, args.config, args.engine)
     placements = len({q["placement_index"] for q in queries})
     if cfg["placements"] == "all":
@@ -330,7 +336,9 @@ def main():
                 "steps_evaluated_per_step"):
         if key in head:
             out[key] = head[key]
-    if 3 in head["engines_used"] and not args.no_compare:
+    if args.one_at_a_time:
+        out["config"]["enumerations"] = "one at a time"
+    if 3 in head["engines_used"] and not args.no_compare and not args.one_at_a_time:
         # The timed steps run up to four enumerations side by side, so the event time of a launch there is the time of
         # a kernel that shares the chip.  The same batch with the enumerations one after the other, a few steps: what
         # the kernels reach with the chip to themselves.

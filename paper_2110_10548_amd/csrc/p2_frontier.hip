@@ -875,7 +875,10 @@ __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long lo
 }
 
 // ---- children of the survivors -----------------------------------------------------------------------
-constexpr int kMatThreads = 256, kMatWaves = kMatThreads / 64;
+// Threads of a block: 256, or 1024 where the planes in LDS leave room for one or two blocks on a compute unit only
+// (large reduction groups), so that the loads and stores of a child are still the work of many wavefronts.
+constexpr int kMatThreads = 256, kMatThreadsBig = 1024;
+constexpr size_t kMatBigLds = 60 * 1024;
 
 // Smallest over the 8 lanes of a slot, in every lane of the slot (all lanes active).
 __device__ inline int min_slot(int v) {
@@ -922,8 +925,8 @@ __device__ inline void canonical_slot(uint4& a, uint4& b, bool is_row, bool is_m
 // go out with 128-bit stores.  Groups are disjoint sets of devices, so the wavefronts do not meet.  The rows that
 // a group's members hold set the bytes of the step (s_count), from which the wavefronts then work out the step's
 // time for every query of the enumeration.
-template <int KW, int MW>
-__global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
+template <int KW, int MW, int NT>
+__global__ __launch_bounds__(NT) void k_front_materialize(const DevQuery* __restrict__ queries, FrontLevel A) {
     extern __shared__ uint4 ldsq[];                      // A.lds_planes planes of [R][WQ] quads
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];     // rows that set a group's bytes
@@ -934,7 +937,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane >> 3, qd = lane & 7, sh = slot * 8;
     const bool is_row = qd < L::QK, is_mask = qd >= L::QK && qd < L::WQ, has_quad = qd < L::WQ;
-    for (int i = tid; i < q.n_patterns; i += kMatThreads) {
+    for (int i = tid; i < q.n_patterns; i += NT) {
         PatLds p;
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
@@ -950,15 +953,15 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         const int cnp = code == CODE_PREFIX2 ? 2 : 1;
         const uint32_t place = sv.slot;                  // the child's place in the next state list of its kind
         __syncthreads();                                 // (the block is done with the planes and counts of its last survivor)
-        for (int i0 = tid; i0 < np * plane_q; i0 += 8 * kMatThreads) {
+        for (int i0 = tid; i0 < np * plane_q; i0 += 8 * NT) {
             uint4 tmp[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { const int w = i0 + u * kMatThreads; tmp[u] = w < np * plane_q ? parent[w] : q_zero(); }
+            for (int u = 0; u < 8; ++u) { const int w = i0 + u * NT; tmp[u] = w < np * plane_q ? parent[w] : q_zero(); }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { const int w = i0 + u * kMatThreads; if (w < np * plane_q) ldsq[w] = tmp[u]; }
+            for (int u = 0; u < 8; ++u) { const int w = i0 + u * NT; if (w < np * plane_q) ldsq[w] = tmp[u]; }
         }
         if (np == 1 && cnp == 2)                         // the devices that take no part have no second pair
-            for (int w = tid; w < plane_q; w += kMatThreads) ldsq[plane_q + w] = q_zero();
+            for (int w = tid; w < plane_q; w += NT) ldsq[plane_q + w] = q_zero();
         __syncthreads();
         // ---- apply the instruction in LDS
         const uint32_t ins = q.instr_of_digit[sv.digit];
@@ -972,7 +975,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         const int my_g = slot / spg, part = slot - my_g * spg;
         const int trips = (g + spg - 1) / spg;
         const bool both = np == 2;                       // the parent has a second plane
-        for (int G0 = wave * gpb; G0 < ng; G0 += kMatWaves * gpb) {
+        for (int G0 = wave * gpb; G0 < ng; G0 += (NT / 64) * gpb) {
             const int G = G0 + my_g;
             const bool act = G < ng && has_quad;
             int base = 0;
@@ -1089,7 +1092,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
             uint4* child = reinterpret_cast<uint4*>(cnp == 2 ? A.next_states2 + (size_t)place * 2 * plane_w
                                                              : A.next_states1 + (size_t)place * plane_w);
             unsigned long long h = 0;                    // (what the search for equal states goes by)
-            for (int w = tid; w < cnp * plane_q; w += kMatThreads) {
+            for (int w = tid; w < cnp * plane_q; w += NT) {
                 const uint4 v = ldsq[w];
                 child[w] = v;
                 if (q_any(v)) h += hash_quad(v, (uint32_t)w);
@@ -1113,7 +1116,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
         for (int G = lane; G < ng; G += 64) same &= s_count[G] == c0;
         const bool uniform = __all(same) != 0;
         if (A.n_msg > 0 && uniform) {
-            for (int j = tid; j < A.n_share; j += kMatThreads) {
+            for (int j = tid; j < A.n_share; j += NT) {
                 const DevQuery& cq = queries[A.share[j]];
                 const DevRows& rw = *cq.rows;
                 double best = 0.0;
@@ -1125,7 +1128,7 @@ __global__ __launch_bounds__(kMatThreads) void k_front_materialize(const DevQuer
                 out[2 * j + 1] = (mult / (double)cq.k) * best;
             }
         } else if (A.n_msg > 0) {
-            for (int j = wave; j < A.n_share; j += kMatWaves) {
+            for (int j = wave; j < A.n_share; j += (NT / 64)) {
                 const DevQuery& cq = queries[A.share[j]];
                 const DevRows& rw = *cq.rows;
                 double best = 0.0;
@@ -1403,9 +1406,15 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
     } else {
         const size_t lds = (size_t)A.level->lds_planes * A.R * FL<KW, MW>::WS * 4;
         const unsigned blocks = A.level->n_surv < 8192u ? A.level->n_surv : 8192u;
-        const hipError_t e = allow_lds_f(k_front_materialize<KW, MW>, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((k_front_materialize<KW, MW>), dim3(blocks), dim3(kMatThreads), lds, stream, A.queries, *A.level);
+        if (lds > kMatBigLds) {
+            const hipError_t e = allow_lds_f(k_front_materialize<KW, MW, kMatThreadsBig>, lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((k_front_materialize<KW, MW, kMatThreadsBig>), dim3(blocks), dim3(kMatThreadsBig), lds, stream, A.queries, *A.level);
+        } else {
+            const hipError_t e = allow_lds_f(k_front_materialize<KW, MW, kMatThreads>, lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((k_front_materialize<KW, MW, kMatThreads>), dim3(blocks), dim3(kMatThreads), lds, stream, A.queries, *A.level);
+        }
     }
     return hipGetLastError();
 }

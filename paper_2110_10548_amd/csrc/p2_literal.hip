@@ -81,23 +81,25 @@ __device__ inline double wave_max(double v) {
     return v;
 }
 
-// One instruction on the literal state.  All 64 lanes call it with identical arguments.
+// One instruction on the literal state.  All nt threads of the block call it with identical arguments
+// (lane = thread number; nt = 64, one wavefront, unless stated; kCost needs nt = 64).
 // Returns false if a premise fails or nothing changes.  With kCost, *cost_lane (lane m = message
 // size m) gets the step time added.
 template <int MW, bool kCost>
-__device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, int lane, double* cost_lane) {
+__device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, int lane, double* cost_lane,
+                         const int nt = kWave) {
     const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
     const int kw = (k + 31) / 32;
-    for (int i = lane; i < ng; i += kWave) { L.gcount[i] = 0; L.gflag[i] = 0; }
-    for (int i = lane; i < ng * kw; i += kWave) L.gbits[i] = 0;
+    for (int i = lane; i < ng; i += nt) { L.gcount[i] = 0; L.gflag[i] = 0; }
+    for (int i = lane; i < ng * kw; i += nt) L.gbits[i] = 0;
     if (op == OP_AG)
-        for (int i = lane; i < q.R; i += kWave) L.devne[i] = 0;
+        for (int i = lane; i < q.R; i += nt) L.devne[i] = 0;
     if (lane == 0) { L.flags[0] = 0; L.flags[1] = 0; }
     __syncthreads();
 
     const int items = ng * k;
     bool bad = false;
-    for (int it = lane; it < items; it += kWave) {
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, k), r = it - G * k;
         const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
@@ -163,7 +165,7 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
     __syncthreads();
 
     // per-group premises
-    for (int G = lane; G < ng; G += kWave) {
+    for (int G = lane; G < ng; G += nt) {
         const uint32_t cnt = L.gcount[G];
         if (op == OP_AR || op == OP_RS || op == OP_RD) {
             if (op == OP_RS && cnt % (uint32_t)g != 0) L.flags[0] = 1;   // scatter: chunks must divide evenly
@@ -202,7 +204,7 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
 
     // write the members' new rows (block p of a ReduceScatter goes to the member of rank p)
     const int32_t* rank = P.rank_off ? q.rank_tbl + (P.rank_off - 1) : nullptr;
-    for (int it = lane; it < items; it += kWave) {
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, k), r = it - G * k;
         const int base = group_base(P.master, G, s, gs);
         uint32_t t[MW];
@@ -233,10 +235,10 @@ __device__ bool lit_step(const DevQuery& q, const DevPattern& P, int op, const L
 }
 
 template <int MW>
-__device__ inline void lit_init(const DevQuery& q, const LitLds& L, int lane) {
+__device__ inline void lit_init(const DevQuery& q, const LitLds& L, int lane, const int nt = kWave) {
     // Sec. 3.5: device i holds column i in every row
     const int cells = q.R * q.k;
-    for (int c = lane; c < cells; c += kWave) {
+    for (int c = lane; c < cells; c += nt) {
         const int d = c / q.k;
 #pragma unroll
         for (int w = 0; w < MW; ++w) L.S[c * MW + w] = (w == (d >> 5)) ? (1u << (d & 31)) : 0u;
@@ -476,18 +478,18 @@ __device__ inline FrontLit carve_front(uint32_t* p, int k) {
 }
 
 // One instruction against the state, read-only: 0 = invalid step, 2 = valid and the result is the
-// goal, 3 = valid prefix.  C = number of row classes.  All 64 lanes call it with the same arguments.
+// goal, 3 = valid prefix.  C = number of row classes.  All nt threads of the block call it with the same arguments.
 template <int MW>
 __device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, const LitLds& L, const FrontLit& X, int C,
-                            const uint32_t* full, int lane) {
+                            const uint32_t* full, int lane, const int nt = kWave) {
     const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
-    for (int i = lane; i < ng; i += kWave) { L.gcount[i] = 0; L.gflag[i] = 0; }
+    for (int i = lane; i < ng; i += nt) { L.gcount[i] = 0; L.gflag[i] = 0; }
     if (lane == 0) { L.flags[0] = 0; L.flags[1] = 0; L.flags[2] = 0; }
     __syncthreads();
     const int items = ng * C;
     bool bad = false, notfull = false;
-    for (int it = lane; it < items; it += kWave) {
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, C), c = it - G * C;
         const int r = (int)X.reps[c];
         const int base = group_base(P.master, G, s, gs);
@@ -546,12 +548,12 @@ __device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, cons
     if (notfull) L.flags[2] = 1;
     // devices the pattern does not touch must already be at the goal
     if (P.master)
-        for (int d = lane; d < q.R; d += kWave) {
+        for (int d = lane; d < q.R; d += nt) {
             const bool part = d % s == 0 && d / gs < ng;
             if (!part && !X.devfull[d]) L.flags[2] = 1;
         }
     __syncthreads();
-    for (int G = lane; G < ng; G += kWave) {
+    for (int G = lane; G < ng; G += nt) {
         const uint32_t cnt = L.gcount[G];
         if (red) {
             if (op == OP_RS && cnt % (uint32_t)g != 0) L.flags[0] = 1;
@@ -569,11 +571,13 @@ __device__ int lit_classify(const DevQuery& q, const DevPattern& P, int op, cons
 
 // Classes of equal rows of the state in L.S, and per device whether it holds anything and whether it
 // is at the goal.  Hash every row over all devices, point each row at the first row with its hash,
-// and keep the pointer only if the two rows really are equal.  Returns the number of classes.
+// and keep the pointer only if the two rows really are equal.  Returns the number of classes.  All nt
+// threads of the block call it (nt a multiple of 64).
 template <int MW>
-__device__ inline int row_classes(const DevQuery& q, const LitLds& L, const FrontLit& X, const uint32_t* full, int lane) {
+__device__ inline int row_classes(const DevQuery& q, const LitLds& L, const FrontLit& X, const uint32_t* full, int lane,
+                                  const int nt = kWave) {
     const int R = q.R, k = q.k;
-    for (int r = lane; r < k; r += kWave) {
+    for (int r = lane; r < k; r += nt) {
         uint32_t a = 0x811c9dc5u, b = 0x9e3779b9u;
         for (int d = 0; d < R; ++d) {
             const uint32_t* x = L.S + (d * k + r) * MW;
@@ -588,7 +592,7 @@ __device__ inline int row_classes(const DevQuery& q, const LitLds& L, const Fron
         X.multr[r] = 0;
     }
     __syncthreads();
-    for (int r = lane; r < k; r += kWave) {
+    for (int r = lane; r < k; r += nt) {
         const uint32_t a = X.h1[r], b = X.h2[r];
         int r0 = 0;
         while (r0 < r && (X.h1[r0] != a || X.h2[r0] != b)) ++r0;
@@ -605,28 +609,44 @@ __device__ inline int row_classes(const DevQuery& q, const LitLds& L, const Fron
         X.rep[r] = (uint32_t)r0;
     }
     __syncthreads();
+    // the representatives in ascending order: the block's first wavefront lists them
     int C = 0;
-    for (int r0 = 0; r0 < k; r0 += kWave) {
-        const int r = r0 + lane;
-        const bool is = r < k && X.rep[r] == (uint32_t)r;
-        const unsigned long long bal = __ballot(is);
-        if (is) X.reps[C + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)r;
-        C += __popcll(bal);
-        if (r < k) atomicAdd(&X.multr[X.rep[r]], 1u);
+    if (lane < kWave) {
+        for (int r0 = 0; r0 < k; r0 += kWave) {
+            const int r = r0 + lane;
+            const bool is = r < k && X.rep[r] == (uint32_t)r;
+            const unsigned long long bal = __ballot(is);
+            if (is) X.reps[C + __popcll(bal & ((1ull << lane) - 1ull))] = (uint32_t)r;
+            C += __popcll(bal);
+            if (r < k) atomicAdd(&X.multr[X.rep[r]], 1u);
+        }
+        // the hashes are no longer needed: their first words become the two flags below
+        if (lane == 0) { L.flags[3] = (uint32_t)C; X.h1[0] = 0; X.h1[1] = 0; }
     }
     __syncthreads();
-    for (int d = lane; d < R; d += kWave) {
+    C = (int)L.flags[3];
+    bool hole = false, partial = false;
+    for (int d = lane; d < R; d += nt) {
         bool any = false, all = true;
         for (int c = 0; c < C; ++c) {
             const uint32_t* x = L.S + (d * k + (int)X.reps[c]) * MW;
+            bool ne = false, fl = true;
 #pragma unroll
-            for (int w = 0; w < MW; ++w) { any |= x[w] != 0; all &= x[w] == full[w]; }
+            for (int w = 0; w < MW; ++w) { ne |= x[w] != 0; fl &= x[w] == full[w]; }
+            any |= ne; all &= fl;
+            hole |= !ne; partial |= ne && !fl;
         }
         X.devany[d] = any; X.devfull[d] = all;
     }
+    if (hole) X.h1[0] = 1;
+    if (partial) X.h1[1] = 1;
     __syncthreads();
     return C;
 }
+// After row_classes (rows of a class are equal on every device, so its representative speaks for them): does
+// every device hold every row; does every row that a device holds carry every column.
+__device__ inline bool rows_all_held(const FrontLit& X) { return X.h1[0] == 0u; }
+__device__ inline bool held_rows_complete(const FrontLit& X) { return X.h1[1] == 0u; }
 
 // ---- groups handed over by the shared-prefix engine ------------------------------------------------
 // A list entry is the index of a group's first candidate: `alphabet` consecutive candidates with the
@@ -1255,8 +1275,11 @@ __device__ inline void cls_judge_all(const DevQuery& q, unsigned long long first
 
 // Frontier level for literal prefixes, on the full literal state: a block rebuilds the state of one
 // prefix and classifies every instruction against it.  With elist, only the entries elist[0 .. *elist_n).
-template <int MW>
-__global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery* __restrict__ qp,
+// NT threads per block: one wavefront where the state is in LDS; eight where it lies in the block's slice of
+// global memory (R * k * MW words: 16 MiB for 512 devices and chunks), so that a pass over it is the work of
+// eight wavefronts' loads in flight instead of one's.
+template <int MW, int NT>
+__global__ __launch_bounds__(NT) void k_front_classify_literal(const DevQuery* __restrict__ qp,
                                                                   const FrontEntry* __restrict__ entries, uint32_t n_entries,
                                                                   const uint32_t* __restrict__ elist,
                                                                   const uint32_t* __restrict__ elist_n,
@@ -1280,29 +1303,15 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
     for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
         const uint32_t e = elist ? elist[i] : i;
         const unsigned long long digits = entries[e].digits;
-        lit_init<MW>(q, L, lane);
+        lit_init<MW>(q, L, lane, NT);
         for (int t = 0; t < parent_len; ++t) {
             const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
-            lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr);
+            lit_step<MW, false>(q, q.pat[ins >> 3], (int)(ins & 7u), L, lane, nullptr, NT);
         }
-        const int C = row_classes<MW>(q, L, X, full, lane);
+        const int C = row_classes<MW>(q, L, X, full, lane, NT);
         // At the size limit only goals count, and few instructions can reach the goal from a given state (see
         // cls_judge_all): the others are not looked at.
-        bool rows_full = true, cols_full = true, root_done = true;
-        if (goals_only) {
-            bool rows_bad = false, cols_bad = false;
-            for (int d = lane; d < R; d += kWave)
-                for (int row = 0; row < q.k; ++row) {
-                    const uint32_t* x = L.S + ((size_t)d * q.k + row) * MW;
-                    bool ne = false, fl = true;
-#pragma unroll
-                    for (int w = 0; w < MW; ++w) { ne |= x[w] != 0u; fl &= x[w] == full[w]; }
-                    rows_bad |= !ne; cols_bad |= ne && !fl;
-                }
-            rows_full = !__any(rows_bad);
-            cols_full = !__any(cols_bad);
-            root_done = X.devfull[0] != 0u;
-        }
+        const bool rows_full = rows_all_held(X), cols_full = held_rows_complete(X), root_done = X.devfull[0] != 0u;
         for (int a = 0; a < I; ++a) {
             const uint32_t ins = q.instr_of_digit[a];
             const DevPattern& P = q.pat[ins >> 3];
@@ -1312,7 +1321,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_literal(const DevQuery
                 const int op = (int)(ins & 7u);
                 if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
             }
-            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane);
+            const int code = lit_classify<MW>(q, P, (int)(ins & 7u), L, X, C, full, lane, NT);
             if (code != 0 && lane == 0) {
                 const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
                 if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
@@ -1771,6 +1780,8 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
 // The state of the class kernels holds up to 64 classes of rows; entries that would need more are evaluated
 // on the full literal state.  A caller may lower the limit (p2_options.max_row_classes), which sends entries
 // down that path.
+// threads of a block of the full-state kernel where the state lies in global memory
+constexpr int kFullThreads = 512;
 static int row_class_cap(int asked) { return asked >= 1 && asked < 64 ? asked : 64; }
 
 // Scratch of launch_front_classify_literal: the slices of the full-state kernel (where that state does not
@@ -1822,10 +1833,15 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     if (e == hipSuccess)                                                                                       \
         hipLaunchKernelGGL(k_front_classify_classes<MWV>, dim3(cls_blocks), dim3(kWave), sc.cls_lds, stream, q, entries, n, \
                            parent_len, goals_only, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap); \
-    if (e == hipSuccess) e = allow_big_lds(k_front_classify_literal<MWV>, sc.full_lds);                        \
-    if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_front_classify_literal<MWV>, dim3(full_blocks), dim3(kWave), sc.full_lds, stream, q, entries, n, \
-                           over, &ctr->n_overflow, parent_len, goals_only, surv, surv_cap, ctr, full_mem, full_words_per);
+    if (e == hipSuccess && sc.full_lds) {                                                                      \
+        e = allow_big_lds(k_front_classify_literal<MWV, kWave>, sc.full_lds);                                  \
+        if (e == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL((k_front_classify_literal<MWV, kWave>), dim3(full_blocks), dim3(kWave), sc.full_lds, stream, q, entries, n, \
+                               over, &ctr->n_overflow, parent_len, goals_only, surv, surv_cap, ctr, full_mem, full_words_per); \
+    } else if (e == hipSuccess) {                                                                              \
+        hipLaunchKernelGGL((k_front_classify_literal<MWV, kFullThreads>), dim3(full_blocks), dim3(kFullThreads), 0, stream, q, entries, n, \
+                           over, &ctr->n_overflow, parent_len, goals_only, surv, surv_cap, ctr, full_mem, full_words_per); \
+    }
     switch (mask_words(R)) {
     case 1: P2_LAUNCH(1) break;
     case 2: P2_LAUNCH(2) break;
