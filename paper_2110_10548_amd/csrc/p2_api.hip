@@ -122,6 +122,7 @@ struct FrontSlot {
     DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, lit_scratch;
     DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
     DevBuf f_sid[2], f_sid2[2], f_delta[3], f_childof[2], f_ssurv;                           // prefixes -> states -> children
+    DevBuf f_walk[2];                                                                        // the last level: states worth a walk
     HostBuf h_fctr;
     SpanRec spans;
     // what the slot's launches of this call worked on (the figures of p2_profile)
@@ -141,7 +142,7 @@ struct FrontSlot {
                          &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1], &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal,
                          &f_unknown, &f_ctr, &lit_scratch, &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1],
                          &f_replist[0], &f_replist[1], &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1], &f_sid[0], &f_sid[1], &f_sid2[0],
-                         &f_sid2[1], &f_delta[0], &f_delta[1], &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv};
+                         &f_sid2[1], &f_delta[0], &f_delta[1], &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv, &f_walk[0], &f_walk[1]};
         for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
         if (h_fctr.p) (void)hipHostFree(h_fctr.p);
         h_fctr.p = nullptr; h_fctr.cap = 0;
@@ -934,13 +935,34 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             };
             P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
             { const int32_t rc = literal_on_side(); if (rc != P2_OK) return rc; }
+            // At the last level only goals count: a filter first leaves the classification the few states from which an
+            // instruction can still end at the goal.
+            const uint32_t* cls_list[2]; const uint32_t* cls_n[2];
+            for (int li = 0; li < 2; ++li) {
+                cls_list[li] = grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr;
+                cls_n[li] = grouped[li] ? &dctr->n_reps[li] : nullptr;
+            }
+            if (!keep && n_s[0] + n_s[1] > 0) {
+                P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
+                for (int li = 0; li < 2; ++li) {
+                    if (n_s[li] == 0) continue;
+                    P2_HIP(S.f_walk[li].ensure((size_t)n_s[li] * sizeof(uint32_t)));
+                    P2_HIP(launch_front_goal_filter(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li], cls_list[li],
+                                                    cls_n[li], li + 1, static_cast<uint8_t*>(S.f_codes[li].p),
+                                                    static_cast<uint8_t*>(S.f_unk[li].p), static_cast<uint32_t*>(S.f_walk[li].p),
+                                                    &dctr->n_walk[li], S.stream));
+                    cls_list[li] = static_cast<const uint32_t*>(S.f_walk[li].p);
+                    cls_n[li] = &dctr->n_walk[li];
+                }
+                P2_HIP(S.spans.end(S.stream));
+            }
             if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.begin(SpanRec::kClassify, S.stream, (n_s[0] > 0) + (n_s[1] > 0)));
             for (int li = 0; li < 2; ++li)
-                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li],
-                                             grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr,
-                                             grouped[li] ? &dctr->n_reps[li] : nullptr, li + 1, max_pairs,
-                                             static_cast<uint8_t*>(S.f_codes[li].p), static_cast<uint8_t*>(S.f_unk[li].p), S.stream));
+                P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li], cls_list[li],
+                                             cls_n[li], li + 1, max_pairs, keep ? 0 : 1,
+                                             static_cast<uint8_t*>(S.f_codes[li].p), static_cast<uint8_t*>(S.f_unk[li].p), dctr, S.stream));
             if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.end(S.stream));
+            uint32_t walked_planes = 0;
             for (int attempt = 0;; ++attempt) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
                 P2_HIP(S.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 if (attempt > 0) {
@@ -969,6 +991,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 if (n_l > 0) P2_HIP(hipStreamWaitEvent(S.stream, S.side_done, 0));
                 P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
                 P2_HIP(hipStreamSynchronize(S.stream));
+                if (attempt == 0) walked_planes = hctr->n_walked_planes;    // (a repeat clears the level's counters)
                 n_surv_l_first = hctr->n_surv_literal;
                 if (hctr->n_unknown > 0 && hctr->n_surv_literal <= cap_l) {
                     // two-pair prefixes that this form could not judge: the literal kernels classify them from their
@@ -995,7 +1018,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
             {   // what the classification launches of this level worked on
                 const double j1 = grouped[0] ? (double)hctr->n_reps[0] : (double)n_s[0], j2 = grouped[1] ? (double)hctr->n_reps[1] : (double)n_s[1];
-                const double planes = j1 + 2.0 * j2;
+                // (at the last level only the states from which an instruction can still end at the goal are walked)
+                const double planes = keep ? j1 + 2.0 * j2 : (double)walked_planes;
                 S.prof_entries += (double)n_c + n_c2;
                 S.prof_prefixes += j1 + j2;
                 S.prof_state_bytes += planes * pl.R * pair_words * 4.0;

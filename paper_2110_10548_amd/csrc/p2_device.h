@@ -261,7 +261,9 @@ struct FrontCounters {
     uint32_t t_count[3];           // children of the judged states, by kind: one-pair states, two-pair states, goals
     uint32_t t_next[3];            // ... places handed out so far
     uint32_t n_ssurv;              // ... entries of their list
-    uint32_t pad0;
+    uint32_t n_walked_planes;      // planes of the states whose patterns the classification walked (the last level skips
+                                   // the states from which no instruction can end at the goal)
+    uint32_t n_walk[2];            // the last level: states of the one-pair / two-pair list left to the classification
     // running totals of the enumeration
     unsigned long long steps, members;
     // distinct states found among the entries of the one-pair / two-pair list (cleared before each level's search)
@@ -328,8 +330,14 @@ hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const 
 // cannot judge the entry.  np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends
 // children that need two pairs to the literal list.
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, uint8_t* codes, uint8_t* unknown,
-                                 hipStream_t stream);
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes, uint8_t* unknown,
+                                 FrontCounters* ctr, hipStream_t stream);
+// The last level, before the classification (which then runs with goals_only on the list this leaves): the entries
+// from which no instruction can end at the goal get a row of invalid codes; the others are listed in
+// walk[0 .. *n_walk) (*n_walk zero on entry; any order).
+hipError_t launch_front_goal_filter(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
+                                    const uint32_t* n_list, int np, uint8_t* codes, uint8_t* unknown, uint32_t* walk, uint32_t* n_walk,
+                                    hipStream_t stream);
 // The survivors of every entry of a list from the codes of the entry that stands for its state (rep null: its own):
 // appended to surv with their places in the next frontier; entries that cannot be judged go to unknown_out
 // (counted in n_unknown); handover != 0 treats every entry so (the hand-over path, for tests).

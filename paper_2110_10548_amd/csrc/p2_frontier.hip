@@ -281,10 +281,13 @@ struct ClsFound { uint32_t bits; int goal_part, two_part; };
 
 // Per device: is it empty, is it at the goal, does it hold two pairs.  The wavefront takes the devices
 // first + slot, first + stride + slot, ...; at_goal and with_two come back summed over the wavefront.
+// With `shortfalls`, also (for the filter of the last level): rows_short = devices that lack a row, cols_short =
+// devices that hold rows whose columns are not all there.
 template <int KW, int MW, int NP>
-__device__ inline void cls_flags(const ClsLane<KW, MW, NP>& c, uint8_t* flags, int first, int stride, int& at_goal, int& with_two) {
+__device__ inline void cls_flags(const ClsLane<KW, MW, NP>& c, uint8_t* flags, int first, int stride, int& at_goal, int& with_two,
+                                 bool shortfalls, int& rows_short, int& cols_short) {
     using L = FL<KW, MW>;
-    at_goal = 0; with_two = 0;
+    at_goal = 0; with_two = 0; rows_short = 0; cols_short = 0;
     for (int d0 = first; d0 < c.R; d0 += stride) {
         const int d = d0 + c.slot;
         const bool act = d < c.R && c.has_quad;
@@ -293,6 +296,12 @@ __device__ inline void cls_flags(const ClsLane<KW, MW, NP>& c, uint8_t* flags, i
         const unsigned long long nz = __ballot(act && c.is_row && q_any(v));
         const unsigned long long ng = __ballot(act && q_any(q_xor(v, c.goal_quad)));
         const unsigned long long n2 = NP == 2 ? __ballot(act && c.is_row && q_any(v1)) : 0ull;
+        unsigned long long rs = 0ull, m0 = 0ull, m1 = 0ull;
+        if (shortfalls) {
+            rs = __ballot(act && c.is_row && q_any(q_xor(q_or(v, v1), c.goal_quad)));
+            m0 = __ballot(act && c.is_mask && q_any(q_xor(v, c.goal_quad)));
+            m1 = NP == 2 ? __ballot(act && c.is_mask && q_any(q_xor(v1, c.goal_quad))) : 0ull;
+        }
         if (c.qd == 0 && d < c.R) {
             const int sh = c.slot * 8;
             const bool empty = ((nz >> sh) & 0xffull) == 0ull, two = ((n2 >> sh) & 0xffull) != 0ull;
@@ -300,16 +309,22 @@ __device__ inline void cls_flags(const ClsLane<KW, MW, NP>& c, uint8_t* flags, i
             flags[d] = (uint8_t)((empty ? kFlagEmpty : 0u) | (goal ? kFlagGoal : 0u) | (two ? kFlagTwo : 0u));
             at_goal += goal ? 1 : 0;
             with_two += two ? 1 : 0;
+            rows_short += ((rs >> sh) & 0xffull) != 0ull ? 1 : 0;
+            cols_short += ((!empty && ((m0 >> sh) & 0xffull) != 0ull) || (two && ((m1 >> sh) & 0xffull) != 0ull)) ? 1 : 0;
         }
     }
-    for (int o = 32; o > 0; o >>= 1) { at_goal += __shfl_xor(at_goal, o, 64); with_two += __shfl_xor(with_two, o, 64); }
+    for (int o = 32; o > 0; o >>= 1) {
+        at_goal += __shfl_xor(at_goal, o, 64); with_two += __shfl_xor(with_two, o, 64);
+        rows_short += __shfl_xor(rows_short, o, 64); cols_short += __shfl_xor(cols_short, o, 64);
+    }
 }
 
 // The batches [first_batch, first_batch + n_batches) of a pattern's groups (8 slots side by side: a batch is
 // 8 groups, or fewer groups with several slots each), every rule at once.  Stops early once every rule of the
-// pattern has failed.
+// pattern has failed; with goal_ops >= 0 (the last level: bit 0 / 1 / 2 = an AllReduce / AllGather / Broadcast may
+// still end at the goal) also once every rule has failed or has left some device short of the goal.
 template <int KW, int MW, int NP>
-__device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P, int first_batch, int n_batches) {
+__device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P, int first_batch, int n_batches, int goal_ops) {
     using L = FL<KW, MW>;
     const uint4* const ldsq = c.ldsq;
     const int plane_q = c.plane_q, slot = c.slot, qd = c.qd;
@@ -424,13 +439,19 @@ __device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P
                 if (is_row) bc_fail |= q_any(q_xor(p.o, q_or(first0, first1)));
                 else bc_fail |= q_any(q_andn(al.o, q_or(first0, first1)));
                 bc_fail |= !differs_g;
-                ng_ar |= q_any(q_xor(p.o, goal_quad)) || split_g;
+                // (what the masks of a group that is not aligned come to is not known here: cls_codes asks for this bit
+                //  only where every group is aligned, and the last level's early exit must not go by a guess)
+                ng_ar |= (is_row && q_any(q_xor(p.o, goal_quad))) || (!unal_g && (q_any(q_xor(p.o, goal_quad)) || split_g));
                 ng_ag |= q_any(q_xor(is_row ? p.o : al.o, goal_quad));
                 ng_bc |= q_any(q_xor(first0, goal_quad)) || q_any(first1);
             }
         }
         // every rule of the pattern has failed already: the other groups cannot change that
-        if (__any(bad_red) && __any(bad_ag) && __any(bad_bc1 && (NP == 1 || bc_fail))) break;
+        const bool dead_red = __any(bad_red), dead_ag = __any(bad_ag), dead_bc = __any(bad_bc1 && (NP == 1 || bc_fail));
+        if (dead_red && dead_ag && dead_bc) break;
+        if (goal_ops >= 0 && (!(goal_ops & 1) || dead_red || __any(ng_ar)) && (!(goal_ops & 2) || dead_ag || __any(ag_uneq) || __any(ng_ag)) &&
+            (!(goal_ops & 4) || dead_bc || __any(ng_bc)))
+            break;
     }
     ClsFound f;
     uint32_t bits = 0;
@@ -564,11 +585,13 @@ __device__ inline int cls_bcast_pairs(const ClsLane<KW, MW, NP>& c, const PatLds
     return 1 | (__any(any_two) ? 2 : 0) | (__any(not_goal) ? 0 : 4);
 }
 
-// One lane: the codes of a pattern's instructions from what its groups have shown.
+// One lane: the codes of a pattern's instructions from what its groups have shown.  goal_ops < 0: every code;
+// else (the last level, where only goals count) bit 0 / 1 / 2: an AllReduce / AllGather / Broadcast may still end
+// at the goal, and everything that does not (or that this form cannot judge) is written as invalid.
 template <int KW, int MW, int NP>
 __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, int pid, uint32_t pf, int goal_part, int two_part,
                                  int n_goal, int n_two, bool MANY_MASKS, int bc_pairs, const int (&ops_r)[5], int n_ops, int max_pairs,
-                                 const Words<KW>& all_rows, const Words<MW>& all_cols, uint8_t* __restrict__ codes,
+                                 const Words<KW>& all_rows, const Words<MW>& all_cols, int goal_ops, uint8_t* __restrict__ codes,
                                  uint8_t* __restrict__ unknown) {
     const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(c.ldsq);
     const int R = c.R;
@@ -583,8 +606,11 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
         const int op = ops_r[oi];
         if (op < 0) continue;
         int code;
-        if (op == OP_AR || op == OP_RS || op == OP_RD) {
+        if (goal_ops >= 0 && !((op == OP_AR && (goal_ops & 1)) || (op == OP_AG && (goal_ops & 2)) || (op == OP_BC && (goal_ops & 4)))) {
+            code = CODE_INVALID;                         // (last level: this instruction cannot end at the goal)
+        } else if (op == OP_AR || op == OP_RS || op == OP_RD) {
             if (BAD_RED || !CHANGED || (op == OP_RS && BAD_RS)) code = CODE_INVALID;
+            else if (goal_ops >= 0 && NG_AR) code = CODE_INVALID;       // (last level: some device is left short of the goal)
             else if (UNAL) code = CODE_UNKNOWN;
             else if (BAD_B) code = CODE_INVALID;
             else if (op == OP_RS) {
@@ -602,6 +628,7 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
             else code = ((bc_pairs & 2) || rest_two) ? CODE_PREFIX2 : ((bc_pairs & 4) && rest_done) ? CODE_GOAL : CODE_PREFIX;
         }
         if (code == CODE_PREFIX2 && max_pairs < 2) code = CODE_PREFIX_LITERAL;
+        if (goal_ops >= 0 && code != CODE_GOAL && code != CODE_UNKNOWN) code = CODE_INVALID;    // (last level: goals only)
         if (code == CODE_UNKNOWN) *unknown = 1;          // (after the block's barriers that follow the clearing)
         codes[pid * n_ops + oi] = (uint8_t)code;
     }
@@ -752,17 +779,72 @@ __device__ inline uint4 goal_quad_of(const Words<KW>& all_rows, const Words<MW>&
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// ---- the last level: which states are worth a walk ---------------------------------------------------
+// At the size limit only goals count, and one instruction ends at the goal only from a state that is nearly there:
+// an AllReduce leaves the rows of its members as they are and touches no other device, so every device must hold
+// every row already; an AllGather leaves the columns of the rows it moves as they are, so every row that a device
+// holds must carry every column; a Broadcast makes its members equal to their roots, and device 0 is a root of
+// every pattern, so device 0 must be at the goal.  A wavefront per state reads the devices straight from device
+// memory (8 at a time, a lane per quad) until all three have failed, in which case the state's row of codes is
+// written as invalid; the other states go on the list walk[0 .. *n_walk) for the classification kernel.
+template <int KW, int MW, int NP>
+__global__ __launch_bounds__(256) void k_front_goal_filter(const DevQuery* __restrict__ qp, const uint32_t* __restrict__ states,
+                                                           uint32_t n_entries, const uint32_t* __restrict__ list,
+                                                           const uint32_t* __restrict__ n_list, uint8_t* __restrict__ codes,
+                                                           uint8_t* __restrict__ unknown, uint32_t* __restrict__ walk,
+                                                           uint32_t* __restrict__ n_walk) {
+    using L = FL<KW, MW>;
+    const DevQuery& q = *qp;
+    const int R = q.R, I = q.alphabet;
+    const int plane_q = R * L::WQ;
+    const int lane = threadIdx.x & 63, slot = lane >> 3, qd = lane & 7, sh = slot * 8;
+    const bool is_row = qd < L::QK, is_mask = qd >= L::QK && qd < L::WQ, has_quad = qd < L::WQ;
+    const uint4 goal_quad = goal_quad_of<KW, MW>(full_mask<KW>(q.k), full_mask<MW>(R), qd, is_row, is_mask);
+    const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = gridDim.x * 4u;
+    const uint32_t n_work = list ? *n_list : n_entries;
+    for (uint32_t at = wave; at < n_work; at += n_waves) {
+        const uint32_t e = list ? list[at] : at;
+        const uint4* src = reinterpret_cast<const uint4*>(states) + (size_t)e * NP * plane_q;
+        bool rows_short = false, cols_short = false, root_short = false;
+        for (int d0 = 0; d0 < R; d0 += 8) {
+            const int d = d0 + slot;
+            const bool act = d < R && has_quad;
+            const uint4 v = act ? src[d * L::WQ + qd] : q_zero();
+            const uint4 v1 = (NP == 2 && act) ? src[plane_q + d * L::WQ + qd] : q_zero();
+            const unsigned long long nz = __ballot(act && is_row && q_any(v));
+            const unsigned long long ng = __ballot(act && q_any(q_xor(v, goal_quad)));
+            const unsigned long long n2 = NP == 2 ? __ballot(act && is_row && q_any(v1)) : 0ull;
+            const unsigned long long rs = __ballot(act && is_row && q_any(q_xor(q_or(v, v1), goal_quad)));
+            const unsigned long long m0 = __ballot(act && is_mask && q_any(q_xor(v, goal_quad)));
+            const unsigned long long m1 = NP == 2 ? __ballot(act && is_mask && q_any(q_xor(v1, goal_quad))) : 0ull;
+            if (d < R) {
+                const bool empty = ((nz >> sh) & 0xffull) == 0ull, two = ((n2 >> sh) & 0xffull) != 0ull;
+                rows_short |= ((rs >> sh) & 0xffull) != 0ull;
+                cols_short |= (!empty && ((m0 >> sh) & 0xffull) != 0ull) || (two && ((m1 >> sh) & 0xffull) != 0ull);
+                if (d == 0) root_short = ((ng >> sh) & 0xffull) != 0ull || two;
+            }
+            if (__any(rows_short) && __any(cols_short) && __any(root_short)) break;
+        }
+        if (__any(rows_short) && __any(cols_short) && __any(root_short)) {
+            for (int a = lane; a < I; a += 64) codes[(size_t)e * I + a] = (uint8_t)CODE_INVALID;
+            if (lane == 0) unknown[e] = 0;
+        } else if (lane == 0) {
+            walk[atomicAdd(n_walk, 1u)] = e;
+        }
+    }
+}
+
 // ---- a block per prefix ---------------------------------------------------------------------------------
 template <int KW, int MW, int NP>
 // (second bound: wavefronts per SIMD, so that two blocks of one-plane states share a compute unit)
 __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify(const DevQuery* __restrict__ qp,
                                                                 const uint32_t* __restrict__ states, uint32_t n_entries,
                                                                 const uint32_t* __restrict__ list, const uint32_t* __restrict__ n_list,
-                                                                int max_pairs, uint8_t* __restrict__ codes,
-                                                                uint8_t* __restrict__ unknown) {
+                                                                int max_pairs, int goals_only, uint8_t* __restrict__ codes,
+                                                                uint8_t* __restrict__ unknown, FrontCounters* __restrict__ ctr) {
     extern __shared__ uint4 ldsq[];                      // NP planes of [R][WQ] quads, then R flag bytes
     __shared__ PatLds spat[kMaxPatterns];
-    __shared__ int s_goal, s_two, s_next, s_n_items;
+    __shared__ int s_goal, s_two, s_next, s_n_items, s_rows_short, s_cols_short;
     __shared__ uint32_t s_pflags[kMaxPatterns];
     __shared__ int s_pgoal[kMaxPatterns], s_ptwo[kMaxPatterns];
     __shared__ ClsItem s_items[kMaxPatterns * kClsChunks];
@@ -808,6 +890,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
 #pragma unroll
     for (int i = 0; i < 5; ++i) { ops_r[i] = i < n_ops ? q.ops[i] : -1; has_bcast |= ops_r[i] == OP_BC; }
     const uint32_t n_work = list ? *n_list : n_entries;
+    uint32_t walked = 0;                                 // states whose patterns were walked (thread 0 counts)
     for (uint32_t at = blockIdx.x; at < n_work; at += gridDim.x) {
         const uint32_t e = list ? list[at] : at;
         __syncthreads();
@@ -820,17 +903,34 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
 #pragma unroll
             for (int u = 0; u < 8; ++u) { const int i = i0 + u * kClsThreads; if (i < NP * plane_q) ldsq[i] = tmp[u]; }
         }
-        if (tid == 0) { s_goal = 0; s_two = 0; s_next = 0; unknown[e] = 0; }
+        if (tid == 0) { s_goal = 0; s_two = 0; s_next = 0; s_rows_short = 0; s_cols_short = 0; unknown[e] = 0; }
         for (int i = tid; i < n_pat; i += kClsThreads) { s_pflags[i] = 0u; s_pgoal[i] = 0; s_ptwo[i] = 0; }
         __syncthreads();
         {
-            int at_goal, with_two;
-            cls_flags<KW, MW, NP>(c, flags, wave * 8, kClsWaves * 8, at_goal, with_two);
+            int at_goal, with_two, rows_short, cols_short;
+            cls_flags<KW, MW, NP>(c, flags, wave * 8, kClsWaves * 8, at_goal, with_two, goals_only != 0, rows_short, cols_short);
             if (lane == 0 && at_goal) atomicAdd(&s_goal, at_goal);
             if (lane == 0 && with_two) atomicAdd(&s_two, with_two);
+            if (lane == 0 && rows_short) atomicAdd(&s_rows_short, rows_short);
+            if (lane == 0 && cols_short) atomicAdd(&s_cols_short, cols_short);
         }
         __syncthreads();
         const int n_goal = s_goal, n_two = s_two, n_items = s_n_items;
+        // At the size limit only goals count, and one instruction ends at the goal only from a state that is nearly
+        // there: an AllReduce leaves the rows of its members as they are and touches no other device, so every device
+        // must hold every row already; an AllGather leaves the columns of the rows it moves as they are, so every row
+        // that a device holds must carry every column; a Broadcast makes its members equal to their roots, and device 0
+        // is a root of every pattern, so device 0 must be at the goal.  A state that fails all three has no goal among
+        // its extensions and is not walked.
+        int goal_ops = -1;
+        if (goals_only) {
+            goal_ops = (s_rows_short == 0 ? 1 : 0) | (s_cols_short == 0 ? 2 : 0) | ((flags[0] & kFlagGoal) ? 4 : 0);
+            if (goal_ops == 0) {
+                for (int a = tid; a < I; a += kClsThreads) codes[(size_t)e * I + a] = (uint8_t)CODE_INVALID;
+                continue;
+            }
+        }
+        if (tid == 0) ++walked;
         // ---- stage A: the patterns' groups, cut into work items that the wavefronts take as they come (patterns
         //      differ widely in cost, and a pattern whose rules have all failed is dropped at once); what an item
         //      finds goes into its pattern's flag word
@@ -844,9 +944,13 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             const int pid = W.pid;
             {
                 const uint32_t pf = s_pflags[pid];
-                if ((pf & kPfBadRed) && (pf & kPfBadAg) && (pf & kPfBadBc1) && (NP == 1 || (pf & kPfBcFail))) continue;
+                const bool dead_red = pf & kPfBadRed, dead_ag = pf & kPfBadAg, dead_bc = (pf & kPfBadBc1) && (NP == 1 || (pf & kPfBcFail));
+                if (dead_red && dead_ag && dead_bc) continue;
+                if (goal_ops >= 0 && (!(goal_ops & 1) || dead_red || (pf & kPfNgAr)) && (!(goal_ops & 2) || dead_ag || (pf & (kPfAgUneq | kPfNgAg))) &&
+                    (!(goal_ops & 4) || dead_bc || (pf & kPfNgBc)))
+                    continue;
             }
-            const ClsFound f = cls_walk<KW, MW, NP>(c, spat[pid], W.first_batch, W.n_batches);
+            const ClsFound f = cls_walk<KW, MW, NP>(c, spat[pid], W.first_batch, W.n_batches, goal_ops);
             if (lane == 0) {
                 if (f.bits) atomicOr(&s_pflags[pid], f.bits);
                 if (f.goal_part) atomicAdd(&s_pgoal[pid], f.goal_part);
@@ -858,14 +962,16 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
         for (int pid = wave; pid < n_pat; pid += kClsWaves) {
             const PatLds P = spat[pid];
             const uint32_t pf = s_pflags[pid];
-            const bool many = (!(pf & kPfBadAg) && (pf & kPfAgUneq)) ? cls_many_masks<KW, MW, NP>(c, P) : false;
+            // (an AllGather of members with different masks is no goal: how many masks it leaves is not asked at the last level)
+            const bool many = (goal_ops < 0 && !(pf & kPfBadAg) && (pf & kPfAgUneq)) ? cls_many_masks<KW, MW, NP>(c, P) : false;
             int bc_pairs = 0;                            // (Broadcast among two-pair devices: the pairs compared)
-            if (NP == 2 && has_bcast && (pf & kPfPatTwo) && !(pf & kPfBcFail)) bc_pairs = cls_bcast_pairs<KW, MW, NP>(c, P);
+            if (NP == 2 && has_bcast && (goal_ops & 4) && (pf & kPfPatTwo) && !(pf & kPfBcFail)) bc_pairs = cls_bcast_pairs<KW, MW, NP>(c, P);
             if (lane == 0)
                 cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, ops_r, n_ops, max_pairs,
-                                      all_rows, all_cols, codes + (size_t)e * I, unknown + e);
+                                      all_rows, all_cols, goal_ops, codes + (size_t)e * I, unknown + e);
         }
     }
+    if (tid == 0 && walked) atomicAdd(&ctr->n_walked_planes, walked * (uint32_t)NP);
 }
 
 __device__ inline unsigned long long rank_of(const DevQuery& q, unsigned long long digits, int len) {
@@ -1378,7 +1484,8 @@ struct FrontArgs {
     const FrontEntry* entries; const uint32_t* states; uint32_t n;
     int np, max_pairs;
     const uint32_t* list; const uint32_t* n_list;
-    uint8_t* codes; uint8_t* unknown;
+    uint8_t* codes; uint8_t* unknown; int goals_only; FrontCounters* ctr;
+    uint32_t* walk; uint32_t* n_walk;
     double* sums; uint32_t* sid; int n_share;
     const DevQuery* queries; const FrontLevel* level;
     int R;
@@ -1399,10 +1506,20 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
         if (e != hipSuccess) return e;
         if (A.np == 2)
             hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.codes, A.unknown);
+                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.unknown, A.ctr);
         else
             hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.codes, A.unknown);
+                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.unknown, A.ctr);
+    } else if (what == 3) {
+        // a wavefront per state, four to a block
+        const unsigned want = (A.n + 3u) / 4u;
+        const unsigned blocks = want < 16384u ? want : 16384u;
+        if (A.np == 2)
+            hipLaunchKernelGGL((k_front_goal_filter<KW, MW, 2>), dim3(blocks), dim3(256), 0, stream, A.q, A.states, A.n, A.list, A.n_list,
+                               A.codes, A.unknown, A.walk, A.n_walk);
+        else
+            hipLaunchKernelGGL((k_front_goal_filter<KW, MW, 1>), dim3(blocks), dim3(256), 0, stream, A.q, A.states, A.n, A.list, A.n_list,
+                               A.codes, A.unknown, A.walk, A.n_walk);
     } else {
         const size_t lds = (size_t)A.level->lds_planes * A.R * FL<KW, MW>::WS * 4;
         const unsigned blocks = A.level->n_surv < 8192u ? A.level->n_surv : 8192u;
@@ -1475,13 +1592,23 @@ hipError_t launch_front_prefixes(const DevQuery* queries, const FrontPrefixes& P
     return hipGetLastError();
 }
 
+hipError_t launch_front_goal_filter(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
+                                    const uint32_t* n_list, int np, uint8_t* codes, uint8_t* unknown, uint32_t* walk, uint32_t* n_walk,
+                                    hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    FrontArgs A{};
+    A.q = q; A.states = states; A.n = n; A.np = np; A.list = list; A.n_list = n_list;
+    A.codes = codes; A.unknown = unknown; A.R = R; A.walk = walk; A.n_walk = n_walk;
+    return front_dispatch(R, k, 3, A, stream);
+}
+
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, uint8_t* codes, uint8_t* unknown,
-                                 hipStream_t stream) {
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes, uint8_t* unknown,
+                                 FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
     A.q = q; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.list = list; A.n_list = n_list;
-    A.codes = codes; A.unknown = unknown; A.R = R;
+    A.codes = codes; A.unknown = unknown; A.R = R; A.goals_only = goals_only; A.ctr = ctr;
     return front_dispatch(R, k, 1, A, stream);
 }
 
