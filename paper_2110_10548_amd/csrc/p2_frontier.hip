@@ -107,93 +107,6 @@ __device__ inline void fstore(uint32_t* plane, int dev, const Words<KW>& r, cons
     for (int i = 0; i < MW; ++i) p[FL<KW, MW>::MO + i] = m.w[i];
 }
 
-// The (up to) two pairs of a device: x1 empty <=> one pair.
-template <int KW, int MW>
-struct Pairs {
-    Words<KW> x0, x1;
-    Words<MW> m0, m1;
-};
-template <int KW, int MW>
-__device__ inline Pairs<KW, MW> load_pairs(const uint32_t* st, int R, int np, int dev) {
-    const Slot<KW, MW> a = fload<KW, MW>(st, dev);
-    Pairs<KW, MW> p;
-    p.x0 = a.r; p.m0 = a.m;
-    if (np == 2) {
-        const Slot<KW, MW> b = fload<KW, MW>(st + R * FL<KW, MW>::WS, dev);
-        p.x1 = b.r; p.m1 = b.m;
-    } else {
-        p.x1 = zero_words<KW>(); p.m1 = zero_words<MW>();
-    }
-    return p;
-}
-// ---- one AllReduce-like group on (up to) two-pair members --------------------------------------------
-template <int KW, int MW>
-struct RedFold {
-    Words<KW> u0;         // rows every member holds
-    Words<KW> xa;         // rows of plane A where the group is split (pair 0 of the members with two pairs)
-    Words<MW> accA, accB; // united masks of plane A (rows xa) and plane B (rows u0 \ xa); equal when not split
-    bool split;           // some member has two pairs
-    uint32_t bad;         // rows differ between members, or a contribution would be reduced twice in plane A (every
-                          // member's pair 0 holds the lowest row, so an overlap there is one whatever the split)
-    uint32_t badB;        // a contribution reduced twice in plane B: means something only if the group is aligned
-    uint32_t unaligned;   // two members split their rows differently
-};
-template <int KW, int MW>
-__device__ inline RedFold<KW, MW> fold_red(const uint32_t* st, int R, int np, int base, int g, int s) {
-    RedFold<KW, MW> f;
-    Pairs<KW, MW> p = load_pairs<KW, MW>(st, R, np, base);
-    f.u0 = or_words(p.x0, p.x1);
-    f.split = fold_or(p.x1) != 0u;
-    f.xa = p.x0;
-    f.accA = p.m0;
-    f.accB = f.split ? p.m1 : p.m0;
-    f.bad = 0; f.badB = 0; f.unaligned = 0;
-    for (int t = 1; t < g; ++t) {
-        p = load_pairs<KW, MW>(st, R, np, base + t * s);
-        const bool two = fold_or(p.x1) != 0u;
-        f.bad |= fold_xor(or_words(p.x0, p.x1), f.u0);
-        if (two) {
-            if (f.split) f.unaligned |= fold_xor(p.x0, f.xa);
-            else { f.split = true; f.xa = p.x0; }
-        }
-        const Words<MW> mB = two ? p.m1 : p.m0;
-        f.bad |= fold_and(p.m0, f.accA);
-        f.badB |= fold_and(mB, f.accB);
-        f.accA = or_words(f.accA, p.m0);
-        f.accB = or_words(f.accB, mB);
-    }
-    return f;
-}
-
-__device__ inline int first_of_group(const PatLds& P, int G) {
-    const int gs = P.g * P.s;
-    return P.master ? G * gs : (G / P.s) * gs + (G % P.s);
-}
-
-// A ReduceScatter on a pattern whose groups are valid, aligned and split (some member holds two pairs): rank t keeps
-// the t-th block of the rows in ascending order; does a block fall on both sides of a split with different masks?
-// (Then that member holds two pairs afterwards.)  One lane walks the pairs; reads the state only.
-template <int KW, int MW>
-__device__ inline bool rs_straddles_split(const uint32_t* st, const PatLds P, int R, int np) {
-    bool straddles = false;
-    for (int G = 0; G < P.n_groups; ++G) {
-        const RedFold<KW, MW> f = fold_red<KW, MW>(st, R, np, first_of_group(P, G), P.g, P.s);
-        if (!f.split || fold_xor(f.accA, f.accB) == 0u) continue;
-        const int rows = popcount(f.u0);
-        if (rows == 0) continue;
-        const int per = div_small(rows, P.g);
-        Words<KW> prev = zero_words<KW>();
-        const Words<KW> xb = andn_words(f.u0, f.xa);
-        for (int t = 0; t < P.g; ++t) {
-            const Words<KW> upto = lowest_n(f.u0, (t + 1) * per);
-            const Words<KW> blk = andn_words(upto, prev);
-            prev = upto;
-            straddles |= fold_and(blk, f.xa) != 0u && fold_and(blk, xb) != 0u;
-        }
-    }
-    return straddles;
-}
-
 // ---- classification, a wavefront per pattern ----------------------------------------------------------
 // Block = one prefix (its planes in LDS), wavefront = one pattern at a time, all rules of that pattern at
 // once.  A lane is (slot, quad): the 8 lanes of a slot read one device with one 128-bit access each, so a
@@ -209,8 +122,8 @@ __device__ inline bool rs_straddles_split(const uint32_t* st, const PatLds P, in
 //   results: AllReduce leaves (rows, united mask), AllGather (united rows, mask), Broadcast the root's pair
 // On two-pair states the AllReduce-like rules are the same statements plane by plane (plane B of a member
 // with one pair is its only pair), plus: the members that have two pairs split their rows alike.  What
-// these word-wise accumulators cannot decide is rare and goes to the single-lane routines above, which walk
-// the pairs: an AllGather of members with different masks (how many masks?), a ReduceScatter of a split
+// these word-wise accumulators cannot decide goes to routines of its own, each a second walk of the pattern by
+// one wavefront: an AllGather of members with different masks (how many masks?), a ReduceScatter of a split
 // group (does a block straddle the split?), a Broadcast among two-pair devices that passes the
 // necessary conditions checked here.
 // The kernel writes a code per instruction of the alphabet for every entry it judges; the survivors are listed
@@ -263,6 +176,17 @@ __device__ inline int sum_slot(int v) {
     v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);      // quad_perm [2, 3, 0, 1]
     v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);     // row_half_mirror
     return v;
+}
+
+// The lowest n set bits of w (none for n <= 0, all for n >= popcount).
+__device__ inline uint32_t low_bits(uint32_t w, int n) {
+    if (n <= 0) return 0u;
+    if (n >= __popc(w)) return w;
+    int pos = 0;                                   // position of the n-th set bit: binary search on prefix counts
+#pragma unroll
+    for (int step = 16; step > 0; step >>= 1)
+        if (__popc(w & ((1u << (pos + step)) - 1u)) < n) pos += step;
+    return w & ((2u << pos) - 1u);
 }
 
 // ---- pieces of the classification kernel ------------------------------------------------------------------
@@ -585,15 +509,85 @@ __device__ inline int cls_bcast_pairs(const ClsLane<KW, MW, NP>& c, const PatLds
     return 1 | (__any(any_two) ? 2 : 0) | (__any(not_goal) ? 0 : 4);
 }
 
+// A ReduceScatter on a pattern whose groups are valid, aligned and split (some member holds two pairs), the
+// wavefront together: rank t keeps the t-th block of the group's rows in ascending order; does a block fall on both
+// sides of a split whose sides carry different masks?  (Then that member holds two pairs afterwards.)  Per group the
+// slots put together the rows (the same on every member), the pair-0 rows of the members with two pairs, and the
+// united masks of either side, as the kernel that builds the child does; then every rank's block is cut out of the
+// rows and looked at from both sides.
+template <int KW, int MW, int NP>
+__device__ inline bool cls_rs_straddles(const ClsLane<KW, MW, NP>& c, const PatLds P) {
+    using L = FL<KW, MW>;
+    const uint4* const ldsq = c.ldsq;
+    const int plane_q = c.plane_q, slot = c.slot, qd = c.qd, sh = slot * 8;
+    const bool is_row = c.is_row, is_mask = c.is_mask;
+    const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s;
+    int spg = 1;
+    while (spg * 2 * ng <= 8) spg *= 2;
+    const int gpb = 8 / spg;
+    const int my_g = slot / spg, part = slot - my_g * spg;
+    const int trips = (g + spg - 1) / spg;
+    bool straddles = false;
+    for (int G0 = 0; G0 < ng; G0 += gpb) {
+        const int G = G0 + my_g;
+        const bool act = G < ng && c.has_quad;
+        int base = 0;
+        if (P.master) base = G * gs;
+        else { const int hi = div_small(G, s); base = hi * gs + (G - hi * s); }
+        // row lanes: u = the rows, xa = pair-0 rows of the members with two pairs; mask lanes: u = united first
+        // masks, mb = united masks of the other side (a member with one pair has its only mask on both sides)
+        uint4 u = q_zero(), xa = q_zero(), mb = q_zero();
+        bool split = false;
+        for (int it = 0; it < trips; ++it) {
+            const int t = it * spg + part;
+            const bool on = act && t < g;
+            const int d = base + t * s;
+            const uint4 v0 = on ? ldsq[d * L::WQ + qd] : q_zero();
+            const uint4 v1 = (NP == 2 && on) ? ldsq[plane_q + d * L::WQ + qd] : q_zero();
+            const bool two = ((__ballot(is_row && q_any(v1)) >> sh) & 0xffull) != 0ull;
+            split |= two;
+            if (is_row) { u = q_or(u, q_or(v0, v1)); if (two) xa = q_or(xa, v0); }
+            else { u = q_or(u, v0); mb = q_or(mb, two ? v1 : v0); }
+        }
+        for (int m = 8; m < 8 * spg; m <<= 1) {
+            u = q_or(u, q_shfl_xor(u, m)); xa = q_or(xa, q_shfl_xor(xa, m)); mb = q_or(mb, q_shfl_xor(mb, m));
+            split |= __shfl_xor((int)split, m, 64) != 0;
+        }
+        const bool sides_differ = ((__ballot(act && is_mask && q_any(q_xor(u, mb))) >> sh) & 0xffull) != 0ull;
+        const int mine = (act && is_row) ? q_popc(u) : 0;
+        const int rows = sum_slot(mine);
+        const int per = div_small(rows, g);
+        int before = 0;                                  // rows in the quads below this lane's
+#pragma unroll
+        for (int j = 0; j < L::QK; ++j) { const int cnt = __shfl(mine, sh + j, 64); if (j < qd) before += cnt; }
+        const uint4 xb = q_andn(u, xa);
+        const bool look = act && split && sides_differ && rows > 0;
+        for (int it = 0; it < trips; ++it) {
+            const int t = it * spg + part;
+            const int lo = t * per, hi = lo + per;
+            uint4 blk = q_zero();
+            if (is_row) {
+                int p0 = before;
+                blk.x = low_bits(u.x, hi - p0) & ~low_bits(u.x, lo - p0); p0 += __popc(u.x);
+                blk.y = low_bits(u.y, hi - p0) & ~low_bits(u.y, lo - p0); p0 += __popc(u.y);
+                blk.z = low_bits(u.z, hi - p0) & ~low_bits(u.z, lo - p0); p0 += __popc(u.z);
+                blk.w = low_bits(u.w, hi - p0) & ~low_bits(u.w, lo - p0);
+            }
+            const unsigned long long on_a = __ballot(is_row && q_any(q_and(blk, xa))), on_b = __ballot(is_row && q_any(q_and(blk, xb)));
+            if (look && t < g && ((on_a >> sh) & 0xffull) != 0ull && ((on_b >> sh) & 0xffull) != 0ull) straddles = true;
+        }
+    }
+    return __any(straddles) != 0;
+}
+
 // One lane: the codes of a pattern's instructions from what its groups have shown.  goal_ops < 0: every code;
 // else (the last level, where only goals count) bit 0 / 1 / 2: an AllReduce / AllGather / Broadcast may still end
 // at the goal, and everything that does not (or that this form cannot judge) is written as invalid.
 template <int KW, int MW, int NP>
 __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, int pid, uint32_t pf, int goal_part, int two_part,
-                                 int n_goal, int n_two, bool MANY_MASKS, int bc_pairs, const int (&ops_r)[5], int n_ops, int max_pairs,
+                                 int n_goal, int n_two, bool MANY_MASKS, int bc_pairs, bool RS_STRADDLES, const int (&ops_r)[5], int n_ops, int max_pairs,
                                  const Words<KW>& all_rows, const Words<MW>& all_cols, int goal_ops, uint8_t* __restrict__ codes,
                                  uint8_t* __restrict__ unknown) {
-    const uint32_t* const lds_words = reinterpret_cast<const uint32_t*>(c.ldsq);
     const int R = c.R;
     const bool BAD_RED = pf & kPfBadRed, BAD_B = pf & kPfBadB, UNAL = pf & kPfUnal, BAD_RS = pf & kPfBadRs;
     const bool BAD_AG = pf & kPfBadAg, CHANGED = pf & kPfChanged, AG_UNEQ = pf & kPfAgUneq;
@@ -614,7 +608,7 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
             else if (UNAL) code = CODE_UNKNOWN;
             else if (BAD_B) code = CODE_INVALID;
             else if (op == OP_RS) {
-                code = ((ANY_TWO && rs_straddles_split<KW, MW>(lds_words, P, R, NP)) || rest_two) ? CODE_PREFIX2 : CODE_PREFIX;
+                code = ((ANY_TWO && RS_STRADDLES) || rest_two) ? CODE_PREFIX2 : CODE_PREFIX;
             } else if (ANY_TWO || rest_two) code = CODE_PREFIX2;
             else code = (op == OP_AR && !NG_AR && rest_done) ? CODE_GOAL : CODE_PREFIX;
         } else if (op == OP_AG) {
@@ -886,9 +880,9 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     c.is_row = c.qd < L::QK; c.is_mask = c.qd >= L::QK && c.qd < L::WQ; c.has_quad = c.qd < L::WQ;
     c.goal_quad = goal_quad_of<KW, MW>(all_rows, all_cols, c.qd, c.is_row, c.is_mask);
     int ops_r[5];
-    bool has_bcast = false;
+    bool has_bcast = false, has_scatter = false;
 #pragma unroll
-    for (int i = 0; i < 5; ++i) { ops_r[i] = i < n_ops ? q.ops[i] : -1; has_bcast |= ops_r[i] == OP_BC; }
+    for (int i = 0; i < 5; ++i) { ops_r[i] = i < n_ops ? q.ops[i] : -1; has_bcast |= ops_r[i] == OP_BC; has_scatter |= ops_r[i] == OP_RS; }
     const uint32_t n_work = list ? *n_list : n_entries;
     uint32_t walked = 0;                                 // states whose patterns were walked (thread 0 counts)
     for (uint32_t at = blockIdx.x; at < n_work; at += gridDim.x) {
@@ -966,8 +960,12 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             const bool many = (goal_ops < 0 && !(pf & kPfBadAg) && (pf & kPfAgUneq)) ? cls_many_masks<KW, MW, NP>(c, P) : false;
             int bc_pairs = 0;                            // (Broadcast among two-pair devices: the pairs compared)
             if (NP == 2 && has_bcast && (goal_ops & 4) && (pf & kPfPatTwo) && !(pf & kPfBcFail)) bc_pairs = cls_bcast_pairs<KW, MW, NP>(c, P);
+            // (ReduceScatter of a split group: asked where cls_codes gets as far as the question, and not at the last level)
+            bool rs_straddles = false;
+            if (NP == 2 && has_scatter && goal_ops < 0 && (pf & kPfAnyTwo) && !(pf & (kPfBadRed | kPfBadRs | kPfUnal | kPfBadB)) && (pf & kPfChanged))
+                rs_straddles = cls_rs_straddles<KW, MW, NP>(c, P);
             if (lane == 0)
-                cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, ops_r, n_ops, max_pairs,
+                cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, rs_straddles, ops_r, n_ops, max_pairs,
                                       all_rows, all_cols, goal_ops, codes + (size_t)e * I, unknown + e);
         }
     }
@@ -992,16 +990,6 @@ __device__ inline int min_slot(int v) {
     v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));
     v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));
     return v;
-}
-// The lowest n set bits of w (none for n <= 0, all for n >= popcount).
-__device__ inline uint32_t low_bits(uint32_t w, int n) {
-    if (n <= 0) return 0u;
-    if (n >= __popc(w)) return w;
-    int pos = 0;                                   // position of the n-th set bit: binary search on prefix counts
-#pragma unroll
-    for (int step = 16; step > 0; step >>= 1)
-        if (__popc(w & ((1u << (pos + step)) - 1u)) < n) pos += step;
-    return w & ((2u << pos) - 1u);
 }
 // A device's two pairs, a lane per quad (a: first pair, b: second), brought into the stored form by the 8 lanes
 // of its slot together: an empty pair has an empty mask, pairs with equal masks are one pair, the pair that
