@@ -162,6 +162,8 @@ struct Ctx {
     DevBuf blob, valid, rerun, sorted, progs, costs, counters, topk_scratch, topk_pos, topk_in, topk_jobs, lit_scratch, post;
     DevBuf sel_progs, sel_costs, gather;                    // the rows that shortlists picked, and whose they are
     HostBuf h_gather;
+    DevBuf f_finish;                                        // frontier engine: what every query's rows are written from
+    HostBuf h_finish;
     DevBuf f_rank, f_share;                                 // frontier engine: ranks of the valid programs, queries of the enumerations
     std::vector<DevBuf> f_evalid, f_egsums;                 // ... per enumeration: valid candidate indices, their cost sums
     FrontSlot slots[kFrontSlots];
@@ -192,14 +194,14 @@ const std::thread::id g_loader_thread = std::this_thread::get_id();
 
 void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
-                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share, &sel_progs, &sel_costs, &gather};
+                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share, &sel_progs, &sel_costs, &gather, &f_finish};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
     for (auto* v : {&f_evalid, &f_egsums}) {
         for (DevBuf& b : *v) if (b.p) (void)hipFree(b.p);
         v->clear();
     }
     for (FrontSlot& sl : slots) sl.release();
-    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare, &h_gather};
+    HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare, &h_gather, &h_finish};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
     if (front_go) { (void)hipEventDestroy(front_go); front_go = nullptr; }
     if (copy_done) { (void)hipEventDestroy(copy_done); copy_done = nullptr; }
@@ -913,7 +915,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             // ---- one state of every group of equal states is judged against the alphabet, into a row of codes
             for (int li = 0; li < 2; ++li) {
                 if (n_s[li] == 0) continue;
-                P2_HIP(S.f_codes[li].ensure((size_t)n_s[li] * pl.alphabet));
+                P2_HIP(S.f_codes[li].ensure((size_t)n_s[li] * front_code_stride(pl.alphabet)));
                 P2_HIP(S.f_unk[li].ensure(n_s[li]));
             }
             // The literal prefixes of the level are judged on a second S.stream while the pair states are (their kernels are
@@ -1049,8 +1051,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(S.f_states2[nxt].ensure(std::max<size_t>(t2, 1) * sw * 8));
             P2_HIP(S.f_hash[nxt].ensure(std::max<size_t>(t1, 1) * sizeof(unsigned long long)));
             P2_HIP(S.f_hash2[nxt].ensure(std::max<size_t>(t2, 1) * sizeof(unsigned long long)));
-            P2_HIP(hipMemsetAsync(S.f_hash[nxt].p, 0, std::max<size_t>(t1, 1) * sizeof(unsigned long long), S.stream));
-            P2_HIP(hipMemsetAsync(S.f_hash2[nxt].p, 0, std::max<size_t>(t2, 1) * sizeof(unsigned long long), S.stream));
+            if (t1 > 0) P2_HIP(hipMemsetAsync(S.f_hash[nxt].p, 0, (size_t)t1 * sizeof(unsigned long long), S.stream));
+            if (t2 > 0) P2_HIP(hipMemsetAsync(S.f_hash2[nxt].p, 0, (size_t)t2 * sizeof(unsigned long long), S.stream));
             P2_HIP(S.f_delta[0].ensure(std::max<size_t>((size_t)t1 * sum_doubles, 1) * 8));
             P2_HIP(S.f_delta[1].ensure(std::max<size_t>((size_t)t2 * sum_doubles, 1) * 8));
             P2_HIP(S.f_delta[2].ensure(std::max<size_t>((size_t)tg * sum_doubles, 1) * 8));
@@ -1090,10 +1092,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             const DevBuf* next_states[2] = {&S.f_states[nxt], &S.f_states2[nxt]};
             const DevBuf* next_hash[2] = {&S.f_hash[nxt], &S.f_hash2[nxt]};
             bool grouped_next[2] = {false, false};
-            P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, S.stream));
+            for (int li = 0; li < 2; ++li) grouped_next[li] = n_next[li] >= kGroupMin && n_next[li] < (1u << 24);
+            if (grouped_next[0] || grouped_next[1]) P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, S.stream));
             for (int li = 0; li < 2; ++li) {
                 const uint32_t n = n_next[li];
-                grouped_next[li] = n >= kGroupMin && n < (1u << 24);
                 if (!grouped_next[li]) continue;
                 size_t table = 1024;
                 while (table < (size_t)n * 2) table *= 2;
@@ -1323,6 +1325,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         size_t ranked = 0;
         for (auto& E : enums) { E.off_valid = ranked; ranked += E.n_valid; }
         P2_HIP(C.f_rank.ensure(sizeof(uint32_t) * std::max<size_t>(ranked, 1)));
+        std::vector<FrontFinish> jobs;
+        uint32_t max_valid = 0;
         for (auto& E : enums) {
             if (E.n_valid == 0) continue;
             const unsigned long long* list = static_cast<const unsigned long long*>(C.f_evalid[E.id].p);
@@ -1342,9 +1346,18 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 F.goal_sums = static_cast<const double*>(C.f_egsums[E.id].p);
                 F.out_first = runs[E.members[m]].out_first;
                 F.sorted = sorted_base; F.progs = progs_base; F.costs = costs_base;
-                ++post_launches;
-                P2_HIP(launch_front_finish(reinterpret_cast<const DevQuery*>(db), F, stream));
+                jobs.push_back(F);
+                max_valid = std::max(max_valid, E.n_valid);
             }
+        }
+        if (!jobs.empty()) {                        // the rows of all of them in one launch
+            P2_HIP(C.f_finish.ensure(sizeof(FrontFinish) * jobs.size()));
+            P2_HIP(C.h_finish.ensure(sizeof(FrontFinish) * jobs.size()));
+            std::memcpy(C.h_finish.p, jobs.data(), sizeof(FrontFinish) * jobs.size());
+            P2_HIP(hipMemcpyAsync(C.f_finish.p, C.h_finish.p, sizeof(FrontFinish) * jobs.size(), hipMemcpyHostToDevice, stream));
+            ++post_launches;
+            P2_HIP(launch_front_finish(reinterpret_cast<const DevQuery*>(db), static_cast<const FrontFinish*>(C.f_finish.p),
+                                       (uint32_t)jobs.size(), max_valid, stream));
         }
     }
     for (auto& L : lcost_launches) {

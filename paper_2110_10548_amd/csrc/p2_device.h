@@ -311,6 +311,9 @@ struct FrontFinish {
     unsigned long long out_first;  // first row of the query in the batch-wide buffers
     unsigned long long* sorted; p2_program* progs; double* costs;
 };
+// Bytes from one state's row of codes to the next: the alphabet rounded up to whole words, so that the kernels that
+// list survivors and children read four codes at a time (the bytes past the alphabet are never looked at).
+__host__ __device__ inline uint32_t front_code_stride(int alphabet) { return ((uint32_t)alphabet + 3u) & ~3u; }
 size_t frontier_state_words(int R, int k);
 // 2 where two planes of the state fit in LDS, else 1.
 int frontier_max_pairs(int R, int k);
@@ -365,7 +368,8 @@ hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry
                              unsigned long long* valid_out, double* goal_sums, int n_share, FrontCounters* ctr,
                              hipStream_t stream);
 hipError_t launch_front_rank(const unsigned long long* valid, uint32_t n, uint32_t* rank, hipStream_t stream);
-hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish& F, hipStream_t stream);
+// The rows of n_jobs queries in one launch (jobs in device memory; max_valid = the largest n_valid among them).
+hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish* jobs, uint32_t n_jobs, uint32_t max_valid, hipStream_t stream);
 
 // One selection of launch_topk_jobs: the k best of (cost[i * stride], index[i]), i < n, ties by index;
 // positions go to out_pos[min(k, n)], nan_flag is set to 1 when a cost is NaN.  All device pointers.

@@ -629,37 +629,65 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
 }
 
 // ---- survivors of every entry from the codes of its state ------------------------------------------------
-// A wavefront takes kExpBatch entries at a time: counts their survivors by kind, reserves list positions and the
-// children's places in the next frontier once (so that the few counters are not hammered), writes.
-constexpr int kExpThreads = 256, kExpBatch = 8;
+// A wavefront takes kExpBatch entries at a time and counts their survivors by kind; the block's wavefronts then
+// reserve list positions and the children's places in the next frontier together (two additions to the level's
+// counters per block and round: returning additions to one address are served one after the other, some 10^8 a
+// second, so a reservation per wavefront was what this kernel spent its time on); then they write.
+constexpr int kExpThreads = 1024, kExpWaves = kExpThreads / 64, kExpBatch = 8;
 template <int NP>
 __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __restrict__ qp, const FrontEntry* __restrict__ entries,
                                                              uint32_t n, const uint32_t* __restrict__ rep,
                                                              const uint8_t* __restrict__ codes, const uint8_t* __restrict__ unknown,
                                                              int handover, FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
                                                              FrontEntry* __restrict__ unknown_out, FrontCounters* __restrict__ ctr) {
+    __shared__ uint32_t s_tot[kExpWaves][4];             // per wavefront: survivors, goals, one-pair children, two-pair children
+    __shared__ uint32_t s_at[kExpWaves][4];              // ... where each kind starts for the wavefront
     const DevQuery& q = *qp;
     const int I = q.alphabet;
-    const int lane = threadIdx.x & 63;
-    const uint32_t wave = (blockIdx.x * kExpThreads + threadIdx.x) >> 6, n_waves = gridDim.x * (kExpThreads / 64);
+    const uint32_t CS = front_code_stride(I);
+    const int CW = (int)(CS / 4u);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t in_alphabet[2];                             // the bytes of a lane's two words that are instructions (invalid = 0 elsewhere)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int left = I - (lane + 64 * h) * 4;
+        in_alphabet[h] = left >= 4 ? 0xffffffffu : left > 0 ? ((1u << (8 * left)) - 1u) : 0u;
+    }
     unsigned long long judged = 0;                       // entries with survivors written here (lane 0 counts)
-    for (uint32_t p0 = wave * kExpBatch; p0 < n; p0 += n_waves * kExpBatch) {
-        const int pending = (int)min((uint32_t)kExpBatch, n - p0);
+    for (uint32_t base = blockIdx.x * (uint32_t)(kExpWaves * kExpBatch); base < n; base += gridDim.x * (uint32_t)(kExpWaves * kExpBatch)) {
+        const uint32_t p0 = base + (uint32_t)(wv * kExpBatch);
+        const int pending = p0 < n ? (int)min((uint32_t)kExpBatch, n - p0) : 0;
         uint32_t row_of[kExpBatch];
         bool unk[kExpBatch];
 #pragma unroll
         for (int b = 0; b < kExpBatch; ++b) {
-            const uint32_t p = p0 + (uint32_t)min(b, pending - 1);
-            row_of[b] = rep ? rep[p] : p;
-            unk[b] = handover != 0 || unknown[row_of[b]] != 0;
+            row_of[b] = 0; unk[b] = false;
+            if (b < pending) {
+                const uint32_t p = p0 + (uint32_t)b;
+                row_of[b] = rep ? rep[p] : p;
+                unk[b] = handover != 0 || unknown[row_of[b]] != 0;
+            }
+        }
+        // the rows of the batch: four codes a word, a lane's two words of every row loaded before any is looked at
+        // (an alphabet has at most 512 instructions: 128 words), and kept for the second pass
+        uint32_t four[kExpBatch][2];
+#pragma unroll
+        for (int b = 0; b < kExpBatch; ++b) {
+            const uint32_t* const row = reinterpret_cast<const uint32_t*>(codes + (size_t)row_of[b] * CS);
+            const bool on = b < pending && !unk[b];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) four[b][h] = (on && lane + 64 * h < CW) ? (row[lane + 64 * h] & in_alphabet[h]) : 0u;
         }
         uint32_t c_surv = 0, c_goal = 0, c_p1 = 0, c_p2 = 0;
 #pragma unroll
         for (int b = 0; b < kExpBatch; ++b) {
-            if (b >= pending || unk[b]) continue;
-            for (int a = lane; a < I; a += 64) {
-                const int code = codes[(size_t)row_of[b] * I + a];
-                c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
+                    c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
+                }
             }
         }
         uint32_t x_surv = c_surv, x_goal = c_goal, x_p1 = c_p1, x_p2 = c_p2;          // inclusive sums over the lanes
@@ -667,11 +695,33 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
             const uint32_t a0 = __shfl_up(x_surv, o, 64), a1 = __shfl_up(x_goal, o, 64), a2 = __shfl_up(x_p1, o, 64), a3 = __shfl_up(x_p2, o, 64);
             if (lane >= o) { x_surv += a0; x_goal += a1; x_p1 += a2; x_p2 += a3; }
         }
-        const uint32_t t_surv = __shfl(x_surv, 63, 64), t_goal = __shfl(x_goal, 63, 64), t_p1 = __shfl(x_p1, 63, 64), t_p2 = __shfl(x_p2, 63, 64);
-        unsigned long long b0 = 0, b1 = 0;
+        if (lane == 63) { s_tot[wv][0] = x_surv; s_tot[wv][1] = x_goal; s_tot[wv][2] = x_p1; s_tot[wv][3] = x_p2; }
+        __syncthreads();
+        if (wv == 0) {
+            // lane w < kExpWaves: the totals of wavefront w; sums over the wavefronts before it; one lane reserves
+            uint32_t t[4], x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { t[j] = lane < kExpWaves ? s_tot[lane][j] : 0u; x[j] = t[j]; }
+            for (int o = 1; o < kExpWaves; o <<= 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { const uint32_t up = __shfl_up(x[j], o, 64); if (lane >= o) x[j] += up; }
+            }
+            uint32_t all[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) all[j] = __shfl(x[j], kExpWaves - 1, 64);
+            unsigned long long b0 = 0, b1 = 0;
+            if (lane == 0) {
+                if (all[0]) b0 = atomicAdd(&ctr->surv_goal, (unsigned long long)all[0] | ((unsigned long long)all[1] << 32));
+                if (all[2] | all[3]) b1 = atomicAdd(&ctr->pref_pref2, (unsigned long long)all[2] | ((unsigned long long)all[3] << 32));
+            }
+            b0 = __shfl(b0, 0, 64); b1 = __shfl(b1, 0, 64);
+            if (lane < kExpWaves) {
+                s_at[lane][0] = (uint32_t)b0 + x[0] - t[0]; s_at[lane][1] = (uint32_t)(b0 >> 32) + x[1] - t[1];
+                s_at[lane][2] = (uint32_t)b1 + x[2] - t[2]; s_at[lane][3] = (uint32_t)(b1 >> 32) + x[3] - t[3];
+            }
+        }
+        __syncthreads();
         if (lane == 0) {
-            if (t_surv) b0 = atomicAdd(&ctr->surv_goal, (unsigned long long)t_surv | ((unsigned long long)t_goal << 32));
-            if (t_p1 | t_p2) b1 = atomicAdd(&ctr->pref_pref2, (unsigned long long)t_p1 | ((unsigned long long)t_p2 << 32));
 #pragma unroll
             for (int b = 0; b < kExpBatch; ++b) {
                 if (b >= pending) continue;
@@ -679,21 +729,25 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
                 else ++judged;
             }
         }
-        b0 = __shfl(b0, 0, 64); b1 = __shfl(b1, 0, 64);
-        uint32_t at_surv = (uint32_t)b0 + x_surv - c_surv, at_goal = (uint32_t)(b0 >> 32) + x_goal - c_goal;
-        uint32_t at_p1 = (uint32_t)b1 + x_p1 - c_p1, at_p2 = (uint32_t)(b1 >> 32) + x_p2 - c_p2;
+        uint32_t at_surv = s_at[wv][0] + x_surv - c_surv, at_goal = s_at[wv][1] + x_goal - c_goal;
+        uint32_t at_p1 = s_at[wv][2] + x_p1 - c_p1, at_p2 = s_at[wv][3] + x_p2 - c_p2;
 #pragma unroll
         for (int b = 0; b < kExpBatch; ++b) {
-            if (b >= pending || unk[b]) continue;
-            for (int a = lane; a < I; a += 64) {
-                const int code = codes[(size_t)row_of[b] * I + a];
-                if (code == CODE_INVALID) continue;
-                FrontSurvivor sv;
-                sv.entry = p0 + b; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
-                sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
-                if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
-                if (at_surv < surv_cap) surv[at_surv] = sv;
-                ++at_surv;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (four[b][h] == 0u) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int a = (lane + 64 * h) * 4 + j;
+                    const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
+                    if (code == CODE_INVALID) continue;
+                    FrontSurvivor sv;
+                    sv.entry = p0 + b; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
+                    sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
+                    if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
+                    if (at_surv < surv_cap) surv[at_surv] = sv;
+                    ++at_surv;
+                }
             }
         }
     }
@@ -820,7 +874,7 @@ __global__ __launch_bounds__(256) void k_front_goal_filter(const DevQuery* __res
             if (__any(rows_short) && __any(cols_short) && __any(root_short)) break;
         }
         if (__any(rows_short) && __any(cols_short) && __any(root_short)) {
-            for (int a = lane; a < I; a += 64) codes[(size_t)e * I + a] = (uint8_t)CODE_INVALID;
+            for (int a = lane; a < I; a += 64) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
             if (lane == 0) unknown[e] = 0;
         } else if (lane == 0) {
             walk[atomicAdd(n_walk, 1u)] = e;
@@ -920,7 +974,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
         if (goals_only) {
             goal_ops = (s_rows_short == 0 ? 1 : 0) | (s_cols_short == 0 ? 2 : 0) | ((flags[0] & kFlagGoal) ? 4 : 0);
             if (goal_ops == 0) {
-                for (int a = tid; a < I; a += kClsThreads) codes[(size_t)e * I + a] = (uint8_t)CODE_INVALID;
+                for (int a = tid; a < I; a += kClsThreads) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
                 continue;
             }
         }
@@ -966,7 +1020,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
                 rs_straddles = cls_rs_straddles<KW, MW, NP>(c, P);
             if (lane == 0)
                 cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, rs_straddles, ops_r, n_ops, max_pairs,
-                                      all_rows, all_cols, goal_ops, codes + (size_t)e * I, unknown + e);
+                                      all_rows, all_cols, goal_ops, codes + (size_t)e * front_code_stride(I), unknown + e);
         }
     }
     if (tid == 0 && walked) atomicAdd(&ctr->n_walked_planes, walked * (uint32_t)NP);
@@ -1254,23 +1308,48 @@ __global__ __launch_bounds__(256) void k_front_children(const DevQuery* __restri
                                                         int keep, int write, uint32_t* __restrict__ child_of,
                                                         FrontSurvivor* __restrict__ ssurv, FrontCounters* __restrict__ ctr) {
     const uint32_t I = (uint32_t)qp->alphabet;
+    const uint32_t CS = front_code_stride((int)I);
     const uint32_t n_work = list ? *n_list : n_states;
     // A wavefront takes kChildChunk states at a time, a lane per instruction: it counts the chunk's children by kind,
     // reserves their places once (the counters are few, and every reservation of the same word waits for the one
     // before it), and hands them out in a second pass over the chunk.
     const int lane = threadIdx.x & 63;
+    uint32_t in_alphabet[2];                             // the bytes of a lane's two words that are instructions (invalid = 0 elsewhere)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int left = (int)I - (lane + 64 * h) * 4;
+        in_alphabet[h] = left >= 4 ? 0xffffffffu : left > 0 ? ((1u << (8 * left)) - 1u) : 0u;
+    }
     const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = gridDim.x * 4u;
     for (uint32_t c0 = wave * kChildChunk; c0 < n_work; c0 += n_waves * kChildChunk) {
         const uint32_t c1 = min(c0 + (uint32_t)kChildChunk, n_work);
+        // the rows of the chunk: four codes a word, a lane's two words of every row loaded before any is looked at
+        // (an alphabet has at most 512 instructions: 128 words)
+        uint32_t st_of[kChildChunk], four[kChildChunk][2];
+#pragma unroll
+        for (int b = 0; b < kChildChunk; ++b) {
+            const uint32_t i = c0 + (uint32_t)b;
+            st_of[b] = i < c1 ? (list ? list[i] : i) : 0u;
+        }
+#pragma unroll
+        for (int b = 0; b < kChildChunk; ++b) {
+            const bool on = c0 + (uint32_t)b < c1 && !unknown[st_of[b]];       // (an unknown state's prefixes go to the literal kernels)
+            const uint32_t* const row = reinterpret_cast<const uint32_t*>(codes + (size_t)st_of[b] * CS);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) four[b][h] = (on && (uint32_t)(lane + 64 * h) < CS / 4u) ? (row[lane + 64 * h] & in_alphabet[h]) : 0u;
+        }
         uint32_t mine[3] = {0u, 0u, 0u};
-        for (uint32_t i = c0; i < c1; ++i) {
-            const uint32_t st = list ? list[i] : i;
-            if (unknown[st]) continue;               // (its prefixes go to the literal kernels)
-            for (uint32_t a = (uint32_t)lane; a < I; a += 64u) {
-                const int code = codes[(size_t)st * I + a];
-                mine[0] += (code == CODE_PREFIX && keep) ? 1u : 0u;
-                mine[1] += (code == CODE_PREFIX2 && keep) ? 1u : 0u;
-                mine[2] += code == CODE_GOAL ? 1u : 0u;
+#pragma unroll
+        for (int b = 0; b < kChildChunk; ++b) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j) {
+                    const int code = (int)((four[b][h] >> (8u * j)) & 0xffu);
+                    mine[0] += (code == CODE_PREFIX && keep) ? 1u : 0u;
+                    mine[1] += (code == CODE_PREFIX2 && keep) ? 1u : 0u;
+                    mine[2] += code == CODE_GOAL ? 1u : 0u;
+                }
             }
         }
         uint32_t before[3], total[3];                // over the lanes: exclusive sums, totals
@@ -1292,18 +1371,24 @@ __global__ __launch_bounds__(256) void k_front_children(const DevQuery* __restri
         if (all == 0) continue;
         uint32_t at_list = __builtin_amdgcn_readfirstlane(atomicAdd(&ctr->n_ssurv, lane == 0 ? all : 0u)) + before[0] + before[1] + before[2];
         uint32_t next[3] = {base[0] + before[0], base[1] + before[1], base[2] + before[2]};
-        for (uint32_t i = c0; i < c1; ++i) {
-            const uint32_t st = list ? list[i] : i;
-            if (unknown[st]) continue;
-            for (uint32_t a = (uint32_t)lane; a < I; a += 64u) {
-                const int code = codes[(size_t)st * I + a];
-                const int kind = (code == CODE_PREFIX && keep) ? 0 : (code == CODE_PREFIX2 && keep) ? 1 : code == CODE_GOAL ? 2 : -1;
-                if (kind < 0) continue;
-                const uint32_t t = kind == 0 ? next[0]++ : kind == 1 ? next[1]++ : next[2]++;
-                child_of[(size_t)st * I + a] = t;
-                FrontSurvivor sv;
-                sv.entry = st; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (np == 2 ? kFromTwoPair : 0)); sv.slot = t;
-                ssurv[at_list++] = sv;
+#pragma unroll
+        for (int b = 0; b < kChildChunk; ++b) {
+            const uint32_t st = st_of[b];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (four[b][h] == 0u) continue;
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j) {
+                    const uint32_t a = (uint32_t)(lane + 64 * h) * 4u + j;
+                    const int code = (int)((four[b][h] >> (8u * j)) & 0xffu);
+                    const int kind = (code == CODE_PREFIX && keep) ? 0 : (code == CODE_PREFIX2 && keep) ? 1 : code == CODE_GOAL ? 2 : -1;
+                    if (kind < 0) continue;
+                    const uint32_t t = kind == 0 ? next[0]++ : kind == 1 ? next[1]++ : next[2]++;
+                    child_of[(size_t)st * I + a] = t;
+                    FrontSurvivor sv;
+                    sv.entry = st; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (np == 2 ? kFromTwoPair : 0)); sv.slot = t;
+                    ssurv[at_list++] = sv;
+                }
             }
         }
     }
@@ -1413,10 +1498,10 @@ __global__ __launch_bounds__(64) void k_front_init(const DevQuery* __restrict__ 
 // Programs and costs of an enumeration's valid programs for one of its queries: entry i of the unordered
 // list, whose place in ascending index order is rank[i], becomes row out_first + rank[i] (row out_first + i where
 // no order is asked for: rank null).
-__global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict__ queries, FrontFinish F) {
-    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= F.n_valid) return;
+__global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict__ queries, const FrontFinish* __restrict__ jobs) {
+    const FrontFinish F = jobs[blockIdx.y];              // (a query per grid row)
     const DevQuery& q = queries[F.query];
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < F.n_valid; i += gridDim.x * 256u) {
     const unsigned long long idx = F.valid[i];
     const size_t row = F.out_first + (F.rank ? F.rank[i] : i);
     int len = 1;
@@ -1437,6 +1522,7 @@ __global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict
     F.progs[row] = pr;
     const double sa = F.goal_sums[((size_t)i * F.n_share + F.share_pos) * 2], sb = F.goal_sums[((size_t)i * F.n_share + F.share_pos) * 2 + 1];
     for (int m = 0; m < q.n_msg; ++m) F.costs[row * q.n_msg + m] = sa + q.msg_bytes[m] * sb;
+    }
 }
 
 // rank[i] = number of entries of the list smaller than entry i (distinct keys).
@@ -1617,8 +1703,8 @@ hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uin
                                const uint8_t* codes, const uint8_t* unknown, int np, int handover, FrontSurvivor* surv,
                                uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const unsigned waves = (n + kExpBatch - 1) / kExpBatch, want = (waves + 3u) / 4u;
-    const unsigned blocks = want < 4096u ? want : 4096u;
+    const unsigned per_block = kExpWaves * kExpBatch, want = (n + per_block - 1) / per_block;
+    const unsigned blocks = want < 2048u ? want : 2048u;
     if (np == 2)
         hipLaunchKernelGGL(k_front_expand<2>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, unknown, handover, surv,
                            surv_cap, unknown_out, ctr);
@@ -1651,9 +1737,13 @@ hipError_t launch_front_rank(const unsigned long long* valid, uint32_t n, uint32
     return hipGetLastError();
 }
 
-hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish& F, hipStream_t stream) {
-    if (F.n_valid == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_front_finish, dim3((F.n_valid + 255u) / 256u), dim3(256), 0, stream, queries, F);
+hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish* jobs, uint32_t n_jobs, uint32_t max_valid, hipStream_t stream) {
+    if (n_jobs == 0 || max_valid == 0) return hipSuccess;
+    const uint32_t want = (max_valid + 255u) / 256u;
+    for (uint32_t j0 = 0; j0 < n_jobs; j0 += 65535u) {
+        const uint32_t nj = n_jobs - j0 < 65535u ? n_jobs - j0 : 65535u;
+        hipLaunchKernelGGL(k_front_finish, dim3(want < 1024u ? want : 1024u, nj), dim3(256), 0, stream, queries, jobs + j0);
+    }
     return hipGetLastError();
 }
 
