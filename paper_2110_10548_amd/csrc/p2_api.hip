@@ -122,6 +122,7 @@ struct FrontSlot {
     DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, lit_scratch;
     DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
     DevBuf f_sid[2], f_sid2[2], f_delta[3], f_childof[2], f_ssurv;                           // prefixes -> states -> children
+    DevBuf f_rowcnt[2];                                                                      // per row of codes: how many survivors by kind
     DevBuf f_walk[2];                                                                        // the last level: states worth a walk
     HostBuf h_fctr;
     SpanRec spans;
@@ -142,7 +143,7 @@ struct FrontSlot {
                          &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1], &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal,
                          &f_unknown, &f_ctr, &lit_scratch, &f_hash[0], &f_hash[1], &f_hash2[0], &f_hash2[1], &f_table, &f_rep[0], &f_rep[1],
                          &f_replist[0], &f_replist[1], &f_codes[0], &f_codes[1], &f_unk[0], &f_unk[1], &f_sid[0], &f_sid[1], &f_sid2[0],
-                         &f_sid2[1], &f_delta[0], &f_delta[1], &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv, &f_walk[0], &f_walk[1]};
+                         &f_sid2[1], &f_delta[0], &f_delta[1], &f_delta[2], &f_childof[0], &f_childof[1], &f_ssurv, &f_walk[0], &f_walk[1], &f_rowcnt[0], &f_rowcnt[1]};
         for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
         if (h_fctr.p) (void)hipHostFree(h_fctr.p);
         h_fctr.p = nullptr; h_fctr.cap = 0;
@@ -917,6 +918,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 if (n_s[li] == 0) continue;
                 P2_HIP(S.f_codes[li].ensure((size_t)n_s[li] * front_code_stride(pl.alphabet)));
                 P2_HIP(S.f_unk[li].ensure(n_s[li]));
+                P2_HIP(S.f_rowcnt[li].ensure((size_t)n_s[li] * sizeof(unsigned long long)));
             }
             // The literal prefixes of the level are judged on a second S.stream while the pair states are (their kernels are
             // a wavefront per prefix and leave most of the chip idle); the two meet before the counters go to the host.
@@ -950,7 +952,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     if (n_s[li] == 0) continue;
                     P2_HIP(S.f_walk[li].ensure((size_t)n_s[li] * sizeof(uint32_t)));
                     P2_HIP(launch_front_goal_filter(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li], cls_list[li],
-                                                    cls_n[li], li + 1, static_cast<uint8_t*>(S.f_codes[li].p),
+                                                    cls_n[li], li + 1, static_cast<uint8_t*>(S.f_codes[li].p), static_cast<unsigned long long*>(S.f_rowcnt[li].p),
                                                     static_cast<uint8_t*>(S.f_unk[li].p), static_cast<uint32_t*>(S.f_walk[li].p),
                                                     &dctr->n_walk[li], S.stream));
                     cls_list[li] = static_cast<const uint32_t*>(S.f_walk[li].p);
@@ -962,7 +964,8 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             for (int li = 0; li < 2; ++li)
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li], cls_list[li],
                                              cls_n[li], li + 1, max_pairs, keep ? 0 : 1,
-                                             static_cast<uint8_t*>(S.f_codes[li].p), static_cast<uint8_t*>(S.f_unk[li].p), dctr, S.stream));
+                                             static_cast<uint8_t*>(S.f_codes[li].p), static_cast<unsigned long long*>(S.f_rowcnt[li].p),
+                                             static_cast<uint8_t*>(S.f_unk[li].p), dctr, S.stream));
             if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.end(S.stream));
             uint32_t walked_planes = 0;
             for (int attempt = 0;; ++attempt) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
@@ -975,11 +978,13 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 if (n_c + n_c2 > 0) P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
                 P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(S.f_entries[cur].p), n_c,
                                            static_cast<const uint32_t*>(S.f_sid[cur].p),
-                                           static_cast<const uint8_t*>(S.f_codes[0].p), static_cast<const uint8_t*>(S.f_unk[0].p), 1, 0,
+                                           static_cast<const uint8_t*>(S.f_codes[0].p), static_cast<const unsigned long long*>(S.f_rowcnt[0].p),
+                                           static_cast<const uint8_t*>(S.f_unk[0].p), 1, 0,
                                            static_cast<FrontSurvivor*>(S.f_surv.p), (uint32_t)cap_c, nullptr, dctr, S.stream));
                 P2_HIP(launch_front_expand(dq, static_cast<const FrontEntry*>(S.f_entries2[cur].p), n_c2,
                                            static_cast<const uint32_t*>(S.f_sid2[cur].p),
-                                           static_cast<const uint8_t*>(S.f_codes[1].p), static_cast<const uint8_t*>(S.f_unk[1].p), 2, handover,
+                                           static_cast<const uint8_t*>(S.f_codes[1].p), static_cast<const unsigned long long*>(S.f_rowcnt[1].p),
+                                           static_cast<const uint8_t*>(S.f_unk[1].p), 2, handover,
                                            static_cast<FrontSurvivor*>(S.f_surv.p), (uint32_t)cap_c,
                                            static_cast<FrontEntry*>(S.f_unknown.p), dctr, S.stream));
                 // (how many children the judged states have, by kind)

@@ -333,20 +333,22 @@ hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const 
 // cannot judge the entry.  np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends
 // children that need two pairs to the literal list.
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes, uint8_t* unknown,
-                                 FrontCounters* ctr, hipStream_t stream);
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes,
+                                 unsigned long long* row_counts, uint8_t* unknown, FrontCounters* ctr, hipStream_t stream);
 // The last level, before the classification (which then runs with goals_only on the list this leaves): the entries
 // from which no instruction can end at the goal get a row of invalid codes; the others are listed in
 // walk[0 .. *n_walk) (*n_walk zero on entry; any order).
 hipError_t launch_front_goal_filter(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                    const uint32_t* n_list, int np, uint8_t* codes, uint8_t* unknown, uint32_t* walk, uint32_t* n_walk,
-                                    hipStream_t stream);
+                                    const uint32_t* n_list, int np, uint8_t* codes, unsigned long long* row_counts, uint8_t* unknown,
+                                    uint32_t* walk, uint32_t* n_walk, hipStream_t stream);
 // The survivors of every entry of a list from the codes of the entry that stands for its state (rep null: its own):
 // appended to surv with their places in the next frontier; entries that cannot be judged go to unknown_out
 // (counted in n_unknown); handover != 0 treats every entry so (the hand-over path, for tests).
+// row_counts: what the classification (or the last level's filter) left beside each row of codes: the numbers of
+// survivors, goals, one-pair and two-pair children among its codes, 16 bits each.
 hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uint32_t n, const uint32_t* rep,
-                               const uint8_t* codes, const uint8_t* unknown, int np, int handover, FrontSurvivor* surv,
-                               uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream);
+                               const uint8_t* codes, const unsigned long long* row_counts, const uint8_t* unknown, int np, int handover,
+                               FrontSurvivor* surv, uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream);
 // Bytes of the scratch buffer launch_front_classify_literal needs for n literal prefixes (always passed).
 size_t front_literal_scratch_bytes(int R, int k, uint32_t n);
 // class_cap: most classes of equal rows the class-state kernel may hold (1..64) before a prefix goes to the

@@ -629,16 +629,20 @@ __device__ inline void cls_codes(const ClsLane<KW, MW, NP>& c, const PatLds P, i
 }
 
 // ---- survivors of every entry from the codes of its state ------------------------------------------------
-// A wavefront takes kExpBatch entries at a time and counts their survivors by kind; the block's wavefronts then
-// reserve list positions and the children's places in the next frontier together (two additions to the level's
-// counters per block and round: returning additions to one address are served one after the other, some 10^8 a
-// second, so a reservation per wavefront was what this kernel spent its time on); then they write.
+// The classification leaves, beside a state's row of codes, how many of them are survivors, goals, one-pair and
+// two-pair children (row_counts: 16 bits each).  A lane per entry (the first `epw` lanes of a wavefront: 8 to 64,
+// fewer where the list is short, so that its second pass is spread over more wavefronts) adds those up; the block's wavefronts reserve
+// list positions and the children's places in the next frontier together (two additions to the level's counters per
+// block and round: returning additions to one address are served one after the other); then the wavefront goes
+// through its entries that have survivors, eight at a time, their rows loaded before any is looked at (four codes
+// a word; an alphabet has at most 512 instructions: 128 words, two per lane), and writes.
 constexpr int kExpThreads = 1024, kExpWaves = kExpThreads / 64, kExpBatch = 8;
 template <int NP>
 __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __restrict__ qp, const FrontEntry* __restrict__ entries,
                                                              uint32_t n, const uint32_t* __restrict__ rep,
-                                                             const uint8_t* __restrict__ codes, const uint8_t* __restrict__ unknown,
-                                                             int handover, FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
+                                                             const uint8_t* __restrict__ codes, const uint2* __restrict__ row_counts,
+                                                             const uint8_t* __restrict__ unknown,
+                                                             int handover, int epw, FrontSurvivor* __restrict__ surv, uint32_t surv_cap,
                                                              FrontEntry* __restrict__ unknown_out, FrontCounters* __restrict__ ctr) {
     __shared__ uint32_t s_tot[kExpWaves][4];             // per wavefront: survivors, goals, one-pair children, two-pair children
     __shared__ uint32_t s_at[kExpWaves][4];              // ... where each kind starts for the wavefront
@@ -653,43 +657,15 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
         const int left = I - (lane + 64 * h) * 4;
         in_alphabet[h] = left >= 4 ? 0xffffffffu : left > 0 ? ((1u << (8 * left)) - 1u) : 0u;
     }
-    unsigned long long judged = 0;                       // entries with survivors written here (lane 0 counts)
-    for (uint32_t base = blockIdx.x * (uint32_t)(kExpWaves * kExpBatch); base < n; base += gridDim.x * (uint32_t)(kExpWaves * kExpBatch)) {
-        const uint32_t p0 = base + (uint32_t)(wv * kExpBatch);
-        const int pending = p0 < n ? (int)min((uint32_t)kExpBatch, n - p0) : 0;
-        uint32_t row_of[kExpBatch];
-        bool unk[kExpBatch];
-#pragma unroll
-        for (int b = 0; b < kExpBatch; ++b) {
-            row_of[b] = 0; unk[b] = false;
-            if (b < pending) {
-                const uint32_t p = p0 + (uint32_t)b;
-                row_of[b] = rep ? rep[p] : p;
-                unk[b] = handover != 0 || unknown[row_of[b]] != 0;
-            }
-        }
-        // the rows of the batch: four codes a word, a lane's two words of every row loaded before any is looked at
-        // (an alphabet has at most 512 instructions: 128 words), and kept for the second pass
-        uint32_t four[kExpBatch][2];
-#pragma unroll
-        for (int b = 0; b < kExpBatch; ++b) {
-            const uint32_t* const row = reinterpret_cast<const uint32_t*>(codes + (size_t)row_of[b] * CS);
-            const bool on = b < pending && !unk[b];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) four[b][h] = (on && lane + 64 * h < CW) ? (row[lane + 64 * h] & in_alphabet[h]) : 0u;
-        }
-        uint32_t c_surv = 0, c_goal = 0, c_p1 = 0, c_p2 = 0;
-#pragma unroll
-        for (int b = 0; b < kExpBatch; ++b) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
-                    c_surv += code != CODE_INVALID; c_goal += code == CODE_GOAL; c_p1 += code == CODE_PREFIX; c_p2 += code == CODE_PREFIX2;
-                }
-            }
-        }
+    unsigned long long judged = 0;                       // entries judged from their states' codes (lane 0 counts)
+    const uint32_t per_block = (uint32_t)(kExpWaves * epw);
+    for (uint32_t base = blockIdx.x * per_block; base < n; base += gridDim.x * per_block) {
+        const uint32_t p = base + (uint32_t)(wv * epw + lane);
+        const bool valid = lane < epw && p < n;
+        const uint32_t row = valid ? (rep ? rep[p] : p) : 0u;
+        const bool unk = valid && (handover != 0 || unknown[row] != 0);
+        const uint2 cnt = (valid && !unk) ? row_counts[row] : make_uint2(0u, 0u);
+        const uint32_t c_surv = cnt.x & 0xffffu, c_goal = cnt.x >> 16, c_p1 = cnt.y & 0xffffu, c_p2 = cnt.y >> 16;
         uint32_t x_surv = c_surv, x_goal = c_goal, x_p1 = c_p1, x_p2 = c_p2;          // inclusive sums over the lanes
         for (int o = 1; o < 64; o <<= 1) {
             const uint32_t a0 = __shfl_up(x_surv, o, 64), a1 = __shfl_up(x_goal, o, 64), a2 = __shfl_up(x_p1, o, 64), a3 = __shfl_up(x_p2, o, 64);
@@ -721,32 +697,68 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
             }
         }
         __syncthreads();
-        if (lane == 0) {
+        if (unk) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[p];
+        {
+            const unsigned long long took = __ballot(valid && !unk);
+            if (lane == 0) judged += (unsigned long long)__popcll(took);
+        }
+        // this entry's first places
+        const uint32_t e_surv = s_at[wv][0] + x_surv - c_surv, e_goal = s_at[wv][1] + x_goal - c_goal;
+        const uint32_t e_p1 = s_at[wv][2] + x_p1 - c_p1, e_p2 = s_at[wv][3] + x_p2 - c_p2;
+        unsigned long long todo = __ballot(c_surv > 0u);
+        while (todo != 0ull) {
+            int src[kExpBatch];
+            uint32_t four[kExpBatch][2];
 #pragma unroll
             for (int b = 0; b < kExpBatch; ++b) {
-                if (b >= pending) continue;
-                if (unk[b]) unknown_out[atomicAdd(&ctr->n_unknown, 1u)] = entries[p0 + b];
-                else ++judged;
+                src[b] = -1;
+                if (todo != 0ull) { src[b] = __ffsll((long long)todo) - 1; todo &= todo - 1ull; }
             }
-        }
-        uint32_t at_surv = s_at[wv][0] + x_surv - c_surv, at_goal = s_at[wv][1] + x_goal - c_goal;
-        uint32_t at_p1 = s_at[wv][2] + x_p1 - c_p1, at_p2 = s_at[wv][3] + x_p2 - c_p2;
 #pragma unroll
-        for (int b = 0; b < kExpBatch; ++b) {
+            for (int b = 0; b < kExpBatch; ++b) {
+                const uint32_t r = (uint32_t)__shfl((int)row, src[b] < 0 ? 0 : src[b], 64);
+                const uint32_t* const words = reinterpret_cast<const uint32_t*>(codes + (size_t)r * CS);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                if (four[b][h] == 0u) continue;
+                for (int h = 0; h < 2; ++h) four[b][h] = (src[b] >= 0 && lane + 64 * h < CW) ? (words[lane + 64 * h] & in_alphabet[h]) : 0u;
+            }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int a = (lane + 64 * h) * 4 + j;
-                    const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
-                    if (code == CODE_INVALID) continue;
-                    FrontSurvivor sv;
-                    sv.entry = p0 + b; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
-                    sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
-                    if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
-                    if (at_surv < surv_cap) surv[at_surv] = sv;
-                    ++at_surv;
+            for (int b = 0; b < kExpBatch; ++b) {
+                if (src[b] < 0) continue;
+                // this lane's survivors of the entry by kind, and those of the lanes before it
+                uint32_t k_surv = 0, k_goal = 0, k_p1 = 0, k_p2 = 0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
+                        k_surv += code != CODE_INVALID; k_goal += code == CODE_GOAL; k_p1 += code == CODE_PREFIX; k_p2 += code == CODE_PREFIX2;
+                    }
+                }
+                uint32_t y_surv = k_surv, y_goal = k_goal, y_p1 = k_p1, y_p2 = k_p2;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t a0 = __shfl_up(y_surv, o, 64), a1 = __shfl_up(y_goal, o, 64), a2 = __shfl_up(y_p1, o, 64), a3 = __shfl_up(y_p2, o, 64);
+                    if (lane >= o) { y_surv += a0; y_goal += a1; y_p1 += a2; y_p2 += a3; }
+                }
+                uint32_t at_surv = (uint32_t)__shfl((int)e_surv, src[b], 64) + y_surv - k_surv;
+                uint32_t at_goal = (uint32_t)__shfl((int)e_goal, src[b], 64) + y_goal - k_goal;
+                uint32_t at_p1 = (uint32_t)__shfl((int)e_p1, src[b], 64) + y_p1 - k_p1;
+                uint32_t at_p2 = (uint32_t)__shfl((int)e_p2, src[b], 64) + y_p2 - k_p2;
+                const uint32_t entry = base + (uint32_t)(wv * epw + src[b]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (four[b][h] == 0u) continue;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int a = (lane + 64 * h) * 4 + j;
+                        const int code = (int)((four[b][h] >> (8 * j)) & 0xffu);
+                        if (code == CODE_INVALID) continue;
+                        FrontSurvivor sv;
+                        sv.entry = entry; sv.digit = (uint16_t)a; sv.code = (uint16_t)(code | (NP == 2 ? kFromTwoPair : 0));
+                        sv.slot = code == CODE_GOAL ? at_goal++ : code == CODE_PREFIX ? at_p1++ : code == CODE_PREFIX2 ? at_p2++ : 0u;
+                        if (code == CODE_PREFIX_LITERAL) atomicAdd(&ctr->n_prefix_literal, 1u);
+                        if (at_surv < surv_cap) surv[at_surv] = sv;
+                        ++at_surv;
+                    }
                 }
             }
         }
@@ -839,8 +851,8 @@ template <int KW, int MW, int NP>
 __global__ __launch_bounds__(256) void k_front_goal_filter(const DevQuery* __restrict__ qp, const uint32_t* __restrict__ states,
                                                            uint32_t n_entries, const uint32_t* __restrict__ list,
                                                            const uint32_t* __restrict__ n_list, uint8_t* __restrict__ codes,
-                                                           uint8_t* __restrict__ unknown, uint32_t* __restrict__ walk,
-                                                           uint32_t* __restrict__ n_walk) {
+                                                           uint2* __restrict__ row_counts, uint8_t* __restrict__ unknown,
+                                                           uint32_t* __restrict__ walk, uint32_t* __restrict__ n_walk) {
     using L = FL<KW, MW>;
     const DevQuery& q = *qp;
     const int R = q.R, I = q.alphabet;
@@ -875,7 +887,7 @@ __global__ __launch_bounds__(256) void k_front_goal_filter(const DevQuery* __res
         }
         if (__any(rows_short) && __any(cols_short) && __any(root_short)) {
             for (int a = lane; a < I; a += 64) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
-            if (lane == 0) unknown[e] = 0;
+            if (lane == 0) { unknown[e] = 0; row_counts[e] = make_uint2(0u, 0u); }
         } else if (lane == 0) {
             walk[atomicAdd(n_walk, 1u)] = e;
         }
@@ -889,7 +901,8 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
                                                                 const uint32_t* __restrict__ states, uint32_t n_entries,
                                                                 const uint32_t* __restrict__ list, const uint32_t* __restrict__ n_list,
                                                                 int max_pairs, int goals_only, uint8_t* __restrict__ codes,
-                                                                uint8_t* __restrict__ unknown, FrontCounters* __restrict__ ctr) {
+                                                                uint2* __restrict__ row_counts, uint8_t* __restrict__ unknown,
+                                                                FrontCounters* __restrict__ ctr) {
     extern __shared__ uint4 ldsq[];                      // NP planes of [R][WQ] quads, then R flag bytes
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ int s_goal, s_two, s_next, s_n_items, s_rows_short, s_cols_short;
@@ -975,6 +988,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             goal_ops = (s_rows_short == 0 ? 1 : 0) | (s_cols_short == 0 ? 2 : 0) | ((flags[0] & kFlagGoal) ? 4 : 0);
             if (goal_ops == 0) {
                 for (int a = tid; a < I; a += kClsThreads) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
+                if (tid == 0) row_counts[e] = make_uint2(0u, 0u);
                 continue;
             }
         }
@@ -1021,6 +1035,24 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             if (lane == 0)
                 cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, rs_straddles, ops_r, n_ops, max_pairs,
                                       all_rows, all_cols, goal_ops, codes + (size_t)e * front_code_stride(I), unknown + e);
+        }
+        // ---- how many of the row's codes are survivors, goals, one-pair and two-pair children (16 bits each), for the
+        //      kernel that lists the survivors of the prefixes: it then reads the rows of the prefixes that have any
+        __syncthreads();
+        if (wave == 0) {
+            const uint32_t* const words = reinterpret_cast<const uint32_t*>(codes + (size_t)e * front_code_stride(I));
+            uint32_t k_surv = 0, k_goal = 0, k_p1 = 0, k_p2 = 0;
+            for (int w = lane; w * 4 < I; w += 64) {
+                const uint32_t four = words[w];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int code = (w * 4 + j < I) ? (int)((four >> (8 * j)) & 0xffu) : CODE_INVALID;
+                    k_surv += code != CODE_INVALID; k_goal += code == CODE_GOAL; k_p1 += code == CODE_PREFIX; k_p2 += code == CODE_PREFIX2;
+                }
+            }
+            uint32_t lo = k_surv | (k_goal << 16), hi = k_p1 | (k_p2 << 16);      // (at most 512 each: no carry between the halves)
+            for (int o = 32; o > 0; o >>= 1) { lo += (uint32_t)__shfl_xor((int)lo, o, 64); hi += (uint32_t)__shfl_xor((int)hi, o, 64); }
+            if (lane == 0) row_counts[e] = make_uint2(lo, hi);
         }
     }
     if (tid == 0 && walked) atomicAdd(&ctr->n_walked_planes, walked * (uint32_t)NP);
@@ -1559,7 +1591,7 @@ struct FrontArgs {
     int np, max_pairs;
     const uint32_t* list; const uint32_t* n_list;
     uint8_t* codes; uint8_t* unknown; int goals_only; FrontCounters* ctr;
-    uint32_t* walk; uint32_t* n_walk;
+    uint32_t* walk; uint32_t* n_walk; uint2* row_counts;
     double* sums; uint32_t* sid; int n_share;
     const DevQuery* queries; const FrontLevel* level;
     int R;
@@ -1580,20 +1612,20 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
         if (e != hipSuccess) return e;
         if (A.np == 2)
             hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.unknown, A.ctr);
+                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.row_counts, A.unknown, A.ctr);
         else
             hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.unknown, A.ctr);
+                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.row_counts, A.unknown, A.ctr);
     } else if (what == 3) {
         // a wavefront per state, four to a block
         const unsigned want = (A.n + 3u) / 4u;
         const unsigned blocks = want < 16384u ? want : 16384u;
         if (A.np == 2)
             hipLaunchKernelGGL((k_front_goal_filter<KW, MW, 2>), dim3(blocks), dim3(256), 0, stream, A.q, A.states, A.n, A.list, A.n_list,
-                               A.codes, A.unknown, A.walk, A.n_walk);
+                               A.codes, A.row_counts, A.unknown, A.walk, A.n_walk);
         else
             hipLaunchKernelGGL((k_front_goal_filter<KW, MW, 1>), dim3(blocks), dim3(256), 0, stream, A.q, A.states, A.n, A.list, A.n_list,
-                               A.codes, A.unknown, A.walk, A.n_walk);
+                               A.codes, A.row_counts, A.unknown, A.walk, A.n_walk);
     } else {
         const size_t lds = (size_t)A.level->lds_planes * A.R * FL<KW, MW>::WS * 4;
         const unsigned blocks = A.level->n_surv < 8192u ? A.level->n_surv : 8192u;
@@ -1667,22 +1699,22 @@ hipError_t launch_front_prefixes(const DevQuery* queries, const FrontPrefixes& P
 }
 
 hipError_t launch_front_goal_filter(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                    const uint32_t* n_list, int np, uint8_t* codes, uint8_t* unknown, uint32_t* walk, uint32_t* n_walk,
-                                    hipStream_t stream) {
+                                    const uint32_t* n_list, int np, uint8_t* codes, unsigned long long* row_counts, uint8_t* unknown,
+                                    uint32_t* walk, uint32_t* n_walk, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
     A.q = q; A.states = states; A.n = n; A.np = np; A.list = list; A.n_list = n_list;
-    A.codes = codes; A.unknown = unknown; A.R = R; A.walk = walk; A.n_walk = n_walk;
+    A.codes = codes; A.unknown = unknown; A.R = R; A.walk = walk; A.n_walk = n_walk; A.row_counts = reinterpret_cast<uint2*>(row_counts);
     return front_dispatch(R, k, 3, A, stream);
 }
 
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes, uint8_t* unknown,
-                                 FrontCounters* ctr, hipStream_t stream) {
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes,
+                                 unsigned long long* row_counts, uint8_t* unknown, FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
     A.q = q; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.list = list; A.n_list = n_list;
-    A.codes = codes; A.unknown = unknown; A.R = R; A.goals_only = goals_only; A.ctr = ctr;
+    A.codes = codes; A.unknown = unknown; A.R = R; A.goals_only = goals_only; A.ctr = ctr; A.row_counts = reinterpret_cast<uint2*>(row_counts);
     return front_dispatch(R, k, 1, A, stream);
 }
 
@@ -1700,16 +1732,20 @@ hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const 
 }
 
 hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uint32_t n, const uint32_t* rep,
-                               const uint8_t* codes, const uint8_t* unknown, int np, int handover, FrontSurvivor* surv,
-                               uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
+                               const uint8_t* codes, const unsigned long long* row_counts, const uint8_t* unknown, int np, int handover,
+                               FrontSurvivor* surv, uint32_t surv_cap, FrontEntry* unknown_out, FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const unsigned per_block = kExpWaves * kExpBatch, want = (n + per_block - 1) / per_block;
+    // entries per wavefront: as many as leave some 4096 wavefronts to share the second pass
+    int epw = 8;
+    while (epw < 64 && n / (unsigned)epw > 4096u) epw *= 2;
+    const unsigned per_block = (unsigned)(kExpWaves * epw), want = (n + per_block - 1) / per_block;
     const unsigned blocks = want < 2048u ? want : 2048u;
+    const uint2* const rc = reinterpret_cast<const uint2*>(row_counts);
     if (np == 2)
-        hipLaunchKernelGGL(k_front_expand<2>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, unknown, handover, surv,
+        hipLaunchKernelGGL(k_front_expand<2>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, rc, unknown, handover, epw, surv,
                            surv_cap, unknown_out, ctr);
     else
-        hipLaunchKernelGGL(k_front_expand<1>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, unknown, handover, surv,
+        hipLaunchKernelGGL(k_front_expand<1>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, rc, unknown, handover, epw, surv,
                            surv_cap, unknown_out, ctr);
     return hipGetLastError();
 }
