@@ -843,12 +843,12 @@ enum : int { CSTEP_INVALID = 0, CSTEP_OK = 1, CSTEP_OVERFLOW = 2 };
 
 // Sec. 3.5: device i holds column i in every row -- one class.
 template <int MW>
-__device__ inline void cls_init(const DevQuery& q, const ClsLds& X, int& C, int lane) {
-    for (int d = lane; d < q.R; d += kWave) {
+__device__ inline void cls_init(const DevQuery& q, const ClsLds& X, int& C, int lane, const int nt = kWave) {
+    for (int d = lane; d < q.R; d += nt) {
 #pragma unroll
         for (int w = 0; w < MW; ++w) X.S[d * X.cs * MW + w] = (w == (d >> 5)) ? (1u << (d & 31)) : 0u;
     }
-    for (int r = lane; r < q.k; r += kWave) X.cls[r] = 0;
+    for (int r = lane; r < q.k; r += nt) X.cls[r] = 0;
     if (lane == 0) X.csize[0] = (uint32_t)q.k;
     C = 1;
     __syncthreads();
@@ -899,29 +899,33 @@ __device__ __forceinline__ uint32_t small_div(uint32_t b, uint32_t per) {
 // grow with the row number, so the new classes are runs of consecutive rows of an old class, and a row
 // starts a run iff some such group starts a new block after the previous row of the class, up to the row.
 template <int MW>
-__device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds& X, int& C, int lane) {
+__device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds& X, int& C, int lane, const int nt = kWave) {
     const int k = q.k, g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs, ngs = X.ngs;
     const int kw = (k + 31) / 32;
-    const unsigned long long below = (1ull << lane) - 1ull;
-    for (int i = lane; i < C * kw; i += kWave) { X.rows[i] = 0; X.bnd[i] = 0; }
+    // (lane = thread of the block's nt; the passes that go by ballots over 64 consecutive rows are dealt out to
+    //  the block's wavefronts by group or by run of rows)
+    const int ln = lane & (kWave - 1), wv = lane / kWave, nw = nt / kWave;
+    const unsigned long long below = (1ull << ln) - 1ull;
+    for (int i = lane; i < C * kw; i += nt) { X.rows[i] = 0; X.bnd[i] = 0; }
+    if (lane == 0) X.flags[3] = 0;                       // (the number of new classes is added up here)
     __syncthreads();
-    for (int r = lane; r < k; r += kWave) atomicOr(&X.rows[(int)X.cls[r] * kw + (r >> 5)], 1u << (r & 31));
+    for (int r = lane; r < k; r += nt) atomicOr(&X.rows[(int)X.cls[r] * kw + (r >> 5)], 1u << (r & 31));
     // block starts of every group, united per class (lane c keeps the words of class c)
-    for (int G = 0; G < ng; ++G) {
+    for (int G = wv; G < ng; G += nw) {
         const uint32_t per = X.gcount[G] / (uint32_t)g;
         if (per == 0u) continue;                          // a group of empty devices
         const unsigned long long gne = (unsigned long long)X.gne[2 * G] | ((unsigned long long)X.gne[2 * G + 1] << 32);
-        const bool mine = lane < C && ((gne >> lane) & 1ull) != 0ull;
+        const bool mine = ln < C && ((gne >> ln) & 1ull) != 0ull;
         uint32_t carry = 0;                               // non-empty rows of the group below the chunk
         for (int r0 = 0; r0 < k; r0 += kWave) {
-            const int r = r0 + lane;
+            const int r = r0 + ln;
             const bool ne = r < k && ((gne >> X.cls[r < k ? r : 0]) & 1ull) != 0ull;
             const unsigned long long bal = __ballot(ne);
             const uint32_t before = carry + (uint32_t)__popcll(bal & below);
             const unsigned long long starts = __ballot(ne && before != 0u && small_div(before, per) * per == before);
-            if (mine) {
-                X.bnd[lane * kw + (r0 >> 5)] |= (uint32_t)starts;
-                if ((r0 >> 5) + 1 < kw) X.bnd[lane * kw + (r0 >> 5) + 1] |= (uint32_t)(starts >> 32);
+            if (mine) {                                   // (several wavefronts, each with a group of its own, may meet in a word)
+                if ((uint32_t)starts) atomicOr(&X.bnd[ln * kw + (r0 >> 5)], (uint32_t)starts);
+                if ((r0 >> 5) + 1 < kw && (uint32_t)(starts >> 32)) atomicOr(&X.bnd[ln * kw + (r0 >> 5) + 1], (uint32_t)(starts >> 32));
             }
             carry += (uint32_t)__popcll(bal);
         }
@@ -929,8 +933,8 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
     __syncthreads();
     // run starts
     int newC = 0;
-    for (int r0 = 0; r0 < k; r0 += kWave) {
-        const int r = r0 + lane;
+    for (int r0 = wv * kWave; r0 < k; r0 += nt) {
+        const int r = r0 + ln;
         bool st = false;
         if (r < k) {
             const int c = (int)X.cls[r];
@@ -951,15 +955,17 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
             }
         }
         const unsigned long long bal = __ballot(st);
-        if (lane == 0) { X.start[r0 >> 5] = (uint32_t)bal; X.start[(r0 >> 5) + 1] = (uint32_t)(bal >> 32); }
+        if (ln == 0) { X.start[r0 >> 5] = (uint32_t)bal; X.start[(r0 >> 5) + 1] = (uint32_t)(bal >> 32); }
         newC += __popcll(bal);
     }
+    if (ln == 0 && newC) atomicAdd(&X.flags[3], (uint32_t)newC);
     __syncthreads();
+    newC = (int)X.flags[3];
     if (newC > cm) return CSTEP_OVERFLOW;                 // (nothing of the state has been written yet)
-    for (int i = lane; i < newC; i += kWave) X.ncsize[i] = 0;
+    for (int i = lane; i < newC; i += nt) X.ncsize[i] = 0;
     __syncthreads();
     // the new class of a row: the number of run starts below the start of its own run
-    for (int r = lane; r < k; r += kWave) {
+    for (int r = lane; r < k; r += nt) {
         const uint32_t* const mine = X.rows + (int)X.cls[r] * kw;
         int w = r >> 5;
         uint32_t m = mine[w] & X.start[w] & (((1u << (r & 31)) << 1) - 1u);
@@ -974,16 +980,16 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
     }
     __syncthreads();
     // the rank that keeps each new class in each group: that of the class's first row
-    for (int G = 0; G < ng; ++G) {
+    for (int G = wv; G < ng; G += nw) {
         const uint32_t per = X.gcount[G] / (uint32_t)g;
         if (per == 0u) {
-            for (int c2 = lane; c2 < newC; c2 += kWave) X.own[c2 * ngs + G] = (uint8_t)0xff;
+            for (int c2 = ln; c2 < newC; c2 += kWave) X.own[c2 * ngs + G] = (uint8_t)0xff;
             continue;
         }
         const unsigned long long gne = (unsigned long long)X.gne[2 * G] | ((unsigned long long)X.gne[2 * G + 1] << 32);
         uint32_t carry = 0;
         for (int r0 = 0; r0 < k; r0 += kWave) {
-            const int r = r0 + lane;
+            const int r = r0 + ln;
             const bool ne = r < k && ((gne >> X.cls[r < k ? r : 0]) & 1ull) != 0ull;
             const unsigned long long bal = __ballot(ne);
             const uint32_t before = carry + (uint32_t)__popcll(bal & below);
@@ -994,7 +1000,7 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
     }
     __syncthreads();
     // members: the rank that keeps the class takes the group's combined row, the others are left empty
-    for (int it = lane; it < q.R * newC; it += kWave) {
+    for (int it = lane; it < q.R * newC; it += nt) {
         const int d = it / newC, c2 = it - d * newC;
         if (P.master && (d % s) != 0) continue;
         const int G = P.master ? d / gs : (d / gs) * s + d % s;
@@ -1024,27 +1030,27 @@ __device__ int cls_scatter(const DevQuery& q, const DevPattern& P, const ClsLds&
         }
     }
     __syncthreads();
-    for (int r = lane; r < k; r += kWave) X.cls[r] = X.ncls[r];
-    for (int i = lane; i < newC; i += kWave) X.csize[i] = X.ncsize[i];
+    for (int r = lane; r < k; r += nt) X.cls[r] = X.ncls[r];
+    for (int i = lane; i < newC; i += nt) X.csize[i] = X.ncsize[i];
     C = newC;
     __syncthreads();
     return CSTEP_OK;
 }
 
-// One instruction on the class state (the rules of lit_step, a class standing for its rows).  All lanes
-// call it with the same arguments.  An invalid step and an overflow leave the state as it was.
+// One instruction on the class state (the rules of lit_step, a class standing for its rows).  All nt threads
+// of the block call it with the same arguments (lane = thread number; nt a multiple of 64).  An invalid step and an overflow leave the state as it was.
 template <int MW>
-__device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int& C, int lane) {
+__device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int& C, int lane, const int nt = kWave) {
     const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cm = X.cm, cs = X.cs;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
-    for (int i = lane; i < ng; i += kWave) { X.gcount[i] = 0; X.gflag[i] = 0; X.gne[2 * i] = 0; X.gne[2 * i + 1] = 0; }
+    for (int i = lane; i < ng; i += nt) { X.gcount[i] = 0; X.gflag[i] = 0; X.gne[2 * i] = 0; X.gne[2 * i + 1] = 0; }
     if (op == OP_AG)
-        for (int i = lane; i < q.R; i += kWave) X.devne[i] = 0;
+        for (int i = lane; i < q.R; i += nt) X.devne[i] = 0;
     if (lane == 0) { X.flags[0] = 0; X.flags[1] = 0; }
     __syncthreads();
     const int items = ng * C;
     bool bad = false;
-    for (int it = lane; it < items; it += kWave) {
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, C), c = it - G * C;
         const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
@@ -1101,7 +1107,7 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
     }
     if (bad) X.flags[0] = 1;
     __syncthreads();
-    for (int G = lane; G < ng; G += kWave) {
+    for (int G = lane; G < ng; G += nt) {
         const uint32_t cnt = X.gcount[G];
         if (red) {
             if (op == OP_RS && cnt % (uint32_t)g != 0) X.flags[0] = 1;   // scatter: chunks must divide evenly
@@ -1118,8 +1124,8 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
     }
     __syncthreads();
     if (X.flags[0] || !X.flags[1]) return CSTEP_INVALID;
-    if (op == OP_RS) return cls_scatter<MW>(q, P, X, C, lane);
-    for (int it = lane; it < items; it += kWave) {
+    if (op == OP_RS) return cls_scatter<MW>(q, P, X, C, lane, nt);
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, C), c = it - G * C;
         const int base = group_base(P.master, G, s, gs);
         uint32_t t[MW];
@@ -1140,15 +1146,15 @@ __device__ int cls_step(const DevQuery& q, const DevPattern& P, int op, const Cl
 // 2 = valid and the result is the goal, 3 = valid.  Needs devany and devfull.
 template <int MW>
 __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, const ClsLds& X, int C, const uint32_t* full,
-                            int lane) {
+                            int lane, const int nt = kWave) {
     const int g = P.g, s = P.s, ng = P.n_groups, gs = g * s, cs = X.cs;
     const bool red = op == OP_AR || op == OP_RS || op == OP_RD;
-    for (int i = lane; i < ng; i += kWave) { X.gcount[i] = 0; X.gflag[i] = 0; }
+    for (int i = lane; i < ng; i += nt) { X.gcount[i] = 0; X.gflag[i] = 0; }
     if (lane == 0) { X.flags[0] = 0; X.flags[1] = 0; X.flags[2] = 0; }
     __syncthreads();
     const int items = ng * C;
     bool bad = false, notfull = false;
-    for (int it = lane; it < items; it += kWave) {
+    for (int it = lane; it < items; it += nt) {
         const int G = div_fast(it, C), c = it - G * C;
         const int base = group_base(P.master, G, s, gs);
         uint32_t acc[MW];
@@ -1205,12 +1211,12 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
     if (notfull) X.flags[2] = 1;
     // devices the pattern does not touch must already be at the goal
     if (P.master)
-        for (int d = lane; d < q.R; d += kWave) {
+        for (int d = lane; d < q.R; d += nt) {
             const bool part = d % s == 0 && d / gs < ng;
             if (!part && !X.devfull[d]) X.flags[2] = 1;
         }
     __syncthreads();
-    for (int G = lane; G < ng; G += kWave) {
+    for (int G = lane; G < ng; G += nt) {
         const uint32_t cnt = X.gcount[G];
         if (red) {
             if (op == OP_RS && cnt % (uint32_t)g != 0) X.flags[0] = 1;
@@ -1230,9 +1236,11 @@ __device__ int cls_classify(const DevQuery& q, const DevPattern& P, int op, cons
 // everywhere, every held row is complete, device 0 is at the goal.
 template <int MW>
 __device__ inline void cls_device_flags(const DevQuery& q, const ClsLds& X, int C, const uint32_t* full, int lane,
-                                        bool& rows_full, bool& cols_full, bool& root_done) {
+                                        bool& rows_full, bool& cols_full, bool& root_done, const int nt = kWave) {
     bool rows_bad = false, cols_bad = false;
-    for (int d = lane; d < q.R; d += kWave) {
+    if (lane == 0) { X.flags[0] = 0; X.flags[1] = 0; }
+    __syncthreads();
+    for (int d = lane; d < q.R; d += nt) {
         bool any = false, all = true;
         for (int c = 0; c < C; ++c) {
             const uint32_t* x = X.S + (d * X.cs + c) * MW;
@@ -1243,10 +1251,13 @@ __device__ inline void cls_device_flags(const DevQuery& q, const ClsLds& X, int 
         }
         X.devany[d] = any; X.devfull[d] = all;
     }
-    rows_full = !__any(rows_bad);
-    cols_full = !__any(cols_bad);
+    if (rows_bad) X.flags[0] = 1;
+    if (cols_bad) X.flags[1] = 1;
     __syncthreads();
+    rows_full = X.flags[0] == 0u;
+    cols_full = X.flags[1] == 0u;
     root_done = X.devfull[0] != 0u;
+    __syncthreads();                                     // (the flags are used again by what follows)
 }
 
 // The last instructions a = part, part + parts, ... of a group against the class state; those that are valid
@@ -1335,9 +1346,10 @@ __global__ __launch_bounds__(NT) void k_front_classify_literal(const DevQuery* _
 
 // The same on the class state (in LDS, or in the block's slice of a global buffer where it does not fit): a
 // prefix is rebuilt at the cost of its classes instead of its k rows.  A prefix that needs more classes than
-// the state holds is put on the list `over` (ctr->n_overflow entries) for the kernel above.
-template <int MW>
-__global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery* __restrict__ qp,
+// the state holds is put on the list `over` (ctr->n_overflow entries) for the kernel above.  NT threads per block:
+// one wavefront where the masks are in LDS, several where they lie in global memory (as in the kernel above).
+template <int MW, int NT>
+__global__ __launch_bounds__(NT) void k_front_classify_classes(const DevQuery* __restrict__ qp,
                                                                   const FrontEntry* __restrict__ entries, uint32_t n_entries,
                                                                   int parent_len, int goals_only, FrontSurvivor* __restrict__ surv,
                                                                   uint32_t surv_cap, FrontCounters* __restrict__ ctr,
@@ -1360,17 +1372,17 @@ __global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery
     for (uint32_t e = blockIdx.x; e < n_entries; e += gridDim.x) {
         const unsigned long long digits = entries[e].digits;
         int C = 1, rc = CSTEP_OK;
-        cls_init<MW>(q, X, C, lane);
+        cls_init<MW>(q, X, C, lane, NT);
         for (int t = 0; t < parent_len && rc == CSTEP_OK; ++t) {
             const uint32_t ins = q.instr_of_digit[(int)((digits >> (9 * t)) & 511ull)];
-            rc = cls_step<MW>(q, q.pat[ins >> 3], (int)(ins & 7u), X, C, lane);
+            rc = cls_step<MW>(q, q.pat[ins >> 3], (int)(ins & 7u), X, C, lane, NT);
         }
         if (rc != CSTEP_OK) {                    // too many classes: the full literal state decides
             if (lane == 0) over[atomicAdd(&ctr->n_overflow, 1u)] = e;
             continue;
         }
         bool rows_full, cols_full, root_done;
-        cls_device_flags<MW>(q, X, C, full, lane, rows_full, cols_full, root_done);
+        cls_device_flags<MW>(q, X, C, full, lane, rows_full, cols_full, root_done, NT);
         for (int a = 0; a < I; ++a) {
             const uint32_t ins = q.instr_of_digit[a];
             const DevPattern& P = q.pat[ins >> 3];
@@ -1380,7 +1392,7 @@ __global__ __launch_bounds__(kWave) void k_front_classify_classes(const DevQuery
                 const int op = (int)(ins & 7u);
                 if (!((op == OP_AR && rows_full) || (op == OP_AG && cols_full) || (op == OP_BC && root_done))) continue;
             }
-            const int code = cls_classify<MW>(q, P, (int)(ins & 7u), X, C, full, lane);
+            const int code = cls_classify<MW>(q, P, (int)(ins & 7u), X, C, full, lane, NT);
             if (code != 0 && lane == 0) {
                 const uint32_t pos = atomicAdd(&ctr->n_surv_literal, 1u);
                 if (pos < surv_cap) { FrontSurvivor sv; sv.entry = e; sv.digit = (uint16_t)a; sv.code = (uint16_t)code; surv[pos] = sv; }
@@ -1782,6 +1794,8 @@ hipError_t launch_cost_literal_list(const DevQuery* queries, const DevPostSeg* s
 // down that path.
 // threads of a block of the full-state kernel where the state lies in global memory
 constexpr int kFullThreads = 512;
+// ... and of the class-state kernel where its masks do
+constexpr int kClassThreads = 256;
 static int row_class_cap(int asked) { return asked >= 1 && asked < 64 ? asked : 64; }
 
 // Scratch of launch_front_classify_literal: the slices of the full-state kernel (where that state does not
@@ -1829,10 +1843,17 @@ hipError_t launch_front_classify_literal(const DevQuery* q, int R, int k, const 
     hipError_t e = hipSuccess;
     // first on the class state; what needs more classes than that holds, on the full literal state
 #define P2_LAUNCH(MWV)                                                                                         \
-    e = allow_big_lds(k_front_classify_classes<MWV>, sc.cls_lds);                                              \
-    if (e == hipSuccess)                                                                                       \
-        hipLaunchKernelGGL(k_front_classify_classes<MWV>, dim3(cls_blocks), dim3(kWave), sc.cls_lds, stream, q, entries, n, \
-                           parent_len, goals_only, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap); \
+    if (cls_mem) {                                                                                             \
+        e = allow_big_lds(k_front_classify_classes<MWV, kClassThreads>, sc.cls_lds);                           \
+        if (e == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL((k_front_classify_classes<MWV, kClassThreads>), dim3(cls_blocks), dim3(kClassThreads), sc.cls_lds, stream, q, entries, n, \
+                               parent_len, goals_only, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap); \
+    } else {                                                                                                   \
+        e = allow_big_lds(k_front_classify_classes<MWV, kWave>, sc.cls_lds);                                   \
+        if (e == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL((k_front_classify_classes<MWV, kWave>), dim3(cls_blocks), dim3(kWave), sc.cls_lds, stream, q, entries, n, \
+                               parent_len, goals_only, surv, surv_cap, ctr, over, cls_mem, cls_words_per, class_cap); \
+    }                                                                                                          \
     if (e == hipSuccess && sc.full_lds) {                                                                      \
         e = allow_big_lds(k_front_classify_literal<MWV, kWave>, sc.full_lds);                                  \
         if (e == hipSuccess)                                                                                   \
