@@ -963,15 +963,17 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.begin(SpanRec::kClassify, S.stream, (n_s[0] > 0) + (n_s[1] > 0)));
             for (int li = 0; li < 2; ++li)
                 P2_HIP(launch_front_classify(dq, pl.R, pl.k, static_cast<const uint32_t*>(list_states[li]->p), n_s[li], cls_list[li],
-                                             cls_n[li], li + 1, max_pairs, keep ? 0 : 1,
+                                             cls_n[li], li + 1, max_pairs, keep ? 0 : 1, (li == 1 && handover) ? 0 : 1,
                                              static_cast<uint8_t*>(S.f_codes[li].p), static_cast<unsigned long long*>(S.f_rowcnt[li].p),
                                              static_cast<uint8_t*>(S.f_unk[li].p), dctr, S.stream));
             if (n_s[0] + n_s[1] > 0) P2_HIP(S.spans.end(S.stream));
-            uint32_t walked_planes = 0;
+            uint32_t walked_planes = 0, kids[3] = {0u, 0u, 0u};
             for (int attempt = 0;; ++attempt) {     // list the survivors of the prefixes; repeat with larger lists if they overflow
                 P2_HIP(S.f_surv.ensure(cap_c * sizeof(FrontSurvivor)));
                 if (attempt > 0) {
                     P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
+                    // (the classification is not repeated: what it counted goes back in)
+                    P2_HIP(hipMemcpyAsync(&dctr->t_count[0], kids, sizeof kids, hipMemcpyHostToDevice, S.stream));
                     const int32_t rc = literal_on_side();
                     if (rc != P2_OK) return rc;
                 }
@@ -987,18 +989,15 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                            static_cast<const uint8_t*>(S.f_unk[1].p), 2, handover,
                                            static_cast<FrontSurvivor*>(S.f_surv.p), (uint32_t)cap_c,
                                            static_cast<FrontEntry*>(S.f_unknown.p), dctr, S.stream));
-                // (how many children the judged states have, by kind)
-                for (int li = 0; li < 2; ++li) {
-                    if (li == 1 && handover) continue;
-                    P2_HIP(launch_front_children(dq, n_s[li], grouped[li] ? static_cast<const uint32_t*>(S.f_replist[li].p) : nullptr,
-                                                 grouped[li] ? &dctr->n_reps[li] : nullptr, static_cast<const uint8_t*>(S.f_codes[li].p),
-                                                 static_cast<const uint8_t*>(S.f_unk[li].p), li + 1, keep, 0, nullptr, nullptr, dctr, S.stream));
-                }
+                // (how many children the judged states have, by kind, the classification has counted)
                 if (n_c + n_c2 > 0) P2_HIP(S.spans.end(S.stream));
                 if (n_l > 0) P2_HIP(hipStreamWaitEvent(S.stream, S.side_done, 0));
                 P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
                 P2_HIP(hipStreamSynchronize(S.stream));
-                if (attempt == 0) walked_planes = hctr->n_walked_planes;    // (a repeat clears the level's counters)
+                if (attempt == 0) {                  // (a repeat clears the level's counters)
+                    walked_planes = hctr->n_walked_planes;
+                    for (int kd = 0; kd < 3; ++kd) kids[kd] = hctr->t_count[kd];
+                }
                 n_surv_l_first = hctr->n_surv_literal;
                 if (hctr->n_unknown > 0 && hctr->n_surv_literal <= cap_l) {
                     // two-pair prefixes that this form could not judge: the literal kernels classify them from their

@@ -331,9 +331,11 @@ hipError_t launch_front_dedup(const uint32_t* states, size_t state_words, const 
 // Judges the entries list[0 .. *n_list) of a frontier list (every entry 0 .. n - 1 if list is null) against the
 // alphabet: codes[e * alphabet + digit] = CODE_* of that extension of entry e, unknown[e] = 1 where the pair form
 // cannot judge the entry.  np: planes per entry (1: the one-pair list, 2: the two-pair list).  max_pairs = 1 sends
-// children that need two pairs to the literal list.
+// children that need two pairs to the literal list.  row_counts[e]: how many of the row's codes are survivors, goals
+// (low word, 16 bits each), one-pair and two-pair children (high word).  count_children != 0 adds the children of the
+// entries it could judge to ctr->t_count (by kind).
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes,
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, int count_children, uint8_t* codes,
                                  unsigned long long* row_counts, uint8_t* unknown, FrontCounters* ctr, hipStream_t stream);
 // The last level, before the classification (which then runs with goals_only on the list this leaves): the entries
 // from which no instruction can end at the goal get a row of invalid codes; the others are listed in

@@ -900,9 +900,9 @@ template <int KW, int MW, int NP>
 __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify(const DevQuery* __restrict__ qp,
                                                                 const uint32_t* __restrict__ states, uint32_t n_entries,
                                                                 const uint32_t* __restrict__ list, const uint32_t* __restrict__ n_list,
-                                                                int max_pairs, int goals_only, uint8_t* __restrict__ codes,
-                                                                uint2* __restrict__ row_counts, uint8_t* __restrict__ unknown,
-                                                                FrontCounters* __restrict__ ctr) {
+                                                                int max_pairs, int goals_only, int count_children,
+                                                                uint8_t* __restrict__ codes, uint2* __restrict__ row_counts,
+                                                                uint8_t* __restrict__ unknown, FrontCounters* __restrict__ ctr) {
     extern __shared__ uint4 ldsq[];                      // NP planes of [R][WQ] quads, then R flag bytes
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ int s_goal, s_two, s_next, s_n_items, s_rows_short, s_cols_short;
@@ -952,6 +952,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     for (int i = 0; i < 5; ++i) { ops_r[i] = i < n_ops ? q.ops[i] : -1; has_bcast |= ops_r[i] == OP_BC; has_scatter |= ops_r[i] == OP_RS; }
     const uint32_t n_work = list ? *n_list : n_entries;
     uint32_t walked = 0;                                 // states whose patterns were walked (thread 0 counts)
+    uint32_t kids[3] = {0u, 0u, 0u};                     // one-pair children, two-pair children, goals of this block's states
     for (uint32_t at = blockIdx.x; at < n_work; at += gridDim.x) {
         const uint32_t e = list ? list[at] : at;
         __syncthreads();
@@ -1052,8 +1053,18 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
             }
             uint32_t lo = k_surv | (k_goal << 16), hi = k_p1 | (k_p2 << 16);      // (at most 512 each: no carry between the halves)
             for (int o = 32; o > 0; o >>= 1) { lo += (uint32_t)__shfl_xor((int)lo, o, 64); hi += (uint32_t)__shfl_xor((int)hi, o, 64); }
-            if (lane == 0) row_counts[e] = make_uint2(lo, hi);
+            if (lane == 0) {
+                row_counts[e] = make_uint2(lo, hi);
+                // the children of the judged states by kind (a state that this form cannot judge has none: its prefixes
+                // go to the literal kernels)
+                if (count_children && unknown[e] == 0) { kids[0] += hi & 0xffffu; kids[1] += hi >> 16; kids[2] += lo >> 16; }
+            }
         }
+    }
+    if (tid == 0) {
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+            if (kids[kd]) atomicAdd(&ctr->t_count[kd], kids[kd]);
     }
     if (tid == 0 && walked) atomicAdd(&ctr->n_walked_planes, walked * (uint32_t)NP);
 }
@@ -1590,7 +1601,7 @@ struct FrontArgs {
     const FrontEntry* entries; const uint32_t* states; uint32_t n;
     int np, max_pairs;
     const uint32_t* list; const uint32_t* n_list;
-    uint8_t* codes; uint8_t* unknown; int goals_only; FrontCounters* ctr;
+    uint8_t* codes; uint8_t* unknown; int goals_only, count_children; FrontCounters* ctr;
     uint32_t* walk; uint32_t* n_walk; uint2* row_counts;
     double* sums; uint32_t* sid; int n_share;
     const DevQuery* queries; const FrontLevel* level;
@@ -1612,10 +1623,10 @@ hipError_t front_go(int what, const FrontArgs& A, hipStream_t stream) {
         if (e != hipSuccess) return e;
         if (A.np == 2)
             hipLaunchKernelGGL((k_front_classify<KW, MW, 2>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.row_counts, A.unknown, A.ctr);
+                               A.n_list, A.max_pairs, A.goals_only, A.count_children, A.codes, A.row_counts, A.unknown, A.ctr);
         else
             hipLaunchKernelGGL((k_front_classify<KW, MW, 1>), dim3(blocks), dim3(kClsThreads), lds, stream, A.q, A.states, A.n, A.list,
-                               A.n_list, A.max_pairs, A.goals_only, A.codes, A.row_counts, A.unknown, A.ctr);
+                               A.n_list, A.max_pairs, A.goals_only, A.count_children, A.codes, A.row_counts, A.unknown, A.ctr);
     } else if (what == 3) {
         // a wavefront per state, four to a block
         const unsigned want = (A.n + 3u) / 4u;
@@ -1709,12 +1720,12 @@ hipError_t launch_front_goal_filter(const DevQuery* q, int R, int k, const uint3
 }
 
 hipError_t launch_front_classify(const DevQuery* q, int R, int k, const uint32_t* states, uint32_t n, const uint32_t* list,
-                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, uint8_t* codes,
+                                 const uint32_t* n_list, int np, int max_pairs, int goals_only, int count_children, uint8_t* codes,
                                  unsigned long long* row_counts, uint8_t* unknown, FrontCounters* ctr, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     FrontArgs A{};
     A.q = q; A.states = states; A.n = n; A.np = np; A.max_pairs = max_pairs; A.list = list; A.n_list = n_list;
-    A.codes = codes; A.unknown = unknown; A.R = R; A.goals_only = goals_only; A.ctr = ctr; A.row_counts = reinterpret_cast<uint2*>(row_counts);
+    A.codes = codes; A.unknown = unknown; A.R = R; A.goals_only = goals_only; A.count_children = count_children; A.ctr = ctr; A.row_counts = reinterpret_cast<uint2*>(row_counts);
     return front_dispatch(R, k, 1, A, stream);
 }
 
