@@ -5,6 +5,7 @@
 #include <cstddef>
 #include <cstring>
 #include <atomic>
+#include <functional>
 #include <thread>
 #include <limits>
 #include <string>
@@ -525,21 +526,19 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
     auto build_and_upload_rows = [&]() -> int32_t {
         if (rows_ready) return P2_OK;
         size_t bytes = 0;
-        if (n_msg > 0) {                                      // without message sizes the tables stay empty
-            // (large batches: the queries' tables are independent, a few host threads share them)
-            const unsigned hw = std::thread::hardware_concurrency();
-            const int n_threads = n_queries >= 32 ? (int)std::min<unsigned>(std::max(hw, 1u), 8u) : 1;
-            if (n_threads <= 1) {
-                for (auto& r : runs) build_cost_tables(r.plan);
-            } else {
-                std::atomic<int> next{0};
-                auto work = [&]() { for (int i = next.fetch_add(1); i < n_queries; i = next.fetch_add(1)) build_cost_tables(runs[i].plan); };
-                std::vector<std::thread> pool;
-                for (int t = 1; t < n_threads; ++t) pool.emplace_back(work);
-                work();
-                for (auto& th : pool) th.join();
-            }
-        }
+        // (large batches: the queries' tables are independent, a few host threads share them, for building and for packing)
+        const unsigned hw = std::thread::hardware_concurrency();
+        const int n_threads = n_queries >= 256 ? (int)std::min<unsigned>(std::max(hw, 1u), 16u) : n_queries >= 32 ? (int)std::min<unsigned>(std::max(hw, 1u), 8u) : 1;
+        auto for_every_query = [&](const std::function<void(int)>& f) {
+            if (n_threads <= 1) { for (int i = 0; i < n_queries; ++i) f(i); return; }
+            std::atomic<int> next{0};
+            auto work = [&]() { for (int i = next.fetch_add(1); i < n_queries; i = next.fetch_add(1)) f(i); };
+            std::vector<std::thread> pool;
+            for (int t = 1; t < n_threads; ++t) pool.emplace_back(work);
+            work();
+            for (auto& th : pool) th.join();
+        };
+        if (n_msg > 0) for_every_query([&](int i) { build_cost_tables(runs[i].plan); });    // without message sizes the tables stay empty
         for (auto& r : runs) {
             size_t n_rows = 0, n_ent = 0;
             for (const Pattern& p : r.plan.patterns) { n_rows += p.row_level.size(); n_ent += p.entries.size(); }
@@ -552,7 +551,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         char* hr = static_cast<char*>(C.h_rows.p);
         char* dr = static_cast<char*>(C.rows.p);
         DevRows* hdr = static_cast<DevRows*>(C.h_rows_hdr.p);
-        for (int i = 0; i < n_queries; ++i) {
+        for_every_query([&](int i) {
             const QueryRun& r = runs[i];
             const Plan& pl = r.plan;
             int32_t* rp = reinterpret_cast<int32_t*>(hr + r.off_rowptr);
@@ -577,7 +576,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             H.row_ptr = reinterpret_cast<const int32_t*>(dr + r.off_rowptr);
             H.row_level = reinterpret_cast<const int32_t*>(dr + r.off_rowlevel);
             H.entries = reinterpret_cast<const uint32_t*>(dr + r.off_entries);
-        }
+        });
         rows_ready = true;
         P2_HIP(hipMemcpyAsync(C.rows.p, C.h_rows.p, bytes, hipMemcpyHostToDevice, C.copy_stream));
         P2_HIP(hipMemcpyAsync(C.rows_hdr.p, C.h_rows_hdr.p, sizeof(DevRows) * (size_t)n_queries, hipMemcpyHostToDevice, C.copy_stream));

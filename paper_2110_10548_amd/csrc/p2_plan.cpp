@@ -129,7 +129,7 @@ inline int group_base(const Pattern& p, int group) {       // local id of the gr
 
 void build_cost_rows(const Plan& pl, Pattern& p) {
     // scratch kept between calls: this runs for every pattern of every query of every call
-    thread_local std::vector<int32_t> stamp, cnt, touched, row_begin;
+    thread_local std::vector<int32_t> stamp, cnt, touched, row_begin, group_of, key_of;
     thread_local std::vector<uint32_t> flat;
     thread_local std::vector<char> dead;
     p.row_ptr.assign(1, 0);
@@ -140,6 +140,15 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
     cnt.assign(p.n_groups, 0);
     int stamp_id = 0;
     int below = pl.D;
+    // a device's group in this pattern (-1: takes no part) and its (replica, group) key: the same at every level
+    group_of.assign(pl.D, -1);
+    key_of.assign(pl.D, 0);
+    for (int d = 0; d < pl.D; ++d) {
+        const int loc = pl.local_of[d];
+        if (!takes_part(p, loc)) continue;
+        group_of[d] = local_group(p, loc);
+        key_of[d] = pl.replica_of[d] * p.n_groups + group_of[d];
+    }
     for (int j = 0; j < pl.n; ++j) {
         below /= pl.h[j];
         if (j < p.span) continue;
@@ -150,10 +159,9 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
             ++stamp_id;
             touched.clear();
             for (int d = u * below; d < (u + 1) * below; ++d) {
-                int loc = pl.local_of[d];
-                if (!takes_part(p, loc)) continue;
-                int lg = local_group(p, loc);
-                size_t key = (size_t)pl.replica_of[d] * p.n_groups + lg;
+                const int lg = group_of[d];
+                if (lg < 0) continue;
+                const size_t key = (size_t)key_of[d];
                 if (stamp[key] == stamp_id) continue;
                 stamp[key] = stamp_id;
                 if (cnt[lg]++ == 0) touched.push_back(lg);
