@@ -306,7 +306,11 @@ int32_t p2_topk_device_noalloc(const double* cost, int64_t cost_stride, const ui
                                int64_t* out_pos, uint32_t* out_nan, void* stream);
 
 /* Timing of the calling thread's last p2_synthesize / p2_synthesize_batch call, taken with HIP
- * events on the call's stream.  Off by default; p2_set_profiling(1) turns the events on. */
+ * events on the call's stream.  Off by default; p2_set_profiling(1) turns the events on.
+ * p2_set_profiling(2) does the same but, of the frontier engine's launches, times only the classification
+ * and the building of the children (front_classify_*, front_materialize_*): front_literal_ms and
+ * front_group_ms then stay zero.  An event pair per group of small launches costs host time (some 2 000 pairs
+ * in a call on a large batch, several per cent of the call), which a measurement of the whole call can do without. */
 typedef struct {
     float eval_ms;             /* all evaluation-kernel launches of the call                       */
     float post_ms;             /* ordering, cost and top-k kernels                                 */

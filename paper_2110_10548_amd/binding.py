@@ -356,7 +356,8 @@ def p2_release_thread():
 
 
 def p2_set_profiling(on):
-    _check(lib().p2_set_profiling(1 if on else 0))
+    """False / True, or 2: of the frontier engine's launches time only classification and children."""
+    _check(lib().p2_set_profiling(2 if on == 2 and on is not True else 1 if on else 0))
 
 
 def p2_get_profile():

@@ -76,11 +76,14 @@ struct SpanRec {
     enum Kind { kClassify = 0, kLiteral = 1, kMaterialize = 2, kGroup = 3, kKinds = 4 };
     struct Span { int kind; size_t first; int dispatches; };
     bool on = false;
+    bool kernels_only = false;         // only the classification and the building of children are timed
+    bool open = false;                 // the span begun last is being recorded
     std::vector<hipEvent_t> pool;
     std::vector<Span> spans;
     size_t used = 0;
     hipError_t begin(int kind, hipStream_t stream, int dispatches = 1) {
-        if (!on) return hipSuccess;
+        open = on && !(kernels_only && kind != kClassify && kind != kMaterialize);
+        if (!open) return hipSuccess;
         while (pool.size() < used + 2) {
             hipEvent_t e = nullptr;
             const hipError_t rc = hipEventCreate(&e);
@@ -91,7 +94,7 @@ struct SpanRec {
         used += 2;
         return hipEventRecord(pool[used - 2], stream);
     }
-    hipError_t end(hipStream_t stream) { return on ? hipEventRecord(pool[used - 1], stream) : hipSuccess; }
+    hipError_t end(hipStream_t stream) { return open ? hipEventRecord(pool[used - 1], stream) : hipSuccess; }
     void reset() { spans.clear(); used = 0; }
     // after the stream has been waited for: time and launches per kind, added to what is there
     hipError_t collect(float ms[kKinds], int32_t launches[kKinds]) {
@@ -184,6 +187,7 @@ struct Prof {
     ~Prof();
     void release();
     bool on = false;
+    bool kernels_only = false;      // p2_set_profiling(2): of the frontier engine's launches, only classification and children
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};     // evaluation begin / end, post end, frontier begin / end
     p2_profile last = {};
 };
@@ -1048,14 +1052,12 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             P2_HIP(S.f_sums2[nxt].ensure(std::max<size_t>((size_t)n_prefix2 * sum_doubles, 1) * 8));
             P2_HIP(S.f_sid2[nxt].ensure(std::max<size_t>(n_prefix2, 1) * sizeof(uint32_t)));
             P2_HIP(S.f_literal[nxt].ensure(std::max<size_t>(n_plit, 1) * sizeof(FrontEntry)));
-            // ... and states: a child per (judged state, valid instruction), its hash (added up from zero), what the step
+            // ... and states: a child per (judged state, valid instruction), its hash, what the step
             // adds to the cost sums; where a state's children are
             P2_HIP(S.f_states[nxt].ensure(std::max<size_t>(t1, 1) * sw * 4));
             P2_HIP(S.f_states2[nxt].ensure(std::max<size_t>(t2, 1) * sw * 8));
             P2_HIP(S.f_hash[nxt].ensure(std::max<size_t>(t1, 1) * sizeof(unsigned long long)));
             P2_HIP(S.f_hash2[nxt].ensure(std::max<size_t>(t2, 1) * sizeof(unsigned long long)));
-            if (t1 > 0) P2_HIP(hipMemsetAsync(S.f_hash[nxt].p, 0, (size_t)t1 * sizeof(unsigned long long), S.stream));
-            if (t2 > 0) P2_HIP(hipMemsetAsync(S.f_hash2[nxt].p, 0, (size_t)t2 * sizeof(unsigned long long), S.stream));
             P2_HIP(S.f_delta[0].ensure(std::max<size_t>((size_t)t1 * sum_doubles, 1) * 8));
             P2_HIP(S.f_delta[1].ensure(std::max<size_t>((size_t)t2 * sum_doubles, 1) * 8));
             P2_HIP(S.f_delta[2].ensure(std::max<size_t>((size_t)tg * sum_doubles, 1) * 8));
@@ -1183,7 +1185,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             FrontSlot& S = C.slots[t];
             P2_HIP(S.open());
             P2_HIP(hipStreamWaitEvent(S.stream, C.front_go, 0));
-            S.spans.on = g_prof.on; S.spans.reset();
+            S.spans.on = g_prof.on; S.spans.kernels_only = g_prof.kernels_only; S.spans.reset();
             S.rc = P2_OK; S.err.clear();
         }
         // the long chains first: large reduction groups, large alphabets
@@ -1545,6 +1547,7 @@ int32_t p2_set_profiling(int32_t on) {
     if (on && !g_prof.ev[0])
         for (auto& e : g_prof.ev) P2_HIP(hipEventCreate(&e));
     g_prof.on = on != 0;
+    g_prof.kernels_only = on == 2;
     return P2_OK;
 }
 int32_t p2_get_profile(p2_profile* out) {

@@ -1121,6 +1121,7 @@ __global__ __launch_bounds__(NT) void k_front_materialize(const DevQuery* __rest
     extern __shared__ uint4 ldsq[];                      // A.lds_planes planes of [R][WQ] quads
     __shared__ PatLds spat[kMaxPatterns];
     __shared__ uint32_t s_count[P2_MAX_DEVICES / 2];     // rows that set a group's bytes
+    __shared__ unsigned long long s_hash[NT / 64];       // the wavefronts' shares of the child's hash
     using L = FL<KW, MW>;
     const DevQuery& q = queries[A.query];
     const int R = q.R;
@@ -1294,7 +1295,13 @@ __global__ __launch_bounds__(NT) void k_front_materialize(const DevQuery* __rest
                 h += other;
                 hl = (uint32_t)h; hh = (uint32_t)(h >> 32);
             }
-            if (lane == 0) atomicAdd((cnp == 2 ? A.next_hash2 : A.next_hash1) + place, h);
+            if (lane == 0) s_hash[wave] = h;
+        }
+        __syncthreads();
+        if (code != CODE_GOAL && tid == 0) {             // (written, not added up: the list needs no clearing)
+            unsigned long long h = 0;
+            for (int w = 0; w < NT / 64; ++w) h += s_hash[w];
+            (cnp == 2 ? A.next_hash2 : A.next_hash1)[place] = h;
         }
         // ---- the step's time for every query of the enumeration (alpha-beta model: latency steps of the
         //      slowest group's link; bytes through the busiest uplink, from the query's bandwidth rows)
