@@ -909,6 +909,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
         }
         void* gs = nullptr;
         const int handover = fp == P2_FRONTIER_PAIRS_TWO_HANDOVER ? 1 : 0;
+        bool ctr_clean = true;                       // (all of the counters were cleared above)
         for (int len = 0; len < pl.max_len && (n_c > 0 || n_c2 > 0 || n_l > 0); ++len) {
             const int keep = len + 1 < pl.max_len ? 1 : 0;
             size_t cap_c = std::max<size_t>(1024, ((size_t)n_c + n_c2) * pl.alphabet / 8);
@@ -940,7 +941,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(hipEventRecord(S.side_done, S.side_stream));
                 return P2_OK;
             };
-            P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
+            // (the kernel that built the last level's children has cleared the counters of a level's first half; the
+            //  kernel that brings them to the host clears those of its second half)
+            if (!ctr_clean) P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
+            ctr_clean = false;
             { const int32_t rc = literal_on_side(); if (rc != P2_OK) return rc; }
             // At the last level only goals count: a filter first leaves the classification the few states from which an
             // instruction can still end at the goal.
@@ -995,7 +999,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 // (how many children the judged states have, by kind, the classification has counted)
                 if (n_c + n_c2 > 0) P2_HIP(S.spans.end(S.stream));
                 if (n_l > 0) P2_HIP(hipStreamWaitEvent(S.stream, S.side_done, 0));
-                P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
+                P2_HIP(launch_front_counters_out(static_cast<FrontCounters*>(S.h_fctr.p), dctr, S.stream));
                 P2_HIP(hipStreamSynchronize(S.stream));
                 if (attempt == 0) {                  // (a repeat clears the level's counters)
                     walked_planes = hctr->n_walked_planes;
@@ -1014,7 +1018,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                                          static_cast<FrontSurvivor*>(S.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
                                                          pl.max_row_classes, S.stream));
                     P2_HIP(S.spans.end(S.stream));
-                    P2_HIP(launch_copy_out(S.h_fctr.p, dctr, sizeof(FrontCounters), S.stream));
+                    P2_HIP(launch_front_counters_out(static_cast<FrontCounters*>(S.h_fctr.p), dctr, S.stream));
                     P2_HIP(hipStreamSynchronize(S.stream));
                 }
                 if ((uint32_t)hctr->surv_goal <= cap_c && hctr->n_surv_literal <= cap_l) break;
@@ -1080,6 +1084,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             lv.states1 = static_cast<const uint32_t*>(S.f_states[cur].p); lv.states2 = static_cast<const uint32_t*>(S.f_states2[cur].p);
             lv.surv = static_cast<const FrontSurvivor*>(S.f_ssurv.p); lv.n_surv = n_ss;
             lv.lds_planes = (n_s[1] > 0 || t2 > 0) ? 2 : 1;
+            lv.n_reps = &dctr->n_reps[0];
+            lv.ctr = dctr;
+            ctr_clean = n_ss > 0;                    // (the kernel is launched only if there are children)
             lv.next_states1 = static_cast<uint32_t*>(S.f_states[nxt].p); lv.next_states2 = static_cast<uint32_t*>(S.f_states2[nxt].p);
             lv.next_hash1 = static_cast<unsigned long long*>(S.f_hash[nxt].p); lv.next_hash2 = static_cast<unsigned long long*>(S.f_hash2[nxt].p);
             lv.delta1 = static_cast<double*>(S.f_delta[0].p); lv.delta2 = static_cast<double*>(S.f_delta[1].p);
@@ -1098,7 +1105,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             const DevBuf* next_hash[2] = {&S.f_hash[nxt], &S.f_hash2[nxt]};
             bool grouped_next[2] = {false, false};
             for (int li = 0; li < 2; ++li) grouped_next[li] = n_next[li] >= kGroupMin && n_next[li] < (1u << 24);
-            if (grouped_next[0] || grouped_next[1]) P2_HIP(hipMemsetAsync(&dctr->n_reps[0], 0, sizeof(uint32_t) * 2, S.stream));
             for (int li = 0; li < 2; ++li) {
                 const uint32_t n = n_next[li];
                 if (!grouped_next[li]) continue;

@@ -281,6 +281,10 @@ struct FrontLevel {
     const FrontSurvivor* surv; uint32_t n_surv;            // (state, instruction) pairs: entry = state, slot = the child's
                                                            // place in the next state list of its kind / among the goals
     int32_t lds_planes;            // 2 if a parent or a child of this level has two pairs, else 1
+    FrontCounters* ctr;            // the level's counters: those of its first half (which the host has read) are cleared
+                                   // by the kernel for the next level; null: left alone
+    uint32_t* n_reps;              // [2] cleared by the kernel (the counts of distinct children, which the search that
+                                   // follows adds up); null: left alone
     uint32_t* next_states1; uint32_t* next_states2;
     unsigned long long* next_hash1; unsigned long long* next_hash2;      // hash of every child's state (zero on entry)
     double* delta1; double* delta2; double* delta_goal;   // [child][n_share][2]: what the step adds to the cost sums
@@ -371,6 +375,8 @@ hipError_t launch_front_emit(const DevQuery* q, uint32_t query, const FrontEntry
                              uint32_t n_surv, int parent_len, int keep_prefixes, FrontEntry* next_literal,
                              unsigned long long* valid_out, double* goal_sums, int n_share, FrontCounters* ctr,
                              hipStream_t stream);
+// The counters to pinned host memory; clears those that the second half of a level counts with.
+hipError_t launch_front_counters_out(FrontCounters* host_dst, FrontCounters* ctr, hipStream_t stream);
 hipError_t launch_front_rank(const unsigned long long* valid, uint32_t n, uint32_t* rank, hipStream_t stream);
 // The rows of n_jobs queries in one launch (jobs in device memory; max_valid = the largest n_valid among them).
 hipError_t launch_front_finish(const DevQuery* queries, const FrontFinish* jobs, uint32_t n_jobs, uint32_t max_valid, hipStream_t stream);

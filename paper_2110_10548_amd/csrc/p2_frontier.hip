@@ -1134,6 +1134,16 @@ __global__ __launch_bounds__(NT) void k_front_materialize(const DevQuery* __rest
         p.g = q.pat[i].g; p.s = q.pat[i].s; p.master = q.pat[i].master; p.n_groups = q.pat[i].n_groups;
         spat[i] = p;
     }
+    // (the search for equal states among the children, which follows this kernel, counts the distinct ones from zero;
+    //  nothing reads the counts of the level's own lists any more)
+    if (A.n_reps && blockIdx.x == 0 && tid < 2) A.n_reps[tid] = 0u;
+    // (likewise the counters of the level's first half, which the host has read by now: the next level counts from zero)
+    if (A.ctr && blockIdx.x == 0 && tid == 0) {
+        FrontCounters* const c = A.ctr;
+        c->surv_goal = 0ull; c->pref_pref2 = 0ull; c->n_surv_literal = 0u; c->n_goal = 0u; c->n_prefix_literal = 0u;
+        c->n_overflow = 0u; c->n_unknown = 0u; c->t_count[0] = 0u; c->t_count[1] = 0u; c->t_count[2] = 0u;
+        c->n_walked_planes = 0u; c->n_walk[0] = 0u; c->n_walk[1] = 0u;
+    }
     __syncthreads();
     for (uint32_t i = blockIdx.x; i < A.n_surv; i += gridDim.x) {
         const FrontSurvivor sv = A.surv[i];
@@ -1575,6 +1585,21 @@ __global__ __launch_bounds__(256) void k_front_finish(const DevQuery* __restrict
     }
 }
 
+// The level's counters to the host (dst: pinned host memory the device can write), before the host's one wait of the
+// level; the counters that only the second half of the level uses (places handed out while the children and the next
+// lists are written) start from zero there, so they are cleared here rather than by a fill of their own.
+__global__ __launch_bounds__(64) void k_front_counters_out(FrontCounters* __restrict__ dst, FrontCounters* __restrict__ ctr) {
+    static_assert(sizeof(FrontCounters) % 4 == 0, "copied word by word");
+    const uint32_t* const src = reinterpret_cast<const uint32_t*>(ctr);
+    uint32_t* const out = reinterpret_cast<uint32_t*>(dst);
+    for (uint32_t i = threadIdx.x; i < sizeof(FrontCounters) / 4; i += 64u) out[i] = src[i];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ctr->next_literal = 0u; ctr->next_goal_literal = 0u; ctr->n_ssurv = 0u;
+        ctr->t_next[0] = 0u; ctr->t_next[1] = 0u; ctr->t_next[2] = 0u;
+    }
+}
+
 // rank[i] = number of entries of the list smaller than entry i (distinct keys).
 __global__ __launch_bounds__(256) void k_front_rank(const unsigned long long* __restrict__ in, uint32_t n, uint32_t* __restrict__ rank) {
     __shared__ unsigned long long tile[256];
@@ -1765,6 +1790,11 @@ hipError_t launch_front_expand(const DevQuery* q, const FrontEntry* entries, uin
     else
         hipLaunchKernelGGL(k_front_expand<1>, dim3(blocks), dim3(kExpThreads), 0, stream, q, entries, n, rep, codes, rc, unknown, handover, epw, surv,
                            surv_cap, unknown_out, ctr);
+    return hipGetLastError();
+}
+
+hipError_t launch_front_counters_out(FrontCounters* host_dst, FrontCounters* ctr, hipStream_t stream) {
+    hipLaunchKernelGGL(k_front_counters_out, dim3(1), dim3(64), 0, stream, host_dst, ctr);
     return hipGetLastError();
 }
 
