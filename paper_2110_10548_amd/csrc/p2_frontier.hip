@@ -886,7 +886,8 @@ __global__ __launch_bounds__(256) void k_front_goal_filter(const DevQuery* __res
             if (__any(rows_short) && __any(cols_short) && __any(root_short)) break;
         }
         if (__any(rows_short) && __any(cols_short) && __any(root_short)) {
-            for (int a = lane; a < I; a += 64) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
+            uint32_t* const words = reinterpret_cast<uint32_t*>(codes + (size_t)e * front_code_stride(I));
+            for (int w = lane; w * 4 < I; w += 64) words[w] = 0u;          // (CODE_INVALID is zero)
             if (lane == 0) { unknown[e] = 0; row_counts[e] = make_uint2(0u, 0u); }
         } else if (lane == 0) {
             walk[atomicAdd(n_walk, 1u)] = e;
@@ -909,6 +910,7 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
     __shared__ uint32_t s_pflags[kMaxPatterns];
     __shared__ int s_pgoal[kMaxPatterns], s_ptwo[kMaxPatterns];
     __shared__ ClsItem s_items[kMaxPatterns * kClsChunks];
+    __shared__ __align__(16) uint8_t s_codes[512];        // the row of codes of the state at hand (an alphabet has at most 512 instructions)
     using L = FL<KW, MW>;
     const DevQuery& q = *qp;
     const int R = q.R, I = q.alphabet, n_ops = q.n_ops, n_pat = q.n_patterns;
@@ -988,7 +990,8 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
         if (goals_only) {
             goal_ops = (s_rows_short == 0 ? 1 : 0) | (s_cols_short == 0 ? 2 : 0) | ((flags[0] & kFlagGoal) ? 4 : 0);
             if (goal_ops == 0) {
-                for (int a = tid; a < I; a += kClsThreads) codes[(size_t)e * front_code_stride(I) + a] = (uint8_t)CODE_INVALID;
+                uint32_t* const words = reinterpret_cast<uint32_t*>(codes + (size_t)e * front_code_stride(I));
+                for (int w = tid; w * 4 < I; w += kClsThreads) words[w] = 0u;      // (CODE_INVALID is zero)
                 if (tid == 0) row_counts[e] = make_uint2(0u, 0u);
                 continue;
             }
@@ -1035,19 +1038,23 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
                 rs_straddles = cls_rs_straddles<KW, MW, NP>(c, P);
             if (lane == 0)
                 cls_codes<KW, MW, NP>(c, P, pid, pf, s_pgoal[pid], s_ptwo[pid], n_goal, n_two, many, bc_pairs, rs_straddles, ops_r, n_ops, max_pairs,
-                                      all_rows, all_cols, goal_ops, codes + (size_t)e * front_code_stride(I), unknown + e);
+                                      all_rows, all_cols, goal_ops, s_codes, unknown + e);
         }
         // ---- how many of the row's codes are survivors, goals, one-pair and two-pair children (16 bits each), for the
         //      kernel that lists the survivors of the prefixes: it then reads the rows of the prefixes that have any
+        //      (the codes were put together in LDS, a byte per instruction from the lane that judged its pattern; they go
+        //      out as whole words, the bytes past the alphabet as invalid)
         __syncthreads();
         if (wave == 0) {
-            const uint32_t* const words = reinterpret_cast<const uint32_t*>(codes + (size_t)e * front_code_stride(I));
+            uint32_t* const words = reinterpret_cast<uint32_t*>(codes + (size_t)e * front_code_stride(I));
             uint32_t k_surv = 0, k_goal = 0, k_p1 = 0, k_p2 = 0;
             for (int w = lane; w * 4 < I; w += 64) {
-                const uint32_t four = words[w];
+                const int left = I - w * 4;
+                const uint32_t four = reinterpret_cast<const uint32_t*>(s_codes)[w] & (left >= 4 ? 0xffffffffu : ((1u << (8 * left)) - 1u));
+                words[w] = four;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int code = (w * 4 + j < I) ? (int)((four >> (8 * j)) & 0xffu) : CODE_INVALID;
+                    const int code = (int)((four >> (8 * j)) & 0xffu);
                     k_surv += code != CODE_INVALID; k_goal += code == CODE_GOAL; k_p1 += code == CODE_PREFIX; k_p2 += code == CODE_PREFIX2;
                 }
             }
