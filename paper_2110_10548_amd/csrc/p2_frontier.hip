@@ -278,12 +278,14 @@ __device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P
         p.init(); sB.init(); al.init(); i0.init(); i1.init();
         uint4 first0 = q_zero(), first1 = q_zero();
         uint32_t fl_or = 0;
-        for (int it0 = 0; it0 < trips; it0 += 4) {       // four members in flight
-            uint4 a0[4], a1[4];
-            uint32_t ff[4];
-            bool on[4];
+        // (members in flight: four, or two where a member is two quads and five accumulators, which leave no registers for more)
+        constexpr int kFlight = 2;
+        for (int it0 = 0; it0 < trips; it0 += kFlight) {
+            uint4 a0[kFlight], a1[kFlight];
+            uint32_t ff[kFlight];
+            bool on[kFlight];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kFlight; ++u) {
                 const int t = (it0 + u) * spg + part;
                 on[u] = act && t < g;
                 const int d = base + t * s;
@@ -292,7 +294,7 @@ __device__ inline ClsFound cls_walk(const ClsLane<KW, MW, NP>& c, const PatLds P
                 ff[u] = on[u] ? (uint32_t)c.flags[d] : 0u;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kFlight; ++u) {
                 const uint4 v0 = a0[u];
                 const uint32_t f = ff[u];
                 fl_or |= f;
