@@ -23,7 +23,9 @@ been judged on its own); the same words are read from LDS once per pattern (`roo
 256 bytes per clock and compute unit) and the state comes from device memory once (`roofline.hbm`).
 `materialize` prices the kernel that builds the children of the judged states against HBM.  Times
 are HIP-event times around every launch of the family on the stream it is launched on, taken inside
-the timed steps (p2_get_profile).  The library runs up to four enumerations of a batch side by
+the timed steps (p2_get_profile; the timed steps bracket these two families only, p2_set_profiling(2):
+event pairs around every group of the engine's small launches as well cost 7 % of a call, and are
+taken in the one-at-a-time leg, whose device_ms_per_step has the full breakdown).  The library runs up to four enumerations of a batch side by
 side, so those are times of kernels that share the chip, and an event pair on one stream also sees
 the time its kernel waits for a turn behind the other streams' kernels, which a profiler's kernel
 duration does not; `one_enumeration_at_a_time` gives the same objects for a few steps with the
