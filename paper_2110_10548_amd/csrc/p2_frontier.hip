@@ -925,23 +925,41 @@ __global__ __launch_bounds__(kClsThreads, NP == 1 ? 4 : 2) void k_front_classify
         spat[i] = p;
     }
     __syncthreads();
-    if (tid == 0) {
-        // work items: a pattern's batches of groups in up to kClsChunks runs; the long items first
-        int n = 0;
-        for (int pass = 0; pass < 2; ++pass)
-            for (int i = 0; i < n_pat; ++i) {
-                const int ng = spat[i].n_groups;
-                int spg = 1;
-                while (spg * 2 * ng <= 8) spg *= 2;
-                const int batches = (ng + 8 / spg - 1) / (8 / spg);
-                const int per = batches >= 2 * kClsChunks ? (batches + kClsChunks - 1) / kClsChunks : batches >= 4 ? 2 : batches;
-                if ((pass == 0) != (per == batches)) continue;       // (whole patterns are the long items)
-                for (int b = 0; b < batches; b += per) {
-                    ClsItem w; w.pid = (uint16_t)i; w.first_batch = (uint16_t)b; w.n_batches = (uint16_t)min(per, batches - b);
-                    s_items[n++] = w;
-                }
+    // work items: a pattern's batches of groups in up to kClsChunks runs; the long items (whole patterns) first, then
+    // the other patterns' runs, pattern after pattern.  A thread per pattern works out its runs and where they go (a
+    // block judges a state or two, so what it sets up first is not paid once and forgotten).
+    {
+        int* const s_runs = s_pgoal;                     // (not in use yet) runs of pattern i, negated for a whole pattern
+        for (int i = tid; i < n_pat; i += kClsThreads) {
+            const int ng = spat[i].n_groups;
+            int spg = 1;
+            while (spg * 2 * ng <= 8) spg *= 2;
+            const int batches = (ng + 8 / spg - 1) / (8 / spg);
+            const int per = batches >= 2 * kClsChunks ? (batches + kClsChunks - 1) / kClsChunks : batches >= 4 ? 2 : batches;
+            s_runs[i] = per == batches ? -1 : (batches + per - 1) / per;
+        }
+        __syncthreads();
+        for (int i = tid; i < n_pat; i += kClsThreads) {
+            const int ng = spat[i].n_groups;
+            int spg = 1;
+            while (spg * 2 * ng <= 8) spg *= 2;
+            const int batches = (ng + 8 / spg - 1) / (8 / spg);
+            const int per = batches >= 2 * kClsChunks ? (batches + kClsChunks - 1) / kClsChunks : batches >= 4 ? 2 : batches;
+            const bool whole = s_runs[i] < 0;
+            int at = 0, n_whole = 0, total = 0;
+            for (int j = 0; j < n_pat; ++j) {
+                const int rj = s_runs[j];
+                n_whole += rj < 0 ? 1 : 0;
+                total += rj < 0 ? 1 : rj;
+                if (j < i && (rj < 0) == whole) at += rj < 0 ? 1 : rj;
             }
-        s_n_items = n;
+            if (!whole) at += n_whole;
+            for (int b = 0; b < batches; b += per) {
+                ClsItem w; w.pid = (uint16_t)i; w.first_batch = (uint16_t)b; w.n_batches = (uint16_t)min(per, batches - b);
+                s_items[at++] = w;
+            }
+            if (i == 0) s_n_items = total;
+        }
     }
     const Words<KW> all_rows = full_mask<KW>(q.k);
     const Words<MW> all_cols = full_mask<MW>(R);
