@@ -30,12 +30,15 @@
 //                    mask among the members' pairs.  More than two: the child is a "literal"
 //                    prefix (it keeps only its instructions; p2_literal.hip takes it from there).
 //   Broadcast      : compared pair against pair (a row's mask is its pair's mask).
-// One level, in launch order (the host waits once, after `children (count)`, and sizes the next
-// level's buffers exactly from the counts, so nothing overflows):
+// One level, in launch order (the host waits once, after `expand`, and sizes the next level's
+// buffers exactly from the counts, so nothing overflows):
+//   goal filter      : the last level only, where nothing but goals counts: the states from which no
+//                      instruction can end at the goal get a row of invalid codes, the others are listed.
 //   classify         : block = one distinct state, its planes in LDS, wavefronts over patterns,
-//                      lanes = (device slot, 16-byte quad); writes a code per instruction.
-//   expand           : for every prefix, the survivors among its extensions (from its state's codes)
-//                      with their places in the next prefix lists / among the goals.
+//                      lanes = (device slot, 16-byte quad); writes a code per instruction, how many of
+//                      them are survivors by kind, and adds up the children of the states it judged.
+//   expand           : for every prefix, the survivors among its extensions (from its state's counts
+//                      and codes) with their places in the next prefix lists / among the goals.
 //   children         : for every (state, valid instruction), the child's place in the next state lists.
 //   materialize      : block = one child: parent planes into LDS, the instruction applied in place,
 //                      the child streamed out with its hash; what the step adds to every query's sums.
