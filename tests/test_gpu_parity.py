@@ -924,6 +924,37 @@ def test_enumerations_side_by_side_or_one_after_the_other(B, oracle):
         assert_same(a, ora, len(msg))
 
 
+def test_profiling_levels_of_the_frontier_engine(B):
+    """p2_set_profiling(1) brackets every group of the frontier engine's launches with an event pair,
+    p2_set_profiling(2) only its classification and the building of children; the results do not depend
+    on either, and what the states-judged figures count is the same."""
+    cfg, queries = queries_of(3, B)
+    msg = cfg["msg_bytes"]
+    mine = [dict(q, engine=3) for q in queries if _levels(q) == 3][:4]
+    try:
+        B.p2_set_profiling(False)
+        plain = B.p2_synthesize_batch(mine, msg)
+        B.p2_set_profiling(True)
+        full = B.p2_synthesize_batch(mine, msg)
+        p_full = B.p2_get_profile()
+        B.p2_set_profiling(2)
+        light = B.p2_synthesize_batch(mine, msg)
+        p_light = B.p2_get_profile()
+    finally:
+        B.p2_set_profiling(False)
+    for a, b, c in zip(plain, full, light):
+        assert a["programs"]["index"].tolist() == b["programs"]["index"].tolist() == c["programs"]["index"].tolist()
+        assert (a["cost"] == b["cost"]).all() and (a["cost"] == c["cost"]).all()
+    assert p_full["front_classify_ms"] > 0 and p_full["front_materialize_ms"] > 0 and p_full["front_group_ms"] > 0
+    assert p_light["front_classify_ms"] > 0 and p_light["front_materialize_ms"] > 0
+    assert p_light["front_group_ms"] == 0 and p_light["front_literal_ms"] == 0
+    for key in ("front_classify_launches", "front_materialize_launches", "front_prefixes", "front_entries", "front_classify_lane_ops"):
+        assert p_full[key] == p_light[key] and p_full[key] > 0
+    # at the size limit only the states from which an instruction can still end at the goal are walked:
+    # fewer lane-operations than every judged state's planes times the alphabet's members would give
+    assert p_full["front_classify_state_bytes"] > 0
+
+
 def test_frontier_matches_flat_engine_on_config3_sample(B):
     cfg, queries = queries_of(3, B)
     mine = [q for q in queries if _levels(q) == 3][:4] + [q for q in queries if _levels(q) == 2][:4]
