@@ -1372,7 +1372,18 @@ __global__ __launch_bounds__(NT) void k_front_materialize(const DevQuery* __rest
                 double best = 0.0;
                 for (int row = rw.pat_begin[pid] + lane; row < rw.pat_begin[pid + 1]; row += 64) {
                     long long dot = 0;
-                    for (int e = rw.row_ptr[row]; e < rw.row_ptr[row + 1]; ++e) {
+                    int e = rw.row_ptr[row];
+                    const int e_end = rw.row_ptr[row + 1];
+                    // (eight entries in flight: a row of the outer levels has an entry per group, and one load after the
+                    //  other made this loop the longest part of the kernel)
+                    for (; e + 8 <= e_end; e += 8) {
+                        uint32_t ent[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) ent[u] = rw.entries[e + u];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) dot += (long long)entry_cnt(ent[u]) * (long long)s_count[entry_group(ent[u])];
+                    }
+                    for (; e < e_end; ++e) {
                         const uint32_t ent = rw.entries[e];
                         dot += (long long)entry_cnt(ent) * (long long)s_count[entry_group(ent)];
                     }
