@@ -129,7 +129,7 @@ inline int group_base(const Pattern& p, int group) {       // local id of the gr
 
 void build_cost_rows(const Plan& pl, Pattern& p) {
     // scratch kept between calls: this runs for every pattern of every query of every call
-    thread_local std::vector<int32_t> stamp, cnt, touched, row_begin, group_of, key_of;
+    thread_local std::vector<int32_t> stamp, cnt, touched, row_begin, group_of, key_of, table, by_group_at, by_group, fill_at;
     thread_local std::vector<uint32_t> flat;
     thread_local std::vector<char> dead;
     p.row_ptr.assign(1, 0);
@@ -155,6 +155,10 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
         // rows of this level, one after the other in `flat`; row r is flat[row_begin[r] .. row_begin[r + 1])
         flat.clear();
         row_begin.assign(1, 0);
+        size_t table_size = 16;                          // open addressing: row indices, -1 = free; at most half full
+        while (table_size < 2 * (size_t)(pl.D / below)) table_size *= 2;
+        table.assign(table_size, -1);
+        const size_t table_mask = table_size - 1;
         for (int u = 0; u < pl.D / below; ++u) {
             ++stamp_id;
             touched.clear();
@@ -170,22 +174,40 @@ void build_cost_rows(const Plan& pl, Pattern& p) {
             std::sort(touched.begin(), touched.end());
             const size_t first = flat.size();
             for (int lg : touched) { flat.push_back(entry_pack((uint32_t)lg, (uint32_t)group_base(p, lg), (uint32_t)cnt[lg])); cnt[lg] = 0; }
-            // units with equal descriptions are one row
+            // units with equal descriptions are one row: looked up by a hash of the description (the innermost level
+            // has a unit per device, and comparing each with every row before it was most of this function's time)
             const size_t len = flat.size() - first;
+            uint64_t hsh = 0x9e3779b97f4a7c15ull ^ len;
+            for (size_t x = first; x < flat.size(); ++x) { hsh ^= flat[x]; hsh *= 0x100000001b3ull; hsh ^= hsh >> 29; }
             bool dup = false;
-            for (size_t r = 0; r + 1 < row_begin.size() && !dup; ++r)
-                dup = (size_t)(row_begin[r + 1] - row_begin[r]) == len &&
-                      std::equal(flat.begin() + first, flat.end(), flat.begin() + row_begin[r]);
+            size_t slot = (size_t)hsh & table_mask;
+            for (;; slot = (slot + 1) & table_mask) {
+                const int32_t r = table[slot];
+                if (r < 0) break;
+                if ((size_t)(row_begin[r + 1] - row_begin[r]) == len &&
+                    std::equal(flat.begin() + first, flat.end(), flat.begin() + row_begin[r])) { dup = true; break; }
+            }
             if (dup) flat.resize(first);
-            else row_begin.push_back((int32_t)flat.size());
+            else { table[slot] = (int32_t)row_begin.size() - 1; row_begin.push_back((int32_t)flat.size()); }
         }
         // drop rows dominated by another row of the same level
         const size_t n_rows = row_begin.size() - 1;
         dead.assign(n_rows, 0);
+        // (a row that dominates row a holds every group of a, its first among them: the rows are listed by group, in
+        //  ascending order, and only those of a's first group are asked)
+        by_group_at.assign((size_t)p.n_groups + 1, 0);
+        for (size_t x = 0; x < flat.size(); ++x) ++by_group_at[entry_group(flat[x]) + 1];
+        for (int g2 = 0; g2 < p.n_groups; ++g2) by_group_at[g2 + 1] += by_group_at[g2];
+        by_group.resize(flat.size());
+        fill_at.assign(by_group_at.begin(), by_group_at.end() - 1);
+        for (size_t r = 0; r < n_rows; ++r)
+            for (int x = row_begin[r]; x < row_begin[r + 1]; ++x) by_group[fill_at[entry_group(flat[x])]++] = (int32_t)r;
         for (size_t a = 0; a < n_rows; ++a) {
             const uint32_t* ra = flat.data() + row_begin[a];
             const size_t na = (size_t)(row_begin[a + 1] - row_begin[a]);
-            for (size_t b = 0; b < n_rows && !dead[a]; ++b) {
+            const uint32_t g0 = entry_group(ra[0]);
+            for (int32_t at = by_group_at[g0]; at < by_group_at[g0 + 1] && !dead[a]; ++at) {
+                const size_t b = (size_t)by_group[at];
                 const uint32_t* rb = flat.data() + row_begin[b];
                 const size_t nb = (size_t)(row_begin[b + 1] - row_begin[b]);
                 if (a == b || dead[b] || nb < na) continue;
