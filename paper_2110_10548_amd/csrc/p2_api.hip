@@ -120,8 +120,7 @@ struct SpanRec {
 // the chip where one does not.
 constexpr int kFrontSlots = 4;
 struct FrontSlot {
-    hipStream_t stream = nullptr, side_stream = nullptr;
-    hipEvent_t side_go = nullptr, side_done = nullptr;
+    hipStream_t stream = nullptr;         // (created by Ctx::open_slot_streams, together with those of the other slots)
     DevBuf f_entries[2], f_states[2], f_sums[2], f_entries2[2], f_states2[2], f_sums2[2], f_literal[2];
     DevBuf f_surv, f_surv_literal, f_unknown, f_ctr, lit_scratch;
     DevBuf f_hash[2], f_hash2[2], f_table, f_rep[2], f_replist[2], f_codes[2], f_unk[2];     // search for equal states
@@ -134,14 +133,6 @@ struct FrontSlot {
     double prof_prefixes = 0.0, prof_state_bytes = 0.0, prof_lane_ops = 0.0, prof_children = 0.0, prof_mat_bytes = 0.0, prof_entries = 0.0;
     int32_t rc = 0;
     std::string err;
-    hipError_t open() {
-        if (stream) return hipSuccess;
-        hipError_t e = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipStreamCreateWithFlags(&side_stream, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&side_go, hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&side_done, hipEventDisableTiming);
-        return e;
-    }
     void release() {
         DevBuf* dev[] = {&f_entries[0], &f_entries[1], &f_states[0], &f_states[1], &f_sums[0], &f_sums[1], &f_entries2[0], &f_entries2[1],
                          &f_states2[0], &f_states2[1], &f_sums2[0], &f_sums2[1], &f_literal[0], &f_literal[1], &f_surv, &f_surv_literal,
@@ -152,9 +143,6 @@ struct FrontSlot {
         if (h_fctr.p) (void)hipHostFree(h_fctr.p);
         h_fctr.p = nullptr; h_fctr.cap = 0;
         spans.release();
-        if (side_go) { (void)hipEventDestroy(side_go); side_go = nullptr; }
-        if (side_done) { (void)hipEventDestroy(side_done); side_done = nullptr; }
-        if (side_stream) { (void)hipStreamDestroy(side_stream); side_stream = nullptr; }
         if (stream) { (void)hipStreamDestroy(stream); stream = nullptr; }
     }
 };
@@ -172,6 +160,8 @@ struct Ctx {
     DevBuf f_rank, f_share;                                 // frontier engine: ranks of the valid programs, queries of the enumerations
     std::vector<DevBuf> f_evalid, f_egsums;                 // ... per enumeration: valid candidate indices, their cost sums
     FrontSlot slots[kFrontSlots];
+    hipStream_t spare_streams[2] = {nullptr, nullptr};      // created to steer the dealing of queues, never used
+    hipError_t open_slot_streams();
     hipEvent_t front_go = nullptr;                          // the call's stream has reached the enumerations
     HostBuf h_rows, h_rows_hdr;
     hipStream_t copy_stream = nullptr;      // uploads that overlap with the kernels of the call's stream
@@ -179,6 +169,29 @@ struct Ctx {
     HostBuf h_blob, h_counters, h_progs, h_costs, h_pos, h_post, h_topk_jobs, h_fshare;
 };
 thread_local Ctx g_ctx;
+
+// The streams of all slots, created together and in a fixed order.  The runtime deals a process's streams out to its
+// hardware queues (four unless the caller's environment says otherwise) as they are created, and streams that share
+// a queue take turns.  Measured with pairs of one-block kernels on freshly created streams: after the null stream
+// (queue A) and one more stream (B: the copy stream above, created at the start of the first batch call) the next six
+// land on C D D C B A.  The slots take the 1st, 2nd, 5th and 6th, a queue each, and the two in between stay unused.
+// Only the overlap depends on this, never a result: with other streams created before these, or another number of
+// queues, the slots work all the same and merely share queues differently.
+hipError_t Ctx::open_slot_streams() {
+    static_assert(kFrontSlots == 4, "the order below is written for four slots");
+    if (slots[0].stream) return hipSuccess;
+    hipStream_t made[6] = {};
+    for (int i = 0; i < 6; ++i) {
+        const hipError_t e = hipStreamCreateWithFlags(&made[i], hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipStreamDestroy(made[j]);
+            return e;
+        }
+    }
+    slots[0].stream = made[0]; slots[1].stream = made[1]; slots[2].stream = made[4]; slots[3].stream = made[5];
+    spare_streams[0] = made[2]; spare_streams[1] = made[3];
+    return hipSuccess;
+}
 
 // Frontier lists shorter than this are judged entry by entry: grouping them by state would cost more than it saves.
 constexpr uint32_t kGroupMin = 256;
@@ -207,6 +220,7 @@ void Ctx::release() {
         v->clear();
     }
     for (FrontSlot& sl : slots) sl.release();
+    for (hipStream_t& sp : spare_streams) { if (sp) (void)hipStreamDestroy(sp); sp = nullptr; }
     HostBuf* host[] = {&h_rows, &h_rows_hdr, &h_blob, &h_counters, &h_progs, &h_costs, &h_pos, &h_post, &h_topk_jobs, &h_fshare, &h_gather, &h_finish};
     for (HostBuf* b : host) { if (b->p) (void)hipHostFree(b->p); b->p = nullptr; b->cap = 0; }
     if (front_go) { (void)hipEventDestroy(front_go); front_go = nullptr; }
@@ -924,28 +938,25 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                 P2_HIP(S.f_unk[li].ensure(n_s[li]));
                 P2_HIP(S.f_rowcnt[li].ensure((size_t)n_s[li] * sizeof(unsigned long long)));
             }
-            // The literal prefixes of the level are judged on a second S.stream while the pair states are (their kernels are
-            // a wavefront per prefix and leave most of the chip idle); the two meet before the counters go to the host.
-            auto literal_on_side = [&]() -> int32_t {
+            // The literal prefixes of the level.  (On a second stream of the slot they would overlap with the pair states'
+            // kernels only if that stream had a hardware queue to itself, which it would take from another slot.)
+            auto literal_prefixes = [&]() -> int32_t {
                 if (n_l == 0) return P2_OK;
                 P2_HIP(S.f_surv_literal.ensure(cap_l * sizeof(FrontSurvivor)));
                 P2_HIP(S.lit_scratch.ensure(front_literal_scratch_bytes(pl.R, pl.k, std::max(n_l, n_c2))));
                 gs = S.lit_scratch.p;
-                P2_HIP(hipEventRecord(S.side_go, S.stream));
-                P2_HIP(hipStreamWaitEvent(S.side_stream, S.side_go, 0));
-                P2_HIP(S.spans.begin(SpanRec::kLiteral, S.side_stream));
+                P2_HIP(S.spans.begin(SpanRec::kLiteral, S.stream));
                 P2_HIP(launch_front_classify_literal(dq, pl.R, pl.k, static_cast<const FrontEntry*>(S.f_literal[cur].p), n_l, len, keep ? 0 : 1,
                                                      static_cast<FrontSurvivor*>(S.f_surv_literal.p), (uint32_t)cap_l, dctr, gs,
-                                                     pl.max_row_classes, S.side_stream));
-                P2_HIP(S.spans.end(S.side_stream));
-                P2_HIP(hipEventRecord(S.side_done, S.side_stream));
+                                                     pl.max_row_classes, S.stream));
+                P2_HIP(S.spans.end(S.stream));
                 return P2_OK;
             };
             // (the kernel that built the last level's children has cleared the counters of a level's first half; the
             //  kernel that brings them to the host clears those of its second half)
             if (!ctr_clean) P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
             ctr_clean = false;
-            { const int32_t rc = literal_on_side(); if (rc != P2_OK) return rc; }
+            { const int32_t rc = literal_prefixes(); if (rc != P2_OK) return rc; }
             // At the last level only goals count: a filter first leaves the classification the few states from which an
             // instruction can still end at the goal.
             const uint32_t* cls_list[2]; const uint32_t* cls_n[2];
@@ -981,7 +992,7 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                     P2_HIP(hipMemsetAsync(dctr, 0, offsetof(FrontCounters, steps), S.stream));
                     // (the classification is not repeated: what it counted goes back in)
                     P2_HIP(hipMemcpyAsync(&dctr->t_count[0], kids, sizeof kids, hipMemcpyHostToDevice, S.stream));
-                    const int32_t rc = literal_on_side();
+                    const int32_t rc = literal_prefixes();
                     if (rc != P2_OK) return rc;
                 }
                 if (n_c + n_c2 > 0) P2_HIP(S.spans.begin(SpanRec::kGroup, S.stream));
@@ -998,7 +1009,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
                                            static_cast<FrontEntry*>(S.f_unknown.p), dctr, S.stream));
                 // (how many children the judged states have, by kind, the classification has counted)
                 if (n_c + n_c2 > 0) P2_HIP(S.spans.end(S.stream));
-                if (n_l > 0) P2_HIP(hipStreamWaitEvent(S.stream, S.side_done, 0));
                 P2_HIP(launch_front_counters_out(static_cast<FrontCounters*>(S.h_fctr.p), dctr, S.stream));
                 P2_HIP(hipStreamSynchronize(S.stream));
                 if (attempt == 0) {                  // (a repeat clears the level's counters)
@@ -1187,9 +1197,9 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             one_at_a_time |= queries[i].opt && (queries[i].opt->flags & P2_FLAG_ONE_ENUMERATION_AT_A_TIME) != 0u;
         const int n_slots = one_at_a_time ? 1 : (int)std::min<size_t>(kFrontSlots, enums.size());
         P2_HIP(hipEventRecord(C.front_go, stream));
+        P2_HIP(C.open_slot_streams());
         for (int t = 0; t < n_slots; ++t) {
             FrontSlot& S = C.slots[t];
-            P2_HIP(S.open());
             P2_HIP(hipStreamWaitEvent(S.stream, C.front_go, 0));
             S.spans.on = g_prof.on; S.spans.kernels_only = g_prof.kernels_only; S.spans.reset();
             S.rc = P2_OK; S.err.clear();
@@ -1214,7 +1224,6 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             }
             // (whatever the slot has queued is waited for, also after a failure: its buffers are reused)
             (void)hipStreamSynchronize(S.stream);
-            (void)hipStreamSynchronize(S.side_stream);
         };
         if (n_slots == 1) {
             work(0, false);
