@@ -160,7 +160,9 @@ struct Ctx {
     DevBuf f_rank, f_share;                                 // frontier engine: ranks of the valid programs, queries of the enumerations
     std::vector<DevBuf> f_evalid, f_egsums;                 // ... per enumeration: valid candidate indices, their cost sums
     FrontSlot slots[kFrontSlots];
-    hipStream_t spare_streams[2] = {nullptr, nullptr};      // created to steer the dealing of queues, never used
+    static constexpr int kSpareStreams = 6;
+    hipStream_t spare_streams[kSpareStreams] = {};          // created beside the slots' streams and found to share a queue with one: never used
+    DevBuf probe_sink;
     hipError_t open_slot_streams();
     hipEvent_t front_go = nullptr;                          // the call's stream has reached the enumerations
     HostBuf h_rows, h_rows_hdr;
@@ -170,26 +172,62 @@ struct Ctx {
 };
 thread_local Ctx g_ctx;
 
-// The streams of all slots, created together and in a fixed order.  The runtime deals a process's streams out to its
-// hardware queues (four unless the caller's environment says otherwise) as they are created, and streams that share
-// a queue take turns.  Measured with pairs of one-block kernels on freshly created streams: after the null stream
-// (queue A) and one more stream (B: the copy stream above, created at the start of the first batch call) the next six
-// land on C D D C B A.  The slots take the 1st, 2nd, 5th and 6th, a queue each, and the two in between stay unused.
-// Only the overlap depends on this, never a result: with other streams created before these, or another number of
-// queues, the slots work all the same and merely share queues differently.
+// The streams of the slots.  The runtime deals a process's streams out to its hardware queues (four unless the
+// caller's environment says otherwise) as they are created, streams that share a queue take turns, and which queue a
+// new stream lands on depends on every stream the process has created before.  So the library looks: it creates a
+// handful of streams, runs a short one-block kernel on pairs of them (side by side: the time of one; taking turns:
+// of two) and gives the slots streams that do not take turns with each other; the other streams stay unused.  With
+// fewer independent queues than slots the remaining slots share.  Only the overlap depends on this, never a result;
+// a pair that is wrongly taken to share (the host thread lost its turn while timing) costs overlap and nothing else.
+__global__ __launch_bounds__(64) void k_queue_probe(uint32_t* sink, int n) {
+    uint32_t x = threadIdx.x + 1u;
+    for (int i = 0; i < n; ++i) x = x * 1664525u + 1013904223u;
+    if (x == 0x9e3779b9u) sink[0] = x;               // (keeps the loop; the sink is the library's own word)
+}
 hipError_t Ctx::open_slot_streams() {
-    static_assert(kFrontSlots == 4, "the order below is written for four slots");
     if (slots[0].stream) return hipSuccess;
-    hipStream_t made[6] = {};
-    for (int i = 0; i < 6; ++i) {
-        const hipError_t e = hipStreamCreateWithFlags(&made[i], hipStreamNonBlocking);
-        if (e != hipSuccess) {
-            for (int j = 0; j < i; ++j) (void)hipStreamDestroy(made[j]);
-            return e;
+    constexpr int kCandidates = kFrontSlots + kSpareStreams;
+    constexpr int kProbeSteps = 8000;                 // some 0.1 ms: several times what a launch and a wait take
+    hipStream_t made[kCandidates] = {};
+    hipError_t e = probe_sink.ensure(256);
+    for (int i = 0; i < kCandidates && e == hipSuccess; ++i) e = hipStreamCreateWithFlags(&made[i], hipStreamNonBlocking);
+    auto timed = [&](hipStream_t a, hipStream_t b, double& ms) -> hipError_t {
+        const auto t0 = std::chrono::steady_clock::now();
+        hipLaunchKernelGGL(k_queue_probe, dim3(1), dim3(64), 0, a, static_cast<uint32_t*>(probe_sink.p), kProbeSteps);
+        if (b) hipLaunchKernelGGL(k_queue_probe, dim3(1), dim3(64), 0, b, static_cast<uint32_t*>(probe_sink.p), kProbeSteps);
+        hipError_t r = hipGetLastError();
+        const hipError_t ra = hipStreamSynchronize(a);
+        const hipError_t rb = b ? hipStreamSynchronize(b) : hipSuccess;
+        ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        return r != hipSuccess ? r : ra != hipSuccess ? ra : rb;
+    };
+    int chosen[kFrontSlots], n_chosen = 0;
+    bool taken[kCandidates] = {};
+    if (e == hipSuccess) {
+        double one = 1e30, t = 0.0;
+        for (int rep = 0; rep < 4 && e == hipSuccess; ++rep) {        // (the first launch also loads the kernel)
+            e = timed(made[0], nullptr, t);
+            if (rep > 0) one = std::min(one, t);
         }
+        for (int c = 0; c < kCandidates && n_chosen < kFrontSlots && e == hipSuccess; ++c) {
+            bool apart = true;
+            for (int k = 0; k < n_chosen && apart && e == hipSuccess; ++k) {
+                double best = 1e30;
+                for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) { e = timed(made[chosen[k]], made[c], t); best = std::min(best, t); }
+                apart = best < 1.5 * one;
+            }
+            if (apart && e == hipSuccess) { chosen[n_chosen++] = c; taken[c] = true; }
+        }
+        for (int c = 0; c < kCandidates && n_chosen < kFrontSlots; ++c)
+            if (!taken[c]) { chosen[n_chosen++] = c; taken[c] = true; }
     }
-    slots[0].stream = made[0]; slots[1].stream = made[1]; slots[2].stream = made[4]; slots[3].stream = made[5];
-    spare_streams[0] = made[2]; spare_streams[1] = made[3];
+    if (e != hipSuccess) {
+        for (hipStream_t st : made) if (st) (void)hipStreamDestroy(st);
+        return e;
+    }
+    for (int t = 0; t < kFrontSlots; ++t) slots[t].stream = made[chosen[t]];
+    int n_spare = 0;
+    for (int c = 0; c < kCandidates; ++c) if (!taken[c]) spare_streams[n_spare++] = made[c];
     return hipSuccess;
 }
 
@@ -213,7 +251,7 @@ const std::thread::id g_loader_thread = std::this_thread::get_id();
 
 void Ctx::release() {
     DevBuf* dev[] = {&rows, &rows_hdr, &blob, &valid, &rerun, &sorted, &progs, &costs, &counters, &topk_scratch, &topk_pos,
-                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share, &sel_progs, &sel_costs, &gather, &f_finish};
+                     &topk_in, &topk_jobs, &lit_scratch, &post, &f_rank, &f_share, &sel_progs, &sel_costs, &gather, &f_finish, &probe_sink};
     for (DevBuf* b : dev) { if (b->p) (void)hipFree(b->p); b->p = nullptr; b->cap = 0; }
     for (auto* v : {&f_evalid, &f_egsums}) {
         for (DevBuf& b : *v) if (b.p) (void)hipFree(b.p);
@@ -1197,6 +1235,10 @@ int32_t run_batch(const p2_query* queries, int32_t n_queries, const double* msg_
             one_at_a_time |= queries[i].opt && (queries[i].opt->flags & P2_FLAG_ONE_ENUMERATION_AT_A_TIME) != 0u;
         const int n_slots = one_at_a_time ? 1 : (int)std::min<size_t>(kFrontSlots, enums.size());
         P2_HIP(hipEventRecord(C.front_go, stream));
+        if (!C.slots[0].stream) {            // (first time: the streams are chosen by timing, on a quiet device)
+            P2_HIP(hipStreamSynchronize(stream));
+            P2_HIP(hipStreamSynchronize(C.copy_stream));
+        }
         P2_HIP(C.open_slot_streams());
         for (int t = 0; t < n_slots; ++t) {
             FrontSlot& S = C.slots[t];
