@@ -235,7 +235,11 @@ typedef struct {
  * under the shared-prefix engine).  P2_FLAG_EVALUATE_EVERY_QUERY in the options of any query of the
  * batch switches this off for the whole batch, on every engine.
  * The kernels of all queries share their launches; the call waits for the device twice: after
- * the evaluation (to size the result lists) and for the results. */
+ * the evaluation (to size the result lists) and for the results.  Queries on the frontier engine
+ * run on streams of the library's own, up to four enumerations side by side, and the call waits
+ * for them; the first such call of a host thread also waits for the caller's stream and spends a
+ * few milliseconds timing short kernels on a handful of new streams, to pick four that do not
+ * share a hardware queue. */
 int32_t p2_synthesize_batch(const p2_query* queries, int32_t n_queries, const double* msg_bytes, int32_t n_msg,
                             p2_program* out_prog, double* out_cost, int64_t cap, int64_t* out_offset,
                             p2_stats* stats);
