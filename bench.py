@@ -354,6 +354,9 @@ def main():
         out["one_enumeration_at_a_time"] = {"ms_per_step": alone["ms_per_step"], "steps": alone["steps"],
                                             "device_ms_per_step": alone["device_ms_per_step"], "roofline": alone["roofline"],
                                             "materialize": alone["materialize"]}
+        # (beside the timed figure, for a reader of the roofline object alone)
+        out["roofline"]["frac_one_enumeration_at_a_time"] = alone["roofline"]["frac"]
+        out["roofline"]["enumerations_side_by_side"] = 4
 
     if not args.no_compare:
         # the other configurations, a few steps each with the default engine, and where that is the shared-prefix
