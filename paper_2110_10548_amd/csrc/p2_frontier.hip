@@ -651,6 +651,9 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
                                                              FrontEntry* __restrict__ unknown_out, FrontCounters* __restrict__ ctr) {
     __shared__ uint32_t s_tot[kExpWaves][4];             // per wavefront: survivors, goals, one-pair children, two-pair children
     __shared__ uint32_t s_at[kExpWaves][4];              // ... where each kind starts for the wavefront
+    __shared__ unsigned long long s_judged;              // entries judged by the block
+    if (threadIdx.x == 0) s_judged = 0ull;
+    __syncthreads();
     const DevQuery& q = *qp;
     const int I = q.alphabet;
     const uint32_t CS = front_code_stride(I);
@@ -768,9 +771,13 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
             }
         }
     }
-    if (lane == 0 && judged) {
-        atomicAdd(&ctr->steps, judged * (unsigned long long)I);
-        atomicAdd(&ctr->members, judged * (unsigned long long)q.reg_sum_part);
+    // (one addition per block: additions to one address are served one after the other, some 10⁸ a second, and a
+    //  launch of four thousand wavefronts that each add twice lasts a tenth of a millisecond for that alone)
+    if (lane == 0 && judged) atomicAdd(&s_judged, judged);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_judged) {
+        atomicAdd(&ctr->steps, s_judged * (unsigned long long)I);
+        atomicAdd(&ctr->members, s_judged * (unsigned long long)q.reg_sum_part);
     }
 }
 
