@@ -1468,16 +1468,18 @@ __global__ __launch_bounds__(256) void k_front_children(const DevQuery* __restri
             before[kd] = x - mine[kd];
             total[kd] = __shfl(x, 63, 64);
         }
+        // One trip to the counters for the three kinds and the list: lanes 0-2 add a kind's total each, lane 3 the
+        // length of the list (returning additions take a microsecond or two each, one after the other).
         uint32_t* const counts = write ? ctr->t_next : ctr->t_count;
-        uint32_t base[3];
-        // (every lane takes part in the reservation, lane 0 alone adds: no lane-dependent branch around a cross-lane read)
-#pragma unroll
-        for (int kd = 0; kd < 3; ++kd)
-            base[kd] = total[kd] ? __builtin_amdgcn_readfirstlane(atomicAdd(&counts[kd], lane == 0 ? total[kd] : 0u)) : 0u;
-        if (!write) continue;
         const uint32_t all = total[0] + total[1] + total[2];
+        const uint32_t add = lane == 0 ? total[0] : lane == 1 ? total[1] : lane == 2 ? total[2] : (lane == 3 && write) ? all : 0u;
+        uint32_t got = 0u;
+        if (lane < 4 && add != 0u) got = atomicAdd(lane < 3 ? &counts[lane] : &ctr->n_ssurv, add);
+        const uint32_t base[3] = {__shfl(got, 0, 64), __shfl(got, 1, 64), __shfl(got, 2, 64)};
+        const uint32_t list_at = __shfl(got, 3, 64);
+        if (!write) continue;
         if (all == 0) continue;
-        uint32_t at_list = __builtin_amdgcn_readfirstlane(atomicAdd(&ctr->n_ssurv, lane == 0 ? all : 0u)) + before[0] + before[1] + before[2];
+        uint32_t at_list = list_at + before[0] + before[1] + before[2];
         uint32_t next[3] = {base[0] + before[0], base[1] + before[1], base[2] + before[2]};
 #pragma unroll
         for (int b = 0; b < kChildChunk; ++b) {
