@@ -724,10 +724,17 @@ __global__ __launch_bounds__(kExpThreads) void k_front_expand(const DevQuery* __
             }
 #pragma unroll
             for (int b = 0; b < kExpBatch; ++b) {
+                // (every load is made, from a word that exists, and what was not asked for is dropped afterwards: loads
+                //  under a condition are waited for one by one, these sixteen are in flight together)
                 const uint32_t r = (uint32_t)__shfl((int)row, src[b] < 0 ? 0 : src[b], 64);
                 const uint32_t* const words = reinterpret_cast<const uint32_t*>(codes + (size_t)r * CS);
 #pragma unroll
-                for (int h = 0; h < 2; ++h) four[b][h] = (src[b] >= 0 && lane + 64 * h < CW) ? (words[lane + 64 * h] & in_alphabet[h]) : 0u;
+                for (int h = 0; h < 2; ++h) four[b][h] = words[lane + 64 * h < CW ? lane + 64 * h : 0];
+            }
+#pragma unroll
+            for (int b = 0; b < kExpBatch; ++b) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) four[b][h] = (src[b] >= 0 && lane + 64 * h < CW) ? (four[b][h] & in_alphabet[h]) : 0u;
             }
 #pragma unroll
             for (int b = 0; b < kExpBatch; ++b) {
@@ -1439,12 +1446,21 @@ __global__ __launch_bounds__(256) void k_front_children(const DevQuery* __restri
             const uint32_t i = c0 + (uint32_t)b;
             st_of[b] = i < c1 ? (list ? list[i] : i) : 0u;
         }
+        // (every load is made, from a state and a word that exist, and what was not asked for is dropped afterwards:
+        //  loads under a condition are waited for one by one, these are in flight together)
+        uint8_t unk[kChildChunk];
 #pragma unroll
         for (int b = 0; b < kChildChunk; ++b) {
-            const bool on = c0 + (uint32_t)b < c1 && !unknown[st_of[b]];       // (an unknown state's prefixes go to the literal kernels)
+            unk[b] = unknown[st_of[b]];
             const uint32_t* const row = reinterpret_cast<const uint32_t*>(codes + (size_t)st_of[b] * CS);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) four[b][h] = (on && (uint32_t)(lane + 64 * h) < CS / 4u) ? (row[lane + 64 * h] & in_alphabet[h]) : 0u;
+            for (int h = 0; h < 2; ++h) four[b][h] = row[(uint32_t)(lane + 64 * h) < CS / 4u ? lane + 64 * h : 0];
+        }
+#pragma unroll
+        for (int b = 0; b < kChildChunk; ++b) {
+            const bool on = c0 + (uint32_t)b < c1 && !unk[b];                  // (an unknown state's prefixes go to the literal kernels)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) four[b][h] = (on && (uint32_t)(lane + 64 * h) < CS / 4u) ? (four[b][h] & in_alphabet[h]) : 0u;
         }
         uint32_t mine[3] = {0u, 0u, 0u};
 #pragma unroll
