@@ -830,11 +830,13 @@ __global__ __launch_bounds__(256) void k_front_verify(const uint4* __restrict__ 
         const uint4* b = states + (size_t)r * quads;
         bool differ = false;
         for (uint32_t i0 = (uint32_t)lane; i0 < quads; i0 += 256u) {
+            // (all eight loads are made, past the end from the last quad again, which changes nothing: loads under a
+            //  condition are waited for pair by pair)
             uint4 x[4], y[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const uint32_t i = i0 + 64u * u;
-                x[u] = i < quads ? a[i] : q_zero(); y[u] = i < quads ? b[i] : q_zero();
+                const uint32_t i = min(i0 + 64u * u, quads - 1u);
+                x[u] = a[i]; y[u] = b[i];
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) differ |= q_any(q_xor(x[u], y[u]));
